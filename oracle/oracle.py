@@ -1,0 +1,416 @@
+"""CPU oracle for one sample-based GNN training step with hot-embedding reuse.
+
+THIS IS TEST INFRASTRUCTURE: a plain, slow, obviously-correct statement of what the hot path
+computes. Only tests, the smoke check and the benchmark's CPU-baseline leg may use it; the
+product path never does. It shares no code with the GPU library.
+
+Integer work (Philox sampling, relabelling, transposition, hot counting, CSR build) lives in
+``no_oracle.c`` (plain C, called through ctypes); floating point is numpy fp64 throughout.
+
+What it follows in the paper:
+  * Algorithm 1: per batch, sample L hops in reverse from the seeds, gather the input
+    features, L forward layers, loss, L backward layers, one parameter update.
+  * Eq. 1 / Eq. 2: AGGREGATE = average over sampled in-neighbours, UPDATE = dense layer.
+    GraphSAGE-mean reading: h_v = act(W_self^T h_v + W_neigh^T mean_u h_u + b); ReLU between
+    layers, none on the logits.
+  * Section 4.1.2: hot vertices by pre-sampling frequency; a hot vertex's layer-1 embedding
+    computed at step t0 may be reused at steps t with t - t0 <= S (S = bound in batches);
+    a reused embedding gets no aggregation and no backward pass.
+"""
+from __future__ import annotations
+
+import ctypes
+import dataclasses
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "no_oracle.c")
+_LIB = os.path.join(_HERE, "libno_oracle.so")
+
+DOMAIN_TRAIN = 0
+DOMAIN_PRESAMPLE = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C part with gcc (plain -O2)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-shared", "-fPIC", "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        c = ctypes
+        P = c.c_void_p
+        L.ora_philox4x32_10.argtypes = [P, P, P]
+        L.ora_philox4x32_10.restype = None
+        L.ora_random64.argtypes = [c.c_uint64, c.c_uint32, c.c_uint32, c.c_uint64, c.c_uint32]
+        L.ora_random64.restype = c.c_uint64
+        L.ora_mulhi64.argtypes = [c.c_uint64, c.c_uint64]
+        L.ora_mulhi64.restype = c.c_uint64
+        L.ora_fisher_yates_prefix.argtypes = [c.c_int64, c.c_int32, P, P]
+        L.ora_fisher_yates_prefix.restype = None
+        L.ora_sample_row.argtypes = [c.c_uint64, c.c_uint32, c.c_uint32, c.c_uint64, c.c_int64, c.c_int32, P]
+        L.ora_sample_row.restype = c.c_int32
+        L.ora_build_csr.argtypes = [P, P, c.c_int64, c.c_int64, P, P]
+        L.ora_build_csr.restype = None
+        L.ora_sample_hop.argtypes = [P, P, P, c.c_int64, c.c_int32, c.c_uint64, c.c_uint32, c.c_uint32,
+                                     P, P, P, P, P]
+        L.ora_sample_hop.restype = c.c_int64
+        L.ora_block_csc.argtypes = [P, P, c.c_int64, c.c_int64, P, P, P]
+        L.ora_block_csc.restype = None
+        L.ora_presample_counts.argtypes = [P, P, c.c_int64, P, c.c_int64, c.c_int32, P, c.c_int32, c.c_int32,
+                                           c.c_uint64, P]
+        L.ora_presample_counts.restype = None
+        L.ora_gather_rows.argtypes = [P, c.c_int64, P, c.c_int64, P]
+        L.ora_gather_rows.restype = None
+        L.ora_mean_aggregate.argtypes = [P, c.c_int64, P, P, c.c_int64, P]
+        L.ora_mean_aggregate.restype = None
+        L.ora_mean_aggregate_adjoint.argtypes = [P, c.c_int64, P, P, c.c_int64, P]
+        L.ora_mean_aggregate_adjoint.restype = None
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u64(x: int) -> int:
+    return int(x) & 0xFFFFFFFFFFFFFFFF
+
+
+# --------------------------------------------------------------------------- random source
+
+def philox4x32_10(ctr: Sequence[int], key: Sequence[int]) -> Tuple[int, int, int, int]:
+    c = np.array(ctr, dtype=np.uint32)
+    k = np.array(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().ora_philox4x32_10(_p(c), _p(k), _p(out))
+    return tuple(int(x) for x in out)
+
+
+def random64(stream: int, domain: int, hop: int, v: int, slot: int) -> int:
+    return int(lib().ora_random64(_u64(stream), domain, hop, v, slot))
+
+
+def fisher_yates_prefix(d: int, k: int, r: Sequence[int]) -> List[int]:
+    rr = np.array(r, dtype=np.int64)
+    out = np.zeros(k, dtype=np.int64)
+    lib().ora_fisher_yates_prefix(d, k, _p(rr), _p(out))
+    return [int(x) for x in out]
+
+
+def sample_row(stream: int, domain: int, hop: int, v: int, d: int, k: int) -> List[int]:
+    out = np.zeros(max(k, 1), dtype=np.int64)
+    n = lib().ora_sample_row(_u64(stream), domain, hop, v, d, k, _p(out))
+    return [int(x) for x in out[:n]]
+
+
+# --------------------------------------------------------------------------- graph
+
+@dataclasses.dataclass
+class Graph:
+    n_vertices: int
+    rowptr: np.ndarray   # int64 [V+1]
+    col: np.ndarray      # int32 [E]
+
+    @property
+    def n_edges(self) -> int:
+        return int(self.rowptr[-1])
+
+
+def build_csr(src: np.ndarray, dst: np.ndarray, n_vertices: int) -> Graph:
+    """In-neighbour CSR (Eq. 1 aggregates over N_in): row dst holds its sources, ascending."""
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    dst = np.ascontiguousarray(dst, dtype=np.int32)
+    rowptr = np.zeros(n_vertices + 1, dtype=np.int64)
+    col = np.zeros(max(len(src), 1), dtype=np.int32)
+    lib().ora_build_csr(_p(src), _p(dst), len(src), n_vertices, _p(rowptr), _p(col))
+    return Graph(n_vertices, rowptr, col[: len(src)])
+
+
+# --------------------------------------------------------------------------- sampled blocks
+
+@dataclasses.dataclass
+class Block:
+    """One sampled hop as a bipartite block: n_src sources (the first n_dst are the
+    destinations themselves), rows = destinations."""
+    dst_global: np.ndarray
+    src_global: np.ndarray
+    indptr: np.ndarray
+    nbr_global: np.ndarray
+    indices: np.ndarray
+    csc_indptr: np.ndarray
+    csc_dst: np.ndarray
+    csc_eid: np.ndarray
+
+    @property
+    def n_dst(self) -> int:
+        return len(self.dst_global)
+
+    @property
+    def n_src(self) -> int:
+        return len(self.src_global)
+
+    @property
+    def nnz(self) -> int:
+        return len(self.indices)
+
+
+def sample_hop(g: Graph, dst_global: np.ndarray, fanout: int, stream: int, domain: int, hop: int,
+               _map: Optional[np.ndarray] = None) -> Block:
+    dst_global = np.ascontiguousarray(dst_global, dtype=np.int32)
+    n_dst = len(dst_global)
+    m = _map if _map is not None else np.full(g.n_vertices, -1, dtype=np.int32)
+    cap_e = max(n_dst * fanout, 1)
+    indptr = np.zeros(n_dst + 1, dtype=np.int32)
+    nbr = np.zeros(cap_e, dtype=np.int32)
+    idx = np.zeros(cap_e, dtype=np.int32)
+    srcg = np.zeros(n_dst + cap_e, dtype=np.int32)
+    n_src = lib().ora_sample_hop(_p(g.rowptr), _p(g.col), _p(dst_global), n_dst, fanout,
+                                 _u64(stream), domain, hop, _p(m), _p(indptr), _p(nbr), _p(idx), _p(srcg))
+    nnz = int(indptr[n_dst])
+    idx = np.ascontiguousarray(idx[:nnz])
+    csc_indptr = np.zeros(n_src + 1, dtype=np.int32)
+    csc_dst = np.zeros(max(nnz, 1), dtype=np.int32)
+    csc_eid = np.zeros(max(nnz, 1), dtype=np.int32)
+    lib().ora_block_csc(_p(indptr), _p(idx), n_dst, n_src, _p(csc_indptr), _p(csc_dst), _p(csc_eid))
+    return Block(dst_global, np.ascontiguousarray(srcg[:n_src]), indptr, np.ascontiguousarray(nbr[:nnz]), idx,
+                 csc_indptr, csc_dst[:nnz], csc_eid[:nnz])
+
+
+# --------------------------------------------------------------------------- hot set and cache
+
+@dataclasses.dataclass
+class Cache:
+    """Hot set (Section 4.1.2) with its embedding store and version record."""
+    hot_ids: np.ndarray          # int32 [n_hot], hotness order
+    slot_of_vertex: np.ndarray   # int32 [V], -1 = cold
+    version: np.ndarray          # int32 [n_hot], step whose weights made the row; -1 = empty
+    emb: np.ndarray              # float64 [n_hot, emb_dim]
+    staleness: int
+    freq: Optional[np.ndarray] = None
+
+    @property
+    def n_hot(self) -> int:
+        return len(self.hot_ids)
+
+    def copy(self) -> "Cache":
+        return Cache(self.hot_ids.copy(), self.slot_of_vertex.copy(), self.version.copy(), self.emb.copy(),
+                     self.staleness, None if self.freq is None else self.freq.copy())
+
+
+def presample_counts(g: Graph, train_ids: np.ndarray, batch: int, fanouts: Sequence[int], epochs: int,
+                     seed: int) -> np.ndarray:
+    train_ids = np.ascontiguousarray(train_ids, dtype=np.int32)
+    fo = np.array(fanouts, dtype=np.int32)
+    freq = np.zeros(g.n_vertices, dtype=np.int64)
+    lib().ora_presample_counts(_p(g.rowptr), _p(g.col), g.n_vertices, _p(train_ids), len(train_ids), batch,
+                               _p(fo), len(fo), epochs, _u64(seed), _p(freq))
+    return freq
+
+
+def select_hot(g: Graph, train_ids: np.ndarray, batch: int, fanouts: Sequence[int], presample_epochs: int,
+               hot_fraction: float, staleness: int, emb_dim: int, seed: int) -> Cache:
+    """Hot set = the floor(hot_fraction * V) most frequently pre-sampled vertices, ties by id."""
+    freq = presample_counts(g, train_ids, batch, fanouts, presample_epochs, seed)
+    n_hot = int(np.floor(hot_fraction * g.n_vertices))
+    order = np.lexsort((np.arange(g.n_vertices), -freq))   # primary: freq descending; then id ascending
+    hot = np.ascontiguousarray(order[:n_hot].astype(np.int32))
+    slot = np.full(g.n_vertices, -1, dtype=np.int32)
+    slot[hot] = np.arange(n_hot, dtype=np.int32)
+    return Cache(hot, slot, np.full(n_hot, -1, dtype=np.int32), np.zeros((n_hot, emb_dim), dtype=np.float64),
+                 staleness, freq)
+
+
+def cache_lookup(cache: Cache, v1: np.ndarray, step: int):
+    """Split V^1 (order kept) into reusable rows and rows to compute.
+    A row is reusable iff the vertex is hot, its slot is filled, and step - version <= S."""
+    slot = cache.slot_of_vertex[v1]
+    ver = np.full(len(v1), -1, dtype=np.int64)
+    ver[slot >= 0] = cache.version[slot[slot >= 0]]
+    hit = (slot >= 0) & (ver >= 0) & (step - ver <= cache.staleness)
+    hit_pos = np.nonzero(hit)[0].astype(np.int32)
+    compute_pos = np.nonzero(~hit)[0].astype(np.int32)
+    return compute_pos, hit_pos, slot[hit_pos].astype(np.int32)
+
+
+@dataclasses.dataclass
+class SampledBatch:
+    blocks: List[Block]               # hop order from the seeds; blocks[-1] is the bottom hop
+    compute_pos: Optional[np.ndarray]  # positions in V^1 of the bottom hop's destinations
+    hit_pos: Optional[np.ndarray]
+    hit_slot: Optional[np.ndarray]
+
+
+def sample_blocks(g: Graph, seeds: np.ndarray, fanouts: Sequence[int], seed: int, step: int,
+                  cache: Optional[Cache] = None, domain: int = DOMAIN_TRAIN) -> SampledBatch:
+    """Reverse L-hop sampling from the seeds (Algorithm 1). The frontier of hop h+1 is the source
+    set of hop h. With a cache, reusable hot vertices are left out of the bottom hop."""
+    L = len(fanouts)
+    stream = _u64(seed + step)
+    m = np.full(g.n_vertices, -1, dtype=np.int32)
+    blocks: List[Block] = []
+    frontier = np.ascontiguousarray(seeds, dtype=np.int32)
+    compute_pos = hit_pos = hit_slot = None
+    for h in range(L):
+        if h == L - 1 and cache is not None and L >= 2:
+            compute_pos, hit_pos, hit_slot = cache_lookup(cache, frontier, step)
+            frontier = np.ascontiguousarray(frontier[compute_pos])
+        b = sample_hop(g, frontier, fanouts[h], stream, domain, h, m)
+        blocks.append(b)
+        frontier = b.src_global
+    return SampledBatch(blocks, compute_pos, hit_pos, hit_slot)
+
+
+# --------------------------------------------------------------------------- gather
+
+def gather_features(table: np.ndarray, ids: np.ndarray) -> np.ndarray:
+    """Feature collection: out[i,:] = table[ids[i],:], bit copy (any dtype)."""
+    table = np.ascontiguousarray(table)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    out = np.empty((len(ids),) + table.shape[1:], dtype=table.dtype)
+    lib().ora_gather_rows(_p(table), table.strides[0], _p(ids), len(ids), _p(out))
+    return out
+
+
+# --------------------------------------------------------------------------- layers (fp64)
+
+def mean_aggregate(x_src: np.ndarray, indptr: np.ndarray, indices: np.ndarray, n_dst: int) -> np.ndarray:
+    x = np.ascontiguousarray(x_src, dtype=np.float64)
+    out = np.zeros((n_dst, x.shape[1]), dtype=np.float64)
+    lib().ora_mean_aggregate(_p(x), x.shape[1], _p(np.ascontiguousarray(indptr, dtype=np.int32)),
+                             _p(np.ascontiguousarray(indices, dtype=np.int32)), n_dst, _p(out))
+    return out
+
+
+def mean_aggregate_adjoint(grad_mean: np.ndarray, indptr: np.ndarray, indices: np.ndarray, n_dst: int,
+                           n_src: int) -> np.ndarray:
+    g = np.ascontiguousarray(grad_mean, dtype=np.float64)
+    out = np.zeros((n_src, g.shape[1]), dtype=np.float64)
+    lib().ora_mean_aggregate_adjoint(_p(g), g.shape[1], _p(np.ascontiguousarray(indptr, dtype=np.int32)),
+                                     _p(np.ascontiguousarray(indices, dtype=np.int32)), n_dst, _p(out))
+    return out
+
+
+def sage_layer_fwd(blk: Block, x_src: np.ndarray, w_self, w_neigh, bias, relu: bool):
+    """Eq. 1 (mean over the sampled row) then Eq. 2 (dense update). Returns (mean, h)."""
+    x = np.asarray(x_src, dtype=np.float64)
+    mean = mean_aggregate(x, blk.indptr, blk.indices, blk.n_dst)
+    z = x[: blk.n_dst] @ np.asarray(w_self, np.float64) + mean @ np.asarray(w_neigh, np.float64) \
+        + np.asarray(bias, np.float64)
+    h = np.maximum(z, 0.0) if relu else z
+    return mean, h
+
+
+def sage_layer_bwd(blk: Block, x_src: np.ndarray, mean: np.ndarray, h: np.ndarray, grad_h: np.ndarray,
+                   w_self, w_neigh, relu: bool, need_grad_x: bool):
+    """Gradients of one layer. grad_x is None for the bottom layer (nothing below it learns)."""
+    x = np.asarray(x_src, dtype=np.float64)
+    gz = np.asarray(grad_h, np.float64) * (np.asarray(h) > 0) if relu else np.asarray(grad_h, np.float64)
+    x_dst = x[: blk.n_dst]
+    gw_self = x_dst.T @ gz
+    gw_neigh = np.asarray(mean, np.float64).T @ gz
+    gb = gz.sum(axis=0)
+    gx = None
+    if need_grad_x:
+        gmean = gz @ np.asarray(w_neigh, np.float64).T
+        gx = mean_aggregate_adjoint(gmean, blk.indptr, blk.indices, blk.n_dst, blk.n_src)
+        gx[: blk.n_dst] += gz @ np.asarray(w_self, np.float64).T
+    return gw_self, gw_neigh, gb, gx
+
+
+def softmax_xent(logits: np.ndarray, labels: np.ndarray):
+    """Mean softmax cross-entropy over the batch and its gradient w.r.t. the logits."""
+    z = np.asarray(logits, np.float64)
+    z = z - z.max(axis=1, keepdims=True)
+    lse = np.log(np.exp(z).sum(axis=1, keepdims=True))
+    logp = z - lse
+    n = z.shape[0]
+    loss = -logp[np.arange(n), labels].mean()
+    g = np.exp(logp)
+    g[np.arange(n), labels] -= 1.0
+    return float(loss), g / n
+
+
+# --------------------------------------------------------------------------- one training step
+
+@dataclasses.dataclass
+class StepResult:
+    loss: float
+    batch: SampledBatch
+    x0: np.ndarray                       # gathered input features (table dtype)
+    h: List[np.ndarray]                  # h[l-1] = output of layer l (h[0] holds all of V^1 with a cache)
+    mean: List[np.ndarray]
+    grads: List[Tuple[np.ndarray, np.ndarray, np.ndarray]]
+    new_weights: List[Tuple[np.ndarray, np.ndarray, np.ndarray]]
+    n_hit: int
+
+
+def _to_f64(x: np.ndarray, feat_is_bf16: bool) -> np.ndarray:
+    if feat_is_bf16:
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
+def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray, fanouts: Sequence[int],
+               weights, lr: float, seed: int, step: int, cache: Optional[Cache] = None,
+               feat_is_bf16: bool = False) -> StepResult:
+    """One pass of Algorithm 1's loop body with plain SGD; updates `cache` in place."""
+    L = len(fanouts)
+    sb = sample_blocks(g, seeds, fanouts, seed, step, cache)
+    bottom = sb.blocks[-1]
+    x0 = gather_features(feat, bottom.src_global)
+    x = _to_f64(x0, feat_is_bf16)
+    hs, means, xs = [], [], []
+    use_cache = cache is not None and L >= 2
+    for l in range(1, L + 1):
+        blk = sb.blocks[L - l]
+        w_self, w_neigh, bias = weights[l - 1]
+        xs.append(x)
+        mean, h = sage_layer_fwd(blk, x, w_self, w_neigh, bias, relu=(l < L))
+        means.append(mean)
+        if l == 1 and use_cache:
+            n_v1 = len(sb.compute_pos) + len(sb.hit_pos)
+            full = np.zeros((n_v1, h.shape[1]), dtype=np.float64)
+            full[sb.compute_pos] = h
+            full[sb.hit_pos] = cache.emb[sb.hit_slot]
+            hs.append(full)
+            x = full
+        else:
+            hs.append(h)
+            x = h
+    loss, gh = softmax_xent(hs[-1], np.asarray(labels)[np.asarray(seeds)])
+    grads = [None] * L
+    for l in range(L, 0, -1):
+        blk = sb.blocks[L - l]
+        w_self, w_neigh, _ = weights[l - 1]
+        h_l = hs[l - 1]
+        if l == 1 and use_cache:
+            h_l = h_l[sb.compute_pos]
+            gh = gh[sb.compute_pos]        # reused rows take no gradient
+        gws, gwn, gb, gx = sage_layer_bwd(blk, xs[l - 1], means[l - 1], h_l, gh, w_self, w_neigh,
+                                          relu=(l < L), need_grad_x=(l > 1))
+        grads[l - 1] = (gws, gwn, gb)
+        gh = gx
+    new_w = [(np.asarray(w[0], np.float64) - lr * gr[0], np.asarray(w[1], np.float64) - lr * gr[1],
+              np.asarray(w[2], np.float64) - lr * gr[2]) for w, gr in zip(weights, grads)]
+    if use_cache:
+        # every computed hot vertex refreshes its slot with the embedding made by step-t weights
+        v1_computed = bottom.dst_global
+        slots = cache.slot_of_vertex[v1_computed]
+        sel = slots >= 0
+        cache.emb[slots[sel]] = hs[0][sb.compute_pos][sel]
+        cache.version[slots[sel]] = step
+    return StepResult(loss, sb, x0, hs, means, grads, new_w, 0 if not use_cache else len(sb.hit_pos))
