@@ -1,0 +1,226 @@
+/*
+ * neutronorch.h - C ABI of the MI355X (gfx950) hot path of one sample-based GNN training
+ * step with hot-vertex embedding reuse: sample -> gather -> train (Algorithm 1), with a
+ * staleness-bounded cache of hot vertices' layer-1 embeddings (Section 4.1.2).
+ *
+ * Conventions
+ *   - Every function returns a status: NO_OK (0) or a negative NO_ERR_* code; on failure
+ *     no_last_error() gives a thread-local message and no output is written unless stated.
+ *   - Pointers named d_* are DEVICE addresses, h_* are HOST addresses. Buffers passed in are
+ *     owned by the caller and are never freed or reallocated by the library. Opaque handles
+ *     are owned by the library and released with the matching *_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). All work is
+ *     enqueued on it; calls return without synchronising unless a host out-parameter is
+ *     documented to need it. Data-dependent sizes live in device scalars; kernels are
+ *     launched at capacity bounds and exit early.
+ *   - Handles are not thread-safe. Same inputs => bit-identical outputs (no float atomics).
+ *   - Vertex ids are int32. Edge (src -> dst) makes src an in-neighbour of dst (Eq. 1).
+ *   - Matrices are row-major; weights are [d_in, d_out].
+ */
+#ifndef NEUTRONORCH_H_
+#define NEUTRONORCH_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    NO_OK = 0,
+    NO_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, bad enum, S < 0, fraction outside [0,1] */
+    NO_ERR_OUT_OF_RANGE = -2,  /* a vertex id outside [0, V) (only where a host-side check is possible) */
+    NO_ERR_CAPACITY = -3,      /* a handle or workspace is too small for the request */
+    NO_ERR_OVERFLOW = -4,      /* 32-bit row pointers requested but E >= 2^31, or V >= 2^31 */
+    NO_ERR_HIP = -5,           /* a HIP runtime call failed; see no_last_error() */
+    NO_ERR_UNSUPPORTED = -6
+};
+
+typedef enum { NO_F32 = 0, NO_BF16 = 1 } no_dtype;
+
+enum { NO_MAX_LAYERS = 8, NO_MAX_FANOUT = 64 };
+
+typedef struct no_graph_s* no_graph_t;    /* in-neighbour CSR, device resident            */
+typedef struct no_blocks_s* no_blocks_t;  /* L sampled blocks, capacity sized             */
+typedef struct no_cache_s* no_cache_t;    /* hot set + embedding cache + version record   */
+typedef struct no_model_s* no_model_t;    /* weights, activations and gradient workspace  */
+
+/* Last error message of the calling thread ("" if none). Never NULL. */
+const char* no_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Graph (input G(V,E) of Algorithm 1; N_in(v) of Eq. 1)
+ * ---------------------------------------------------------------------------------------- */
+
+enum { NO_CSR_INPUT_ON_DEVICE = 1u };
+
+/* Builds the in-neighbour CSR of a directed multigraph: row v lists every src with an edge
+ * (src -> v), ascending by src, duplicates and self-loops kept.
+ *   src, dst     int32[n_edges]; host pointers, or device pointers with NO_CSR_INPUT_ON_DEVICE.
+ *   rowptr_bits  32 or 64: width of the row-pointer array (32 needs n_edges < 2^31).
+ * Synchronises the stream before returning (it validates ids and sizes scratch). */
+int32_t no_build_csr(const int32_t* src, const int32_t* dst, int64_t n_edges, int64_t n_vertices,
+                     int32_t rowptr_bits, uint32_t flags, void* stream, no_graph_t* out);
+
+/* Device pointers into the graph: d_rowptr is int32[V+1] or int64[V+1] by *rowptr_bits. */
+int32_t no_graph_view(no_graph_t g, int64_t* n_vertices, int64_t* n_edges, int32_t* rowptr_bits,
+                      const void** d_rowptr, const int32_t** d_col);
+int32_t no_graph_destroy(no_graph_t g);
+
+/* ------------------------------------------------------------------------------------------
+ * Sampled blocks (the sample() loop of Algorithm 1, lines 4-7)
+ * ---------------------------------------------------------------------------------------- */
+
+/* One hop as a bipartite block. Rows are destinations; the first n_dst sources are the
+ * destinations themselves, further sources follow in order of first occurrence over the
+ * sampled edges in (row, slot) order. All pointers are device addresses inside the handle. */
+typedef struct no_block_view {
+    int32_t n_dst_cap, n_src_cap, nnz_cap;
+    const int32_t* d_n_dst;       /* device scalars */
+    const int32_t* d_n_src;
+    const int32_t* d_nnz;
+    const int32_t* d_dst_global;  /* [n_dst]  */
+    const int32_t* d_src_global;  /* [n_src]  */
+    const int32_t* d_indptr;      /* [n_dst+1] */
+    const int32_t* d_nbr_global;  /* [nnz] sampled neighbour ids, row-major, slot order */
+    const int32_t* d_indices;     /* [nnz] local source index of each sampled edge */
+    const int32_t* d_csc_indptr;  /* [n_src+1] transpose; NULL when not built (bottom hop) */
+    const int32_t* d_csc_dst;     /* [nnz] destination row of each transposed entry */
+    const int32_t* d_csc_eid;     /* [nnz] edge id, ascending inside a column */
+    /* bottom hop only, when sampled with a cache (else NULL): split of V^1 */
+    const int32_t* d_compute_pos; /* [n_compute] positions in V^1 of this block's destinations */
+    const int32_t* d_hit_pos;     /* [n_hit] positions in V^1 served from the cache */
+    const int32_t* d_hit_slot;    /* [n_hit] their cache slots */
+    const int32_t* d_n_compute;
+    const int32_t* d_n_hit;
+} no_block_view;
+
+/* Allocates blocks for up to n_seeds_cap seeds and the given fanouts (hop order counted from
+ * the seeds: fanouts[0] applies to the seed batch, the last entry to the bottom hop).
+ * Capacities are the no-de-duplication bounds, vertex sets capped at V. The transpose of hop
+ * h is built for h < n_layers-1 (the bottom layer back-propagates nothing to its inputs). */
+int32_t no_blocks_create(no_graph_t g, int32_t n_seeds_cap, const int32_t* h_fanouts, int32_t n_layers,
+                         no_blocks_t* out);
+
+/* Samples n_layers hops from d_seeds[n_seeds] (unique ids). Hop h gives every destination v
+ * min(deg(v), fanouts[h]) distinct entries of its CSR row, uniformly without replacement, as a
+ * pure function of (seed + step, domain 0, h, v, slot) through Philox4x32-10; the whole row in
+ * stored order when deg <= fanout. The destinations of hop h+1 are the sources of hop h.
+ * With cache != NULL (and n_layers >= 2) the destinations of the bottom hop are only those
+ * vertices of V^1 that cannot be served from the cache at `step` (not hot, empty slot, or
+ * step - version > S). Asynchronous. */
+int32_t no_sample_blocks(no_graph_t g, const int32_t* d_seeds, int32_t n_seeds, uint64_t seed, int64_t step,
+                         no_cache_t cache, no_blocks_t blocks, void* stream);
+
+int32_t no_blocks_view(no_blocks_t blocks, int32_t hop, no_block_view* out);
+/* Copies (n_dst, n_src, nnz, n_hit) of every hop to h_sizes[4*n_layers] (n_hit is 0 except at
+ * the bottom hop with a cache). Synchronises the stream. */
+int32_t no_blocks_sizes(no_blocks_t blocks, void* stream, int32_t* h_sizes);
+int32_t no_blocks_destroy(no_blocks_t blocks);
+
+/* ------------------------------------------------------------------------------------------
+ * Hot set and embedding cache (Section 4.1.2; version record of Section 4.2)
+ * ---------------------------------------------------------------------------------------- */
+
+/* Pre-sampling hotness: the train ids, in the given order, are cut into batches of `batch`;
+ * for presample_epochs epochs every batch is sampled for hops 0..n_layers-2 (Philox domain 1,
+ * stream seed + epoch*n_batches + b) and each vertex of the resulting V^1 counts once. The hot
+ * set is the floor(hot_fraction * V) most frequent vertices, ties by ascending id; slot = rank.
+ * Creates an empty cache [n_hot, emb_dim] fp32 (versions -1). Synchronises the stream. */
+int32_t no_select_hot(no_graph_t g, const int32_t* d_train_ids, int64_t n_train, int32_t batch,
+                      const int32_t* h_fanouts, int32_t n_layers, int32_t presample_epochs,
+                      double hot_fraction, int32_t staleness, int32_t emb_dim, uint64_t seed,
+                      void* stream, no_cache_t* out);
+
+/* d_hot_ids int32[n_hot] (hotness order), d_slot_of_vertex int32[V] (-1 = cold),
+ * d_version int32[n_hot] (step whose weights produced the row; -1 = empty), d_emb fp32[n_hot, emb_dim],
+ * d_freq int32[V] pre-sampling counts. Any out pointer may be NULL. */
+int32_t no_cache_view(no_cache_t c, int64_t* n_hot, int32_t* staleness, int32_t* emb_dim,
+                      const int32_t** d_hot_ids, const int32_t** d_slot_of_vertex,
+                      int32_t** d_version, float** d_emb, const int32_t** d_freq);
+int32_t no_cache_set_staleness(no_cache_t c, int32_t staleness);
+int32_t no_cache_invalidate(no_cache_t c, void* stream);   /* all versions = -1 */
+int32_t no_cache_destroy(no_cache_t c);
+
+/* ------------------------------------------------------------------------------------------
+ * Gather (feature collection, Algorithm 1 line 9)
+ * ---------------------------------------------------------------------------------------- */
+
+/* d_out[i, 0:dim] = d_table[d_ids[i], 0:dim] for i < n, a bit copy of `dim` elements of dt.
+ * n = *d_n_ids when d_n_ids != NULL (must be <= n_ids_cap), else n_ids_cap. Strides in bytes,
+ * multiples of the element size. Ids must lie in [0, n_rows) (not checked). */
+int32_t no_gather_features(const void* d_table, no_dtype dt, int64_t n_rows, int32_t dim,
+                           int64_t table_stride_bytes, const int32_t* d_ids, const int32_t* d_n_ids,
+                           int32_t n_ids_cap, void* d_out, int64_t out_stride_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * GraphSAGE-mean layer (Eq. 1 with AGGREGATE = average, Eq. 2 with a dense UPDATE)
+ * ---------------------------------------------------------------------------------------- */
+
+size_t no_sage_layer_ws_bytes(int32_t n_dst_cap, int32_t n_src_cap, int32_t d_in, int32_t d_out);
+
+/* Forward: d_mean[v,:] = average of d_x_src[indices[e],:] over row v (zeros for an empty row);
+ * d_h = act(d_x_src[0:n_dst] * W_self + d_mean * W_neigh + bias), act = ReLU if relu else identity.
+ * d_x_src [n_src, d_in] of dt_x (bf16 is upcast; accumulation is fp32), d_mean [n_dst_cap, d_in]
+ * and d_h [n_dst_cap, d_out] fp32, dense. Uses d_indptr/d_indices/d_n_dst of the view. */
+int32_t no_sage_layer_fwd(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+                          const float* d_w_self, const float* d_w_neigh, const float* d_bias,
+                          int32_t d_out, int32_t relu, float* d_mean, float* d_h,
+                          void* d_ws, size_t ws_bytes, void* stream);
+
+/* Backward: gz = d_grad_h * [d_h > 0] (or d_grad_h when relu == 0);
+ * d_gw_self = x_dst^T gz, d_gw_neigh = mean^T gz, d_gbias = column sums of gz (all overwritten);
+ * if d_grad_x_src != NULL (not the bottom layer; needs the transpose in the view):
+ *   d_grad_x_src[u,:] = [u < n_dst] gz[u,:] W_self^T + sum over transposed entries (v,e) of u of
+ *   (gz[v,:] W_neigh^T) / len(row v), rows u < n_src, fp32 [n_src_cap, d_in].
+ * Reductions run in a fixed order (no float atomics). */
+int32_t no_sage_layer_bwd(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+                          const float* d_mean, const float* d_h, const float* d_grad_h,
+                          const float* d_w_self, const float* d_w_neigh, int32_t d_out, int32_t relu,
+                          float* d_gw_self, float* d_gw_neigh, float* d_gbias, float* d_grad_x_src,
+                          void* d_ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Whole step (loop body of Algorithm 1 with plain SGD, plus hot-embedding reuse)
+ * ---------------------------------------------------------------------------------------- */
+
+typedef struct no_step_stats {
+    float loss;
+    int32_t n_dst[NO_MAX_LAYERS], n_src[NO_MAX_LAYERS], nnz[NO_MAX_LAYERS];  /* per hop */
+    int32_t n_hit;        /* rows of V^1 served from the cache */
+    int32_t n_refresh;    /* computed rows written back to the cache */
+    int32_t n_v1;         /* |V^1| */
+    int32_t pad;
+} no_step_stats;
+
+/* dims = [F, hidden.., C] (n_layers+1 entries). Weights live inside the handle; the caller
+ * fills them through no_model_params before the first step. */
+int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t* h_dims, int32_t n_seeds_cap,
+                        const int32_t* h_fanouts, no_dtype feat_dtype, no_model_t* out);
+int32_t no_model_params(no_model_t m, int32_t layer /*1-based*/, float** d_w_self, float** d_w_neigh,
+                        float** d_bias);
+/* Gradients of the last step, device pointers (same shapes as the parameters). */
+int32_t no_model_grads(no_model_t m, int32_t layer, float** d_gw_self, float** d_gw_neigh, float** d_gbias);
+/* Activations of the last step: d_h fp32 [rows, dims[layer]] (layer 1 with a cache: all of V^1),
+ * d_mean fp32 [n_dst, dims[layer-1]]. */
+int32_t no_model_activations(no_model_t m, int32_t layer, const float** d_h, const float** d_mean);
+int32_t no_model_blocks(no_model_t m, no_blocks_t* blocks);   /* blocks of the last step (owned by m) */
+int32_t no_model_gathered(no_model_t m, const void** d_x0);   /* gathered input features of the last step */
+
+/* One training step at parameter version `step` (= number of updates already applied):
+ * sample (with hot skipping if cache != NULL), gather the bottom sources' features, forward
+ * (layer-1 rows of reusable hot vertices come from the cache), mean softmax cross-entropy on the
+ * seeds, backward (reused rows take no gradient), W <- W - lr * grad for every tensor, then every
+ * computed hot vertex's layer-1 row is stored in the cache with version = step.
+ * d_stats (device, may be NULL) receives the statistics; if h_stats != NULL the stream is
+ * synchronised and the statistics are copied to the host. */
+int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
+                      const int32_t* d_seeds, int32_t n_seeds, no_cache_t cache, int64_t step,
+                      uint64_t seed, float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream);
+int32_t no_model_destroy(no_model_t m);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NEUTRONORCH_H_ */

@@ -1,0 +1,43 @@
+// fp32 matrix products for the dense UPDATE of Eq. 2 and its gradients, on the gfx950 matrix
+// cores (v_mfma_f32_32x32x2_f32). Two shapes:
+//   NN: C[M,N] = sum_p A_p[M,K_p] * B_p[K_p,N] (+ bias, ReLU, optional 1/len row scale); M is a
+//       device scalar (rows past it are skipped); B may be given transposed.
+//   TN: P[s][K',N] = A[rows of split s]^T * G[rows of split s]; the reduction length is a device
+//       scalar; splits are summed in a fixed order afterwards (no float atomics).
+#pragma once
+#include "common.hpp"
+
+namespace no {
+
+struct GemmNNArgs {
+    const float* A[2]; int64_t lda[2]; int a_align[2];
+    const float* B[2]; int64_t ldb[2]; int b_align[2];
+    int32_t K[2];
+    float* C[2]; int64_t ldc[2];
+    const int32_t* row_scale_indptr[2];   // per problem: multiply row m by 1/(indptr[m+1]-indptr[m]) (0 if empty)
+    int32_t n_problems;                   // 1 or 2
+    int32_t accumulate;                   // 1: both products are summed into C[0]; 0: independent problems (grid.z)
+    const int32_t* d_M; int32_t M_cap; int32_t N;
+    const float* bias; int32_t relu;
+};
+
+struct GemmTNArgs {
+    const float* A[2]; int64_t lda[2]; int a_align[2];   // [R, Kp] row-major; two problems share G
+    const float* G; int64_t ldg; int g_align;            // [R, N]
+    float* P;                                            // partials [2][splits][Kp][N]
+    int32_t Kp, N;
+    const int32_t* d_R; int32_t R_cap; int32_t splits;
+};
+
+int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st);
+int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st);
+// out[q][i] = sum_s P[q][s][i], q < n_out, i < elems; fixed order.
+int32_t reduce_partials(const float* P, int32_t n_out, int32_t splits, int64_t elems, float* const* outs, hipStream_t st);
+
+inline int ptr_align(const void* p, int64_t ld) {
+    if ((((uintptr_t)p) & 15) == 0 && (ld & 3) == 0) return 4;
+    if ((((uintptr_t)p) & 7) == 0 && (ld & 1) == 0) return 2;
+    return 1;
+}
+
+}  // namespace no

@@ -1,0 +1,78 @@
+// Definitions of the opaque handles of the C ABI.
+#pragma once
+#include "common.hpp"
+
+struct no_graph_s {
+    int64_t n_vertices = 0, n_edges = 0;
+    int32_t rowptr_bits = 64;
+    no::DevBuf<int32_t> rowptr32;
+    no::DevBuf<int64_t> rowptr64;
+    no::DevBuf<int32_t> col;
+    void release() { rowptr32.release(); rowptr64.release(); col.release(); }
+};
+
+namespace no {
+
+// Per-hop device arrays of a sampled block. Scalars live in `counts` of the owning handle.
+struct HopBuffers {
+    int32_t fanout = 0;
+    int32_t n_dst_cap = 0, n_src_cap = 0, nnz_cap = 0;
+    bool has_csc = false;
+    const int32_t* d_dst = nullptr;     // alias: seeds copy, previous hop's src_global, or compute list
+    const int32_t* d_n_dst = nullptr;   // alias into counts
+    DevBuf<int32_t> src_global, indptr, nbr_global, indices, edge_row;
+    DevBuf<int32_t> csc_indptr, csc_cnt, csc_dst, csc_eid, csc_keys;
+    void release() {
+        src_global.release(); indptr.release(); nbr_global.release(); indices.release(); edge_row.release();
+        csc_indptr.release(); csc_cnt.release(); csc_dst.release(); csc_eid.release(); csc_keys.release();
+    }
+};
+
+}  // namespace no
+
+struct no_blocks_s {
+    int32_t n_layers = 0;
+    int32_t n_seeds_cap = 0;
+    int64_t n_vertices = 0;
+    bool build_csc = true;             // transpose hops 0..L-2 (select_hot's private blocks skip it)
+    no::HopBuffers hop[NO_MAX_LAYERS];
+    // counts[4*h + {0,1,2}] = n_dst, n_src, nnz of hop h; counts[4*L + {0,1}] = n_compute, n_hit;
+    // counts[4*L + 2] = scratch total
+    no::DevBuf<int32_t> counts;
+    no::DevBuf<int32_t> seeds;          // copy of the seed ids (hop 0 destinations)
+    no::DevBuf<int32_t> map;            // vertex -> local id scratch, EMPTY between hops, [V]
+    no::DevBuf<int32_t> rank;           // scan output over edges / destinations, [max cap + 1]
+    no::DevBuf<int32_t> tmp_a, tmp_b;   // radix sort temporaries [max nnz_cap with csc]
+    no::DevBuf<char> ws;                // scan / sort workspace
+    // bottom hop with a cache
+    no::DevBuf<int32_t> compute_list, compute_pos, hit_pos, hit_slot;
+    bool last_used_cache = false;
+    void release() {
+        for (auto& h : hop) h.release();
+        counts.release(); seeds.release(); map.release(); rank.release(); tmp_a.release(); tmp_b.release();
+        ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();
+    }
+};
+
+struct no_cache_s {
+    int64_t n_vertices = 0;
+    int64_t n_hot = 0;
+    int32_t staleness = 0;
+    int32_t emb_dim = 0;
+    no::DevBuf<int32_t> hot_ids, slot_of_vertex, version, freq;
+    no::DevBuf<float> emb;
+    void release() { hot_ids.release(); slot_of_vertex.release(); version.release(); freq.release(); emb.release(); }
+};
+
+namespace no {
+// Internal entry used by no_sample_blocks and no_select_hot.
+int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key,
+                           uint32_t domain, int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b,
+                           hipStream_t st);
+int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fanouts, int32_t n_layers,
+                           bool build_csc, no_blocks_s** out);
+void fill_block_view(const no_blocks_s* b, int32_t hop, no_block_view* v);
+
+// Layer pieces used by no_sage_layer_* and no_train_step (sage.hip / gemm.hip).
+struct GemmOperand { const float* p; int64_t ld; };
+}  // namespace no

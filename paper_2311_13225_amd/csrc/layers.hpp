@@ -1,0 +1,36 @@
+// Internal interfaces between the layer kernels (sage.hip, gather.hip) and the step driver.
+#pragma once
+#include "common.hpp"
+#include "gemm.hpp"
+
+namespace no {
+
+struct LayerWorkspace {
+    float* gz = nullptr;             // [n_dst_cap, d_out] masked output gradient
+    float* gmean = nullptr;          // [n_dst_cap, d_in]  gradient of the mean, pre-divided by the row length
+    float* x_dst_f32 = nullptr;      // [n_dst_cap, d_in]  fp32 copy of bf16 destination rows
+    float* partials = nullptr;       // [2, splits, d_in, d_out]
+    float* bias_partials = nullptr;  // [splits, d_out]
+    int32_t splits = 1;
+    size_t bytes = 0;
+};
+
+int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out);
+LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_t d_out);
+
+int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
+                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st);
+int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
+                            const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
+                            hipStream_t st);
+int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
+                     const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
+                     const LayerWorkspace& w, hipStream_t st);
+int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
+                      const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
+                      int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
+                      const LayerWorkspace& w, hipStream_t st);
+int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
+                    const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
+
+}  // namespace no

@@ -1,0 +1,345 @@
+// no_sage_layer_fwd / no_sage_layer_bwd: one GraphSAGE-mean layer over a sampled block.
+// Forward: mean over each destination's sampled row (Eq. 1, AGGREGATE = average), then the dense
+// UPDATE of Eq. 2 on the matrix cores. Backward: the matching weight gradients and, for layers
+// above the bottom one, the input gradient through the transposed block (segment sums in a fixed
+// order, no float atomics). The bottom layer needs only the saved mean and the new embedding.
+#include "layers.hpp"
+
+namespace no {
+
+// ------------------------------------------------------------------------ row segment reduce
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+template <typename T, int VEC> struct RowVec;
+template <> struct RowVec<float, 4> {
+    static __device__ __forceinline__ void add(float (&acc)[4], const float* p) {
+        float4 v = *reinterpret_cast<const float4*>(p);
+        acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+    }
+};
+template <> struct RowVec<float, 2> {
+    static __device__ __forceinline__ void add(float (&acc)[2], const float* p) {
+        float2 v = *reinterpret_cast<const float2*>(p);
+        acc[0] += v.x; acc[1] += v.y;
+    }
+};
+template <> struct RowVec<float, 1> {
+    static __device__ __forceinline__ void add(float (&acc)[1], const float* p) { acc[0] += p[0]; }
+};
+template <> struct RowVec<uint16_t, 8> {
+    static __device__ __forceinline__ void add(float (&acc)[8], const uint16_t* p) {
+        uint4 v = *reinterpret_cast<const uint4*>(p);
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += __uint_as_float(w[i] << 16);
+            acc[2 * i + 1] += __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+template <> struct RowVec<uint16_t, 2> {
+    static __device__ __forceinline__ void add(float (&acc)[2], const uint16_t* p) {
+        uint32_t w = *reinterpret_cast<const uint32_t*>(p);
+        acc[0] += __uint_as_float(w << 16);
+        acc[1] += __uint_as_float(w & 0xffff0000u);
+    }
+};
+template <> struct RowVec<uint16_t, 1> {
+    static __device__ __forceinline__ void add(float (&acc)[1], const uint16_t* p) { acc[0] += bf16_to_f32(p[0]); }
+};
+
+// out[row, :] = init + scale * sum_{p in [seg[row], seg[row+1])} src[idx[p], :]
+//   MEAN: scale = 1/len (0 for an empty segment), init = 0            (forward aggregate)
+//   else: scale = 1, init = out[row,:] for row < *d_n_init, else 0    (backward through the transpose)
+// A group of 2^g_log2 lanes owns a row; each lane owns vector units u0, u0+G, ... of the row.
+template <typename T, int VEC, bool MEAN>
+__global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__ src, int64_t ld_src,
+                                                           const int32_t* __restrict__ seg, const int32_t* __restrict__ idx,
+                                                           const int32_t* d_n_rows, int32_t n_rows_cap,
+                                                           const int32_t* d_n_init, float* __restrict__ out, int64_t ld_out,
+                                                           int32_t units, int32_t g_log2) {
+    int32_t n = *d_n_rows;
+    if (n > n_rows_cap) n = n_rows_cap;
+    const int32_t n_init = (!MEAN && d_n_init) ? *d_n_init : 0;
+    const int32_t lane = (int32_t)(threadIdx.x & 63);
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int32_t rows_per_pass = 64 >> g_log2;
+    const int32_t sub = lane >> g_log2, u0 = lane & ((1 << g_log2) - 1), g = 1 << g_log2;
+    for (int64_t row = wave * rows_per_pass + sub; row < n; row += n_waves * rows_per_pass) {
+        const int32_t b = seg[row], e = seg[row + 1];
+        const float scale = MEAN ? (e > b ? 1.f / (float)(e - b) : 0.f) : 1.f;
+        for (int32_t u = u0; u < units; u += g) {
+            float acc[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+            float* o = out + row * ld_out + (int64_t)u * VEC;
+            if (!MEAN && row < n_init) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = o[c];
+            }
+            int32_t p = b;
+            for (; p + 4 <= e; p += 4) {
+                const int32_t i0 = idx[p], i1 = idx[p + 1], i2 = idx[p + 2], i3 = idx[p + 3];
+                float a0[VEC], a1[VEC], a2[VEC], a3[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) a0[c] = a1[c] = a2[c] = a3[c] = 0.f;
+                RowVec<T, VEC>::add(a0, src + (int64_t)i0 * ld_src + (int64_t)u * VEC);
+                RowVec<T, VEC>::add(a1, src + (int64_t)i1 * ld_src + (int64_t)u * VEC);
+                RowVec<T, VEC>::add(a2, src + (int64_t)i2 * ld_src + (int64_t)u * VEC);
+                RowVec<T, VEC>::add(a3, src + (int64_t)i3 * ld_src + (int64_t)u * VEC);
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = (((acc[c] + a0[c]) + a1[c]) + a2[c]) + a3[c];
+            }
+            for (; p < e; ++p) RowVec<T, VEC>::add(acc, src + (int64_t)idx[p] * ld_src + (int64_t)u * VEC);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) o[c] = acc[c] * scale;
+        }
+    }
+}
+
+template <typename T, int VEC, bool MEAN>
+static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, const int32_t* idx, const int32_t* d_n,
+                           int32_t n_cap, const int32_t* d_n_init, float* out, int64_t ld_out, int32_t dim, hipStream_t st) {
+    const int32_t units = dim / VEC;
+    int g_log2 = 0;
+    while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
+    int64_t waves = ceil_div(n_cap, 64 >> g_log2);
+    int64_t blocks = ceil_div(waves, 4);
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)blocks), dim3(256), 0, st, src, ld_src, seg, idx, d_n,
+                       n_cap, d_n_init, out, ld_out, units, g_log2);
+}
+
+int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
+                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st) {
+    if (n_dst_cap <= 0) return NO_OK;
+    if (dt == NO_F32) {
+        const float* x = (const float*)x_src;
+        const bool a16 = (((uintptr_t)x | (uintptr_t)mean) & 15) == 0, a8 = (((uintptr_t)x | (uintptr_t)mean) & 7) == 0;
+        if (dim % 4 == 0 && a16) launch_segment<float, 4, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+        else if (dim % 2 == 0 && a8) launch_segment<float, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+        else launch_segment<float, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+    } else {
+        const uint16_t* x = (const uint16_t*)x_src;
+        if (dim % 8 == 0 && ((uintptr_t)x & 15) == 0 && ((uintptr_t)mean & 15) == 0)
+            launch_segment<uint16_t, 8, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+        else if (dim % 2 == 0 && ((uintptr_t)x & 3) == 0)
+            launch_segment<uint16_t, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+        else launch_segment<uint16_t, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+    }
+    return launch_status("mean_aggregate");
+}
+
+// grad_x[u,:] = (u < n_dst ? grad_x[u,:] : 0) + sum over transposed entries of u of gmean_scaled[csc_dst[p],:]
+int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
+                            const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
+                            hipStream_t st) {
+    if (n_src_cap <= 0) return NO_OK;
+    const bool a16 = (((uintptr_t)gmean_scaled | (uintptr_t)grad_x) & 15) == 0;
+    const bool a8 = (((uintptr_t)gmean_scaled | (uintptr_t)grad_x) & 7) == 0;
+    if (dim % 4 == 0 && a16)
+        launch_segment<float, 4, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st);
+    else if (dim % 2 == 0 && a8)
+        launch_segment<float, 2, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st);
+    else
+        launch_segment<float, 1, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st);
+    return launch_status("transpose_aggregate");
+}
+
+// ------------------------------------------------------------------------ small elementwise kernels
+
+__global__ void relu_mask_kernel(const float* __restrict__ grad_h, const float* __restrict__ h, const int32_t* d_n,
+                                 int32_t n_cap, int32_t dim, int32_t relu, float* __restrict__ gz) {
+    int32_t n = *d_n;
+    if (n > n_cap) n = n_cap;
+    const int64_t total = (int64_t)n * dim;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < total; i += stride) gz[i] = (!relu || h[i] > 0.f) ? grad_h[i] : 0.f;
+}
+
+// partial[s][j] = sum of gz[r][j] over the rows of split s (same split rule as the TN product)
+__global__ void colsum_partials_kernel(const float* __restrict__ gz, const int32_t* d_n, int32_t n_cap, int32_t dim,
+                                       int32_t splits, float* __restrict__ partial) {
+    int32_t R = *d_n;
+    if (R > n_cap) R = n_cap;
+    int chunk = (R + splits - 1) / splits;
+    chunk = (chunk + 31) / 32 * 32;
+    const int s = (int)blockIdx.y;
+    const int r0 = s * chunk, r1 = min(R, r0 + chunk);
+    const int j = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (j >= dim) return;
+    float acc = 0.f;
+    for (int r = r0; r < r1; ++r) acc += gz[(int64_t)r * dim + j];
+    partial[(int64_t)s * dim + j] = acc;
+}
+
+__global__ void bf16_rows_to_f32_kernel(const uint16_t* __restrict__ x, const int32_t* d_n, int32_t n_cap, int32_t dim,
+                                        float* __restrict__ out) {
+    int32_t n = *d_n;
+    if (n > n_cap) n = n_cap;
+    const int64_t total = (int64_t)n * dim;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < total; i += stride) out[i] = bf16_to_f32(x[i]);
+}
+
+static inline unsigned ew_blocks(int64_t total) {
+    int64_t b = ceil_div(total, 256 * 4);
+    if (b > 256 * 16) b = 256 * 16;
+    if (b < 1) b = 1;
+    return (unsigned)b;
+}
+
+// ------------------------------------------------------------------------ workspace layout
+
+int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out) {
+    const int64_t tiles = 2 * ceil_div(d_in, 128) * ceil_div(d_out, 128);
+    int64_t s = ceil_div(768, tiles);
+    const int64_t by_rows = ceil_div(n_dst_cap, 256);
+    if (s > by_rows) s = by_rows;
+    if (s > 64) s = 64;
+    if (s < 1) s = 1;
+    return (int32_t)s;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_t d_out) {
+    LayerWorkspace w;
+    w.splits = layer_splits(n_dst_cap, d_in, d_out);
+    size_t off = 0;
+    char* base = (char*)ws;
+    w.gz = (float*)(base + off);        off += align256((size_t)n_dst_cap * d_out * 4);
+    w.gmean = (float*)(base + off);     off += align256((size_t)n_dst_cap * d_in * 4);
+    w.x_dst_f32 = (float*)(base + off); off += align256((size_t)n_dst_cap * d_in * 4);
+    w.partials = (float*)(base + off);  off += align256((size_t)2 * w.splits * d_in * d_out * 4);
+    w.bias_partials = (float*)(base + off); off += align256((size_t)w.splits * d_out * 4);
+    w.bytes = off;
+    return w;
+}
+
+// ------------------------------------------------------------------------ layer forward / backward
+
+int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
+                     const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
+                     const LayerWorkspace& w, hipStream_t st) {
+    NO_CHECK(mean_aggregate(x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap, mean, st));
+    const float* x_dst = (const float*)x_src;
+    if (dt == NO_BF16) {
+        hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)blk.n_dst_cap * d_in)), dim3(256), 0, st,
+                           (const uint16_t*)x_src, blk.d_n_dst, blk.n_dst_cap, d_in, w.x_dst_f32);
+        x_dst = w.x_dst_f32;
+    }
+    GemmNNArgs a{};
+    a.A[0] = x_dst; a.lda[0] = d_in; a.a_align[0] = ptr_align(x_dst, d_in);
+    a.A[1] = mean;  a.lda[1] = d_in; a.a_align[1] = ptr_align(mean, d_in);
+    a.B[0] = w_self;  a.ldb[0] = d_out; a.b_align[0] = ptr_align(w_self, d_out);
+    a.B[1] = w_neigh; a.ldb[1] = d_out; a.b_align[1] = ptr_align(w_neigh, d_out);
+    a.K[0] = a.K[1] = d_in;
+    a.C[0] = h; a.ldc[0] = d_out;
+    a.n_problems = 2; a.accumulate = 1;
+    a.d_M = blk.d_n_dst; a.M_cap = blk.n_dst_cap; a.N = d_out;
+    a.bias = bias; a.relu = relu;
+    return gemm_nn(a, false, st);
+}
+
+int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
+                      const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
+                      int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
+                      const LayerWorkspace& w, hipStream_t st) {
+    const int32_t n_cap = blk.n_dst_cap;
+    hipLaunchKernelGGL(relu_mask_kernel, dim3(ew_blocks((int64_t)n_cap * d_out)), dim3(256), 0, st, grad_h, h, blk.d_n_dst,
+                       n_cap, d_out, relu, w.gz);
+    const float* x_dst = (const float*)x_src;
+    if (dt == NO_BF16) {
+        hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)n_cap * d_in)), dim3(256), 0, st,
+                           (const uint16_t*)x_src, blk.d_n_dst, n_cap, d_in, w.x_dst_f32);
+        x_dst = w.x_dst_f32;
+    }
+    // weight gradients: x_dst^T gz and mean^T gz, split over rows, summed in split order
+    GemmTNArgs t{};
+    t.A[0] = x_dst; t.lda[0] = d_in; t.a_align[0] = ptr_align(x_dst, d_in);
+    t.A[1] = mean;  t.lda[1] = d_in; t.a_align[1] = ptr_align(mean, d_in);
+    t.G = w.gz; t.ldg = d_out; t.g_align = ptr_align(w.gz, d_out);
+    t.P = w.partials; t.Kp = d_in; t.N = d_out;
+    t.d_R = blk.d_n_dst; t.R_cap = n_cap; t.splits = w.splits;
+    NO_CHECK(gemm_tn_partials(t, st));
+    hipLaunchKernelGGL(colsum_partials_kernel, dim3((unsigned)ceil_div(d_out, 256), (unsigned)w.splits), dim3(256), 0, st,
+                       (const float*)w.gz, blk.d_n_dst, n_cap, d_out, w.splits, w.bias_partials);
+    float* outs[2] = {gw_self, gw_neigh};
+    NO_CHECK(reduce_partials(w.partials, 2, w.splits, (int64_t)d_in * d_out, outs, st));
+    float* bouts[1] = {gbias};
+    NO_CHECK(reduce_partials(w.bias_partials, 1, w.splits, d_out, bouts, st));
+    if (grad_x_src) {
+        // gz W_self^T -> rows [0, n_dst) of grad_x; (gz W_neigh^T) / len(row) -> gmean; then the transpose adds
+        GemmNNArgs a{};
+        a.A[0] = a.A[1] = w.gz; a.lda[0] = a.lda[1] = d_out; a.a_align[0] = a.a_align[1] = ptr_align(w.gz, d_out);
+        a.B[0] = w_self;  a.ldb[0] = d_out; a.b_align[0] = ptr_align(w_self, d_out);
+        a.B[1] = w_neigh; a.ldb[1] = d_out; a.b_align[1] = ptr_align(w_neigh, d_out);
+        a.K[0] = a.K[1] = d_out;
+        a.C[0] = grad_x_src; a.ldc[0] = d_in;
+        a.C[1] = w.gmean;    a.ldc[1] = d_in;
+        a.row_scale_indptr[1] = blk.d_indptr;
+        a.n_problems = 2; a.accumulate = 0;
+        a.d_M = blk.d_n_dst; a.M_cap = n_cap; a.N = d_in;
+        NO_CHECK(gemm_nn(a, true, st));
+        NO_CHECK(transpose_aggregate(w.gmean, d_in, blk.d_csc_indptr, blk.d_csc_dst, blk.d_n_src, blk.n_src_cap,
+                                     blk.d_n_dst, grad_x_src, st));
+    }
+    return launch_status("sage_backward");
+}
+
+}  // namespace no
+
+using namespace no;
+
+static int32_t check_layer_args(const no_block_view* blk, const void* x, no_dtype dt, int32_t d_in, int32_t d_out,
+                                const char* who) {
+    NO_REQUIRE(blk && x, NO_ERR_INVALID_ARG, "%s: NULL argument", who);
+    NO_REQUIRE(dt == NO_F32 || dt == NO_BF16, NO_ERR_INVALID_ARG, "%s: unknown dtype", who);
+    NO_REQUIRE(d_in >= 1 && d_out >= 1, NO_ERR_INVALID_ARG, "%s: dimensions must be positive", who);
+    NO_REQUIRE(blk->n_dst_cap >= 1 && blk->n_src_cap >= blk->n_dst_cap, NO_ERR_INVALID_ARG, "%s: bad block capacities", who);
+    NO_REQUIRE(blk->d_n_dst && blk->d_indptr && blk->d_indices, NO_ERR_INVALID_ARG, "%s: block view lacks CSR arrays", who);
+    return NO_OK;
+}
+
+extern "C" size_t no_sage_layer_ws_bytes(int32_t n_dst_cap, int32_t n_src_cap, int32_t d_in, int32_t d_out) {
+    (void)n_src_cap;
+    if (n_dst_cap < 1 || d_in < 1 || d_out < 1) return 0;
+    return carve_workspace(nullptr, n_dst_cap, d_in, d_out).bytes;
+}
+
+extern "C" int32_t no_sage_layer_fwd(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+                                     const float* d_w_self, const float* d_w_neigh, const float* d_bias, int32_t d_out,
+                                     int32_t relu, float* d_mean, float* d_h, void* d_ws, size_t ws_bytes, void* stream) {
+    clear_error();
+    NO_CHECK(check_layer_args(blk, d_x_src, dt_x, d_in, d_out, "no_sage_layer_fwd"));
+    NO_REQUIRE(d_w_self && d_w_neigh && d_bias && d_mean && d_h, NO_ERR_INVALID_ARG, "no_sage_layer_fwd: NULL argument");
+    LayerWorkspace w = carve_workspace(d_ws, blk->n_dst_cap, d_in, d_out);
+    NO_REQUIRE(d_ws != nullptr && ws_bytes >= w.bytes, NO_ERR_CAPACITY, "no_sage_layer_fwd: workspace too small (%zu < %zu)",
+               ws_bytes, w.bytes);
+    return sage_forward(*blk, d_x_src, dt_x, d_in, d_w_self, d_w_neigh, d_bias, d_out, relu, d_mean, d_h, w,
+                        (hipStream_t)stream);
+}
+
+extern "C" int32_t no_sage_layer_bwd(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+                                     const float* d_mean, const float* d_h, const float* d_grad_h, const float* d_w_self,
+                                     const float* d_w_neigh, int32_t d_out, int32_t relu, float* d_gw_self,
+                                     float* d_gw_neigh, float* d_gbias, float* d_grad_x_src, void* d_ws, size_t ws_bytes,
+                                     void* stream) {
+    clear_error();
+    NO_CHECK(check_layer_args(blk, d_x_src, dt_x, d_in, d_out, "no_sage_layer_bwd"));
+    NO_REQUIRE(d_mean && d_h && d_grad_h && d_w_self && d_w_neigh && d_gw_self && d_gw_neigh && d_gbias, NO_ERR_INVALID_ARG,
+               "no_sage_layer_bwd: NULL argument");
+    NO_REQUIRE(!d_grad_x_src || (blk->d_csc_indptr && blk->d_csc_dst && blk->d_n_src), NO_ERR_INVALID_ARG,
+               "no_sage_layer_bwd: input gradient requested but the block has no transpose");
+    LayerWorkspace w = carve_workspace(d_ws, blk->n_dst_cap, d_in, d_out);
+    NO_REQUIRE(d_ws != nullptr && ws_bytes >= w.bytes, NO_ERR_CAPACITY, "no_sage_layer_bwd: workspace too small (%zu < %zu)",
+               ws_bytes, w.bytes);
+    return sage_backward(*blk, d_x_src, dt_x, d_in, d_mean, d_h, d_grad_h, d_w_self, d_w_neigh, d_out, relu, d_gw_self,
+                         d_gw_neigh, d_gbias, d_grad_x_src, w, (hipStream_t)stream);
+}

@@ -1,0 +1,357 @@
+// no_train_step: the loop body of Algorithm 1 on one stream with no host synchronisation:
+// sample -> gather -> forward -> loss -> backward -> SGD, with hot-vertex embedding reuse
+// (Section 4.1.2): layer-1 rows of reusable hot vertices come from the cache, take no gradient,
+// and every computed hot vertex refreshes its slot with version = step.
+#include "handles.hpp"
+#include "layers.hpp"
+
+struct no_model_s {
+    int32_t n_layers = 0;
+    int32_t dims[NO_MAX_LAYERS + 1] = {0};
+    int32_t fanouts[NO_MAX_LAYERS] = {0};
+    int32_t n_seeds_cap = 0;
+    no_dtype feat_dtype = NO_F32;
+    int64_t n_vertices = 0;
+    no_blocks_s* blocks = nullptr;
+    no::DevBuf<float> params, grads;                 // per layer: w_self, w_neigh, bias
+    size_t off_w_self[NO_MAX_LAYERS], off_w_neigh[NO_MAX_LAYERS], off_bias[NO_MAX_LAYERS];
+    size_t n_params = 0;
+    no::DevBuf<char> x0;                             // gathered input rows [bottom n_src_cap, F]
+    no::DevBuf<float> mean[NO_MAX_LAYERS];           // layer l (index l-1): [n_dst_cap, d_{l-1}]
+    no::DevBuf<float> h[NO_MAX_LAYERS];              // layer l output [rows, d_l]; h[0] holds all of V^1
+    no::DevBuf<float> gh[NO_MAX_LAYERS];             // gradient w.r.t. h[l-1]
+    no::DevBuf<float> h1c, gh1c;                     // layer-1 rows of the computed vertices (with a cache)
+    no::DevBuf<char> ws;
+    size_t ws_bytes = 0;
+    no::DevBuf<float> row_loss;
+    no::DevBuf<no_step_stats> stats;
+    bool last_used_cache = false;
+    void release() {
+        if (blocks) { blocks->release(); delete blocks; blocks = nullptr; }
+        params.release(); grads.release(); x0.release();
+        for (auto& b : mean) b.release();
+        for (auto& b : h) b.release();
+        for (auto& b : gh) b.release();
+        h1c.release(); gh1c.release(); ws.release(); row_loss.release(); stats.release();
+    }
+};
+
+namespace no {
+
+// One wavefront per seed: numerically stable softmax cross-entropy and its gradient, scaled by 1/n.
+__global__ void __launch_bounds__(256) softmax_xent_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                           const int32_t* __restrict__ seeds, int32_t n, int32_t n_classes,
+                                                           float* __restrict__ grad, float* __restrict__ row_loss) {
+    const int lane = (int)(threadIdx.x & 63);
+    const int row = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    if (row >= n) return;
+    const float* z = logits + (int64_t)row * n_classes;
+    float mx = -INFINITY;
+    for (int c = lane; c < n_classes; c += 64) mx = fmaxf(mx, z[c]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    float s = 0.f;
+    for (int c = lane; c < n_classes; c += 64) s += expf(z[c] - mx);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    const int y = labels[seeds[row]];
+    const float inv = 1.f / s, inv_n = 1.f / (float)n;
+    for (int c = lane; c < n_classes; c += 64) {
+        float p = expf(z[c] - mx) * inv;
+        grad[(int64_t)row * n_classes + c] = (p - (c == y ? 1.f : 0.f)) * inv_n;
+    }
+    if (lane == 0) row_loss[row] = -(z[y] - mx - logf(s));
+}
+
+// One block: mean of the per-seed losses in a fixed order, and the size statistics of the step.
+__global__ void __launch_bounds__(256) finish_stats_kernel(const float* __restrict__ row_loss, int32_t n, const int32_t* counts,
+                                                           int32_t n_layers, int32_t used_cache, no_step_stats* stats) {
+    __shared__ float sm[256];
+    float s = 0.f;
+    for (int i = (int)threadIdx.x; i < n; i += 256) s += row_loss[i];
+    sm[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        stats->loss = sm[0] / (float)n;
+        for (int h = 0; h < NO_MAX_LAYERS; ++h) {
+            stats->n_dst[h] = h < n_layers ? counts[4 * h] : 0;
+            stats->n_src[h] = h < n_layers ? counts[4 * h + 1] : 0;
+            stats->nnz[h] = h < n_layers ? counts[4 * h + 2] : 0;
+        }
+        stats->n_hit = used_cache ? counts[4 * n_layers + 1] : 0;
+        stats->n_v1 = n_layers >= 2 ? counts[4 * (n_layers - 2) + 1] : counts[0];
+        stats->pad = 0;
+    }
+}
+
+__global__ void zero_refresh_kernel(no_step_stats* stats) { stats->n_refresh = 0; }
+
+__global__ void sgd_kernel(float* __restrict__ w, const float* __restrict__ g, float lr, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) w[i] -= lr * g[i];
+}
+
+// h1[compute_pos[i], :] = h1c[i, :] (i < n_compute); h1[hit_pos[i], :] = emb[hit_slot[i], :] (i < n_hit).
+// One wavefront per row; dim is a multiple of 1 (scalar path keeps any width valid).
+__global__ void __launch_bounds__(256) assemble_h1_kernel(const float* __restrict__ h1c, const float* __restrict__ emb,
+                                                          const int32_t* __restrict__ compute_pos,
+                                                          const int32_t* __restrict__ hit_pos,
+                                                          const int32_t* __restrict__ hit_slot, const int32_t* d_n_compute,
+                                                          const int32_t* d_n_hit, int32_t dim, float* __restrict__ h1) {
+    const int32_t nc = *d_n_compute, nh = *d_n_hit;
+    const int lane = (int)(threadIdx.x & 63);
+    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (row >= (int64_t)nc + nh) return;
+    const float* src;
+    float* dst;
+    if (row < nc) { src = h1c + row * dim; dst = h1 + (int64_t)compute_pos[row] * dim; }
+    else { const int64_t i = row - nc; src = emb + (int64_t)hit_slot[i] * dim; dst = h1 + (int64_t)hit_pos[i] * dim; }
+    for (int c = lane; c < dim; c += 64) dst[c] = src[c];
+}
+
+// Every computed vertex that is hot stores its fresh layer-1 row and stamps version = step.
+__global__ void __launch_bounds__(256) refresh_cache_kernel(const float* __restrict__ h1c, const int32_t* __restrict__ computed_ids,
+                                                            const int32_t* d_n_compute, const int32_t* __restrict__ slot_of_vertex,
+                                                            int32_t dim, int32_t step, float* __restrict__ emb,
+                                                            int32_t* __restrict__ version, no_step_stats* stats) {
+    const int lane = (int)(threadIdx.x & 63);
+    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (row >= *d_n_compute) return;
+    const int32_t slot = slot_of_vertex[computed_ids[row]];
+    if (slot < 0) return;
+    const float* src = h1c + row * dim;
+    float* dst = emb + (int64_t)slot * dim;
+    for (int c = lane; c < dim; c += 64) dst[c] = src[c];
+    if (lane == 0) { version[slot] = step; atomicAdd(&stats->n_refresh, 1); }
+}
+
+static inline unsigned wave_rows_blocks(int64_t rows) { int64_t b = ceil_div(rows, 4); return (unsigned)(b < 1 ? 1 : b); }
+
+}  // namespace no
+
+using namespace no;
+
+extern "C" int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t* h_dims, int32_t n_seeds_cap,
+                                   const int32_t* h_fanouts, no_dtype feat_dtype, no_model_t* out) {
+    clear_error();
+    NO_REQUIRE(out != nullptr, NO_ERR_INVALID_ARG, "no_model_create: out is NULL");
+    *out = nullptr;
+    NO_REQUIRE(g && h_dims && h_fanouts, NO_ERR_INVALID_ARG, "no_model_create: NULL argument");
+    NO_REQUIRE(n_layers >= 1 && n_layers <= NO_MAX_LAYERS, NO_ERR_INVALID_ARG, "no_model_create: bad n_layers");
+    NO_REQUIRE(n_seeds_cap >= 1 && n_seeds_cap <= g->n_vertices, NO_ERR_INVALID_ARG, "no_model_create: bad n_seeds_cap");
+    NO_REQUIRE(feat_dtype == NO_F32 || feat_dtype == NO_BF16, NO_ERR_INVALID_ARG, "no_model_create: unknown dtype");
+    for (int32_t l = 0; l <= n_layers; ++l)
+        NO_REQUIRE(h_dims[l] >= 1 && h_dims[l] <= 65536, NO_ERR_INVALID_ARG, "no_model_create: bad dims[%d]", l);
+    for (int32_t h = 0; h < n_layers; ++h)
+        NO_REQUIRE(h_fanouts[h] >= 1 && h_fanouts[h] <= NO_MAX_FANOUT, NO_ERR_INVALID_ARG, "no_model_create: bad fanout[%d]", h);
+    no_model_s* m = new no_model_s();
+    struct Guard { no_model_s* m; ~Guard() { if (m) { m->release(); delete m; } } } guard{m};
+    m->n_layers = n_layers;
+    m->n_seeds_cap = n_seeds_cap;
+    m->feat_dtype = feat_dtype;
+    m->n_vertices = g->n_vertices;
+    for (int32_t l = 0; l <= n_layers; ++l) m->dims[l] = h_dims[l];
+    for (int32_t h = 0; h < n_layers; ++h) m->fanouts[h] = h_fanouts[h];
+    NO_CHECK(blocks_create_impl(g, n_seeds_cap, h_fanouts, n_layers, true, &m->blocks));
+    size_t off = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const size_t wsz = (size_t)m->dims[l] * m->dims[l + 1];
+        m->off_w_self[l] = off;  off += (wsz + 63) & ~(size_t)63;
+        m->off_w_neigh[l] = off; off += (wsz + 63) & ~(size_t)63;
+        m->off_bias[l] = off;    off += ((size_t)m->dims[l + 1] + 63) & ~(size_t)63;
+    }
+    m->n_params = off;
+    NO_CHECK(m->params.alloc(off));
+    NO_CHECK(m->grads.alloc(off));
+    NO_HIP_CHECK(hipMemset(m->params.p, 0, off * 4));
+    NO_HIP_CHECK(hipMemset(m->grads.p, 0, off * 4));
+    const int32_t L = n_layers;
+    const HopBuffers& bottom = m->blocks->hop[L - 1];
+    const size_t es = feat_dtype == NO_F32 ? 4 : 2;
+    NO_CHECK(m->x0.alloc((size_t)bottom.n_src_cap * m->dims[0] * es));
+    size_t ws_bytes = 0;
+    for (int32_t l = 1; l <= L; ++l) {
+        const HopBuffers& H = m->blocks->hop[L - l];
+        NO_CHECK(m->mean[l - 1].alloc((size_t)H.n_dst_cap * m->dims[l - 1]));
+        NO_CHECK(m->h[l - 1].alloc((size_t)H.n_dst_cap * m->dims[l]));
+        NO_CHECK(m->gh[l - 1].alloc((size_t)H.n_dst_cap * m->dims[l]));
+        const size_t b = carve_workspace(nullptr, H.n_dst_cap, m->dims[l - 1], m->dims[l]).bytes;
+        if (b > ws_bytes) ws_bytes = b;
+    }
+    if (L >= 2) {
+        NO_CHECK(m->h1c.alloc((size_t)bottom.n_dst_cap * m->dims[1]));
+        NO_CHECK(m->gh1c.alloc((size_t)bottom.n_dst_cap * m->dims[1]));
+    }
+    m->ws_bytes = ws_bytes;
+    NO_CHECK(m->ws.alloc(ws_bytes));
+    NO_CHECK(m->row_loss.alloc((size_t)n_seeds_cap));
+    NO_CHECK(m->stats.alloc(1));
+    NO_HIP_CHECK(hipMemset(m->stats.p, 0, sizeof(no_step_stats)));
+    NO_HIP_CHECK(hipDeviceSynchronize());
+    guard.m = nullptr;
+    *out = m;
+    return NO_OK;
+}
+
+static int32_t check_layer_index(no_model_t m, int32_t layer, const char* who) {
+    NO_REQUIRE(m != nullptr, NO_ERR_INVALID_ARG, "%s: model is NULL", who);
+    NO_REQUIRE(layer >= 1 && layer <= m->n_layers, NO_ERR_INVALID_ARG, "%s: layer must be in [1, %d]", who, m->n_layers);
+    return NO_OK;
+}
+
+extern "C" int32_t no_model_params(no_model_t m, int32_t layer, float** d_w_self, float** d_w_neigh, float** d_bias) {
+    clear_error();
+    NO_CHECK(check_layer_index(m, layer, "no_model_params"));
+    if (d_w_self) *d_w_self = m->params.p + m->off_w_self[layer - 1];
+    if (d_w_neigh) *d_w_neigh = m->params.p + m->off_w_neigh[layer - 1];
+    if (d_bias) *d_bias = m->params.p + m->off_bias[layer - 1];
+    return NO_OK;
+}
+
+extern "C" int32_t no_model_grads(no_model_t m, int32_t layer, float** d_gw_self, float** d_gw_neigh, float** d_gbias) {
+    clear_error();
+    NO_CHECK(check_layer_index(m, layer, "no_model_grads"));
+    if (d_gw_self) *d_gw_self = m->grads.p + m->off_w_self[layer - 1];
+    if (d_gw_neigh) *d_gw_neigh = m->grads.p + m->off_w_neigh[layer - 1];
+    if (d_gbias) *d_gbias = m->grads.p + m->off_bias[layer - 1];
+    return NO_OK;
+}
+
+extern "C" int32_t no_model_activations(no_model_t m, int32_t layer, const float** d_h, const float** d_mean) {
+    clear_error();
+    NO_CHECK(check_layer_index(m, layer, "no_model_activations"));
+    if (d_h) *d_h = m->h[layer - 1].p;
+    if (d_mean) *d_mean = m->mean[layer - 1].p;
+    return NO_OK;
+}
+
+extern "C" int32_t no_model_blocks(no_model_t m, no_blocks_t* blocks) {
+    clear_error();
+    NO_REQUIRE(m && blocks, NO_ERR_INVALID_ARG, "no_model_blocks: NULL argument");
+    *blocks = m->blocks;
+    return NO_OK;
+}
+
+extern "C" int32_t no_model_gathered(no_model_t m, const void** d_x0) {
+    clear_error();
+    NO_REQUIRE(m && d_x0, NO_ERR_INVALID_ARG, "no_model_gathered: NULL argument");
+    *d_x0 = m->x0.p;
+    return NO_OK;
+}
+
+extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
+                                 const int32_t* d_seeds, int32_t n_seeds, no_cache_t cache, int64_t step, uint64_t seed,
+                                 float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream) {
+    clear_error();
+    NO_REQUIRE(m && g && d_features && d_labels && d_seeds, NO_ERR_INVALID_ARG, "no_train_step: NULL argument");
+    NO_REQUIRE(n_seeds >= 1, NO_ERR_INVALID_ARG, "no_train_step: n_seeds must be positive");
+    NO_REQUIRE(n_seeds <= m->n_seeds_cap, NO_ERR_CAPACITY, "no_train_step: %d seeds exceed the capacity %d", n_seeds,
+               m->n_seeds_cap);
+    NO_REQUIRE(m->n_vertices == g->n_vertices, NO_ERR_INVALID_ARG, "no_train_step: model was created for another graph");
+    NO_REQUIRE(step >= 0 && step < (1ll << 31), NO_ERR_INVALID_ARG, "no_train_step: step out of range");
+    const int32_t L = m->n_layers;
+    if (cache) {
+        NO_REQUIRE(cache->n_vertices == g->n_vertices, NO_ERR_INVALID_ARG, "no_train_step: cache belongs to another graph");
+        NO_REQUIRE(L < 2 || cache->emb_dim == m->dims[1], NO_ERR_INVALID_ARG,
+                   "no_train_step: cache rows have %d columns, layer 1 has %d", cache->emb_dim, m->dims[1]);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    no_blocks_s* B = m->blocks;
+    no_step_stats* stats = d_stats ? d_stats : m->stats.p;
+
+    // sample
+    NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st));
+    const bool used_cache = B->last_used_cache;
+    m->last_used_cache = used_cache;
+    const int32_t* extra = B->counts.p + 4 * L;
+
+    // gather the bottom hop's source rows
+    const HopBuffers& bottom = B->hop[L - 1];
+    const int32_t es = m->feat_dtype == NO_F32 ? 4 : 2;
+    const int32_t row_bytes = m->dims[0] * es;
+    NO_CHECK(gather_rows(d_features, row_bytes, row_bytes, bottom.src_global.p, B->counts.p + 4 * (L - 1) + 1,
+                         bottom.n_src_cap, m->x0.p, row_bytes, st));
+
+    // forward
+    no_block_view view[NO_MAX_LAYERS];
+    for (int32_t h = 0; h < L; ++h) fill_block_view(B, h, &view[h]);
+    for (int32_t l = 1; l <= L; ++l) {
+        const no_block_view& blk = view[L - l];
+        const int32_t d_in = m->dims[l - 1], d_out = m->dims[l];
+        const void* x = l == 1 ? (const void*)m->x0.p : (const void*)m->h[l - 2].p;
+        const no_dtype dt = l == 1 ? m->feat_dtype : NO_F32;
+        float* h_out = (l == 1 && used_cache) ? m->h1c.p : m->h[l - 1].p;
+        LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
+        NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
+                              m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st));
+        if (l == 1 && used_cache) {
+            hipLaunchKernelGGL(assemble_h1_kernel, dim3(wave_rows_blocks(blk.n_dst_cap)), dim3(256), 0, st,
+                               (const float*)m->h1c.p, (const float*)cache->emb.p, (const int32_t*)B->compute_pos.p,
+                               (const int32_t*)B->hit_pos.p, (const int32_t*)B->hit_slot.p, extra + 0, extra + 1, d_out,
+                               m->h[0].p);
+        }
+    }
+
+    // loss on the seeds
+    const int32_t C = m->dims[L];
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3(wave_rows_blocks(n_seeds)), dim3(256), 0, st, (const float*)m->h[L - 1].p,
+                       d_labels, (const int32_t*)B->seeds.p, n_seeds, C, m->gh[L - 1].p, m->row_loss.p);
+    hipLaunchKernelGGL(finish_stats_kernel, dim3(1), dim3(256), 0, st, (const float*)m->row_loss.p, n_seeds,
+                       (const int32_t*)B->counts.p, L, used_cache ? 1 : 0, stats);
+    hipLaunchKernelGGL(zero_refresh_kernel, dim3(1), dim3(1), 0, st, stats);
+
+    // backward
+    for (int32_t l = L; l >= 1; --l) {
+        const no_block_view& blk = view[L - l];
+        const int32_t d_in = m->dims[l - 1], d_out = m->dims[l];
+        const void* x = l == 1 ? (const void*)m->x0.p : (const void*)m->h[l - 2].p;
+        const no_dtype dt = l == 1 ? m->feat_dtype : NO_F32;
+        const float* h_l = m->h[l - 1].p;
+        const float* gh_l = m->gh[l - 1].p;
+        if (l == 1 && used_cache) {
+            // reused rows take no gradient: keep only the rows of the computed vertices
+            NO_CHECK(gather_rows(m->gh[0].p, d_out * 4, (int64_t)d_out * 4, B->compute_pos.p, extra + 0, blk.n_dst_cap,
+                                 m->gh1c.p, (int64_t)d_out * 4, st));
+            h_l = m->h1c.p;
+            gh_l = m->gh1c.p;
+        }
+        LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
+        NO_CHECK(sage_backward(blk, x, dt, d_in, m->mean[l - 1].p, h_l, gh_l, m->params.p + m->off_w_self[l - 1],
+                               m->params.p + m->off_w_neigh[l - 1], d_out, l < L ? 1 : 0,
+                               m->grads.p + m->off_w_self[l - 1], m->grads.p + m->off_w_neigh[l - 1],
+                               m->grads.p + m->off_bias[l - 1], l > 1 ? m->gh[l - 2].p : nullptr, w, st));
+    }
+
+    // parameter update, then cache refresh with the rows computed by the pre-update weights
+    {
+        int64_t blocks = ceil_div((int64_t)m->n_params, 256 * 4);
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)blocks), dim3(256), 0, st, m->params.p, (const float*)m->grads.p, lr,
+                           (int64_t)m->n_params);
+    }
+    if (used_cache) {
+        hipLaunchKernelGGL(refresh_cache_kernel, dim3(wave_rows_blocks(bottom.n_dst_cap)), dim3(256), 0, st,
+                           (const float*)m->h1c.p, (const int32_t*)B->compute_list.p, extra + 0,
+                           (const int32_t*)cache->slot_of_vertex.p, m->dims[1], (int32_t)step, cache->emb.p,
+                           cache->version.p, stats);
+    }
+    NO_CHECK(launch_status("train_step"));
+    if (h_stats) {
+        NO_HIP_CHECK(hipMemcpyAsync(h_stats, stats, sizeof(no_step_stats), hipMemcpyDeviceToHost, st));
+        NO_HIP_CHECK(hipStreamSynchronize(st));
+    }
+    return NO_OK;
+}
+
+extern "C" int32_t no_model_destroy(no_model_t m) {
+    clear_error();
+    if (!m) return NO_OK;
+    m->release();
+    delete m;
+    return NO_OK;
+}

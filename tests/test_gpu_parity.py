@@ -1,0 +1,392 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded
+inputs. Integer outputs (CSR, sampled blocks, transposes, hot sets, cache versions, gathered
+bytes) must match bit for bit; fp32 activations and gradients must satisfy
+|gpu - ora| <= 1e-4 * |ora| + 1e-4 * max|ora| per tensor."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import oracle as ora
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-4
+
+
+def nb():
+    from paper_2311_13225_amd import binding
+    return binding
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def assert_close(gpu, ref, what=""):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    if ref.size == 0:
+        return
+    tol = RTOL * np.abs(ref) + RTOL * np.abs(ref).max()
+    err = np.abs(gpu - ref)
+    bad = err > tol
+    assert not bad.any(), "%s: %d of %d outside tolerance, worst err %.3e (tol %.3e)" % (
+        what, bad.sum(), ref.size, err.max(), tol[np.unravel_index(err.argmax(), err.shape)])
+
+
+def make_graph(V, E, seed, bits, symmetrise=False):
+    src, dst = si.rmat_edges(V, E, seed, symmetrise=symmetrise)
+    og = ora.build_csr(src, dst, V)
+    gg = nb().no_build_csr(src, dst, V, bits)
+    return src, dst, og, gg
+
+
+# --------------------------------------------------------------------------------------- CSR
+
+@pytest.mark.parametrize("V,E,bits", [(50, 0, 32), (1, 5, 64), (300, 4000, 32), (10_000, 100_000, 64),
+                                      (70_000, 1_500_000, 32)])
+def test_build_csr_matches_oracle(V, E, bits):
+    print("case", V, E, bits, flush=True)
+    src, dst, og, gg = make_graph(V, E, 1, bits)
+    v, e, b, rowptr, col = nb().no_graph_view(gg)
+    assert (v, e, b) == (V, E, bits)
+    assert np.array_equal(rowptr.cpu().numpy().astype(np.int64), og.rowptr)
+    if E:
+        assert np.array_equal(col.cpu().numpy(), og.col)
+
+
+def test_build_csr_from_device_and_rejects_bad_ids():
+    src, dst = si.rmat_edges(500, 5000, 2)
+    og = ora.build_csr(src, dst, 500)
+    gg = nb().no_build_csr(dev(src), dev(dst), 500, 64)
+    assert np.array_equal(nb().no_graph_view(gg)[4].cpu().numpy(), og.col)
+    bad = src.copy()
+    bad[7] = 500
+    with pytest.raises(nb().NoError) as ei:
+        nb().no_build_csr(bad, dst, 500, 64)
+    assert ei.value.code == -2
+    with pytest.raises(nb().NoError):
+        nb().no_build_csr(src, dst, 500, 48)
+
+
+# --------------------------------------------------------------------------------------- sampling
+
+def compare_blocks(b, blocks, sb, with_cache=False):
+    sizes = b.no_blocks_sizes(blocks)
+    L = len(sb.blocks)
+    for h, ob in enumerate(sb.blocks):
+        assert sizes[h, 0] == ob.n_dst and sizes[h, 1] == ob.n_src and sizes[h, 2] == ob.nnz, (h, sizes[h], ob.n_dst, ob.n_src, ob.nnz)
+        ga = b.block_arrays(blocks, h, sizes)
+        for name in ["dst_global", "src_global", "indptr", "nbr_global", "indices"]:
+            assert np.array_equal(ga[name], getattr(ob, name)), (h, name)
+        if h < L - 1:
+            for name in ["csc_indptr", "csc_dst", "csc_eid"]:
+                assert np.array_equal(ga[name], getattr(ob, name)), (h, name)
+        else:
+            assert ga["csc_indptr"] is None
+        if with_cache and h == L - 1:
+            assert sizes[h, 3] == len(sb.hit_pos)
+            assert np.array_equal(ga["compute_pos"], sb.compute_pos)
+            assert np.array_equal(ga["hit_pos"], sb.hit_pos)
+            assert np.array_equal(ga["hit_slot"], sb.hit_slot)
+    return sizes
+
+
+@pytest.mark.parametrize("bits", [32, 64])
+def test_sample_blocks_tiny_config(bits):
+    b = nb()
+    w = si.WORKLOADS["tiny"]
+    src, dst, og, gg = make_graph(w.n_vertices, w.n_edges, w.seed, bits)
+    train = si.train_split(w.n_vertices, 0.65, w.seed)
+    blocks = b.no_blocks_create(gg, w.batch, w.fanouts)
+    for step in [0, 1, 7]:
+        seeds = si.batch_seeds(train, w.batch, step)
+        b.no_sample_blocks(gg, dev(seeds), 0, step, None, blocks)
+        compare_blocks(b, blocks, ora.sample_blocks(og, seeds, w.fanouts, 0, step))
+    # ragged batch smaller than the capacity, other seed
+    seeds = train[:37].copy()
+    b.no_sample_blocks(gg, dev(seeds), 12345678901234567, 3, None, blocks)
+    compare_blocks(b, blocks, ora.sample_blocks(og, seeds, w.fanouts, 12345678901234567, 3))
+
+
+@pytest.mark.parametrize("fanouts", [(1,), (3, 2), (8, 8), (9, 16, 2), (17, 5), (32, 3), (33, 2), (64,), (25, 10)])
+def test_sample_blocks_group_widths_and_dense_rows(fanouts):
+    """Every lane-group width (8/16/32/64), rows shorter and much longer than the fanout."""
+    b = nb()
+    V = 3000
+    src, dst, og, gg = make_graph(V, 150_000, 5, 64)
+    train = si.train_split(V, 0.65, 5)
+    cap = 64 if len(fanouts) < 3 else 16
+    blocks = b.no_blocks_create(gg, cap, fanouts)
+    for step in range(2):
+        seeds = si.batch_seeds(train, cap, step)
+        b.no_sample_blocks(gg, dev(seeds), 99, step, None, blocks)
+        compare_blocks(b, blocks, ora.sample_blocks(og, seeds, fanouts, 99, step))
+
+
+def test_sample_blocks_sparse_graph_with_isolated_vertices():
+    b = nb()
+    V = 5000
+    src, dst, og, gg = make_graph(V, 6000, 9, 32)
+    seeds = si.train_split(V, 0.9, 9)[:512]
+    blocks = b.no_blocks_create(gg, 512, (5, 5, 5))
+    b.no_sample_blocks(gg, dev(seeds), 1, 0, None, blocks)
+    sizes = compare_blocks(b, blocks, ora.sample_blocks(og, seeds, (5, 5, 5), 1, 0))
+    assert sizes[0, 2] < 512 * 5       # some rows are short or empty
+
+
+def test_sample_blocks_rejects_bad_arguments():
+    b = nb()
+    src, dst, og, gg = make_graph(300, 2000, 1, 32)
+    blocks = b.no_blocks_create(gg, 8, (2, 2))
+    seeds = dev(np.arange(9, dtype=np.int32))
+    with pytest.raises(b.NoError) as ei:
+        b.no_sample_blocks(gg, seeds, 0, 0, None, blocks)
+    assert ei.value.code == -3
+    with pytest.raises(b.NoError):
+        b.no_blocks_create(gg, 8, (0, 2))
+    with pytest.raises(b.NoError):
+        b.no_blocks_create(gg, 8, (65,))
+
+
+# --------------------------------------------------------------------------------------- hot set
+
+@pytest.mark.parametrize("fanouts,frac", [((10, 5), 0.05), ((4, 3, 2), 0.1), ((6,), 0.2)])
+def test_select_hot_matches_oracle(fanouts, frac):
+    b = nb()
+    V = 10_000
+    src, dst, og, gg = make_graph(V, 100_000, 0, 32)
+    train = si.train_split(V, 0.3, 0)
+    oc = ora.select_hot(og, train, 256, fanouts, 2, frac, 1, 16, 42)
+    gc = b.no_select_hot(gg, dev(train), 256, fanouts, 2, frac, 1, 16, 42)
+    view = b.no_cache_view(gc, V)
+    assert view["n_hot"] == oc.n_hot and view["emb_dim"] == 16 and view["staleness"] == 1
+    assert np.array_equal(view["freq"].cpu().numpy().astype(np.int64), oc.freq)
+    assert np.array_equal(view["hot_ids"].cpu().numpy(), oc.hot_ids)
+    assert np.array_equal(view["slot_of_vertex"].cpu().numpy(), oc.slot_of_vertex)
+    assert (view["version"].cpu().numpy() == -1).all()
+    assert not view["emb"].cpu().numpy().any()
+
+
+def test_sample_blocks_with_cache_lookup():
+    b = nb()
+    w = si.WORKLOADS["tiny"]
+    src, dst, og, gg = make_graph(w.n_vertices, w.n_edges, w.seed, 32)
+    train = si.train_split(w.n_vertices, 0.65, w.seed)
+    oc = ora.select_hot(og, train, w.batch, w.fanouts, 1, 0.2, 2, 8, 0)
+    gc = b.no_select_hot(gg, dev(train), w.batch, w.fanouts, 1, 0.2, 2, 8, 0)
+    rng = np.random.default_rng(0)
+    ver = rng.integers(-1, 6, oc.n_hot).astype(np.int32)       # empty, fresh and stale slots
+    oc.version[:] = ver
+    b.no_cache_view(gc, w.n_vertices)["version"].copy_(dev(ver))
+    blocks = b.no_blocks_create(gg, w.batch, w.fanouts)
+    total_hits = 0
+    for step in [5, 6, 9]:
+        seeds = si.batch_seeds(train, w.batch, step)
+        b.no_sample_blocks(gg, dev(seeds), 0, step, gc, blocks)
+        sb = ora.sample_blocks(og, seeds, w.fanouts, 0, step, oc)
+        compare_blocks(b, blocks, sb, with_cache=True)
+        total_hits += len(sb.hit_pos)
+    assert total_hits > 0
+
+
+# --------------------------------------------------------------------------------------- gather
+
+@pytest.mark.parametrize("dim,dtype", [(64, "f32"), (602, "f32"), (100, "f32"), (7, "f32"), (256, "f32"),
+                                       (128, "bf16"), (6, "bf16"), (5, "bf16")])
+def test_gather_is_bit_copy(dim, dtype):
+    b = nb()
+    V, n = 5000, 3001
+    table = si.features(V, dim, 3, dtype)
+    ids = np.random.default_rng(1).integers(0, V, n).astype(np.int32)
+    t = dev(table.view(np.int16) if dtype == "bf16" else table)
+    out = b.no_gather_features(t, dev(ids))
+    assert np.array_equal(out.cpu().numpy().view(table.dtype), ora.gather_features(table, ids))
+    # device-side count: only the first rows are written
+    out2 = torch.zeros_like(out)
+    b.no_gather_features(t, dev(ids), out2, dev(np.array([1234], np.int32)))
+    got = out2.cpu().numpy().view(table.dtype)
+    assert np.array_equal(got[:1234], table[ids[:1234]]) and not got[1234:].any()
+    b.no_gather_features(t, dev(ids), out2, dev(np.array([0], np.int32)))
+
+
+# --------------------------------------------------------------------------------------- layers
+
+def layer_case(V, E, F, d_out, fanouts, B, seed, bf16=False):
+    src, dst = si.rmat_edges(V, E, seed)
+    og = ora.build_csr(src, dst, V)
+    seeds = si.train_split(V, 0.65, seed)[:B]
+    sb = ora.sample_blocks(og, seeds, fanouts, seed, 0)
+    blk = sb.blocks[-1]
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((blk.n_src, F)).astype(np.float32)
+    if bf16:
+        xb = si.f32_to_bf16_bits(x)
+        x = si.bf16_bits_to_f32(xb)
+    else:
+        xb = None
+    (w_self, w_neigh, bias), = si.init_weights([F, d_out], seed)
+    return blk, x, xb, w_self, w_neigh, bias, rng
+
+
+@pytest.mark.parametrize("F,d_out,relu,bf16", [(64, 64, True, False), (602, 256, True, False), (100, 47, False, False),
+                                               (33, 5, True, False), (256, 130, True, False), (128, 256, True, True),
+                                               (6, 3, False, True)])
+def test_sage_layer_forward_backward(F, d_out, relu, bf16):
+    b = nb()
+    blk, x, xb, w_self, w_neigh, bias, rng = layer_case(4000, 60_000, F, d_out, (7, 6), 300, 11, bf16)
+    n_dst, n_src, nnz = blk.n_dst, blk.n_src, blk.nnz
+    cap_dst, cap_src = n_dst + 77, n_src + 130          # capacities larger than the actual sizes
+    d_n_dst, d_n_src = dev(np.array([n_dst], np.int32)), dev(np.array([n_src], np.int32))
+    indptr = dev(np.concatenate([blk.indptr, np.zeros(77, np.int32)]))
+    view = b.block_view_from_tensors(d_n_dst, d_n_src, indptr, dev(blk.indices), cap_dst, cap_src,
+                                     dev(np.concatenate([blk.csc_indptr, np.zeros(130, np.int32)])), dev(blk.csc_dst))
+    xs = dev(xb.view(np.int16)) if bf16 else dev(x)
+    ws = torch.empty(b.no_sage_layer_ws_bytes(cap_dst, cap_src, F, d_out), dtype=torch.uint8, device="cuda")
+    mean = torch.full((cap_dst, F), 7.0, device="cuda")
+    h = torch.full((cap_dst, d_out), 7.0, device="cuda")
+    tw_self, tw_neigh, tbias = dev(w_self), dev(w_neigh), dev(bias)
+    b.no_sage_layer_fwd(view, xs, tw_self, tw_neigh, tbias, relu, mean, h, ws)
+    o_mean, o_h = ora.sage_layer_fwd(blk, x, w_self, w_neigh, bias, relu)
+    assert_close(mean[:n_dst].cpu().numpy(), o_mean, "mean")
+    assert_close(h[:n_dst].cpu().numpy(), o_h, "h")
+    assert (h[n_dst:] == 7.0).all() and (mean[n_dst:] == 7.0).all()      # rows past n_dst untouched
+
+    # backward: feed the oracle's own forward values so the ReLU masks agree
+    grad_h = rng.standard_normal((n_dst, d_out)).astype(np.float32)
+    o_h32 = o_h.astype(np.float32)
+    gws = torch.zeros((F, d_out), device="cuda")
+    gwn = torch.zeros((F, d_out), device="cuda")
+    gb = torch.zeros((d_out,), device="cuda")
+    gx = torch.full((cap_src, F), 3.0, device="cuda")
+    hh = torch.zeros((cap_dst, d_out), device="cuda")
+    hh[:n_dst] = dev(o_h32)
+    gh = torch.zeros((cap_dst, d_out), device="cuda")
+    gh[:n_dst] = dev(grad_h)
+    mm = torch.zeros((cap_dst, F), device="cuda")
+    mm[:n_dst] = dev(o_mean.astype(np.float32))
+    for need_gx in (True, False):
+        b.no_sage_layer_bwd(view, xs, mm, hh, gh, tw_self, tw_neigh, relu, gws, gwn, gb, gx if need_gx else None, ws)
+        r = ora.sage_layer_bwd(blk, x, o_mean.astype(np.float32), o_h32, grad_h, w_self, w_neigh, relu, need_gx)
+        assert_close(gws.cpu().numpy(), r[0], "gw_self")
+        assert_close(gwn.cpu().numpy(), r[1], "gw_neigh")
+        assert_close(gb.cpu().numpy(), r[2], "gbias")
+        if need_gx:
+            assert_close(gx[:n_src].cpu().numpy(), r[3], "grad_x")
+            assert (gx[n_src:] == 3.0).all()
+    # bit-stable: the same call twice gives identical bits (fixed reduction order, no float atomics)
+    g1 = gws.clone()
+    b.no_sage_layer_bwd(view, xs, mm, hh, gh, tw_self, tw_neigh, relu, gws, gwn, gb, None, ws)
+    assert torch.equal(g1, gws)
+
+
+def test_sage_layer_empty_block_and_small_workspace():
+    b = nb()
+    n0 = dev(np.array([0], np.int32))
+    view = b.block_view_from_tensors(n0, n0, dev(np.zeros(9, np.int32)), dev(np.zeros(4, np.int32)), 8, 8)
+    x = torch.zeros((8, 4), device="cuda")
+    w = torch.ones((4, 3), device="cuda")
+    bias = torch.ones(3, device="cuda")
+    mean = torch.zeros((8, 4), device="cuda")
+    h = torch.full((8, 3), 5.0, device="cuda")
+    ws = torch.empty(b.no_sage_layer_ws_bytes(8, 8, 4, 3), dtype=torch.uint8, device="cuda")
+    b.no_sage_layer_fwd(view, x, w, w, bias, True, mean, h, ws)
+    assert (h == 5.0).all()
+    with pytest.raises(b.NoError) as ei:
+        b.no_sage_layer_fwd(view, x, w, w, bias, True, mean, h, ws[:16])
+    assert ei.value.code == -3
+
+
+# --------------------------------------------------------------------------------------- whole step
+
+def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None, bits=32, presample=1):
+    b = nb()
+    V = V or w.n_vertices
+    E = E or w.n_edges
+    src, dst, og, gg = make_graph(V, E, w.seed, bits, w.symmetrise)
+    feat = si.features(V, w.feat_dim, w.seed, w.feat_dtype)
+    lab = si.labels(V, w.n_classes, w.seed)
+    train = si.train_split(V, 0.65, w.seed)
+    weights = si.init_weights(w.dims, w.seed)
+    bf16 = w.feat_dtype == "bf16"
+    model = b.no_model_create(gg, w.dims, w.batch, w.fanouts, b.NO_BF16 if bf16 else b.NO_F32)
+    for l in range(w.n_layers):
+        for t, a in zip(b.no_model_params(model, l + 1), weights[l]):
+            t.copy_(dev(a))
+    frac = w.hot_fraction if hot_fraction is None else hot_fraction
+    oc = gc = None
+    if use_cache:
+        oc = ora.select_hot(og, train, w.batch, w.fanouts, presample, frac, w.staleness, w.hidden, w.seed)
+        gc = b.no_select_hot(gg, dev(train), w.batch, w.fanouts, presample, frac, w.staleness, w.hidden, w.seed)
+        assert np.array_equal(b.no_cache_view(gc, V)["hot_ids"].cpu().numpy(), oc.hot_ids)
+    tfeat = dev(feat.view(np.int16) if bf16 else feat)
+    tlab = dev(lab)
+    ow = [tuple(np.asarray(t, np.float64) for t in x) for x in weights]
+    hits = 0
+    for step in range(n_steps):
+        seeds = si.batch_seeds(train, w.batch, step)
+        print("step", step, flush=True)
+        st = b.no_train_step(model, gg, tfeat, tlab, dev(seeds), gc, step, w.seed, lr)
+        r = ora.train_step(og, feat, lab, seeds, w.fanouts, ow, lr, w.seed, step, oc, feat_is_bf16=bf16)
+        # integers: block sizes, blocks, hits
+        blocks = b.no_model_blocks(model)
+        sizes = compare_blocks(b, blocks, r.batch, with_cache=use_cache and w.n_layers >= 2 and oc.n_hot > 0)
+        for h in range(w.n_layers):
+            assert (st.n_dst[h], st.n_src[h], st.nnz[h]) == tuple(int(x) for x in sizes[h, :3])
+        assert st.n_hit == r.n_hit
+        hits += r.n_hit
+        # gathered rows: bit copy
+        x0 = b.no_model_gathered(model, r.batch.blocks[-1].n_src).cpu().numpy()
+        assert np.array_equal(x0.view(feat.dtype), r.x0)
+        # floats
+        assert abs(st.loss - r.loss) <= RTOL * abs(r.loss) + 1e-6, (st.loss, r.loss)
+        for l in range(1, w.n_layers + 1):
+            n_rows = r.h[l - 1].shape[0]
+            n_dst = r.batch.blocks[w.n_layers - l].n_dst
+            gh, gm = b.no_model_activations(model, l, n_rows, n_dst)
+            assert_close(gm.cpu().numpy(), r.mean[l - 1], "mean%d step %d" % (l, step))
+            assert_close(gh.cpu().numpy(), r.h[l - 1], "h%d step %d" % (l, step))
+            for t, ref, name in zip(b.no_model_grads(model, l), r.grads[l - 1], ["gw_self", "gw_neigh", "gbias"]):
+                assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step))
+            for t, ref, name in zip(b.no_model_params(model, l), r.new_weights[l - 1], ["w_self", "w_neigh", "bias"]):
+                assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step))
+        ow = r.new_weights
+        if use_cache and oc.n_hot > 0:
+            view = b.no_cache_view(gc, V)
+            assert np.array_equal(view["version"].cpu().numpy(), oc.version)
+            assert_close(view["emb"].cpu().numpy(), oc.emb, "emb step %d" % step)
+    return hits
+
+
+def test_train_steps_tiny_config_exact():
+    run_steps(si.WORKLOADS["tiny"], 3, use_cache=False)
+
+
+def test_train_steps_tiny_config_with_cache_S0_never_hits():
+    assert run_steps(si.WORKLOADS["tiny"], 3, use_cache=True) == 0      # the tiny config has S = 0
+
+
+def test_train_steps_with_reuse():
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=2, hot_fraction=0.2)
+    assert run_steps(w, 5, use_cache=True, lr=0.02) > 0
+
+
+def test_train_steps_three_layers_with_reuse():
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(4, 3, 3), staleness=1, hot_fraction=0.3, n_classes=47,
+                            feat_dim=100, hidden=40, batch=128)
+    assert run_steps(w, 4, use_cache=True, lr=0.02, bits=64) > 0
+
+
+def test_train_step_single_layer_and_bf16_features():
+    import dataclasses
+    w1 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(6,), batch=200)
+    run_steps(w1, 2, use_cache=False)
+    wb = dataclasses.replace(si.WORKLOADS["tiny"], feat_dtype="bf16", feat_dim=128, staleness=2, hot_fraction=0.1)
+    run_steps(wb, 3, use_cache=True)
