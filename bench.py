@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the sample -> gather -> train hot path on one MI355X.
+
+A "step" is one pass of the whole path (sample L hops, gather, forward, loss, backward, SGD,
+cache refresh) over one batch of seeds of the named synthetic workload, with graph, features,
+labels, weights and the seed batches already resident in HBM. Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dense|tiny|sparse|sweep]
+
+`value` = train steps/s of the unprofiled timed region. A second pass over the same steps with
+per-stage HIP events on the step's stream gives the stage times, the sampled-edges/s and gather
+GB/s figures (`extra`) and the `roofline` object of the dominant kernel. `cpu_baseline` times the
+CPU oracle on a bounded number of the same steps.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="dense")
+    ap.add_argument("--no-cache", action="store_true", help="exact training (no hot-embedding reuse)")
+    ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: auto, 0: skip)")
+    ap.add_argument("--presample-epochs", type=int, default=3)
+    ap.add_argument("--lr", type=float, default=0.01)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported."
+            % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import synth_inputs as si
+    from paper_2311_13225_amd import binding as b
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    b.lib()   # fail loudly if the HIP library is missing
+    w = si.WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    t0 = time.time()
+    src, dst = si.rmat_edges(w.n_vertices, w.n_edges, w.seed, symmetrise=w.symmetrise)
+    log("[bench] R-MAT %d vertices %d edges: %.1fs" % (w.n_vertices, len(src), time.time() - t0))
+    t0 = time.time()
+    feat = si.features(w.n_vertices, w.feat_dim, w.seed, w.feat_dtype)
+    lab = si.labels(w.n_vertices, w.n_classes, w.seed)
+    train = si.train_split(w.n_vertices, 0.65, w.seed)
+    weights = si.init_weights(w.dims, w.seed)
+    bf16 = w.feat_dtype == "bf16"
+    log("[bench] features/labels: %.1fs" % (time.time() - t0))
+
+    t0 = time.time()
+    g = b.no_build_csr(src, dst, w.n_vertices, w.rowptr_bits)
+    torch.cuda.synchronize()
+    t_csr = time.time() - t0
+    log("[bench] no_build_csr (incl. H2D of the edge list): %.2fs" % t_csr)
+    tfeat = dev(feat.view(np.int16) if bf16 else feat)
+    tlab = dev(lab)
+    ttrain = dev(train)
+    cache = None
+    t_hot = 0.0
+    if not args.no_cache:
+        t0 = time.time()
+        cache = b.no_select_hot(g, ttrain, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
+                                w.hidden, w.seed)
+        torch.cuda.synchronize()
+        t_hot = time.time() - t0
+        log("[bench] no_select_hot (%d pre-sampling epochs): %.2fs" % (args.presample_epochs, t_hot))
+    model = b.no_model_create(g, w.dims, w.batch, w.fanouts, b.NO_BF16 if bf16 else b.NO_F32)
+
+    def load_weights():
+        for l in range(w.n_layers):
+            for t, a in zip(b.no_model_params(model, l + 1), weights[l]):
+                t.copy_(dev(a))
+
+    seed_batches = [dev(si.batch_seeds(train, w.batch, t)) for t in range(W + K)]
+    stream = torch.cuda.current_stream()
+
+    def run(first, count, want_stats=False):
+        out = []
+        for t in range(first, first + count):
+            st = b.no_train_step(model, g, tfeat, tlab, seed_batches[t], cache, t, w.seed, args.lr, want_stats=want_stats)
+            out.append(st)
+        return out
+
+    # ---- pass 1: throughput (no events, no host sync inside the region)
+    load_weights()
+    if cache is not None:
+        b.no_cache_invalidate(cache)
+    run(0, W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(W, K)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / K
+    steps_per_s = K / elapsed
+    log("[bench] %d steps in %.3fs -> %.1f steps/s (%.3f ms/step)" % (K, elapsed, steps_per_s, ms_per_step))
+
+    # ---- pass 2: same steps again with per-stage events and per-step statistics
+    load_weights()
+    if cache is not None:
+        b.no_cache_invalidate(cache)
+    run(0, W)
+    torch.cuda.synchronize()
+    b.no_model_profile(model, True)
+    stats = run(W, K, want_stats=True)
+    stage_ms, n_prof = b.no_model_stage_ms(model)
+    b.no_model_profile(model, False)
+    per_step = {k: v / max(n_prof, 1) for k, v in stage_ms.items()}
+    L = w.n_layers
+    es = 2 if bf16 else 4
+    F = w.feat_dim
+    mean = lambda xs: float(sum(xs)) / max(len(xs), 1)
+    nnz_total = mean([sum(s.nnz[h] for h in range(L)) for s in stats])
+    n_src_bottom = mean([s.n_src[L - 1] for s in stats])
+    n_dst_bottom = mean([s.n_dst[L - 1] for s in stats])
+    nnz_bottom = mean([s.nnz[L - 1] for s in stats])
+    n_hit = mean([s.n_hit for s in stats])
+    n_v1 = mean([s.n_v1 for s in stats])
+    loss_last = stats[-1].loss
+    # algorithmic work per launch (units: one step's rows/edges as measured)
+    gather_bytes = n_src_bottom * (4 + 2 * F * es)
+    agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4     # compulsory traffic
+    gemm_fwd_flops = 2.0 * n_dst_bottom * (2 * F) * w.dims[1]
+    gemm_dw_flops = gemm_fwd_flops
+    kern = {
+        "gather_rows_kernel": ("hbm", gather_bytes / 1e9 / (per_step["gather"] / 1e3), HBM_PEAK_GBPS, "GB/s", per_step["gather"]),
+        "segment_rows_kernel(mean,l1)": ("hbm", agg_bytes / 1e9 / (per_step["agg_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", per_step["agg_l1"]),
+        "gemm_nn_kernel(l1 fwd)": ("mfma", gemm_fwd_flops / 1e12 / (per_step["gemm_fwd_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", per_step["gemm_fwd_l1"]),
+        "gemm_tn_kernel(l1 dW)": ("mfma", gemm_dw_flops / 1e12 / (per_step["gemm_dw_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", per_step["gemm_dw_l1"]),
+    }
+    dominant = max(kern, key=lambda k: kern[k][4])
+    bound, achieved, peak, unit, dur = kern[dominant]
+    roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": None, "avg_launch_ms": round(dur, 4),
+                "all": {k: {"bound": v[0], "achieved": round(v[1], 3), "peak": v[2], "unit": v[3],
+                            "frac": round(v[1] / v[2], 4), "avg_launch_ms": round(v[4], 4)} for k, v in kern.items()}}
+    extra = {
+        "sampled_edges_per_s": round(nnz_total / (per_step["sample"] / 1e3), 1),
+        "sampled_edges_per_step": round(nnz_total, 1),
+        "gather_GBps": round(kern["gather_rows_kernel"][1], 2),
+        "gather_frac_hbm_peak": round(kern["gather_rows_kernel"][1] / HBM_PEAK_GBPS, 4),
+        "aggregate_GBps": round(kern["segment_rows_kernel(mean,l1)"][1], 2),
+        "aggregate_frac_hbm_peak": round(kern["segment_rows_kernel(mean,l1)"][1] / HBM_PEAK_GBPS, 4),
+        "rows_gathered_per_step": round(n_src_bottom, 1),
+        "cache_hit_rate": round(n_hit / max(n_v1, 1.0), 4),
+        "stage_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
+        "profiled_ms_per_step": round(sum(per_step.values()), 4),
+        "setup_s": {"build_csr": round(t_csr, 2), "select_hot": round(t_hot, 2)},
+        "loss_after_last_step": round(float(loss_last), 5),
+    }
+    log("[bench] stage ms/step: " + ", ".join("%s=%.3f" % kv for kv in per_step.items()))
+
+    # ---- CPU baseline: the oracle, as it stands, on a bounded number of the same steps
+    cpu = None
+    cpu_steps = args.cpu_steps
+    if cpu_steps != 0:
+        from oracle import oracle as ora
+        try:
+            from threadpoolctl import threadpool_info
+            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            blas_threads = 1
+        t0 = time.time()
+        og = ora.build_csr(src, dst, w.n_vertices)
+        oc = None
+        if cache is not None:
+            oc = ora.select_hot(og, train, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
+                                w.hidden, w.seed)
+        log("[bench] oracle setup (CSR + hot set): %.1fs" % (time.time() - t0))
+        ow = [tuple(np.asarray(t, np.float64) for t in x) for x in weights]
+        # one untimed step to estimate the cost, then time as many as fit in ~20 s (at least 2)
+        t0 = time.perf_counter()
+        r = ora.train_step(og, feat, lab, si.batch_seeds(train, w.batch, 0), w.fanouts, ow, args.lr, w.seed, 0, oc,
+                           feat_is_bf16=bf16)
+        one = time.perf_counter() - t0
+        ow = r.new_weights
+        if cpu_steps < 0:
+            cpu_steps = int(max(2, min(K, 20.0 / max(one, 1e-3))))
+        t0 = time.perf_counter()
+        for t in range(1, 1 + cpu_steps):
+            r = ora.train_step(og, feat, lab, si.batch_seeds(train, w.batch, t), w.fanouts, ow, args.lr, w.seed, t, oc,
+                               feat_is_bf16=bf16)
+            ow = r.new_weights
+        cpu_elapsed = time.perf_counter() - t0
+        cpu = {"value": round(cpu_steps / cpu_elapsed, 4), "unit": "steps/s", "cores": int(blas_threads), "kind": "oracle",
+               "sample": "%d steps (steps 1..%d of the same workload, after 1 untimed step); C parts single-threaded, "
+                         "numpy fp64 BLAS on %d threads" % (cpu_steps, cpu_steps, blas_threads)}
+        log("[bench] oracle: %d steps in %.1fs" % (cpu_steps, cpu_elapsed))
+
+    line = {
+        "metric": "train_steps_per_s", "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1,
+        "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: R-MAT %d vertices / %d directed edges, %d x %s features, %d classes, %d-layer "
+                               "GraphSAGE-mean hidden %d, fanout %s, batch %d, hot %.0f%%, S=%d"
+                               % (w.name, w.n_vertices, len(src), w.feat_dim, w.feat_dtype, w.n_classes, w.n_layers,
+                                  w.hidden, list(w.fanouts), w.batch, 0.0 if cache is None else 100 * w.hot_fraction,
+                                  w.staleness),
+                   "hot_reuse": cache is not None},
+        "roofline": roofline, "cpu_baseline": cpu, "extra": extra,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

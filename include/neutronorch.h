@@ -220,6 +220,30 @@ int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const 
                       uint64_t seed, float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream);
 int32_t no_model_destroy(no_model_t m);
 
+/* Per-stage timing of no_train_step with HIP events on the step's own stream. While enabled,
+ * every step records an event pair around each stage and synchronises the stream at its end to
+ * accumulate the elapsed times (so it is for measurement passes, not for throughput runs).
+ * Stages that are a single kernel launch: NO_STAGE_GATHER, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1,
+ * NO_STAGE_GEMM_DW_L1. */
+enum {
+    NO_STAGE_SAMPLE = 0,      /* all hops: sampling, relabel, transpose, hot lookup */
+    NO_STAGE_GATHER = 1,      /* feature rows of the bottom hop's sources */
+    NO_STAGE_AGG_L1 = 2,      /* layer-1 mean aggregation kernel */
+    NO_STAGE_GEMM_FWD_L1 = 3, /* layer-1 dense update kernel */
+    NO_STAGE_FWD_UPPER = 4,   /* cache row assembly + layers 2..L forward */
+    NO_STAGE_LOSS = 5,
+    NO_STAGE_BWD_UPPER = 6,   /* layers L..2 backward */
+    NO_STAGE_BWD_L1_PREP = 7, /* gradient row selection, ReLU mask */
+    NO_STAGE_GEMM_DW_L1 = 8,  /* layer-1 weight-gradient kernel (split partial products) */
+    NO_STAGE_BWD_L1_REDUCE = 9,
+    NO_STAGE_UPDATE = 10,     /* SGD + cache refresh */
+    NO_STAGE_COUNT = 11
+};
+int32_t no_model_profile(no_model_t m, int32_t enable);   /* enabling resets the accumulators */
+/* h_total_ms[NO_STAGE_COUNT]: summed milliseconds per stage; *h_steps: steps accumulated. */
+int32_t no_model_stage_ms(no_model_t m, double* h_total_ms, int32_t* h_steps);
+const char* no_stage_name(int32_t stage);
+
 #ifdef __cplusplus
 }
 #endif

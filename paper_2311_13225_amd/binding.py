@@ -77,7 +77,11 @@ _SIGNATURES = {
     "no_model_gathered": (_I32, [_P, _P]),
     "no_train_step": (_I32, [_P, _P, _P, _P, _P, _I32, _P, _I64, _U64, C.c_float, _P, _P, _P]),
     "no_model_destroy": (_I32, [_P]),
+    "no_model_profile": (_I32, [_P, _I32]),
+    "no_model_stage_ms": (_I32, [_P, _P, _P]),
+    "no_stage_name": (C.c_char_p, [_I32]),
 }
+NO_STAGE_COUNT = 11
 EXPORTS = sorted(_SIGNATURES)
 
 
@@ -422,3 +426,15 @@ def no_train_step(m: Model, g: Graph, features: torch.Tensor, labels: torch.Tens
                                cache.h if cache is not None else None, step, seed & 0xFFFFFFFFFFFFFFFF, lr, None,
                                C.byref(hs) if want_stats else None, _stream(stream)))
     return hs
+
+
+def no_model_profile(m: Model, enable: bool):
+    _check(lib().no_model_profile(m.h, 1 if enable else 0))
+
+
+def no_model_stage_ms(m: Model) -> Tuple[dict, int]:
+    """({stage name: summed milliseconds}, steps accumulated) since profiling was enabled."""
+    ms = (C.c_double * NO_STAGE_COUNT)()
+    steps = C.c_int32()
+    _check(lib().no_model_stage_ms(m.h, ms, C.byref(steps)))
+    return {lib().no_stage_name(i).decode(): float(ms[i]) for i in range(NO_STAGE_COUNT)}, steps.value

@@ -20,11 +20,12 @@ struct HopBuffers {
     bool has_csc = false;
     const int32_t* d_dst = nullptr;     // alias: seeds copy, previous hop's src_global, or compute list
     const int32_t* d_n_dst = nullptr;   // alias into counts
-    DevBuf<int32_t> src_global, indptr, nbr_global, indices, edge_row;
-    DevBuf<int32_t> csc_indptr, csc_cnt, csc_dst, csc_eid, csc_keys;
+    DevBuf<int32_t> src_global, indptr, nbr_pad, nbr_global, indices, edge_row;
+    DevBuf<int32_t> csc_indptr, csc_cnt, csc_cur, csc_dst, csc_eid;
     void release() {
-        src_global.release(); indptr.release(); nbr_global.release(); indices.release(); edge_row.release();
-        csc_indptr.release(); csc_cnt.release(); csc_dst.release(); csc_eid.release(); csc_keys.release();
+        src_global.release(); indptr.release(); nbr_pad.release(); nbr_global.release(); indices.release();
+        edge_row.release(); csc_indptr.release(); csc_cnt.release(); csc_cur.release(); csc_dst.release();
+        csc_eid.release();
     }
 };
 
@@ -36,21 +37,18 @@ struct no_blocks_s {
     int64_t n_vertices = 0;
     bool build_csc = true;             // transpose hops 0..L-2 (select_hot's private blocks skip it)
     no::HopBuffers hop[NO_MAX_LAYERS];
-    // counts[4*h + {0,1,2}] = n_dst, n_src, nnz of hop h; counts[4*L + {0,1}] = n_compute, n_hit;
-    // counts[4*L + 2] = scratch total
+    // counts[4*h + {0,1,2}] = n_dst, n_src, nnz of hop h; counts[4*L + {0,1,4}] = n_compute, n_hit, n_refresh
     no::DevBuf<int32_t> counts;
     no::DevBuf<int32_t> seeds;          // copy of the seed ids (hop 0 destinations)
-    no::DevBuf<int32_t> map;            // vertex -> local id scratch, EMPTY between hops, [V]
-    no::DevBuf<int32_t> rank;           // scan output over edges / destinations, [max cap + 1]
-    no::DevBuf<int32_t> tmp_a, tmp_b;   // radix sort temporaries [max nnz_cap with csc]
-    no::DevBuf<char> ws;                // scan / sort workspace
+    no::DevBuf<int32_t> map;            // vertex -> local id, EMPTY between calls, [V]
+    no::DevBuf<int32_t> tmp_a;          // unordered transpose fill [max nnz_cap with a transpose]
+    no::DevBuf<char> ws;                // tile sums of the scans
     // bottom hop with a cache
     no::DevBuf<int32_t> compute_list, compute_pos, hit_pos, hit_slot;
     bool last_used_cache = false;
     void release() {
         for (auto& h : hop) h.release();
-        counts.release(); seeds.release(); map.release(); rank.release(); tmp_a.release(); tmp_b.release();
-        ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();
+        counts.release(); seeds.release(); map.release(); tmp_a.release(); ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();
     }
 };
 

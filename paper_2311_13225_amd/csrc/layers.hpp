@@ -5,6 +5,29 @@
 
 namespace no {
 
+// Event-pair timer for the stages of a step; a disabled profiler costs one branch per mark.
+struct StageProfiler {
+    static constexpr int MAX_MARKS = 96;
+    bool enabled = false;
+    bool created = false;
+    hipStream_t st = nullptr;
+    hipEvent_t ev[2 * MAX_MARKS];
+    int stage_of[MAX_MARKS];
+    int n = 0;
+    double total_ms[NO_STAGE_COUNT] = {0};
+    int32_t steps = 0;
+    void begin(int stage) {
+        if (!enabled || n >= MAX_MARKS) return;
+        stage_of[n] = stage;
+        (void)hipEventRecord(ev[2 * n], st);
+    }
+    void end() {
+        if (!enabled || n >= MAX_MARKS) return;
+        (void)hipEventRecord(ev[2 * n + 1], st);
+        ++n;
+    }
+};
+
 struct LayerWorkspace {
     float* gz = nullptr;             // [n_dst_cap, d_out] masked output gradient
     float* gmean = nullptr;          // [n_dst_cap, d_in]  gradient of the mean, pre-divided by the row length
@@ -25,11 +48,13 @@ int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_
                             hipStream_t st);
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
-                     const LayerWorkspace& w, hipStream_t st);
+                     const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int agg_stage = -1,
+                     int gemm_stage = -1);
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
-                      const LayerWorkspace& w, hipStream_t st);
+                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int prep_stage = -1,
+                      int dw_stage = -1, int reduce_stage = -1, int dx_stage = -1);
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
                     const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
 

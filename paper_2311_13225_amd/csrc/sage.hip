@@ -226,8 +226,10 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
-                     const LayerWorkspace& w, hipStream_t st) {
+                     const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage) {
+    if (prof && agg_stage >= 0) prof->begin(agg_stage);
     NO_CHECK(mean_aggregate(x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap, mean, st));
+    if (prof && agg_stage >= 0) prof->end();
     const float* x_dst = (const float*)x_src;
     if (dt == NO_BF16) {
         hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)blk.n_dst_cap * d_in)), dim3(256), 0, st,
@@ -244,14 +246,19 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     a.n_problems = 2; a.accumulate = 1;
     a.d_M = blk.d_n_dst; a.M_cap = blk.n_dst_cap; a.N = d_out;
     a.bias = bias; a.relu = relu;
-    return gemm_nn(a, false, st);
+    if (prof && gemm_stage >= 0) prof->begin(gemm_stage);
+    int32_t rc = gemm_nn(a, false, st);
+    if (prof && gemm_stage >= 0) prof->end();
+    return rc;
 }
 
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
-                      const LayerWorkspace& w, hipStream_t st) {
+                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int prep_stage, int dw_stage,
+                      int reduce_stage, int dx_stage) {
     const int32_t n_cap = blk.n_dst_cap;
+    if (prof && prep_stage >= 0) prof->begin(prep_stage);
     hipLaunchKernelGGL(relu_mask_kernel, dim3(ew_blocks((int64_t)n_cap * d_out)), dim3(256), 0, st, grad_h, h, blk.d_n_dst,
                        n_cap, d_out, relu, w.gz);
     const float* x_dst = (const float*)x_src;
@@ -267,14 +274,20 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     t.G = w.gz; t.ldg = d_out; t.g_align = ptr_align(w.gz, d_out);
     t.P = w.partials; t.Kp = d_in; t.N = d_out;
     t.d_R = blk.d_n_dst; t.R_cap = n_cap; t.splits = w.splits;
+    if (prof && prep_stage >= 0) prof->end();
+    if (prof && dw_stage >= 0) prof->begin(dw_stage);
     NO_CHECK(gemm_tn_partials(t, st));
+    if (prof && dw_stage >= 0) prof->end();
+    if (prof && reduce_stage >= 0) prof->begin(reduce_stage);
     hipLaunchKernelGGL(colsum_partials_kernel, dim3((unsigned)ceil_div(d_out, 256), (unsigned)w.splits), dim3(256), 0, st,
                        (const float*)w.gz, blk.d_n_dst, n_cap, d_out, w.splits, w.bias_partials);
     float* outs[2] = {gw_self, gw_neigh};
     NO_CHECK(reduce_partials(w.partials, 2, w.splits, (int64_t)d_in * d_out, outs, st));
     float* bouts[1] = {gbias};
     NO_CHECK(reduce_partials(w.bias_partials, 1, w.splits, d_out, bouts, st));
+    if (prof && reduce_stage >= 0) prof->end();
     if (grad_x_src) {
+        if (prof && dx_stage >= 0) prof->begin(dx_stage);
         // gz W_self^T -> rows [0, n_dst) of grad_x; (gz W_neigh^T) / len(row) -> gmean; then the transpose adds
         GemmNNArgs a{};
         a.A[0] = a.A[1] = w.gz; a.lda[0] = a.lda[1] = d_out; a.a_align[0] = a.a_align[1] = ptr_align(w.gz, d_out);
@@ -289,6 +302,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
         NO_CHECK(gemm_nn(a, true, st));
         NO_CHECK(transpose_aggregate(w.gmean, d_in, blk.d_csc_indptr, blk.d_csc_dst, blk.d_n_src, blk.n_src_cap,
                                      blk.d_n_dst, grad_x_src, st));
+        if (prof && dx_stage >= 0) prof->end();
     }
     return launch_status("sage_backward");
 }

@@ -3,14 +3,27 @@
 // by the backward pass, and the hot-vertex lookup that removes reusable vertices from the bottom
 // hop (Section 4.1.2, Stage 1 of Section 4.2).
 //
-// Sampling: a sub-wave group of G lanes (G = 8/16/32/64 >= fanout) serves one destination; lane j
-// draws slot j with Philox4x32-10 keyed by (stream; vertex, slot, domain, hop) and the group
-// resolves the partial Fisher-Yates swap chain with cross-lane shuffles. The result is a pure
-// function of the key, independent of launch shape.
+// One hop is four kernels over a fixed-stride ("padded") edge array, slot q = row * fanout + j:
+//   1. sample_rows   a sub-wave group of G lanes (G = 8/16/32/64 >= fanout) serves one destination;
+//                    lane j draws slot j with Philox4x32-10 keyed by (stream; vertex, slot, domain,
+//                    hop), the group resolves the partial Fisher-Yates swap chain with cross-lane
+//                    shuffles, and every sampled id does atomicMin(map[id], n_dst + q): the first
+//                    occurrence of an id in (row, slot) order wins, whatever the execution order;
+//   2. edge_tile_sums  per 2048-slot tile: number of sampled edges and of first occurrences;
+//   3. edge_assign   tile prefix + block scan: compact edge ids, row pointers, new local ids in
+//                    first-occurrence order, map[id] = local id;
+//   4. edge_indices  indices[e] = map[id]; counts per source for the transpose.
+// `map` is a direct-address table int32[V] (HBM is plentiful; no hashing, no probing order to
+// reason about). It carries the local ids from one hop to the next and is wiped after the last.
+// The transpose (hops above the bottom one) is a counting sort: scan of the per-source counts,
+// unordered fill through atomic cursors, then every edge ranks itself inside its (short) column so
+// that columns end up in ascending edge id regardless of the fill order.
 #include "primitives.hpp"
 #include "handles.hpp"
 
 namespace no {
+
+constexpr int ETHREADS = 256, EITEMS = 8, ETILE = ETHREADS * EITEMS;
 
 // ---------------------------------------------------------------------------- Philox4x32-10
 
@@ -28,70 +41,32 @@ __device__ __forceinline__ uint64_t philox_random64(uint32_t k0, uint32_t k1, ui
     return ((uint64_t)c1 << 32) | (uint64_t)c0;
 }
 
-template <typename RowT>
-struct DegreeLoader {       // min(deg(dst[i]), k)
-    const RowT* rowptr;
-    const int32_t* dst;
-    int32_t k;
-    __device__ __forceinline__ int32_t operator()(int64_t i) const {
-        int32_t v = dst[i];
-        int64_t d = (int64_t)rowptr[v + 1] - (int64_t)rowptr[v];
-        return d < (int64_t)k ? (int32_t)d : k;
-    }
-};
-
-struct FirstSeenLoader {    // 1 iff edge e is the first occurrence of a vertex that is not a destination
-    const int32_t* map;
-    const int32_t* nbr;
-    const int32_t* d_n_dst;
-    __device__ __forceinline__ int32_t operator()(int64_t e) const { return map[nbr[e]] == *d_n_dst + (int32_t)e; }
-};
-
-struct ComputeLoader {      // 1 iff V^1 row i cannot be served from the cache at `step`
-    const int32_t* v1;
-    const int32_t* slot_of_vertex;
-    const int32_t* version;
-    int64_t step;
-    int32_t staleness;
-    __device__ __forceinline__ bool hit(int64_t i, int32_t* slot_out) const {
-        int32_t s = slot_of_vertex[v1[i]];
-        *slot_out = s;
-        if (s < 0) return false;
-        int32_t ver = version[s];
-        return ver >= 0 && step - (int64_t)ver <= (int64_t)staleness;
-    }
-    __device__ __forceinline__ int32_t operator()(int64_t i) const { int32_t s; return hit(i, &s) ? 0 : 1; }
-};
-
-// ---------------------------------------------------------------------------- kernels
-
-__global__ void hop_begin_kernel(const int32_t* dst, const int32_t* d_n_dst, int32_t cap, int32_t* map,
-                                 int32_t* count_out) {
-    int32_t n = *d_n_dst;
-    if (n > cap) n = cap;
-    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) *count_out = n;
-    if (i < n) map[dst[i]] = i;
-}
+// ---------------------------------------------------------------------------- 1. sampling
 
 template <int G, typename RowT>
 __global__ void __launch_bounds__(256) sample_rows_kernel(const RowT* __restrict__ rowptr, const int32_t* __restrict__ col,
                                                           const int32_t* __restrict__ dst, const int32_t* d_n_dst,
-                                                          int32_t k, uint32_t key0, uint32_t key1, uint32_t c3,
-                                                          const int32_t* __restrict__ indptr, int32_t* __restrict__ nbr,
-                                                          int32_t* __restrict__ edge_row, int32_t* map) {
-    const int32_t n_dst = *d_n_dst;
+                                                          int32_t n_fixed, int32_t n_cap, int32_t k, uint32_t key0,
+                                                          uint32_t key1, uint32_t c3, int32_t* __restrict__ nbr_pad,
+                                                          int32_t* __restrict__ src_global, int32_t* map,
+                                                          int32_t insert_dst, int32_t* seeds_copy, int32_t* count_out) {
+    int32_t n_dst = d_n_dst ? *d_n_dst : n_fixed;
+    if (n_dst > n_cap) n_dst = n_cap;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = n_dst;
     const int32_t i = (int32_t)(blockIdx.x * (256 / G) + threadIdx.x / G);
     const int32_t j = (int32_t)(threadIdx.x % G);
     const bool row_ok = i < n_dst;
     int32_t v = 0;
     int64_t begin = 0, d = 0;
-    int32_t out0 = 0;
     if (row_ok) {
         v = dst[i];
         begin = (int64_t)rowptr[v];
         d = (int64_t)rowptr[v + 1] - begin;
-        out0 = indptr[i];
+        if (j == 0) {
+            src_global[i] = v;
+            if (insert_dst) map[v] = i;       // a plain store and the atomicMin below commute: i is the smaller value
+            if (seeds_copy) seeds_copy[i] = v;
+        }
     }
     int64_t pos = j;
     const bool take_all = d <= (int64_t)k;
@@ -124,151 +99,335 @@ __global__ void __launch_bounds__(256) sample_rows_kernel(const RowT* __restrict
         int64_t wb = __shfl(w, b < 0 ? 0 : b, G);
         if (!take_all) pos = b < 0 ? r : wb;
     }
-    int32_t cnt = d < (int64_t)k ? (int32_t)d : k;
-    if (row_ok && j < cnt) {
-        int32_t u = col[begin + pos];
-        int32_t e = out0 + j;
-        nbr[e] = u;
-        edge_row[e] = i;
-        atomicMin(&map[u], n_dst + e);   // integer min: order independent
+    const int32_t cnt = d < (int64_t)k ? (int32_t)d : k;
+    if (row_ok && j < k) {
+        const int32_t q = i * k + j;
+        if (j < cnt) {
+            int32_t u = col[begin + pos];
+            nbr_pad[q] = u;
+            atomicMin(&map[u], n_dst + q);   // integer min: order independent
+        } else {
+            nbr_pad[q] = -1;
+        }
     }
 }
 
-__global__ void relabel_kernel(const int32_t* __restrict__ dst, const int32_t* d_n_dst, const int32_t* d_nnz,
-                               const int32_t* __restrict__ nbr, const int32_t* __restrict__ map,
-                               const int32_t* __restrict__ rank, int32_t* __restrict__ indices,
-                               int32_t* __restrict__ src_global, int32_t* d_n_src, int32_t* csc_cnt, int32_t* iota) {
-    const int32_t n_dst = *d_n_dst, nnz = *d_nnz;
-    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t == 0) *d_n_src = n_dst + rank[nnz];
-    if (t < n_dst) { src_global[t] = dst[t]; return; }
-    t -= n_dst;
-    if (t >= nnz) return;
-    int32_t e = (int32_t)t;
-    int32_t u = nbr[e];
-    int32_t m = map[u];
-    int32_t local;
-    if (m < n_dst) local = m;
-    else {
-        local = n_dst + rank[m - n_dst];
-        if (m == n_dst + e) src_global[local] = u;
+// ---------------------------------------------------------------------------- 2./3. compaction and new ids
+
+__device__ __forceinline__ int64_t slot_flags(const int32_t* __restrict__ nbr_pad, const int32_t* map, int64_t q,
+                                              int32_t n_dst, int32_t* u_out) {
+    const int32_t u = nbr_pad[q];
+    *u_out = u;
+    if (u < 0) return 0;
+    return 1ll + ((map[u] == n_dst + (int32_t)q) ? (1ll << 32) : 0ll);    // low word: sampled; high word: first seen
+}
+
+__global__ void __launch_bounds__(ETHREADS) edge_tile_sums_kernel(const int32_t* __restrict__ nbr_pad, const int32_t* map,
+                                                                  const int32_t* d_n_dst, int32_t k, int64_t* tile_sums,
+                                                                  int32_t* zero_a, int32_t* zero_b, int32_t n_zero) {
+    for (int64_t t = (int64_t)blockIdx.x * ETHREADS + threadIdx.x; t < n_zero; t += (int64_t)gridDim.x * ETHREADS) {
+        zero_a[t] = 0;
+        zero_b[t] = 0;
     }
+    const int32_t n_dst = *d_n_dst;
+    const int64_t n_pad = (int64_t)n_dst * k;
+    const int64_t base = (int64_t)blockIdx.x * ETILE;
+    if (base >= n_pad) return;
+    __shared__ int64_t smem[ETHREADS / 64];
+    const int64_t q0 = base + (int64_t)threadIdx.x * EITEMS;
+    int64_t s = 0;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        int32_t u;
+        if (q0 + t < n_pad) s += slot_flags(nbr_pad, map, q0 + t, n_dst, &u);
+    }
+    s = block_sum<int64_t, ETHREADS>(s, smem);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = s;
+}
+
+__global__ void __launch_bounds__(ETHREADS) edge_assign_kernel(const int32_t* __restrict__ nbr_pad, int32_t* map,
+                                                               const int32_t* d_n_dst, int32_t k, uint64_t k_magic,
+                                                               const int64_t* __restrict__ tile_sums,
+                                                               int32_t* __restrict__ indptr, int32_t* __restrict__ nbr,
+                                                               int32_t* __restrict__ edge_row, int32_t* __restrict__ src_global,
+                                                               int32_t* counts /* [0]=n_dst (in), [1]=n_src, [2]=nnz */) {
+    __shared__ int64_t smem[ETHREADS / 64 + 1];
+    const int32_t n_dst = *d_n_dst;
+    const int64_t n_pad = (int64_t)n_dst * k;
+    const int64_t n_tiles = (n_pad + ETILE - 1) / ETILE;
+    if (blockIdx.x == 0) {
+        int64_t s = 0;
+        for (int64_t t = threadIdx.x; t < n_tiles; t += ETHREADS) s += tile_sums[t];
+        s = block_sum<int64_t, ETHREADS>(s, smem);
+        if (threadIdx.x == 0) {
+            const int32_t nnz = (int32_t)(s & 0xffffffffll), n_new = (int32_t)(s >> 32);
+            indptr[n_dst] = nnz;
+            counts[1] = n_dst + n_new;
+            counts[2] = nnz;
+        }
+    }
+    const int64_t base = (int64_t)blockIdx.x * ETILE;
+    if (base >= n_pad) return;
+    int64_t tile_off = 0;
+    {
+        int64_t s = 0;
+        for (int64_t t = threadIdx.x; t < (int64_t)blockIdx.x; t += ETHREADS) s += tile_sums[t];
+        tile_off = block_sum<int64_t, ETHREADS>(s, smem);
+    }
+    const int64_t q0 = base + (int64_t)threadIdx.x * EITEMS;
+    int64_t f[EITEMS];
+    int32_t u[EITEMS];
+    int64_t s = 0;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        f[t] = 0;
+        u[t] = -1;
+        if (q0 + t < n_pad) f[t] = slot_flags(nbr_pad, map, q0 + t, n_dst, &u[t]);
+        s += f[t];
+    }
+    int64_t total;
+    int64_t run = block_exclusive_scan<int64_t, ETHREADS>(s, &total, smem) + tile_off;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        const int64_t q = q0 + t;
+        if (q < n_pad) {
+            const int32_t e = (int32_t)(run & 0xffffffffll);
+            const int32_t row = k == 1 ? (int32_t)q : (int32_t)__umul64hi((uint64_t)q, k_magic);   // q / k, exact
+            if (q - (int64_t)row * k == 0) indptr[row] = e;
+            if (f[t] & 1) {
+                nbr[e] = u[t];
+                edge_row[e] = row;
+                if (f[t] >> 32) {
+                    const int32_t local = n_dst + (int32_t)(run >> 32);
+                    src_global[local] = u[t];
+                    map[u[t]] = local;     // only the first occurrence writes; later readers never match n_dst + q
+                }
+            }
+            run += f[t];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------- 4. local indices (+ transpose)
+
+__global__ void edge_indices_kernel(const int32_t* d_nnz, const int32_t* __restrict__ nbr, const int32_t* __restrict__ map,
+                                    int32_t* __restrict__ indices, int32_t* csc_cnt) {
+    const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= *d_nnz) return;
+    const int32_t local = map[nbr[e]];
     indices[e] = local;
-    if (csc_cnt) { atomicAdd(&csc_cnt[local], 1); iota[e] = e; }
+    if (csc_cnt) atomicAdd(&csc_cnt[local], 1);     // integer count: order independent
 }
 
-__global__ void csc_rows_kernel(const int32_t* d_nnz, const int32_t* __restrict__ csc_eid,
-                                const int32_t* __restrict__ edge_row, int32_t* __restrict__ csc_dst) {
-    int32_t p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < *d_nnz) csc_dst[p] = edge_row[csc_eid[p]];
+__global__ void csc_fill_kernel(const int32_t* d_nnz, const int32_t* __restrict__ indices,
+                                const int32_t* __restrict__ csc_indptr, int32_t* cursor, int32_t* __restrict__ unordered) {
+    const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= *d_nnz) return;
+    const int32_t u = indices[e];
+    unordered[csc_indptr[u] + atomicAdd(&cursor[u], 1)] = e;
 }
 
-__global__ void hop_end_kernel(const int32_t* src_global, const int32_t* d_n_src, int32_t* map) {
+// Every edge finds its rank among the edges of its column; columns are short (a source is sampled by
+// few destinations), so the quadratic work is small and needs no sort network or shared memory.
+__global__ void csc_rank_kernel(const int32_t* d_nnz, const int32_t* __restrict__ indices,
+                                const int32_t* __restrict__ csc_indptr, const int32_t* __restrict__ unordered,
+                                const int32_t* __restrict__ edge_row, int32_t* __restrict__ csc_eid,
+                                int32_t* __restrict__ csc_dst) {
+    const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= *d_nnz) return;
+    const int32_t u = indices[e];
+    const int32_t b = csc_indptr[u], len = csc_indptr[u + 1] - b;
+    int32_t r = 0;
+    if (len > 1)
+        for (int32_t t = 0; t < len; ++t) r += unordered[b + t] < e ? 1 : 0;
+    csc_eid[b + r] = e;
+    csc_dst[b + r] = edge_row[e];
+}
+
+__global__ void map_wipe_kernel(const int32_t* src_global, const int32_t* d_n_src, int32_t* map) {
     int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < *d_n_src) map[src_global[i]] = EMPTY;
 }
 
-__global__ void partition_v1_kernel(ComputeLoader ld, const int32_t* d_n_v1, const int32_t* __restrict__ rank,
-                                    int32_t* compute_list, int32_t* compute_pos, int32_t* hit_pos, int32_t* hit_slot,
-                                    int32_t* d_n_hit) {
-    const int32_t n = *d_n_v1;
-    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) *d_n_hit = n - rank[n];
-    if (i >= n) return;
-    int32_t slot;
-    if (ld.hit(i, &slot)) {
-        int32_t p = i - rank[i];
-        hit_pos[p] = i;
-        hit_slot[p] = slot;
-    } else {
-        int32_t p = rank[i];
-        compute_pos[p] = i;
-        compute_list[p] = ld.v1[i];
+// ---------------------------------------------------------------------------- hot lookup on V^1
+
+struct CacheProbe {
+    const int32_t* v1;
+    const int32_t* slot_of_vertex;
+    const int32_t* version;
+    int64_t step;
+    int32_t staleness;
+    // low word: 1 if the row must be computed; high word: 1 if it is computed AND hot (it will refresh its slot)
+    __device__ __forceinline__ int64_t operator()(int64_t i, int32_t* slot_out) const {
+        const int32_t s = slot_of_vertex[v1[i]];
+        *slot_out = s;
+        if (s < 0) return 1;
+        const int32_t ver = version[s];
+        const bool hit = ver >= 0 && step - (int64_t)ver <= (int64_t)staleness;
+        return hit ? 0 : (1ll + (1ll << 32));
+    }
+};
+
+__global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe, const int32_t* d_n_v1, int64_t* tile_sums) {
+    const int64_t n = *d_n_v1;
+    const int64_t base = (int64_t)blockIdx.x * ETILE;
+    if (base >= n) return;
+    __shared__ int64_t smem[ETHREADS / 64];
+    const int64_t i0 = base + (int64_t)threadIdx.x * EITEMS;
+    int64_t s = 0;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        int32_t slot;
+        if (i0 + t < n) s += probe(i0 + t, &slot);
+    }
+    s = block_sum<int64_t, ETHREADS>(s, smem);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = s;
+}
+
+// Stable split of V^1 into rows to compute and rows served from the cache; re-keys the id map for
+// the bottom hop (computed vertex -> its index in the compute list, reusable vertex -> no entry).
+__global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(CacheProbe probe, const int32_t* d_n_v1,
+                                                                const int64_t* __restrict__ tile_sums, int32_t* map,
+                                                                int32_t* compute_list, int32_t* compute_pos, int32_t* hit_pos,
+                                                                int32_t* hit_slot, int32_t* extra /* n_compute, n_hit, -, -, n_refresh */) {
+    __shared__ int64_t smem[ETHREADS / 64 + 1];
+    const int64_t n = *d_n_v1;
+    const int64_t n_tiles = (n + ETILE - 1) / ETILE;
+    if (blockIdx.x == 0) {
+        int64_t s = 0;
+        for (int64_t t = threadIdx.x; t < n_tiles; t += ETHREADS) s += tile_sums[t];
+        s = block_sum<int64_t, ETHREADS>(s, smem);
+        if (threadIdx.x == 0) {
+            const int32_t n_compute = (int32_t)(s & 0xffffffffll);
+            extra[0] = n_compute;
+            extra[1] = (int32_t)n - n_compute;
+            extra[4] = (int32_t)(s >> 32);
+        }
+    }
+    const int64_t base = (int64_t)blockIdx.x * ETILE;
+    if (base >= n) return;
+    int64_t tile_off = 0;
+    {
+        int64_t s = 0;
+        for (int64_t t = threadIdx.x; t < (int64_t)blockIdx.x; t += ETHREADS) s += tile_sums[t] & 0xffffffffll;
+        tile_off = block_sum<int64_t, ETHREADS>(s, smem);
+    }
+    const int64_t i0 = base + (int64_t)threadIdx.x * EITEMS;
+    int32_t c[EITEMS], slot[EITEMS];
+    int64_t s = 0;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        c[t] = 0;
+        slot[t] = -1;
+        if (i0 + t < n) c[t] = (int32_t)(probe(i0 + t, &slot[t]) & 1);
+        s += c[t];
+    }
+    int64_t total;
+    int64_t run = block_exclusive_scan<int64_t, ETHREADS>(s, &total, smem) + tile_off;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        const int64_t i = i0 + t;
+        if (i < n) {
+            const int32_t v = probe.v1[i];
+            if (c[t]) {
+                compute_pos[run] = (int32_t)i;
+                compute_list[run] = v;
+                map[v] = (int32_t)run;
+            } else {
+                const int64_t p = i - run;
+                hit_pos[p] = (int32_t)i;
+                hit_slot[p] = slot[t];
+                map[v] = EMPTY;
+            }
+            run += c[t];
+        }
     }
 }
 
-__global__ void set_count_kernel(int32_t* p, int32_t v) { *p = v; }
+__global__ void set_counts_kernel(int32_t* p, int32_t a, int32_t b, int32_t c) { p[0] = a; p[1] = b; p[4] = c; }
 
 // ---------------------------------------------------------------------------- host side
 
+static inline int64_t edge_tiles(int64_t n_pad_cap) { int64_t t = ceil_div(n_pad_cap, ETILE); return t < 1 ? 1 : t; }
+
 template <typename RowT>
 static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b, int32_t h, const int32_t* d_dst,
-                          const int32_t* d_n_dst_in, uint32_t key0, uint32_t key1, uint32_t domain, hipStream_t st) {
+                          const int32_t* d_n_dst_in, int32_t n_fixed, bool insert_dst, uint32_t key0, uint32_t key1,
+                          uint32_t domain, hipStream_t st) {
     HopBuffers& H = b->hop[h];
     int32_t* cnt = b->counts.p + 4 * h;              // n_dst, n_src, nnz
-    int32_t* scratch_total = b->counts.p + 4 * b->n_layers + 2;
     const int32_t k = H.fanout;
     const int T = 256;
     H.d_dst = d_dst;
     H.d_n_dst = cnt;
-    hipLaunchKernelGGL(hop_begin_kernel, dim3((unsigned)ceil_div(H.n_dst_cap, T)), dim3(T), 0, st, d_dst, d_n_dst_in,
-                       H.n_dst_cap, b->map.p, cnt);
-    NO_CHECK((exclusive_scan<DegreeLoader<RowT>, int32_t>(DegreeLoader<RowT>{rowptr, d_dst, k}, cnt, H.n_dst_cap,
-                                                           H.indptr.p, cnt + 2, b->ws.p, st)));
+    int64_t* tile_sums = (int64_t*)b->ws.p;
     const uint32_t c3 = (domain << 8) | (uint32_t)h;
-#define NO_LAUNCH_SAMPLE(G)                                                                                        \
-    hipLaunchKernelGGL((sample_rows_kernel<G, RowT>), dim3((unsigned)ceil_div(H.n_dst_cap, 256 / G)), dim3(256), 0, st, \
-                       rowptr, col, d_dst, cnt, k, key0, key1, c3, H.indptr.p, H.nbr_global.p, H.edge_row.p, b->map.p)
+    int32_t* seeds_copy = (h == 0) ? b->seeds.p : nullptr;
+#define NO_LAUNCH_SAMPLE(G)                                                                                            \
+    hipLaunchKernelGGL((sample_rows_kernel<G, RowT>), dim3((unsigned)ceil_div(H.n_dst_cap, 256 / G)), dim3(256), 0, st,    \
+                       rowptr, col, d_dst, d_n_dst_in, n_fixed, H.n_dst_cap, k, key0, key1, c3, H.nbr_pad.p,               \
+                       H.src_global.p, b->map.p, insert_dst ? 1 : 0, seeds_copy, cnt)
     if (k <= 8) NO_LAUNCH_SAMPLE(8);
     else if (k <= 16) NO_LAUNCH_SAMPLE(16);
     else if (k <= 32) NO_LAUNCH_SAMPLE(32);
     else NO_LAUNCH_SAMPLE(64);
 #undef NO_LAUNCH_SAMPLE
-    NO_CHECK((exclusive_scan<FirstSeenLoader, int32_t>(FirstSeenLoader{b->map.p, H.nbr_global.p, cnt}, cnt + 2, H.nnz_cap,
-                                                        b->rank.p, scratch_total, b->ws.p, st)));
-    int32_t* csc_cnt = H.has_csc ? H.csc_cnt.p : nullptr;
-    if (H.has_csc) NO_CHECK(fill_i32(csc_cnt, 0, H.n_src_cap, st));
-    hipLaunchKernelGGL(relabel_kernel, dim3((unsigned)ceil_div((int64_t)H.n_dst_cap + H.nnz_cap, T)), dim3(T), 0, st, d_dst,
-                       cnt, cnt + 2, H.nbr_global.p, b->map.p, b->rank.p, H.indices.p, H.src_global.p, cnt + 1, csc_cnt,
-                       H.csc_dst.p);
+    const unsigned tiles = (unsigned)edge_tiles(H.nnz_cap);
+    hipLaunchKernelGGL(edge_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p,
+                       (const int32_t*)b->map.p, (const int32_t*)cnt, k, tile_sums, H.csc_cnt.p, H.csc_cur.p,
+                       H.has_csc ? H.n_src_cap + 1 : 0);
+    const uint64_t k_magic = k > 1 ? (~0ull / (uint64_t)k) + 1ull : 0ull;     // ceil(2^64 / k)
+    hipLaunchKernelGGL(edge_assign_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
+                       (const int32_t*)cnt, k, k_magic, (const int64_t*)tile_sums, H.indptr.p, H.nbr_global.p, H.edge_row.p,
+                       H.src_global.p, cnt);
+    hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st, (const int32_t*)(cnt + 2),
+                       (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,
+                       H.has_csc ? H.csc_cnt.p : nullptr);
     if (H.has_csc) {
-        NO_CHECK(exclusive_scan_i32(csc_cnt, cnt + 1, H.n_src_cap, H.csc_indptr.p, nullptr, b->ws.p, st));
-        int bits = ilog2_ceil((uint64_t)H.n_src_cap);
-        if (bits < 1) bits = 1;
-        NO_CHECK(radix_sort_pairs((const uint32_t*)H.indices.p, (const uint32_t*)H.csc_dst.p, (uint32_t*)H.csc_keys.p,
-                                  (uint32_t*)H.csc_eid.p, (uint32_t*)b->tmp_a.p, (uint32_t*)b->tmp_b.p, cnt + 2,
-                                  H.nnz_cap, bits, b->ws.p, st));
-        hipLaunchKernelGGL(csc_rows_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st, cnt + 2, H.csc_eid.p,
-                           H.edge_row.p, H.csc_dst.p);
+        NO_CHECK(exclusive_scan2(ArrayLoader{H.csc_cnt.p}, cnt + 1, H.n_src_cap, H.csc_indptr.p, nullptr, b->ws.p, st));
+        hipLaunchKernelGGL(csc_fill_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st, (const int32_t*)(cnt + 2),
+                           (const int32_t*)H.indices.p, (const int32_t*)H.csc_indptr.p, H.csc_cur.p, b->tmp_a.p);
+        hipLaunchKernelGGL(csc_rank_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st, (const int32_t*)(cnt + 2),
+                           (const int32_t*)H.indices.p, (const int32_t*)H.csc_indptr.p, (const int32_t*)b->tmp_a.p,
+                           (const int32_t*)H.edge_row.p, H.csc_eid.p, H.csc_dst.p);
     }
-    hipLaunchKernelGGL(hop_end_kernel, dim3((unsigned)ceil_div(H.n_src_cap, T)), dim3(T), 0, st, H.src_global.p, cnt + 1,
-                       b->map.p);
     return launch_status("sample_hop");
 }
 
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key, uint32_t domain,
                            int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st) {
     const int32_t L = b->n_layers;
-    int32_t* extra = b->counts.p + 4 * L;     // n_compute, n_hit, scratch
-    NO_HIP_CHECK(hipMemcpyAsync(b->seeds.p, d_seeds, (size_t)n_seeds * 4, hipMemcpyDeviceToDevice, st));
-    hipLaunchKernelGGL(set_count_kernel, dim3(1), dim3(1), 0, st, extra + 3, n_seeds);
+    int32_t* extra = b->counts.p + 4 * L;     // n_compute, n_hit, -, -, n_refresh
     const uint32_t key0 = (uint32_t)stream_key, key1 = (uint32_t)(stream_key >> 32);
-    const int32_t* d_dst = b->seeds.p;
-    const int32_t* d_n = extra + 3;
+    const int32_t* d_dst = d_seeds;
+    const int32_t* d_n = nullptr;
     const bool use_cache = cache != nullptr && L >= 2 && n_hops == L && cache->n_hot > 0;
-    b->last_used_cache = false;
+    b->last_used_cache = use_cache;
     for (int32_t h = 0; h < n_hops; ++h) {
         if (h == L - 1 && use_cache) {
             // split V^1 (= sources of hop L-2) into reusable rows and rows to compute
             HopBuffers& P = b->hop[h - 1];
-            ComputeLoader ld{d_dst, cache->slot_of_vertex.p, cache->version.p, step, cache->staleness};
-            NO_CHECK((exclusive_scan<ComputeLoader, int32_t>(ld, d_n, P.n_src_cap, b->rank.p, extra + 0, b->ws.p, st)));
-            hipLaunchKernelGGL(partition_v1_kernel, dim3((unsigned)ceil_div(P.n_src_cap, 256)), dim3(256), 0, st, ld, d_n,
-                               b->rank.p, b->compute_list.p, b->compute_pos.p, b->hit_pos.p, b->hit_slot.p, extra + 1);
+            CacheProbe probe{d_dst, cache->slot_of_vertex.p, cache->version.p, step, cache->staleness};
+            const unsigned tiles = (unsigned)edge_tiles(P.n_src_cap);
+            int64_t* tile_sums = (int64_t*)b->ws.p;
+            hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, probe, d_n, tile_sums);
+            hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, probe, d_n,
+                               (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->hit_pos.p,
+                               b->hit_slot.p, extra);
             d_dst = b->compute_list.p;
             d_n = extra + 0;
-            b->last_used_cache = true;
         }
         if (g->rowptr_bits == 64)
-            NO_CHECK(sample_hop<int64_t>(g->rowptr64.p, g->col.p, b, h, d_dst, d_n, key0, key1, domain, st));
+            NO_CHECK(sample_hop<int64_t>(g->rowptr64.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st));
         else
-            NO_CHECK(sample_hop<int32_t>(g->rowptr32.p, g->col.p, b, h, d_dst, d_n, key0, key1, domain, st));
+            NO_CHECK(sample_hop<int32_t>(g->rowptr32.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st));
         d_dst = b->hop[h].src_global.p;
         d_n = b->counts.p + 4 * h + 1;
     }
-    if (!b->last_used_cache) {
-        hipLaunchKernelGGL(set_count_kernel, dim3(1), dim3(1), 0, st, extra + 1, 0);
-    }
+    const HopBuffers& last = b->hop[n_hops - 1];
+    hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, 256)), dim3(256), 0, st,
+                       (const int32_t*)last.src_global.p, d_n, b->map.p);
+    if (!use_cache) hipLaunchKernelGGL(set_counts_kernel, dim3(1), dim3(1), 0, st, extra, 0, 0, 0);
     return launch_status("sample_blocks");
 }
 
@@ -282,7 +441,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
     b->n_vertices = g->n_vertices;
     b->build_csc = build_csc;
     int64_t dst_cap = n_seeds_cap;
-    int64_t max_rank = 1, max_sort = 1, max_scan = 1;
+    int64_t max_pad = 1, max_sort = 1, max_src = 1;
     for (int32_t h = 0; h < n_layers; ++h) {
         HopBuffers& H = b->hop[h];
         int64_t nnz_cap = dst_cap * fanouts[h];
@@ -296,34 +455,30 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
         H.has_csc = build_csc && h < n_layers - 1;
         NO_CHECK(H.src_global.alloc((size_t)src_cap));
         NO_CHECK(H.indptr.alloc((size_t)dst_cap + 1));
+        NO_CHECK(H.nbr_pad.alloc((size_t)nnz_cap));
         NO_CHECK(H.nbr_global.alloc((size_t)nnz_cap));
         NO_CHECK(H.indices.alloc((size_t)nnz_cap));
         NO_CHECK(H.edge_row.alloc((size_t)nnz_cap));
         if (H.has_csc) {
             NO_CHECK(H.csc_indptr.alloc((size_t)src_cap + 1));
             NO_CHECK(H.csc_cnt.alloc((size_t)src_cap + 1));
+            NO_CHECK(H.csc_cur.alloc((size_t)src_cap + 1));
             NO_CHECK(H.csc_dst.alloc((size_t)nnz_cap));
             NO_CHECK(H.csc_eid.alloc((size_t)nnz_cap));
-            NO_CHECK(H.csc_keys.alloc((size_t)nnz_cap));
             if (nnz_cap > max_sort) max_sort = nnz_cap;
         }
-        if (nnz_cap > max_rank) max_rank = nnz_cap;
-        if (src_cap > max_rank) max_rank = src_cap;
-        if (dst_cap > max_rank) max_rank = dst_cap;
+        if (nnz_cap > max_pad) max_pad = nnz_cap;
+        if (src_cap > max_src) max_src = src_cap;
         dst_cap = src_cap;
     }
-    max_scan = max_rank;
     NO_CHECK(b->counts.alloc((size_t)4 * n_layers + 8));
     NO_HIP_CHECK(hipMemset(b->counts.p, 0, ((size_t)4 * n_layers + 8) * 4));
     NO_CHECK(b->seeds.alloc((size_t)n_seeds_cap));
     NO_CHECK(b->map.alloc((size_t)g->n_vertices));
     NO_CHECK(fill_i32(b->map.p, EMPTY, g->n_vertices, nullptr));
-    NO_CHECK(b->rank.alloc((size_t)max_rank + 2));
     NO_CHECK(b->tmp_a.alloc((size_t)max_sort));
-    NO_CHECK(b->tmp_b.alloc((size_t)max_sort));
-    size_t ws = scan_ws_bytes(max_scan + 1);
-    size_t rs = radix_ws_bytes(max_sort);
-    NO_CHECK(b->ws.alloc(ws > rs ? ws : rs));
+    const int64_t max_items = max_pad > max_src ? max_pad : max_src;
+    NO_CHECK(b->ws.alloc((size_t)(edge_tiles(max_items + 1) + 2) * sizeof(int64_t)));
     if (n_layers >= 2) {
         size_t v1_cap = (size_t)b->hop[n_layers - 2].n_src_cap;
         NO_CHECK(b->compute_list.alloc(v1_cap));
@@ -347,7 +502,7 @@ void fill_block_view(const no_blocks_s* b, int32_t h, no_block_view* v) {
     v->d_n_dst = cnt;
     v->d_n_src = cnt + 1;
     v->d_nnz = cnt + 2;
-    v->d_dst_global = H.d_dst ? H.d_dst : (h == 0 ? b->seeds.p : b->hop[h - 1].src_global.p);
+    v->d_dst_global = H.src_global.p;     // the first n_dst sources are the destinations
     v->d_src_global = H.src_global.p;
     v->d_indptr = H.indptr.p;
     v->d_nbr_global = H.nbr_global.p;

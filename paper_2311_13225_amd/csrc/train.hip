@@ -26,7 +26,9 @@ struct no_model_s {
     no::DevBuf<float> row_loss;
     no::DevBuf<no_step_stats> stats;
     bool last_used_cache = false;
+    no::StageProfiler prof;
     void release() {
+        if (prof.created) { for (auto& e : prof.ev) (void)hipEventDestroy(e); prof.created = false; }
         if (blocks) { blocks->release(); delete blocks; blocks = nullptr; }
         params.release(); grads.release(); x0.release();
         for (auto& b : mean) b.release();
@@ -83,12 +85,11 @@ __global__ void __launch_bounds__(256) finish_stats_kernel(const float* __restri
             stats->nnz[h] = h < n_layers ? counts[4 * h + 2] : 0;
         }
         stats->n_hit = used_cache ? counts[4 * n_layers + 1] : 0;
+        stats->n_refresh = used_cache ? counts[4 * n_layers + 4] : 0;
         stats->n_v1 = n_layers >= 2 ? counts[4 * (n_layers - 2) + 1] : counts[0];
         stats->pad = 0;
     }
 }
-
-__global__ void zero_refresh_kernel(no_step_stats* stats) { stats->n_refresh = 0; }
 
 __global__ void sgd_kernel(float* __restrict__ w, const float* __restrict__ g, float lr, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -118,7 +119,7 @@ __global__ void __launch_bounds__(256) assemble_h1_kernel(const float* __restric
 __global__ void __launch_bounds__(256) refresh_cache_kernel(const float* __restrict__ h1c, const int32_t* __restrict__ computed_ids,
                                                             const int32_t* d_n_compute, const int32_t* __restrict__ slot_of_vertex,
                                                             int32_t dim, int32_t step, float* __restrict__ emb,
-                                                            int32_t* __restrict__ version, no_step_stats* stats) {
+                                                            int32_t* __restrict__ version) {
     const int lane = (int)(threadIdx.x & 63);
     const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     if (row >= *d_n_compute) return;
@@ -127,7 +128,7 @@ __global__ void __launch_bounds__(256) refresh_cache_kernel(const float* __restr
     const float* src = h1c + row * dim;
     float* dst = emb + (int64_t)slot * dim;
     for (int c = lane; c < dim; c += 64) dst[c] = src[c];
-    if (lane == 0) { version[slot] = step; atomicAdd(&stats->n_refresh, 1); }
+    if (lane == 0) version[slot] = step;
 }
 
 static inline unsigned wave_rows_blocks(int64_t rows) { int64_t b = ceil_div(rows, 4); return (unsigned)(b < 1 ? 1 : b); }
@@ -264,8 +265,14 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
     no_blocks_s* B = m->blocks;
     no_step_stats* stats = d_stats ? d_stats : m->stats.p;
 
+    StageProfiler& prof = m->prof;
+    prof.st = st;
+    prof.n = 0;
+
     // sample
+    prof.begin(NO_STAGE_SAMPLE);
     NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st));
+    prof.end();
     const bool used_cache = B->last_used_cache;
     m->last_used_cache = used_cache;
     const int32_t* extra = B->counts.p + 4 * L;
@@ -274,8 +281,10 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
     const HopBuffers& bottom = B->hop[L - 1];
     const int32_t es = m->feat_dtype == NO_F32 ? 4 : 2;
     const int32_t row_bytes = m->dims[0] * es;
+    prof.begin(NO_STAGE_GATHER);
     NO_CHECK(gather_rows(d_features, row_bytes, row_bytes, bottom.src_global.p, B->counts.p + 4 * (L - 1) + 1,
                          bottom.n_src_cap, m->x0.p, row_bytes, st));
+    prof.end();
 
     // forward
     no_block_view view[NO_MAX_LAYERS];
@@ -287,23 +296,29 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         const no_dtype dt = l == 1 ? m->feat_dtype : NO_F32;
         float* h_out = (l == 1 && used_cache) ? m->h1c.p : m->h[l - 1].p;
         LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
+        if (l == 2) prof.begin(NO_STAGE_FWD_UPPER);
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
-                              m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st));
+                              m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
+                              l == 1 ? &prof : nullptr, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1));
+        if (l == L && L >= 2) prof.end();
         if (l == 1 && used_cache) {
+            prof.begin(NO_STAGE_FWD_UPPER);
             hipLaunchKernelGGL(assemble_h1_kernel, dim3(wave_rows_blocks(blk.n_dst_cap)), dim3(256), 0, st,
                                (const float*)m->h1c.p, (const float*)cache->emb.p, (const int32_t*)B->compute_pos.p,
                                (const int32_t*)B->hit_pos.p, (const int32_t*)B->hit_slot.p, extra + 0, extra + 1, d_out,
                                m->h[0].p);
+            prof.end();
         }
     }
 
     // loss on the seeds
     const int32_t C = m->dims[L];
+    prof.begin(NO_STAGE_LOSS);
     hipLaunchKernelGGL(softmax_xent_kernel, dim3(wave_rows_blocks(n_seeds)), dim3(256), 0, st, (const float*)m->h[L - 1].p,
                        d_labels, (const int32_t*)B->seeds.p, n_seeds, C, m->gh[L - 1].p, m->row_loss.p);
     hipLaunchKernelGGL(finish_stats_kernel, dim3(1), dim3(256), 0, st, (const float*)m->row_loss.p, n_seeds,
                        (const int32_t*)B->counts.p, L, used_cache ? 1 : 0, stats);
-    hipLaunchKernelGGL(zero_refresh_kernel, dim3(1), dim3(1), 0, st, stats);
+    prof.end();
 
     // backward
     for (int32_t l = L; l >= 1; --l) {
@@ -313,10 +328,14 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         const no_dtype dt = l == 1 ? m->feat_dtype : NO_F32;
         const float* h_l = m->h[l - 1].p;
         const float* gh_l = m->gh[l - 1].p;
+        if (l == L && L >= 2) prof.begin(NO_STAGE_BWD_UPPER);
+        if (l == 1 && L >= 2) prof.end();
         if (l == 1 && used_cache) {
             // reused rows take no gradient: keep only the rows of the computed vertices
+            prof.begin(NO_STAGE_BWD_L1_PREP);
             NO_CHECK(gather_rows(m->gh[0].p, d_out * 4, (int64_t)d_out * 4, B->compute_pos.p, extra + 0, blk.n_dst_cap,
                                  m->gh1c.p, (int64_t)d_out * 4, st));
+            prof.end();
             h_l = m->h1c.p;
             gh_l = m->gh1c.p;
         }
@@ -324,10 +343,13 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         NO_CHECK(sage_backward(blk, x, dt, d_in, m->mean[l - 1].p, h_l, gh_l, m->params.p + m->off_w_self[l - 1],
                                m->params.p + m->off_w_neigh[l - 1], d_out, l < L ? 1 : 0,
                                m->grads.p + m->off_w_self[l - 1], m->grads.p + m->off_w_neigh[l - 1],
-                               m->grads.p + m->off_bias[l - 1], l > 1 ? m->gh[l - 2].p : nullptr, w, st));
+                               m->grads.p + m->off_bias[l - 1], l > 1 ? m->gh[l - 2].p : nullptr, w, st,
+                               l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
+                               -1));
     }
 
     // parameter update, then cache refresh with the rows computed by the pre-update weights
+    prof.begin(NO_STAGE_UPDATE);
     {
         int64_t blocks = ceil_div((int64_t)m->n_params, 256 * 4);
         if (blocks > 4096) blocks = 4096;
@@ -338,9 +360,19 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         hipLaunchKernelGGL(refresh_cache_kernel, dim3(wave_rows_blocks(bottom.n_dst_cap)), dim3(256), 0, st,
                            (const float*)m->h1c.p, (const int32_t*)B->compute_list.p, extra + 0,
                            (const int32_t*)cache->slot_of_vertex.p, m->dims[1], (int32_t)step, cache->emb.p,
-                           cache->version.p, stats);
+                           cache->version.p);
     }
+    prof.end();
     NO_CHECK(launch_status("train_step"));
+    if (prof.enabled) {
+        NO_HIP_CHECK(hipStreamSynchronize(st));
+        for (int i = 0; i < prof.n; ++i) {
+            float ms = 0.f;
+            NO_HIP_CHECK(hipEventElapsedTime(&ms, prof.ev[2 * i], prof.ev[2 * i + 1]));
+            prof.total_ms[prof.stage_of[i]] += (double)ms;
+        }
+        prof.steps += 1;
+    }
     if (h_stats) {
         NO_HIP_CHECK(hipMemcpyAsync(h_stats, stats, sizeof(no_step_stats), hipMemcpyDeviceToHost, st));
         NO_HIP_CHECK(hipStreamSynchronize(st));
@@ -354,4 +386,34 @@ extern "C" int32_t no_model_destroy(no_model_t m) {
     m->release();
     delete m;
     return NO_OK;
+}
+
+extern "C" int32_t no_model_profile(no_model_t m, int32_t enable) {
+    clear_error();
+    NO_REQUIRE(m != nullptr, NO_ERR_INVALID_ARG, "no_model_profile: model is NULL");
+    StageProfiler& p = m->prof;
+    if (enable && !p.created) {
+        for (auto& e : p.ev) NO_HIP_CHECK(hipEventCreate(&e));
+        p.created = true;
+    }
+    if (enable) {
+        for (auto& t : p.total_ms) t = 0.0;
+        p.steps = 0;
+    }
+    p.enabled = enable != 0;
+    return NO_OK;
+}
+
+extern "C" int32_t no_model_stage_ms(no_model_t m, double* h_total_ms, int32_t* h_steps) {
+    clear_error();
+    NO_REQUIRE(m && h_total_ms && h_steps, NO_ERR_INVALID_ARG, "no_model_stage_ms: NULL argument");
+    for (int s = 0; s < NO_STAGE_COUNT; ++s) h_total_ms[s] = m->prof.total_ms[s];
+    *h_steps = m->prof.steps;
+    return NO_OK;
+}
+
+extern "C" const char* no_stage_name(int32_t stage) {
+    static const char* names[NO_STAGE_COUNT] = {"sample", "gather", "agg_l1", "gemm_fwd_l1", "fwd_upper", "loss",
+                                                "bwd_upper", "bwd_l1_prep", "gemm_dw_l1", "bwd_l1_reduce", "update"};
+    return (stage >= 0 && stage < NO_STAGE_COUNT) ? names[stage] : "?";
 }

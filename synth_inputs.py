@@ -78,17 +78,49 @@ def _rng(seed: int, tag: str) -> np.random.Generator:
 # R-MAT
 # ----------------------------------------------------------------------------
 
+def _rmat_chunk(args):
+    seed, chunk_index, quota, n_vertices, scale, ta, tb, tc = args
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 0x726D6174, chunk_index])))
+    src = np.empty(quota, dtype=np.int32)
+    dst = np.empty(quota, dtype=np.int32)
+    filled = 0
+    while filled < quota:
+        m = int((quota - filled) * 1.35) + 1024
+        u = rng.integers(0, 65536, size=(scale, m), dtype=np.uint16)
+        s = np.zeros(m, dtype=np.int32)
+        d = np.zeros(m, dtype=np.int32)
+        for level in range(scale):
+            ul = u[level]
+            # quadrant a: neither bit, b: dst bit, c: src bit, d: both
+            ge_tb = ul >= tb
+            s <<= 1
+            s |= ge_tb
+            d <<= 1
+            d |= ((ul >= ta) & ~ge_tb) | (ul >= tc)
+        ok = (s < n_vertices) & (d < n_vertices)
+        s = s[ok]
+        d = d[ok]
+        take = min(len(s), quota - filled)
+        src[filled:filled + take] = s[:take]
+        dst[filled:filled + take] = d[:take]
+        filled += take
+    return src, dst
+
+
 def rmat_edges(n_vertices: int, n_edges: int, seed: int = 0, a: float = 0.57, b: float = 0.19,
                c: float = 0.19, symmetrise: bool = False, permute: bool = True,
-               chunk: int = 1 << 22) -> Tuple[np.ndarray, np.ndarray]:
+               chunk: int = 1 << 22, workers: Optional[int] = None) -> Tuple[np.ndarray, np.ndarray]:
     """Directed edge list (src, dst), int32, of an R-MAT graph.
 
     One quadrant choice per bit level (probabilities a, b, c, 1-a-b-c, 16 random bits
     per level); endpoints >= n_vertices are rejected and redrawn; vertex ids are then
     relabelled by a seeded permutation so that hubs are scattered over the id range.
     With ``symmetrise`` n_edges/2 pairs are drawn and emitted in both directions.
-    Multi-edges and self-loops are kept, as R-MAT makes them.
+    Multi-edges and self-loops are kept, as R-MAT makes them. Edges are drawn in chunks
+    with one generator per chunk, so the result does not depend on the worker count.
     """
+    import concurrent.futures
+    import os
     if n_vertices <= 0 or n_vertices >= 2 ** 31:
         raise ValueError("n_vertices out of range")
     scale = max(1, int(np.ceil(np.log2(n_vertices))))
@@ -96,35 +128,21 @@ def rmat_edges(n_vertices: int, n_edges: int, seed: int = 0, a: float = 0.57, b:
     ta = int(round(a * 65536))
     tb = ta + int(round(b * 65536))
     tc = tb + int(round(c * 65536))
-    rng = _rng(seed, "rmat")
-    src = np.empty(n_draw, dtype=np.int32)
-    dst = np.empty(n_draw, dtype=np.int32)
-    filled = 0
-    words_per_edge = (scale + 3) // 4
-    while filled < n_draw:
-        m = min(chunk, int((n_draw - filled) * 1.35) + 1024)
-        s = np.zeros(m, dtype=np.int64)
-        d = np.zeros(m, dtype=np.int64)
-        level = 0
-        for _ in range(words_per_edge):
-            bits = rng.integers(0, 1 << 64, size=m, dtype=np.uint64)
-            for q in range(4):
-                if level >= scale:
-                    break
-                u = ((bits >> np.uint64(16 * q)) & np.uint64(0xFFFF)).astype(np.int64)
-                # quadrant: 0 (a): neither bit, 1 (b): dst bit, 2 (c): src bit, 3: both
-                sbit = (u >= tb).astype(np.int64)          # quadrants c, d
-                dbit = (((u >= ta) & (u < tb)) | (u >= tc)).astype(np.int64)  # quadrants b, d
-                s = (s << 1) | sbit
-                d = (d << 1) | dbit
-                level += 1
-        ok = (s < n_vertices) & (d < n_vertices)
-        s = s[ok]
-        d = d[ok]
-        take = min(len(s), n_draw - filled)
-        src[filled:filled + take] = s[:take]
-        dst[filled:filled + take] = d[:take]
-        filled += take
+    jobs = [(seed, i, min(chunk, n_draw - lo), n_vertices, scale, ta, tb, tc)
+            for i, lo in enumerate(range(0, n_draw, chunk))]
+    if workers is None:
+        workers = max(1, min(16, (os.cpu_count() or 1)))
+    if len(jobs) <= 1 or workers == 1:
+        parts = [_rmat_chunk(j) for j in jobs]
+    else:
+        with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as ex:
+            parts = list(ex.map(_rmat_chunk, jobs))
+    if parts:
+        src = np.concatenate([p[0] for p in parts])
+        dst = np.concatenate([p[1] for p in parts])
+    else:
+        src = np.zeros(0, dtype=np.int32)
+        dst = np.zeros(0, dtype=np.int32)
     if permute:
         perm = _rng(seed, "vperm").permutation(n_vertices).astype(np.int32)
         src = perm[src]
