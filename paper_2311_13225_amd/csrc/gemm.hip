@@ -1,102 +1,122 @@
-// LDS-tiled fp32 MFMA matrix products (see gemm.hpp). Block tile 128x128x32, 256 threads =
-// 4 wavefronts, each owning a 64x64 sub-tile as 2x2 v_mfma_f32_32x32x2_f32 accumulators.
+// LDS-tiled fp32 MFMA matrix products (see gemm.hpp). Block tile BM x BN x 32 with BM, BN in
+// {64, 128}, 256 threads = 2 x 2 wavefronts, each owning a (BM/2) x (BN/2) sub-tile as
+// v_mfma_f32_32x32x2_f32 accumulators. The tile shape is picked per call so that tall-skinny
+// problems whose row count is a device scalar still spread over the 256 compute units.
 //
 // Operand tiles sit in LDS in one of two layouts, chosen by how the operand lies in memory:
 //   KC (reduction index contiguous in memory): T[x][k], pitch 36 floats; a lane fetches the four
 //       k values it needs for four consecutive MFMAs with one 16-byte LDS read, conflict free.
-//   XC (tile row/column index contiguous): T[k][x], pitch 128; four 4-byte LDS reads.
+//   XC (tile row/column index contiguous): T[k][x], pitch = tile width; four 4-byte LDS reads.
 // Within each group of 8 reduction indices lanes 0-31 take indices 0-3 and lanes 32-63 take 4-7
 // for MFMA 0-3; both operands use the same assignment, so every index is summed exactly once.
 #include "gemm.hpp"
+
+#include <stdlib.h>
 
 namespace no {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int PITCH_KC = 36, PITCH_XC = 128;
-constexpr int TILE_FLOATS = 128 * PITCH_KC;   // >= 32 * PITCH_XC
+constexpr int BK = 32;
+constexpr int PITCH_KC = 36;
 
-__device__ __forceinline__ float4 load4(const float* p, int valid, int align) {
+template <bool KC, int BX> struct TileShape {
+    static constexpr int FLOATS = KC ? BX * PITCH_KC : BK * BX;
+    static constexpr int PASSES = BX / 32;
+};
+
+// 16-byte load from a 4-byte aligned address (rows of 602 floats start on 8-byte boundaries only).
+typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+__device__ __forceinline__ float4 load4_fast(const float* p) {
+    float4_a4 v = *reinterpret_cast<const float4_a4*>(p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ float4 load4_guarded(const float* p, int valid) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (valid >= 4) {
-        if (align == 4) v = *reinterpret_cast<const float4*>(p);
-        else if (align == 2) {
-            float2 a = *reinterpret_cast<const float2*>(p), b = *reinterpret_cast<const float2*>(p + 2);
-            v = make_float4(a.x, a.y, b.x, b.y);
-        } else v = make_float4(p[0], p[1], p[2], p[3]);
-    } else {
-        if (valid > 0) v.x = p[0];
-        if (valid > 1) v.y = p[1];
-        if (valid > 2) v.z = p[2];
-    }
+    if (valid > 0) v.x = p[0];
+    if (valid > 1) v.y = p[1];
+    if (valid > 2) v.z = p[2];
+    if (valid > 3) v.w = p[3];
     return v;
 }
 
-// Global -> registers for one 128 x 32 operand tile. x = tile row/column index, k = reduction index.
-template <bool KC>
-__device__ __forceinline__ void tile_fetch(float4 (&reg)[4], const float* src, int64_t ld, int x0, int x_lim, int k0,
-                                           int k_lim, int align) {
+// Global -> registers for one BX x 32 operand tile. x = tile row/column index, k = reduction index.
+// FAST: the whole tile lies inside the operand (no guards, no branches: the hot path).
+// Otherwise every element is guarded and out-of-range elements read as zero; ones_col >= 0 (XC only)
+// adds a virtual column of ones at index `ones_col`, which makes row `ones_col` of the product the
+// column sums of the other operand (the bias gradient).
+template <bool KC, int BX, bool FAST>
+__device__ __forceinline__ void tile_fetch(float4 (&reg)[BX / 32], const float* src, int64_t ld, int x0, int x_lim, int k0,
+                                           int k_lim, int ones_col = -1) {
     const int tid = (int)threadIdx.x;
     if (KC) {
         const int kq = tid & 7, xr = tid >> 3;
 #pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
+        for (int pass = 0; pass < BX / 32; ++pass) {
             const int gx = x0 + xr + 32 * pass, gk = k0 + kq * 4;
-            int valid = gx < x_lim ? k_lim - gk : 0;
-            reg[pass] = valid > 0 ? load4(src + (int64_t)gx * ld + gk, valid, align) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (FAST) reg[pass] = load4_fast(src + (int64_t)gx * ld + gk);
+            else reg[pass] = load4_guarded(src + (int64_t)gx * ld + gk, gx < x_lim ? k_lim - gk : 0);
         }
     } else {
-        const int xq = tid & 31, kr = tid >> 5;
+        constexpr int XQ = BX / 4, ROWS = 256 / XQ;
+        const int xq = tid % XQ, kr = tid / XQ;
 #pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
-            const int gk = k0 + kr + 8 * pass, gx = x0 + xq * 4;
-            int valid = gk < k_lim ? x_lim - gx : 0;
-            reg[pass] = valid > 0 ? load4(src + (int64_t)gk * ld + gx, valid, align) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int pass = 0; pass < BX / 32; ++pass) {
+            const int gk = k0 + kr + ROWS * pass, gx = x0 + xq * 4;
+            if (FAST) reg[pass] = load4_fast(src + (int64_t)gk * ld + gx);
+            else {
+                float4 v = load4_guarded(src + (int64_t)gk * ld + gx, gk < k_lim ? x_lim - gx : 0);
+                if (ones_col >= 0 && gk < k_lim && ones_col >= gx && ones_col < gx + 4) {
+                    const int c = ones_col - gx;
+                    if (c == 0) v.x = 1.f; else if (c == 1) v.y = 1.f; else if (c == 2) v.z = 1.f; else v.w = 1.f;
+                }
+                reg[pass] = v;
+            }
         }
     }
 }
 
-template <bool KC>
-__device__ __forceinline__ void tile_store(const float4 (&reg)[4], float* S) {
+template <bool KC, int BX>
+__device__ __forceinline__ void tile_store(const float4 (&reg)[BX / 32], float* S) {
     const int tid = (int)threadIdx.x;
     if (KC) {
         const int kq = tid & 7, xr = tid >> 3;
 #pragma unroll
-        for (int pass = 0; pass < 4; ++pass)
+        for (int pass = 0; pass < BX / 32; ++pass)
             *reinterpret_cast<float4*>(&S[(xr + 32 * pass) * PITCH_KC + kq * 4]) = reg[pass];
     } else {
-        const int xq = tid & 31, kr = tid >> 5;
+        constexpr int XQ = BX / 4, ROWS = 256 / XQ;
+        const int xq = tid % XQ, kr = tid / XQ;
 #pragma unroll
-        for (int pass = 0; pass < 4; ++pass)
-            *reinterpret_cast<float4*>(&S[(kr + 8 * pass) * PITCH_XC + xq * 4]) = reg[pass];
+        for (int pass = 0; pass < BX / 32; ++pass)
+            *reinterpret_cast<float4*>(&S[(kr + ROWS * pass) * BX + xq * 4]) = reg[pass];
     }
 }
 
 // The four reduction values (chunk of 8, this lane's half) of tile row/column x.
-template <bool KC>
+template <bool KC, int BX>
 __device__ __forceinline__ float4 tile_frag(const float* S, int x, int chunk, int half) {
     if (KC) return *reinterpret_cast<const float4*>(&S[x * PITCH_KC + chunk * 8 + half * 4]);
-    const float* p = &S[(chunk * 8 + half * 4) * PITCH_XC + x];
-    return make_float4(p[0], p[PITCH_XC], p[2 * PITCH_XC], p[3 * PITCH_XC]);
+    const float* p = &S[(chunk * 8 + half * 4) * BX + x];
+    return make_float4(p[0], p[BX], p[2 * BX], p[3 * BX]);
 }
 
-template <bool A_KC, bool B_KC>
-__device__ __forceinline__ void tile_mma(const float* As, const float* Bs, floatx16 (&acc)[2][2], int wm, int wn) {
+template <bool A_KC, bool B_KC, int BM, int BN>
+__device__ __forceinline__ void tile_mma(const float* As, const float* Bs, floatx16 (&acc)[BM / 64][BN / 64], int wm, int wn) {
+    constexpr int MI = BM / 64, NI = BN / 64;
     const int lane = (int)(threadIdx.x & 63);
     const int half = lane >> 5, l32 = lane & 31;
 #pragma unroll
     for (int chunk = 0; chunk < BK / 8; ++chunk) {
-        float4 a[2], b[2];
+        float4 a[MI], b[NI];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            a[i] = tile_frag<A_KC>(As, wm * 64 + i * 32 + l32, chunk, half);
-            b[i] = tile_frag<B_KC>(Bs, wn * 64 + i * 32 + l32, chunk, half);
-        }
+        for (int i = 0; i < MI; ++i) a[i] = tile_frag<A_KC, BM>(As, wm * (BM / 2) + i * 32 + l32, chunk, half);
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+        for (int i = 0; i < NI; ++i) b[i] = tile_frag<B_KC, BN>(Bs, wn * (BN / 2) + i * 32 + l32, chunk, half);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].x, b[ni].x, acc[mi][ni], 0, 0, 0);
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].y, b[ni].y, acc[mi][ni], 0, 0, 0);
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].z, b[ni].z, acc[mi][ni], 0, 0, 0);
@@ -108,12 +128,23 @@ __device__ __forceinline__ void tile_mma(const float* As, const float* Bs, float
 // Accumulator element r of lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32 of the 32x32 tile.
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
+template <int MI, int NI>
+__device__ __forceinline__ void acc_zero(floatx16 (&acc)[MI][NI]) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+}
+
 // ------------------------------------------------------------------------------------------ NN
 
-template <bool B_KC>
+template <bool B_KC, int BM, int BN>
 __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
-    __shared__ __attribute__((aligned(16))) float As[TILE_FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[TILE_FLOATS];
+    constexpr int MI = BM / 64, NI = BN / 64;
+    __shared__ __attribute__((aligned(16))) float As[TileShape<true, BM>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float Bs[TileShape<B_KC, BN>::FLOATS];
     int M = *g.d_M;
     if (M > g.M_cap) M = g.M_cap;
     const int m0 = (int)blockIdx.y * BM, n0 = (int)blockIdx.x * BN;
@@ -121,33 +152,40 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
     const int prob = g.accumulate ? 0 : (int)blockIdx.z;
     const int n_phases = g.accumulate ? g.n_problems : 1;
     const int wave = (int)(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
-    floatx16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    floatx16 acc[MI][NI];
+    acc_zero<MI, NI>(acc);
 
     for (int ph = 0; ph < n_phases; ++ph) {
         const int q = g.accumulate ? ph : prob;
         const float* A = g.A[q];
         const float* B = g.B[q];
         const int64_t lda = g.lda[q], ldb = g.ldb[q];
-        const int K = g.K[q], aal = g.a_align[q], bal = g.b_align[q];
-        float4 ra[4], rb[4];
-        tile_fetch<true>(ra, A, lda, m0, M, 0, K, aal);
-        tile_fetch<B_KC>(rb, B, ldb, n0, g.N, 0, K, bal);
-        for (int k0 = 0; k0 < K; k0 += BK) {
+        const int K = g.K[q];
+        const bool full_x = (m0 + BM <= M) && (n0 + BN <= g.N);
+        const int n_steps = (K + BK - 1) / BK;
+        const int n_fast = full_x ? K / BK : 0;          // steps whose tiles need no guards
+        float4 ra[BM / 32], rb[BN / 32];
+        if (n_fast > 0) {
+            tile_fetch<true, BM, true>(ra, A, lda, m0, M, 0, K);
+            tile_fetch<B_KC, BN, true>(rb, B, ldb, n0, g.N, 0, K);
+        } else {
+            tile_fetch<true, BM, false>(ra, A, lda, m0, M, 0, K);
+            tile_fetch<B_KC, BN, false>(rb, B, ldb, n0, g.N, 0, K);
+        }
+        for (int s = 0; s < n_steps; ++s) {
             __syncthreads();
-            tile_store<true>(ra, As);
-            tile_store<B_KC>(rb, Bs);
+            tile_store<true, BM>(ra, As);
+            tile_store<B_KC, BN>(rb, Bs);
             __syncthreads();
-            if (k0 + BK < K) {
-                tile_fetch<true>(ra, A, lda, m0, M, k0 + BK, K, aal);
-                tile_fetch<B_KC>(rb, B, ldb, n0, g.N, k0 + BK, K, bal);
+            const int kn = (s + 1) * BK;
+            if (s + 1 < n_fast) {
+                tile_fetch<true, BM, true>(ra, A, lda, m0, M, kn, K);
+                tile_fetch<B_KC, BN, true>(rb, B, ldb, n0, g.N, kn, K);
+            } else if (s + 1 < n_steps) {
+                tile_fetch<true, BM, false>(ra, A, lda, m0, M, kn, K);
+                tile_fetch<B_KC, BN, false>(rb, B, ldb, n0, g.N, kn, K);
             }
-            tile_mma<true, B_KC>(As, Bs, acc, wm, wn);
+            tile_mma<true, B_KC, BM, BN>(As, Bs, acc, wm, wn);
         }
     }
     const int lane = (int)(threadIdx.x & 63);
@@ -155,16 +193,16 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
     const int64_t ldc = g.ldc[prob];
     const int32_t* sp = g.row_scale_indptr[prob];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 64 + mi * 32 + acc_row(r, lane);
+            const int row = m0 + wm * (BM / 2) + mi * 32 + acc_row(r, lane);
             if (row >= M) continue;
             float scale = 1.f;
             if (sp) { int len = sp[row + 1] - sp[row]; scale = len > 0 ? 1.f / (float)len : 0.f; }
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const int col = n0 + wn * 64 + ni * 32 + (lane & 31);
+            for (int ni = 0; ni < NI; ++ni) {
+                const int col = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
                 if (col >= g.N) continue;
                 float v = acc[mi][ni][r];
                 if (g.bias) v += g.bias[col];
@@ -174,19 +212,51 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
         }
 }
 
+// Largest tile that still gives the chip enough blocks, assuming about half the row capacity is used.
+static void pick_tile(int64_t rows_est, int64_t cols, int64_t batch, int* bm, int* bn) {
+    // NO_GEMM_TILE=<bm>x<bn> pins the tile shape (tuning aid; both values in {64, 128})
+    static const char* forced = getenv("NO_GEMM_TILE");
+    if (forced) {
+        int fm = 0, fn = 0;
+        if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128)) {
+            *bm = fm; *bn = fn;
+            return;
+        }
+    }
+    const int cand[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
+    for (int c = 0; c < 4; ++c) {
+        if (cols <= 64 && cand[c][1] == 128) continue;
+        const int64_t blocks = ceil_div(rows_est, cand[c][0]) * ceil_div(cols, cand[c][1]) * batch;
+        if (blocks >= 512 || c == 3) { *bm = cand[c][0]; *bn = cand[c][1]; return; }
+    }
+}
+
+template <bool B_KC>
+static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st) {
+    const unsigned z = (unsigned)(a.accumulate ? 1 : a.n_problems);
+    dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.M_cap, bm), z);
+    if (bm == 128 && bn == 128) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 128, 128>), grid, dim3(256), 0, st, a);
+    else if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), 0, st, a);
+    else if (bm == 128 && bn == 64) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 64, 64>), grid, dim3(256), 0, st, a);
+}
+
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st) {
-    dim3 grid((unsigned)ceil_div(a.N, BN), (unsigned)ceil_div(a.M_cap, BM), (unsigned)(a.accumulate ? 1 : a.n_problems));
     if (a.M_cap <= 0 || a.N <= 0) return NO_OK;
-    if (b_transposed) hipLaunchKernelGGL(gemm_nn_kernel<true>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(gemm_nn_kernel<false>, grid, dim3(256), 0, st, a);
+    int bm, bn;
+    pick_tile(a.M_est > 0 ? a.M_est : (a.M_cap + 1) / 2, a.N, a.accumulate ? 1 : a.n_problems, &bm, &bn);
+    if (b_transposed) launch_nn<true>(a, bm, bn, st);
+    else launch_nn<false>(a, bm, bn, st);
     return launch_status("gemm_nn");
 }
 
 // ------------------------------------------------------------------------------------------ TN
 
+template <int BM, int BN>
 __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
-    __shared__ __attribute__((aligned(16))) float As[TILE_FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[TILE_FLOATS];
+    constexpr int MI = BM / 64, NI = BN / 64;
+    __shared__ __attribute__((aligned(16))) float As[TileShape<false, BM>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float Bs[TileShape<false, BN>::FLOATS];
     int R = *g.d_R;
     if (R > g.R_cap) R = g.R_cap;
     const int prob = (int)blockIdx.z / g.splits, split = (int)blockIdx.z % g.splits;
@@ -196,43 +266,51 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
     const int r1 = min(R, r0 + chunk);
     const int m0 = (int)blockIdx.y * BM, n0 = (int)blockIdx.x * BN;
     const int wave = (int)(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
-    floatx16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    floatx16 acc[MI][NI];
+    acc_zero<MI, NI>(acc);
     const float* A = g.A[prob];
     const int64_t lda = g.lda[prob];
-    const int aal = g.a_align[prob];
+    const int ones_col = prob == 0 ? g.Kp : -1;       // product 0 carries the column sums of G in row Kp
     if (r0 < r1) {
-        float4 ra[4], rb[4];
-        tile_fetch<false>(ra, A, lda, m0, g.Kp, r0, r1, aal);
-        tile_fetch<false>(rb, g.G, g.ldg, n0, g.N, r0, r1, g.g_align);
-        for (int k0 = r0; k0 < r1; k0 += BK) {
+        const bool full_x = (m0 + BM <= g.Kp) && (n0 + BN <= g.N);
+        const int n_steps = (r1 - r0 + BK - 1) / BK;
+        const int n_fast = full_x ? (r1 - r0) / BK : 0;
+        float4 ra[BM / 32], rb[BN / 32];
+        if (n_fast > 0) {
+            tile_fetch<false, BM, true>(ra, A, lda, m0, g.Kp, r0, r1);
+            tile_fetch<false, BN, true>(rb, g.G, g.ldg, n0, g.N, r0, r1);
+        } else {
+            tile_fetch<false, BM, false>(ra, A, lda, m0, g.Kp, r0, r1, ones_col);
+            tile_fetch<false, BN, false>(rb, g.G, g.ldg, n0, g.N, r0, r1);
+        }
+        for (int s = 0; s < n_steps; ++s) {
             __syncthreads();
-            tile_store<false>(ra, As);
-            tile_store<false>(rb, Bs);
+            tile_store<false, BM>(ra, As);
+            tile_store<false, BN>(rb, Bs);
             __syncthreads();
-            if (k0 + BK < r1) {
-                tile_fetch<false>(ra, A, lda, m0, g.Kp, k0 + BK, r1, aal);
-                tile_fetch<false>(rb, g.G, g.ldg, n0, g.N, k0 + BK, r1, g.g_align);
+            const int kn = r0 + (s + 1) * BK;
+            if (s + 1 < n_fast) {
+                tile_fetch<false, BM, true>(ra, A, lda, m0, g.Kp, kn, r1);
+                tile_fetch<false, BN, true>(rb, g.G, g.ldg, n0, g.N, kn, r1);
+            } else if (s + 1 < n_steps) {
+                tile_fetch<false, BM, false>(ra, A, lda, m0, g.Kp, kn, r1, ones_col);
+                tile_fetch<false, BN, false>(rb, g.G, g.ldg, n0, g.N, kn, r1);
             }
-            tile_mma<false, false>(As, Bs, acc, wm, wn);
+            tile_mma<false, false, BM, BN>(As, Bs, acc, wm, wn);
         }
     }
     const int lane = (int)(threadIdx.x & 63);
-    float* P = g.P + ((int64_t)prob * g.splits + split) * (int64_t)g.Kp * g.N;
+    const int rows_out = g.Kp + 1;
+    float* P = g.P + ((int64_t)prob * g.splits + split) * (int64_t)rows_out * g.N;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 64 + mi * 32 + acc_row(r, lane);
-            if (row >= g.Kp) continue;
+            const int row = m0 + wm * (BM / 2) + mi * 32 + acc_row(r, lane);
+            if (row >= rows_out) continue;
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const int col = n0 + wn * 64 + ni * 32 + (lane & 31);
+            for (int ni = 0; ni < NI; ++ni) {
+                const int col = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
                 if (col < g.N) P[(int64_t)row * g.N + col] = acc[mi][ni][r];
             }
         }
@@ -240,30 +318,44 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
 
 int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st) {
     if (a.Kp <= 0 || a.N <= 0) return NO_OK;
-    dim3 grid((unsigned)ceil_div(a.N, BN), (unsigned)ceil_div(a.Kp, BM), (unsigned)(2 * a.splits));
-    hipLaunchKernelGGL(gemm_tn_kernel, grid, dim3(256), 0, st, a);
+    int bm, bn;
+    pick_tile(a.Kp + 1, a.N, 2 * a.splits, &bm, &bn);
+    dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.Kp + 1, bm), (unsigned)(2 * a.splits));
+    if (bm == 128 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<128, 128>), grid, dim3(256), 0, st, a);
+    else if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<64, 128>), grid, dim3(256), 0, st, a);
+    else if (bm == 128 && bn == 64) hipLaunchKernelGGL((gemm_tn_kernel<128, 64>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((gemm_tn_kernel<64, 64>), grid, dim3(256), 0, st, a);
     return launch_status("gemm_tn");
 }
 
-struct ReduceOuts { float* p[4]; };
-
-__global__ void reduce_partials_kernel(const float* __restrict__ P, int32_t splits, int64_t elems, ReduceOuts outs) {
+// Sums the split partial products in split order: g_self = rows [0,Kp) of product 0, g_bias = row Kp of
+// product 0, g_neigh = rows [0,Kp) of product 1. With lr != 0 the parameters take their SGD step in the
+// same pass (W <- W - lr * g), after every kernel that read them.
+__global__ void reduce_grads_kernel(const float* __restrict__ P, int32_t splits, int32_t Kp, int32_t N, float* g_self,
+                                    float* g_neigh, float* g_bias, float lr, float* w_self, float* w_neigh, float* w_bias) {
+    const int64_t per = (int64_t)(Kp + 1) * N;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int q = (int)blockIdx.y;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= elems) return;
-    const float* p = P + (int64_t)q * splits * elems + i;
+    if (i >= per) return;
+    const bool bias_row = i >= (int64_t)Kp * N;
+    if (q == 1 && bias_row) return;
+    const float* p = P + (int64_t)q * splits * per + i;
     float s = 0.f;
-    for (int32_t k = 0; k < splits; ++k) s += p[(int64_t)k * elems];
-    outs.p[q][i] = s;
+    for (int32_t k = 0; k < splits; ++k) s += p[(int64_t)k * per];
+    float* gout = bias_row ? g_bias + (i - (int64_t)Kp * N) : (q == 0 ? g_self + i : g_neigh + i);
+    *gout = s;
+    if (lr != 0.f) {
+        float* w = bias_row ? w_bias + (i - (int64_t)Kp * N) : (q == 0 ? w_self + i : w_neigh + i);
+        *w -= lr * s;
+    }
 }
 
-int32_t reduce_partials(const float* P, int32_t n_out, int32_t splits, int64_t elems, float* const* outs, hipStream_t st) {
-    if (elems <= 0 || n_out <= 0) return NO_OK;
-    ReduceOuts o{};
-    for (int q = 0; q < n_out && q < 4; ++q) o.p[q] = outs[q];
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(elems, 256), (unsigned)n_out), dim3(256), 0, st, P,
-                       splits, elems, o);
-    return launch_status("reduce_partials");
+int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
+                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st) {
+    const int64_t per = (int64_t)(Kp + 1) * N;
+    hipLaunchKernelGGL(reduce_grads_kernel, dim3((unsigned)ceil_div(per, 256), 2), dim3(256), 0, st, P, splits, Kp, N, g_self,
+                       g_neigh, g_bias, lr, w_self, w_neigh, w_bias);
+    return launch_status("reduce_grads");
 }
 
 }  // namespace no

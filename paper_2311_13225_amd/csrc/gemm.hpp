@@ -18,21 +18,23 @@ struct GemmNNArgs {
     int32_t n_problems;                   // 1 or 2
     int32_t accumulate;                   // 1: both products are summed into C[0]; 0: independent problems (grid.z)
     const int32_t* d_M; int32_t M_cap; int32_t N;
+    int32_t M_est;                        // expected row count for tile selection (0: half the capacity)
     const float* bias; int32_t relu;
 };
 
 struct GemmTNArgs {
     const float* A[2]; int64_t lda[2]; int a_align[2];   // [R, Kp] row-major; two problems share G
     const float* G; int64_t ldg; int g_align;            // [R, N]
-    float* P;                                            // partials [2][splits][Kp][N]
+    float* P;                                            // partials [2][splits][Kp+1][N]; row Kp of product 0 = column sums of G
     int32_t Kp, N;
     const int32_t* d_R; int32_t R_cap; int32_t splits;
 };
 
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st);
 int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st);
-// out[q][i] = sum_s P[q][s][i], q < n_out, i < elems; fixed order.
-int32_t reduce_partials(const float* P, int32_t n_out, int32_t splits, int64_t elems, float* const* outs, hipStream_t st);
+// Sums the partials in split order into the three gradients; with lr != 0 also applies W <- W - lr * g.
+int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
+                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st);
 
 inline int ptr_align(const void* p, int64_t ld) {
     if ((((uintptr_t)p) & 15) == 0 && (ld & 3) == 0) return 4;

@@ -32,8 +32,7 @@ struct LayerWorkspace {
     float* gz = nullptr;             // [n_dst_cap, d_out] masked output gradient
     float* gmean = nullptr;          // [n_dst_cap, d_in]  gradient of the mean, pre-divided by the row length
     float* x_dst_f32 = nullptr;      // [n_dst_cap, d_in]  fp32 copy of bf16 destination rows
-    float* partials = nullptr;       // [2, splits, d_in, d_out]
-    float* bias_partials = nullptr;  // [splits, d_out]
+    float* partials = nullptr;       // [2, splits, d_in + 1, d_out]
     int32_t splits = 1;
     size_t bytes = 0;
 };
@@ -54,7 +53,9 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int prep_stage = -1,
-                      int dw_stage = -1, int reduce_stage = -1, int dx_stage = -1);
+                      int dw_stage = -1, int reduce_stage = -1, int dx_stage = -1,
+                      const int32_t* grad_rows = nullptr, float lr = 0.f, float* w_self_rw = nullptr,
+                      float* w_neigh_rw = nullptr, float* bias_rw = nullptr);
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
                     const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
 

@@ -151,30 +151,21 @@ int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_
 
 // ------------------------------------------------------------------------ small elementwise kernels
 
-__global__ void relu_mask_kernel(const float* __restrict__ grad_h, const float* __restrict__ h, const int32_t* d_n,
-                                 int32_t n_cap, int32_t dim, int32_t relu, float* __restrict__ gz) {
+// gz[r,:] = grad_h[rows ? rows[r] : r, :] masked by [h[r,:] > 0] when relu: selects the rows that take a gradient
+// (the computed vertices when hot rows were reused) and applies the activation's derivative in one pass.
+__global__ void mask_rows_kernel(const float* __restrict__ grad_h, const int32_t* __restrict__ rows,
+                                 const float* __restrict__ h, const int32_t* d_n, int32_t n_cap, int32_t dim, int32_t relu,
+                                 float* __restrict__ gz) {
     int32_t n = *d_n;
     if (n > n_cap) n = n_cap;
     const int64_t total = (int64_t)n * dim;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < total; i += stride) gz[i] = (!relu || h[i] > 0.f) ? grad_h[i] : 0.f;
-}
-
-// partial[s][j] = sum of gz[r][j] over the rows of split s (same split rule as the TN product)
-__global__ void colsum_partials_kernel(const float* __restrict__ gz, const int32_t* d_n, int32_t n_cap, int32_t dim,
-                                       int32_t splits, float* __restrict__ partial) {
-    int32_t R = *d_n;
-    if (R > n_cap) R = n_cap;
-    int chunk = (R + splits - 1) / splits;
-    chunk = (chunk + 31) / 32 * 32;
-    const int s = (int)blockIdx.y;
-    const int r0 = s * chunk, r1 = min(R, r0 + chunk);
-    const int j = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (j >= dim) return;
-    float acc = 0.f;
-    for (int r = r0; r < r1; ++r) acc += gz[(int64_t)r * dim + j];
-    partial[(int64_t)s * dim + j] = acc;
+    for (; i < total; i += stride) {
+        const int64_t r = i / dim, c = i - r * dim;
+        const float g = rows ? grad_h[(int64_t)rows[r] * dim + c] : grad_h[i];
+        gz[i] = (!relu || h[i] > 0.f) ? g : 0.f;
+    }
 }
 
 __global__ void bf16_rows_to_f32_kernel(const uint16_t* __restrict__ x, const int32_t* d_n, int32_t n_cap, int32_t dim,
@@ -216,8 +207,7 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
     w.gz = (float*)(base + off);        off += align256((size_t)n_dst_cap * d_out * 4);
     w.gmean = (float*)(base + off);     off += align256((size_t)n_dst_cap * d_in * 4);
     w.x_dst_f32 = (float*)(base + off); off += align256((size_t)n_dst_cap * d_in * 4);
-    w.partials = (float*)(base + off);  off += align256((size_t)2 * w.splits * d_in * d_out * 4);
-    w.bias_partials = (float*)(base + off); off += align256((size_t)w.splits * d_out * 4);
+    w.partials = (float*)(base + off);  off += align256((size_t)2 * w.splits * (d_in + 1) * d_out * 4);
     w.bytes = off;
     return w;
 }
@@ -256,41 +246,29 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int prep_stage, int dw_stage,
-                      int reduce_stage, int dx_stage) {
+                      int reduce_stage, int dx_stage, const int32_t* grad_rows, float lr, float* w_self_rw,
+                      float* w_neigh_rw, float* bias_rw) {
     const int32_t n_cap = blk.n_dst_cap;
     if (prof && prep_stage >= 0) prof->begin(prep_stage);
-    hipLaunchKernelGGL(relu_mask_kernel, dim3(ew_blocks((int64_t)n_cap * d_out)), dim3(256), 0, st, grad_h, h, blk.d_n_dst,
-                       n_cap, d_out, relu, w.gz);
+    const float* gz = grad_h;
+    if (relu || grad_rows) {
+        hipLaunchKernelGGL(mask_rows_kernel, dim3(ew_blocks((int64_t)n_cap * d_out)), dim3(256), 0, st, grad_h, grad_rows, h,
+                           blk.d_n_dst, n_cap, d_out, relu, w.gz);
+        gz = w.gz;
+    }
     const float* x_dst = (const float*)x_src;
     if (dt == NO_BF16) {
         hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)n_cap * d_in)), dim3(256), 0, st,
                            (const uint16_t*)x_src, blk.d_n_dst, n_cap, d_in, w.x_dst_f32);
         x_dst = w.x_dst_f32;
     }
-    // weight gradients: x_dst^T gz and mean^T gz, split over rows, summed in split order
-    GemmTNArgs t{};
-    t.A[0] = x_dst; t.lda[0] = d_in; t.a_align[0] = ptr_align(x_dst, d_in);
-    t.A[1] = mean;  t.lda[1] = d_in; t.a_align[1] = ptr_align(mean, d_in);
-    t.G = w.gz; t.ldg = d_out; t.g_align = ptr_align(w.gz, d_out);
-    t.P = w.partials; t.Kp = d_in; t.N = d_out;
-    t.d_R = blk.d_n_dst; t.R_cap = n_cap; t.splits = w.splits;
     if (prof && prep_stage >= 0) prof->end();
-    if (prof && dw_stage >= 0) prof->begin(dw_stage);
-    NO_CHECK(gemm_tn_partials(t, st));
-    if (prof && dw_stage >= 0) prof->end();
-    if (prof && reduce_stage >= 0) prof->begin(reduce_stage);
-    hipLaunchKernelGGL(colsum_partials_kernel, dim3((unsigned)ceil_div(d_out, 256), (unsigned)w.splits), dim3(256), 0, st,
-                       (const float*)w.gz, blk.d_n_dst, n_cap, d_out, w.splits, w.bias_partials);
-    float* outs[2] = {gw_self, gw_neigh};
-    NO_CHECK(reduce_partials(w.partials, 2, w.splits, (int64_t)d_in * d_out, outs, st));
-    float* bouts[1] = {gbias};
-    NO_CHECK(reduce_partials(w.bias_partials, 1, w.splits, d_out, bouts, st));
-    if (prof && reduce_stage >= 0) prof->end();
     if (grad_x_src) {
-        if (prof && dx_stage >= 0) prof->begin(dx_stage);
+        // uses the pre-update weights, so it runs before the reduce that may apply the SGD step:
         // gz W_self^T -> rows [0, n_dst) of grad_x; (gz W_neigh^T) / len(row) -> gmean; then the transpose adds
+        if (prof && dx_stage >= 0) prof->begin(dx_stage);
         GemmNNArgs a{};
-        a.A[0] = a.A[1] = w.gz; a.lda[0] = a.lda[1] = d_out; a.a_align[0] = a.a_align[1] = ptr_align(w.gz, d_out);
+        a.A[0] = a.A[1] = gz; a.lda[0] = a.lda[1] = d_out; a.a_align[0] = a.a_align[1] = ptr_align(gz, d_out);
         a.B[0] = w_self;  a.ldb[0] = d_out; a.b_align[0] = ptr_align(w_self, d_out);
         a.B[1] = w_neigh; a.ldb[1] = d_out; a.b_align[1] = ptr_align(w_neigh, d_out);
         a.K[0] = a.K[1] = d_out;
@@ -304,6 +282,20 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                                      blk.d_n_dst, grad_x_src, st));
         if (prof && dx_stage >= 0) prof->end();
     }
+    // weight gradients x_dst^T gz, mean^T gz and the bias gradient (column sums of gz, carried by a virtual
+    // column of ones in the first product), split over rows and summed in split order
+    GemmTNArgs t{};
+    t.A[0] = x_dst; t.lda[0] = d_in; t.a_align[0] = ptr_align(x_dst, d_in);
+    t.A[1] = mean;  t.lda[1] = d_in; t.a_align[1] = ptr_align(mean, d_in);
+    t.G = gz; t.ldg = d_out; t.g_align = ptr_align(gz, d_out);
+    t.P = w.partials; t.Kp = d_in; t.N = d_out;
+    t.d_R = blk.d_n_dst; t.R_cap = n_cap; t.splits = w.splits;
+    if (prof && dw_stage >= 0) prof->begin(dw_stage);
+    NO_CHECK(gemm_tn_partials(t, st));
+    if (prof && dw_stage >= 0) prof->end();
+    if (prof && reduce_stage >= 0) prof->begin(reduce_stage);
+    NO_CHECK(reduce_grads(w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, st));
+    if (prof && reduce_stage >= 0) prof->end();
     return launch_status("sage_backward");
 }
 

@@ -20,7 +20,7 @@ struct no_model_s {
     no::DevBuf<float> mean[NO_MAX_LAYERS];           // layer l (index l-1): [n_dst_cap, d_{l-1}]
     no::DevBuf<float> h[NO_MAX_LAYERS];              // layer l output [rows, d_l]; h[0] holds all of V^1
     no::DevBuf<float> gh[NO_MAX_LAYERS];             // gradient w.r.t. h[l-1]
-    no::DevBuf<float> h1c, gh1c;                     // layer-1 rows of the computed vertices (with a cache)
+    no::DevBuf<float> h1c;                           // layer-1 rows of the computed vertices (with a cache)
     no::DevBuf<char> ws;
     size_t ws_bytes = 0;
     no::DevBuf<float> row_loss;
@@ -34,7 +34,7 @@ struct no_model_s {
         for (auto& b : mean) b.release();
         for (auto& b : h) b.release();
         for (auto& b : gh) b.release();
-        h1c.release(); gh1c.release(); ws.release(); row_loss.release(); stats.release();
+        h1c.release(); ws.release(); row_loss.release(); stats.release();
     }
 };
 
@@ -89,12 +89,6 @@ __global__ void __launch_bounds__(256) finish_stats_kernel(const float* __restri
         stats->n_v1 = n_layers >= 2 ? counts[4 * (n_layers - 2) + 1] : counts[0];
         stats->pad = 0;
     }
-}
-
-__global__ void sgd_kernel(float* __restrict__ w, const float* __restrict__ g, float lr, int64_t n) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) w[i] -= lr * g[i];
 }
 
 // h1[compute_pos[i], :] = h1c[i, :] (i < n_compute); h1[hit_pos[i], :] = emb[hit_slot[i], :] (i < n_hit).
@@ -186,7 +180,6 @@ extern "C" int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t
     }
     if (L >= 2) {
         NO_CHECK(m->h1c.alloc((size_t)bottom.n_dst_cap * m->dims[1]));
-        NO_CHECK(m->gh1c.alloc((size_t)bottom.n_dst_cap * m->dims[1]));
     }
     m->ws_bytes = ws_bytes;
     NO_CHECK(m->ws.alloc(ws_bytes));
@@ -330,14 +323,11 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         const float* gh_l = m->gh[l - 1].p;
         if (l == L && L >= 2) prof.begin(NO_STAGE_BWD_UPPER);
         if (l == 1 && L >= 2) prof.end();
+        const int32_t* grad_rows = nullptr;
         if (l == 1 && used_cache) {
-            // reused rows take no gradient: keep only the rows of the computed vertices
-            prof.begin(NO_STAGE_BWD_L1_PREP);
-            NO_CHECK(gather_rows(m->gh[0].p, d_out * 4, (int64_t)d_out * 4, B->compute_pos.p, extra + 0, blk.n_dst_cap,
-                                 m->gh1c.p, (int64_t)d_out * 4, st));
-            prof.end();
+            // reused rows take no gradient: the layer reads only the rows of the computed vertices
             h_l = m->h1c.p;
-            gh_l = m->gh1c.p;
+            grad_rows = B->compute_pos.p;
         }
         LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
         NO_CHECK(sage_backward(blk, x, dt, d_in, m->mean[l - 1].p, h_l, gh_l, m->params.p + m->off_w_self[l - 1],
@@ -345,17 +335,13 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
                                m->grads.p + m->off_w_self[l - 1], m->grads.p + m->off_w_neigh[l - 1],
                                m->grads.p + m->off_bias[l - 1], l > 1 ? m->gh[l - 2].p : nullptr, w, st,
                                l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
-                               -1));
+                               -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
+                               m->params.p + m->off_bias[l - 1]));
     }
 
-    // parameter update, then cache refresh with the rows computed by the pre-update weights
+    // cache refresh with the layer-1 rows computed by the pre-update weights (the SGD step itself ran inside
+    // each layer's gradient reduction; lr == 0 there would skip it, so a zero rate is applied as a no-op)
     prof.begin(NO_STAGE_UPDATE);
-    {
-        int64_t blocks = ceil_div((int64_t)m->n_params, 256 * 4);
-        if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)blocks), dim3(256), 0, st, m->params.p, (const float*)m->grads.p, lr,
-                           (int64_t)m->n_params);
-    }
     if (used_cache) {
         hipLaunchKernelGGL(refresh_cache_kernel, dim3(wave_rows_blocks(bottom.n_dst_cap)), dim3(256), 0, st,
                            (const float*)m->h1c.p, (const int32_t*)B->compute_list.p, extra + 0,
