@@ -304,21 +304,32 @@ def mean_aggregate_adjoint(grad_mean: np.ndarray, indptr: np.ndarray, indices: n
     return out
 
 
-def sage_layer_fwd(blk: Block, x_src: np.ndarray, w_self, w_neigh, bias, relu: bool):
-    """Eq. 1 (mean over the sampled row) then Eq. 2 (dense update). Returns (mean, h)."""
+def sage_layer_fwd_z(blk: Block, x_src: np.ndarray, w_self, w_neigh, bias, relu: bool):
+    """Eq. 1 (mean over the sampled row) then Eq. 2 (dense update). Returns (mean, z, h), z = pre-activation."""
     x = np.asarray(x_src, dtype=np.float64)
     mean = mean_aggregate(x, blk.indptr, blk.indices, blk.n_dst)
     z = x[: blk.n_dst] @ np.asarray(w_self, np.float64) + mean @ np.asarray(w_neigh, np.float64) \
         + np.asarray(bias, np.float64)
     h = np.maximum(z, 0.0) if relu else z
+    return mean, z, h
+
+
+def sage_layer_fwd(blk: Block, x_src: np.ndarray, w_self, w_neigh, bias, relu: bool):
+    """Returns (mean, h) of one layer."""
+    mean, _, h = sage_layer_fwd_z(blk, x_src, w_self, w_neigh, bias, relu)
     return mean, h
 
 
 def sage_layer_bwd(blk: Block, x_src: np.ndarray, mean: np.ndarray, h: np.ndarray, grad_h: np.ndarray,
-                   w_self, w_neigh, relu: bool, need_grad_x: bool):
-    """Gradients of one layer. grad_x is None for the bottom layer (nothing below it learns)."""
+                   w_self, w_neigh, relu: bool, need_grad_x: bool, active: Optional[np.ndarray] = None):
+    """Gradients of one layer. grad_x is None for the bottom layer (nothing below it learns).
+    `active` (bool, shape of h) overrides the ReLU decision h > 0: a caller may supply decisions taken
+    in another precision for pre-activations that are zero to within rounding, where either is valid."""
     x = np.asarray(x_src, dtype=np.float64)
-    gz = np.asarray(grad_h, np.float64) * (np.asarray(h) > 0) if relu else np.asarray(grad_h, np.float64)
+    if relu:
+        gz = np.asarray(grad_h, np.float64) * ((np.asarray(h) > 0) if active is None else active)
+    else:
+        gz = np.asarray(grad_h, np.float64)
     x_dst = x[: blk.n_dst]
     gw_self = x_dst.T @ gz
     gw_neigh = np.asarray(mean, np.float64).T @ gz
@@ -366,21 +377,24 @@ def _to_f64(x: np.ndarray, feat_is_bf16: bool) -> np.ndarray:
 
 def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray, fanouts: Sequence[int],
                weights, lr: float, seed: int, step: int, cache: Optional[Cache] = None,
-               feat_is_bf16: bool = False) -> StepResult:
-    """One pass of Algorithm 1's loop body with plain SGD; updates `cache` in place."""
+               feat_is_bf16: bool = False, relu_decisions=None) -> StepResult:
+    """One pass of Algorithm 1's loop body with plain SGD; updates `cache` in place.
+    relu_decisions: optional callable(layer, z_layer) -> bool array or None, consulted in the backward
+    pass for the ReLU decisions of layer `layer` given its pre-activations (rows of the computed vertices)."""
     L = len(fanouts)
     sb = sample_blocks(g, seeds, fanouts, seed, step, cache)
     bottom = sb.blocks[-1]
     x0 = gather_features(feat, bottom.src_global)
     x = _to_f64(x0, feat_is_bf16)
-    hs, means, xs = [], [], []
+    hs, means, xs, zs = [], [], [], []
     use_cache = cache is not None and L >= 2
     for l in range(1, L + 1):
         blk = sb.blocks[L - l]
         w_self, w_neigh, bias = weights[l - 1]
         xs.append(x)
-        mean, h = sage_layer_fwd(blk, x, w_self, w_neigh, bias, relu=(l < L))
+        mean, z, h = sage_layer_fwd_z(blk, x, w_self, w_neigh, bias, relu=(l < L))
         means.append(mean)
+        zs.append(z)
         if l == 1 and use_cache:
             n_v1 = len(sb.compute_pos) + len(sb.hit_pos)
             full = np.zeros((n_v1, h.shape[1]), dtype=np.float64)
@@ -400,8 +414,9 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
         if l == 1 and use_cache:
             h_l = h_l[sb.compute_pos]
             gh = gh[sb.compute_pos]        # reused rows take no gradient
+        active = relu_decisions(l, zs[l - 1]) if (relu_decisions is not None and l < L) else None
         gws, gwn, gb, gx = sage_layer_bwd(blk, xs[l - 1], means[l - 1], h_l, gh, w_self, w_neigh,
-                                          relu=(l < L), need_grad_x=(l > 1))
+                                          relu=(l < L), need_grad_x=(l > 1), active=active)
         grads[l - 1] = (gws, gwn, gb)
         gh = gx
     new_w = [(np.asarray(w[0], np.float64) - lr * gr[0], np.asarray(w[1], np.float64) - lr * gr[1],

@@ -44,11 +44,23 @@ struct no_blocks_s {
     no::DevBuf<int32_t> tmp_a;          // unordered transpose fill [max nnz_cap with a transpose]
     no::DevBuf<char> ws;                // tile sums of the scans
     // bottom hop with a cache
-    no::DevBuf<int32_t> compute_list, compute_pos, hit_pos, hit_slot;
+    no::DevBuf<int32_t> compute_list, compute_pos, hit_pos, hit_slot, probe_slot;
     bool last_used_cache = false;
+    // The transposes and the final wipe of the id map do not feed the forward pass: they run on a side
+    // stream (same priority) and are joined where their results are first needed.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork[NO_MAX_LAYERS] = {nullptr};
+    hipEvent_t ev_side_done = nullptr;
+    bool side_pending = false;
+    no::DevBuf<char> ws_side;
     void release() {
+        if (side) { (void)hipStreamSynchronize(side); (void)hipStreamDestroy(side); side = nullptr; }
+        for (auto& e : ev_fork) if (e) { (void)hipEventDestroy(e); e = nullptr; }
+        if (ev_side_done) { (void)hipEventDestroy(ev_side_done); ev_side_done = nullptr; }
+        ws_side.release();
         for (auto& h : hop) h.release();
         counts.release(); seeds.release(); map.release(); tmp_a.release(); ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();
+        probe_slot.release();
     }
 };
 
@@ -64,9 +76,12 @@ struct no_cache_s {
 
 namespace no {
 // Internal entry used by no_sample_blocks and no_select_hot.
+// With join == false the caller must call blocks_join(b, st) before anything on `st` reads a transpose
+// or starts another sampling call on the same blocks.
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key,
                            uint32_t domain, int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b,
-                           hipStream_t st);
+                           hipStream_t st, bool join = true);
+int32_t blocks_join(no_blocks_s* b, hipStream_t st);
 int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fanouts, int32_t n_layers,
                            bool build_csc, no_blocks_s** out);
 void fill_block_view(const no_blocks_s* b, int32_t hop, no_block_view* v);

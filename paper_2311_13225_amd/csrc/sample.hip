@@ -238,8 +238,16 @@ __global__ void csc_rank_kernel(const int32_t* d_nnz, const int32_t* __restrict_
     const int32_t u = indices[e];
     const int32_t b = csc_indptr[u], len = csc_indptr[u + 1] - b;
     int32_t r = 0;
-    if (len > 1)
-        for (int32_t t = 0; t < len; ++t) r += unordered[b + t] < e ? 1 : 0;
+    if (len > 1) {
+        const int32_t* col = unordered + b;
+        int32_t t = 0;
+        for (; t + 8 <= len; t += 8) {       // independent loads: eight compares in flight
+            const int32_t x0 = col[t], x1 = col[t + 1], x2 = col[t + 2], x3 = col[t + 3];
+            const int32_t x4 = col[t + 4], x5 = col[t + 5], x6 = col[t + 6], x7 = col[t + 7];
+            r += (x0 < e) + (x1 < e) + (x2 < e) + (x3 < e) + (x4 < e) + (x5 < e) + (x6 < e) + (x7 < e);
+        }
+        for (; t < len; ++t) r += col[t] < e ? 1 : 0;
+    }
     csc_eid[b + r] = e;
     csc_dst[b + r] = edge_row[e];
 }
@@ -268,7 +276,8 @@ struct CacheProbe {
     }
 };
 
-__global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe, const int32_t* d_n_v1, int64_t* tile_sums) {
+__global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe, const int32_t* d_n_v1, int64_t* tile_sums,
+                                                                int32_t* probe_slot /* [n]: slot if served from the cache, else -1 */) {
     const int64_t n = *d_n_v1;
     const int64_t base = (int64_t)blockIdx.x * ETILE;
     if (base >= n) return;
@@ -278,7 +287,11 @@ __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe
 #pragma unroll
     for (int t = 0; t < EITEMS; ++t) {
         int32_t slot;
-        if (i0 + t < n) s += probe(i0 + t, &slot);
+        if (i0 + t < n) {
+            const int64_t f = probe(i0 + t, &slot);
+            probe_slot[i0 + t] = (f & 1) ? -1 : slot;
+            s += f;
+        }
     }
     s = block_sum<int64_t, ETHREADS>(s, smem);
     if (threadIdx.x == 0) tile_sums[blockIdx.x] = s;
@@ -286,7 +299,8 @@ __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe
 
 // Stable split of V^1 into rows to compute and rows served from the cache; re-keys the id map for
 // the bottom hop (computed vertex -> its index in the compute list, reusable vertex -> no entry).
-__global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(CacheProbe probe, const int32_t* d_n_v1,
+__global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* __restrict__ v1, const int32_t* __restrict__ probe_slot,
+                                                                const int32_t* d_n_v1,
                                                                 const int64_t* __restrict__ tile_sums, int32_t* map,
                                                                 int32_t* compute_list, int32_t* compute_pos, int32_t* hit_pos,
                                                                 int32_t* hit_slot, int32_t* extra /* n_compute, n_hit, -, -, n_refresh */) {
@@ -319,7 +333,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(CacheProbe probe
     for (int t = 0; t < EITEMS; ++t) {
         c[t] = 0;
         slot[t] = -1;
-        if (i0 + t < n) c[t] = (int32_t)(probe(i0 + t, &slot[t]) & 1);
+        if (i0 + t < n) { slot[t] = probe_slot[i0 + t]; c[t] = slot[t] < 0 ? 1 : 0; }
         s += c[t];
     }
     int64_t total;
@@ -328,7 +342,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(CacheProbe probe
     for (int t = 0; t < EITEMS; ++t) {
         const int64_t i = i0 + t;
         if (i < n) {
-            const int32_t v = probe.v1[i];
+            const int32_t v = v1[i];
             if (c[t]) {
                 compute_pos[run] = (int32_t)i;
                 compute_list[run] = v;
@@ -384,18 +398,32 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
                        (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,
                        H.has_csc ? H.csc_cnt.p : nullptr);
     if (H.has_csc) {
-        NO_CHECK(exclusive_scan2(ArrayLoader{H.csc_cnt.p}, cnt + 1, H.n_src_cap, H.csc_indptr.p, nullptr, b->ws.p, st));
-        hipLaunchKernelGGL(csc_fill_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st, (const int32_t*)(cnt + 2),
+        // fork: the transpose only needs this hop's indices; the next hop proceeds on the main stream
+        hipStream_t sd = b->side;
+        NO_HIP_CHECK(hipEventRecord(b->ev_fork[h], st));
+        NO_HIP_CHECK(hipStreamWaitEvent(sd, b->ev_fork[h], 0));
+        NO_CHECK(exclusive_scan2(ArrayLoader{H.csc_cnt.p}, cnt + 1, H.n_src_cap, H.csc_indptr.p, nullptr, b->ws_side.p, sd));
+        hipLaunchKernelGGL(csc_fill_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd, (const int32_t*)(cnt + 2),
                            (const int32_t*)H.indices.p, (const int32_t*)H.csc_indptr.p, H.csc_cur.p, b->tmp_a.p);
-        hipLaunchKernelGGL(csc_rank_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st, (const int32_t*)(cnt + 2),
+        hipLaunchKernelGGL(csc_rank_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd, (const int32_t*)(cnt + 2),
                            (const int32_t*)H.indices.p, (const int32_t*)H.csc_indptr.p, (const int32_t*)b->tmp_a.p,
                            (const int32_t*)H.edge_row.p, H.csc_eid.p, H.csc_dst.p);
+        b->side_pending = true;
     }
     return launch_status("sample_hop");
 }
 
+int32_t blocks_join(no_blocks_s* b, hipStream_t st) {
+    if (!b->side_pending) return NO_OK;
+    NO_HIP_CHECK(hipEventRecord(b->ev_side_done, b->side));
+    NO_HIP_CHECK(hipStreamWaitEvent(st, b->ev_side_done, 0));
+    b->side_pending = false;
+    return NO_OK;
+}
+
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key, uint32_t domain,
-                           int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st) {
+                           int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st, bool join) {
+    NO_CHECK(blocks_join(b, st));      // a previous call that was never joined
     const int32_t L = b->n_layers;
     int32_t* extra = b->counts.p + 4 * L;     // n_compute, n_hit, -, -, n_refresh
     const uint32_t key0 = (uint32_t)stream_key, key1 = (uint32_t)(stream_key >> 32);
@@ -410,9 +438,10 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
             CacheProbe probe{d_dst, cache->slot_of_vertex.p, cache->version.p, step, cache->staleness};
             const unsigned tiles = (unsigned)edge_tiles(P.n_src_cap);
             int64_t* tile_sums = (int64_t*)b->ws.p;
-            hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, probe, d_n, tile_sums);
-            hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, probe, d_n,
-                               (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->hit_pos.p,
+            hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, probe, d_n, tile_sums,
+                               b->probe_slot.p);
+            hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, d_dst,
+                               (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->hit_pos.p,
                                b->hit_slot.p, extra);
             d_dst = b->compute_list.p;
             d_n = extra + 0;
@@ -424,11 +453,17 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
         d_dst = b->hop[h].src_global.p;
         d_n = b->counts.p + 4 * h + 1;
     }
-    const HopBuffers& last = b->hop[n_hops - 1];
-    hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, 256)), dim3(256), 0, st,
-                       (const int32_t*)last.src_global.p, d_n, b->map.p);
     if (!use_cache) hipLaunchKernelGGL(set_counts_kernel, dim3(1), dim3(1), 0, st, extra, 0, 0, 0);
-    return launch_status("sample_blocks");
+    // the id map is wiped on the side stream, after the last hop's lookups and behind the transposes
+    const HopBuffers& last = b->hop[n_hops - 1];
+    NO_HIP_CHECK(hipEventRecord(b->ev_fork[n_hops - 1], st));
+    NO_HIP_CHECK(hipStreamWaitEvent(b->side, b->ev_fork[n_hops - 1], 0));
+    hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, 256)), dim3(256), 0, b->side,
+                       (const int32_t*)last.src_global.p, d_n, b->map.p);
+    b->side_pending = true;
+    NO_CHECK(launch_status("sample_blocks"));
+    if (join) NO_CHECK(blocks_join(b, st));
+    return NO_OK;
 }
 
 int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fanouts, int32_t n_layers,
@@ -479,12 +514,17 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
     NO_CHECK(b->tmp_a.alloc((size_t)max_sort));
     const int64_t max_items = max_pad > max_src ? max_pad : max_src;
     NO_CHECK(b->ws.alloc((size_t)(edge_tiles(max_items + 1) + 2) * sizeof(int64_t)));
+    NO_CHECK(b->ws_side.alloc((size_t)(edge_tiles(max_items + 1) + 2) * sizeof(int64_t)));
+    NO_HIP_CHECK(hipStreamCreateWithFlags(&b->side, hipStreamNonBlocking));
+    for (int32_t h = 0; h < n_layers; ++h) NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_fork[h], hipEventDisableTiming));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_side_done, hipEventDisableTiming));
     if (n_layers >= 2) {
         size_t v1_cap = (size_t)b->hop[n_layers - 2].n_src_cap;
         NO_CHECK(b->compute_list.alloc(v1_cap));
         NO_CHECK(b->compute_pos.alloc(v1_cap));
         NO_CHECK(b->hit_pos.alloc(v1_cap));
         NO_CHECK(b->hit_slot.alloc(v1_cap));
+        NO_CHECK(b->probe_slot.alloc(v1_cap));
     }
     NO_HIP_CHECK(hipDeviceSynchronize());
     guard.b = nullptr;

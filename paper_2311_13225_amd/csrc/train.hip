@@ -264,7 +264,7 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
 
     // sample
     prof.begin(NO_STAGE_SAMPLE);
-    NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st));
+    NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false));
     prof.end();
     const bool used_cache = B->last_used_cache;
     m->last_used_cache = used_cache;
@@ -313,7 +313,8 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
                        (const int32_t*)B->counts.p, L, used_cache ? 1 : 0, stats);
     prof.end();
 
-    // backward
+    // backward (first joins the side stream: the transposes are needed from here on)
+    NO_CHECK(blocks_join(B, st));
     for (int32_t l = L; l >= 1; --l) {
         const no_block_view& blk = view[L - l];
         const int32_t d_in = m->dims[l - 1], d_out = m->dims[l];

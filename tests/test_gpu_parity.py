@@ -304,7 +304,8 @@ def test_sage_layer_empty_block_and_small_workspace():
 
 # --------------------------------------------------------------------------------------- whole step
 
-def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None, bits=32, presample=1):
+def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None, bits=32, presample=1,
+              n_train_presample=None):
     b = nb()
     V = V or w.n_vertices
     E = E or w.n_edges
@@ -321,8 +322,10 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
     frac = w.hot_fraction if hot_fraction is None else hot_fraction
     oc = gc = None
     if use_cache:
-        oc = ora.select_hot(og, train, w.batch, w.fanouts, presample, frac, w.staleness, w.hidden, w.seed)
-        gc = b.no_select_hot(gg, dev(train), w.batch, w.fanouts, presample, frac, w.staleness, w.hidden, w.seed)
+        # hotness may be pre-sampled on a prefix of the train ids to bound the oracle's cost at full size
+        pre = train if n_train_presample is None else train[:n_train_presample]
+        oc = ora.select_hot(og, pre, w.batch, w.fanouts, presample, frac, w.staleness, w.hidden, w.seed)
+        gc = b.no_select_hot(gg, dev(pre), w.batch, w.fanouts, presample, frac, w.staleness, w.hidden, w.seed)
         assert np.array_equal(b.no_cache_view(gc, V)["hot_ids"].cpu().numpy(), oc.hot_ids)
     tfeat = dev(feat.view(np.int16) if bf16 else feat)
     tlab = dev(lab)
@@ -332,7 +335,27 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
         seeds = si.batch_seeds(train, w.batch, step)
         print("step", step, flush=True)
         st = b.no_train_step(model, gg, tfeat, tlab, dev(seeds), gc, step, w.seed, lr)
-        r = ora.train_step(og, feat, lab, seeds, w.fanouts, ow, lr, w.seed, step, oc, feat_is_bf16=bf16)
+        ambiguous = []
+
+        def relu_decisions(layer, z_ora):
+            """The ReLU decision is a float deciding a bit. Where the oracle's pre-activation is zero to
+            within rounding (|z| <= 1e-5 max|z|) the decision the kernel took in fp32 is as valid as the
+            oracle's, so the oracle's backward uses the kernel's; everywhere else the two must agree exactly
+            (asserted here), so a wrong mask cannot hide behind this."""
+            blocks_ = b.no_model_blocks(model)
+            sizes_ = b.no_blocks_sizes(blocks_)
+            n_rows = st.n_v1 if (layer == 1 and w.n_layers >= 2) else z_ora.shape[0]
+            gh = b.no_model_activations(model, layer, n_rows, 1)[0].cpu().numpy()
+            if gh.shape[0] != z_ora.shape[0]:
+                gh = gh[b.block_arrays(blocks_, w.n_layers - 1, sizes_)["compute_pos"]]
+            tau = 1e-5 * max(np.abs(z_ora).max(), 1e-30)
+            assert (gh[z_ora > tau] > 0).all(), "layer %d: kernel masks a clearly positive pre-activation" % layer
+            assert (gh[z_ora < -tau] == 0).all(), "layer %d: kernel keeps a clearly negative pre-activation" % layer
+            ambiguous.append(int(((gh > 0) != (z_ora > 0)).sum()))
+            return gh > 0
+
+        r = ora.train_step(og, feat, lab, seeds, w.fanouts, ow, lr, w.seed, step, oc, feat_is_bf16=bf16,
+                           relu_decisions=relu_decisions)
         # integers: block sizes, blocks, hits
         blocks = b.no_model_blocks(model)
         sizes = compare_blocks(b, blocks, r.batch, with_cache=use_cache and w.n_layers >= 2 and oc.n_hot > 0)
