@@ -18,6 +18,8 @@ namespace no {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 32;
+constexpr int PIPE_DEPTH_NN = 2;   // register stages of the interior pipeline (forward / input-gradient products)
+constexpr int PIPE_DEPTH_TN = 1;   // the weight-gradient product is register-bound at 128x128: one stage
 constexpr int PITCH_KC = 36;
 
 template <bool KC, int BX> struct TileShape {
@@ -32,11 +34,11 @@ __device__ __forceinline__ float4 load4_fast(const float* p) {
     return make_float4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ float4 load4_guarded(const float* p, int valid) {
+    if (valid >= 4) return load4_fast(p);      // only the lanes that straddle an edge go element by element
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (valid > 0) v.x = p[0];
     if (valid > 1) v.y = p[1];
     if (valid > 2) v.z = p[2];
-    if (valid > 3) v.w = p[3];
     return v;
 }
 
@@ -138,6 +140,84 @@ __device__ __forceinline__ void acc_zero(floatx16 (&acc)[MI][NI]) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 }
 
+// One reduction sweep of a block tile: steps [0, n_steps) of 32 indices starting at k_begin; the first
+// n_fast steps touch only in-range elements. Interior steps run as a software pipeline with D register
+// stages, so the 16-byte global loads of step s+D are in flight while step s is multiplied (with only
+// 2-3 blocks per compute unit a single stage cannot cover the memory latency); the remaining steps
+// (ragged tail, edge tiles) use the guarded single-stage loop.
+template <bool A_KC, bool B_KC, int BM, int BN, int D>
+__device__ __forceinline__ void run_k_loop(const float* A, int64_t lda, int am0, int a_lim, const float* B, int64_t ldb,
+                                           int bn0, int b_lim, int k_begin, int k_lim, int n_steps, int n_fast,
+                                           int ones_col, float* As, float* Bs, floatx16 (&acc)[BM / 64][BN / 64], int wm,
+                                           int wn) {
+    int s = 0;
+    if (n_fast >= D) {
+        float4 ra[D][BM / 32], rb[D][BN / 32];
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            tile_fetch<A_KC, BM, true>(ra[d], A, lda, am0, a_lim, k_begin + d * BK, k_lim);
+            tile_fetch<B_KC, BN, true>(rb[d], B, ldb, bn0, b_lim, k_begin + d * BK, k_lim);
+        }
+        while (s + 2 * D <= n_fast) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                __syncthreads();
+                tile_store<A_KC, BM>(ra[d], As);
+                tile_store<B_KC, BN>(rb[d], Bs);
+                __syncthreads();
+                tile_fetch<A_KC, BM, true>(ra[d], A, lda, am0, a_lim, k_begin + (s + d + D) * BK, k_lim);
+                tile_fetch<B_KC, BN, true>(rb[d], B, ldb, bn0, b_lim, k_begin + (s + d + D) * BK, k_lim);
+                tile_mma<A_KC, B_KC, BM, BN>(As, Bs, acc, wm, wn);
+            }
+            s += D;
+        }
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            __syncthreads();
+            tile_store<A_KC, BM>(ra[d], As);
+            tile_store<B_KC, BN>(rb[d], Bs);
+            __syncthreads();
+            tile_mma<A_KC, B_KC, BM, BN>(As, Bs, acc, wm, wn);
+        }
+        s += D;
+    }
+    if (s >= n_steps) return;
+    float4 ra[BM / 32], rb[BN / 32];
+    if (s < n_fast) {
+        tile_fetch<A_KC, BM, true>(ra, A, lda, am0, a_lim, k_begin + s * BK, k_lim);
+        tile_fetch<B_KC, BN, true>(rb, B, ldb, bn0, b_lim, k_begin + s * BK, k_lim);
+    } else {
+        tile_fetch<A_KC, BM, false>(ra, A, lda, am0, a_lim, k_begin + s * BK, k_lim, ones_col);
+        tile_fetch<B_KC, BN, false>(rb, B, ldb, bn0, b_lim, k_begin + s * BK, k_lim);
+    }
+    for (; s < n_steps; ++s) {
+        __syncthreads();
+        tile_store<A_KC, BM>(ra, As);
+        tile_store<B_KC, BN>(rb, Bs);
+        __syncthreads();
+        const int kn = k_begin + (s + 1) * BK;
+        if (s + 1 < n_fast) {
+            tile_fetch<A_KC, BM, true>(ra, A, lda, am0, a_lim, kn, k_lim);
+            tile_fetch<B_KC, BN, true>(rb, B, ldb, bn0, b_lim, kn, k_lim);
+        } else if (s + 1 < n_steps) {
+            tile_fetch<A_KC, BM, false>(ra, A, lda, am0, a_lim, kn, k_lim, ones_col);
+            tile_fetch<B_KC, BN, false>(rb, B, ldb, bn0, b_lim, kn, k_lim);
+        }
+        tile_mma<A_KC, B_KC, BM, BN>(As, Bs, acc, wm, wn);
+    }
+}
+
+// Workgroups are handed to the 8 accelerator dies (XCDs, each with its own L2) round-robin by linear
+// id. The tiles that share an operand panel (all column tiles of one row tile; all tiles of one
+// reduction slice) get consecutive *logical* ids, and logical ids are dealt out in chunks per XCD, so
+// a panel is fetched into one L2 once instead of into several.
+constexpr int N_XCD = 8;
+__device__ __forceinline__ int64_t xcd_logical_id(int64_t total_padded) {
+    const int64_t id = blockIdx.x;
+    return (id % N_XCD) * (total_padded / N_XCD) + id / N_XCD;
+}
+static inline unsigned xcd_padded(int64_t total) { return (unsigned)(ceil_div(total, N_XCD) * N_XCD); }
+
 // ------------------------------------------------------------------------------------------ NN
 
 template <bool B_KC, int BM, int BN>
@@ -147,9 +227,16 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
     __shared__ __attribute__((aligned(16))) float Bs[TileShape<B_KC, BN>::FLOATS];
     int M = *g.d_M;
     if (M > g.M_cap) M = g.M_cap;
-    const int m0 = (int)blockIdx.y * BM, n0 = (int)blockIdx.x * BN;
+    // the grid covers the row capacity; only the tiles of the actual M rows are dealt out to the XCDs
+    const int gx = (g.N + BN - 1) / BN, gy = (M + BM - 1) / BM, gz = g.accumulate ? 1 : g.n_problems;
+    const int64_t total = (int64_t)gx * gy * gz;
+    if ((int64_t)blockIdx.x >= (total + N_XCD - 1) / N_XCD * N_XCD) return;
+    const int64_t lid = xcd_logical_id((total + N_XCD - 1) / N_XCD * N_XCD);
+    if (lid >= total) return;
+    const int bx = (int)(lid % gx), by = (int)((lid / gx) % gy), bz = (int)(lid / ((int64_t)gx * gy));
+    const int m0 = by * BM, n0 = bx * BN;
     if (m0 >= M) return;
-    const int prob = g.accumulate ? 0 : (int)blockIdx.z;
+    const int prob = g.accumulate ? 0 : bz;
     const int n_phases = g.accumulate ? g.n_problems : 1;
     const int wave = (int)(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
     floatx16 acc[MI][NI];
@@ -164,29 +251,7 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
         const bool full_x = (m0 + BM <= M) && (n0 + BN <= g.N);
         const int n_steps = (K + BK - 1) / BK;
         const int n_fast = full_x ? K / BK : 0;          // steps whose tiles need no guards
-        float4 ra[BM / 32], rb[BN / 32];
-        if (n_fast > 0) {
-            tile_fetch<true, BM, true>(ra, A, lda, m0, M, 0, K);
-            tile_fetch<B_KC, BN, true>(rb, B, ldb, n0, g.N, 0, K);
-        } else {
-            tile_fetch<true, BM, false>(ra, A, lda, m0, M, 0, K);
-            tile_fetch<B_KC, BN, false>(rb, B, ldb, n0, g.N, 0, K);
-        }
-        for (int s = 0; s < n_steps; ++s) {
-            __syncthreads();
-            tile_store<true, BM>(ra, As);
-            tile_store<B_KC, BN>(rb, Bs);
-            __syncthreads();
-            const int kn = (s + 1) * BK;
-            if (s + 1 < n_fast) {
-                tile_fetch<true, BM, true>(ra, A, lda, m0, M, kn, K);
-                tile_fetch<B_KC, BN, true>(rb, B, ldb, n0, g.N, kn, K);
-            } else if (s + 1 < n_steps) {
-                tile_fetch<true, BM, false>(ra, A, lda, m0, M, kn, K);
-                tile_fetch<B_KC, BN, false>(rb, B, ldb, n0, g.N, kn, K);
-            }
-            tile_mma<true, B_KC, BM, BN>(As, Bs, acc, wm, wn);
-        }
+        run_k_loop<true, B_KC, BM, BN, PIPE_DEPTH_NN>(A, lda, m0, M, B, ldb, n0, g.N, 0, K, n_steps, n_fast, -1, As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
     float* C = g.C[prob];
@@ -233,8 +298,8 @@ static void pick_tile(int64_t rows_est, int64_t cols, int64_t batch, int* bm, in
 
 template <bool B_KC>
 static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st) {
-    const unsigned z = (unsigned)(a.accumulate ? 1 : a.n_problems);
-    dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.M_cap, bm), z);
+    const int64_t z = a.accumulate ? 1 : a.n_problems;
+    dim3 grid(xcd_padded(ceil_div(a.N, bn) * ceil_div(a.M_cap, bm) * z));
     if (bm == 128 && bn == 128) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 128, 128>), grid, dim3(256), 0, st, a);
     else if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), 0, st, a);
     else if (bm == 128 && bn == 64) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), 0, st, a);
@@ -259,12 +324,15 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
     __shared__ __attribute__((aligned(16))) float Bs[TileShape<false, BN>::FLOATS];
     int R = *g.d_R;
     if (R > g.R_cap) R = g.R_cap;
-    const int prob = (int)blockIdx.z / g.splits, split = (int)blockIdx.z % g.splits;
+    // plain 3-D grid: dealing the slices out per XCD measured slower here (the partial tiles are written
+    // once and the operand slices are small), so the tiles of a slice stay spread over the dies
+    const int bx = (int)blockIdx.x, by = (int)blockIdx.y, bz = (int)blockIdx.z;
+    const int prob = bz / g.splits, split = bz % g.splits;
     int chunk = (R + g.splits - 1) / g.splits;
     chunk = (chunk + BK - 1) / BK * BK;
     const int r0 = split * chunk;
     const int r1 = min(R, r0 + chunk);
-    const int m0 = (int)blockIdx.y * BM, n0 = (int)blockIdx.x * BN;
+    const int m0 = by * BM, n0 = bx * BN;
     const int wave = (int)(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
     floatx16 acc[MI][NI];
     acc_zero<MI, NI>(acc);
@@ -275,29 +343,8 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
         const bool full_x = (m0 + BM <= g.Kp) && (n0 + BN <= g.N);
         const int n_steps = (r1 - r0 + BK - 1) / BK;
         const int n_fast = full_x ? (r1 - r0) / BK : 0;
-        float4 ra[BM / 32], rb[BN / 32];
-        if (n_fast > 0) {
-            tile_fetch<false, BM, true>(ra, A, lda, m0, g.Kp, r0, r1);
-            tile_fetch<false, BN, true>(rb, g.G, g.ldg, n0, g.N, r0, r1);
-        } else {
-            tile_fetch<false, BM, false>(ra, A, lda, m0, g.Kp, r0, r1, ones_col);
-            tile_fetch<false, BN, false>(rb, g.G, g.ldg, n0, g.N, r0, r1);
-        }
-        for (int s = 0; s < n_steps; ++s) {
-            __syncthreads();
-            tile_store<false, BM>(ra, As);
-            tile_store<false, BN>(rb, Bs);
-            __syncthreads();
-            const int kn = r0 + (s + 1) * BK;
-            if (s + 1 < n_fast) {
-                tile_fetch<false, BM, true>(ra, A, lda, m0, g.Kp, kn, r1);
-                tile_fetch<false, BN, true>(rb, g.G, g.ldg, n0, g.N, kn, r1);
-            } else if (s + 1 < n_steps) {
-                tile_fetch<false, BM, false>(ra, A, lda, m0, g.Kp, kn, r1, ones_col);
-                tile_fetch<false, BN, false>(rb, g.G, g.ldg, n0, g.N, kn, r1);
-            }
-            tile_mma<false, false, BM, BN>(As, Bs, acc, wm, wn);
-        }
+        run_k_loop<false, false, BM, BN, PIPE_DEPTH_TN>(A, lda, m0, g.Kp, g.G, g.ldg, n0, g.N, r0, r1, n_steps, n_fast, ones_col,
+                                                     As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
     const int rows_out = g.Kp + 1;
