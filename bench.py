@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: auto, 0: skip)")
     ap.add_argument("--presample-epochs", type=int, default=3)
     ap.add_argument("--lr", type=float, default=0.01)
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="only run a plain copy of known size (1,000,000 rows x 1024 B through no_gather_features with "
+                         "ids 0..n-1): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported."
@@ -56,6 +59,17 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(3)
     b.lib()   # fail loudly if the HIP library is missing
+    if args.copy_reference:
+        rows, dim = 1_000_000, 256
+        t = torch.randn(rows, dim, device="cuda")
+        ids = torch.arange(rows, device="cuda", dtype=torch.int32)
+        out = torch.empty(rows, dim, device="cuda")
+        for _ in range(3):
+            b.no_gather_features(t, ids, out)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_reference": True, "launches": 3, "bytes_read_per_launch": rows * dim * 4 + rows * 4,
+                          "bytes_written_per_launch": rows * dim * 4}), flush=True)
+        return
     w = si.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -154,8 +168,17 @@ def main():
     }
     dominant = max(kern, key=lambda k: kern[k][4])
     bound, achieved, peak, unit, dur = kern[dominant]
+    # HBM bytes per launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by the copy reference),
+    # recorded in profiles/dense_hbm_traffic.json for this workload; null for other workloads or kernels
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "dense_hbm_traffic.json")
+    if args.workload == "dense" and cache is not None and os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("bytes_per_launch", {}).get(dominant)
+        except Exception:
+            traffic = None
     roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": None, "avg_launch_ms": round(dur, 4),
+                "frac": round(achieved / peak, 4), "traffic": traffic, "avg_launch_ms": round(dur, 4),
                 "all": {k: {"bound": v[0], "achieved": round(v[1], 3), "peak": v[2], "unit": v[3],
                             "frac": round(v[1] / v[2], 4), "avg_launch_ms": round(v[4], 4)} for k, v in kern.items()}}
     extra = {

@@ -211,8 +211,8 @@ int32_t no_model_gathered(no_model_t m, const void** d_x0);   /* gathered input 
 /* One training step at parameter version `step` (= number of updates already applied):
  * sample (with hot skipping if cache != NULL), gather the bottom sources' features, forward
  * (layer-1 rows of reusable hot vertices come from the cache), mean softmax cross-entropy on the
- * seeds, backward (reused rows take no gradient), W <- W - lr * grad for every tensor, then every
- * computed hot vertex's layer-1 row is stored in the cache with version = step.
+ * seeds, backward (reused rows take no gradient), W <- W - lr * grad for every tensor; every computed
+ * hot vertex's layer-1 row (made by the pre-update weights) is stored in the cache with version = step.
  * d_stats (device, may be NULL) receives the statistics; if h_stats != NULL the stream is
  * synchronised and the statistics are copied to the host. */
 int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
@@ -230,13 +230,13 @@ enum {
     NO_STAGE_GATHER = 1,      /* feature rows of the bottom hop's sources */
     NO_STAGE_AGG_L1 = 2,      /* layer-1 mean aggregation kernel */
     NO_STAGE_GEMM_FWD_L1 = 3, /* layer-1 dense update kernel */
-    NO_STAGE_FWD_UPPER = 4,   /* cache row assembly + layers 2..L forward */
+    NO_STAGE_FWD_UPPER = 4,   /* cache row assembly and refresh + layers 2..L forward */
     NO_STAGE_LOSS = 5,
     NO_STAGE_BWD_UPPER = 6,   /* layers L..2 backward */
     NO_STAGE_BWD_L1_PREP = 7, /* gradient row selection, ReLU mask */
     NO_STAGE_GEMM_DW_L1 = 8,  /* layer-1 weight-gradient kernel (split partial products) */
     NO_STAGE_BWD_L1_REDUCE = 9,
-    NO_STAGE_UPDATE = 10,     /* SGD + cache refresh */
+    NO_STAGE_UPDATE = 10,     /* unused: the SGD step is fused into the gradient reductions */
     NO_STAGE_COUNT = 11
 };
 int32_t no_model_profile(no_model_t m, int32_t enable);   /* enabling resets the accumulators */

@@ -65,7 +65,8 @@ __global__ void __launch_bounds__(256) softmax_xent_kernel(const float* __restri
     if (lane == 0) row_loss[row] = -(z[y] - mx - logf(s));
 }
 
-// One block: mean of the per-seed losses in a fixed order, and the size statistics of the step.
+// One block: mean of the per-seed losses in a fixed order, and the size statistics of the step. (A
+// "last block done" ticket inside the kernel above measured slower: 256 same-address atomics.)
 __global__ void __launch_bounds__(256) finish_stats_kernel(const float* __restrict__ row_loss, int32_t n, const int32_t* counts,
                                                            int32_t n_layers, int32_t used_cache, no_step_stats* stats) {
     __shared__ float sm[256];
@@ -91,38 +92,40 @@ __global__ void __launch_bounds__(256) finish_stats_kernel(const float* __restri
     }
 }
 
-// h1[compute_pos[i], :] = h1c[i, :] (i < n_compute); h1[hit_pos[i], :] = emb[hit_slot[i], :] (i < n_hit).
-// One wavefront per row; dim is a multiple of 1 (scalar path keeps any width valid).
-__global__ void __launch_bounds__(256) assemble_h1_kernel(const float* __restrict__ h1c, const float* __restrict__ emb,
+// Layer-1 rows of all of V^1, one wavefront per row:
+//   computed rows: h1[compute_pos[i], :] = h1c[i, :]; if the vertex is hot its slot is refreshed with this
+//                  row (made by the step's pre-update weights) and stamped version = step;
+//   reused rows:   h1[hit_pos[i], :] = emb[hit_slot[i], :].
+// A vertex is either computed or reused in a step, so refreshed and read slots never coincide.
+__global__ void __launch_bounds__(256) assemble_h1_kernel(const float* __restrict__ h1c, float* emb,
                                                           const int32_t* __restrict__ compute_pos,
+                                                          const int32_t* __restrict__ compute_ids,
                                                           const int32_t* __restrict__ hit_pos,
                                                           const int32_t* __restrict__ hit_slot, const int32_t* d_n_compute,
-                                                          const int32_t* d_n_hit, int32_t dim, float* __restrict__ h1) {
+                                                          const int32_t* d_n_hit, const int32_t* __restrict__ slot_of_vertex,
+                                                          int32_t* version, int32_t step, int32_t dim,
+                                                          float* __restrict__ h1) {
     const int32_t nc = *d_n_compute, nh = *d_n_hit;
     const int lane = (int)(threadIdx.x & 63);
     const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     if (row >= (int64_t)nc + nh) return;
-    const float* src;
-    float* dst;
-    if (row < nc) { src = h1c + row * dim; dst = h1 + (int64_t)compute_pos[row] * dim; }
-    else { const int64_t i = row - nc; src = emb + (int64_t)hit_slot[i] * dim; dst = h1 + (int64_t)hit_pos[i] * dim; }
-    for (int c = lane; c < dim; c += 64) dst[c] = src[c];
-}
-
-// Every computed vertex that is hot stores its fresh layer-1 row and stamps version = step.
-__global__ void __launch_bounds__(256) refresh_cache_kernel(const float* __restrict__ h1c, const int32_t* __restrict__ computed_ids,
-                                                            const int32_t* d_n_compute, const int32_t* __restrict__ slot_of_vertex,
-                                                            int32_t dim, int32_t step, float* __restrict__ emb,
-                                                            int32_t* __restrict__ version) {
-    const int lane = (int)(threadIdx.x & 63);
-    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (row >= *d_n_compute) return;
-    const int32_t slot = slot_of_vertex[computed_ids[row]];
-    if (slot < 0) return;
-    const float* src = h1c + row * dim;
-    float* dst = emb + (int64_t)slot * dim;
-    for (int c = lane; c < dim; c += 64) dst[c] = src[c];
-    if (lane == 0) version[slot] = step;
+    if (row < nc) {
+        const float* src = h1c + row * dim;
+        float* dst = h1 + (int64_t)compute_pos[row] * dim;
+        const int32_t slot = slot_of_vertex[compute_ids[row]];
+        float* keep = slot >= 0 ? emb + (int64_t)slot * dim : nullptr;
+        for (int c = lane; c < dim; c += 64) {
+            const float v = src[c];
+            dst[c] = v;
+            if (keep) keep[c] = v;
+        }
+        if (keep && lane == 0) version[slot] = step;
+    } else {
+        const int64_t i = row - nc;
+        const float* src = emb + (int64_t)hit_slot[i] * dim;
+        float* dst = h1 + (int64_t)hit_pos[i] * dim;
+        for (int c = lane; c < dim; c += 64) dst[c] = src[c];
+    }
 }
 
 static inline unsigned wave_rows_blocks(int64_t rows) { int64_t b = ceil_div(rows, 4); return (unsigned)(b < 1 ? 1 : b); }
@@ -297,8 +300,10 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         if (l == 1 && used_cache) {
             prof.begin(NO_STAGE_FWD_UPPER);
             hipLaunchKernelGGL(assemble_h1_kernel, dim3(wave_rows_blocks(blk.n_dst_cap)), dim3(256), 0, st,
-                               (const float*)m->h1c.p, (const float*)cache->emb.p, (const int32_t*)B->compute_pos.p,
-                               (const int32_t*)B->hit_pos.p, (const int32_t*)B->hit_slot.p, extra + 0, extra + 1, d_out,
+                               (const float*)m->h1c.p, cache->emb.p, (const int32_t*)B->compute_pos.p,
+                               (const int32_t*)B->compute_list.p, (const int32_t*)B->hit_pos.p,
+                               (const int32_t*)B->hit_slot.p, extra + 0, extra + 1,
+                               (const int32_t*)cache->slot_of_vertex.p, cache->version.p, (int32_t)step, d_out,
                                m->h[0].p);
             prof.end();
         }
@@ -340,16 +345,8 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
                                m->params.p + m->off_bias[l - 1]));
     }
 
-    // cache refresh with the layer-1 rows computed by the pre-update weights (the SGD step itself ran inside
-    // each layer's gradient reduction; lr == 0 there would skip it, so a zero rate is applied as a no-op)
-    prof.begin(NO_STAGE_UPDATE);
-    if (used_cache) {
-        hipLaunchKernelGGL(refresh_cache_kernel, dim3(wave_rows_blocks(bottom.n_dst_cap)), dim3(256), 0, st,
-                           (const float*)m->h1c.p, (const int32_t*)B->compute_list.p, extra + 0,
-                           (const int32_t*)cache->slot_of_vertex.p, m->dims[1], (int32_t)step, cache->emb.p,
-                           cache->version.p);
-    }
-    prof.end();
+    // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;
+    //  the cache was refreshed during the forward pass with rows made by the pre-update weights)
     NO_CHECK(launch_status("train_step"));
     if (prof.enabled) {
         NO_HIP_CHECK(hipStreamSynchronize(st));
