@@ -18,8 +18,6 @@ namespace no {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 32;
-constexpr int PIPE_DEPTH_NN = 2;   // register stages of the interior pipeline (forward / input-gradient products)
-constexpr int PIPE_DEPTH_TN = 1;   // the weight-gradient product is register-bound at 128x128: one stage
 constexpr int PITCH_KC = 36;
 
 template <bool KC, int BX> struct TileShape {
@@ -103,9 +101,15 @@ __device__ __forceinline__ float4 tile_frag(const float* S, int x, int chunk, in
     return make_float4(p[0], p[BX], p[2 * BX], p[3 * BX]);
 }
 
+// Number of independent accumulator sets per wave tile: with a single 32x32 accumulator every MFMA would
+// depend on the one before it, so small wave tiles keep two sets (even / odd chunks of 8 indices) that
+// are summed in the epilogue; larger tiles already interleave 2-4 accumulators.
+template <int BM, int BN> struct AccSets { static constexpr int N = ((BM / 64) * (BN / 64) >= 4) ? 1 : 2; };
+
 template <bool A_KC, bool B_KC, int BM, int BN>
-__device__ __forceinline__ void tile_mma(const float* As, const float* Bs, floatx16 (&acc)[BM / 64][BN / 64], int wm, int wn) {
-    constexpr int MI = BM / 64, NI = BN / 64;
+__device__ __forceinline__ void tile_mma(const float* As, const float* Bs,
+                                         floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
+    constexpr int MI = BM / 64, NI = BN / 64, SETS = AccSets<BM, BN>::N;
     const int lane = (int)(threadIdx.x & 63);
     const int half = lane >> 5, l32 = lane & 31;
 #pragma unroll
@@ -115,95 +119,94 @@ __device__ __forceinline__ void tile_mma(const float* As, const float* Bs, float
         for (int i = 0; i < MI; ++i) a[i] = tile_frag<A_KC, BM>(As, wm * (BM / 2) + i * 32 + l32, chunk, half);
 #pragma unroll
         for (int i = 0; i < NI; ++i) b[i] = tile_frag<B_KC, BN>(Bs, wn * (BN / 2) + i * 32 + l32, chunk, half);
+        constexpr int dummy = 0;
+        (void)dummy;
+        const int set = chunk % SETS;
+        // index-major order: consecutive MFMAs go to different accumulators
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+        for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].x, b[ni].x, acc[mi][ni], 0, 0, 0);
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].y, b[ni].y, acc[mi][ni], 0, 0, 0);
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].z, b[ni].z, acc[mi][ni], 0, 0, 0);
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi].w, b[ni].w, acc[mi][ni], 0, 0, 0);
-            }
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const float av = kk == 0 ? a[mi].x : kk == 1 ? a[mi].y : kk == 2 ? a[mi].z : a[mi].w;
+                    const float bv = kk == 0 ? b[ni].x : kk == 1 ? b[ni].y : kk == 2 ? b[ni].z : b[ni].w;
+                    acc[set][mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[set][mi][ni], 0, 0, 0);
+                }
     }
 }
 
 // Accumulator element r of lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32 of the 32x32 tile.
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
-template <int MI, int NI>
-__device__ __forceinline__ void acc_zero(floatx16 (&acc)[MI][NI]) {
+template <int SETS, int MI, int NI>
+__device__ __forceinline__ void acc_zero(floatx16 (&acc)[SETS][MI][NI]) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int s = 0; s < SETS; ++s)
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[s][i][j][r] = 0.f;
 }
 
-// One reduction sweep of a block tile: steps [0, n_steps) of 32 indices starting at k_begin; the first
-// n_fast steps touch only in-range elements. Interior steps run as a software pipeline with D register
-// stages, so the 16-byte global loads of step s+D are in flight while step s is multiplied (with only
-// 2-3 blocks per compute unit a single stage cannot cover the memory latency); the remaining steps
-// (ragged tail, edge tiles) use the guarded single-stage loop.
-template <bool A_KC, bool B_KC, int BM, int BN, int D>
-__device__ __forceinline__ void run_k_loop(const float* A, int64_t lda, int am0, int a_lim, const float* B, int64_t ldb,
-                                           int bn0, int b_lim, int k_begin, int k_lim, int n_steps, int n_fast,
-                                           int ones_col, float* As, float* Bs, floatx16 (&acc)[BM / 64][BN / 64], int wm,
-                                           int wn) {
-    int s = 0;
-    if (n_fast >= D) {
-        float4 ra[D][BM / 32], rb[D][BN / 32];
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            tile_fetch<A_KC, BM, true>(ra[d], A, lda, am0, a_lim, k_begin + d * BK, k_lim);
-            tile_fetch<B_KC, BN, true>(rb[d], B, ldb, bn0, b_lim, k_begin + d * BK, k_lim);
-        }
-        while (s + 2 * D <= n_fast) {
-#pragma unroll
-            for (int d = 0; d < D; ++d) {
-                __syncthreads();
-                tile_store<A_KC, BM>(ra[d], As);
-                tile_store<B_KC, BN>(rb[d], Bs);
-                __syncthreads();
-                tile_fetch<A_KC, BM, true>(ra[d], A, lda, am0, a_lim, k_begin + (s + d + D) * BK, k_lim);
-                tile_fetch<B_KC, BN, true>(rb[d], B, ldb, bn0, b_lim, k_begin + (s + d + D) * BK, k_lim);
-                tile_mma<A_KC, B_KC, BM, BN>(As, Bs, acc, wm, wn);
-            }
-            s += D;
-        }
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            __syncthreads();
-            tile_store<A_KC, BM>(ra[d], As);
-            tile_store<B_KC, BN>(rb[d], Bs);
-            __syncthreads();
-            tile_mma<A_KC, B_KC, BM, BN>(As, Bs, acc, wm, wn);
-        }
-        s += D;
-    }
-    if (s >= n_steps) return;
-    float4 ra[BM / 32], rb[BN / 32];
-    if (s < n_fast) {
-        tile_fetch<A_KC, BM, true>(ra, A, lda, am0, a_lim, k_begin + s * BK, k_lim);
-        tile_fetch<B_KC, BN, true>(rb, B, ldb, bn0, b_lim, k_begin + s * BK, k_lim);
+// Sum of the accumulator sets for element r of tile (mi, ni).
+template <int SETS, int MI, int NI>
+__device__ __forceinline__ float acc_get(const floatx16 (&acc)[SETS][MI][NI], int mi, int ni, int r) {
+    float v = acc[0][mi][ni][r];
+    if (SETS > 1) v += acc[SETS - 1][mi][ni][r];
+    return v;
+}
+
+// A block's reduction is a flat list of steps of 32 indices, possibly spanning two operand pairs
+// (phases). LDS holds two copies of the operand tiles: while step t is multiplied out of one copy, the
+// global loads of step t+1 (issued before the multiply) land in registers and are stored into the other
+// copy, so a step costs one barrier. Interior steps use unguarded 16-byte loads.
+struct StepSource {
+    const float* A; int64_t lda; const float* B; int64_t ldb;
+    int k_begin, k_lim;      // reduction range of this phase
+    int n_steps, n_fast;     // steps in this phase; the first n_fast need no guards
+    int ones_col;            // virtual column of ones in A (XC layout only), or -1
+};
+
+template <bool A_KC, bool B_KC, int BM, int BN>
+__device__ __forceinline__ void fetch_step(float4 (&ra)[BM / 32], float4 (&rb)[BN / 32], const StepSource& p0,
+                                           const StepSource& p1, int t, int am0, int a_lim, int bn0, int b_lim) {
+    const bool second = t >= p0.n_steps;
+    const StepSource& p = second ? p1 : p0;
+    const int s = second ? t - p0.n_steps : t;
+    const int k0 = p.k_begin + s * BK;
+    if (s < p.n_fast) {
+        tile_fetch<A_KC, BM, true>(ra, p.A, p.lda, am0, a_lim, k0, p.k_lim);
+        tile_fetch<B_KC, BN, true>(rb, p.B, p.ldb, bn0, b_lim, k0, p.k_lim);
     } else {
-        tile_fetch<A_KC, BM, false>(ra, A, lda, am0, a_lim, k_begin + s * BK, k_lim, ones_col);
-        tile_fetch<B_KC, BN, false>(rb, B, ldb, bn0, b_lim, k_begin + s * BK, k_lim);
+        tile_fetch<A_KC, BM, false>(ra, p.A, p.lda, am0, a_lim, k0, p.k_lim, p.ones_col);
+        tile_fetch<B_KC, BN, false>(rb, p.B, p.ldb, bn0, b_lim, k0, p.k_lim);
     }
-    for (; s < n_steps; ++s) {
-        __syncthreads();
-        tile_store<A_KC, BM>(ra, As);
-        tile_store<B_KC, BN>(rb, Bs);
-        __syncthreads();
-        const int kn = k_begin + (s + 1) * BK;
-        if (s + 1 < n_fast) {
-            tile_fetch<A_KC, BM, true>(ra, A, lda, am0, a_lim, kn, k_lim);
-            tile_fetch<B_KC, BN, true>(rb, B, ldb, bn0, b_lim, kn, k_lim);
-        } else if (s + 1 < n_steps) {
-            tile_fetch<A_KC, BM, false>(ra, A, lda, am0, a_lim, kn, k_lim, ones_col);
-            tile_fetch<B_KC, BN, false>(rb, B, ldb, bn0, b_lim, kn, k_lim);
+}
+
+template <bool A_KC, bool B_KC, int BM, int BN>
+__device__ __forceinline__ void run_steps(const StepSource& p0, const StepSource& p1, int total_steps, int am0, int a_lim,
+                                          int bn0, int b_lim, float* As, float* Bs,
+                                          floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
+    constexpr int A_FLOATS = TileShape<A_KC, BM>::FLOATS, B_FLOATS = TileShape<B_KC, BN>::FLOATS;
+    if (total_steps <= 0) return;
+    float4 ra[BM / 32], rb[BN / 32];
+    fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, 0, am0, a_lim, bn0, b_lim);
+    tile_store<A_KC, BM>(ra, As);
+    tile_store<B_KC, BN>(rb, Bs);
+    __syncthreads();
+    for (int t = 0; t < total_steps; ++t) {
+        const int cur = t & 1;
+        const bool more = t + 1 < total_steps;
+        if (more) fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, t + 1, am0, a_lim, bn0, b_lim);
+        tile_mma<A_KC, B_KC, BM, BN>(As + cur * A_FLOATS, Bs + cur * B_FLOATS, acc, wm, wn);
+        if (more) {
+            tile_store<A_KC, BM>(ra, As + (cur ^ 1) * A_FLOATS);
+            tile_store<B_KC, BN>(rb, Bs + (cur ^ 1) * B_FLOATS);
         }
-        tile_mma<A_KC, B_KC, BM, BN>(As, Bs, acc, wm, wn);
+        __syncthreads();
     }
 }
 
@@ -223,8 +226,8 @@ static inline unsigned xcd_padded(int64_t total) { return (unsigned)(ceil_div(to
 template <bool B_KC, int BM, int BN>
 __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
     constexpr int MI = BM / 64, NI = BN / 64;
-    __shared__ __attribute__((aligned(16))) float As[TileShape<true, BM>::FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[TileShape<B_KC, BN>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float As[2 * TileShape<true, BM>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float Bs[2 * TileShape<B_KC, BN>::FLOATS];
     int M = *g.d_M;
     if (M > g.M_cap) M = g.M_cap;
     // the grid covers the row capacity; only the tiles of the actual M rows are dealt out to the XCDs
@@ -239,19 +242,17 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
     const int prob = g.accumulate ? 0 : bz;
     const int n_phases = g.accumulate ? g.n_problems : 1;
     const int wave = (int)(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
-    floatx16 acc[MI][NI];
-    acc_zero<MI, NI>(acc);
-
-    for (int ph = 0; ph < n_phases; ++ph) {
-        const int q = g.accumulate ? ph : prob;
-        const float* A = g.A[q];
-        const float* B = g.B[q];
-        const int64_t lda = g.lda[q], ldb = g.ldb[q];
-        const int K = g.K[q];
+    constexpr int SETS = AccSets<BM, BN>::N;
+    floatx16 acc[SETS][MI][NI];
+    acc_zero<SETS, MI, NI>(acc);
+    {
         const bool full_x = (m0 + BM <= M) && (n0 + BN <= g.N);
-        const int n_steps = (K + BK - 1) / BK;
-        const int n_fast = full_x ? K / BK : 0;          // steps whose tiles need no guards
-        run_k_loop<true, B_KC, BM, BN, PIPE_DEPTH_NN>(A, lda, m0, M, B, ldb, n0, g.N, 0, K, n_steps, n_fast, -1, As, Bs, acc, wm, wn);
+        const int q0 = g.accumulate ? 0 : prob, q1 = g.accumulate && n_phases > 1 ? 1 : q0;
+        StepSource p0{g.A[q0], g.lda[q0], g.B[q0], g.ldb[q0], 0, g.K[q0], (g.K[q0] + BK - 1) / BK,
+                      full_x ? g.K[q0] / BK : 0, -1};
+        StepSource p1{g.A[q1], g.lda[q1], g.B[q1], g.ldb[q1], 0, g.K[q1], n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0,
+                      full_x ? g.K[q1] / BK : 0, -1};
+        run_steps<true, B_KC, BM, BN>(p0, p1, p0.n_steps + p1.n_steps, m0, M, n0, g.N, As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
     float* C = g.C[prob];
@@ -269,7 +270,7 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
             for (int ni = 0; ni < NI; ++ni) {
                 const int col = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
                 if (col >= g.N) continue;
-                float v = acc[mi][ni][r];
+                float v = acc_get<SETS, MI, NI>(acc, mi, ni, r);
                 if (g.bias) v += g.bias[col];
                 if (g.relu) v = v > 0.f ? v : 0.f;
                 C[(int64_t)row * ldc + col] = v * scale;
@@ -278,18 +279,19 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
 }
 
 // Largest tile that still gives the chip enough blocks, assuming about half the row capacity is used.
-static void pick_tile(int64_t rows_est, int64_t cols, int64_t batch, int* bm, int* bn) {
+static void pick_tile(int64_t rows_est, int64_t cols, int64_t batch, bool allow_128x128, int* bm, int* bn) {
     // NO_GEMM_TILE=<bm>x<bn> pins the tile shape (tuning aid; both values in {64, 128})
     static const char* forced = getenv("NO_GEMM_TILE");
     if (forced) {
         int fm = 0, fn = 0;
-        if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128)) {
+        if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128) &&
+            (allow_128x128 || fm + fn < 256)) {
             *bm = fm; *bn = fn;
             return;
         }
     }
     const int cand[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
-    for (int c = 0; c < 4; ++c) {
+    for (int c = allow_128x128 ? 0 : 1; c < 4; ++c) {
         if (cols <= 64 && cand[c][1] == 128) continue;
         const int64_t blocks = ceil_div(rows_est, cand[c][0]) * ceil_div(cols, cand[c][1]) * batch;
         if (blocks >= 512 || c == 3) { *bm = cand[c][0]; *bn = cand[c][1]; return; }
@@ -300,8 +302,7 @@ template <bool B_KC>
 static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st) {
     const int64_t z = a.accumulate ? 1 : a.n_problems;
     dim3 grid(xcd_padded(ceil_div(a.N, bn) * ceil_div(a.M_cap, bm) * z));
-    if (bm == 128 && bn == 128) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 128, 128>), grid, dim3(256), 0, st, a);
-    else if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), 0, st, a);
+    if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), 0, st, a);
     else if (bm == 128 && bn == 64) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 64, 64>), grid, dim3(256), 0, st, a);
 }
@@ -309,7 +310,8 @@ static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st) {
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st) {
     if (a.M_cap <= 0 || a.N <= 0) return NO_OK;
     int bm, bn;
-    pick_tile(a.M_est > 0 ? a.M_est : (a.M_cap + 1) / 2, a.N, a.accumulate ? 1 : a.n_problems, &bm, &bn);
+    // two LDS copies of a 128x128 tile pair in the padded layout exceed 64 KB: the forward product stops at 128x64
+    pick_tile(a.M_est > 0 ? a.M_est : (a.M_cap + 1) / 2, a.N, a.accumulate ? 1 : a.n_problems, false, &bm, &bn);
     if (b_transposed) launch_nn<true>(a, bm, bn, st);
     else launch_nn<false>(a, bm, bn, st);
     return launch_status("gemm_nn");
@@ -320,8 +322,8 @@ int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st) {
 template <int BM, int BN>
 __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
     constexpr int MI = BM / 64, NI = BN / 64;
-    __shared__ __attribute__((aligned(16))) float As[TileShape<false, BM>::FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[TileShape<false, BN>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float As[2 * TileShape<false, BM>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float Bs[2 * TileShape<false, BN>::FLOATS];
     int R = *g.d_R;
     if (R > g.R_cap) R = g.R_cap;
     // plain 3-D grid: dealing the slices out per XCD measured slower here (the partial tiles are written
@@ -334,17 +336,18 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
     const int r1 = min(R, r0 + chunk);
     const int m0 = by * BM, n0 = bx * BN;
     const int wave = (int)(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
-    floatx16 acc[MI][NI];
-    acc_zero<MI, NI>(acc);
+    constexpr int SETS = AccSets<BM, BN>::N;
+    floatx16 acc[SETS][MI][NI];
+    acc_zero<SETS, MI, NI>(acc);
     const float* A = g.A[prob];
     const int64_t lda = g.lda[prob];
     const int ones_col = prob == 0 ? g.Kp : -1;       // product 0 carries the column sums of G in row Kp
     if (r0 < r1) {
         const bool full_x = (m0 + BM <= g.Kp) && (n0 + BN <= g.N);
-        const int n_steps = (r1 - r0 + BK - 1) / BK;
-        const int n_fast = full_x ? (r1 - r0) / BK : 0;
-        run_k_loop<false, false, BM, BN, PIPE_DEPTH_TN>(A, lda, m0, g.Kp, g.G, g.ldg, n0, g.N, r0, r1, n_steps, n_fast, ones_col,
-                                                     As, Bs, acc, wm, wn);
+        StepSource p0{A, lda, g.G, g.ldg, r0, r1, (r1 - r0 + BK - 1) / BK, full_x ? (r1 - r0) / BK : 0, ones_col};
+        StepSource p1 = p0;
+        p1.n_steps = 0;
+        run_steps<false, false, BM, BN>(p0, p1, p0.n_steps, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
     const int rows_out = g.Kp + 1;
@@ -358,7 +361,7 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
                 const int col = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
-                if (col < g.N) P[(int64_t)row * g.N + col] = acc[mi][ni][r];
+                if (col < g.N) P[(int64_t)row * g.N + col] = acc_get<SETS, MI, NI>(acc, mi, ni, r);
             }
         }
 }
@@ -366,7 +369,7 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
 int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st) {
     if (a.Kp <= 0 || a.N <= 0) return NO_OK;
     int bm, bn;
-    pick_tile(a.Kp + 1, a.N, 2 * a.splits, &bm, &bn);
+    pick_tile(a.Kp + 1, a.N, 2 * a.splits, true, &bm, &bn);
     dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.Kp + 1, bm), (unsigned)(2 * a.splits));
     if (bm == 128 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<128, 128>), grid, dim3(256), 0, st, a);
     else if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<64, 128>), grid, dim3(256), 0, st, a);
