@@ -156,8 +156,9 @@ def main():
     n_v1 = mean([s.n_v1 for s in stats])
     loss_last = stats[-1].loss
     # algorithmic work per launch (units: one step's rows/edges as measured)
-    gather_bytes = n_src_bottom * (4 + 2 * F * es)
-    agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4     # compulsory traffic
+    # the step gathers the destination rows densely and reads the neighbour rows inside the aggregation
+    gather_bytes = n_dst_bottom * (4 + 2 * F * es)
+    agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4     # compulsory traffic (each row once)
     gemm_fwd_flops = 2.0 * n_dst_bottom * (2 * F) * w.dims[1]
     gemm_dw_flops = gemm_fwd_flops
     kern = {

@@ -206,10 +206,13 @@ int32_t no_model_grads(no_model_t m, int32_t layer, float** d_gw_self, float** d
  * d_mean fp32 [n_dst, dims[layer-1]]. */
 int32_t no_model_activations(no_model_t m, int32_t layer, const float** d_h, const float** d_mean);
 int32_t no_model_blocks(no_model_t m, no_blocks_t* blocks);   /* blocks of the last step (owned by m) */
-int32_t no_model_gathered(no_model_t m, const void** d_x0);   /* gathered input features of the last step */
+/* Gathered feature rows of the last step: the rows of the bottom hop's destinations [n_dst, F] (the
+ * neighbour rows are read from the table by the fused layer-1 aggregation and are not materialised). */
+int32_t no_model_gathered(no_model_t m, const void** d_x0);
 
 /* One training step at parameter version `step` (= number of updates already applied):
- * sample (with hot skipping if cache != NULL), gather the bottom sources' features, forward
+ * sample (with hot skipping if cache != NULL), gather the bottom hop's feature rows (destination rows
+ * densely, neighbour rows inside the layer-1 aggregation), forward
  * (layer-1 rows of reusable hot vertices come from the cache), mean softmax cross-entropy on the
  * seeds, backward (reused rows take no gradient), W <- W - lr * grad for every tensor; every computed
  * hot vertex's layer-1 row (made by the pre-update weights) is stored in the cache with version = step.

@@ -161,8 +161,8 @@ __device__ __forceinline__ float acc_get(const floatx16 (&acc)[SETS][MI][NI], in
 
 // A block's reduction is a flat list of steps of 32 indices, possibly spanning two operand pairs
 // (phases). LDS holds two copies of the operand tiles: while step t is multiplied out of one copy, the
-// global loads of step t+1 (issued before the multiply) land in registers and are stored into the other
-// copy, so a step costs one barrier. Interior steps use unguarded 16-byte loads.
+// global loads of later steps land in registers and are stored into the other copy, so a step costs one
+// barrier. Interior steps use unguarded 16-byte loads.
 struct StepSource {
     const float* A; int64_t lda; const float* B; int64_t ldb;
     int k_begin, k_lim;      // reduction range of this phase
@@ -192,6 +192,8 @@ __device__ __forceinline__ void run_steps(const StepSource& p0, const StepSource
                                           floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
     constexpr int A_FLOATS = TileShape<A_KC, BM>::FLOATS, B_FLOATS = TileShape<B_KC, BN>::FLOATS;
     if (total_steps <= 0) return;
+    // One register stage (a second one measured slower: the registers cost more occupancy than the
+    // longer load window gains).
     float4 ra[BM / 32], rb[BN / 32];
     fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, 0, am0, a_lim, bn0, b_lim);
     tile_store<A_KC, BM>(ra, As);

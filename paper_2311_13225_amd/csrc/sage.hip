@@ -5,6 +5,8 @@
 // order, no float atomics). The bottom layer needs only the saved mean and the new embedding.
 #include "layers.hpp"
 
+#include <stdlib.h>
+
 namespace no {
 
 // ------------------------------------------------------------------------ row segment reduce
@@ -189,7 +191,9 @@ static inline unsigned ew_blocks(int64_t total) {
 
 int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out) {
     const int64_t tiles = 2 * ceil_div(d_in, 128) * ceil_div(d_out, 128);
-    int64_t s = ceil_div(768, tiles);
+    static const char* env = getenv("NO_TN_BLOCKS");      // tuning aid: target number of blocks of the split product
+    const int64_t target = env ? atoi(env) : 768;
+    int64_t s = ceil_div(target > 0 ? target : 768, tiles);
     const int64_t by_rows = ceil_div(n_dst_cap, 256);
     if (s > by_rows) s = by_rows;
     if (s > 64) s = 64;
@@ -216,9 +220,13 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
-                     const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage) {
+                     const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
+                     const void* agg_table) {
+    // agg_table != NULL: the rows to average are rows of that table addressed by blk.d_indices (global ids),
+    // while x_src holds only the destination rows (fused gather + aggregate of the bottom layer)
     if (prof && agg_stage >= 0) prof->begin(agg_stage);
-    NO_CHECK(mean_aggregate(x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap, mean, st));
+    NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap,
+                            mean, st));
     if (prof && agg_stage >= 0) prof->end();
     const float* x_dst = (const float*)x_src;
     if (dt == NO_BF16) {

@@ -367,7 +367,7 @@ static inline int64_t edge_tiles(int64_t n_pad_cap) { int64_t t = ceil_div(n_pad
 template <typename RowT>
 static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b, int32_t h, const int32_t* d_dst,
                           const int32_t* d_n_dst_in, int32_t n_fixed, bool insert_dst, uint32_t key0, uint32_t key1,
-                          uint32_t domain, hipStream_t st) {
+                          uint32_t domain, hipStream_t st, bool last_hop) {
     HopBuffers& H = b->hop[h];
     int32_t* cnt = b->counts.p + 4 * h;              // n_dst, n_src, nnz
     const int32_t k = H.fanout;
@@ -394,6 +394,18 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     hipLaunchKernelGGL(edge_assign_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
                        (const int32_t*)cnt, k, k_magic, (const int64_t*)tile_sums, H.indptr.p, H.nbr_global.p, H.edge_row.p,
                        H.src_global.p, cnt);
+    if (last_hop) {
+        // Nothing downstream on the caller's stream needs the last hop's local indices before the join (the
+        // bottom layer aggregates through the global ids): they are filled on the side stream, ahead of the
+        // wipe of the id map that the caller queues there next.
+        NO_HIP_CHECK(hipEventRecord(b->ev_fork[h], st));
+        NO_HIP_CHECK(hipStreamWaitEvent(b->side, b->ev_fork[h], 0));
+        hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, b->side,
+                           (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,
+                           (int32_t*)nullptr);
+        b->side_pending = true;
+        return launch_status("sample_hop");
+    }
     hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st, (const int32_t*)(cnt + 2),
                        (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,
                        H.has_csc ? H.csc_cnt.p : nullptr);
@@ -447,17 +459,17 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
             d_n = extra + 0;
         }
         if (g->rowptr_bits == 64)
-            NO_CHECK(sample_hop<int64_t>(g->rowptr64.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st));
+            NO_CHECK(sample_hop<int64_t>(g->rowptr64.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st,
+                                         h == n_hops - 1));
         else
-            NO_CHECK(sample_hop<int32_t>(g->rowptr32.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st));
+            NO_CHECK(sample_hop<int32_t>(g->rowptr32.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st,
+                                         h == n_hops - 1));
         d_dst = b->hop[h].src_global.p;
         d_n = b->counts.p + 4 * h + 1;
     }
     if (!use_cache) hipLaunchKernelGGL(set_counts_kernel, dim3(1), dim3(1), 0, st, extra, 0, 0, 0);
-    // the id map is wiped on the side stream, after the last hop's lookups and behind the transposes
+    // the id map is wiped on the side stream, behind the last hop's index lookups and the transposes
     const HopBuffers& last = b->hop[n_hops - 1];
-    NO_HIP_CHECK(hipEventRecord(b->ev_fork[n_hops - 1], st));
-    NO_HIP_CHECK(hipStreamWaitEvent(b->side, b->ev_fork[n_hops - 1], 0));
     hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, 256)), dim3(256), 0, b->side,
                        (const int32_t*)last.src_global.p, d_n, b->map.p);
     b->side_pending = true;

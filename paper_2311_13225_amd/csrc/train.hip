@@ -16,7 +16,7 @@ struct no_model_s {
     no::DevBuf<float> params, grads;                 // per layer: w_self, w_neigh, bias
     size_t off_w_self[NO_MAX_LAYERS], off_w_neigh[NO_MAX_LAYERS], off_bias[NO_MAX_LAYERS];
     size_t n_params = 0;
-    no::DevBuf<char> x0;                             // gathered input rows [bottom n_src_cap, F]
+    no::DevBuf<char> x0;                             // gathered rows of the bottom hop's destinations [n_dst_cap, F]
     no::DevBuf<float> mean[NO_MAX_LAYERS];           // layer l (index l-1): [n_dst_cap, d_{l-1}]
     no::DevBuf<float> h[NO_MAX_LAYERS];              // layer l output [rows, d_l]; h[0] holds all of V^1
     no::DevBuf<float> gh[NO_MAX_LAYERS];             // gradient w.r.t. h[l-1]
@@ -171,7 +171,7 @@ extern "C" int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t
     const int32_t L = n_layers;
     const HopBuffers& bottom = m->blocks->hop[L - 1];
     const size_t es = feat_dtype == NO_F32 ? 4 : 2;
-    NO_CHECK(m->x0.alloc((size_t)bottom.n_src_cap * m->dims[0] * es));
+    NO_CHECK(m->x0.alloc((size_t)bottom.n_dst_cap * m->dims[0] * es));
     size_t ws_bytes = 0;
     for (int32_t l = 1; l <= L; ++l) {
         const HopBuffers& H = m->blocks->hop[L - l];
@@ -273,13 +273,15 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
     m->last_used_cache = used_cache;
     const int32_t* extra = B->counts.p + 4 * L;
 
-    // gather the bottom hop's source rows
+    // Gather. Only the destination rows of the bottom hop are materialised (the self path of layer 1 and its
+    // weight gradient read them densely); the neighbour rows are read from the feature table by the layer-1
+    // mean aggregation itself, through the sampled global ids, so they are never written and re-read.
     const HopBuffers& bottom = B->hop[L - 1];
     const int32_t es = m->feat_dtype == NO_F32 ? 4 : 2;
     const int32_t row_bytes = m->dims[0] * es;
     prof.begin(NO_STAGE_GATHER);
-    NO_CHECK(gather_rows(d_features, row_bytes, row_bytes, bottom.src_global.p, B->counts.p + 4 * (L - 1) + 1,
-                         bottom.n_src_cap, m->x0.p, row_bytes, st));
+    NO_CHECK(gather_rows(d_features, row_bytes, row_bytes, bottom.src_global.p, B->counts.p + 4 * (L - 1) + 0,
+                         bottom.n_dst_cap, m->x0.p, row_bytes, st));
     prof.end();
 
     // forward
@@ -293,6 +295,14 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         float* h_out = (l == 1 && used_cache) ? m->h1c.p : m->h[l - 1].p;
         LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
         if (l == 2) prof.begin(NO_STAGE_FWD_UPPER);
+        if (l == 1) {
+            // fused gather + aggregate: rows of the table addressed by the sampled neighbours' global ids
+            no_block_view fused = blk;
+            fused.d_indices = blk.d_nbr_global;
+            NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
+                                  m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
+                                  NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features));
+        } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
                               l == 1 ? &prof : nullptr, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1));

@@ -363,9 +363,10 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
             assert (st.n_dst[h], st.n_src[h], st.nnz[h]) == tuple(int(x) for x in sizes[h, :3])
         assert st.n_hit == r.n_hit
         hits += r.n_hit
-        # gathered rows: bit copy
-        x0 = b.no_model_gathered(model, r.batch.blocks[-1].n_src).cpu().numpy()
-        assert np.array_equal(x0.view(feat.dtype), r.x0)
+        # gathered rows (the step materialises the bottom destinations' rows; the rest is read in place): bit copy
+        n_dst_bottom = r.batch.blocks[-1].n_dst
+        x0 = b.no_model_gathered(model, n_dst_bottom).cpu().numpy()
+        assert np.array_equal(x0.view(feat.dtype), r.x0[:n_dst_bottom])
         # floats
         assert abs(st.loss - r.loss) <= RTOL * abs(r.loss) + 1e-6, (st.loss, r.loss)
         for l in range(1, w.n_layers + 1):
@@ -413,3 +414,50 @@ def test_train_step_single_layer_and_bf16_features():
     run_steps(w1, 2, use_cache=False)
     wb = dataclasses.replace(si.WORKLOADS["tiny"], feat_dtype="bf16", feat_dim=128, staleness=2, hot_fraction=0.1)
     run_steps(wb, 3, use_cache=True)
+
+
+@pytest.mark.parametrize("hot_fraction,staleness", [(0.0, 2), (0.1, 0), (0.1, 2), (0.1, 4), (0.3, 2), (0.3, 4)])
+def test_hot_reuse_sweep_points(hot_fraction, staleness):
+    """The sweep of BASELINE's last config (hot fraction x staleness bound), on a shrunken copy of its graph."""
+    import dataclasses
+    w = dataclasses.replace(si.scaled(si.WORKLOADS["sweep"], 0.01), batch=256, hot_fraction=hot_fraction,
+                            staleness=staleness, feat_dim=64, hidden=32)
+    hits = run_steps(w, 6, use_cache=True, lr=0.02, bits=32)
+    if hot_fraction == 0.0 or staleness == 0:
+        assert hits == 0
+    else:
+        assert hits > 0
+
+
+def test_large_config_shape_scaled_bf16():
+    """configs[3] (bf16 features, int64 row pointers, 3 layers, 172 classes) on a shrunken graph."""
+    w = si.scaled(si.WORKLOADS["large"], 0.0005)
+    assert run_steps(w, 4, use_cache=True, lr=0.01, bits=64) > 0
+
+
+def test_cache_invalidate_and_set_staleness():
+    b = nb()
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=3, hot_fraction=0.2)
+    src, dst, og, gg = make_graph(w.n_vertices, w.n_edges, w.seed, 32)
+    feat = si.features(w.n_vertices, w.feat_dim, w.seed)
+    lab = si.labels(w.n_vertices, w.n_classes, w.seed)
+    train = si.train_split(w.n_vertices, 0.65, w.seed)
+    model = b.no_model_create(gg, w.dims, w.batch, w.fanouts)
+    for l in range(w.n_layers):
+        for t, a in zip(b.no_model_params(model, l + 1), si.init_weights(w.dims, w.seed)[l]):
+            t.copy_(dev(a))
+    gc = b.no_select_hot(gg, dev(train), w.batch, w.fanouts, 1, w.hot_fraction, w.staleness, w.hidden, w.seed)
+    tfeat, tlab = dev(feat), dev(lab)
+    step = lambda t: b.no_train_step(model, gg, tfeat, tlab, dev(si.batch_seeds(train, w.batch, t)), gc, t, 0, 0.01)
+    assert step(0).n_hit == 0 and step(0).n_refresh >= 0
+    assert step(1).n_hit > 0
+    b.no_cache_invalidate(gc)
+    assert step(2).n_hit == 0                      # every slot is empty again
+    assert step(3).n_hit > 0
+    b.no_cache_set_staleness(gc, 0)
+    assert step(4).n_hit == 0                      # bound 0: nothing may be reused
+    with pytest.raises(b.NoError):
+        b.no_cache_set_staleness(gc, -1)
+    st = step(5)
+    assert st.n_v1 == st.n_dst[1] + st.n_hit and st.n_refresh <= st.n_dst[1]
