@@ -39,6 +39,11 @@ def main():
     ap.add_argument("--no-cache", action="store_true", help="exact training (no hot-embedding reuse)")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: auto, 0: skip)")
     ap.add_argument("--presample-epochs", type=int, default=3)
+    ap.add_argument("--presample-batches", type=int, default=0,
+                    help="pre-sample hotness on the first N batches of the train split only (0: all)")
+    ap.add_argument("--device-features", action="store_true",
+                    help="generate the feature table in device memory (implied for tables over 2^31 elements); "
+                         "the CPU baseline is skipped then")
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain copy of known size (1,000,000 rows x 1024 B through no_gather_features with "
@@ -78,7 +83,8 @@ def main():
     src, dst = si.rmat_edges(w.n_vertices, w.n_edges, w.seed, symmetrise=w.symmetrise)
     log("[bench] R-MAT %d vertices %d edges: %.1fs" % (w.n_vertices, len(src), time.time() - t0))
     t0 = time.time()
-    feat = si.features(w.n_vertices, w.feat_dim, w.seed, w.feat_dtype)
+    device_features = args.device_features or w.n_vertices * w.feat_dim > (1 << 31)
+    feat = None if device_features else si.features(w.n_vertices, w.feat_dim, w.seed, w.feat_dtype)
     lab = si.labels(w.n_vertices, w.n_classes, w.seed)
     train = si.train_split(w.n_vertices, 0.65, w.seed)
     weights = si.init_weights(w.dims, w.seed)
@@ -90,14 +96,18 @@ def main():
     torch.cuda.synchronize()
     t_csr = time.time() - t0
     log("[bench] no_build_csr (incl. H2D of the edge list): %.2fs" % t_csr)
-    tfeat = dev(feat.view(np.int16) if bf16 else feat)
+    if device_features:
+        tfeat = si.features_on_device(w.n_vertices, w.feat_dim, w.seed, w.feat_dtype)
+    else:
+        tfeat = dev(feat.view(np.int16) if bf16 else feat)
     tlab = dev(lab)
     ttrain = dev(train)
     cache = None
     t_hot = 0.0
     if not args.no_cache:
         t0 = time.time()
-        cache = b.no_select_hot(g, ttrain, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
+        pre = ttrain if args.presample_batches <= 0 else ttrain[: args.presample_batches * w.batch].contiguous()
+        cache = b.no_select_hot(g, pre, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
                                 w.hidden, w.seed)
         torch.cuda.synchronize()
         t_hot = time.time() - t0
@@ -200,7 +210,7 @@ def main():
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded number of the same steps
     cpu = None
-    cpu_steps = args.cpu_steps
+    cpu_steps = 0 if device_features else args.cpu_steps
     if cpu_steps != 0:
         from oracle import oracle as ora
         try:
@@ -212,7 +222,8 @@ def main():
         og = ora.build_csr(src, dst, w.n_vertices)
         oc = None
         if cache is not None:
-            oc = ora.select_hot(og, train, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
+            pre_h = train if args.presample_batches <= 0 else train[: args.presample_batches * w.batch]
+            oc = ora.select_hot(og, pre_h, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
                                 w.hidden, w.seed)
         log("[bench] oracle setup (CSR + hot set): %.1fs" % (time.time() - t0))
         ow = [tuple(np.asarray(t, np.float64) for t in x) for x in weights]

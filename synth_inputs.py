@@ -178,6 +178,22 @@ def features(n_vertices: int, dim: int, seed: int = 0, dtype: str = "f32") -> np
     raise ValueError(dtype)
 
 
+def features_on_device(n_vertices: int, dim: int, seed: int = 0, dtype: str = "f32", device: str = "cuda",
+                       chunk_rows: int = 1 << 22):
+    """Feature table generated directly in device memory with torch's generator (for tables too large
+    to make on the host in reasonable time, e.g. 111 M x 128). Returns a torch tensor: float32, or int16
+    bf16 bit patterns (round-to-nearest-even). Rows are i.i.d. N(0,1); not the same values as features()."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(0x66656174 + 1000003 * seed)
+    out = torch.empty((n_vertices, dim), dtype=torch.float32 if dtype == "f32" else torch.int16, device=device)
+    for lo in range(0, n_vertices, chunk_rows):
+        hi = min(n_vertices, lo + chunk_rows)
+        x = torch.randn((hi - lo, dim), generator=gen, device=device, dtype=torch.float32)
+        out[lo:hi] = x if dtype == "f32" else x.to(torch.bfloat16).view(torch.int16)
+    return out
+
+
 def labels(n_vertices: int, n_classes: int, seed: int = 0) -> np.ndarray:
     return _rng(seed, "label").integers(0, n_classes, size=n_vertices, dtype=np.int32)
 
