@@ -165,9 +165,27 @@ def main():
     n_hit = mean([s.n_hit for s in stats])
     n_v1 = mean([s.n_v1 for s in stats])
     loss_last = stats[-1].loss
-    # algorithmic work per launch (units: one step's rows/edges as measured)
-    # the step gathers the destination rows densely and reads the neighbour rows inside the aggregation
-    gather_bytes = n_dst_bottom * (4 + 2 * F * es)
+    # Gather: inside the step only the bottom destinations' rows are copied (on the side stream, next to the
+    # aggregation, which reads the neighbour rows in place), so the step has no gather stage to time. The
+    # gather figure is no_gather_features on the FULL source list of the last step's bottom hop (what an
+    # unfused step would collect), timed alone with events on the stream it runs on.
+    blocks = b.no_model_blocks(model)
+    view = b.no_blocks_view(blocks, L - 1)
+    n_src_last = int(stats[-1].n_src[L - 1])
+    ids_last = b._view(view.d_src_global, (n_src_last,), "<i4", blocks).clone()
+    gout = torch.empty((n_src_last, F), dtype=tfeat.dtype, device="cuda")
+    for _ in range(3):
+        b.no_gather_features(tfeat, ids_last, gout)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_rep = 20
+    e0.record()
+    for _ in range(n_rep):
+        b.no_gather_features(tfeat, ids_last, gout)
+    e1.record()
+    torch.cuda.synchronize()
+    per_step["gather"] = e0.elapsed_time(e1) / n_rep          # ms per launch, standalone
+    gather_bytes = n_src_last * (4 + 2 * F * es)
+    del gout
     agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4     # compulsory traffic (each row once)
     gemm_fwd_flops = 2.0 * n_dst_bottom * (2 * F) * w.dims[1]
     gemm_dw_flops = gemm_fwd_flops
@@ -200,9 +218,11 @@ def main():
         "aggregate_GBps": round(kern["segment_rows_kernel(mean,l1)"][1], 2),
         "aggregate_frac_hbm_peak": round(kern["segment_rows_kernel(mean,l1)"][1] / HBM_PEAK_GBPS, 4),
         "rows_gathered_per_step": round(n_src_bottom, 1),
+        "gather_measurement": "no_gather_features alone on the %d source rows of the last step's bottom hop "
+                              "(in the step the neighbour rows are read inside the aggregation)" % n_src_last,
         "cache_hit_rate": round(n_hit / max(n_v1, 1.0), 4),
         "stage_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
-        "profiled_ms_per_step": round(sum(per_step.values()), 4),
+        "profiled_ms_per_step": round(sum(v for k, v in per_step.items() if k != "gather"), 4),
         "setup_s": {"build_csr": round(t_csr, 2), "select_hot": round(t_hot, 2)},
         "loss_after_last_step": round(float(loss_last), 5),
     }

@@ -51,12 +51,14 @@ struct no_blocks_s {
     hipStream_t side = nullptr;
     hipEvent_t ev_fork[NO_MAX_LAYERS] = {nullptr};
     hipEvent_t ev_side_done = nullptr;
+    hipEvent_t ev_gather_done = nullptr;
     bool side_pending = false;
     no::DevBuf<char> ws_side;
     void release() {
         if (side) { (void)hipStreamSynchronize(side); (void)hipStreamDestroy(side); side = nullptr; }
         for (auto& e : ev_fork) if (e) { (void)hipEventDestroy(e); e = nullptr; }
         if (ev_side_done) { (void)hipEventDestroy(ev_side_done); ev_side_done = nullptr; }
+        if (ev_gather_done) { (void)hipEventDestroy(ev_gather_done); ev_gather_done = nullptr; }
         ws_side.release();
         for (auto& h : hop) h.release();
         counts.release(); seeds.release(); map.release(); tmp_a.release(); ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();
@@ -78,9 +80,12 @@ namespace no {
 // Internal entry used by no_sample_blocks and no_select_hot.
 // With join == false the caller must call blocks_join(b, st) before anything on `st` reads a transpose
 // or starts another sampling call on the same blocks.
+// Optional job run first on the side stream: dense copy of the last hop's destination feature rows
+// (out[i,:] = table[dst[i],:]); the caller waits on b->ev_gather_done before reading `out`.
+struct SideGather { const void* table = nullptr; int32_t row_bytes = 0; void* out = nullptr; };
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key,
                            uint32_t domain, int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b,
-                           hipStream_t st, bool join = true);
+                           hipStream_t st, bool join = true, const SideGather* gather = nullptr);
 int32_t blocks_join(no_blocks_s* b, hipStream_t st);
 int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fanouts, int32_t n_layers,
                            bool build_csc, no_blocks_s** out);

@@ -221,13 +221,14 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
-                     const void* agg_table) {
+                     const void* agg_table, hipEvent_t wait_before_gemm) {
     // agg_table != NULL: the rows to average are rows of that table addressed by blk.d_indices (global ids),
     // while x_src holds only the destination rows (fused gather + aggregate of the bottom layer)
     if (prof && agg_stage >= 0) prof->begin(agg_stage);
     NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap,
                             mean, st));
     if (prof && agg_stage >= 0) prof->end();
+    if (wait_before_gemm) NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
     const float* x_dst = (const float*)x_src;
     if (dt == NO_BF16) {
         hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)blk.n_dst_cap * d_in)), dim3(256), 0, st,

@@ -20,6 +20,7 @@
 // that columns end up in ascending edge id regardless of the fill order.
 #include "primitives.hpp"
 #include "handles.hpp"
+#include "layers.hpp"
 
 namespace no {
 
@@ -394,35 +395,48 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     hipLaunchKernelGGL(edge_assign_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
                        (const int32_t*)cnt, k, k_magic, (const int64_t*)tile_sums, H.indptr.p, H.nbr_global.p, H.edge_row.p,
                        H.src_global.p, cnt);
-    if (last_hop) {
-        // Nothing downstream on the caller's stream needs the last hop's local indices before the join (the
-        // bottom layer aggregates through the global ids): they are filled on the side stream, ahead of the
-        // wipe of the id map that the caller queues there next.
-        NO_HIP_CHECK(hipEventRecord(b->ev_fork[h], st));
-        NO_HIP_CHECK(hipStreamWaitEvent(b->side, b->ev_fork[h], 0));
-        hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, b->side,
+    if (!last_hop)
+        hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st,
                            (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,
-                           (int32_t*)nullptr);
-        b->side_pending = true;
-        return launch_status("sample_hop");
+                           H.has_csc ? H.csc_cnt.p : nullptr);
+    return launch_status("sample_hop");
+}
+
+// Work that nothing on the caller's stream needs before the join, queued on the side stream behind ONE
+// fork event recorded after the last hop's ids are final: the transposes of the upper hops, the last hop's
+// local indices (the bottom layer aggregates through the global ids), and the wipe of the id map.
+static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d_n_src_last, hipStream_t st,
+                                const SideGather* gather) {
+    const int T = 256;
+    hipStream_t sd = b->side;
+    NO_HIP_CHECK(hipEventRecord(b->ev_fork[0], st));
+    NO_HIP_CHECK(hipStreamWaitEvent(sd, b->ev_fork[0], 0));
+    if (gather && gather->table) {
+        const HopBuffers& lastg = b->hop[n_hops - 1];
+        NO_CHECK(gather_rows(gather->table, gather->row_bytes, gather->row_bytes, lastg.src_global.p,
+                             b->counts.p + 4 * (n_hops - 1), lastg.n_dst_cap, gather->out, gather->row_bytes, sd));
+        NO_HIP_CHECK(hipEventRecord(b->ev_gather_done, sd));
     }
-    hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st, (const int32_t*)(cnt + 2),
-                       (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,
-                       H.has_csc ? H.csc_cnt.p : nullptr);
-    if (H.has_csc) {
-        // fork: the transpose only needs this hop's indices; the next hop proceeds on the main stream
-        hipStream_t sd = b->side;
-        NO_HIP_CHECK(hipEventRecord(b->ev_fork[h], st));
-        NO_HIP_CHECK(hipStreamWaitEvent(sd, b->ev_fork[h], 0));
+    for (int32_t h = 0; h < n_hops; ++h) {
+        HopBuffers& H = b->hop[h];
+        int32_t* cnt = b->counts.p + 4 * h;
+        if (!H.has_csc) continue;
         NO_CHECK(exclusive_scan2(ArrayLoader{H.csc_cnt.p}, cnt + 1, H.n_src_cap, H.csc_indptr.p, nullptr, b->ws_side.p, sd));
         hipLaunchKernelGGL(csc_fill_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd, (const int32_t*)(cnt + 2),
                            (const int32_t*)H.indices.p, (const int32_t*)H.csc_indptr.p, H.csc_cur.p, b->tmp_a.p);
         hipLaunchKernelGGL(csc_rank_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd, (const int32_t*)(cnt + 2),
                            (const int32_t*)H.indices.p, (const int32_t*)H.csc_indptr.p, (const int32_t*)b->tmp_a.p,
                            (const int32_t*)H.edge_row.p, H.csc_eid.p, H.csc_dst.p);
-        b->side_pending = true;
     }
-    return launch_status("sample_hop");
+    HopBuffers& last = b->hop[n_hops - 1];
+    int32_t* cnt = b->counts.p + 4 * (n_hops - 1);
+    hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(last.nnz_cap, T)), dim3(T), 0, sd,
+                       (const int32_t*)(cnt + 2), (const int32_t*)last.nbr_global.p, (const int32_t*)b->map.p,
+                       last.indices.p, last.has_csc ? last.csc_cnt.p : nullptr);
+    hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, T)), dim3(T), 0, sd,
+                       (const int32_t*)last.src_global.p, d_n_src_last, b->map.p);
+    b->side_pending = true;
+    return launch_status("side work");
 }
 
 int32_t blocks_join(no_blocks_s* b, hipStream_t st) {
@@ -434,7 +448,8 @@ int32_t blocks_join(no_blocks_s* b, hipStream_t st) {
 }
 
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key, uint32_t domain,
-                           int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st, bool join) {
+                           int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st, bool join,
+                           const SideGather* gather) {
     NO_CHECK(blocks_join(b, st));      // a previous call that was never joined
     const int32_t L = b->n_layers;
     int32_t* extra = b->counts.p + 4 * L;     // n_compute, n_hit, -, -, n_refresh
@@ -468,11 +483,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
         d_n = b->counts.p + 4 * h + 1;
     }
     if (!use_cache) hipLaunchKernelGGL(set_counts_kernel, dim3(1), dim3(1), 0, st, extra, 0, 0, 0);
-    // the id map is wiped on the side stream, behind the last hop's index lookups and the transposes
-    const HopBuffers& last = b->hop[n_hops - 1];
-    hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, 256)), dim3(256), 0, b->side,
-                       (const int32_t*)last.src_global.p, d_n, b->map.p);
-    b->side_pending = true;
+    NO_CHECK(launch_side_work(b, n_hops, d_n, st, gather));
     NO_CHECK(launch_status("sample_blocks"));
     if (join) NO_CHECK(blocks_join(b, st));
     return NO_OK;
@@ -530,6 +541,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
     NO_HIP_CHECK(hipStreamCreateWithFlags(&b->side, hipStreamNonBlocking));
     for (int32_t h = 0; h < n_layers; ++h) NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_fork[h], hipEventDisableTiming));
     NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_side_done, hipEventDisableTiming));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_gather_done, hipEventDisableTiming));
     if (n_layers >= 2) {
         size_t v1_cap = (size_t)b->hop[n_layers - 2].n_src_cap;
         NO_CHECK(b->compute_list.alloc(v1_cap));

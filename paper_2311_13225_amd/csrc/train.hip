@@ -265,24 +265,24 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
     prof.st = st;
     prof.n = 0;
 
-    // sample
+    // Sample. Only the destination rows of the bottom hop are gathered densely (the self path of layer 1 and
+    // its weight gradient read them); that copy runs on the blocks' side stream next to the layer-1 aggregation,
+    // which reads the neighbour rows from the feature table itself through the sampled global ids, so those
+    // rows are never written and re-read.
+    const int32_t es = m->feat_dtype == NO_F32 ? 4 : 2;
+    const int32_t row_bytes = m->dims[0] * es;
+    SideGather sg;
+    sg.table = d_features;
+    sg.row_bytes = row_bytes;
+    sg.out = m->x0.p;
     prof.begin(NO_STAGE_SAMPLE);
-    NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false));
+    NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg));
     prof.end();
     const bool used_cache = B->last_used_cache;
     m->last_used_cache = used_cache;
     const int32_t* extra = B->counts.p + 4 * L;
-
-    // Gather. Only the destination rows of the bottom hop are materialised (the self path of layer 1 and its
-    // weight gradient read them densely); the neighbour rows are read from the feature table by the layer-1
-    // mean aggregation itself, through the sampled global ids, so they are never written and re-read.
     const HopBuffers& bottom = B->hop[L - 1];
-    const int32_t es = m->feat_dtype == NO_F32 ? 4 : 2;
-    const int32_t row_bytes = m->dims[0] * es;
-    prof.begin(NO_STAGE_GATHER);
-    NO_CHECK(gather_rows(d_features, row_bytes, row_bytes, bottom.src_global.p, B->counts.p + 4 * (L - 1) + 0,
-                         bottom.n_dst_cap, m->x0.p, row_bytes, st));
-    prof.end();
+    (void)bottom;
 
     // forward
     no_block_view view[NO_MAX_LAYERS];
@@ -296,12 +296,13 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
         if (l == 2) prof.begin(NO_STAGE_FWD_UPPER);
         if (l == 1) {
-            // fused gather + aggregate: rows of the table addressed by the sampled neighbours' global ids
+            // fused gather + aggregate: rows of the table addressed by the sampled neighbours' global ids; the
+            // dense product then waits for the destination rows copied on the side stream
             no_block_view fused = blk;
             fused.d_indices = blk.d_nbr_global;
             NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
-                                  NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features));
+                                  NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features, B->ev_gather_done));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
