@@ -199,17 +199,18 @@ def main():
     bound, achieved, peak, unit, dur = kern[dominant]
     # HBM bytes per launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by the copy reference),
     # recorded in profiles/dense_hbm_traffic.json for this workload; null for other workloads or kernels
-    traffic = None
+    traffic_all = {}
     tpath = os.path.join(ROOT, "profiles", "dense_hbm_traffic.json")
     if args.workload == "dense" and cache is not None and os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("bytes_per_launch", {}).get(dominant)
+            traffic_all = json.load(open(tpath)).get("bytes_per_launch", {})
         except Exception:
-            traffic = None
+            traffic_all = {}
     roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": traffic, "avg_launch_ms": round(dur, 4),
+                "frac": round(achieved / peak, 4), "traffic": traffic_all.get(dominant), "avg_launch_ms": round(dur, 4),
                 "all": {k: {"bound": v[0], "achieved": round(v[1], 3), "peak": v[2], "unit": v[3],
-                            "frac": round(v[1] / v[2], 4), "avg_launch_ms": round(v[4], 4)} for k, v in kern.items()}}
+                            "frac": round(v[1] / v[2], 4), "avg_launch_ms": round(v[4], 4),
+                            "traffic": traffic_all.get(k)} for k, v in kern.items()}}
     extra = {
         "sampled_edges_per_s": round(nnz_total / (per_step["sample"] / 1e3), 1),
         "sampled_edges_per_step": round(nnz_total, 1),
