@@ -12,8 +12,8 @@
  * Readings where the paper is silent (see each function):
  *   - graph = CSR over in-neighbours (Eq. 1 aggregates over N_in(v));
  *   - sampling is uniform, without replacement, over the edge positions of a row, and takes
- *     the whole row in stored order when deg <= fanout (Section 2.2: the sampler "uniformly
- *     selects" a fixed number of neighbours per vertex);
+ *     the whole row in stored order when deg <= fanout (Section 2.2: a fixed number of neighbours per
+ *     vertex, chosen uniformly);
  *   - the random source is Philox4x32-10 (Salmon et al., SC'11), counter-based so that a
  *     sample is a pure function of (stream, domain, hop, vertex, slot).
  */
