@@ -47,15 +47,15 @@ class Workload:
 
 
 WORKLOADS = {
-    # configs[0]: the small case the oracle finishes in seconds
+    # tiny: the small case the oracle finishes in seconds
     "tiny": Workload("tiny", 10_000, 100_000, False, 32, 64, "f32", 16, 64, (10, 5), 256, 0.05, 0),
-    # configs[1]: dense-neighbourhood graph (Reddit-shaped)
+    # dense-neighbourhood graph (Reddit-shaped): the benchmark workload
     "dense": Workload("dense", 233_000, 114_000_000, False, 64, 602, "f32", 41, 256, (25, 10), 1024, 0.10, 1),
-    # configs[2]: mid-size sparse graph (Products-shaped)
+    # mid-size sparse graph (Products-shaped)
     "sparse": Workload("sparse", 2_400_000, 124_000_000, True, 32, 100, "f32", 47, 256, (15, 10, 5), 1024, 0.10, 2),
-    # configs[3]: large graph (Papers100M-shaped), bf16 features
+    # large graph (Papers100M-shaped), bf16 features
     "large": Workload("large", 111_000_000, 1_600_000_000, False, 64, 128, "bf16", 172, 256, (15, 10, 5), 1024, 0.10, 2),
-    # configs[4]: hot-reuse sweep on the sparse graph with wider features
+    # hot-reuse sweep on the sparse graph with wider features
     "sweep": Workload("sweep", 2_400_000, 124_000_000, True, 32, 256, "f32", 47, 256, (15, 10, 5), 4096, 0.10, 2),
 }
 

@@ -1,5 +1,5 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times:
-the dense (configs[1]) and sparse (configs[2]) workloads, several training steps with hot
+"""GPU parity at the full sizes of the named workloads, in the launch configuration bench.py times:
+the dense (Reddit-shaped) and sparse (Products-shaped) workloads, several training steps with hot
 reuse, every integer array bit-exact and every float tensor within tolerance against the oracle.
 The oracle's per-step cost at these sizes is about a second, so whole steps are compared, not
 samples."""

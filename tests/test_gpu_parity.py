@@ -418,7 +418,8 @@ def test_train_step_single_layer_and_bf16_features():
 
 @pytest.mark.parametrize("hot_fraction,staleness", [(0.0, 2), (0.1, 0), (0.1, 2), (0.1, 4), (0.3, 2), (0.3, 4)])
 def test_hot_reuse_sweep_points(hot_fraction, staleness):
-    """The sweep of BASELINE's last config (hot fraction x staleness bound), on a shrunken copy of its graph."""
+    """The hot-reuse sweep (hot fraction x staleness bound, the shape of the paper's Fig. 14 experiment) on a
+    shrunken copy of the sweep workload's graph."""
     import dataclasses
     w = dataclasses.replace(si.scaled(si.WORKLOADS["sweep"], 0.01), batch=256, hot_fraction=hot_fraction,
                             staleness=staleness, feat_dim=64, hidden=32)
@@ -430,7 +431,7 @@ def test_hot_reuse_sweep_points(hot_fraction, staleness):
 
 
 def test_large_config_shape_scaled_bf16():
-    """configs[3] (bf16 features, int64 row pointers, 3 layers, 172 classes) on a shrunken graph."""
+    """The large workload's shape (bf16 features, int64 row pointers, 3 layers, 172 classes) on a shrunken graph."""
     w = si.scaled(si.WORKLOADS["large"], 0.0005)
     assert run_steps(w, 4, use_cache=True, lr=0.01, bits=64) > 0
 
