@@ -106,7 +106,9 @@ int32_t no_blocks_create(no_graph_t g, int32_t n_seeds_cap, const int32_t* h_fan
 /* Samples n_layers hops from d_seeds[n_seeds] (unique ids). Hop h gives every destination v
  * min(deg(v), fanouts[h]) distinct entries of its CSR row, uniformly without replacement, as a
  * pure function of (seed + step, domain 0, h, v, slot) through Philox4x32-10; the whole row in
- * stored order when deg <= fanout. The destinations of hop h+1 are the sources of hop h.
+ * stored order when deg <= fanout. The destinations of hop h+1 are the sources of hop h. Seed ids outside
+ * [0, V) are read as vertex 0 and flagged (no_step_stats.bad_seed); the blocks are then meaningless but
+ * every access stays inside the library's and the graph's arrays.
  * With cache != NULL (and n_layers >= 2) the destinations of the bottom hop are only those
  * vertices of V^1 that cannot be served from the cache at `step` (not hot, empty slot, or
  * step - version > S). Asynchronous. */
@@ -191,7 +193,7 @@ typedef struct no_step_stats {
     int32_t n_hit;        /* rows of V^1 served from the cache */
     int32_t n_refresh;    /* computed rows written back to the cache */
     int32_t n_v1;         /* |V^1| */
-    int32_t pad;
+    int32_t bad_seed;     /* 1 if any seed id of this or an earlier step lay outside [0, V) (it was read as vertex 0) */
 } no_step_stats;
 
 /* dims = [F, hidden.., C] (n_layers+1 entries). Weights live inside the handle; the caller

@@ -43,7 +43,7 @@ class no_block_view(C.Structure):
 class no_step_stats(C.Structure):
     _fields_ = [("loss", C.c_float), ("n_dst", C.c_int32 * NO_MAX_LAYERS), ("n_src", C.c_int32 * NO_MAX_LAYERS),
                 ("nnz", C.c_int32 * NO_MAX_LAYERS), ("n_hit", C.c_int32), ("n_refresh", C.c_int32),
-                ("n_v1", C.c_int32), ("pad", C.c_int32)]
+                ("n_v1", C.c_int32), ("bad_seed", C.c_int32)]
 
 
 _lib = None

@@ -37,7 +37,7 @@ struct no_blocks_s {
     int64_t n_vertices = 0;
     bool build_csc = true;             // transpose hops 0..L-2 (select_hot's private blocks skip it)
     no::HopBuffers hop[NO_MAX_LAYERS];
-    // counts[4*h + {0,1,2}] = n_dst, n_src, nnz of hop h; counts[4*L + {0,1,4}] = n_compute, n_hit, n_refresh
+    // counts[4*h + {0,1,2}] = n_dst, n_src, nnz of hop h; counts[4*L + {0,1,4,5}] = n_compute, n_hit, n_refresh, bad-seed flag
     no::DevBuf<int32_t> counts;
     no::DevBuf<int32_t> seeds;          // copy of the seed ids (hop 0 destinations)
     no::DevBuf<int32_t> map;            // vertex -> local id, EMPTY between calls, [V]

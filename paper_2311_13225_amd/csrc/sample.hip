@@ -50,7 +50,8 @@ __global__ void __launch_bounds__(256) sample_rows_kernel(const RowT* __restrict
                                                           int32_t n_fixed, int32_t n_cap, int32_t k, uint32_t key0,
                                                           uint32_t key1, uint32_t c3, int32_t* __restrict__ nbr_pad,
                                                           int32_t* __restrict__ src_global, int32_t* map,
-                                                          int32_t insert_dst, int32_t* seeds_copy, int32_t* count_out) {
+                                                          int32_t insert_dst, int32_t* seeds_copy, int32_t* count_out,
+                                                          int32_t n_vertices, int32_t* bad_id_flag) {
     int32_t n_dst = d_n_dst ? *d_n_dst : n_fixed;
     if (n_dst > n_cap) n_dst = n_cap;
     if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = n_dst;
@@ -61,6 +62,11 @@ __global__ void __launch_bounds__(256) sample_rows_kernel(const RowT* __restrict
     int64_t begin = 0, d = 0;
     if (row_ok) {
         v = dst[i];
+        if (insert_dst && (uint32_t)v >= (uint32_t)n_vertices) {
+            // a caller-supplied seed outside [0, V): stay inside the graph's arrays and report it
+            v = 0;
+            *bad_id_flag = 1;
+        }
         begin = (int64_t)rowptr[v];
         d = (int64_t)rowptr[v + 1] - begin;
         if (j == 0) {
@@ -381,7 +387,8 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
 #define NO_LAUNCH_SAMPLE(G)                                                                                            \
     hipLaunchKernelGGL((sample_rows_kernel<G, RowT>), dim3((unsigned)ceil_div(H.n_dst_cap, 256 / G)), dim3(256), 0, st,    \
                        rowptr, col, d_dst, d_n_dst_in, n_fixed, H.n_dst_cap, k, key0, key1, c3, H.nbr_pad.p,               \
-                       H.src_global.p, b->map.p, insert_dst ? 1 : 0, seeds_copy, cnt)
+                       H.src_global.p, b->map.p, insert_dst ? 1 : 0, seeds_copy, cnt, (int32_t)b->n_vertices,               \
+                       b->counts.p + 4 * b->n_layers + 5)
     if (k <= 8) NO_LAUNCH_SAMPLE(8);
     else if (k <= 16) NO_LAUNCH_SAMPLE(16);
     else if (k <= 32) NO_LAUNCH_SAMPLE(32);

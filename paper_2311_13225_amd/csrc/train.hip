@@ -88,7 +88,7 @@ __global__ void __launch_bounds__(256) finish_stats_kernel(const float* __restri
         stats->n_hit = used_cache ? counts[4 * n_layers + 1] : 0;
         stats->n_refresh = used_cache ? counts[4 * n_layers + 4] : 0;
         stats->n_v1 = n_layers >= 2 ? counts[4 * (n_layers - 2) + 1] : counts[0];
-        stats->pad = 0;
+        stats->bad_seed = counts[4 * n_layers + 5];
     }
 }
 

@@ -462,3 +462,18 @@ def test_cache_invalidate_and_set_staleness():
         b.no_cache_set_staleness(gc, -1)
     st = step(5)
     assert st.n_v1 == st.n_dst[1] + st.n_hit and st.n_refresh <= st.n_dst[1]
+
+
+def test_out_of_range_seed_is_flagged_not_followed():
+    b = nb()
+    w = si.WORKLOADS["tiny"]
+    src, dst, og, gg = make_graph(w.n_vertices, w.n_edges, w.seed, 32)
+    model = b.no_model_create(gg, w.dims, w.batch, w.fanouts)
+    feat, lab = dev(si.features(w.n_vertices, w.feat_dim, 0)), dev(si.labels(w.n_vertices, w.n_classes, 0))
+    seeds = si.train_split(w.n_vertices, 0.65, 0)[:64].copy()
+    st = b.no_train_step(model, gg, feat, lab, dev(seeds), None, 0, 0, 0.01)
+    assert st.bad_seed == 0
+    seeds[5] = w.n_vertices + 12345
+    seeds[9] = -7
+    st = b.no_train_step(model, gg, feat, lab, dev(seeds), None, 1, 0, 0.01)
+    assert st.bad_seed == 1
