@@ -281,22 +281,21 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
 }
 
 // Largest tile that still gives the chip enough blocks, assuming about half the row capacity is used.
-static void pick_tile(int64_t rows_est, int64_t cols, int64_t batch, bool allow_128x128, int* bm, int* bn) {
+static void pick_tile(int64_t rows_est, int64_t cols, int64_t batch, int* bm, int* bn) {
     // NO_GEMM_TILE=<bm>x<bn> pins the tile shape (tuning aid; both values in {64, 128})
     static const char* forced = getenv("NO_GEMM_TILE");
     if (forced) {
         int fm = 0, fn = 0;
-        if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128) &&
-            (allow_128x128 || fm + fn < 256)) {
+        if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128) && fm + fn < 256) {
             *bm = fm; *bn = fn;
             return;
         }
     }
-    const int cand[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
-    for (int c = allow_128x128 ? 0 : 1; c < 4; ++c) {
+    const int cand[3][2] = {{64, 128}, {128, 64}, {64, 64}};
+    for (int c = 0; c < 3; ++c) {
         if (cols <= 64 && cand[c][1] == 128) continue;
         const int64_t blocks = ceil_div(rows_est, cand[c][0]) * ceil_div(cols, cand[c][1]) * batch;
-        if (blocks >= 512 || c == 3) { *bm = cand[c][0]; *bn = cand[c][1]; return; }
+        if (blocks >= 512 || c == 2) { *bm = cand[c][0]; *bn = cand[c][1]; return; }
     }
 }
 
@@ -313,7 +312,7 @@ int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st) {
     if (a.M_cap <= 0 || a.N <= 0) return NO_OK;
     int bm, bn;
     // two LDS copies of a 128x128 tile pair in the padded layout exceed 64 KB: the forward product stops at 128x64
-    pick_tile(a.M_est > 0 ? a.M_est : (a.M_cap + 1) / 2, a.N, a.accumulate ? 1 : a.n_problems, false, &bm, &bn);
+    pick_tile(a.M_est > 0 ? a.M_est : (a.M_cap + 1) / 2, a.N, a.accumulate ? 1 : a.n_problems, &bm, &bn);
     if (b_transposed) launch_nn<true>(a, bm, bn, st);
     else launch_nn<false>(a, bm, bn, st);
     return launch_status("gemm_nn");
@@ -370,8 +369,15 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
 
 int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st) {
     if (a.Kp <= 0 || a.N <= 0) return NO_OK;
-    int bm, bn;
-    pick_tile(a.Kp + 1, a.N, 2 * a.splits, true, &bm, &bn);
+    // 64x64 tiles: the output of one split is small, so the chip is filled by many small blocks over a
+    // moderate number of splits rather than by few large blocks over many splits (fewer partials to reduce).
+    // NO_TN_TILE=<bm>x<bn> pins another shape (tuning aid; both values in {64, 128}).
+    int bm = 64, bn = 64;
+    static const char* forced = getenv("NO_TN_TILE");
+    if (forced) {
+        int fm = 0, fn = 0;
+        if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128)) { bm = fm; bn = fn; }
+    }
     dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.Kp + 1, bm), (unsigned)(2 * a.splits));
     if (bm == 128 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<128, 128>), grid, dim3(256), 0, st, a);
     else if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<64, 128>), grid, dim3(256), 0, st, a);

@@ -189,11 +189,13 @@ static inline unsigned ew_blocks(int64_t total) {
 
 // ------------------------------------------------------------------------ workspace layout
 
+// Number of row slices of the weight-gradient product: enough 64x64 output tiles x slices to give every
+// compute unit several blocks, bounded so that a slice keeps at least 256 rows of the capacity.
 int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out) {
-    const int64_t tiles = 2 * ceil_div(d_in, 128) * ceil_div(d_out, 128);
+    const int64_t tiles = 2 * ceil_div(d_in + 1, 64) * ceil_div(d_out, 64);
     static const char* env = getenv("NO_TN_BLOCKS");      // tuning aid: target number of blocks of the split product
-    const int64_t target = env ? atoi(env) : 768;
-    int64_t s = ceil_div(target > 0 ? target : 768, tiles);
+    const int64_t target = env && atoi(env) > 0 ? atoi(env) : 1600;
+    int64_t s = ceil_div(target, tiles);
     const int64_t by_rows = ceil_div(n_dst_cap, 256);
     if (s > by_rows) s = by_rows;
     if (s > 64) s = 64;
