@@ -54,50 +54,90 @@ template <> struct RowVec<uint16_t, 1> {
 // out[row, :] = init + scale * sum_{p in [seg[row], seg[row+1])} src[idx[p], :]
 //   MEAN: scale = 1/len (0 for an empty segment), init = 0            (forward aggregate)
 //   else: scale = 1, init = out[row,:] for row < *d_n_init, else 0    (backward through the transpose)
-// A group of 2^g_log2 lanes owns a row; each lane owns vector units u0, u0+G, ... of the row.
+// A group of G = 2^g_log2 lanes owns one work item = (row, chunk of G vector units); a lane owns one
+// vector unit of it. Rows wider than 64 units are split into several items handled by different
+// wavefronts, so a wide row keeps many short independent load chains in flight instead of one long one;
+// the items of a row are consecutive, which keeps the reads of a source row next to each other in time.
+// Up to eight source rows are loaded before the first add; the adds stay in segment order.
 template <typename T, int VEC, bool MEAN>
 __global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__ src, int64_t ld_src,
                                                            const int32_t* __restrict__ seg, const int32_t* __restrict__ idx,
                                                            const int32_t* d_n_rows, int32_t n_rows_cap,
                                                            const int32_t* d_n_init, float* __restrict__ out, int64_t ld_out,
-                                                           int32_t units, int32_t g_log2) {
+                                                           int32_t units, int32_t g_log2, int32_t n_chunks) {
     int32_t n = *d_n_rows;
     if (n > n_rows_cap) n = n_rows_cap;
     const int32_t n_init = (!MEAN && d_n_init) ? *d_n_init : 0;
     const int32_t lane = (int32_t)(threadIdx.x & 63);
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    const int32_t rows_per_pass = 64 >> g_log2;
-    const int32_t sub = lane >> g_log2, u0 = lane & ((1 << g_log2) - 1), g = 1 << g_log2;
-    for (int64_t row = wave * rows_per_pass + sub; row < n; row += n_waves * rows_per_pass) {
+    const int32_t items_per_pass = 64 >> g_log2;
+    const int32_t sub = lane >> g_log2, u0 = lane & ((1 << g_log2) - 1);
+    const int64_t n_items = (int64_t)n * n_chunks;
+    for (int64_t item = wave * items_per_pass + sub; item < n_items; item += n_waves * items_per_pass) {
+        const int64_t row = item / n_chunks;
+        const int32_t u = (int32_t)(item - row * n_chunks) * (1 << g_log2) + u0;
+        if (u >= units) continue;
         const int32_t b = seg[row], e = seg[row + 1];
         const float scale = MEAN ? (e > b ? 1.f / (float)(e - b) : 0.f) : 1.f;
-        for (int32_t u = u0; u < units; u += g) {
-            float acc[VEC];
+        const T* col = src + (int64_t)u * VEC;
+        float acc[VEC];
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
-            float* o = out + row * ld_out + (int64_t)u * VEC;
-            if (!MEAN && row < n_init) {
+        for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+        float* o = out + row * ld_out + (int64_t)u * VEC;
+        if (!MEAN && row < n_init) {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) acc[c] = o[c];
-            }
-            int32_t p = b;
-            for (; p + 4 <= e; p += 4) {
-                const int32_t i0 = idx[p], i1 = idx[p + 1], i2 = idx[p + 2], i3 = idx[p + 3];
-                float a0[VEC], a1[VEC], a2[VEC], a3[VEC];
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) a0[c] = a1[c] = a2[c] = a3[c] = 0.f;
-                RowVec<T, VEC>::add(a0, src + (int64_t)i0 * ld_src + (int64_t)u * VEC);
-                RowVec<T, VEC>::add(a1, src + (int64_t)i1 * ld_src + (int64_t)u * VEC);
-                RowVec<T, VEC>::add(a2, src + (int64_t)i2 * ld_src + (int64_t)u * VEC);
-                RowVec<T, VEC>::add(a3, src + (int64_t)i3 * ld_src + (int64_t)u * VEC);
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) acc[c] = (((acc[c] + a0[c]) + a1[c]) + a2[c]) + a3[c];
-            }
-            for (; p < e; ++p) RowVec<T, VEC>::add(acc, src + (int64_t)idx[p] * ld_src + (int64_t)u * VEC);
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) o[c] = acc[c] * scale;
+            for (int c = 0; c < VEC; ++c) acc[c] = o[c];
         }
+        int32_t p = b;
+        for (; p + 8 <= e; p += 8) {
+            int32_t ix[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ix[j] = idx[p + j];
+            float a[8][VEC];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) a[j][c] = 0.f;
+                RowVec<T, VEC>::add(a[j], col + (int64_t)ix[j] * ld_src);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] += a[j][c];
+        }
+        if (p + 4 <= e) {
+            int32_t ix[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ix[j] = idx[p + j];
+            float a[4][VEC];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) a[j][c] = 0.f;
+                RowVec<T, VEC>::add(a[j], col + (int64_t)ix[j] * ld_src);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] += a[j][c];
+            p += 4;
+        }
+        if (p < e) {        // one to three rows left
+            const int32_t i0 = idx[p], i1 = p + 1 < e ? idx[p + 1] : i0, i2 = p + 2 < e ? idx[p + 2] : i0;
+            float a[3][VEC];
+#pragma unroll
+            for (int j = 0; j < 3; ++j)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) a[j][c] = 0.f;
+            RowVec<T, VEC>::add(a[0], col + (int64_t)i0 * ld_src);
+            if (p + 1 < e) RowVec<T, VEC>::add(a[1], col + (int64_t)i1 * ld_src);
+            if (p + 2 < e) RowVec<T, VEC>::add(a[2], col + (int64_t)i2 * ld_src);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[c] = ((acc[c] + a[0][c]) + a[1][c]) + a[2][c];
+        }
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) o[c] = acc[c] * scale;
     }
 }
 
@@ -107,12 +147,13 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
     const int32_t units = dim / VEC;
     int g_log2 = 0;
     while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
-    int64_t waves = ceil_div(n_cap, 64 >> g_log2);
+    const int32_t n_chunks = (int32_t)ceil_div(units, 1 << g_log2);
+    int64_t waves = ceil_div((int64_t)n_cap * n_chunks, 64 >> g_log2);
     int64_t blocks = ceil_div(waves, 4);
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks > 256 * 64) blocks = 256 * 64;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)blocks), dim3(256), 0, st, src, ld_src, seg, idx, d_n,
-                       n_cap, d_n_init, out, ld_out, units, g_log2);
+                       n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks);
 }
 
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
