@@ -45,17 +45,19 @@ __device__ __forceinline__ float4 load4_guarded(const float* p, int valid) {
 // Otherwise every element is guarded and out-of-range elements read as zero; ones_col >= 0 (XC only)
 // adds a virtual column of ones at index `ones_col`, which makes row `ones_col` of the product the
 // column sums of the other operand (the bias gradient).
+// KC tiles take the memory row of tile row (xr + 32 * pass) from xrow[pass] (the tile row itself, or an entry
+// of a row index when the operand is a set of rows of a larger table).
 template <bool KC, int BX, bool FAST>
 __device__ __forceinline__ void tile_fetch(float4 (&reg)[BX / 32], const float* src, int64_t ld, int x0, int x_lim, int k0,
-                                           int k_lim, int ones_col = -1) {
+                                           int k_lim, const int32_t (&xrow)[BX / 32], int ones_col = -1) {
     const int tid = (int)threadIdx.x;
     if (KC) {
         const int kq = tid & 7, xr = tid >> 3;
 #pragma unroll
         for (int pass = 0; pass < BX / 32; ++pass) {
             const int gx = x0 + xr + 32 * pass, gk = k0 + kq * 4;
-            if (FAST) reg[pass] = load4_fast(src + (int64_t)gx * ld + gk);
-            else reg[pass] = load4_guarded(src + (int64_t)gx * ld + gk, gx < x_lim ? k_lim - gk : 0);
+            if (FAST) reg[pass] = load4_fast(src + (int64_t)xrow[pass] * ld + gk);
+            else reg[pass] = load4_guarded(src + (int64_t)xrow[pass] * ld + gk, gx < x_lim ? k_lim - gk : 0);
         }
     } else {
         constexpr int XQ = BX / 4, ROWS = 256 / XQ;
@@ -165,6 +167,7 @@ __device__ __forceinline__ float acc_get(const floatx16 (&acc)[SETS][MI][NI], in
 // barrier. Interior steps use unguarded 16-byte loads.
 struct StepSource {
     const float* A; int64_t lda; const float* B; int64_t ldb;
+    const int32_t* a_rows;   // KC layout only: tile row x of A is memory row a_rows[x] (NULL: row x)
     int k_begin, k_lim;      // reduction range of this phase
     int n_steps, n_fast;     // steps in this phase; the first n_fast need no guards
     int ones_col;            // virtual column of ones in A (XC layout only), or -1
@@ -172,17 +175,21 @@ struct StepSource {
 
 template <bool A_KC, bool B_KC, int BM, int BN>
 __device__ __forceinline__ void fetch_step(float4 (&ra)[BM / 32], float4 (&rb)[BN / 32], const StepSource& p0,
-                                           const StepSource& p1, int t, int am0, int a_lim, int bn0, int b_lim) {
+                                           const StepSource& p1, int t, int am0, int a_lim, int bn0, int b_lim,
+                                           const int32_t (&arow)[2][BM / 32], const int32_t (&brow)[BN / 32]) {
     const bool second = t >= p0.n_steps;
     const StepSource& p = second ? p1 : p0;
     const int s = second ? t - p0.n_steps : t;
     const int k0 = p.k_begin + s * BK;
+    int32_t ar[BM / 32];
+#pragma unroll
+    for (int i = 0; i < BM / 32; ++i) ar[i] = second ? arow[1][i] : arow[0][i];
     if (s < p.n_fast) {
-        tile_fetch<A_KC, BM, true>(ra, p.A, p.lda, am0, a_lim, k0, p.k_lim);
-        tile_fetch<B_KC, BN, true>(rb, p.B, p.ldb, bn0, b_lim, k0, p.k_lim);
+        tile_fetch<A_KC, BM, true>(ra, p.A, p.lda, am0, a_lim, k0, p.k_lim, ar);
+        tile_fetch<B_KC, BN, true>(rb, p.B, p.ldb, bn0, b_lim, k0, p.k_lim, brow);
     } else {
-        tile_fetch<A_KC, BM, false>(ra, p.A, p.lda, am0, a_lim, k0, p.k_lim, p.ones_col);
-        tile_fetch<B_KC, BN, false>(rb, p.B, p.ldb, bn0, b_lim, k0, p.k_lim);
+        tile_fetch<A_KC, BM, false>(ra, p.A, p.lda, am0, a_lim, k0, p.k_lim, ar, p.ones_col);
+        tile_fetch<B_KC, BN, false>(rb, p.B, p.ldb, bn0, b_lim, k0, p.k_lim, brow);
     }
 }
 
@@ -195,14 +202,24 @@ __device__ __forceinline__ void run_steps(const StepSource& p0, const StepSource
     // One register stage (a second one measured slower: the registers cost more occupancy than the
     // longer load window gains).
     float4 ra[BM / 32], rb[BN / 32];
-    fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, 0, am0, a_lim, bn0, b_lim);
+    // memory rows of this thread's tile rows (loop invariant; used by the KC layout only)
+    int32_t arow[2][BM / 32], brow[BN / 32];
+#pragma unroll
+    for (int i = 0; i < BM / 32; ++i) {
+        const int gx = am0 + (int)(threadIdx.x >> 3) + 32 * i;
+        arow[0][i] = (A_KC && p0.a_rows) ? (gx < a_lim ? p0.a_rows[gx] : 0) : gx;
+        arow[1][i] = (A_KC && p1.a_rows) ? (gx < a_lim ? p1.a_rows[gx] : 0) : gx;
+    }
+#pragma unroll
+    for (int i = 0; i < BN / 32; ++i) brow[i] = bn0 + (int)(threadIdx.x >> 3) + 32 * i;
+    fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, 0, am0, a_lim, bn0, b_lim, arow, brow);
     tile_store<A_KC, BM>(ra, As);
     tile_store<B_KC, BN>(rb, Bs);
     __syncthreads();
     for (int t = 0; t < total_steps; ++t) {
         const int cur = t & 1;
         const bool more = t + 1 < total_steps;
-        if (more) fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, t + 1, am0, a_lim, bn0, b_lim);
+        if (more) fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, t + 1, am0, a_lim, bn0, b_lim, arow, brow);
         tile_mma<A_KC, B_KC, BM, BN>(As + cur * A_FLOATS, Bs + cur * B_FLOATS, acc, wm, wn);
         if (more) {
             tile_store<A_KC, BM>(ra, As + (cur ^ 1) * A_FLOATS);
@@ -250,10 +267,10 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
     {
         const bool full_x = (m0 + BM <= M) && (n0 + BN <= g.N);
         const int q0 = g.accumulate ? 0 : prob, q1 = g.accumulate && n_phases > 1 ? 1 : q0;
-        StepSource p0{g.A[q0], g.lda[q0], g.B[q0], g.ldb[q0], 0, g.K[q0], (g.K[q0] + BK - 1) / BK,
+        StepSource p0{g.A[q0], g.lda[q0], g.B[q0], g.ldb[q0], g.a_rows[q0], 0, g.K[q0], (g.K[q0] + BK - 1) / BK,
                       full_x ? g.K[q0] / BK : 0, -1};
-        StepSource p1{g.A[q1], g.lda[q1], g.B[q1], g.ldb[q1], 0, g.K[q1], n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0,
-                      full_x ? g.K[q1] / BK : 0, -1};
+        StepSource p1{g.A[q1], g.lda[q1], g.B[q1], g.ldb[q1], g.a_rows[q1], 0, g.K[q1],
+                      n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0, full_x ? g.K[q1] / BK : 0, -1};
         run_steps<true, B_KC, BM, BN>(p0, p1, p0.n_steps + p1.n_steps, m0, M, n0, g.N, As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
@@ -345,7 +362,7 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
     const int ones_col = prob == 0 ? g.Kp : -1;       // product 0 carries the column sums of G in row Kp
     if (r0 < r1) {
         const bool full_x = (m0 + BM <= g.Kp) && (n0 + BN <= g.N);
-        StepSource p0{A, lda, g.G, g.ldg, r0, r1, (r1 - r0 + BK - 1) / BK, full_x ? (r1 - r0) / BK : 0, ones_col};
+        StepSource p0{A, lda, g.G, g.ldg, nullptr, r0, r1, (r1 - r0 + BK - 1) / BK, full_x ? (r1 - r0) / BK : 0, ones_col};
         StepSource p1 = p0;
         p1.n_steps = 0;
         run_steps<false, false, BM, BN>(p0, p1, p0.n_steps, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);

@@ -1,7 +1,8 @@
 // fp32 matrix products for the dense UPDATE of Eq. 2 and its gradients, on the gfx950 matrix
 // cores (v_mfma_f32_32x32x2_f32). Two shapes:
 //   NN: C[M,N] = sum_p A_p[M,K_p] * B_p[K_p,N] (+ bias, ReLU, optional 1/len row scale); M is a
-//       device scalar (rows past it are skipped); B may be given transposed.
+//       device scalar (rows past it are skipped); B may be given transposed; the rows of A_p may be
+//       picked out of a larger table by an index (gather fused into the operand load).
 //   TN: P[s][K',N] = A[rows of split s]^T * G[rows of split s]; the reduction length is a device
 //       scalar; splits are summed in a fixed order afterwards (no float atomics).
 #pragma once
@@ -11,6 +12,7 @@ namespace no {
 
 struct GemmNNArgs {
     const float* A[2]; int64_t lda[2]; int a_align[2];
+    const int32_t* a_rows[2];             // per problem: row m of the operand is row a_rows[m] of A (NULL: row m)
     const float* B[2]; int64_t ldb[2]; int b_align[2];
     int32_t K[2];
     float* C[2]; int64_t ldc[2];

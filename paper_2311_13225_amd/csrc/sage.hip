@@ -266,13 +266,17 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
                      const void* agg_table, hipEvent_t wait_before_gemm) {
     // agg_table != NULL: the rows to average are rows of that table addressed by blk.d_indices (global ids),
-    // while x_src holds only the destination rows (fused gather + aggregate of the bottom layer)
+    // while x_src holds only the destination rows (fused gather + aggregate of the bottom layer). An fp32
+    // table also feeds the self product directly, row m = table row src_global[m], so the forward pass
+    // does not wait for the dense copy of the destination rows at all.
+    const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global;
     if (prof && agg_stage >= 0) prof->begin(agg_stage);
     NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap,
                             mean, st));
     if (prof && agg_stage >= 0) prof->end();
-    if (wait_before_gemm) NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
-    const float* x_dst = (const float*)x_src;
+    if (wait_before_gemm && !direct_self)
+        NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
+    const float* x_dst = direct_self ? (const float*)agg_table : (const float*)x_src;
     if (dt == NO_BF16) {
         hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)blk.n_dst_cap * d_in)), dim3(256), 0, st,
                            (const uint16_t*)x_src, blk.d_n_dst, blk.n_dst_cap, d_in, w.x_dst_f32);
@@ -280,6 +284,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     }
     GemmNNArgs a{};
     a.A[0] = x_dst; a.lda[0] = d_in; a.a_align[0] = ptr_align(x_dst, d_in);
+    a.a_rows[0] = direct_self ? blk.d_src_global : nullptr;
     a.A[1] = mean;  a.lda[1] = d_in; a.a_align[1] = ptr_align(mean, d_in);
     a.B[0] = w_self;  a.ldb[0] = d_out; a.b_align[0] = ptr_align(w_self, d_out);
     a.B[1] = w_neigh; a.ldb[1] = d_out; a.b_align[1] = ptr_align(w_neigh, d_out);
