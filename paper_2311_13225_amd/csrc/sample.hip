@@ -418,12 +418,17 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
     hipStream_t sd = b->side;
     NO_HIP_CHECK(hipEventRecord(b->ev_fork[0], st));
     NO_HIP_CHECK(hipStreamWaitEvent(sd, b->ev_fork[0], 0));
-    if (gather && gather->table) {
+    // the dense copy of the bottom destinations' rows goes first when the forward pass waits for it, else last
+    // (then it runs next to the matrix products instead of next to the bandwidth-bound aggregation)
+    auto copy_rows = [&]() -> int32_t {
         const HopBuffers& lastg = b->hop[n_hops - 1];
         NO_CHECK(gather_rows(gather->table, gather->row_bytes, gather->row_bytes, lastg.src_global.p,
                              b->counts.p + 4 * (n_hops - 1), lastg.n_dst_cap, gather->out, gather->row_bytes, sd));
         NO_HIP_CHECK(hipEventRecord(b->ev_gather_done, sd));
-    }
+        return NO_OK;
+    };
+    const bool have_copy = gather && gather->table;
+    if (have_copy && gather->needed_by_forward) NO_CHECK(copy_rows());
     for (int32_t h = 0; h < n_hops; ++h) {
         HopBuffers& H = b->hop[h];
         int32_t* cnt = b->counts.p + 4 * h;
@@ -442,6 +447,7 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
                        last.indices.p, last.has_csc ? last.csc_cnt.p : nullptr);
     hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, T)), dim3(T), 0, sd,
                        (const int32_t*)last.src_global.p, d_n_src_last, b->map.p);
+    if (have_copy && !gather->needed_by_forward) NO_CHECK(copy_rows());
     b->side_pending = true;
     return launch_status("side work");
 }
