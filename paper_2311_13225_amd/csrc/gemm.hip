@@ -297,6 +297,107 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
         }
 }
 
+// Small products (few output tiles, e.g. the classifier layer over the seeds): a block owns a 32x32 output
+// tile and its four wavefronts split the reduction, chunk c of 32 indices going to wave c % 4. Operands go
+// from memory straight into MFMA registers with several chunks of loads in flight, so the product takes a
+// few memory round trips instead of one per 32 indices; the four partial tiles are summed in wave order
+// through LDS. Out-of-range rows and columns are clamped to valid addresses and dropped at the store.
+template <bool B_KC>
+__global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
+    __shared__ float red[4][16][64];
+    int M = *g.d_M;
+    if (M > g.M_cap) M = g.M_cap;
+    const int m0 = (int)blockIdx.y * 32, n0 = (int)blockIdx.x * 32;
+    if (m0 >= M) return;
+    const int prob = g.accumulate ? 0 : (int)blockIdx.z;
+    const int n_phases = g.accumulate ? g.n_problems : 1;
+    const int lane = (int)(threadIdx.x & 63), wave = (int)(threadIdx.x >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    const int row_c = min(m0 + l32, M - 1), col_c = min(n0 + l32, g.N - 1);
+    floatx16 acc, acc2;                       // two sets, so consecutive MFMAs of a round do not depend on each other
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = acc2[r] = 0.f;
+    int chunk_base = 0;                       // chunks of earlier phases
+    for (int ph = 0; ph < n_phases; ++ph) {
+        const int q = g.accumulate ? ph : prob;
+        const int K = g.K[q];
+        const float* A = g.A[q] + (int64_t)(g.a_rows[q] ? g.a_rows[q][row_c] : row_c) * g.lda[q];
+        const float* B = g.B[q];
+        const int64_t ldb = g.ldb[q];
+        const int n_chunks = (K + 31) / 32;
+        // first chunk of this phase that belongs to this wave
+        int c = ((wave - chunk_base) % 4 + 4) % 4;
+        for (; c + 4 < n_chunks && (c + 4) * 32 + 32 <= K; c += 8) {     // two full chunks per round
+            float4 av[2][4];
+            float bv[2][4][4];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int sc = 0; sc < 4; ++sc) {
+                    const int k = (c + 4 * u) * 32 + sc * 8 + half * 4;
+                    av[u][sc] = load4_fast(A + k);
+                    if (B_KC) {
+                        const float4 t = load4_fast(B + (int64_t)col_c * ldb + k);
+                        bv[u][sc][0] = t.x; bv[u][sc][1] = t.y; bv[u][sc][2] = t.z; bv[u][sc][3] = t.w;
+                    } else {
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) bv[u][sc][kk] = B[(int64_t)(k + kk) * ldb + col_c];
+                    }
+                }
+#pragma unroll
+            for (int sc = 0; sc < 4; ++sc) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[0][sc].x, bv[0][sc][0], acc, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[1][sc].x, bv[1][sc][0], acc2, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[0][sc].y, bv[0][sc][1], acc, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[1][sc].y, bv[1][sc][1], acc2, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[0][sc].z, bv[0][sc][2], acc, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[1][sc].z, bv[1][sc][2], acc2, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[0][sc].w, bv[0][sc][3], acc, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[1][sc].w, bv[1][sc][3], acc2, 0, 0, 0);
+            }
+        }
+        for (; c < n_chunks; c += 4) {                                    // remaining chunks, guarded in k
+#pragma unroll
+            for (int sc = 0; sc < 4; ++sc) {
+                const int k = c * 32 + sc * 8 + half * 4;
+                const float4 a4 = load4_guarded(A + k, K - k);
+                float b4[4];
+                if (B_KC) {
+                    const float4 t = load4_guarded(B + (int64_t)col_c * ldb + k, K - k);
+                    b4[0] = t.x; b4[1] = t.y; b4[2] = t.z; b4[3] = t.w;
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) b4[kk] = k + kk < K ? B[(int64_t)(k + kk) * ldb + col_c] : 0.f;
+                }
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4[0], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4[1], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4[2], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4[3], acc, 0, 0, 0);
+            }
+        }
+        chunk_base += n_chunks;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r] + acc2[r];
+    __syncthreads();
+    float* C = g.C[prob];
+    const int64_t ldc = g.ldc[prob];
+    const int32_t* sp = g.row_scale_indptr[prob];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = (int)threadIdx.x + 256 * i;
+        const int r = e >> 6, ln = e & 63;
+        const int row = m0 + acc_row(r, ln), col = n0 + (ln & 31);
+        if (row >= M || col >= g.N) continue;
+        float v = ((red[0][r][ln] + red[1][r][ln]) + red[2][r][ln]) + red[3][r][ln];
+        if (g.bias) v += g.bias[col];
+        if (g.relu) v = v > 0.f ? v : 0.f;
+        float scale = 1.f;
+        if (sp) { const int len = sp[row + 1] - sp[row]; scale = len > 0 ? 1.f / (float)len : 0.f; }
+        C[(int64_t)row * ldc + col] = v * scale;
+    }
+}
+
 // Largest tile that still gives the chip enough blocks, assuming about half the row capacity is used.
 static void pick_tile(int64_t rows_est, int64_t cols, int64_t batch, int* bm, int* bn) {
     // NO_GEMM_TILE=<bm>x<bn> pins the tile shape (tuning aid; both values in {64, 128})
@@ -327,6 +428,17 @@ static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st) {
 
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st) {
     if (a.M_cap <= 0 || a.N <= 0) return NO_OK;
+    const int64_t z = a.accumulate ? 1 : a.n_problems;
+    int64_t k_total = 0;
+    for (int q = 0; q < a.n_problems; ++q) k_total += a.K[q];
+    if (!a.accumulate) k_total /= a.n_problems;
+    static const char* no_small = getenv("NO_GEMM_NO_SMALL");      // tuning aid: keep small products on the tiled kernel
+    if (!no_small && ceil_div(a.M_cap, 64) * ceil_div(a.N, 64) * z <= 128 && k_total >= 128) {
+        dim3 grid((unsigned)ceil_div(a.N, 32), (unsigned)ceil_div(a.M_cap, 32), (unsigned)z);
+        if (b_transposed) hipLaunchKernelGGL((gemm_nn_small_kernel<true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((gemm_nn_small_kernel<false>), grid, dim3(256), 0, st, a);
+        return launch_status("gemm_nn_small");
+    }
     int bm, bn;
     // two LDS copies of a 128x128 tile pair in the padded layout exceed 64 KB: the forward product stops at 128x64
     pick_tile(a.M_est > 0 ? a.M_est : (a.M_cap + 1) / 2, a.N, a.accumulate ? 1 : a.n_problems, &bm, &bn);
