@@ -273,30 +273,48 @@ struct CacheProbe {
     int64_t step;
     int32_t staleness;
     // low word: 1 if the row must be computed; high word: 1 if it is computed AND hot (it will refresh its slot)
-    __device__ __forceinline__ int64_t operator()(int64_t i, int32_t* slot_out) const {
-        const int32_t s = slot_of_vertex[v1[i]];
-        *slot_out = s;
-        if (s < 0) return 1;
-        const int32_t ver = version[s];
+    __device__ __forceinline__ int64_t flags(int32_t slot, int32_t ver) const {
+        if (slot < 0) return 1;
         const bool hit = ver >= 0 && step - (int64_t)ver <= (int64_t)staleness;
         return hit ? 0 : (1ll + (1ll << 32));
     }
 };
 
+// Blocks [0, v1_blocks) probe the cache for a tile of V^1; the remaining blocks write the local indices of
+// the hop above (one edge per thread), which must be read out of the id map before the partition re-keys it:
+// sharing the launch keeps that pass off the dependency chain of the sampling.
 __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe, const int32_t* d_n_v1, int64_t* tile_sums,
-                                                                int32_t* probe_slot /* [n]: slot if served from the cache, else -1 */) {
+                                                                int32_t* __restrict__ probe_slot /* [n]: slot if served from the cache, else -1 */,
+                                                                uint32_t v1_blocks, const int32_t* d_nnz,
+                                                                const int32_t* __restrict__ nbr, const int32_t* map,
+                                                                int32_t* __restrict__ indices, int32_t* csc_cnt) {
+    if (blockIdx.x >= v1_blocks) {
+        const int32_t e = (int32_t)((blockIdx.x - v1_blocks) * ETHREADS + threadIdx.x);
+        if (e >= *d_nnz) return;
+        const int32_t local = map[nbr[e]];
+        indices[e] = local;
+        if (csc_cnt) atomicAdd(&csc_cnt[local], 1);     // integer count: order independent
+        return;
+    }
     const int64_t n = *d_n_v1;
     const int64_t base = (int64_t)blockIdx.x * ETILE;
     if (base >= n) return;
     __shared__ int64_t smem[ETHREADS / 64];
     const int64_t i0 = base + (int64_t)threadIdx.x * EITEMS;
+    // three dependent loads per vertex; each level is issued for all items before the next is needed
+    int32_t v[EITEMS], slot[EITEMS], ver[EITEMS];
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) v[t] = i0 + t < n ? probe.v1[i0 + t] : -1;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) slot[t] = v[t] >= 0 ? probe.slot_of_vertex[v[t]] : -1;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) ver[t] = slot[t] >= 0 ? probe.version[slot[t]] : -1;
     int64_t s = 0;
 #pragma unroll
     for (int t = 0; t < EITEMS; ++t) {
-        int32_t slot;
         if (i0 + t < n) {
-            const int64_t f = probe(i0 + t, &slot);
-            probe_slot[i0 + t] = (f & 1) ? -1 : slot;
+            const int64_t f = probe.flags(slot[t], ver[t]);
+            probe_slot[i0 + t] = (f & 1) ? -1 : slot[t];
             s += f;
         }
     }
@@ -334,13 +352,14 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
         tile_off = block_sum<int64_t, ETHREADS>(s, smem);
     }
     const int64_t i0 = base + (int64_t)threadIdx.x * EITEMS;
-    int32_t c[EITEMS], slot[EITEMS];
+    int32_t c[EITEMS], slot[EITEMS], vv[EITEMS];
     int64_t s = 0;
 #pragma unroll
     for (int t = 0; t < EITEMS; ++t) {
         c[t] = 0;
         slot[t] = -1;
-        if (i0 + t < n) { slot[t] = probe_slot[i0 + t]; c[t] = slot[t] < 0 ? 1 : 0; }
+        vv[t] = 0;
+        if (i0 + t < n) { slot[t] = probe_slot[i0 + t]; vv[t] = v1[i0 + t]; c[t] = slot[t] < 0 ? 1 : 0; }
         s += c[t];
     }
     int64_t total;
@@ -349,7 +368,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
     for (int t = 0; t < EITEMS; ++t) {
         const int64_t i = i0 + t;
         if (i < n) {
-            const int32_t v = v1[i];
+            const int32_t v = vv[t];
             if (c[t]) {
                 compute_pos[run] = (int32_t)i;
                 compute_list[run] = v;
@@ -374,7 +393,7 @@ static inline int64_t edge_tiles(int64_t n_pad_cap) { int64_t t = ceil_div(n_pad
 template <typename RowT>
 static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b, int32_t h, const int32_t* d_dst,
                           const int32_t* d_n_dst_in, int32_t n_fixed, bool insert_dst, uint32_t key0, uint32_t key1,
-                          uint32_t domain, hipStream_t st, bool last_hop) {
+                          uint32_t domain, hipStream_t st, bool indices_now) {
     HopBuffers& H = b->hop[h];
     int32_t* cnt = b->counts.p + 4 * h;              // n_dst, n_src, nnz
     const int32_t k = H.fanout;
@@ -402,7 +421,7 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     hipLaunchKernelGGL(edge_assign_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
                        (const int32_t*)cnt, k, k_magic, (const int64_t*)tile_sums, H.indptr.p, H.nbr_global.p, H.edge_row.p,
                        H.src_global.p, cnt);
-    if (!last_hop)
+    if (indices_now)
         hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st,
                            (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,
                            H.has_csc ? H.csc_cnt.p : nullptr);
@@ -410,10 +429,12 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
 }
 
 // Work that nothing on the caller's stream needs before the join, queued on the side stream behind ONE
-// fork event recorded after the last hop's ids are final: the transposes of the upper hops, the last hop's
-// local indices (the bottom layer aggregates through the global ids), and the wipe of the id map.
+// fork event recorded after the last hop's ids are final: the local indices of the hops that do not have
+// them yet (the bottom layer aggregates through the global ids; a vertex keeps its local id from the hop
+// that first saw it, so the map still answers for the hops above unless the cache split re-keyed it),
+// the transposes of the upper hops, and the wipe of the id map.
 static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d_n_src_last, hipStream_t st,
-                                const SideGather* gather) {
+                                const SideGather* gather, const bool* indices_done) {
     const int T = 256;
     hipStream_t sd = b->side;
     NO_HIP_CHECK(hipEventRecord(b->ev_fork[0], st));
@@ -432,6 +453,10 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
     for (int32_t h = 0; h < n_hops; ++h) {
         HopBuffers& H = b->hop[h];
         int32_t* cnt = b->counts.p + 4 * h;
+        if (!indices_done[h])
+            hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd,
+                               (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p,
+                               H.indices.p, H.has_csc ? H.csc_cnt.p : nullptr);
         if (!H.has_csc) continue;
         NO_CHECK(exclusive_scan2(ArrayLoader{H.csc_cnt.p}, cnt + 1, H.n_src_cap, H.csc_indptr.p, nullptr, b->ws_side.p, sd));
         hipLaunchKernelGGL(csc_fill_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd, (const int32_t*)(cnt + 2),
@@ -441,10 +466,6 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
                            (const int32_t*)H.edge_row.p, H.csc_eid.p, H.csc_dst.p);
     }
     HopBuffers& last = b->hop[n_hops - 1];
-    int32_t* cnt = b->counts.p + 4 * (n_hops - 1);
-    hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(last.nnz_cap, T)), dim3(T), 0, sd,
-                       (const int32_t*)(cnt + 2), (const int32_t*)last.nbr_global.p, (const int32_t*)b->map.p,
-                       last.indices.p, last.has_csc ? last.csc_cnt.p : nullptr);
     hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, T)), dim3(T), 0, sd,
                        (const int32_t*)last.src_global.p, d_n_src_last, b->map.p);
     if (have_copy && !gather->needed_by_forward) NO_CHECK(copy_rows());
@@ -471,32 +492,42 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
     const int32_t* d_n = nullptr;
     const bool use_cache = cache != nullptr && L >= 2 && n_hops == L && cache->n_hot > 0;
     b->last_used_cache = use_cache;
+    bool indices_done[NO_MAX_LAYERS] = {};
     for (int32_t h = 0; h < n_hops; ++h) {
         if (h == L - 1 && use_cache) {
-            // split V^1 (= sources of hop L-2) into reusable rows and rows to compute
+            // split V^1 (= sources of hop L-2) into reusable rows and rows to compute; the same launch writes
+            // hop L-2's local indices, which the re-keyed map could no longer give
             HopBuffers& P = b->hop[h - 1];
             CacheProbe probe{d_dst, cache->slot_of_vertex.p, cache->version.p, step, cache->staleness};
             const unsigned tiles = (unsigned)edge_tiles(P.n_src_cap);
+            const unsigned idx_blocks = (unsigned)ceil_div(P.nnz_cap, ETHREADS);
             int64_t* tile_sums = (int64_t*)b->ws.p;
-            hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, probe, d_n, tile_sums,
-                               b->probe_slot.p);
+            hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles + idx_blocks), dim3(ETHREADS), 0, st, probe, d_n, tile_sums,
+                               b->probe_slot.p, tiles, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2),
+                               (const int32_t*)P.nbr_global.p, (const int32_t*)b->map.p, P.indices.p,
+                               P.has_csc ? P.csc_cnt.p : nullptr);
+            indices_done[h - 1] = true;
             hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, d_dst,
                                (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->hit_pos.p,
                                b->hit_slot.p, extra);
             d_dst = b->compute_list.p;
             d_n = extra + 0;
         }
+        // with the cache split ahead, the hops above L-2 read the map before the split re-keys it; every other
+        // hop's indices wait for the side stream
+        const bool indices_now = use_cache && h < L - 2;
         if (g->rowptr_bits == 64)
             NO_CHECK(sample_hop<int64_t>(g->rowptr64.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st,
-                                         h == n_hops - 1));
+                                         indices_now));
         else
             NO_CHECK(sample_hop<int32_t>(g->rowptr32.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st,
-                                         h == n_hops - 1));
+                                         indices_now));
+        if (indices_now) indices_done[h] = true;
         d_dst = b->hop[h].src_global.p;
         d_n = b->counts.p + 4 * h + 1;
     }
     if (!use_cache) hipLaunchKernelGGL(set_counts_kernel, dim3(1), dim3(1), 0, st, extra, 0, 0, 0);
-    NO_CHECK(launch_side_work(b, n_hops, d_n, st, gather));
+    NO_CHECK(launch_side_work(b, n_hops, d_n, st, gather, indices_done));
     NO_CHECK(launch_status("sample_blocks"));
     if (join) NO_CHECK(blocks_join(b, st));
     return NO_OK;
