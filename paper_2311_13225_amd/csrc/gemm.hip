@@ -104,7 +104,7 @@ __device__ __forceinline__ float4 tile_frag(const float* S, int x, int chunk, in
 }
 
 // Number of independent accumulator sets per wave tile: with a single 32x32 accumulator every MFMA would
-// depend on the one before it, so small wave tiles keep two sets (even / odd chunks of 8 indices) that
+// depend on the one before it, so small wave tiles keep two sets (even / odd reduction indices) that
 // are summed in the epilogue; larger tiles already interleave 2-4 accumulators.
 template <int BM, int BN> struct AccSets { static constexpr int N = ((BM / 64) * (BN / 64) >= 4) ? 1 : 2; };
 
@@ -114,16 +114,23 @@ __device__ __forceinline__ void tile_mma(const float* As, const float* Bs,
     constexpr int MI = BM / 64, NI = BN / 64, SETS = AccSets<BM, BN>::N;
     const int lane = (int)(threadIdx.x & 63);
     const int half = lane >> 5, l32 = lane & 31;
+    // the fragments of chunk c + 1 are requested from LDS before the MFMAs of chunk c are issued, so the
+    // matrix pipe is not left idle for an LDS round trip between chunks
+    float4 a[2][MI], b[2][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) a[0][i] = tile_frag<A_KC, BM>(As, wm * (BM / 2) + i * 32 + l32, 0, half);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) b[0][i] = tile_frag<B_KC, BN>(Bs, wn * (BN / 2) + i * 32 + l32, 0, half);
 #pragma unroll
     for (int chunk = 0; chunk < BK / 8; ++chunk) {
-        float4 a[MI], b[NI];
+        const int cb = chunk & 1, nb = cb ^ 1;
+        if (chunk + 1 < BK / 8) {
 #pragma unroll
-        for (int i = 0; i < MI; ++i) a[i] = tile_frag<A_KC, BM>(As, wm * (BM / 2) + i * 32 + l32, chunk, half);
+            for (int i = 0; i < MI; ++i) a[nb][i] = tile_frag<A_KC, BM>(As, wm * (BM / 2) + i * 32 + l32, chunk + 1, half);
 #pragma unroll
-        for (int i = 0; i < NI; ++i) b[i] = tile_frag<B_KC, BN>(Bs, wn * (BN / 2) + i * 32 + l32, chunk, half);
-        constexpr int dummy = 0;
-        (void)dummy;
-        const int set = chunk % SETS;
+            for (int i = 0; i < NI; ++i) b[nb][i] = tile_frag<B_KC, BN>(Bs, wn * (BN / 2) + i * 32 + l32, chunk + 1, half);
+        }
+        __builtin_amdgcn_sched_barrier(0);      // keep the LDS reads ahead of this chunk's MFMAs
         // index-major order: consecutive MFMAs go to different accumulators
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
@@ -131,10 +138,12 @@ __device__ __forceinline__ void tile_mma(const float* As, const float* Bs,
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
-                    const float av = kk == 0 ? a[mi].x : kk == 1 ? a[mi].y : kk == 2 ? a[mi].z : a[mi].w;
-                    const float bv = kk == 0 ? b[ni].x : kk == 1 ? b[ni].y : kk == 2 ? b[ni].z : b[ni].w;
+                    const int set = kk % SETS;
+                    const float av = kk == 0 ? a[cb][mi].x : kk == 1 ? a[cb][mi].y : kk == 2 ? a[cb][mi].z : a[cb][mi].w;
+                    const float bv = kk == 0 ? b[cb][ni].x : kk == 1 ? b[cb][ni].y : kk == 2 ? b[cb][ni].z : b[cb][ni].w;
                     acc[set][mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[set][mi][ni], 0, 0, 0);
                 }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
