@@ -16,6 +16,11 @@ What it follows in the paper:
   * Section 4.1.2: hot vertices by pre-sampling frequency; a hot vertex's layer-1 embedding
     computed at step t0 may be reused at steps t with t - t0 <= S (S = bound in batches);
     a reused embedding gets no aggregation and no backward pass.
+  * Section 4.2 (Stage 2 and "Bounded Staleness"): n batches form a super-batch; while one
+    super-batch trains, the embeddings of ALL hot vertices are recomputed for the next one
+    (one-hop sample at the bottom fanout, layer-1 forward) and become the cache contents at the
+    super-batch boundary, so a row made with parameter version k*n serves steps (k+1)*n ...
+    (k+2)*n - 1: version gap at most 2n - 1 (`refresh_hot`, `train_superbatches`).
 """
 from __future__ import annotations
 
@@ -33,6 +38,7 @@ _LIB = os.path.join(_HERE, "libno_oracle.so")
 
 DOMAIN_TRAIN = 0
 DOMAIN_PRESAMPLE = 1
+DOMAIN_REFRESH = 2
 
 
 def build(force: bool = False) -> str:
@@ -429,3 +435,48 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
         cache.emb[slots[sel]] = hs[0][sb.compute_pos][sel]
         cache.version[slots[sel]] = step
     return StepResult(loss, sb, x0, hs, means, grads, new_w, 0 if not use_cache else len(sb.hit_pos))
+
+
+# --------------------------------------------------------------------------- bulk refresh (Section 4.2)
+
+def refresh_hot(g: Graph, feat: np.ndarray, cache: Cache, layer1_weights, fanout: int, version: int, seed: int,
+                feat_is_bf16: bool = False):
+    """Stage 2 of Section 4.2 for one super-batch: the layer-1 embedding of EVERY hot vertex, from a one-hop
+    sample at the bottom fanout and the given (snapshot of the) layer-1 parameters. Row i belongs to
+    hot_ids[i]. Returns the pending cache contents (emb [n_hot, d1] fp64, version [n_hot] = `version`);
+    they replace the cache at the next super-batch boundary (`commit_refresh`).
+    Sampling stream: Philox key seed + version, domain DOMAIN_REFRESH, hop 0."""
+    blk = sample_hop(g, cache.hot_ids, fanout, _u64(seed + version), DOMAIN_REFRESH, 0)
+    x = _to_f64(gather_features(feat, blk.src_global), feat_is_bf16)
+    w_self, w_neigh, bias = layer1_weights
+    _, h = sage_layer_fwd(blk, x, w_self, w_neigh, bias, relu=True)
+    return h, np.full(cache.n_hot, version, dtype=np.int32)
+
+
+def commit_refresh(cache: Cache, emb: np.ndarray, version: np.ndarray) -> None:
+    """Super-batch boundary: the pending rows become the cache contents."""
+    cache.emb[...] = emb
+    cache.version[...] = version
+
+
+def train_superbatches(g: Graph, feat: np.ndarray, labels: np.ndarray, batches: Sequence[np.ndarray],
+                       fanouts: Sequence[int], weights, lr: float, seed: int, cache: Cache, n: int,
+                       feat_is_bf16: bool = False, on_step=None):
+    """The schedule of Section 4.2 in its sequential meaning. At every step t with t % n == 0 the rows
+    computed during the previous super-batch are committed, then the refresh for the next super-batch is
+    computed from the parameters as they stand before step t (version t). Steps are Algorithm 1 with reuse
+    under the cache's bound S (S = 2n - 1 lets every committed row serve its whole super-batch).
+    Returns the list of StepResult and the final weights."""
+    pending = None
+    out = []
+    for t, seeds in enumerate(batches):
+        if t % n == 0:
+            if pending is not None:
+                commit_refresh(cache, *pending)
+            pending = refresh_hot(g, feat, cache, weights[0], fanouts[-1], t, seed, feat_is_bf16)
+        r = train_step(g, feat, labels, seeds, fanouts, weights, lr, seed, t, cache, feat_is_bf16)
+        if on_step is not None:
+            on_step(t, r, cache)
+        weights = r.new_weights
+        out.append(r)
+    return out, weights

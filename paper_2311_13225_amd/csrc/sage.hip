@@ -269,7 +269,8 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     // while x_src holds only the destination rows (fused gather + aggregate of the bottom layer). An fp32
     // table also feeds the self product directly, row m = table row src_global[m], so the forward pass
     // does not wait for the dense copy of the destination rows at all.
-    const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global;
+    static const char* no_direct = getenv("NO_SELF_FROM_COPY");      // tuning aid: self product reads the dense copy
+    const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global && !no_direct;
     if (prof && agg_stage >= 0) prof->begin(agg_stage);
     NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap,
                             mean, st));

@@ -275,7 +275,8 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
     sg.table = d_features;
     sg.row_bytes = row_bytes;
     sg.out = m->x0.p;
-    sg.needed_by_forward = m->feat_dtype != NO_F32;   // fp32: the forward product reads the table rows itself
+    static const char* no_direct = getenv("NO_SELF_FROM_COPY");
+    sg.needed_by_forward = m->feat_dtype != NO_F32 || no_direct;   // fp32: the forward product reads the table rows itself
     prof.begin(NO_STAGE_SAMPLE);
     NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg));
     prof.end();
