@@ -145,6 +145,34 @@ int32_t no_cache_set_staleness(no_cache_t c, int32_t staleness);
 int32_t no_cache_invalidate(no_cache_t c, void* stream);   /* all versions = -1 */
 int32_t no_cache_destroy(no_cache_t c);
 
+/* Bulk refresh of the hot embeddings for the next super-batch (Section 4.2: Stage 2, "Embedding computation
+ * for hot vertices", and "Bounded Staleness"). The paper lets the CPU do this while the GPU trains the n
+ * batches of the current super-batch; here it runs on a stream of its own on the same GPU.
+ *
+ * no_refresh_hot_begin: for every hot vertex v (slot order): min(deg(v), fanout) in-neighbours drawn like a
+ * bottom-hop destination (Philox stream seed + version, domain 2, hop 0), their mean, and
+ * relu(W_self^T x_v + W_neigh^T mean + b) (Eq. 1 / Eq. 2), into a PENDING copy of the cache stamped
+ * `version` (the parameter version = number of updates the given weights have seen). d_features is the
+ * [V, feat_dim] table (fp32 or bf16 bits), d_w_self / d_w_neigh [feat_dim, emb_dim] and d_bias [emb_dim]
+ * fp32 device arrays: they are copied in `stream` order before the call returns to the host, so later updates
+ * of them on `stream` do not race with the refresh; the table must stay unchanged until the commit. All other
+ * work runs on the cache's own stream (default priority) after that copy. The first call allocates the
+ * refresh buffers (a one-hop block over n_hot destinations, the mean rows, the pending rows) and fixes
+ * (dt, feat_dim, fanout) for later calls. Errors: NO_ERR_INVALID_ARG (NULL, bad sizes, another refresh still
+ * pending, parameters differing from the first call), NO_ERR_OVERFLOW (n_hot * (fanout + 1) >= 2^31),
+ * NO_ERR_HIP. A cache without hot vertices makes both calls no-ops.
+ *
+ * no_refresh_hot_commit: `stream` waits for the pending refresh, then the pending rows and versions
+ * become the cache's contents (the two copies are swapped: pointers returned by no_cache_view before the
+ * commit now name the other copy). Rows written by a step's own refresh-on-miss since the begin are
+ * replaced as well. Work already queued on `stream` keeps reading the previous copy. With the commit at
+ * every n-th step, begin right after it, and staleness bound 2n - 1, every hot vertex is served from the
+ * cache from the second super-batch on and the largest version gap is 2n - 1. */
+int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* d_features, no_dtype dt, int32_t feat_dim,
+                             const float* d_w_self, const float* d_w_neigh, const float* d_bias, int32_t fanout,
+                             int64_t version, uint64_t seed, void* stream);
+int32_t no_refresh_hot_commit(no_cache_t c, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Gather (feature collection, Algorithm 1 line 9)
  * ---------------------------------------------------------------------------------------- */

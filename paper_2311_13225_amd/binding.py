@@ -64,6 +64,8 @@ _SIGNATURES = {
     "no_cache_set_staleness": (_I32, [_P, _I32]),
     "no_cache_invalidate": (_I32, [_P, _P]),
     "no_cache_destroy": (_I32, [_P]),
+    "no_refresh_hot_begin": (_I32, [_P, _P, _P, _I32, _I32, _P, _P, _P, _I32, _I64, _U64, _P]),
+    "no_refresh_hot_commit": (_I32, [_P, _P]),
     "no_gather_features": (_I32, [_P, _I32, _I64, _I32, _I64, _P, _P, _I32, _P, _I64, _P]),
     "no_sage_layer_ws_bytes": (C.c_size_t, [_I32, _I32, _I32, _I32]),
     "no_sage_layer_fwd": (_I32, [_P, _P, _I32, _I32, _P, _P, _P, _I32, _I32, _P, _P, _P, C.c_size_t, _P]),
@@ -311,6 +313,22 @@ def no_cache_set_staleness(c: Cache, staleness: int):
 
 def no_cache_invalidate(c: Cache, stream=None):
     _check(lib().no_cache_invalidate(c.h, _stream(stream)))
+
+
+def no_refresh_hot_begin(c: Cache, g: Graph, features: torch.Tensor, w_self: torch.Tensor, w_neigh: torch.Tensor,
+                         bias: torch.Tensor, fanout: int, version: int, seed: int, stream=None):
+    """Starts the bulk refresh of all hot embeddings into the pending copy of the cache (own stream)."""
+    assert features.is_cuda and features.dim() == 2 and features.is_contiguous()
+    for t in (w_self, w_neigh, bias):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    _check(lib().no_refresh_hot_begin(c.h, g.h, features.data_ptr(), _dtype_code(features), features.shape[1],
+                                      w_self.data_ptr(), w_neigh.data_ptr(), bias.data_ptr(), fanout, version,
+                                      seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+
+
+def no_refresh_hot_commit(c: Cache, stream=None):
+    """The pending rows become the cache contents (views from no_cache_view taken earlier name the other copy)."""
+    _check(lib().no_refresh_hot_commit(c.h, _stream(stream)))
 
 
 # ------------------------------------------------------------------------------------------ gather

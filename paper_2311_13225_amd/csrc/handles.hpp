@@ -66,6 +66,30 @@ struct no_blocks_s {
     }
 };
 
+// Buffers of the bulk refresh (Section 4.2, Stage 2), created by the first no_refresh_hot_begin.
+struct RefreshState {
+    no_blocks_s* blocks = nullptr;         // one hop over all hot vertices
+    int32_t fanout = 0, feat_dim = 0;
+    no_dtype dt = NO_F32;
+    no::DevBuf<float> emb_pending;         // [n_hot, emb_dim]: swapped with the cache's rows at the commit
+    no::DevBuf<int32_t> version_pending;   // [n_hot]
+    no::DevBuf<float> snap;                // parameter snapshot: w_self, w_neigh, bias
+    no::DevBuf<float> mean;                // [n_hot, feat_dim]
+    no::DevBuf<char> x0;                   // bf16 tables only: the hot vertices' own rows
+    no::DevBuf<float> x_f32;               // bf16 tables only: the same rows in fp32
+    hipStream_t stream = nullptr;          // default priority, non-blocking
+    hipEvent_t ev_snap = nullptr, ev_done = nullptr;
+    bool pending = false;
+    void release() {
+        if (stream) { (void)hipStreamSynchronize(stream); (void)hipStreamDestroy(stream); stream = nullptr; }
+        if (ev_snap) { (void)hipEventDestroy(ev_snap); ev_snap = nullptr; }
+        if (ev_done) { (void)hipEventDestroy(ev_done); ev_done = nullptr; }
+        if (blocks) { blocks->release(); delete blocks; blocks = nullptr; }
+        emb_pending.release(); version_pending.release(); snap.release(); mean.release(); x0.release(); x_f32.release();
+        pending = false;
+    }
+};
+
 struct no_cache_s {
     int64_t n_vertices = 0;
     int64_t n_hot = 0;
@@ -73,7 +97,11 @@ struct no_cache_s {
     int32_t emb_dim = 0;
     no::DevBuf<int32_t> hot_ids, slot_of_vertex, version, freq;
     no::DevBuf<float> emb;
-    void release() { hot_ids.release(); slot_of_vertex.release(); version.release(); freq.release(); emb.release(); }
+    RefreshState* refresh = nullptr;
+    void release() {
+        if (refresh) { refresh->release(); delete refresh; refresh = nullptr; }
+        hot_ids.release(); slot_of_vertex.release(); version.release(); freq.release(); emb.release();
+    }
 };
 
 namespace no {

@@ -305,7 +305,7 @@ def test_sage_layer_empty_block_and_small_workspace():
 # --------------------------------------------------------------------------------------- whole step
 
 def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None, bits=32, presample=1,
-              n_train_presample=None):
+              n_train_presample=None, superbatch=0):
     b = nb()
     V = V or w.n_vertices
     E = E or w.n_edges
@@ -331,9 +331,18 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
     tlab = dev(lab)
     ow = [tuple(np.asarray(t, np.float64) for t in x) for x in weights]
     hits = 0
+    pending = None
     for step in range(n_steps):
         seeds = si.batch_seeds(train, w.batch, step)
         print("step", step, flush=True)
+        if superbatch and step % superbatch == 0:
+            # super-batch boundary (Section 4.2): install the rows refreshed during the last super-batch, then
+            # start the refresh for the next one from the parameters as they stand now
+            if pending is not None:
+                ora.commit_refresh(oc, *pending)
+                b.no_refresh_hot_commit(gc)
+            pending = ora.refresh_hot(og, feat, oc, ow[0], w.fanouts[-1], step, w.seed, feat_is_bf16=bf16)
+            b.no_refresh_hot_begin(gc, gg, tfeat, *b.no_model_params(model, 1), w.fanouts[-1], step, w.seed)
         st = b.no_train_step(model, gg, tfeat, tlab, dev(seeds), gc, step, w.seed, lr)
         ambiguous = []
 
@@ -434,6 +443,59 @@ def test_large_config_shape_scaled_bf16():
     """The large workload's shape (bf16 features, int64 row pointers, 3 layers, 172 classes) on a shrunken graph."""
     w = si.scaled(si.WORKLOADS["large"], 0.0005)
     assert run_steps(w, 4, use_cache=True, lr=0.01, bits=64) > 0
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_refresh_hot_rows_match_oracle(bf16):
+    """Bulk refresh (Section 4.2, Stage 2) alone: rows and versions of every hot vertex against the oracle; the
+    pending copy stays invisible until the commit; misuse is refused."""
+    b = nb()
+    V, E, F, D = 3000, 40_000, 70 if not bf16 else 64, 48
+    src, dst, og, gg = make_graph(V, E, 4, 32)
+    feat = si.features(V, F, 4, "bf16" if bf16 else "f32")
+    train = si.train_split(V, 0.65, 4)
+    (w_self, w_neigh, bias), = si.init_weights([F, D], 4)
+    fan = (5, 4)
+    oc = ora.select_hot(og, train, 64, fan, 1, 0.15, 3, D, 4)
+    gc = b.no_select_hot(gg, dev(train), 64, fan, 1, 0.15, 3, D, 4)
+    tfeat = dev(feat.view(np.int16) if bf16 else feat)
+    tw = [dev(w_self), dev(w_neigh), dev(bias)]
+    with pytest.raises(b.NoError):
+        b.no_refresh_hot_commit(gc)                       # nothing pending
+    b.no_refresh_hot_begin(gc, gg, tfeat, *tw, fan[-1], 6, 99)
+    tw[0].mul_(2.0)                                       # later updates on the stream do not reach the snapshot
+    with pytest.raises(b.NoError):
+        b.no_refresh_hot_begin(gc, gg, tfeat, *tw, fan[-1], 7, 99)    # one refresh at a time
+    torch.cuda.synchronize()
+    view = b.no_cache_view(gc, V)
+    assert (view["version"] == -1).all() and (view["emb"] == 0).all()     # not installed yet
+    b.no_refresh_hot_commit(gc)
+    emb, ver = ora.refresh_hot(og, feat, oc, (w_self, w_neigh, bias), fan[-1], 6, 99, feat_is_bf16=bf16)
+    view = b.no_cache_view(gc, V)
+    assert np.array_equal(view["version"].cpu().numpy(), ver)
+    assert_close(view["emb"].cpu().numpy(), emb, "refreshed rows")
+    with pytest.raises(b.NoError):
+        b.no_refresh_hot_begin(gc, gg, tfeat, *tw, fan[-1] + 1, 8, 99)      # buffers were sized for another fanout
+    # a second round lands in the other copy and replaces the first at its commit
+    tw[0].copy_(dev(w_self))
+    b.no_refresh_hot_begin(gc, gg, tfeat, *tw, fan[-1], 9, 99)
+    b.no_refresh_hot_commit(gc)
+    emb2, ver2 = ora.refresh_hot(og, feat, oc, (w_self, w_neigh, bias), fan[-1], 9, 99, feat_is_bf16=bf16)
+    view = b.no_cache_view(gc, V)
+    assert np.array_equal(view["version"].cpu().numpy(), ver2)
+    assert_close(view["emb"].cpu().numpy(), emb2, "refreshed rows, second round")
+    assert not np.array_equal(emb, emb2)
+
+
+def test_superbatch_schedule_with_bulk_refresh():
+    """n = 3 batches per super-batch, bound 2n - 1 = 5: every step against the oracle walking the same schedule;
+    from the second super-batch on every hot vertex of V^1 is served from the cache."""
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=5, hot_fraction=0.2)
+    assert run_steps(w, 9, use_cache=True, lr=0.02, superbatch=3) > 0
+    w3 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(4, 3, 3), staleness=3, hot_fraction=0.3, n_classes=47,
+                             feat_dim=100, hidden=40, batch=128, feat_dtype="bf16")
+    assert run_steps(w3, 6, use_cache=True, lr=0.02, bits=64, superbatch=2) > 0
 
 
 def test_cache_invalidate_and_set_staleness():
