@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--no-cache", action="store_true", help="exact training (no hot-embedding reuse)")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: auto, 0: skip)")
     ap.add_argument("--presample-epochs", type=int, default=3)
+    ap.add_argument("--superbatch", type=int, default=4,
+                    help="also time the super-batch schedule: bulk refresh of all hot rows every n steps on a second "
+                         "stream, bound 2n-1 (0 = skip)")
     ap.add_argument("--presample-batches", type=int, default=0,
                     help="pre-sample hotness on the first N batches of the train split only (0: all)")
     ap.add_argument("--device-features", action="store_true",
@@ -143,6 +146,54 @@ def main():
     steps_per_s = K / elapsed
     log("[bench] %d steps in %.3fs -> %.1f steps/s (%.3f ms/step)" % (K, elapsed, steps_per_s, ms_per_step))
 
+    # ---- pass 1b: the super-batch schedule of Section 4.2 (reported in `extra`, never as `value`): every n steps the
+    # rows refreshed during the last super-batch are committed and the refresh for the next one starts on the
+    # cache's own stream; bound 2n - 1, so from the second super-batch on every hot vertex of V^1 is served
+    superbatch = None
+    if cache is not None and args.superbatch > 0 and w.n_layers >= 2:
+        n_sb = args.superbatch
+        load_weights()
+        b.no_cache_invalidate(cache)
+        b.no_cache_set_staleness(cache, 2 * n_sb - 1)
+        w1 = b.no_model_params(model, 1)
+
+        def run_sb(first, count, want_stats=False):
+            out = []
+            for t in range(first, first + count):
+                if t % n_sb == 0:
+                    if t > 0:
+                        b.no_refresh_hot_commit(cache)
+                    b.no_refresh_hot_begin(cache, g, tfeat, *w1, w.fanouts[-1], t, w.seed)
+                out.append(b.no_train_step(model, g, tfeat, tlab, seed_batches[t], cache, t, w.seed, args.lr,
+                                           want_stats=want_stats))
+            return out
+
+        W_sb = max(W, 2 * n_sb) // n_sb * n_sb         # warm-up ends on a boundary, past the first super-batch
+        K_sb = min(K, W + K - W_sb)
+        run_sb(0, W_sb - n_sb)
+        sb_stats = run_sb(W_sb - n_sb, n_sb, want_stats=True)       # last warm-up super-batch: hit statistics
+        sb_hit = sum(s_.n_hit for s_ in sb_stats) / max(1.0, float(sum(s_.n_v1 for s_ in sb_stats)))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_sb(W_sb, K_sb)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        b.no_refresh_hot_commit(cache)                  # leave nothing pending
+        torch.cuda.synchronize()
+        # refresh alone (begin + commit back to back on an idle GPU)
+        t0 = time.perf_counter()
+        for _ in range(5):
+            b.no_refresh_hot_begin(cache, g, tfeat, *w1, w.fanouts[-1], 0, w.seed)
+            b.no_refresh_hot_commit(cache)
+        torch.cuda.synchronize()
+        refresh_ms = (time.perf_counter() - t0) * 1e3 / 5
+        superbatch = {"n": n_sb, "staleness": 2 * n_sb - 1, "steps_per_s": round(K_sb / el, 2),
+                      "ms_per_step": round(el * 1e3 / K_sb, 4), "timed_steps": K_sb,
+                      "cache_hit_rate": round(sb_hit, 4), "refresh_alone_ms": round(refresh_ms, 3), "n_hot": int(b.no_cache_view(cache, w.n_vertices)["n_hot"])}
+        log("[bench] super-batch schedule n=%d: %.1f steps/s (%.3f ms/step), refresh alone %.3f ms" %
+            (n_sb, K_sb / el, el * 1e3 / K_sb, refresh_ms))
+        b.no_cache_set_staleness(cache, w.staleness)
+
     # ---- pass 2: same steps again with per-stage events and per-step statistics
     load_weights()
     if cache is not None:
@@ -226,6 +277,7 @@ def main():
         "profiled_ms_per_step": round(sum(v for k, v in per_step.items() if k != "gather"), 4),
         "setup_s": {"build_csr": round(t_csr, 2), "select_hot": round(t_hot, 2)},
         "loss_after_last_step": round(float(loss_last), 5),
+        "superbatch_schedule": superbatch,
     }
     log("[bench] stage ms/step: " + ", ".join("%s=%.3f" % kv for kv in per_step.items()))
 
