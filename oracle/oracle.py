@@ -12,7 +12,8 @@ What it follows in the paper:
     features, L forward layers, loss, L backward layers, one parameter update.
   * Eq. 1 / Eq. 2: AGGREGATE = average over sampled in-neighbours, UPDATE = dense layer.
     GraphSAGE-mean reading: h_v = act(W_self^T h_v + W_neigh^T mean_u h_u + b); ReLU between
-    layers, none on the logits.
+    layers, none on the logits. GCN-style reading (arch "gcn"): Eq. 1 as printed, the average over
+    N_in(v) U {v} of the sampled block, then h_v = act(W^T a_v + b).
   * Section 4.1.2: hot vertices by pre-sampling frequency; a hot vertex's layer-1 embedding
     computed at step t0 may be reused at steps t with t - t0 <= S (S = bound in batches);
     a reused embedding gets no aggregation and no backward pass.
@@ -348,6 +349,57 @@ def sage_layer_bwd(blk: Block, x_src: np.ndarray, mean: np.ndarray, h: np.ndarra
     return gw_self, gw_neigh, gb, gx
 
 
+def gcn_aggregate(x_src: np.ndarray, indptr: np.ndarray, indices: np.ndarray, n_dst: int) -> np.ndarray:
+    """Eq. 1 as printed, AGGREGATE = average over N_in(v) U {v}: a_v = (x_v + sum of the sampled row) / (len + 1).
+    Destination v is source row v of the block."""
+    x = np.asarray(x_src, dtype=np.float64)
+    ln = np.diff(np.asarray(indptr[: n_dst + 1], dtype=np.int64))
+    out = x[:n_dst].copy()
+    rows = np.repeat(np.arange(n_dst), ln)
+    np.add.at(out, rows, x[np.asarray(indices[: ln.sum()], dtype=np.int64)])
+    return out / (ln + 1.0)[:, None]
+
+
+def gcn_aggregate_adjoint(grad_a: np.ndarray, indptr: np.ndarray, indices: np.ndarray, n_dst: int,
+                          n_src: int) -> np.ndarray:
+    g = np.asarray(grad_a, dtype=np.float64)
+    ln = np.diff(np.asarray(indptr[: n_dst + 1], dtype=np.int64))
+    gs = g / (ln + 1.0)[:, None]
+    out = np.zeros((n_src, g.shape[1]), dtype=np.float64)
+    out[:n_dst] += gs
+    rows = np.repeat(np.arange(n_dst), ln)
+    np.add.at(out, np.asarray(indices[: ln.sum()], dtype=np.int64), gs[rows])
+    return out
+
+
+def gcn_layer_fwd_z(blk: Block, x_src: np.ndarray, w, bias, relu: bool):
+    """GCN-style layer: Eq. 1 over N_in(v) U {v} (average), Eq. 2 with one weight matrix. Returns (a, z, h)."""
+    a = gcn_aggregate(x_src, blk.indptr, blk.indices, blk.n_dst)
+    z = a @ np.asarray(w, np.float64) + np.asarray(bias, np.float64)
+    h = np.maximum(z, 0.0) if relu else z
+    return a, z, h
+
+
+def gcn_layer_fwd(blk: Block, x_src: np.ndarray, w, bias, relu: bool):
+    a, _, h = gcn_layer_fwd_z(blk, x_src, w, bias, relu)
+    return a, h
+
+
+def gcn_layer_bwd(blk: Block, a: np.ndarray, h: np.ndarray, grad_h: np.ndarray, w, relu: bool, need_grad_x: bool,
+                  active: Optional[np.ndarray] = None):
+    """Gradients of the GCN-style layer: (gw, gb, grad_x or None)."""
+    if relu:
+        gz = np.asarray(grad_h, np.float64) * ((np.asarray(h) > 0) if active is None else active)
+    else:
+        gz = np.asarray(grad_h, np.float64)
+    gw = np.asarray(a, np.float64).T @ gz
+    gb = gz.sum(axis=0)
+    gx = None
+    if need_grad_x:
+        gx = gcn_aggregate_adjoint(gz @ np.asarray(w, np.float64).T, blk.indptr, blk.indices, blk.n_dst, blk.n_src)
+    return gw, gb, gx
+
+
 def softmax_xent(logits: np.ndarray, labels: np.ndarray):
     """Mean softmax cross-entropy over the batch and its gradient w.r.t. the logits."""
     z = np.asarray(logits, np.float64)
@@ -383,8 +435,10 @@ def _to_f64(x: np.ndarray, feat_is_bf16: bool) -> np.ndarray:
 
 def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray, fanouts: Sequence[int],
                weights, lr: float, seed: int, step: int, cache: Optional[Cache] = None,
-               feat_is_bf16: bool = False, relu_decisions=None) -> StepResult:
+               feat_is_bf16: bool = False, relu_decisions=None, arch: str = "sage") -> StepResult:
     """One pass of Algorithm 1's loop body with plain SGD; updates `cache` in place.
+    arch "sage": GraphSAGE-mean layers, weights[l] = (w_self, w_neigh, bias); arch "gcn": layers that average
+    over N_in(v) U {v} with one matrix, weights[l] = (w, bias); `mean` then holds that aggregate.
     relu_decisions: optional callable(layer, z_layer) -> bool array or None, consulted in the backward
     pass for the ReLU decisions of layer `layer` given its pre-activations (rows of the computed vertices)."""
     L = len(fanouts)
@@ -396,9 +450,12 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
     use_cache = cache is not None and L >= 2
     for l in range(1, L + 1):
         blk = sb.blocks[L - l]
-        w_self, w_neigh, bias = weights[l - 1]
         xs.append(x)
-        mean, z, h = sage_layer_fwd_z(blk, x, w_self, w_neigh, bias, relu=(l < L))
+        if arch == "gcn":
+            mean, z, h = gcn_layer_fwd_z(blk, x, weights[l - 1][0], weights[l - 1][1], relu=(l < L))
+        else:
+            w_self, w_neigh, bias = weights[l - 1]
+            mean, z, h = sage_layer_fwd_z(blk, x, w_self, w_neigh, bias, relu=(l < L))
         means.append(mean)
         zs.append(z)
         if l == 1 and use_cache:
@@ -415,18 +472,22 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
     grads = [None] * L
     for l in range(L, 0, -1):
         blk = sb.blocks[L - l]
-        w_self, w_neigh, _ = weights[l - 1]
         h_l = hs[l - 1]
         if l == 1 and use_cache:
             h_l = h_l[sb.compute_pos]
             gh = gh[sb.compute_pos]        # reused rows take no gradient
         active = relu_decisions(l, zs[l - 1]) if (relu_decisions is not None and l < L) else None
-        gws, gwn, gb, gx = sage_layer_bwd(blk, xs[l - 1], means[l - 1], h_l, gh, w_self, w_neigh,
-                                          relu=(l < L), need_grad_x=(l > 1), active=active)
-        grads[l - 1] = (gws, gwn, gb)
+        if arch == "gcn":
+            gw, gb, gx = gcn_layer_bwd(blk, means[l - 1], h_l, gh, weights[l - 1][0], relu=(l < L),
+                                       need_grad_x=(l > 1), active=active)
+            grads[l - 1] = (gw, gb)
+        else:
+            w_self, w_neigh, _ = weights[l - 1]
+            gws, gwn, gb, gx = sage_layer_bwd(blk, xs[l - 1], means[l - 1], h_l, gh, w_self, w_neigh,
+                                              relu=(l < L), need_grad_x=(l > 1), active=active)
+            grads[l - 1] = (gws, gwn, gb)
         gh = gx
-    new_w = [(np.asarray(w[0], np.float64) - lr * gr[0], np.asarray(w[1], np.float64) - lr * gr[1],
-              np.asarray(w[2], np.float64) - lr * gr[2]) for w, gr in zip(weights, grads)]
+    new_w = [tuple(np.asarray(p, np.float64) - lr * q for p, q in zip(w, gr)) for w, gr in zip(weights, grads)]
     if use_cache:
         # every computed hot vertex refreshes its slot with the embedding made by step-t weights
         v1_computed = bottom.dst_global
@@ -448,8 +509,11 @@ def refresh_hot(g: Graph, feat: np.ndarray, cache: Cache, layer1_weights, fanout
     Sampling stream: Philox key seed + version, domain DOMAIN_REFRESH, hop 0."""
     blk = sample_hop(g, cache.hot_ids, fanout, _u64(seed + version), DOMAIN_REFRESH, 0)
     x = _to_f64(gather_features(feat, blk.src_global), feat_is_bf16)
-    w_self, w_neigh, bias = layer1_weights
-    _, h = sage_layer_fwd(blk, x, w_self, w_neigh, bias, relu=True)
+    if len(layer1_weights) == 2:          # GCN-style layer: (w, bias)
+        _, h = gcn_layer_fwd(blk, x, layer1_weights[0], layer1_weights[1], relu=True)
+    else:
+        w_self, w_neigh, bias = layer1_weights
+        _, h = sage_layer_fwd(blk, x, w_self, w_neigh, bias, relu=True)
     return h, np.full(cache.n_hot, version, dtype=np.int32)
 
 
@@ -461,7 +525,7 @@ def commit_refresh(cache: Cache, emb: np.ndarray, version: np.ndarray) -> None:
 
 def train_superbatches(g: Graph, feat: np.ndarray, labels: np.ndarray, batches: Sequence[np.ndarray],
                        fanouts: Sequence[int], weights, lr: float, seed: int, cache: Cache, n: int,
-                       feat_is_bf16: bool = False, on_step=None):
+                       feat_is_bf16: bool = False, on_step=None, arch: str = "sage"):
     """The schedule of Section 4.2 in its sequential meaning. At every step t with t % n == 0 the rows
     computed during the previous super-batch are committed, then the refresh for the next super-batch is
     computed from the parameters as they stand before step t (version t). Steps are Algorithm 1 with reuse
@@ -474,7 +538,7 @@ def train_superbatches(g: Graph, feat: np.ndarray, labels: np.ndarray, batches: 
             if pending is not None:
                 commit_refresh(cache, *pending)
             pending = refresh_hot(g, feat, cache, weights[0], fanouts[-1], t, seed, feat_is_bf16)
-        r = train_step(g, feat, labels, seeds, fanouts, weights, lr, seed, t, cache, feat_is_bf16)
+        r = train_step(g, feat, labels, seeds, fanouts, weights, lr, seed, t, cache, feat_is_bf16, arch=arch)
         if on_step is not None:
             on_step(t, r, cache)
         weights = r.new_weights
