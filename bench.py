@@ -48,6 +48,8 @@ def main():
                     help="generate the feature table in device memory (implied for tables over 2^31 elements); "
                          "the CPU baseline is skipped then")
     ap.add_argument("--lr", type=float, default=0.01)
+    ap.add_argument("--arch", choices=["sage", "gcn"], default="sage",
+                    help="layer form: GraphSAGE-mean (the headline configuration) or the GCN-style layer")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain copy of known size (1,000,000 rows x 1024 B through no_gather_features with "
                          "ids 0..n-1): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -116,6 +118,9 @@ def main():
         t_hot = time.time() - t0
         log("[bench] no_select_hot (%d pre-sampling epochs): %.2fs" % (args.presample_epochs, t_hot))
     model = b.no_model_create(g, w.dims, w.batch, w.fanouts, b.NO_BF16 if bf16 else b.NO_F32)
+    gcn = args.arch == "gcn"
+    if gcn:
+        b.no_model_set_arch(model, b.NO_ARCH_GCN)
 
     def load_weights():
         for l in range(w.n_layers):
@@ -163,7 +168,7 @@ def main():
                 if t % n_sb == 0:
                     if t > 0:
                         b.no_refresh_hot_commit(cache)
-                    b.no_refresh_hot_begin(cache, g, tfeat, *w1, w.fanouts[-1], t, w.seed)
+                    b.no_refresh_hot_begin(cache, g, tfeat, w1[0], None if gcn else w1[1], w1[2], w.fanouts[-1], t, w.seed)
                 out.append(b.no_train_step(model, g, tfeat, tlab, seed_batches[t], cache, t, w.seed, args.lr,
                                            want_stats=want_stats))
             return out
@@ -183,7 +188,7 @@ def main():
         # refresh alone (begin + commit back to back on an idle GPU)
         t0 = time.perf_counter()
         for _ in range(5):
-            b.no_refresh_hot_begin(cache, g, tfeat, *w1, w.fanouts[-1], 0, w.seed)
+            b.no_refresh_hot_begin(cache, g, tfeat, w1[0], None if gcn else w1[1], w1[2], w.fanouts[-1], 0, w.seed)
             b.no_refresh_hot_commit(cache)
         torch.cuda.synchronize()
         refresh_ms = (time.perf_counter() - t0) * 1e3 / 5
@@ -238,7 +243,7 @@ def main():
     gather_bytes = n_src_last * (4 + 2 * F * es)
     del gout
     agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4     # compulsory traffic (each row once)
-    gemm_fwd_flops = 2.0 * n_dst_bottom * (2 * F) * w.dims[1]
+    gemm_fwd_flops = 2.0 * n_dst_bottom * ((1 if gcn else 2) * F) * w.dims[1]
     gemm_dw_flops = gemm_fwd_flops
     kern = {
         "gather_rows_kernel": ("hbm", gather_bytes / 1e9 / (per_step["gather"] / 1e3), HBM_PEAK_GBPS, "GB/s", per_step["gather"]),
@@ -299,11 +304,11 @@ def main():
             oc = ora.select_hot(og, pre_h, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
                                 w.hidden, w.seed)
         log("[bench] oracle setup (CSR + hot set): %.1fs" % (time.time() - t0))
-        ow = [tuple(np.asarray(t, np.float64) for t in x) for x in weights]
+        ow = [tuple(np.asarray(t, np.float64) for t in ((x[0], x[2]) if gcn else x)) for x in weights]
         # one untimed step to estimate the cost, then time as many as fit in ~20 s (at least 2)
         t0 = time.perf_counter()
         r = ora.train_step(og, feat, lab, si.batch_seeds(train, w.batch, 0), w.fanouts, ow, args.lr, w.seed, 0, oc,
-                           feat_is_bf16=bf16)
+                           feat_is_bf16=bf16, arch=args.arch)
         one = time.perf_counter() - t0
         ow = r.new_weights
         if cpu_steps < 0:
@@ -311,7 +316,7 @@ def main():
         t0 = time.perf_counter()
         for t in range(1, 1 + cpu_steps):
             r = ora.train_step(og, feat, lab, si.batch_seeds(train, w.batch, t), w.fanouts, ow, args.lr, w.seed, t, oc,
-                               feat_is_bf16=bf16)
+                               feat_is_bf16=bf16, arch=args.arch)
             ow = r.new_weights
         cpu_elapsed = time.perf_counter() - t0
         cpu = {"value": round(cpu_steps / cpu_elapsed, 4), "unit": "steps/s", "cores": int(blas_threads), "kind": "oracle",
@@ -324,9 +329,9 @@ def main():
         "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: R-MAT %d vertices / %d directed edges, %d x %s features, %d classes, %d-layer "
-                               "GraphSAGE-mean hidden %d, fanout %s, batch %d, hot %.0f%%, S=%d"
+                               "%s hidden %d, fanout %s, batch %d, hot %.0f%%, S=%d"
                                % (w.name, w.n_vertices, len(src), w.feat_dim, w.feat_dtype, w.n_classes, w.n_layers,
-                                  w.hidden, list(w.fanouts), w.batch, 0.0 if cache is None else 100 * w.hot_fraction,
+                                  "GCN-style" if gcn else "GraphSAGE-mean", w.hidden, list(w.fanouts), w.batch, 0.0 if cache is None else 100 * w.hot_fraction,
                                   w.staleness),
                    "hot_reuse": cache is not None},
         "roofline": roofline, "cpu_baseline": cpu, "extra": extra,

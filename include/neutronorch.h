@@ -38,6 +38,9 @@ enum {
 };
 
 typedef enum { NO_F32 = 0, NO_BF16 = 1 } no_dtype;
+/* Layer form: GraphSAGE-mean (separate self path, two matrices) or GCN-style (Eq. 1 as printed: the average runs
+ * over N_in(v) U {v}; Eq. 2 with one matrix). */
+typedef enum { NO_ARCH_SAGE_MEAN = 0, NO_ARCH_GCN = 1 } no_arch;
 
 enum { NO_MAX_LAYERS = 8, NO_MAX_FANOUT = 64 };
 
@@ -160,7 +163,8 @@ int32_t no_cache_destroy(no_cache_t c);
  * refresh buffers (a one-hop block over n_hot destinations, the mean rows, the pending rows) and fixes
  * (dt, feat_dim, fanout) for later calls. Errors: NO_ERR_INVALID_ARG (NULL, bad sizes, another refresh still
  * pending, parameters differing from the first call), NO_ERR_OVERFLOW (n_hot * (fanout + 1) >= 2^31),
- * NO_ERR_HIP. A cache without hot vertices makes both calls no-ops.
+ * NO_ERR_HIP. A cache without hot vertices makes both calls no-ops. d_w_neigh == NULL selects the GCN-style
+ * layer (one matrix d_w_self, average over N_in(v) U {v}).
  *
  * no_refresh_hot_commit: `stream` waits for the pending refresh, then the pending rows and versions
  * become the cache's contents (the two copies are swapped: pointers returned by no_cache_view before the
@@ -211,6 +215,19 @@ int32_t no_sage_layer_bwd(const no_block_view* blk, const void* d_x_src, no_dtyp
                           float* d_gw_self, float* d_gw_neigh, float* d_gbias, float* d_grad_x_src,
                           void* d_ws, size_t ws_bytes, void* stream);
 
+/* GCN-style layer (Eq. 1 as printed, AGGREGATE = average over N_in(v) U {v}; Eq. 2 with one matrix).
+ * Forward: d_agg[v,:] = (d_x_src[v,:] + sum of d_x_src[indices[e],:] over row v) / (len(row v) + 1) (destination
+ * v is source row v); d_h = act(d_agg * W + bias). Shapes, dtypes, workspace and errors as no_sage_layer_fwd.
+ * Backward: gz as above; d_gw = agg^T gz, d_gbias = column sums of gz; if d_grad_x_src != NULL:
+ * with ga[v,:] = (gz[v,:] W^T) / (len(row v) + 1): d_grad_x_src[u,:] = [u < n_dst] ga[u,:] + sum of ga[v,:] over the
+ * transposed entries (v,e) of u. The workspace size is no_sage_layer_ws_bytes. */
+int32_t no_gcn_layer_fwd(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+                         const float* d_w, const float* d_bias, int32_t d_out, int32_t relu, float* d_agg,
+                         float* d_h, void* d_ws, size_t ws_bytes, void* stream);
+int32_t no_gcn_layer_bwd(const no_block_view* blk, int32_t d_in, const float* d_agg, const float* d_h,
+                         const float* d_grad_h, const float* d_w, int32_t d_out, int32_t relu, float* d_gw,
+                         float* d_gbias, float* d_grad_x_src, void* d_ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Whole step (loop body of Algorithm 1 with plain SGD, plus hot-embedding reuse)
  * ---------------------------------------------------------------------------------------- */
@@ -230,6 +247,11 @@ int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t* h_dims, i
                         const int32_t* h_fanouts, no_dtype feat_dtype, no_model_t* out);
 int32_t no_model_params(no_model_t m, int32_t layer /*1-based*/, float** d_w_self, float** d_w_neigh,
                         float** d_bias);
+/* Selects the layer form of every layer (default NO_ARCH_SAGE_MEAN); call before the first step. With
+ * NO_ARCH_GCN layer l computes h = act(W^T a + b), a_v = (x_v + sum of the sampled row) / (len + 1) (Eq. 1 over
+ * N_in(v) U {v}, AGGREGATE = average; Eq. 2): W is the layer's w_self array, w_neigh and its gradient are unused,
+ * the `mean` activation holds a, and no_model_gathered is not filled (the aggregation reads the table itself). */
+int32_t no_model_set_arch(no_model_t m, no_arch arch);
 /* Gradients of the last step, device pointers (same shapes as the parameters). */
 int32_t no_model_grads(no_model_t m, int32_t layer, float** d_gw_self, float** d_gw_neigh, float** d_gbias);
 /* Activations of the last step: d_h fp32 [rows, dims[layer]] (layer 1 with a cache: all of V^1),

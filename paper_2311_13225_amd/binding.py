@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libneutronorch.so")
 
 NO_F32, NO_BF16 = 0, 1
+NO_ARCH_SAGE_MEAN, NO_ARCH_GCN = 0, 1
 NO_CSR_INPUT_ON_DEVICE = 1
 NO_MAX_LAYERS = 8
 ERROR_NAMES = {0: "NO_OK", -1: "NO_ERR_INVALID_ARG", -2: "NO_ERR_OUT_OF_RANGE", -3: "NO_ERR_CAPACITY",
@@ -74,6 +75,9 @@ _SIGNATURES = {
     "no_model_create": (_I32, [_P, _I32, _P, _I32, _P, _I32, _P]),
     "no_model_params": (_I32, [_P, _I32, _P, _P, _P]),
     "no_model_grads": (_I32, [_P, _I32, _P, _P, _P]),
+    "no_model_set_arch": (_I32, [_P, _I32]),
+    "no_gcn_layer_fwd": (_I32, [_P, _P, _I32, _I32, _P, _P, _I32, _I32, _P, _P, _P, C.c_size_t, _P]),
+    "no_gcn_layer_bwd": (_I32, [_P, _I32, _P, _P, _P, _P, _I32, _I32, _P, _P, _P, _P, C.c_size_t, _P]),
     "no_model_activations": (_I32, [_P, _I32, _P, _P]),
     "no_model_blocks": (_I32, [_P, _P]),
     "no_model_gathered": (_I32, [_P, _P]),
@@ -320,9 +324,10 @@ def no_refresh_hot_begin(c: Cache, g: Graph, features: torch.Tensor, w_self: tor
     """Starts the bulk refresh of all hot embeddings into the pending copy of the cache (own stream)."""
     assert features.is_cuda and features.dim() == 2 and features.is_contiguous()
     for t in (w_self, w_neigh, bias):
-        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+        assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous())
     _check(lib().no_refresh_hot_begin(c.h, g.h, features.data_ptr(), _dtype_code(features), features.shape[1],
-                                      w_self.data_ptr(), w_neigh.data_ptr(), bias.data_ptr(), fanout, version,
+                                      w_self.data_ptr(), None if w_neigh is None else w_neigh.data_ptr(),
+                                      bias.data_ptr(), fanout, version,
                                       seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
 
 
@@ -381,6 +386,23 @@ def no_sage_layer_bwd(blk: no_block_view, x_src: torch.Tensor, mean: torch.Tenso
                                    _ptr(grad_x_src), ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)))
 
 
+def no_gcn_layer_fwd(blk: no_block_view, x_src: torch.Tensor, w: torch.Tensor, bias: torch.Tensor, relu: bool,
+                     agg: torch.Tensor, h: torch.Tensor, ws: torch.Tensor, stream=None):
+    d_in, d_out = w.shape
+    _check(lib().no_gcn_layer_fwd(C.byref(blk), x_src.data_ptr(), _dtype_code(x_src), d_in, w.data_ptr(), bias.data_ptr(),
+                                  d_out, 1 if relu else 0, agg.data_ptr(), h.data_ptr(), ws.data_ptr(),
+                                  ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def no_gcn_layer_bwd(blk: no_block_view, agg: torch.Tensor, h: torch.Tensor, grad_h: torch.Tensor, w: torch.Tensor,
+                     relu: bool, gw: torch.Tensor, gbias: torch.Tensor, grad_x_src: Optional[torch.Tensor],
+                     ws: torch.Tensor, stream=None):
+    d_in, d_out = w.shape
+    _check(lib().no_gcn_layer_bwd(C.byref(blk), d_in, agg.data_ptr(), h.data_ptr(), grad_h.data_ptr(), w.data_ptr(), d_out,
+                                  1 if relu else 0, gw.data_ptr(), gbias.data_ptr(), _ptr(grad_x_src), ws.data_ptr(),
+                                  ws.numel() * ws.element_size(), _stream(stream)))
+
+
 # ------------------------------------------------------------------------------------------ model / step
 
 def no_model_create(g: Graph, dims: Sequence[int], n_seeds_cap: int, fanouts: Sequence[int],
@@ -391,6 +413,12 @@ def no_model_create(g: Graph, dims: Sequence[int], n_seeds_cap: int, fanouts: Se
     m = Model(out)
     m.n_layers, m.dims, m.feat_dtype = len(fanouts), [int(d) for d in dims], feat_dtype
     return m
+
+
+def no_model_set_arch(m: Model, arch: int):
+    """NO_ARCH_SAGE_MEAN (default) or NO_ARCH_GCN for every layer; call before the first step."""
+    _check(lib().no_model_set_arch(m.h, arch))
+    m.arch = arch
 
 
 def _three(fn, m: Model, layer: int):

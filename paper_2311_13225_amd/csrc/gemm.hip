@@ -293,7 +293,7 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
             const int row = m0 + wm * (BM / 2) + mi * 32 + acc_row(r, lane);
             if (row >= M) continue;
             float scale = 1.f;
-            if (sp) { int len = sp[row + 1] - sp[row]; scale = len > 0 ? 1.f / (float)len : 0.f; }
+            if (sp) { int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale = len > 0 ? 1.f / (float)len : 0.f; }
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
                 const int col = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
@@ -402,7 +402,7 @@ __global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
         if (g.bias) v += g.bias[col];
         if (g.relu) v = v > 0.f ? v : 0.f;
         float scale = 1.f;
-        if (sp) { const int len = sp[row + 1] - sp[row]; scale = len > 0 ? 1.f / (float)len : 0.f; }
+        if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale = len > 0 ? 1.f / (float)len : 0.f; }
         C[(int64_t)row * ldc + col] = v * scale;
     }
 }
@@ -516,7 +516,7 @@ int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st) {
         int fm = 0, fn = 0;
         if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128)) { bm = fm; bn = fn; }
     }
-    dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.Kp + 1, bm), (unsigned)(2 * a.splits));
+    dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.Kp + 1, bm), (unsigned)(a.n_problems * a.splits));
     if (bm == 128 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<128, 128>), grid, dim3(256), 0, st, a);
     else if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<64, 128>), grid, dim3(256), 0, st, a);
     else if (bm == 128 && bn == 64) hipLaunchKernelGGL((gemm_tn_kernel<128, 64>), grid, dim3(256), 0, st, a);
@@ -547,9 +547,9 @@ __global__ void reduce_grads_kernel(const float* __restrict__ P, int32_t splits,
 }
 
 int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
-                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st) {
+                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems) {
     const int64_t per = (int64_t)(Kp + 1) * N;
-    hipLaunchKernelGGL(reduce_grads_kernel, dim3((unsigned)ceil_div(per, 256), 2), dim3(256), 0, st, P, splits, Kp, N, g_self,
+    hipLaunchKernelGGL(reduce_grads_kernel, dim3((unsigned)ceil_div(per, 256), (unsigned)n_problems), dim3(256), 0, st, P, splits, Kp, N, g_self,
                        g_neigh, g_bias, lr, w_self, w_neigh, w_bias);
     return launch_status("reduce_grads");
 }

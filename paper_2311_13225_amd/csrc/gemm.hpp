@@ -16,7 +16,8 @@ struct GemmNNArgs {
     const float* B[2]; int64_t ldb[2]; int b_align[2];
     int32_t K[2];
     float* C[2]; int64_t ldc[2];
-    const int32_t* row_scale_indptr[2];   // per problem: multiply row m by 1/(indptr[m+1]-indptr[m]) (0 if empty)
+    const int32_t* row_scale_indptr[2];   // per problem: multiply row m by 1/(indptr[m+1]-indptr[m]+row_scale_plus) (0 if that is 0)
+    int32_t row_scale_plus;               // 1 when the row itself counts in the average (Eq. 1 over N_in(v) U {v})
     int32_t n_problems;                   // 1 or 2
     int32_t accumulate;                   // 1: both products are summed into C[0]; 0: independent problems (grid.z)
     const int32_t* d_M; int32_t M_cap; int32_t N;
@@ -30,13 +31,14 @@ struct GemmTNArgs {
     float* P;                                            // partials [2][splits][Kp+1][N]; row Kp of product 0 = column sums of G
     int32_t Kp, N;
     const int32_t* d_R; int32_t R_cap; int32_t splits;
+    int32_t n_problems = 2;                              // 1: only A[0]
 };
 
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st);
 int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st);
 // Sums the partials in split order into the three gradients; with lr != 0 also applies W <- W - lr * g.
 int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
-                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st);
+                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems = 2);
 
 inline int ptr_align(const void* p, int64_t ld) {
     if ((((uintptr_t)p) & 15) == 0 && (ld & 3) == 0) return 4;

@@ -40,22 +40,25 @@ struct LayerWorkspace {
 int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out);
 LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_t d_out);
 
+// with_self: the destination's own row (row r of x_src, or row self_idx[r]) joins the average (Eq. 1 over N_in(v) U {v})
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
-                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st);
+                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, bool with_self = false,
+                       const int32_t* self_idx = nullptr);
 int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
                             const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
                             hipStream_t st);
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int agg_stage = -1,
-                     int gemm_stage = -1, const void* agg_table = nullptr, hipEvent_t wait_before_gemm = nullptr);
+                     int gemm_stage = -1, const void* agg_table = nullptr, hipEvent_t wait_before_gemm = nullptr,
+                     int32_t arch = NO_ARCH_SAGE_MEAN);
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int prep_stage = -1,
                       int dw_stage = -1, int reduce_stage = -1, int dx_stage = -1,
                       const int32_t* grad_rows = nullptr, float lr = 0.f, float* w_self_rw = nullptr,
-                      float* w_neigh_rw = nullptr, float* bias_rw = nullptr);
+                      float* w_neigh_rw = nullptr, float* bias_rw = nullptr, int32_t arch = NO_ARCH_SAGE_MEAN);
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
                     const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
 

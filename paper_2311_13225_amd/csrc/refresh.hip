@@ -41,7 +41,8 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
                                         const float* d_w_self, const float* d_w_neigh, const float* d_bias, int32_t fanout,
                                         int64_t version, uint64_t seed, void* stream) {
     clear_error();
-    NO_REQUIRE(c && g && d_features && d_w_self && d_w_neigh && d_bias, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: NULL argument");
+    NO_REQUIRE(c && g && d_features && d_w_self && d_bias, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: NULL argument");
+    const int32_t arch = d_w_neigh ? NO_ARCH_SAGE_MEAN : NO_ARCH_GCN;       // one matrix: the GCN-style layer
     NO_REQUIRE(dt == NO_F32 || dt == NO_BF16, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: unknown dtype");
     NO_REQUIRE(feat_dim >= 1, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: feat_dim must be positive");
     NO_REQUIRE(fanout >= 1 && fanout <= NO_MAX_FANOUT, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: bad fanout");
@@ -64,15 +65,16 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
     float* w_neigh = w_self + (size_t)feat_dim * d_out;
     float* bias = w_neigh + (size_t)feat_dim * d_out;
     NO_HIP_CHECK(hipMemcpyAsync(w_self, d_w_self, (size_t)feat_dim * d_out * 4, hipMemcpyDeviceToDevice, st));
-    NO_HIP_CHECK(hipMemcpyAsync(w_neigh, d_w_neigh, (size_t)feat_dim * d_out * 4, hipMemcpyDeviceToDevice, st));
+    if (d_w_neigh)
+        NO_HIP_CHECK(hipMemcpyAsync(w_neigh, d_w_neigh, (size_t)feat_dim * d_out * 4, hipMemcpyDeviceToDevice, st));
     NO_HIP_CHECK(hipMemcpyAsync(bias, d_bias, (size_t)d_out * 4, hipMemcpyDeviceToDevice, st));
     NO_HIP_CHECK(hipEventRecord(r->ev_snap, st));
     NO_HIP_CHECK(hipStreamWaitEvent(r->stream, r->ev_snap, 0));
 
-    const bool bf16 = dt == NO_BF16;
+    const bool bf16 = dt == NO_BF16 && arch == NO_ARCH_SAGE_MEAN;    // only the separate self path needs the rows' own copy
     SideGather sg;
     sg.table = d_features;
-    sg.row_bytes = feat_dim * (bf16 ? 2 : 4);
+    sg.row_bytes = feat_dim * (dt == NO_BF16 ? 2 : 4);
     sg.out = r->x0.p;
     sg.needed_by_forward = true;
     NO_CHECK(sample_blocks_impl(g, c->hot_ids.p, n_hot, seed + (uint64_t)version, 2u, 1, nullptr, 0, r->blocks, r->stream, true,
@@ -84,7 +86,7 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
     w.x_dst_f32 = bf16 ? r->x_f32.p : nullptr;
     NO_CHECK(sage_forward(view, bf16 ? (const void*)r->x0.p : d_features, dt, feat_dim, w_self, w_neigh, bias, d_out, 1,
                           r->mean.p, r->emb_pending.p, w, r->stream, nullptr, -1, -1, d_features,
-                          bf16 ? r->blocks->ev_gather_done : nullptr));
+                          bf16 ? r->blocks->ev_gather_done : nullptr, arch));
     NO_CHECK(fill_i32(r->version_pending.p, (int32_t)version, n_hot, r->stream));
     NO_HIP_CHECK(hipEventRecord(r->ev_done, r->stream));
     r->pending = true;

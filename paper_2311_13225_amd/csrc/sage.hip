@@ -52,7 +52,8 @@ template <> struct RowVec<uint16_t, 1> {
 };
 
 // out[row, :] = init + scale * sum_{p in [seg[row], seg[row+1])} src[idx[p], :]
-//   MEAN: scale = 1/len (0 for an empty segment), init = 0            (forward aggregate)
+//   MEAN: scale = 1/len (0 for an empty segment), init = 0            (forward aggregate); with_self: the
+//         row's own source row is added first and scale = 1/(len + 1)
 //   else: scale = 1, init = out[row,:] for row < *d_n_init, else 0    (backward through the transpose)
 // A group of G = 2^g_log2 lanes owns one work item = (row, chunk of G vector units); a lane owns one
 // vector unit of it. Rows wider than 64 units are split into several items handled by different
@@ -64,7 +65,8 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__
                                                            const int32_t* __restrict__ seg, const int32_t* __restrict__ idx,
                                                            const int32_t* d_n_rows, int32_t n_rows_cap,
                                                            const int32_t* d_n_init, float* __restrict__ out, int64_t ld_out,
-                                                           int32_t units, int32_t g_log2, int32_t n_chunks) {
+                                                           int32_t units, int32_t g_log2, int32_t n_chunks,
+                                                           const int32_t* __restrict__ self_idx, int32_t with_self) {
     int32_t n = *d_n_rows;
     if (n > n_rows_cap) n = n_rows_cap;
     const int32_t n_init = (!MEAN && d_n_init) ? *d_n_init : 0;
@@ -79,11 +81,16 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__
         const int32_t u = (int32_t)(item - row * n_chunks) * (1 << g_log2) + u0;
         if (u >= units) continue;
         const int32_t b = seg[row], e = seg[row + 1];
-        const float scale = MEAN ? (e > b ? 1.f / (float)(e - b) : 0.f) : 1.f;
+        float scale = MEAN ? (e > b ? 1.f / (float)(e - b) : 0.f) : 1.f;
         const T* col = src + (int64_t)u * VEC;
         float acc[VEC];
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+        if (MEAN && with_self) {
+            // Eq. 1 over N_in(v) U {v}: the destination's own row (row `row` of src, or self_idx[row]) joins the average
+            RowVec<T, VEC>::add(acc, col + (int64_t)(self_idx ? self_idx[row] : (int32_t)row) * ld_src);
+            scale = 1.f / (float)(e - b + 1);
+        }
         float* o = out + row * ld_out + (int64_t)u * VEC;
         if (!MEAN && row < n_init) {
 #pragma unroll
@@ -143,7 +150,8 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__
 
 template <typename T, int VEC, bool MEAN>
 static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, const int32_t* idx, const int32_t* d_n,
-                           int32_t n_cap, const int32_t* d_n_init, float* out, int64_t ld_out, int32_t dim, hipStream_t st) {
+                           int32_t n_cap, const int32_t* d_n_init, float* out, int64_t ld_out, int32_t dim, hipStream_t st,
+                           const int32_t* self_idx = nullptr, int32_t with_self = 0) {
     const int32_t units = dim / VEC;
     int g_log2 = 0;
     while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
@@ -153,25 +161,27 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
     if (blocks > 256 * 64) blocks = 256 * 64;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)blocks), dim3(256), 0, st, src, ld_src, seg, idx, d_n,
-                       n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks);
+                       n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, with_self);
 }
 
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
-                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st) {
+                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, bool with_self,
+                       const int32_t* self_idx) {
     if (n_dst_cap <= 0) return NO_OK;
+    const int32_t ws = with_self ? 1 : 0;
     if (dt == NO_F32) {
         const float* x = (const float*)x_src;
         const bool a16 = (((uintptr_t)x | (uintptr_t)mean) & 15) == 0, a8 = (((uintptr_t)x | (uintptr_t)mean) & 7) == 0;
-        if (dim % 4 == 0 && a16) launch_segment<float, 4, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
-        else if (dim % 2 == 0 && a8) launch_segment<float, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
-        else launch_segment<float, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+        if (dim % 4 == 0 && a16) launch_segment<float, 4, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
+        else if (dim % 2 == 0 && a8) launch_segment<float, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
+        else launch_segment<float, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
     } else {
         const uint16_t* x = (const uint16_t*)x_src;
         if (dim % 8 == 0 && ((uintptr_t)x & 15) == 0 && ((uintptr_t)mean & 15) == 0)
-            launch_segment<uint16_t, 8, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+            launch_segment<uint16_t, 8, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
         else if (dim % 2 == 0 && ((uintptr_t)x & 3) == 0)
-            launch_segment<uint16_t, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
-        else launch_segment<uint16_t, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st);
+            launch_segment<uint16_t, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
+        else launch_segment<uint16_t, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
     }
     return launch_status("mean_aggregate");
 }
@@ -264,7 +274,26 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
-                     const void* agg_table, hipEvent_t wait_before_gemm) {
+                     const void* agg_table, hipEvent_t wait_before_gemm, int32_t arch) {
+    if (arch == NO_ARCH_GCN) {
+        // Eq. 1 over N_in(v) U {v} (the destination's own row joins the average), Eq. 2 with one matrix
+        if (prof && agg_stage >= 0) prof->begin(agg_stage);
+        NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
+                                blk.n_dst_cap, mean, st, true, agg_table ? blk.d_src_global : nullptr));
+        if (prof && agg_stage >= 0) prof->end();
+        GemmNNArgs a{};
+        a.A[0] = mean; a.lda[0] = d_in; a.a_align[0] = ptr_align(mean, d_in);
+        a.B[0] = w_self; a.ldb[0] = d_out; a.b_align[0] = ptr_align(w_self, d_out);
+        a.K[0] = d_in;
+        a.C[0] = h; a.ldc[0] = d_out;
+        a.n_problems = 1; a.accumulate = 1;
+        a.d_M = blk.d_n_dst; a.M_cap = blk.n_dst_cap; a.N = d_out;
+        a.bias = bias; a.relu = relu;
+        if (prof && gemm_stage >= 0) prof->begin(gemm_stage);
+        int32_t rc = gemm_nn(a, false, st);
+        if (prof && gemm_stage >= 0) prof->end();
+        return rc;
+    }
     // agg_table != NULL: the rows to average are rows of that table addressed by blk.d_indices (global ids),
     // while x_src holds only the destination rows (fused gather + aggregate of the bottom layer). An fp32
     // table also feeds the self product directly, row m = table row src_global[m], so the forward pass
@@ -273,7 +302,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global && !no_direct;
     if (prof && agg_stage >= 0) prof->begin(agg_stage);
     NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap,
-                            mean, st));
+                            mean, st, false, nullptr));
     if (prof && agg_stage >= 0) prof->end();
     if (wait_before_gemm && !direct_self)
         NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
@@ -305,7 +334,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int prep_stage, int dw_stage,
                       int reduce_stage, int dx_stage, const int32_t* grad_rows, float lr, float* w_self_rw,
-                      float* w_neigh_rw, float* bias_rw) {
+                      float* w_neigh_rw, float* bias_rw, int32_t arch) {
+    const bool gcn = arch == NO_ARCH_GCN;
     const int32_t n_cap = blk.n_dst_cap;
     if (prof && prep_stage >= 0) prof->begin(prep_stage);
     const float* gz = grad_h;
@@ -315,7 +345,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
         gz = w.gz;
     }
     const float* x_dst = (const float*)x_src;
-    if (dt == NO_BF16) {
+    if (dt == NO_BF16 && !gcn) {
         hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)n_cap * d_in)), dim3(256), 0, st,
                            (const uint16_t*)x_src, blk.d_n_dst, n_cap, d_in, w.x_dst_f32);
         x_dst = w.x_dst_f32;
@@ -333,6 +363,13 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
         a.C[0] = grad_x_src; a.ldc[0] = d_in;
         a.C[1] = w.gmean;    a.ldc[1] = d_in;
         a.row_scale_indptr[1] = blk.d_indptr;
+        if (gcn) {
+            // one matrix: gz W^T / (len + 1) is both the destination's own share (rows [0, n_dst) of grad_x) and
+            // what the transpose spreads over the sampled sources
+            a.B[1] = w_self; a.b_align[1] = a.b_align[0];
+            a.row_scale_indptr[0] = blk.d_indptr;
+            a.row_scale_plus = 1;
+        }
         a.n_problems = 2; a.accumulate = 0;
         a.d_M = blk.d_n_dst; a.M_cap = n_cap; a.N = d_in;
         NO_CHECK(gemm_nn(a, true, st));
@@ -345,6 +382,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     GemmTNArgs t{};
     t.A[0] = x_dst; t.lda[0] = d_in; t.a_align[0] = ptr_align(x_dst, d_in);
     t.A[1] = mean;  t.lda[1] = d_in; t.a_align[1] = ptr_align(mean, d_in);
+    if (gcn) { t.A[0] = mean; t.a_align[0] = t.a_align[1]; t.n_problems = 1; }
     t.G = gz; t.ldg = d_out; t.g_align = ptr_align(gz, d_out);
     t.P = w.partials; t.Kp = d_in; t.N = d_out;
     t.d_R = blk.d_n_dst; t.R_cap = n_cap; t.splits = w.splits;
@@ -352,7 +390,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     NO_CHECK(gemm_tn_partials(t, st));
     if (prof && dw_stage >= 0) prof->end();
     if (prof && reduce_stage >= 0) prof->begin(reduce_stage);
-    NO_CHECK(reduce_grads(w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, st));
+    NO_CHECK(reduce_grads(w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, st,
+                          gcn ? 1 : 2));
     if (prof && reduce_stage >= 0) prof->end();
     return launch_status("sage_backward");
 }
@@ -406,4 +445,33 @@ extern "C" int32_t no_sage_layer_bwd(const no_block_view* blk, const void* d_x_s
                ws_bytes, w.bytes);
     return sage_backward(*blk, d_x_src, dt_x, d_in, d_mean, d_h, d_grad_h, d_w_self, d_w_neigh, d_out, relu, d_gw_self,
                          d_gw_neigh, d_gbias, d_grad_x_src, w, (hipStream_t)stream);
+}
+
+extern "C" int32_t no_gcn_layer_fwd(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+                                    const float* d_w, const float* d_bias, int32_t d_out, int32_t relu, float* d_agg,
+                                    float* d_h, void* d_ws, size_t ws_bytes, void* stream) {
+    clear_error();
+    NO_CHECK(check_layer_args(blk, d_x_src, dt_x, d_in, d_out, "no_gcn_layer_fwd"));
+    NO_REQUIRE(d_w && d_bias && d_agg && d_h, NO_ERR_INVALID_ARG, "no_gcn_layer_fwd: NULL argument");
+    LayerWorkspace w = carve_workspace(d_ws, blk->n_dst_cap, d_in, d_out);
+    NO_REQUIRE(d_ws != nullptr && ws_bytes >= w.bytes, NO_ERR_CAPACITY, "no_gcn_layer_fwd: workspace too small (%zu < %zu)",
+               ws_bytes, w.bytes);
+    return sage_forward(*blk, d_x_src, dt_x, d_in, d_w, nullptr, d_bias, d_out, relu, d_agg, d_h, w, (hipStream_t)stream,
+                        nullptr, -1, -1, nullptr, nullptr, NO_ARCH_GCN);
+}
+
+extern "C" int32_t no_gcn_layer_bwd(const no_block_view* blk, int32_t d_in, const float* d_agg, const float* d_h,
+                                    const float* d_grad_h, const float* d_w, int32_t d_out, int32_t relu, float* d_gw,
+                                    float* d_gbias, float* d_grad_x_src, void* d_ws, size_t ws_bytes, void* stream) {
+    clear_error();
+    NO_CHECK(check_layer_args(blk, d_agg, NO_F32, d_in, d_out, "no_gcn_layer_bwd"));
+    NO_REQUIRE(d_h && d_grad_h && d_w && d_gw && d_gbias, NO_ERR_INVALID_ARG, "no_gcn_layer_bwd: NULL argument");
+    NO_REQUIRE(!d_grad_x_src || (blk->d_csc_indptr && blk->d_csc_dst && blk->d_n_src), NO_ERR_INVALID_ARG,
+               "no_gcn_layer_bwd: input gradient requested but the block has no transpose");
+    LayerWorkspace w = carve_workspace(d_ws, blk->n_dst_cap, d_in, d_out);
+    NO_REQUIRE(d_ws != nullptr && ws_bytes >= w.bytes, NO_ERR_CAPACITY, "no_gcn_layer_bwd: workspace too small (%zu < %zu)",
+               ws_bytes, w.bytes);
+    return sage_backward(*blk, d_agg, NO_F32, d_in, d_agg, d_h, d_grad_h, d_w, nullptr, d_out, relu, d_gw, nullptr, d_gbias,
+                         d_grad_x_src, w, (hipStream_t)stream, nullptr, -1, -1, -1, -1, nullptr, 0.f, nullptr, nullptr, nullptr,
+                         NO_ARCH_GCN);
 }

@@ -26,6 +26,7 @@ struct no_model_s {
     no::DevBuf<float> row_loss;
     no::DevBuf<no_step_stats> stats;
     bool last_used_cache = false;
+    int32_t arch = NO_ARCH_SAGE_MEAN;
     no::StageProfiler prof;
     void release() {
         if (prof.created) { for (auto& e : prof.ev) (void)hipEventDestroy(e); prof.created = false; }
@@ -210,6 +211,14 @@ extern "C" int32_t no_model_params(no_model_t m, int32_t layer, float** d_w_self
     return NO_OK;
 }
 
+extern "C" int32_t no_model_set_arch(no_model_t m, no_arch arch) {
+    clear_error();
+    NO_REQUIRE(m != nullptr, NO_ERR_INVALID_ARG, "no_model_set_arch: model is NULL");
+    NO_REQUIRE(arch == NO_ARCH_SAGE_MEAN || arch == NO_ARCH_GCN, NO_ERR_INVALID_ARG, "no_model_set_arch: unknown layer form");
+    m->arch = arch;
+    return NO_OK;
+}
+
 extern "C" int32_t no_model_grads(no_model_t m, int32_t layer, float** d_gw_self, float** d_gw_neigh, float** d_gbias) {
     clear_error();
     NO_CHECK(check_layer_index(m, layer, "no_model_grads"));
@@ -272,7 +281,7 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
     const int32_t es = m->feat_dtype == NO_F32 ? 4 : 2;
     const int32_t row_bytes = m->dims[0] * es;
     SideGather sg;
-    sg.table = d_features;
+    sg.table = m->arch == NO_ARCH_GCN ? nullptr : d_features;    // GCN-style layers read every row inside the aggregation
     sg.row_bytes = row_bytes;
     sg.out = m->x0.p;
     static const char* no_direct = getenv("NO_SELF_FROM_COPY");
@@ -304,11 +313,12 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
             fused.d_indices = blk.d_nbr_global;
             NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
-                                  NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features, B->ev_gather_done));
+                                  NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features,
+                                  m->arch == NO_ARCH_GCN ? nullptr : B->ev_gather_done, m->arch));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
-                              l == 1 ? &prof : nullptr, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1));
+                              l == 1 ? &prof : nullptr, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, nullptr, nullptr, m->arch));
         if (l == L && L >= 2) prof.end();
         if (l == 1 && used_cache) {
             prof.begin(NO_STAGE_FWD_UPPER);
@@ -355,7 +365,7 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
                                m->grads.p + m->off_bias[l - 1], l > 1 ? m->gh[l - 2].p : nullptr, w, st,
                                l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
                                -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
-                               m->params.p + m->off_bias[l - 1]));
+                               m->params.p + m->off_bias[l - 1], m->arch));
     }
 
     // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;

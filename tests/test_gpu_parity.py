@@ -305,7 +305,7 @@ def test_sage_layer_empty_block_and_small_workspace():
 # --------------------------------------------------------------------------------------- whole step
 
 def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None, bits=32, presample=1,
-              n_train_presample=None, superbatch=0):
+              n_train_presample=None, superbatch=0, arch="sage"):
     b = nb()
     V = V or w.n_vertices
     E = E or w.n_edges
@@ -316,9 +316,13 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
     weights = si.init_weights(w.dims, w.seed)
     bf16 = w.feat_dtype == "bf16"
     model = b.no_model_create(gg, w.dims, w.batch, w.fanouts, b.NO_BF16 if bf16 else b.NO_F32)
+    gcn = arch == "gcn"
+    if gcn:
+        b.no_model_set_arch(model, b.NO_ARCH_GCN)
     for l in range(w.n_layers):
         for t, a in zip(b.no_model_params(model, l + 1), weights[l]):
             t.copy_(dev(a))
+    pick = (lambda three: (three[0], three[2])) if gcn else (lambda three: three)     # GCN-style: (w, bias)
     frac = w.hot_fraction if hot_fraction is None else hot_fraction
     oc = gc = None
     if use_cache:
@@ -329,7 +333,7 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
         assert np.array_equal(b.no_cache_view(gc, V)["hot_ids"].cpu().numpy(), oc.hot_ids)
     tfeat = dev(feat.view(np.int16) if bf16 else feat)
     tlab = dev(lab)
-    ow = [tuple(np.asarray(t, np.float64) for t in x) for x in weights]
+    ow = [tuple(np.asarray(t, np.float64) for t in pick(x)) for x in weights]
     hits = 0
     pending = None
     for step in range(n_steps):
@@ -342,7 +346,8 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
                 ora.commit_refresh(oc, *pending)
                 b.no_refresh_hot_commit(gc)
             pending = ora.refresh_hot(og, feat, oc, ow[0], w.fanouts[-1], step, w.seed, feat_is_bf16=bf16)
-            b.no_refresh_hot_begin(gc, gg, tfeat, *b.no_model_params(model, 1), w.fanouts[-1], step, w.seed)
+            p1 = b.no_model_params(model, 1)
+            b.no_refresh_hot_begin(gc, gg, tfeat, p1[0], None if gcn else p1[1], p1[2], w.fanouts[-1], step, w.seed)
         st = b.no_train_step(model, gg, tfeat, tlab, dev(seeds), gc, step, w.seed, lr)
         ambiguous = []
 
@@ -364,7 +369,7 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
             return gh > 0
 
         r = ora.train_step(og, feat, lab, seeds, w.fanouts, ow, lr, w.seed, step, oc, feat_is_bf16=bf16,
-                           relu_decisions=relu_decisions)
+                           relu_decisions=relu_decisions, arch=arch)
         # integers: block sizes, blocks, hits
         blocks = b.no_model_blocks(model)
         sizes = compare_blocks(b, blocks, r.batch, with_cache=use_cache and w.n_layers >= 2 and oc.n_hot > 0)
@@ -374,8 +379,9 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
         hits += r.n_hit
         # gathered rows (the step materialises the bottom destinations' rows; the rest is read in place): bit copy
         n_dst_bottom = r.batch.blocks[-1].n_dst
-        x0 = b.no_model_gathered(model, n_dst_bottom).cpu().numpy()
-        assert np.array_equal(x0.view(feat.dtype), r.x0[:n_dst_bottom])
+        if not gcn:
+            x0 = b.no_model_gathered(model, n_dst_bottom).cpu().numpy()
+            assert np.array_equal(x0.view(feat.dtype), r.x0[:n_dst_bottom])
         # floats
         assert abs(st.loss - r.loss) <= RTOL * abs(r.loss) + 1e-6, (st.loss, r.loss)
         for l in range(1, w.n_layers + 1):
@@ -384,10 +390,11 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
             gh, gm = b.no_model_activations(model, l, n_rows, n_dst)
             assert_close(gm.cpu().numpy(), r.mean[l - 1], "mean%d step %d" % (l, step))
             assert_close(gh.cpu().numpy(), r.h[l - 1], "h%d step %d" % (l, step))
-            for t, ref, name in zip(b.no_model_grads(model, l), r.grads[l - 1], ["gw_self", "gw_neigh", "gbias"]):
+            names = ["gw", "gbias"] if gcn else ["gw_self", "gw_neigh", "gbias"]
+            for t, ref, name in zip(pick(b.no_model_grads(model, l)), r.grads[l - 1], names):
                 assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step))
-            for t, ref, name in zip(b.no_model_params(model, l), r.new_weights[l - 1], ["w_self", "w_neigh", "bias"]):
-                assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step))
+            for t, ref, name in zip(pick(b.no_model_params(model, l)), r.new_weights[l - 1], names):
+                assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name[1:], l, step))
         ow = r.new_weights
         if use_cache and oc.n_hot > 0:
             view = b.no_cache_view(gc, V)
@@ -496,6 +503,66 @@ def test_superbatch_schedule_with_bulk_refresh():
     w3 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(4, 3, 3), staleness=3, hot_fraction=0.3, n_classes=47,
                              feat_dim=100, hidden=40, batch=128, feat_dtype="bf16")
     assert run_steps(w3, 6, use_cache=True, lr=0.02, bits=64, superbatch=2) > 0
+
+
+@pytest.mark.parametrize("F,d_out,relu,bf16", [(64, 64, True, False), (602, 256, True, False), (100, 47, False, False),
+                                               (33, 5, True, False), (128, 256, True, True), (70, 41, False, False)])
+def test_gcn_layer_forward_backward(F, d_out, relu, bf16):
+    """GCN-style layer (Eq. 1 over N_in(v) U {v}, one matrix) through its own entry points."""
+    b = nb()
+    blk, x, xb, w_self, _, bias, rng = layer_case(4000, 60_000, F, d_out, (7, 6), 300, 11, bf16)
+    n_dst, n_src = blk.n_dst, blk.n_src
+    cap_dst, cap_src = n_dst + 77, n_src + 130
+    d_n_dst, d_n_src = dev(np.array([n_dst], np.int32)), dev(np.array([n_src], np.int32))
+    indptr = dev(np.concatenate([blk.indptr, np.zeros(77, np.int32)]))
+    view = b.block_view_from_tensors(d_n_dst, d_n_src, indptr, dev(blk.indices), cap_dst, cap_src,
+                                     dev(np.concatenate([blk.csc_indptr, np.zeros(130, np.int32)])), dev(blk.csc_dst))
+    xs = dev(xb.view(np.int16)) if bf16 else dev(x)
+    ws = torch.empty(b.no_sage_layer_ws_bytes(cap_dst, cap_src, F, d_out), dtype=torch.uint8, device="cuda")
+    agg = torch.full((cap_dst, F), 7.0, device="cuda")
+    h = torch.full((cap_dst, d_out), 7.0, device="cuda")
+    tw, tbias = dev(w_self), dev(bias)
+    b.no_gcn_layer_fwd(view, xs, tw, tbias, relu, agg, h, ws)
+    o_agg, o_h = ora.gcn_layer_fwd(blk, x, w_self, bias, relu)
+    assert_close(agg[:n_dst].cpu().numpy(), o_agg, "agg")
+    assert_close(h[:n_dst].cpu().numpy(), o_h, "h")
+    assert (h[n_dst:] == 7.0).all() and (agg[n_dst:] == 7.0).all()
+    grad_h = rng.standard_normal((n_dst, d_out)).astype(np.float32)
+    o_h32 = o_h.astype(np.float32)
+    gw = torch.zeros((F, d_out), device="cuda")
+    gb = torch.zeros((d_out,), device="cuda")
+    gx = torch.full((cap_src, F), 3.0, device="cuda")
+    hh = torch.zeros((cap_dst, d_out), device="cuda")
+    hh[:n_dst] = dev(o_h32)
+    gh = torch.zeros((cap_dst, d_out), device="cuda")
+    gh[:n_dst] = dev(grad_h)
+    aa = torch.zeros((cap_dst, F), device="cuda")
+    aa[:n_dst] = dev(o_agg.astype(np.float32))
+    for need_gx in (True, False):
+        b.no_gcn_layer_bwd(view, aa, hh, gh, tw, relu, gw, gb, gx if need_gx else None, ws)
+        r = ora.gcn_layer_bwd(blk, o_agg.astype(np.float32), o_h32, grad_h, w_self, relu, need_gx)
+        assert_close(gw.cpu().numpy(), r[0], "gw")
+        assert_close(gb.cpu().numpy(), r[1], "gbias")
+        if need_gx:
+            assert_close(gx[:n_src].cpu().numpy(), r[2], "grad_x")
+            assert (gx[n_src:] == 3.0).all()
+    g1 = gw.clone()
+    b.no_gcn_layer_bwd(view, aa, hh, gh, tw, relu, gw, gb, None, ws)
+    assert torch.equal(g1, gw)
+
+
+def test_gcn_train_steps():
+    """Whole steps with GCN-style layers: plain, with reuse (2 and 3 layers, bf16 table), and under the
+    super-batch schedule with bulk refresh."""
+    import dataclasses
+    run_steps(si.WORKLOADS["tiny"], 3, use_cache=False, arch="gcn")
+    w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=2, hot_fraction=0.2)
+    assert run_steps(w, 5, use_cache=True, lr=0.02, arch="gcn") > 0
+    w3 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(4, 3, 3), staleness=3, hot_fraction=0.3, n_classes=47,
+                             feat_dim=100, hidden=40, batch=128, feat_dtype="bf16")
+    assert run_steps(w3, 6, use_cache=True, lr=0.02, bits=64, superbatch=2, arch="gcn") > 0
+    w1 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(6,), batch=200)
+    run_steps(w1, 2, use_cache=False, arch="gcn")
 
 
 def test_cache_invalidate_and_set_staleness():
