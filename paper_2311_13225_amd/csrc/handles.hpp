@@ -52,6 +52,8 @@ struct no_blocks_s {
     hipEvent_t ev_fork[NO_MAX_LAYERS] = {nullptr};
     hipEvent_t ev_side_done = nullptr;
     hipEvent_t ev_gather_done = nullptr;
+    hipEvent_t ev_indices_done = nullptr;    // side stream: local indices of every hop written
+    bool upper_indices_deferred = false;     // the last call left the upper hops' indices to the side stream
     bool side_pending = false;
     no::DevBuf<char> ws_side;
     void release() {
@@ -59,6 +61,7 @@ struct no_blocks_s {
         for (auto& e : ev_fork) if (e) { (void)hipEventDestroy(e); e = nullptr; }
         if (ev_side_done) { (void)hipEventDestroy(ev_side_done); ev_side_done = nullptr; }
         if (ev_gather_done) { (void)hipEventDestroy(ev_gather_done); ev_gather_done = nullptr; }
+        if (ev_indices_done) { (void)hipEventDestroy(ev_indices_done); ev_indices_done = nullptr; }
         ws_side.release();
         for (auto& h : hop) h.release();
         counts.release(); seeds.release(); map.release(); tmp_a.release(); ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();

@@ -450,13 +450,22 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
     };
     const bool have_copy = gather && gather->table;
     if (have_copy && gather->needed_by_forward) NO_CHECK(copy_rows());
+    // local indices first: the forward pass of the layers above the bottom one aggregates through them, so it
+    // waits for ev_indices_done (not for the whole side stream) when they were left to this stream
+    b->upper_indices_deferred = false;
     for (int32_t h = 0; h < n_hops; ++h) {
         HopBuffers& H = b->hop[h];
         int32_t* cnt = b->counts.p + 4 * h;
-        if (!indices_done[h])
-            hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd,
-                               (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p,
-                               H.indices.p, H.has_csc ? H.csc_cnt.p : nullptr);
+        if (indices_done[h]) continue;
+        hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd,
+                           (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p,
+                           H.indices.p, H.has_csc ? H.csc_cnt.p : nullptr);
+        if (h < n_hops - 1) b->upper_indices_deferred = true;
+    }
+    NO_HIP_CHECK(hipEventRecord(b->ev_indices_done, sd));
+    for (int32_t h = 0; h < n_hops; ++h) {
+        HopBuffers& H = b->hop[h];
+        int32_t* cnt = b->counts.p + 4 * h;
         if (!H.has_csc) continue;
         NO_CHECK(exclusive_scan2(ArrayLoader{H.csc_cnt.p}, cnt + 1, H.n_src_cap, H.csc_indptr.p, nullptr, b->ws_side.p, sd));
         hipLaunchKernelGGL(csc_fill_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd, (const int32_t*)(cnt + 2),
@@ -586,6 +595,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
     for (int32_t h = 0; h < n_layers; ++h) NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_fork[h], hipEventDisableTiming));
     NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_side_done, hipEventDisableTiming));
     NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_gather_done, hipEventDisableTiming));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_indices_done, hipEventDisableTiming));
     if (n_layers >= 2) {
         size_t v1_cap = (size_t)b->hop[n_layers - 2].n_src_cap;
         NO_CHECK(b->compute_list.alloc(v1_cap));

@@ -306,6 +306,9 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         float* h_out = (l == 1 && used_cache) ? m->h1c.p : m->h[l - 1].p;
         LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
         if (l == 2) prof.begin(NO_STAGE_FWD_UPPER);
+        // layers above the bottom one aggregate through local indices; without the cache split those are written
+        // on the blocks' side stream
+        if (l == 2 && B->upper_indices_deferred) NO_HIP_CHECK(hipStreamWaitEvent(st, B->ev_indices_done, 0));
         if (l == 1) {
             // fused gather + aggregate: rows of the table addressed by the sampled neighbours' global ids; the
             // dense product then waits for the destination rows copied on the side stream
