@@ -48,6 +48,9 @@ def main():
                     help="generate the feature table in device memory (implied for tables over 2^31 elements); "
                          "the CPU baseline is skipped then")
     ap.add_argument("--lr", type=float, default=0.01)
+    ap.add_argument("--no-ahead", action="store_true",
+                    help="throughput pass with no_train_step (sample, then train) instead of no_train_step_ahead "
+                         "(batch t+1 sampled on a second stream while batch t trains)")
     ap.add_argument("--arch", choices=["sage", "gcn"], default="sage",
                     help="layer form: GraphSAGE-mean (the headline configuration) or the GCN-style layer")
     ap.add_argument("--copy-reference", action="store_true",
@@ -130,10 +133,16 @@ def main():
     seed_batches = [dev(si.batch_seeds(train, w.batch, t)) for t in range(W + K)]
     stream = torch.cuda.current_stream()
 
-    def run(first, count, want_stats=False):
+    def run(first, count, want_stats=False, ahead=False):
         out = []
         for t in range(first, first + count):
-            st = b.no_train_step(model, g, tfeat, tlab, seed_batches[t], cache, t, w.seed, args.lr, want_stats=want_stats)
+            if ahead:
+                nxt = seed_batches[t + 1] if t + 1 < W + K else None
+                st = b.no_train_step_ahead(model, g, tfeat, tlab, seed_batches[t], nxt, False, cache, t, w.seed, args.lr,
+                                           want_stats=want_stats)
+            else:
+                st = b.no_train_step(model, g, tfeat, tlab, seed_batches[t], cache, t, w.seed, args.lr,
+                                     want_stats=want_stats)
             out.append(st)
         return out
 
@@ -141,10 +150,11 @@ def main():
     load_weights()
     if cache is not None:
         b.no_cache_invalidate(cache)
-    run(0, W)
+    use_ahead = not args.no_ahead
+    run(0, W, ahead=use_ahead)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(W, K)
+    run(W, K, ahead=use_ahead)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / K
@@ -162,15 +172,27 @@ def main():
         b.no_cache_set_staleness(cache, 2 * n_sb - 1)
         w1 = b.no_model_params(model, 1)
 
+        sb_pending = [False]
+
         def run_sb(first, count, want_stats=False):
             out = []
             for t in range(first, first + count):
                 if t % n_sb == 0:
-                    if t > 0:
+                    if sb_pending[0]:
                         b.no_refresh_hot_commit(cache)
                     b.no_refresh_hot_begin(cache, g, tfeat, w1[0], None if gcn else w1[1], w1[2], w.fanouts[-1], t, w.seed)
-                out.append(b.no_train_step(model, g, tfeat, tlab, seed_batches[t], cache, t, w.seed, args.lr,
-                                           want_stats=want_stats))
+                    sb_pending[0] = True
+                if use_ahead:
+                    nxt = seed_batches[t + 1] if t + 1 < W + K else None
+                    # the boundary commit moves inside the call that samples the first batch of the next super-batch
+                    commit = nxt is not None and (t + 1) % n_sb == 0 and sb_pending[0]
+                    out.append(b.no_train_step_ahead(model, g, tfeat, tlab, seed_batches[t], nxt, commit, cache, t, w.seed,
+                                                     args.lr, want_stats=want_stats))
+                    if commit:
+                        sb_pending[0] = False
+                else:
+                    out.append(b.no_train_step(model, g, tfeat, tlab, seed_batches[t], cache, t, w.seed, args.lr,
+                                               want_stats=want_stats))
             return out
 
         W_sb = max(W, 2 * n_sb) // n_sb * n_sb         # warm-up ends on a boundary, past the first super-batch
@@ -183,7 +205,9 @@ def main():
         run_sb(W_sb, K_sb)
         torch.cuda.synchronize()
         el = time.perf_counter() - t0
-        b.no_refresh_hot_commit(cache)                  # leave nothing pending
+        if sb_pending[0]:
+            b.no_refresh_hot_commit(cache)              # leave nothing pending
+            sb_pending[0] = False
         torch.cuda.synchronize()
         # refresh alone (begin + commit back to back on an idle GPU)
         t0 = time.perf_counter()

@@ -82,6 +82,7 @@ _SIGNATURES = {
     "no_model_blocks": (_I32, [_P, _P]),
     "no_model_gathered": (_I32, [_P, _P]),
     "no_train_step": (_I32, [_P, _P, _P, _P, _P, _I32, _P, _I64, _U64, C.c_float, _P, _P, _P]),
+    "no_train_step_ahead": (_I32, [_P, _P, _P, _P, _P, _I32, _P, _I32, _I32, _P, _I64, _U64, C.c_float, _P, _P, _P]),
     "no_model_destroy": (_I32, [_P]),
     "no_model_profile": (_I32, [_P, _I32]),
     "no_model_stage_ms": (_I32, [_P, _P, _P]),
@@ -471,6 +472,26 @@ def no_train_step(m: Model, g: Graph, features: torch.Tensor, labels: torch.Tens
     _check(lib().no_train_step(m.h, g.h, features.data_ptr(), labels.data_ptr(), seeds.data_ptr(), seeds.numel(),
                                cache.h if cache is not None else None, step, seed & 0xFFFFFFFFFFFFFFFF, lr, None,
                                C.byref(hs) if want_stats else None, _stream(stream)))
+    return hs
+
+
+def no_train_step_ahead(m: Model, g: Graph, features: torch.Tensor, labels: torch.Tensor, seeds: torch.Tensor,
+                        next_seeds: Optional[torch.Tensor], commit_refresh_before_next: bool, cache: Optional[Cache],
+                        step: int, seed: int, lr: float, want_stats: bool = True, stream=None) -> Optional[no_step_stats]:
+    """no_train_step that also samples batch step + 1 (next_seeds) on the model's sampling stream while this batch
+    trains. Pass the SAME tensor as `seeds` of the next call, or the sample is dropped."""
+    assert features.is_cuda and features.is_contiguous() and features.shape[1] == m.dims[0]
+    assert _dtype_code(features) == m.feat_dtype
+    assert labels.is_cuda and labels.dtype == torch.int32 and labels.is_contiguous()
+    for t in (seeds, next_seeds):
+        assert t is None or (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous())
+    hs = no_step_stats() if want_stats else None
+    _check(lib().no_train_step_ahead(m.h, g.h, features.data_ptr(), labels.data_ptr(), seeds.data_ptr(), seeds.numel(),
+                                     None if next_seeds is None else next_seeds.data_ptr(),
+                                     0 if next_seeds is None else next_seeds.numel(),
+                                     1 if commit_refresh_before_next else 0,
+                                     cache.h if cache is not None else None, step, seed & 0xFFFFFFFFFFFFFFFF, lr, None,
+                                     C.byref(hs) if want_stats else None, _stream(stream)))
     return hs
 
 

@@ -118,6 +118,8 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
                            uint32_t domain, int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b,
                            hipStream_t st, bool join = true, const SideGather* gather = nullptr);
 int32_t blocks_join(no_blocks_s* b, hipStream_t st);
+// The pending bulk refresh becomes the cache contents once `st` has waited for it (no_refresh_hot_commit).
+int32_t refresh_commit_impl(no_cache_s* c, hipStream_t st);
 int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fanouts, int32_t n_layers,
                            bool build_csc, no_blocks_s** out);
 void fill_block_view(const no_blocks_s* b, int32_t hop, no_block_view* v);

@@ -93,16 +93,22 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
     return NO_OK;
 }
 
-extern "C" int32_t no_refresh_hot_commit(no_cache_t c, void* stream) {
-    clear_error();
-    NO_REQUIRE(c != nullptr, NO_ERR_INVALID_ARG, "no_refresh_hot_commit: cache is NULL");
+namespace no {
+int32_t refresh_commit_impl(no_cache_s* c, hipStream_t st) {
     if (c->n_hot == 0) return NO_OK;
     RefreshState* r = c->refresh;
     NO_REQUIRE(r && r->pending, NO_ERR_INVALID_ARG, "no_refresh_hot_commit: no refresh is pending");
-    NO_HIP_CHECK(hipStreamWaitEvent((hipStream_t)stream, r->ev_done, 0));
-    // work queued on `stream` so far holds the old pointers; work queued from here on sees the new rows
+    NO_HIP_CHECK(hipStreamWaitEvent(st, r->ev_done, 0));
+    // work queued on `st` so far holds the old pointers; work queued from here on sees the new rows
     std::swap(c->emb.p, r->emb_pending.p);
     std::swap(c->version.p, r->version_pending.p);
     r->pending = false;
     return NO_OK;
+}
+}  // namespace no
+
+extern "C" int32_t no_refresh_hot_commit(no_cache_t c, void* stream) {
+    clear_error();
+    NO_REQUIRE(c != nullptr, NO_ERR_INVALID_ARG, "no_refresh_hot_commit: cache is NULL");
+    return refresh_commit_impl(c, (hipStream_t)stream);
 }

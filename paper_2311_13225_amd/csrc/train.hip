@@ -5,6 +5,8 @@
 #include "handles.hpp"
 #include "layers.hpp"
 
+#include <utility>
+
 struct no_model_s {
     int32_t n_layers = 0;
     int32_t dims[NO_MAX_LAYERS + 1] = {0};
@@ -27,9 +29,26 @@ struct no_model_s {
     no::DevBuf<no_step_stats> stats;
     bool last_used_cache = false;
     int32_t arch = NO_ARCH_SAGE_MEAN;
+    // sampling ahead (Section 4.2, Stage 1): a second set of blocks and destination rows filled on a stream of its
+    // own while the current batch trains; created by the first call that asks for it
+    no_blocks_s* blocks_alt = nullptr;
+    no::DevBuf<char> x0_alt;
+    hipStream_t sample_stream = nullptr;
+    hipEvent_t ev_can_sample = nullptr, ev_sampled = nullptr;
+    bool ahead_valid = false;
+    int64_t ahead_step = -1;
+    uint64_t ahead_seed = 0;
+    const int32_t* ahead_seeds = nullptr;
+    int32_t ahead_n = 0;
+    no_cache_s* ahead_cache = nullptr;
     no::StageProfiler prof;
     void release() {
         if (prof.created) { for (auto& e : prof.ev) (void)hipEventDestroy(e); prof.created = false; }
+        if (sample_stream) { (void)hipStreamSynchronize(sample_stream); (void)hipStreamDestroy(sample_stream); sample_stream = nullptr; }
+        if (ev_can_sample) { (void)hipEventDestroy(ev_can_sample); ev_can_sample = nullptr; }
+        if (ev_sampled) { (void)hipEventDestroy(ev_sampled); ev_sampled = nullptr; }
+        if (blocks_alt) { blocks_alt->release(); delete blocks_alt; blocks_alt = nullptr; }
+        x0_alt.release();
         if (blocks) { blocks->release(); delete blocks; blocks = nullptr; }
         params.release(); grads.release(); x0.release();
         for (auto& b : mean) b.release();
@@ -250,9 +269,20 @@ extern "C" int32_t no_model_gathered(no_model_t m, const void** d_x0) {
     return NO_OK;
 }
 
-extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
-                                 const int32_t* d_seeds, int32_t n_seeds, no_cache_t cache, int64_t step, uint64_t seed,
-                                 float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream) {
+static int32_t ensure_lookahead(no_model_s* m, no_graph_s* g) {
+    if (m->blocks_alt) return NO_OK;
+    NO_CHECK(blocks_create_impl(g, m->n_seeds_cap, m->fanouts, m->n_layers, true, &m->blocks_alt));
+    NO_CHECK(m->x0_alt.alloc(m->x0.n));
+    NO_HIP_CHECK(hipStreamCreateWithFlags(&m->sample_stream, hipStreamNonBlocking));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_can_sample, hipEventDisableTiming));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_sampled, hipEventDisableTiming));
+    return NO_OK;
+}
+
+static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
+                               const int32_t* d_seeds, int32_t n_seeds, const int32_t* d_next_seeds, int32_t n_next_seeds,
+                               int32_t commit_refresh_before_next, no_cache_t cache, int64_t step, uint64_t seed,
+                               float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream) {
     clear_error();
     NO_REQUIRE(m && g && d_features && d_labels && d_seeds, NO_ERR_INVALID_ARG, "no_train_step: NULL argument");
     NO_REQUIRE(n_seeds >= 1, NO_ERR_INVALID_ARG, "no_train_step: n_seeds must be positive");
@@ -267,6 +297,25 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
                    "no_train_step: cache rows have %d columns, layer 1 has %d", cache->emb_dim, m->dims[1]);
     }
     hipStream_t st = (hipStream_t)stream;
+    if (d_next_seeds) {
+        NO_REQUIRE(n_next_seeds >= 1 && n_next_seeds <= m->n_seeds_cap, NO_ERR_CAPACITY,
+                   "no_train_step_ahead: %d next seeds outside [1, %d]", n_next_seeds, m->n_seeds_cap);
+        NO_REQUIRE(step + 1 < (1ll << 31), NO_ERR_INVALID_ARG, "no_train_step_ahead: step out of range");
+        NO_CHECK(ensure_lookahead(m, g));
+    }
+    // a batch sampled ahead by the previous call is used if it is exactly this one; anything else is dropped
+    const bool presampled = m->ahead_valid && m->ahead_step == step && m->ahead_seed == seed && m->ahead_seeds == d_seeds &&
+                            m->ahead_n == n_seeds && m->ahead_cache == cache;
+    if (m->ahead_valid) {
+        NO_HIP_CHECK(hipStreamWaitEvent(st, m->ev_sampled, 0));
+        if (presampled) {
+            std::swap(m->blocks, m->blocks_alt);
+            std::swap(m->x0.p, m->x0_alt.p);
+        } else {
+            NO_CHECK(blocks_join(m->blocks_alt, st));
+        }
+        m->ahead_valid = false;
+    }
     no_blocks_s* B = m->blocks;
     no_step_stats* stats = d_stats ? d_stats : m->stats.p;
 
@@ -287,7 +336,8 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
     static const char* no_direct = getenv("NO_SELF_FROM_COPY");
     sg.needed_by_forward = m->feat_dtype != NO_F32 || no_direct;   // fp32: the forward product reads the table rows itself
     prof.begin(NO_STAGE_SAMPLE);
-    NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg));
+    if (!presampled)
+        NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg));
     prof.end();
     const bool used_cache = B->last_used_cache;
     m->last_used_cache = used_cache;
@@ -332,6 +382,25 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
                                (const int32_t*)cache->slot_of_vertex.p, cache->version.p, (int32_t)step, d_out,
                                m->h[0].p);
             prof.end();
+        }
+        if (l == 1 && d_next_seeds) {
+            // This step has made its last change to the cache (the rows refreshed on a miss): the next batch can be
+            // sampled now, on the sampling stream, next to the rest of this step. A bulk refresh due at the boundary
+            // between the two steps is committed first, so the next batch is split against the new rows.
+            if (commit_refresh_before_next && cache) NO_CHECK(refresh_commit_impl(cache, st));
+            NO_HIP_CHECK(hipEventRecord(m->ev_can_sample, st));
+            NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_can_sample, 0));
+            SideGather sg2 = sg;
+            sg2.out = m->x0_alt.p;
+            NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
+                                        m->blocks_alt, m->sample_stream, false, &sg2));
+            NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
+            m->ahead_valid = true;
+            m->ahead_step = step + 1;
+            m->ahead_seed = seed;
+            m->ahead_seeds = d_next_seeds;
+            m->ahead_n = n_next_seeds;
+            m->ahead_cache = cache;
         }
     }
 
@@ -388,6 +457,22 @@ extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_featu
         NO_HIP_CHECK(hipStreamSynchronize(st));
     }
     return NO_OK;
+}
+
+extern "C" int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
+                                 const int32_t* d_seeds, int32_t n_seeds, no_cache_t cache, int64_t step, uint64_t seed,
+                                 float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream) {
+    return train_step_impl(m, g, d_features, d_labels, d_seeds, n_seeds, nullptr, 0, 0, cache, step, seed, lr, d_stats, h_stats,
+                           stream);
+}
+
+extern "C" int32_t no_train_step_ahead(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
+                                       const int32_t* d_seeds, int32_t n_seeds, const int32_t* d_next_seeds,
+                                       int32_t n_next_seeds, int32_t commit_refresh_before_next, no_cache_t cache,
+                                       int64_t step, uint64_t seed, float lr, no_step_stats* d_stats,
+                                       no_step_stats* h_stats, void* stream) {
+    return train_step_impl(m, g, d_features, d_labels, d_seeds, n_seeds, d_next_seeds, n_next_seeds,
+                           commit_refresh_before_next, cache, step, seed, lr, d_stats, h_stats, stream);
 }
 
 extern "C" int32_t no_model_destroy(no_model_t m) {

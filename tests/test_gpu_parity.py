@@ -305,7 +305,7 @@ def test_sage_layer_empty_block_and_small_workspace():
 # --------------------------------------------------------------------------------------- whole step
 
 def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None, bits=32, presample=1,
-              n_train_presample=None, superbatch=0, arch="sage"):
+              n_train_presample=None, superbatch=0, arch="sage", ahead=False):
     b = nb()
     V = V or w.n_vertices
     E = E or w.n_edges
@@ -336,6 +336,8 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
     ow = [tuple(np.asarray(t, np.float64) for t in pick(x)) for x in weights]
     hits = 0
     pending = None
+    seed_tensors = [dev(si.batch_seeds(train, w.batch, t)) for t in range(n_steps)]
+    commit = False
     for step in range(n_steps):
         seeds = si.batch_seeds(train, w.batch, step)
         print("step", step, flush=True)
@@ -344,11 +346,17 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
             # start the refresh for the next one from the parameters as they stand now
             if pending is not None:
                 ora.commit_refresh(oc, *pending)
-                b.no_refresh_hot_commit(gc)
+                if not ahead:           # sampling ahead: committed inside the previous step's call
+                    b.no_refresh_hot_commit(gc)
             pending = ora.refresh_hot(og, feat, oc, ow[0], w.fanouts[-1], step, w.seed, feat_is_bf16=bf16)
             p1 = b.no_model_params(model, 1)
             b.no_refresh_hot_begin(gc, gg, tfeat, p1[0], None if gcn else p1[1], p1[2], w.fanouts[-1], step, w.seed)
-        st = b.no_train_step(model, gg, tfeat, tlab, dev(seeds), gc, step, w.seed, lr)
+        if ahead:
+            nxt = seed_tensors[step + 1] if step + 1 < n_steps else None
+            commit = bool(superbatch) and nxt is not None and (step + 1) % superbatch == 0
+            st = b.no_train_step_ahead(model, gg, tfeat, tlab, seed_tensors[step], nxt, commit, gc, step, w.seed, lr)
+        else:
+            st = b.no_train_step(model, gg, tfeat, tlab, seed_tensors[step], gc, step, w.seed, lr)
         ambiguous = []
 
         def relu_decisions(layer, z_ora):
@@ -398,8 +406,14 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
         ow = r.new_weights
         if use_cache and oc.n_hot > 0:
             view = b.no_cache_view(gc, V)
-            assert np.array_equal(view["version"].cpu().numpy(), oc.version)
-            assert_close(view["emb"].cpu().numpy(), oc.emb, "emb step %d" % step)
+            if ahead and commit:
+                # the boundary commit ran inside this call (after the step's last use of the cache): the cache
+                # already holds what the oracle installs at the start of the next step
+                assert np.array_equal(view["version"].cpu().numpy(), pending[1])
+                assert_close(view["emb"].cpu().numpy(), pending[0], "committed emb step %d" % step)
+            else:
+                assert np.array_equal(view["version"].cpu().numpy(), oc.version)
+                assert_close(view["emb"].cpu().numpy(), oc.emb, "emb step %d" % step)
     return hits
 
 
@@ -563,6 +577,52 @@ def test_gcn_train_steps():
     assert run_steps(w3, 6, use_cache=True, lr=0.02, bits=64, superbatch=2, arch="gcn") > 0
     w1 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(6,), batch=200)
     run_steps(w1, 2, use_cache=False, arch="gcn")
+
+
+def test_sampling_ahead_gives_the_same_steps():
+    """no_train_step_ahead samples batch t+1 on a second stream while batch t trains: every step must equal the
+    oracle's sequential step, with and without reuse, under the super-batch schedule (commit inside the call),
+    for both layer forms; a lookahead that is not consumed is dropped."""
+    import dataclasses
+    run_steps(si.WORKLOADS["tiny"], 4, use_cache=False, ahead=True)
+    w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=2, hot_fraction=0.2)
+    assert run_steps(w, 6, use_cache=True, lr=0.02, ahead=True) > 0
+    w5 = dataclasses.replace(si.WORKLOADS["tiny"], staleness=5, hot_fraction=0.2)
+    assert run_steps(w5, 9, use_cache=True, lr=0.02, superbatch=3, ahead=True) > 0
+    w3 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(4, 3, 3), staleness=3, hot_fraction=0.3, n_classes=47,
+                             feat_dim=100, hidden=40, batch=128, feat_dtype="bf16")
+    assert run_steps(w3, 6, use_cache=True, lr=0.02, bits=64, superbatch=2, ahead=True) > 0
+    assert run_steps(w3, 4, use_cache=True, lr=0.02, bits=64, ahead=True, arch="gcn") > 0
+
+
+def test_sampling_ahead_dropped_when_not_consumed():
+    b = nb()
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=2, hot_fraction=0.2)
+    src, dst, og, gg = make_graph(w.n_vertices, w.n_edges, w.seed, 32)
+    feat = si.features(w.n_vertices, w.feat_dim, w.seed)
+    lab = si.labels(w.n_vertices, w.n_classes, w.seed)
+    train = si.train_split(w.n_vertices, 0.65, w.seed)
+    weights = si.init_weights(w.dims, w.seed)
+    losses = []
+    for mode in ("plain", "mismatch"):
+        model = b.no_model_create(gg, w.dims, w.batch, w.fanouts)
+        for l in range(w.n_layers):
+            for t, a in zip(b.no_model_params(model, l + 1), weights[l]):
+                t.copy_(dev(a))
+        gc = b.no_select_hot(gg, dev(train), w.batch, w.fanouts, 1, w.hot_fraction, w.staleness, w.hidden, w.seed)
+        tfeat, tlab = dev(feat), dev(lab)
+        seeds = [dev(si.batch_seeds(train, w.batch, t)) for t in range(4)]
+        out = []
+        for t in range(4):
+            if mode == "plain":
+                st = b.no_train_step(model, gg, tfeat, tlab, seeds[t], gc, t, w.seed, 0.02)
+            else:
+                # announce a batch that never comes (wrong tensor), then ask for the right one
+                st = b.no_train_step_ahead(model, gg, tfeat, tlab, seeds[t], seeds[0], False, gc, t, w.seed, 0.02)
+            out.append((st.loss, st.n_hit, tuple(st.n_src[:2])))
+        losses.append(out)
+    assert losses[0] == losses[1]
 
 
 def test_cache_invalidate_and_set_staleness():
