@@ -116,7 +116,8 @@ namespace no {
 struct SideGather { const void* table = nullptr; int32_t row_bytes = 0; void* out = nullptr; bool needed_by_forward = true; };
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key,
                            uint32_t domain, int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b,
-                           hipStream_t st, bool join = true, const SideGather* gather = nullptr);
+                           hipStream_t st, bool join = true, const SideGather* gather = nullptr,
+                           bool inline_side = false);
 int32_t blocks_join(no_blocks_s* b, hipStream_t st);
 // The pending bulk refresh becomes the cache contents once `st` has waited for it (no_refresh_hot_commit).
 int32_t refresh_commit_impl(no_cache_s* c, hipStream_t st);

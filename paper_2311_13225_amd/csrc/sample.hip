@@ -434,18 +434,22 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
 // that first saw it, so the map still answers for the hops above unless the cache split re-keyed it),
 // the transposes of the upper hops, and the wipe of the id map.
 static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d_n_src_last, hipStream_t st,
-                                const SideGather* gather, const bool* indices_done) {
+                                const SideGather* gather, const bool* indices_done, bool inline_side) {
     const int T = 256;
-    hipStream_t sd = b->side;
-    NO_HIP_CHECK(hipEventRecord(b->ev_fork[0], st));
-    NO_HIP_CHECK(hipStreamWaitEvent(sd, b->ev_fork[0], 0));
+    // inline_side: the caller's stream is itself off every dependency chain (sampling ahead), so the work stays on
+    // it and costs no fork, join or readiness events
+    hipStream_t sd = inline_side ? st : b->side;
+    if (!inline_side) {
+        NO_HIP_CHECK(hipEventRecord(b->ev_fork[0], st));
+        NO_HIP_CHECK(hipStreamWaitEvent(sd, b->ev_fork[0], 0));
+    }
     // the dense copy of the bottom destinations' rows goes first when the forward pass waits for it, else last
     // (then it runs next to the matrix products instead of next to the bandwidth-bound aggregation)
     auto copy_rows = [&]() -> int32_t {
         const HopBuffers& lastg = b->hop[n_hops - 1];
         NO_CHECK(gather_rows(gather->table, gather->row_bytes, gather->row_bytes, lastg.src_global.p,
                              b->counts.p + 4 * (n_hops - 1), lastg.n_dst_cap, gather->out, gather->row_bytes, sd));
-        NO_HIP_CHECK(hipEventRecord(b->ev_gather_done, sd));
+        if (!inline_side) NO_HIP_CHECK(hipEventRecord(b->ev_gather_done, sd));
         return NO_OK;
     };
     const bool have_copy = gather && gather->table;
@@ -460,9 +464,9 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
         hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd,
                            (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p,
                            H.indices.p, H.has_csc ? H.csc_cnt.p : nullptr);
-        if (h < n_hops - 1) b->upper_indices_deferred = true;
+        if (h < n_hops - 1 && !inline_side) b->upper_indices_deferred = true;
     }
-    NO_HIP_CHECK(hipEventRecord(b->ev_indices_done, sd));
+    if (!inline_side) NO_HIP_CHECK(hipEventRecord(b->ev_indices_done, sd));
     for (int32_t h = 0; h < n_hops; ++h) {
         HopBuffers& H = b->hop[h];
         int32_t* cnt = b->counts.p + 4 * h;
@@ -478,7 +482,7 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
     hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, T)), dim3(T), 0, sd,
                        (const int32_t*)last.src_global.p, d_n_src_last, b->map.p);
     if (have_copy && !gather->needed_by_forward) NO_CHECK(copy_rows());
-    b->side_pending = true;
+    b->side_pending = !inline_side;
     return launch_status("side work");
 }
 
@@ -492,7 +496,7 @@ int32_t blocks_join(no_blocks_s* b, hipStream_t st) {
 
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key, uint32_t domain,
                            int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st, bool join,
-                           const SideGather* gather) {
+                           const SideGather* gather, bool inline_side) {
     NO_CHECK(blocks_join(b, st));      // a previous call that was never joined
     const int32_t L = b->n_layers;
     int32_t* extra = b->counts.p + 4 * L;     // n_compute, n_hit, -, -, n_refresh
@@ -536,7 +540,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
         d_n = b->counts.p + 4 * h + 1;
     }
     if (!use_cache) hipLaunchKernelGGL(set_counts_kernel, dim3(1), dim3(1), 0, st, extra, 0, 0, 0);
-    NO_CHECK(launch_side_work(b, n_hops, d_n, st, gather, indices_done));
+    NO_CHECK(launch_side_work(b, n_hops, d_n, st, gather, indices_done, inline_side));
     NO_CHECK(launch_status("sample_blocks"));
     if (join) NO_CHECK(blocks_join(b, st));
     return NO_OK;

@@ -367,7 +367,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
                                   NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features,
-                                  m->arch == NO_ARCH_GCN ? nullptr : B->ev_gather_done, m->arch));
+                                  (m->arch == NO_ARCH_GCN || presampled) ? nullptr : B->ev_gather_done, m->arch));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
@@ -393,7 +393,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             SideGather sg2 = sg;
             sg2.out = m->x0_alt.p;
             NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
-                                        m->blocks_alt, m->sample_stream, false, &sg2));
+                                        m->blocks_alt, m->sample_stream, false, &sg2, true));
             NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
             m->ahead_valid = true;
             m->ahead_step = step + 1;
