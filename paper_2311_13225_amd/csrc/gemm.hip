@@ -527,8 +527,40 @@ int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st) {
 // Sums the split partial products in split order: g_self = rows [0,Kp) of product 0, g_bias = row Kp of
 // product 0, g_neigh = rows [0,Kp) of product 1. With lr != 0 the parameters take their SGD step in the
 // same pass (W <- W - lr * g), after every kernel that read them.
-__global__ void reduce_grads_kernel(const float* __restrict__ P, int32_t splits, int32_t Kp, int32_t N, float* g_self,
-                                    float* g_neigh, float* g_bias, float lr, float* w_self, float* w_neigh, float* w_bias) {
+__device__ void write_step_stats(const StatsJob& j) {
+    __shared__ float sm[256];
+    float s = 0.f;
+    for (int i = (int)threadIdx.x; i < j.n; i += 256) s += j.row_loss[i];
+    sm[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        no_step_stats* stats = j.stats;
+        const int32_t* counts = j.counts;
+        const int n_layers = j.n_layers;
+        stats->loss = sm[0] / (float)j.n;
+        for (int h = 0; h < NO_MAX_LAYERS; ++h) {
+            stats->n_dst[h] = h < n_layers ? counts[4 * h] : 0;
+            stats->n_src[h] = h < n_layers ? counts[4 * h + 1] : 0;
+            stats->nnz[h] = h < n_layers ? counts[4 * h + 2] : 0;
+        }
+        stats->n_hit = j.used_cache ? counts[4 * n_layers + 1] : 0;
+        stats->n_refresh = j.used_cache ? counts[4 * n_layers + 4] : 0;
+        stats->n_v1 = n_layers >= 2 ? counts[4 * (n_layers - 2) + 1] : counts[0];
+        stats->bad_seed = counts[4 * n_layers + 5];
+    }
+}
+
+__global__ void __launch_bounds__(256) reduce_grads_kernel(const float* __restrict__ P, int32_t splits, int32_t Kp, int32_t N,
+                                                           float* g_self, float* g_neigh, float* g_bias, float lr, float* w_self,
+                                                           float* w_neigh, float* w_bias, StatsJob job) {
+    if (job.stats && blockIdx.x == gridDim.x - 1) {      // the extra block of the launch
+        if (blockIdx.y == 0) write_step_stats(job);
+        return;
+    }
     const int64_t per = (int64_t)(Kp + 1) * N;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int q = (int)blockIdx.y;
@@ -547,10 +579,12 @@ __global__ void reduce_grads_kernel(const float* __restrict__ P, int32_t splits,
 }
 
 int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
-                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems) {
+                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems,
+                     const StatsJob* stats_job) {
     const int64_t per = (int64_t)(Kp + 1) * N;
-    hipLaunchKernelGGL(reduce_grads_kernel, dim3((unsigned)ceil_div(per, 256), (unsigned)n_problems), dim3(256), 0, st, P, splits, Kp, N, g_self,
-                       g_neigh, g_bias, lr, w_self, w_neigh, w_bias);
+    const StatsJob job = stats_job ? *stats_job : StatsJob{};
+    hipLaunchKernelGGL(reduce_grads_kernel, dim3((unsigned)ceil_div(per, 256) + (job.stats ? 1u : 0u), (unsigned)n_problems), dim3(256), 0, st, P, splits, Kp, N, g_self,
+                       g_neigh, g_bias, lr, w_self, w_neigh, w_bias, job);
     return launch_status("reduce_grads");
 }
 

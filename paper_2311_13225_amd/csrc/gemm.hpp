@@ -34,11 +34,21 @@ struct GemmTNArgs {
     int32_t n_problems = 2;                              // 1: only A[0]
 };
 
+// Statistics of a training step, written by one extra block of the last gradient reduction of the step (they are
+// nobody's input, so they do not get a launch of their own on the step's dependency chain): mean of the per-seed
+// losses in a fixed order and the block sizes.
+struct StatsJob {
+    const float* row_loss = nullptr; int32_t n = 0;
+    const int32_t* counts = nullptr; int32_t n_layers = 0; int32_t used_cache = 0;
+    no_step_stats* stats = nullptr;       // NULL: no job
+};
+
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st);
 int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st);
 // Sums the partials in split order into the three gradients; with lr != 0 also applies W <- W - lr * g.
 int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
-                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems = 2);
+                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems = 2,
+                     const StatsJob* stats_job = nullptr);
 
 inline int ptr_align(const void* p, int64_t ld) {
     if ((((uintptr_t)p) & 15) == 0 && (ld & 3) == 0) return 4;

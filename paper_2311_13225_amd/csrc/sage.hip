@@ -241,13 +241,14 @@ static inline unsigned ew_blocks(int64_t total) {
 // ------------------------------------------------------------------------ workspace layout
 
 // Number of row slices of the weight-gradient product: enough 64x64 output tiles x slices to give every
-// compute unit several blocks, bounded so that a slice keeps at least 256 rows of the capacity.
+// compute unit several blocks, bounded so that a slice keeps at least 64 rows of the capacity.
 int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out) {
     const int64_t tiles = 2 * ceil_div(d_in + 1, 64) * ceil_div(d_out, 64);
     static const char* env = getenv("NO_TN_BLOCKS");      // tuning aid: target number of blocks of the split product
     const int64_t target = env && atoi(env) > 0 ? atoi(env) : 1600;
     int64_t s = ceil_div(target, tiles);
-    const int64_t by_rows = ceil_div(n_dst_cap, 256);
+    static const char* env_rows = getenv("NO_TN_MIN_ROWS");       // tuning aid: fewest rows of the capacity per slice
+    const int64_t by_rows = ceil_div(n_dst_cap, env_rows && atoi(env_rows) > 0 ? atoi(env_rows) : 64);
     if (s > by_rows) s = by_rows;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
@@ -334,7 +335,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int prep_stage, int dw_stage,
                       int reduce_stage, int dx_stage, const int32_t* grad_rows, float lr, float* w_self_rw,
-                      float* w_neigh_rw, float* bias_rw, int32_t arch) {
+                      float* w_neigh_rw, float* bias_rw, int32_t arch, const StatsJob* stats_job) {
     const bool gcn = arch == NO_ARCH_GCN;
     const int32_t n_cap = blk.n_dst_cap;
     if (prof && prep_stage >= 0) prof->begin(prep_stage);
@@ -391,7 +392,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     if (prof && dw_stage >= 0) prof->end();
     if (prof && reduce_stage >= 0) prof->begin(reduce_stage);
     NO_CHECK(reduce_grads(w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, st,
-                          gcn ? 1 : 2));
+                          gcn ? 1 : 2, stats_job));
     if (prof && reduce_stage >= 0) prof->end();
     return launch_status("sage_backward");
 }

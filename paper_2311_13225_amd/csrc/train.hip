@@ -85,33 +85,6 @@ __global__ void __launch_bounds__(256) softmax_xent_kernel(const float* __restri
     if (lane == 0) row_loss[row] = -(z[y] - mx - logf(s));
 }
 
-// One block: mean of the per-seed losses in a fixed order, and the size statistics of the step. (A
-// "last block done" ticket inside the kernel above measured slower: 256 same-address atomics.)
-__global__ void __launch_bounds__(256) finish_stats_kernel(const float* __restrict__ row_loss, int32_t n, const int32_t* counts,
-                                                           int32_t n_layers, int32_t used_cache, no_step_stats* stats) {
-    __shared__ float sm[256];
-    float s = 0.f;
-    for (int i = (int)threadIdx.x; i < n; i += 256) s += row_loss[i];
-    sm[threadIdx.x] = s;
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        stats->loss = sm[0] / (float)n;
-        for (int h = 0; h < NO_MAX_LAYERS; ++h) {
-            stats->n_dst[h] = h < n_layers ? counts[4 * h] : 0;
-            stats->n_src[h] = h < n_layers ? counts[4 * h + 1] : 0;
-            stats->nnz[h] = h < n_layers ? counts[4 * h + 2] : 0;
-        }
-        stats->n_hit = used_cache ? counts[4 * n_layers + 1] : 0;
-        stats->n_refresh = used_cache ? counts[4 * n_layers + 4] : 0;
-        stats->n_v1 = n_layers >= 2 ? counts[4 * (n_layers - 2) + 1] : counts[0];
-        stats->bad_seed = counts[4 * n_layers + 5];
-    }
-}
-
 // Layer-1 rows of all of V^1, one wavefront per row:
 //   computed rows: h1[compute_pos[i], :] = h1c[i, :]; if the vertex is hot its slot is refreshed with this
 //                  row (made by the step's pre-update weights) and stamped version = step;
@@ -409,9 +382,12 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     prof.begin(NO_STAGE_LOSS);
     hipLaunchKernelGGL(softmax_xent_kernel, dim3(wave_rows_blocks(n_seeds)), dim3(256), 0, st, (const float*)m->h[L - 1].p,
                        d_labels, (const int32_t*)B->seeds.p, n_seeds, C, m->gh[L - 1].p, m->row_loss.p);
-    hipLaunchKernelGGL(finish_stats_kernel, dim3(1), dim3(256), 0, st, (const float*)m->row_loss.p, n_seeds,
-                       (const int32_t*)B->counts.p, L, used_cache ? 1 : 0, stats);
     prof.end();
+    // (mean loss and block sizes are written by an extra block of the step's last kernel, the layer-1 reduction)
+    StatsJob stats_job;
+    stats_job.row_loss = m->row_loss.p; stats_job.n = n_seeds;
+    stats_job.counts = B->counts.p; stats_job.n_layers = L; stats_job.used_cache = used_cache ? 1 : 0;
+    stats_job.stats = stats;
 
     // backward (first joins the side stream: the transposes are needed from here on)
     NO_CHECK(blocks_join(B, st));
@@ -437,7 +413,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
                                m->grads.p + m->off_bias[l - 1], l > 1 ? m->gh[l - 2].p : nullptr, w, st,
                                l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
                                -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
-                               m->params.p + m->off_bias[l - 1], m->arch));
+                               m->params.p + m->off_bias[l - 1], m->arch, l == 1 ? &stats_job : nullptr));
     }
 
     // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;
