@@ -37,6 +37,11 @@ struct LayerWorkspace {
     size_t bytes = 0;
 };
 
+// What the layer below needs from a layer's input gradient: masked by its ReLU decision (its output h, one row per
+// source row of this layer) and, when only some rows take a gradient, compacted to them (out_rows[u] = row of gz_out
+// for source row u, -1 = none; NULL = same row). With this the input gradient goes straight to gz_out.
+struct BelowLayer { const float* h = nullptr; const int32_t* out_rows = nullptr; float* gz_out = nullptr; };
+
 int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out);
 LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_t d_out);
 
@@ -46,7 +51,8 @@ int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_
                        const int32_t* self_idx = nullptr);
 int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
                             const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
-                            hipStream_t st);
+                            hipStream_t st, const float* mask_h = nullptr, const int32_t* out_rows = nullptr,
+                            float* masked_out = nullptr);
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int agg_stage = -1,
@@ -59,7 +65,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       int dw_stage = -1, int reduce_stage = -1, int dx_stage = -1,
                       const int32_t* grad_rows = nullptr, float lr = 0.f, float* w_self_rw = nullptr,
                       float* w_neigh_rw = nullptr, float* bias_rw = nullptr, int32_t arch = NO_ARCH_SAGE_MEAN,
-                      const StatsJob* stats_job = nullptr);
+                      const StatsJob* stats_job = nullptr, const float* gz_in = nullptr,
+                      const BelowLayer* below = nullptr);
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
                     const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
 

@@ -66,7 +66,9 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__
                                                            const int32_t* d_n_rows, int32_t n_rows_cap,
                                                            const int32_t* d_n_init, float* __restrict__ out, int64_t ld_out,
                                                            int32_t units, int32_t g_log2, int32_t n_chunks,
-                                                           const int32_t* __restrict__ self_idx, int32_t with_self) {
+                                                           const int32_t* __restrict__ self_idx, int32_t with_self,
+                                                           const float* __restrict__ mask_h, const int32_t* __restrict__ out_rows,
+                                                           float* __restrict__ masked_out) {
     int32_t n = *d_n_rows;
     if (n > n_rows_cap) n = n_rows_cap;
     const int32_t n_init = (!MEAN && d_n_init) ? *d_n_init : 0;
@@ -143,6 +145,18 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc[c] = ((acc[c] + a[0][c]) + a[1][c]) + a[2][c];
         }
+        if (!MEAN && masked_out) {
+            // the consumer is the layer below: apply its ReLU decision (its output h, row `row`) and place the row
+            // where that layer's gradient rows live (out_rows[row], -1 = the row takes no gradient)
+            const int64_t r = out_rows ? (int64_t)out_rows[row] : row;
+            if (r >= 0) {
+                const float* hm = mask_h + row * ld_out + (int64_t)u * VEC;
+                float* mo = masked_out + r * ld_out + (int64_t)u * VEC;
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) mo[c] = hm[c] > 0.f ? acc[c] : 0.f;
+            }
+            continue;
+        }
 #pragma unroll
         for (int c = 0; c < VEC; ++c) o[c] = acc[c] * scale;
     }
@@ -151,7 +165,8 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__
 template <typename T, int VEC, bool MEAN>
 static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, const int32_t* idx, const int32_t* d_n,
                            int32_t n_cap, const int32_t* d_n_init, float* out, int64_t ld_out, int32_t dim, hipStream_t st,
-                           const int32_t* self_idx = nullptr, int32_t with_self = 0) {
+                           const int32_t* self_idx = nullptr, int32_t with_self = 0, const float* mask_h = nullptr,
+                           const int32_t* out_rows = nullptr, float* masked_out = nullptr) {
     const int32_t units = dim / VEC;
     int g_log2 = 0;
     while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
@@ -161,7 +176,7 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
     if (blocks > 256 * 64) blocks = 256 * 64;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)blocks), dim3(256), 0, st, src, ld_src, seg, idx, d_n,
-                       n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, with_self);
+                       n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, with_self, mask_h, out_rows, masked_out);
 }
 
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
@@ -189,16 +204,19 @@ int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_
 // grad_x[u,:] = (u < n_dst ? grad_x[u,:] : 0) + sum over transposed entries of u of gmean_scaled[csc_dst[p],:]
 int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
                             const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
-                            hipStream_t st) {
+                            hipStream_t st, const float* mask_h, const int32_t* out_rows, float* masked_out) {
     if (n_src_cap <= 0) return NO_OK;
-    const bool a16 = (((uintptr_t)gmean_scaled | (uintptr_t)grad_x) & 15) == 0;
-    const bool a8 = (((uintptr_t)gmean_scaled | (uintptr_t)grad_x) & 7) == 0;
+    const uintptr_t al = (uintptr_t)gmean_scaled | (uintptr_t)grad_x | (uintptr_t)mask_h | (uintptr_t)masked_out;
+    const bool a16 = (al & 15) == 0, a8 = (al & 7) == 0;
     if (dim % 4 == 0 && a16)
-        launch_segment<float, 4, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st);
+        launch_segment<float, 4, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st,
+                                        nullptr, 0, mask_h, out_rows, masked_out);
     else if (dim % 2 == 0 && a8)
-        launch_segment<float, 2, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st);
+        launch_segment<float, 2, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st,
+                                        nullptr, 0, mask_h, out_rows, masked_out);
     else
-        launch_segment<float, 1, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st);
+        launch_segment<float, 1, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st,
+                                        nullptr, 0, mask_h, out_rows, masked_out);
     return launch_status("transpose_aggregate");
 }
 
@@ -335,12 +353,14 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int prep_stage, int dw_stage,
                       int reduce_stage, int dx_stage, const int32_t* grad_rows, float lr, float* w_self_rw,
-                      float* w_neigh_rw, float* bias_rw, int32_t arch, const StatsJob* stats_job) {
+                      float* w_neigh_rw, float* bias_rw, int32_t arch, const StatsJob* stats_job, const float* gz_in,
+                      const BelowLayer* below) {
     const bool gcn = arch == NO_ARCH_GCN;
     const int32_t n_cap = blk.n_dst_cap;
     if (prof && prep_stage >= 0) prof->begin(prep_stage);
-    const float* gz = grad_h;
-    if (relu || grad_rows) {
+    // gz_in: the layer above already applied this layer's ReLU decision and row selection while it wrote the gradient
+    const float* gz = gz_in ? gz_in : grad_h;
+    if (!gz_in && (relu || grad_rows)) {
         hipLaunchKernelGGL(mask_rows_kernel, dim3(ew_blocks((int64_t)n_cap * d_out)), dim3(256), 0, st, grad_h, grad_rows, h,
                            blk.d_n_dst, n_cap, d_out, relu, w.gz);
         gz = w.gz;
@@ -375,7 +395,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
         a.d_M = blk.d_n_dst; a.M_cap = n_cap; a.N = d_in;
         NO_CHECK(gemm_nn(a, true, st));
         NO_CHECK(transpose_aggregate(w.gmean, d_in, blk.d_csc_indptr, blk.d_csc_dst, blk.d_n_src, blk.n_src_cap,
-                                     blk.d_n_dst, grad_x_src, st));
+                                     blk.d_n_dst, grad_x_src, st, below ? below->h : nullptr, below ? below->out_rows : nullptr,
+                                     below ? below->gz_out : nullptr));
         if (prof && dx_stage >= 0) prof->end();
     }
     // weight gradients x_dst^T gz, mean^T gz and the bias gradient (column sums of gz, carried by a virtual

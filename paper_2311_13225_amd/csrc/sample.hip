@@ -327,7 +327,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe
 __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* __restrict__ v1, const int32_t* __restrict__ probe_slot,
                                                                 const int32_t* d_n_v1,
                                                                 const int64_t* __restrict__ tile_sums, int32_t* map,
-                                                                int32_t* compute_list, int32_t* compute_pos, int32_t* hit_pos,
+                                                                int32_t* compute_list, int32_t* compute_pos, int32_t* compute_inv, int32_t* hit_pos,
                                                                 int32_t* hit_slot, int32_t* extra /* n_compute, n_hit, -, -, n_refresh */) {
     __shared__ int64_t smem[ETHREADS / 64 + 1];
     const int64_t n = *d_n_v1;
@@ -371,11 +371,13 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
             const int32_t v = vv[t];
             if (c[t]) {
                 compute_pos[run] = (int32_t)i;
+                compute_inv[i] = (int32_t)run;
                 compute_list[run] = v;
                 map[v] = (int32_t)run;
             } else {
                 const int64_t p = i - run;
                 hit_pos[p] = (int32_t)i;
+                compute_inv[i] = -1;
                 hit_slot[p] = slot[t];
                 map[v] = EMPTY;
             }
@@ -521,7 +523,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
                                P.has_csc ? P.csc_cnt.p : nullptr);
             indices_done[h - 1] = true;
             hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, d_dst,
-                               (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->hit_pos.p,
+                               (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->hit_pos.p,
                                b->hit_slot.p, extra);
             d_dst = b->compute_list.p;
             d_n = extra + 0;
@@ -604,6 +606,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
         size_t v1_cap = (size_t)b->hop[n_layers - 2].n_src_cap;
         NO_CHECK(b->compute_list.alloc(v1_cap));
         NO_CHECK(b->compute_pos.alloc(v1_cap));
+        NO_CHECK(b->compute_inv.alloc(v1_cap));
         NO_CHECK(b->hit_pos.alloc(v1_cap));
         NO_CHECK(b->hit_slot.alloc(v1_cap));
         NO_CHECK(b->probe_slot.alloc(v1_cap));

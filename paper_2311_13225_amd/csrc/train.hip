@@ -23,8 +23,9 @@ struct no_model_s {
     no::DevBuf<float> h[NO_MAX_LAYERS];              // layer l output [rows, d_l]; h[0] holds all of V^1
     no::DevBuf<float> gh[NO_MAX_LAYERS];             // gradient w.r.t. h[l-1]
     no::DevBuf<float> h1c;                           // layer-1 rows of the computed vertices (with a cache)
-    no::DevBuf<char> ws;
+    no::DevBuf<char> ws;                             // one region per layer (a layer writes the next one's gz while its own is in use)
     size_t ws_bytes = 0;
+    size_t ws_off[NO_MAX_LAYERS] = {0};
     no::DevBuf<float> row_loss;
     no::DevBuf<no_step_stats> stats;
     bool last_used_cache = false;
@@ -171,8 +172,8 @@ extern "C" int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t
         NO_CHECK(m->mean[l - 1].alloc((size_t)H.n_dst_cap * m->dims[l - 1]));
         NO_CHECK(m->h[l - 1].alloc((size_t)H.n_dst_cap * m->dims[l]));
         NO_CHECK(m->gh[l - 1].alloc((size_t)H.n_dst_cap * m->dims[l]));
-        const size_t b = carve_workspace(nullptr, H.n_dst_cap, m->dims[l - 1], m->dims[l]).bytes;
-        if (b > ws_bytes) ws_bytes = b;
+        m->ws_off[l - 1] = ws_bytes;
+        ws_bytes += carve_workspace(nullptr, H.n_dst_cap, m->dims[l - 1], m->dims[l]).bytes;
     }
     if (L >= 2) {
         NO_CHECK(m->h1c.alloc((size_t)bottom.n_dst_cap * m->dims[1]));
@@ -327,7 +328,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         const void* x = l == 1 ? (const void*)m->x0.p : (const void*)m->h[l - 2].p;
         const no_dtype dt = l == 1 ? m->feat_dtype : NO_F32;
         float* h_out = (l == 1 && used_cache) ? m->h1c.p : m->h[l - 1].p;
-        LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
+        LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
         if (l == 2) prof.begin(NO_STAGE_FWD_UPPER);
         // layers above the bottom one aggregate through local indices; without the cache split those are written
         // on the blocks' side stream
@@ -406,14 +407,26 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             h_l = m->h1c.p;
             grad_rows = B->compute_pos.p;
         }
-        LayerWorkspace w = carve_workspace(m->ws.p, blk.n_dst_cap, d_in, d_out);
+        // the input gradient of layer l >= 2 is written as the gz of layer l-1: masked by that layer's ReLU and,
+        // with reuse, compacted to the computed rows (so layer l-1 launches no masking pass)
+        BelowLayer below;
+        const float* gz_in = nullptr;
+        if (l >= 2) {
+            const no_block_view& blk_below = view[L - l + 1];
+            below.h = m->h[l - 2].p;
+            below.out_rows = (l == 2 && used_cache) ? B->compute_inv.p : nullptr;
+            below.gz_out = carve_workspace(m->ws.p + m->ws_off[l - 2], blk_below.n_dst_cap, m->dims[l - 2], m->dims[l - 1]).gz;
+        }
+        if (l < L) gz_in = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out).gz;
+        LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
         NO_CHECK(sage_backward(blk, x, dt, d_in, m->mean[l - 1].p, h_l, gh_l, m->params.p + m->off_w_self[l - 1],
                                m->params.p + m->off_w_neigh[l - 1], d_out, l < L ? 1 : 0,
                                m->grads.p + m->off_w_self[l - 1], m->grads.p + m->off_w_neigh[l - 1],
                                m->grads.p + m->off_bias[l - 1], l > 1 ? m->gh[l - 2].p : nullptr, w, st,
                                l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
                                -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
-                               m->params.p + m->off_bias[l - 1], m->arch, l == 1 ? &stats_job : nullptr));
+                               m->params.p + m->off_bias[l - 1], m->arch, l == 1 ? &stats_job : nullptr, gz_in,
+                               l >= 2 ? &below : nullptr));
     }
 
     // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;
