@@ -294,6 +294,8 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
             if (row >= M) continue;
             float scale = 1.f;
             if (sp) { int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale = len > 0 ? 1.f / (float)len : 0.f; }
+            const int64_t crow = (g.c_rows && prob == 0) ? (int64_t)g.c_rows[row] : (int64_t)row;
+            const int64_t krow = (g.c_keep_rows && prob == 0) ? (int64_t)g.c_keep_rows[row] : -1;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
                 const int col = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
@@ -301,7 +303,11 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
                 float v = acc_get<SETS, MI, NI>(acc, mi, ni, r);
                 if (g.bias) v += g.bias[col];
                 if (g.relu) v = v > 0.f ? v : 0.f;
-                C[(int64_t)row * ldc + col] = v * scale;
+                C[crow * ldc + col] = v * scale;
+                if (krow >= 0) {
+                    g.c_keep[krow * ldc + col] = v * scale;
+                    if (col == 0) g.c_keep_stamp[krow] = g.stamp;
+                }
             }
         }
 }
@@ -403,7 +409,13 @@ __global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
         if (g.relu) v = v > 0.f ? v : 0.f;
         float scale = 1.f;
         if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale = len > 0 ? 1.f / (float)len : 0.f; }
-        C[(int64_t)row * ldc + col] = v * scale;
+        const int64_t crow = (g.c_rows && prob == 0) ? (int64_t)g.c_rows[row] : (int64_t)row;
+        C[crow * ldc + col] = v * scale;
+        const int64_t krow = (g.c_keep_rows && prob == 0) ? (int64_t)g.c_keep_rows[row] : -1;
+        if (krow >= 0) {
+            g.c_keep[krow * ldc + col] = v * scale;
+            if (col == 0) g.c_keep_stamp[krow] = g.stamp;
+        }
     }
 }
 

@@ -23,6 +23,11 @@ struct GemmNNArgs {
     const int32_t* d_M; int32_t M_cap; int32_t N;
     int32_t M_est;                        // expected row count for tile selection (0: half the capacity)
     const float* bias; int32_t relu;
+    // Scattered output of C[0] (layer 1 with reuse, Section 4.1.2): row m goes to row c_rows[m] (NULL: m); a row with
+    // c_keep_rows[m] >= 0 is also stored as row c_keep_rows[m] of c_keep (same leading dimension) and
+    // c_keep_stamp[that row] = stamp: the cache refresh of a recomputed hot vertex.
+    const int32_t* c_rows;
+    float* c_keep; const int32_t* c_keep_rows; int32_t* c_keep_stamp; int32_t stamp;
 };
 
 struct GemmTNArgs {

@@ -45,6 +45,7 @@ struct no_blocks_s {
     no::DevBuf<char> ws;                // tile sums of the scans
     // bottom hop with a cache
     no::DevBuf<int32_t> compute_list, compute_pos, hit_pos, hit_slot, probe_slot;
+    no::DevBuf<int32_t> refresh_slot;        // [n_compute]: cache slot a computed row refreshes (its vertex is hot), else -1
     no::DevBuf<int32_t> compute_inv;         // [|V^1|]: index in the compute list of position i of V^1, -1 if served from the cache
     bool last_used_cache = false;
     // The transposes and the final wipe of the id map do not feed the forward pass: they run on a side
@@ -66,7 +67,7 @@ struct no_blocks_s {
         ws_side.release();
         for (auto& h : hop) h.release();
         counts.release(); seeds.release(); map.release(); tmp_a.release(); ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();
-        probe_slot.release(); compute_inv.release();
+        probe_slot.release(); compute_inv.release(); refresh_slot.release();
     }
 };
 

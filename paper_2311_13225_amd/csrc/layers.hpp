@@ -37,6 +37,22 @@ struct LayerWorkspace {
     size_t bytes = 0;
 };
 
+// Row copies carried by extra blocks of an aggregation launch: dst[dst_rows[i], :] = src[src_rows[i], :] for i < *d_n.
+struct RowCopyJob {
+    const float* src = nullptr; const int32_t* src_rows = nullptr; const int32_t* dst_rows = nullptr;
+    const int32_t* d_n = nullptr; int32_t n_cap = 0; float* dst = nullptr; int32_t dim = 0;
+    uint32_t first_block = 0;             // set by the launcher
+};
+
+// Layer 1 with reuse (Section 4.1.2): where the computed rows go, which of them refresh the cache, and the reused
+// rows to copy in from the cache.
+struct Layer1Reuse {
+    const int32_t* compute_pos = nullptr;     // row m of the layer's output -> row of H^1
+    const int32_t* refresh_slot = nullptr;    // >= 0: the row is also stored in that cache slot, stamped `step`
+    float* emb = nullptr; int32_t* version = nullptr; int32_t step = 0;
+    RowCopyJob hits;                          // H^1[hit_pos[i]] = emb[hit_slot[i]]
+};
+
 // What the layer below needs from a layer's input gradient: masked by its ReLU decision (its output h, one row per
 // source row of this layer) and, when only some rows take a gradient, compacted to them (out_rows[u] = row of gz_out
 // for source row u, -1 = none; NULL = same row). With this the input gradient goes straight to gz_out.
@@ -48,7 +64,7 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 // with_self: the destination's own row (row r of x_src, or row self_idx[r]) joins the average (Eq. 1 over N_in(v) U {v})
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
                        const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, bool with_self = false,
-                       const int32_t* self_idx = nullptr);
+                       const int32_t* self_idx = nullptr, const RowCopyJob* copy = nullptr);
 int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
                             const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
                             hipStream_t st, const float* mask_h = nullptr, const int32_t* out_rows = nullptr,
@@ -57,7 +73,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int agg_stage = -1,
                      int gemm_stage = -1, const void* agg_table = nullptr, hipEvent_t wait_before_gemm = nullptr,
-                     int32_t arch = NO_ARCH_SAGE_MEAN);
+                     int32_t arch = NO_ARCH_SAGE_MEAN, const Layer1Reuse* reuse = nullptr);
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,

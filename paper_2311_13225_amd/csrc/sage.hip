@@ -61,7 +61,7 @@ template <> struct RowVec<uint16_t, 1> {
 // the items of a row are consecutive, which keeps the reads of a source row next to each other in time.
 // Up to eight source rows are loaded before the first add; the adds stay in segment order.
 template <typename T, int VEC, bool MEAN>
-__global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__ src, int64_t ld_src,
+__global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const T* __restrict__ src, int64_t ld_src,
                                                            const int32_t* __restrict__ seg, const int32_t* __restrict__ idx,
                                                            const int32_t* d_n_rows, int32_t n_rows_cap,
                                                            const int32_t* d_n_init, float* __restrict__ out, int64_t ld_out,
@@ -69,12 +69,26 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(const T* __restrict__
                                                            const int32_t* __restrict__ self_idx, int32_t with_self,
                                                            const float* __restrict__ mask_h, const int32_t* __restrict__ out_rows,
                                                            float* __restrict__ masked_out) {
+    if (job.dst && blockIdx.x >= job.first_block) {
+        // extra blocks of the launch: dst[dst_rows[i], :] = src[src_rows[i], :], one wavefront per row (rows that are
+        // ready before this kernel's own output is, e.g. the cached layer-1 rows of the reused vertices)
+        const int32_t nj = *job.d_n;
+        const int64_t w0 = (((int64_t)(blockIdx.x - job.first_block)) * blockDim.x + threadIdx.x) >> 6;
+        const int64_t nw = ((int64_t)(gridDim.x - job.first_block) * blockDim.x) >> 6;
+        const int ln = (int)(threadIdx.x & 63);
+        for (int64_t i = w0; i < nj; i += nw) {
+            const float* s_ = job.src + (int64_t)job.src_rows[i] * job.dim;
+            float* d_ = job.dst + (int64_t)job.dst_rows[i] * job.dim;
+            for (int c = ln; c < job.dim; c += 64) d_[c] = s_[c];
+        }
+        return;
+    }
     int32_t n = *d_n_rows;
     if (n > n_rows_cap) n = n_rows_cap;
     const int32_t n_init = (!MEAN && d_n_init) ? *d_n_init : 0;
     const int32_t lane = (int32_t)(threadIdx.x & 63);
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int64_t n_waves = ((int64_t)(job.dst ? job.first_block : gridDim.x) * blockDim.x) >> 6;
     const int32_t items_per_pass = 64 >> g_log2;
     const int32_t sub = lane >> g_log2, u0 = lane & ((1 << g_log2) - 1);
     const int64_t n_items = (int64_t)n * n_chunks;
@@ -166,7 +180,7 @@ template <typename T, int VEC, bool MEAN>
 static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, const int32_t* idx, const int32_t* d_n,
                            int32_t n_cap, const int32_t* d_n_init, float* out, int64_t ld_out, int32_t dim, hipStream_t st,
                            const int32_t* self_idx = nullptr, int32_t with_self = 0, const float* mask_h = nullptr,
-                           const int32_t* out_rows = nullptr, float* masked_out = nullptr) {
+                           const int32_t* out_rows = nullptr, float* masked_out = nullptr, const RowCopyJob* copy = nullptr) {
     const int32_t units = dim / VEC;
     int g_log2 = 0;
     while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
@@ -175,28 +189,36 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
     int64_t blocks = ceil_div(waves, 4);
     if (blocks > 256 * 64) blocks = 256 * 64;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)blocks), dim3(256), 0, st, src, ld_src, seg, idx, d_n,
+    RowCopyJob job = copy ? *copy : RowCopyJob{};
+    int64_t copy_blocks = 0;
+    if (job.dst) {
+        job.first_block = (uint32_t)blocks;
+        copy_blocks = ceil_div(job.n_cap, 4);
+        if (copy_blocks > 1024) copy_blocks = 1024;
+        if (copy_blocks < 1) copy_blocks = 1;
+    }
+    hipLaunchKernelGGL((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)(blocks + copy_blocks)), dim3(256), 0, st, job, src, ld_src, seg, idx, d_n,
                        n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, with_self, mask_h, out_rows, masked_out);
 }
 
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
                        const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, bool with_self,
-                       const int32_t* self_idx) {
+                       const int32_t* self_idx, const RowCopyJob* copy) {
     if (n_dst_cap <= 0) return NO_OK;
     const int32_t ws = with_self ? 1 : 0;
     if (dt == NO_F32) {
         const float* x = (const float*)x_src;
         const bool a16 = (((uintptr_t)x | (uintptr_t)mean) & 15) == 0, a8 = (((uintptr_t)x | (uintptr_t)mean) & 7) == 0;
-        if (dim % 4 == 0 && a16) launch_segment<float, 4, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
-        else if (dim % 2 == 0 && a8) launch_segment<float, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
-        else launch_segment<float, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
+        if (dim % 4 == 0 && a16) launch_segment<float, 4, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
+        else if (dim % 2 == 0 && a8) launch_segment<float, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
+        else launch_segment<float, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
     } else {
         const uint16_t* x = (const uint16_t*)x_src;
         if (dim % 8 == 0 && ((uintptr_t)x & 15) == 0 && ((uintptr_t)mean & 15) == 0)
-            launch_segment<uint16_t, 8, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
+            launch_segment<uint16_t, 8, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
         else if (dim % 2 == 0 && ((uintptr_t)x & 3) == 0)
-            launch_segment<uint16_t, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
-        else launch_segment<uint16_t, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws);
+            launch_segment<uint16_t, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
+        else launch_segment<uint16_t, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
     }
     return launch_status("mean_aggregate");
 }
@@ -293,12 +315,20 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
-                     const void* agg_table, hipEvent_t wait_before_gemm, int32_t arch) {
+                     const void* agg_table, hipEvent_t wait_before_gemm, int32_t arch, const Layer1Reuse* reuse) {
+    // reuse: the output rows are scattered into H^1, recomputed hot rows also refresh the cache, and the reused
+    // rows are copied in from the cache by extra blocks of the aggregation launch (they do not depend on this layer)
+    const RowCopyJob* hits = (reuse && reuse->hits.dst) ? &reuse->hits : nullptr;
+    auto scatter = [&](GemmNNArgs& a) {
+        if (!reuse) return;
+        a.c_rows = reuse->compute_pos;
+        a.c_keep = reuse->emb; a.c_keep_rows = reuse->refresh_slot; a.c_keep_stamp = reuse->version; a.stamp = reuse->step;
+    };
     if (arch == NO_ARCH_GCN) {
         // Eq. 1 over N_in(v) U {v} (the destination's own row joins the average), Eq. 2 with one matrix
         if (prof && agg_stage >= 0) prof->begin(agg_stage);
         NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
-                                blk.n_dst_cap, mean, st, true, agg_table ? blk.d_src_global : nullptr));
+                                blk.n_dst_cap, mean, st, true, agg_table ? blk.d_src_global : nullptr, hits));
         if (prof && agg_stage >= 0) prof->end();
         GemmNNArgs a{};
         a.A[0] = mean; a.lda[0] = d_in; a.a_align[0] = ptr_align(mean, d_in);
@@ -308,6 +338,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
         a.n_problems = 1; a.accumulate = 1;
         a.d_M = blk.d_n_dst; a.M_cap = blk.n_dst_cap; a.N = d_out;
         a.bias = bias; a.relu = relu;
+        scatter(a);
         if (prof && gemm_stage >= 0) prof->begin(gemm_stage);
         int32_t rc = gemm_nn(a, false, st);
         if (prof && gemm_stage >= 0) prof->end();
@@ -321,7 +352,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global && !no_direct;
     if (prof && agg_stage >= 0) prof->begin(agg_stage);
     NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap,
-                            mean, st, false, nullptr));
+                            mean, st, false, nullptr, hits));
     if (prof && agg_stage >= 0) prof->end();
     if (wait_before_gemm && !direct_self)
         NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
@@ -342,6 +373,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     a.n_problems = 2; a.accumulate = 1;
     a.d_M = blk.d_n_dst; a.M_cap = blk.n_dst_cap; a.N = d_out;
     a.bias = bias; a.relu = relu;
+    scatter(a);
     if (prof && gemm_stage >= 0) prof->begin(gemm_stage);
     int32_t rc = gemm_nn(a, false, st);
     if (prof && gemm_stage >= 0) prof->end();

@@ -284,7 +284,7 @@ struct CacheProbe {
 // the hop above (one edge per thread), which must be read out of the id map before the partition re-keys it:
 // sharing the launch keeps that pass off the dependency chain of the sampling.
 __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe, const int32_t* d_n_v1, int64_t* tile_sums,
-                                                                int32_t* __restrict__ probe_slot /* [n]: slot if served from the cache, else -1 */,
+                                                                int32_t* __restrict__ probe_slot /* [n]: slot if served from the cache; -1 cold; -2 - slot if hot but to be computed */,
                                                                 uint32_t v1_blocks, const int32_t* d_nnz,
                                                                 const int32_t* __restrict__ nbr, const int32_t* map,
                                                                 int32_t* __restrict__ indices, int32_t* csc_cnt) {
@@ -314,7 +314,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe
     for (int t = 0; t < EITEMS; ++t) {
         if (i0 + t < n) {
             const int64_t f = probe.flags(slot[t], ver[t]);
-            probe_slot[i0 + t] = (f & 1) ? -1 : slot[t];
+            probe_slot[i0 + t] = (f & 1) ? (slot[t] >= 0 ? -2 - slot[t] : -1) : slot[t];
             s += f;
         }
     }
@@ -327,7 +327,8 @@ __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe
 __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* __restrict__ v1, const int32_t* __restrict__ probe_slot,
                                                                 const int32_t* d_n_v1,
                                                                 const int64_t* __restrict__ tile_sums, int32_t* map,
-                                                                int32_t* compute_list, int32_t* compute_pos, int32_t* compute_inv, int32_t* hit_pos,
+                                                                int32_t* compute_list, int32_t* compute_pos, int32_t* compute_inv,
+                                                                int32_t* refresh_slot, int32_t* hit_pos,
                                                                 int32_t* hit_slot, int32_t* extra /* n_compute, n_hit, -, -, n_refresh */) {
     __shared__ int64_t smem[ETHREADS / 64 + 1];
     const int64_t n = *d_n_v1;
@@ -372,6 +373,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
             if (c[t]) {
                 compute_pos[run] = (int32_t)i;
                 compute_inv[i] = (int32_t)run;
+                refresh_slot[run] = slot[t] <= -2 ? -2 - slot[t] : -1;
                 compute_list[run] = v;
                 map[v] = (int32_t)run;
             } else {
@@ -523,7 +525,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
                                P.has_csc ? P.csc_cnt.p : nullptr);
             indices_done[h - 1] = true;
             hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, d_dst,
-                               (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->hit_pos.p,
+                               (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
                                b->hit_slot.p, extra);
             d_dst = b->compute_list.p;
             d_n = extra + 0;
@@ -607,6 +609,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
         NO_CHECK(b->compute_list.alloc(v1_cap));
         NO_CHECK(b->compute_pos.alloc(v1_cap));
         NO_CHECK(b->compute_inv.alloc(v1_cap));
+        NO_CHECK(b->refresh_slot.alloc(v1_cap));
         NO_CHECK(b->hit_pos.alloc(v1_cap));
         NO_CHECK(b->hit_slot.alloc(v1_cap));
         NO_CHECK(b->probe_slot.alloc(v1_cap));

@@ -22,7 +22,6 @@ struct no_model_s {
     no::DevBuf<float> mean[NO_MAX_LAYERS];           // layer l (index l-1): [n_dst_cap, d_{l-1}]
     no::DevBuf<float> h[NO_MAX_LAYERS];              // layer l output [rows, d_l]; h[0] holds all of V^1
     no::DevBuf<float> gh[NO_MAX_LAYERS];             // gradient w.r.t. h[l-1]
-    no::DevBuf<float> h1c;                           // layer-1 rows of the computed vertices (with a cache)
     no::DevBuf<char> ws;                             // one region per layer (a layer writes the next one's gz while its own is in use)
     size_t ws_bytes = 0;
     size_t ws_off[NO_MAX_LAYERS] = {0};
@@ -55,7 +54,7 @@ struct no_model_s {
         for (auto& b : mean) b.release();
         for (auto& b : h) b.release();
         for (auto& b : gh) b.release();
-        h1c.release(); ws.release(); row_loss.release(); stats.release();
+        ws.release(); row_loss.release(); stats.release();
     }
 };
 
@@ -84,42 +83,6 @@ __global__ void __launch_bounds__(256) softmax_xent_kernel(const float* __restri
         grad[(int64_t)row * n_classes + c] = (p - (c == y ? 1.f : 0.f)) * inv_n;
     }
     if (lane == 0) row_loss[row] = -(z[y] - mx - logf(s));
-}
-
-// Layer-1 rows of all of V^1, one wavefront per row:
-//   computed rows: h1[compute_pos[i], :] = h1c[i, :]; if the vertex is hot its slot is refreshed with this
-//                  row (made by the step's pre-update weights) and stamped version = step;
-//   reused rows:   h1[hit_pos[i], :] = emb[hit_slot[i], :].
-// A vertex is either computed or reused in a step, so refreshed and read slots never coincide.
-__global__ void __launch_bounds__(256) assemble_h1_kernel(const float* __restrict__ h1c, float* emb,
-                                                          const int32_t* __restrict__ compute_pos,
-                                                          const int32_t* __restrict__ compute_ids,
-                                                          const int32_t* __restrict__ hit_pos,
-                                                          const int32_t* __restrict__ hit_slot, const int32_t* d_n_compute,
-                                                          const int32_t* d_n_hit, const int32_t* __restrict__ slot_of_vertex,
-                                                          int32_t* version, int32_t step, int32_t dim,
-                                                          float* __restrict__ h1) {
-    const int32_t nc = *d_n_compute, nh = *d_n_hit;
-    const int lane = (int)(threadIdx.x & 63);
-    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (row >= (int64_t)nc + nh) return;
-    if (row < nc) {
-        const float* src = h1c + row * dim;
-        float* dst = h1 + (int64_t)compute_pos[row] * dim;
-        const int32_t slot = slot_of_vertex[compute_ids[row]];
-        float* keep = slot >= 0 ? emb + (int64_t)slot * dim : nullptr;
-        for (int c = lane; c < dim; c += 64) {
-            const float v = src[c];
-            dst[c] = v;
-            if (keep) keep[c] = v;
-        }
-        if (keep && lane == 0) version[slot] = step;
-    } else {
-        const int64_t i = row - nc;
-        const float* src = emb + (int64_t)hit_slot[i] * dim;
-        float* dst = h1 + (int64_t)hit_pos[i] * dim;
-        for (int c = lane; c < dim; c += 64) dst[c] = src[c];
-    }
 }
 
 static inline unsigned wave_rows_blocks(int64_t rows) { int64_t b = ceil_div(rows, 4); return (unsigned)(b < 1 ? 1 : b); }
@@ -174,9 +137,6 @@ extern "C" int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t
         NO_CHECK(m->gh[l - 1].alloc((size_t)H.n_dst_cap * m->dims[l]));
         m->ws_off[l - 1] = ws_bytes;
         ws_bytes += carve_workspace(nullptr, H.n_dst_cap, m->dims[l - 1], m->dims[l]).bytes;
-    }
-    if (L >= 2) {
-        NO_CHECK(m->h1c.alloc((size_t)bottom.n_dst_cap * m->dims[1]));
     }
     m->ws_bytes = ws_bytes;
     NO_CHECK(m->ws.alloc(ws_bytes));
@@ -327,7 +287,18 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         const int32_t d_in = m->dims[l - 1], d_out = m->dims[l];
         const void* x = l == 1 ? (const void*)m->x0.p : (const void*)m->h[l - 2].p;
         const no_dtype dt = l == 1 ? m->feat_dtype : NO_F32;
-        float* h_out = (l == 1 && used_cache) ? m->h1c.p : m->h[l - 1].p;
+        float* h_out = m->h[l - 1].p;
+        Layer1Reuse reuse;
+        if (l == 1 && used_cache) {
+            // H^1 holds all of V^1: the computed rows are scattered to their positions by the product's epilogue,
+            // which also refreshes the cache slot of a recomputed hot vertex (rows made by the step's pre-update
+            // weights, version = step); the reused rows are copied from the cache beside the aggregation
+            reuse.compute_pos = B->compute_pos.p;
+            reuse.refresh_slot = B->refresh_slot.p;
+            reuse.emb = cache->emb.p; reuse.version = cache->version.p; reuse.step = (int32_t)step;
+            reuse.hits.src = cache->emb.p; reuse.hits.src_rows = B->hit_slot.p; reuse.hits.dst_rows = B->hit_pos.p;
+            reuse.hits.d_n = extra + 1; reuse.hits.n_cap = blk.n_dst_cap; reuse.hits.dst = m->h[0].p; reuse.hits.dim = d_out;
+        }
         LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
         if (l == 2) prof.begin(NO_STAGE_FWD_UPPER);
         // layers above the bottom one aggregate through local indices; without the cache split those are written
@@ -341,22 +312,13 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
                                   NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features,
-                                  (m->arch == NO_ARCH_GCN || presampled) ? nullptr : B->ev_gather_done, m->arch));
+                                  (m->arch == NO_ARCH_GCN || presampled) ? nullptr : B->ev_gather_done, m->arch,
+                                  (l == 1 && used_cache) ? &reuse : nullptr));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
                               l == 1 ? &prof : nullptr, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, nullptr, nullptr, m->arch));
         if (l == L && L >= 2) prof.end();
-        if (l == 1 && used_cache) {
-            prof.begin(NO_STAGE_FWD_UPPER);
-            hipLaunchKernelGGL(assemble_h1_kernel, dim3(wave_rows_blocks(blk.n_dst_cap)), dim3(256), 0, st,
-                               (const float*)m->h1c.p, cache->emb.p, (const int32_t*)B->compute_pos.p,
-                               (const int32_t*)B->compute_list.p, (const int32_t*)B->hit_pos.p,
-                               (const int32_t*)B->hit_slot.p, extra + 0, extra + 1,
-                               (const int32_t*)cache->slot_of_vertex.p, cache->version.p, (int32_t)step, d_out,
-                               m->h[0].p);
-            prof.end();
-        }
         if (l == 1 && d_next_seeds) {
             // This step has made its last change to the cache (the rows refreshed on a miss): the next batch can be
             // sampled now, on the sampling stream, next to the rest of this step. A bulk refresh due at the boundary
@@ -403,8 +365,8 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         if (l == 1 && L >= 2) prof.end();
         const int32_t* grad_rows = nullptr;
         if (l == 1 && used_cache) {
-            // reused rows take no gradient: the layer reads only the rows of the computed vertices
-            h_l = m->h1c.p;
+            // reused rows take no gradient: the layer reads only the rows of the computed vertices (its gz arrives
+            // compacted from the layer above)
             grad_rows = B->compute_pos.p;
         }
         // the input gradient of layer l >= 2 is written as the gz of layer l-1: masked by that layer's ReLU and,
