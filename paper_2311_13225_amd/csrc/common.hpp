@@ -2,6 +2,7 @@
 // launch arithmetic, device buffers owned by handles.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdarg.h>
@@ -44,6 +45,15 @@ inline int32_t launch_status(const char* what) {
     }
     return NO_OK;
 }
+
+// Launch with an optional pair of events that take the kernel's own start and end times (HIP's extended launch):
+// a stage that is a single kernel is then timed like a kernel trace times it, without the dispatch latency and the
+// event packets that a record-before / record-after pair on the stream adds.
+#define NO_LAUNCH_TIMED(kernel, grid, block, st, ev0, ev1, ...)                                      \
+    do {                                                                                             \
+        if (ev0) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev0, ev1, 0, __VA_ARGS__);        \
+        else hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                            \
+    } while (0)
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int ilog2_ceil(uint64_t x) { int b = 0; while ((1ull << b) < x) ++b; return b; }

@@ -439,15 +439,15 @@ static void pick_tile(int64_t rows_est, int64_t cols, int64_t batch, int* bm, in
 }
 
 template <bool B_KC>
-static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st) {
+static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     const int64_t z = a.accumulate ? 1 : a.n_problems;
     dim3 grid(xcd_padded(ceil_div(a.N, bn) * ceil_div(a.M_cap, bm) * z));
-    if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), 0, st, a);
-    else if (bm == 128 && bn == 64) hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((gemm_nn_kernel<B_KC, 64, 64>), grid, dim3(256), 0, st, a);
+    if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), st, ev0, ev1, a);
+    else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), st, ev0, ev1, a);
+    else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64>), grid, dim3(256), st, ev0, ev1, a);
 }
 
-int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st) {
+int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     if (a.M_cap <= 0 || a.N <= 0) return NO_OK;
     const int64_t z = a.accumulate ? 1 : a.n_problems;
     int64_t k_total = 0;
@@ -456,15 +456,15 @@ int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st) {
     static const char* no_small = getenv("NO_GEMM_NO_SMALL");      // tuning aid: keep small products on the tiled kernel
     if (!no_small && ceil_div(a.M_cap, 64) * ceil_div(a.N, 64) * z <= 128 && k_total >= 128) {
         dim3 grid((unsigned)ceil_div(a.N, 32), (unsigned)ceil_div(a.M_cap, 32), (unsigned)z);
-        if (b_transposed) hipLaunchKernelGGL((gemm_nn_small_kernel<true>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((gemm_nn_small_kernel<false>), grid, dim3(256), 0, st, a);
+        if (b_transposed) NO_LAUNCH_TIMED((gemm_nn_small_kernel<true>), grid, dim3(256), st, ev0, ev1, a);
+        else NO_LAUNCH_TIMED((gemm_nn_small_kernel<false>), grid, dim3(256), st, ev0, ev1, a);
         return launch_status("gemm_nn_small");
     }
     int bm, bn;
     // two LDS copies of a 128x128 tile pair in the padded layout exceed 64 KB: the forward product stops at 128x64
     pick_tile(a.M_est > 0 ? a.M_est : (a.M_cap + 1) / 2, a.N, a.accumulate ? 1 : a.n_problems, &bm, &bn);
-    if (b_transposed) launch_nn<true>(a, bm, bn, st);
-    else launch_nn<false>(a, bm, bn, st);
+    if (b_transposed) launch_nn<true>(a, bm, bn, st, ev0, ev1);
+    else launch_nn<false>(a, bm, bn, st, ev0, ev1);
     return launch_status("gemm_nn");
 }
 
@@ -517,7 +517,7 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
         }
 }
 
-int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st) {
+int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     if (a.Kp <= 0 || a.N <= 0) return NO_OK;
     // 64x64 tiles: the output of one split is small, so the chip is filled by many small blocks over a
     // moderate number of splits rather than by few large blocks over many splits (fewer partials to reduce).
@@ -529,10 +529,10 @@ int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st) {
         if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128)) { bm = fm; bn = fn; }
     }
     dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.Kp + 1, bm), (unsigned)(a.n_problems * a.splits));
-    if (bm == 128 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<128, 128>), grid, dim3(256), 0, st, a);
-    else if (bm == 64 && bn == 128) hipLaunchKernelGGL((gemm_tn_kernel<64, 128>), grid, dim3(256), 0, st, a);
-    else if (bm == 128 && bn == 64) hipLaunchKernelGGL((gemm_tn_kernel<128, 64>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((gemm_tn_kernel<64, 64>), grid, dim3(256), 0, st, a);
+    if (bm == 128 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 128>), grid, dim3(256), st, ev0, ev1, a);
+    else if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 128>), grid, dim3(256), st, ev0, ev1, a);
+    else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 64>), grid, dim3(256), st, ev0, ev1, a);
+    else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64>), grid, dim3(256), st, ev0, ev1, a);
     return launch_status("gemm_tn");
 }
 

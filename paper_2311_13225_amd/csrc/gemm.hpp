@@ -48,8 +48,9 @@ struct StatsJob {
     no_step_stats* stats = nullptr;       // NULL: no job
 };
 
-int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st);
-int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st);
+// ev0 / ev1 (optional): events that take the product kernel's own start and end times
+int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // Sums the partials in split order into the three gradients; with lr != 0 also applies W <- W - lr * g.
 int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
                      float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems = 2,

@@ -26,6 +26,15 @@ struct StageProfiler {
         (void)hipEventRecord(ev[2 * n + 1], st);
         ++n;
     }
+    // a stage that is one kernel: the pair is handed to the launch and takes the kernel's own start and end
+    void kernel_pair(int stage, hipEvent_t* a, hipEvent_t* b) {
+        *a = *b = nullptr;
+        if (!enabled || n >= MAX_MARKS) return;
+        stage_of[n] = stage;
+        *a = ev[2 * n];
+        *b = ev[2 * n + 1];
+        ++n;
+    }
 };
 
 struct LayerWorkspace {
@@ -64,7 +73,8 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 // with_self: the destination's own row (row r of x_src, or row self_idx[r]) joins the average (Eq. 1 over N_in(v) U {v})
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
                        const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, bool with_self = false,
-                       const int32_t* self_idx = nullptr, const RowCopyJob* copy = nullptr);
+                       const int32_t* self_idx = nullptr, const RowCopyJob* copy = nullptr, hipEvent_t ev0 = nullptr,
+                       hipEvent_t ev1 = nullptr);
 int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
                             const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
                             hipStream_t st, const float* mask_h = nullptr, const int32_t* out_rows = nullptr,

@@ -180,7 +180,8 @@ template <typename T, int VEC, bool MEAN>
 static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, const int32_t* idx, const int32_t* d_n,
                            int32_t n_cap, const int32_t* d_n_init, float* out, int64_t ld_out, int32_t dim, hipStream_t st,
                            const int32_t* self_idx = nullptr, int32_t with_self = 0, const float* mask_h = nullptr,
-                           const int32_t* out_rows = nullptr, float* masked_out = nullptr, const RowCopyJob* copy = nullptr) {
+                           const int32_t* out_rows = nullptr, float* masked_out = nullptr, const RowCopyJob* copy = nullptr,
+                           hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr) {
     const int32_t units = dim / VEC;
     int g_log2 = 0;
     while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
@@ -197,28 +198,28 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
         if (copy_blocks > 1024) copy_blocks = 1024;
         if (copy_blocks < 1) copy_blocks = 1;
     }
-    hipLaunchKernelGGL((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)(blocks + copy_blocks)), dim3(256), 0, st, job, src, ld_src, seg, idx, d_n,
+    NO_LAUNCH_TIMED((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)(blocks + copy_blocks)), dim3(256), st, ev0, ev1, job, src, ld_src, seg, idx, d_n,
                        n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, with_self, mask_h, out_rows, masked_out);
 }
 
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
                        const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, bool with_self,
-                       const int32_t* self_idx, const RowCopyJob* copy) {
+                       const int32_t* self_idx, const RowCopyJob* copy, hipEvent_t ev0, hipEvent_t ev1) {
     if (n_dst_cap <= 0) return NO_OK;
     const int32_t ws = with_self ? 1 : 0;
     if (dt == NO_F32) {
         const float* x = (const float*)x_src;
         const bool a16 = (((uintptr_t)x | (uintptr_t)mean) & 15) == 0, a8 = (((uintptr_t)x | (uintptr_t)mean) & 7) == 0;
-        if (dim % 4 == 0 && a16) launch_segment<float, 4, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
-        else if (dim % 2 == 0 && a8) launch_segment<float, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
-        else launch_segment<float, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
+        if (dim % 4 == 0 && a16) launch_segment<float, 4, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
+        else if (dim % 2 == 0 && a8) launch_segment<float, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
+        else launch_segment<float, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
     } else {
         const uint16_t* x = (const uint16_t*)x_src;
         if (dim % 8 == 0 && ((uintptr_t)x & 15) == 0 && ((uintptr_t)mean & 15) == 0)
-            launch_segment<uint16_t, 8, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
+            launch_segment<uint16_t, 8, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
         else if (dim % 2 == 0 && ((uintptr_t)x & 3) == 0)
-            launch_segment<uint16_t, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
-        else launch_segment<uint16_t, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy);
+            launch_segment<uint16_t, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
+        else launch_segment<uint16_t, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
     }
     return launch_status("mean_aggregate");
 }
@@ -326,10 +327,10 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     };
     if (arch == NO_ARCH_GCN) {
         // Eq. 1 over N_in(v) U {v} (the destination's own row joins the average), Eq. 2 with one matrix
-        if (prof && agg_stage >= 0) prof->begin(agg_stage);
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (prof && agg_stage >= 0) prof->kernel_pair(agg_stage, &e0, &e1);
         NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
-                                blk.n_dst_cap, mean, st, true, agg_table ? blk.d_src_global : nullptr, hits));
-        if (prof && agg_stage >= 0) prof->end();
+                                blk.n_dst_cap, mean, st, true, agg_table ? blk.d_src_global : nullptr, hits, e0, e1));
         GemmNNArgs a{};
         a.A[0] = mean; a.lda[0] = d_in; a.a_align[0] = ptr_align(mean, d_in);
         a.B[0] = w_self; a.ldb[0] = d_out; a.b_align[0] = ptr_align(w_self, d_out);
@@ -339,10 +340,9 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
         a.d_M = blk.d_n_dst; a.M_cap = blk.n_dst_cap; a.N = d_out;
         a.bias = bias; a.relu = relu;
         scatter(a);
-        if (prof && gemm_stage >= 0) prof->begin(gemm_stage);
-        int32_t rc = gemm_nn(a, false, st);
-        if (prof && gemm_stage >= 0) prof->end();
-        return rc;
+        e0 = e1 = nullptr;
+        if (prof && gemm_stage >= 0) prof->kernel_pair(gemm_stage, &e0, &e1);
+        return gemm_nn(a, false, st, e0, e1);
     }
     // agg_table != NULL: the rows to average are rows of that table addressed by blk.d_indices (global ids),
     // while x_src holds only the destination rows (fused gather + aggregate of the bottom layer). An fp32
@@ -350,10 +350,10 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     // does not wait for the dense copy of the destination rows at all.
     static const char* no_direct = getenv("NO_SELF_FROM_COPY");      // tuning aid: self product reads the dense copy
     const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global && !no_direct;
-    if (prof && agg_stage >= 0) prof->begin(agg_stage);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (prof && agg_stage >= 0) prof->kernel_pair(agg_stage, &e0, &e1);
     NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap,
-                            mean, st, false, nullptr, hits));
-    if (prof && agg_stage >= 0) prof->end();
+                            mean, st, false, nullptr, hits, e0, e1));
     if (wait_before_gemm && !direct_self)
         NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
     const float* x_dst = direct_self ? (const float*)agg_table : (const float*)x_src;
@@ -374,10 +374,9 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     a.d_M = blk.d_n_dst; a.M_cap = blk.n_dst_cap; a.N = d_out;
     a.bias = bias; a.relu = relu;
     scatter(a);
-    if (prof && gemm_stage >= 0) prof->begin(gemm_stage);
-    int32_t rc = gemm_nn(a, false, st);
-    if (prof && gemm_stage >= 0) prof->end();
-    return rc;
+    e0 = e1 = nullptr;
+    if (prof && gemm_stage >= 0) prof->kernel_pair(gemm_stage, &e0, &e1);
+    return gemm_nn(a, false, st, e0, e1);
 }
 
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
@@ -440,9 +439,9 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     t.G = gz; t.ldg = d_out; t.g_align = ptr_align(gz, d_out);
     t.P = w.partials; t.Kp = d_in; t.N = d_out;
     t.d_R = blk.d_n_dst; t.R_cap = n_cap; t.splits = w.splits;
-    if (prof && dw_stage >= 0) prof->begin(dw_stage);
-    NO_CHECK(gemm_tn_partials(t, st));
-    if (prof && dw_stage >= 0) prof->end();
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (prof && dw_stage >= 0) prof->kernel_pair(dw_stage, &e0, &e1);
+    NO_CHECK(gemm_tn_partials(t, st, e0, e1));
     if (prof && reduce_stage >= 0) prof->begin(reduce_stage);
     NO_CHECK(reduce_grads(w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, st,
                           gcn ? 1 : 2, stats_job));
