@@ -22,6 +22,8 @@ What it follows in the paper:
     (one-hop sample at the bottom fanout, layer-1 forward) and become the cache contents at the
     super-batch boundary, so a row made with parameter version k*n serves steps (k+1)*n ...
     (k+2)*n - 1: version gap at most 2n - 1 (`refresh_hot`, `train_superbatches`).
+  * Section 4.3: the weight drift that stale rows may see is monitored against
+    epsilon = (largest change of a weight in one update) x 2n (`weight_drift`, `drift_tolerance`).
 """
 from __future__ import annotations
 
@@ -544,3 +546,21 @@ def train_superbatches(g: Graph, feat: np.ndarray, labels: np.ndarray, batches: 
         weights = r.new_weights
         out.append(r)
     return out, weights
+
+
+# --------------------------------------------------------------------------- weight-drift monitor (Section 4.3)
+
+def max_weight_update(old_weights, new_weights) -> float:
+    """Largest change of any entry of the given parameter arrays in one update (the paper's max delta ||W||)."""
+    return max(float(np.abs(np.asarray(b, np.float64) - np.asarray(a, np.float64)).max())
+               for a, b in zip(old_weights, new_weights))
+
+
+def weight_drift(weights, snapshot) -> float:
+    """max |W - W~| between the current parameters and the ones a set of stale embeddings was made with."""
+    return max_weight_update(snapshot, weights)
+
+
+def drift_tolerance(max_update: float, n: int) -> float:
+    """The tolerated drift of Section 4.3: epsilon = (largest single-update change) x 2n."""
+    return max_update * 2 * n

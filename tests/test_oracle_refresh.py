@@ -151,3 +151,34 @@ def test_bound_below_n_makes_committed_rows_unusable():
         assert (t - ver_before[r.batch.hit_slot] <= S).all()
         total_hits += r.n_hit
     assert total_hits > 0
+
+
+def test_weight_drift_stays_within_the_paper_tolerance():
+    """Section 4.3: with eps = (largest single-update change of a layer-1 weight) x 2n, the drift between the
+    parameters a served row was made with (version kn) and the parameters of the step that uses it (at most
+    2n - 1 updates later) never exceeds eps: triangle inequality over the updates in between."""
+    src, dst, g, feat, lab, train, weights, B = _problem(E=2500)
+    fan = (3, 2)
+    n = 3
+    cache = ora.select_hot(g, train, B, fan, 2, 0.3, 2 * n - 1, 5, 0)
+    batches = [si.batch_seeds(train, B, t) for t in range(4 * n)]
+    ws, snaps, max_upd, drifts = weights, {}, 0.0, []
+    pending_snap = current_snap = None
+    pending = None
+    for t, seeds in enumerate(batches):
+        if t % n == 0:
+            if pending is not None:
+                ora.commit_refresh(cache, *pending)
+                current_snap = pending_snap
+            pending = ora.refresh_hot(g, feat, cache, ws[0], fan[-1], t, 9)
+            pending_snap = ws[0]
+        if current_snap is not None:
+            drifts.append(ora.weight_drift(ws[0], current_snap))
+        r = ora.train_step(g, feat, lab, seeds, fan, ws, 0.05, 9, t, cache)
+        upd = ora.max_weight_update(ws[0], r.new_weights[0])
+        assert abs(upd - 0.05 * max(np.abs(gr).max() for gr in r.grads[0])) < 1e-15      # the SGD closed form
+        max_upd = max(max_upd, upd)
+        ws = r.new_weights
+    eps = ora.drift_tolerance(max_upd, n)
+    assert eps == max_upd * 2 * n
+    assert drifts and max(drifts) > 0 and max(drifts) <= (2 * n - 1) * max_upd <= eps
