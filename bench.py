@@ -266,7 +266,9 @@ def main():
     per_step["gather"] = e0.elapsed_time(e1) / n_rep          # ms per launch, standalone
     gather_bytes = n_src_last * (4 + 2 * F * es)
     del gout
-    agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4     # compulsory traffic (each row once)
+    # compulsory traffic (each distinct source row once) plus the reused layer-1 rows that extra blocks of the same
+    # launch copy from the cache into H^1 (read + write)
+    agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4 + (n_hit * w.dims[1] * 4 * 2 if L >= 2 else 0)
     gemm_fwd_flops = 2.0 * n_dst_bottom * ((1 if gcn else 2) * F) * w.dims[1]
     gemm_dw_flops = gemm_fwd_flops
     kern = {

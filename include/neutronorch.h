@@ -291,6 +291,16 @@ int32_t no_train_step_ahead(no_model_t m, no_graph_t g, const void* d_features, 
                             const int32_t* d_seeds, int32_t n_seeds, const int32_t* d_next_seeds, int32_t n_next_seeds,
                             int32_t commit_refresh_before_next, no_cache_t cache, int64_t step, uint64_t seed,
                             float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream);
+/* Weight-drift monitor (convergence analysis, Section 4.3: the tolerated drift of the parameters behind stale
+ * embeddings is epsilon = (largest change of a weight in one update) x 2n for super-batches of n steps).
+ * *h_max_update = lr * max |g| over the layer-1 gradients of the last step (the largest change that step made to a
+ * layer-1 parameter; lr is the rate that step used); *h_drift = max |W - W~| between the layer-1 parameters now and
+ * the snapshot behind the rows installed by the last no_refresh_hot_commit of `cache`, or -1 when there is no such
+ * snapshot (cache NULL, nothing committed yet, or made for another layer shape). The caller keeps the running
+ * maximum of the first value and compares the second with epsilon. Synchronises `stream`; meant for super-batch
+ * boundaries, not for the inside of a step. */
+int32_t no_model_weight_drift(no_model_t m, no_cache_t cache, float lr, float* h_max_update, float* h_drift,
+                              void* stream);
 int32_t no_model_destroy(no_model_t m);
 
 /* Per-stage timing of no_train_step with HIP events on the step's own stream. While enabled,

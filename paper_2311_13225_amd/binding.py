@@ -83,6 +83,7 @@ _SIGNATURES = {
     "no_model_gathered": (_I32, [_P, _P]),
     "no_train_step": (_I32, [_P, _P, _P, _P, _P, _I32, _P, _I64, _U64, C.c_float, _P, _P, _P]),
     "no_train_step_ahead": (_I32, [_P, _P, _P, _P, _P, _I32, _P, _I32, _I32, _P, _I64, _U64, C.c_float, _P, _P, _P]),
+    "no_model_weight_drift": (_I32, [_P, _P, C.c_float, _P, _P, _P]),
     "no_model_destroy": (_I32, [_P]),
     "no_model_profile": (_I32, [_P, _I32]),
     "no_model_stage_ms": (_I32, [_P, _P, _P]),
@@ -493,6 +494,15 @@ def no_train_step_ahead(m: Model, g: Graph, features: torch.Tensor, labels: torc
                                      cache.h if cache is not None else None, step, seed & 0xFFFFFFFFFFFFFFFF, lr, None,
                                      C.byref(hs) if want_stats else None, _stream(stream)))
     return hs
+
+
+def no_model_weight_drift(m: Model, cache: Optional[Cache], lr: float, stream=None) -> Tuple[float, float]:
+    """(largest change of a layer-1 parameter in the last update, drift from the snapshot behind the committed rows
+    or -1): the two quantities of the weight-drift monitor. Synchronises the stream."""
+    a, d = C.c_float(), C.c_float()
+    _check(lib().no_model_weight_drift(m.h, cache.h if cache is not None else None, lr, C.byref(a), C.byref(d),
+                                       _stream(stream)))
+    return a.value, d.value
 
 
 def no_model_profile(m: Model, enable: bool):

@@ -78,7 +78,11 @@ struct RefreshState {
     no_dtype dt = NO_F32;
     no::DevBuf<float> emb_pending;         // [n_hot, emb_dim]: swapped with the cache's rows at the commit
     no::DevBuf<int32_t> version_pending;   // [n_hot]
-    no::DevBuf<float> snap;                // parameter snapshot: w_self, w_neigh, bias
+    no::DevBuf<float> snap;                // parameter snapshot of the pending refresh: w_self, w_neigh, bias
+    no::DevBuf<float> snap_cur;            // the snapshot the committed rows were made with (swapped at the commit)
+    bool have_cur = false;                 // a refresh has been committed
+    size_t snap_n = 0;                     // floats in a snapshot
+    int32_t snap_arch = 0;
     no::DevBuf<float> mean;                // [n_hot, feat_dim]
     no::DevBuf<char> x0;                   // bf16 tables only: the hot vertices' own rows
     no::DevBuf<float> x_f32;               // bf16 tables only: the same rows in fp32
@@ -90,7 +94,7 @@ struct RefreshState {
         if (ev_snap) { (void)hipEventDestroy(ev_snap); ev_snap = nullptr; }
         if (ev_done) { (void)hipEventDestroy(ev_done); ev_done = nullptr; }
         if (blocks) { blocks->release(); delete blocks; blocks = nullptr; }
-        emb_pending.release(); version_pending.release(); snap.release(); mean.release(); x0.release(); x_f32.release();
+        emb_pending.release(); version_pending.release(); snap.release(); snap_cur.release(); mean.release(); x0.release(); x_f32.release();
         pending = false;
     }
 };

@@ -23,7 +23,9 @@ static int32_t refresh_create(no_cache_s* c, no_graph_s* g, no_dtype dt, int32_t
     NO_CHECK(blocks_create_impl(g, (int32_t)c->n_hot, &fanout, 1, false, &r->blocks));
     NO_CHECK(r->emb_pending.alloc((size_t)c->n_hot * c->emb_dim));
     NO_CHECK(r->version_pending.alloc((size_t)c->n_hot));
-    NO_CHECK(r->snap.alloc((size_t)2 * feat_dim * c->emb_dim + c->emb_dim));
+    r->snap_n = (size_t)2 * feat_dim * c->emb_dim + c->emb_dim;
+    NO_CHECK(r->snap.alloc(r->snap_n));
+    NO_CHECK(r->snap_cur.alloc(r->snap_n));
     NO_CHECK(r->mean.alloc((size_t)c->n_hot * feat_dim));
     if (dt == NO_BF16) {
         NO_CHECK(r->x0.alloc((size_t)c->n_hot * feat_dim * 2));
@@ -71,6 +73,7 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
     NO_HIP_CHECK(hipEventRecord(r->ev_snap, st));
     NO_HIP_CHECK(hipStreamWaitEvent(r->stream, r->ev_snap, 0));
 
+    r->snap_arch = arch;
     const bool bf16 = dt == NO_BF16 && arch == NO_ARCH_SAGE_MEAN;    // only the separate self path needs the rows' own copy
     SideGather sg;
     sg.table = d_features;
@@ -102,6 +105,8 @@ int32_t refresh_commit_impl(no_cache_s* c, hipStream_t st) {
     // work queued on `st` so far holds the old pointers; work queued from here on sees the new rows
     std::swap(c->emb.p, r->emb_pending.p);
     std::swap(c->version.p, r->version_pending.p);
+    std::swap(r->snap.p, r->snap_cur.p);
+    r->have_cur = true;
     r->pending = false;
     return NO_OK;
 }

@@ -141,7 +141,7 @@ extern "C" int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t
     m->ws_bytes = ws_bytes;
     NO_CHECK(m->ws.alloc(ws_bytes));
     NO_CHECK(m->row_loss.alloc((size_t)n_seeds_cap));
-    NO_CHECK(m->stats.alloc(1));
+    NO_CHECK(m->stats.alloc(2));        // the record, and behind it the two words of the weight-drift query
     NO_HIP_CHECK(hipMemset(m->stats.p, 0, sizeof(no_step_stats)));
     NO_HIP_CHECK(hipDeviceSynchronize());
     guard.m = nullptr;
@@ -424,6 +424,61 @@ extern "C" int32_t no_train_step_ahead(no_model_t m, no_graph_t g, const void* d
                                        no_step_stats* h_stats, void* stream) {
     return train_step_impl(m, g, d_features, d_labels, d_seeds, n_seeds, d_next_seeds, n_next_seeds,
                            commit_refresh_before_next, cache, step, seed, lr, d_stats, h_stats, stream);
+}
+
+namespace no {
+// out[0] = max(out[0], scale * max_i |a[i] - (b ? b[i] : 0)|) on the bit pattern (values are >= 0, so the unsigned
+// integer order is the float order and the integer max is order independent)
+__global__ void __launch_bounds__(256) max_abs_diff_kernel(const float* __restrict__ a, const float* __restrict__ b, int64_t n,
+                                                           float scale, uint32_t* out_bits) {
+    float m = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        m = fmaxf(m, fabsf(a[i] - (b ? b[i] : 0.f)));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if ((threadIdx.x & 63) == 0) atomicMax(out_bits, __float_as_uint(m * scale));
+}
+}  // namespace no
+
+extern "C" int32_t no_model_weight_drift(no_model_t m, no_cache_t cache, float lr, float* h_max_update, float* h_drift,
+                                         void* stream) {
+    clear_error();
+    NO_REQUIRE(m && h_max_update && h_drift, NO_ERR_INVALID_ARG, "no_model_weight_drift: NULL argument");
+    NO_REQUIRE(lr >= 0.f, NO_ERR_INVALID_ARG, "no_model_weight_drift: lr must be >= 0");
+    hipStream_t st = (hipStream_t)stream;
+    const int32_t d_in = m->dims[0], d_out = m->dims[1];
+    const size_t wsz = (size_t)d_in * d_out;
+    const bool gcn = m->arch == NO_ARCH_GCN;
+    uint32_t* bits = (uint32_t*)(m->stats.p + 1);           // two words behind the statistics record
+    NO_CHECK(fill_i32((int32_t*)bits, 0, 2, st));
+    auto launch = [&](const float* a, const float* b, size_t n, float scale, uint32_t* out) {
+        int64_t blocks = ceil_div((int64_t)n, 256 * 8);
+        if (blocks > 256) blocks = 256;
+        if (blocks < 1) blocks = 1;
+        hipLaunchKernelGGL(max_abs_diff_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a, b, (int64_t)n, scale, out);
+    };
+    // the largest change of a layer-1 parameter in the last update: lr * max |gradient|
+    launch(m->grads.p + m->off_w_self[0], nullptr, wsz, lr, bits);
+    if (!gcn) launch(m->grads.p + m->off_w_neigh[0], nullptr, wsz, lr, bits);
+    launch(m->grads.p + m->off_bias[0], nullptr, (size_t)d_out, lr, bits);
+    // the drift of the layer-1 parameters away from the ones the rows now in the cache were refreshed with
+    const RefreshState* r = cache ? cache->refresh : nullptr;
+    const bool have = r && r->have_cur && r->feat_dim == d_in && cache->emb_dim == d_out && (r->snap_arch == NO_ARCH_GCN) == gcn;
+    if (have) {
+        const float* s_self = r->snap_cur.p;
+        const float* s_neigh = s_self + wsz;
+        const float* s_bias = s_neigh + wsz;
+        launch(m->params.p + m->off_w_self[0], s_self, wsz, 1.f, bits + 1);
+        if (!gcn) launch(m->params.p + m->off_w_neigh[0], s_neigh, wsz, 1.f, bits + 1);
+        launch(m->params.p + m->off_bias[0], s_bias, (size_t)d_out, 1.f, bits + 1);
+    }
+    NO_CHECK(launch_status("weight drift"));
+    float host[2];
+    NO_HIP_CHECK(hipMemcpyAsync(host, bits, 8, hipMemcpyDeviceToHost, st));
+    NO_HIP_CHECK(hipStreamSynchronize(st));
+    *h_max_update = host[0];
+    *h_drift = have ? host[1] : -1.f;
+    return NO_OK;
 }
 
 extern "C" int32_t no_model_destroy(no_model_t m) {

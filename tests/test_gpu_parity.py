@@ -336,6 +336,7 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
     ow = [tuple(np.asarray(t, np.float64) for t in pick(x)) for x in weights]
     hits = 0
     pending = None
+    pending_snap = current_snap = None          # layer-1 parameters behind the pending / the committed rows
     seed_tensors = [dev(si.batch_seeds(train, w.batch, t)) for t in range(n_steps)]
     commit = False
     for step in range(n_steps):
@@ -346,8 +347,10 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
             # start the refresh for the next one from the parameters as they stand now
             if pending is not None:
                 ora.commit_refresh(oc, *pending)
+                current_snap = pending_snap
                 if not ahead:           # sampling ahead: committed inside the previous step's call
                     b.no_refresh_hot_commit(gc)
+            pending_snap = ow[0]
             pending = ora.refresh_hot(og, feat, oc, ow[0], w.fanouts[-1], step, w.seed, feat_is_bf16=bf16)
             p1 = b.no_model_params(model, 1)
             b.no_refresh_hot_begin(gc, gg, tfeat, p1[0], None if gcn else p1[1], p1[2], w.fanouts[-1], step, w.seed)
@@ -403,6 +406,17 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
                 assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step))
             for t, ref, name in zip(pick(b.no_model_params(model, l)), r.new_weights[l - 1], names):
                 assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name[1:], l, step))
+        if superbatch and not ahead:
+            # weight-drift monitor (Section 4.3): largest change of a layer-1 parameter in this update, and the drift
+            # from the parameters behind the rows now in the cache
+            upd, drift = b.no_model_weight_drift(model, gc, lr)
+            o_upd = ora.max_weight_update(ow[0], r.new_weights[0])
+            assert abs(upd - o_upd) <= RTOL * o_upd + 1e-12, (upd, o_upd)
+            if current_snap is None:
+                assert drift == -1.0
+            else:
+                o_drift = ora.weight_drift(r.new_weights[0], current_snap)
+                assert abs(drift - o_drift) <= RTOL * o_drift + 1e-7, (drift, o_drift)
         ow = r.new_weights
         if use_cache and oc.n_hot > 0:
             view = b.no_cache_view(gc, V)
