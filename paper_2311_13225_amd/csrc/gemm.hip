@@ -208,8 +208,7 @@ __device__ __forceinline__ void run_steps(const StepSource& p0, const StepSource
                                           floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
     constexpr int A_FLOATS = TileShape<A_KC, BM>::FLOATS, B_FLOATS = TileShape<B_KC, BN>::FLOATS;
     if (total_steps <= 0) return;
-    // One register stage (a second one measured slower: the registers cost more occupancy than the
-    // longer load window gains).
+    // One register stage (see run_steps2 for two).
     float4 ra[BM / 32], rb[BN / 32];
     // memory rows of this thread's tile rows (loop invariant; used by the KC layout only)
     int32_t arow[2][BM / 32], brow[BN / 32];
@@ -238,6 +237,52 @@ __device__ __forceinline__ void run_steps(const StepSource& p0, const StepSource
     }
 }
 
+// Two register stages: the loads of steps t+1 and t+2 are in flight while step t is multiplied, so a load has two
+// steps to arrive instead of one. Worth its 4 x (BM + BN) / 32 extra registers where few blocks share a compute unit
+// (tall-skinny products whose tiles do not even fill the chip twice): there the step time is the load latency.
+template <bool A_KC, bool B_KC, int BM, int BN>
+__device__ __forceinline__ void run_steps2(const StepSource& p0, const StepSource& p1, int total_steps, int am0, int a_lim,
+                                           int bn0, int b_lim, float* As, float* Bs,
+                                           floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
+    constexpr int A_FLOATS = TileShape<A_KC, BM>::FLOATS, B_FLOATS = TileShape<B_KC, BN>::FLOATS;
+    if (total_steps <= 0) return;
+    float4 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
+    int32_t arow[2][BM / 32], brow[BN / 32];
+#pragma unroll
+    for (int i = 0; i < BM / 32; ++i) {
+        const int gx = am0 + (int)(threadIdx.x >> 3) + 32 * i;
+        arow[0][i] = (A_KC && p0.a_rows) ? (gx < a_lim ? p0.a_rows[gx] : 0) : gx;
+        arow[1][i] = (A_KC && p1.a_rows) ? (gx < a_lim ? p1.a_rows[gx] : 0) : gx;
+    }
+#pragma unroll
+    for (int i = 0; i < BN / 32; ++i) brow[i] = bn0 + (int)(threadIdx.x >> 3) + 32 * i;
+    fetch_step<A_KC, B_KC, BM, BN>(ra0, rb0, p0, p1, 0, am0, a_lim, bn0, b_lim, arow, brow);
+    tile_store<A_KC, BM>(ra0, As);
+    tile_store<B_KC, BN>(rb0, Bs);
+    if (total_steps > 1) fetch_step<A_KC, B_KC, BM, BN>(ra0, rb0, p0, p1, 1, am0, a_lim, bn0, b_lim, arow, brow);
+    if (total_steps > 2) fetch_step<A_KC, B_KC, BM, BN>(ra1, rb1, p0, p1, 2, am0, a_lim, bn0, b_lim, arow, brow);
+    __syncthreads();
+    for (int t = 0; t < total_steps; t += 2) {
+        // even step: LDS copy 0 is current, stage 0 holds step t+1
+        tile_mma<A_KC, B_KC, BM, BN>(As, Bs, acc, wm, wn);
+        if (t + 1 < total_steps) {
+            tile_store<A_KC, BM>(ra0, As + A_FLOATS);
+            tile_store<B_KC, BN>(rb0, Bs + B_FLOATS);
+            if (t + 3 < total_steps) fetch_step<A_KC, B_KC, BM, BN>(ra0, rb0, p0, p1, t + 3, am0, a_lim, bn0, b_lim, arow, brow);
+        }
+        __syncthreads();
+        if (t + 1 >= total_steps) break;
+        // odd step: LDS copy 1 is current, stage 1 holds step t+2
+        tile_mma<A_KC, B_KC, BM, BN>(As + A_FLOATS, Bs + B_FLOATS, acc, wm, wn);
+        if (t + 2 < total_steps) {
+            tile_store<A_KC, BM>(ra1, As);
+            tile_store<B_KC, BN>(rb1, Bs);
+            if (t + 4 < total_steps) fetch_step<A_KC, B_KC, BM, BN>(ra1, rb1, p0, p1, t + 4, am0, a_lim, bn0, b_lim, arow, brow);
+        }
+        __syncthreads();
+    }
+}
+
 // Workgroups are handed to the 8 accelerator dies (XCDs, each with its own L2) round-robin by linear
 // id. The tiles that share an operand panel (all column tiles of one row tile; all tiles of one
 // reduction slice) get consecutive *logical* ids, and logical ids are dealt out in chunks per XCD, so
@@ -251,7 +296,7 @@ static inline unsigned xcd_padded(int64_t total) { return (unsigned)(ceil_div(to
 
 // ------------------------------------------------------------------------------------------ NN
 
-template <bool B_KC, int BM, int BN>
+template <bool B_KC, int BM, int BN, int STAGES = 1>
 __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
     constexpr int MI = BM / 64, NI = BN / 64;
     __shared__ __attribute__((aligned(16))) float As[2 * TileShape<true, BM>::FLOATS];
@@ -280,7 +325,8 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
                       full_x ? g.K[q0] / BK : 0, -1};
         StepSource p1{g.A[q1], g.lda[q1], g.B[q1], g.ldb[q1], g.a_rows[q1], 0, g.K[q1],
                       n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0, full_x ? g.K[q1] / BK : 0, -1};
-        run_steps<true, B_KC, BM, BN>(p0, p1, p0.n_steps + p1.n_steps, m0, M, n0, g.N, As, Bs, acc, wm, wn);
+        if (STAGES == 2) run_steps2<true, B_KC, BM, BN>(p0, p1, p0.n_steps + p1.n_steps, m0, M, n0, g.N, As, Bs, acc, wm, wn);
+        else run_steps<true, B_KC, BM, BN>(p0, p1, p0.n_steps + p1.n_steps, m0, M, n0, g.N, As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
     float* C = g.C[prob];
@@ -444,7 +490,14 @@ static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st, hipEv
     dim3 grid(xcd_padded(ceil_div(a.N, bn) * ceil_div(a.M_cap, bm) * z));
     if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), st, ev0, ev1, a);
-    else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64>), grid, dim3(256), st, ev0, ev1, a);
+    else {
+        // 64x64 tiles are picked when larger ones would leave compute units idle, i.e. when only two or three
+        // blocks share a unit: two register stages (NO_GEMM_STAGES=1 goes back to one: tuning aid)
+        static const char* env_st = getenv("NO_GEMM_STAGES");
+        const int stages = env_st ? atoi(env_st) : 2;
+        if (stages == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64>), grid, dim3(256), st, ev0, ev1, a);
+    }
 }
 
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
@@ -470,7 +523,7 @@ int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent
 
 // ------------------------------------------------------------------------------------------ TN
 
-template <int BM, int BN>
+template <int BM, int BN, int STAGES = 1>
 __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
     constexpr int MI = BM / 64, NI = BN / 64;
     __shared__ __attribute__((aligned(16))) float As[2 * TileShape<false, BM>::FLOATS];
@@ -498,7 +551,8 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
         StepSource p0{A, lda, g.G, g.ldg, nullptr, r0, r1, (r1 - r0 + BK - 1) / BK, full_x ? (r1 - r0) / BK : 0, ones_col};
         StepSource p1 = p0;
         p1.n_steps = 0;
-        run_steps<false, false, BM, BN>(p0, p1, p0.n_steps, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
+        if (STAGES == 2) run_steps2<false, false, BM, BN>(p0, p1, p0.n_steps, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
+        else run_steps<false, false, BM, BN>(p0, p1, p0.n_steps, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
     const int rows_out = g.Kp + 1;
@@ -532,7 +586,12 @@ int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0, hi
     if (bm == 128 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 64>), grid, dim3(256), st, ev0, ev1, a);
-    else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64>), grid, dim3(256), st, ev0, ev1, a);
+    else {
+        static const char* env_st = getenv("NO_TN_STAGES");        // tuning aid (two stages measured no faster here)
+        const int stages = env_st ? atoi(env_st) : 1;
+        if (stages == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64>), grid, dim3(256), st, ev0, ev1, a);
+    }
     return launch_status("gemm_tn");
 }
 
