@@ -373,6 +373,8 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
             gh = b.no_model_activations(model, layer, n_rows, 1)[0].cpu().numpy()
             if gh.shape[0] != z_ora.shape[0]:
                 gh = gh[b.block_arrays(blocks_, w.n_layers - 1, sizes_)["compute_pos"]]
+            if z_ora.size == 0:
+                return np.zeros(z_ora.shape, dtype=bool)
             tau = 1e-5 * max(np.abs(z_ora).max(), 1e-30)
             assert (gh[z_ora > tau] > 0).all(), "layer %d: kernel masks a clearly positive pre-activation" % layer
             assert (gh[z_ora < -tau] == 0).all(), "layer %d: kernel keeps a clearly negative pre-activation" % layer
@@ -607,6 +609,17 @@ def test_sampling_ahead_gives_the_same_steps():
                              feat_dim=100, hidden=40, batch=128, feat_dtype="bf16")
     assert run_steps(w3, 6, use_cache=True, lr=0.02, bits=64, superbatch=2, ahead=True) > 0
     assert run_steps(w3, 4, use_cache=True, lr=0.02, bits=64, ahead=True, arch="gcn") > 0
+
+
+@pytest.mark.parametrize("ahead", [False, True])
+def test_every_vertex_hot_leaves_an_empty_bottom_hop(ahead):
+    """Degenerate case of the reuse rule: with every vertex hot, a bulk refresh committed and the bound not yet
+    exceeded, all of V^1 is served from the cache: the bottom hop has no destinations, layer 1 computes nothing and
+    its gradients are exactly zero."""
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=3, hot_fraction=1.0)
+    hits = run_steps(w, 5, use_cache=True, lr=0.02, superbatch=2, ahead=ahead)
+    assert hits > 0
 
 
 def test_sampling_ahead_dropped_when_not_consumed():
