@@ -358,7 +358,7 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
         }
 }
 
-// Small products (few output tiles, e.g. the classifier layer over the seeds): a block owns a 32x32 output
+// Small products (few output tiles, e.g. the classifier layer over the seeds and its input gradient): a block owns a 32x32 output
 // tile and its four wavefronts split the reduction, chunk c of 32 indices going to wave c % 4. Operands go
 // from memory straight into MFMA registers with several chunks of loads in flight, so the product takes a
 // few memory round trips instead of one per 32 indices; the four partial tiles are summed in wave order
@@ -503,11 +503,8 @@ static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st, hipEv
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     if (a.M_cap <= 0 || a.N <= 0) return NO_OK;
     const int64_t z = a.accumulate ? 1 : a.n_problems;
-    int64_t k_total = 0;
-    for (int q = 0; q < a.n_problems; ++q) k_total += a.K[q];
-    if (!a.accumulate) k_total /= a.n_problems;
     static const char* no_small = getenv("NO_GEMM_NO_SMALL");      // tuning aid: keep small products on the tiled kernel
-    if (!no_small && ceil_div(a.M_cap, 64) * ceil_div(a.N, 64) * z <= 128 && k_total >= 128) {
+    if (!no_small && ceil_div(a.M_cap, 64) * ceil_div(a.N, 64) * z <= 128) {
         dim3 grid((unsigned)ceil_div(a.N, 32), (unsigned)ceil_div(a.M_cap, 32), (unsigned)z);
         if (b_transposed) NO_LAUNCH_TIMED((gemm_nn_small_kernel<true>), grid, dim3(256), st, ev0, ev1, a);
         else NO_LAUNCH_TIMED((gemm_nn_small_kernel<false>), grid, dim3(256), st, ev0, ev1, a);
