@@ -636,8 +636,17 @@ __global__ void __launch_bounds__(256) reduce_grads_kernel(const float* __restri
     const bool bias_row = i >= (int64_t)Kp * N;
     if (q == 1 && bias_row) return;
     const float* p = P + (int64_t)q * splits * per + i;
+    // eight partials are requested before the first add; the adds stay in split order
     float s = 0.f;
-    for (int32_t k = 0; k < splits; ++k) s += p[(int64_t)k * per];
+    int32_t k = 0;
+    for (; k + 8 <= splits; k += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = p[(int64_t)(k + j) * per];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += v[j];
+    }
+    for (; k < splits; ++k) s += p[(int64_t)k * per];
     float* gout = bias_row ? g_bias + (i - (int64_t)Kp * N) : (q == 0 ? g_self + i : g_neigh + i);
     *gout = s;
     if (lr != 0.f) {
