@@ -108,9 +108,15 @@ __device__ __forceinline__ float4 tile_frag(const float* S, int x, int chunk, in
 // are summed in the epilogue; larger tiles already interleave 2-4 accumulators.
 template <int BM, int BN> struct AccSets { static constexpr int N = ((BM / 64) * (BN / 64) >= 4) ? 1 : 2; };
 
-template <bool A_KC, bool B_KC, int BM, int BN>
+struct NoSideWork { __device__ __forceinline__ void operator()(int) const {} };
+
+// side(chunk) is issued right after the MFMAs of `chunk` (4 chunks per step): the wave issues in order, so LDS stores
+// and global loads placed there run while the matrix pipe works through the MFMAs just queued, instead of after the
+// whole step's MFMAs have been issued.
+template <bool A_KC, bool B_KC, int BM, int BN, class Side = NoSideWork>
 __device__ __forceinline__ void tile_mma(const float* As, const float* Bs,
-                                         floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
+                                         floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn,
+                                         Side side = Side()) {
     constexpr int MI = BM / 64, NI = BN / 64, SETS = AccSets<BM, BN>::N;
     const int lane = (int)(threadIdx.x & 63);
     const int half = lane >> 5, l32 = lane & 31;
@@ -144,6 +150,8 @@ __device__ __forceinline__ void tile_mma(const float* As, const float* Bs,
                     acc[set][mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[set][mi][ni], 0, 0, 0);
                 }
         __builtin_amdgcn_sched_barrier(0);
+        side(chunk);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -173,15 +181,16 @@ __device__ __forceinline__ float acc_get(const floatx16 (&acc)[SETS][MI][NI], in
 // A block's reduction is a flat list of steps of 32 indices, possibly spanning two operand pairs
 // (phases). LDS holds two copies of the operand tiles: while step t is multiplied out of one copy, the
 // global loads of later steps land in registers and are stored into the other copy, so a step costs one
-// barrier. Interior steps use unguarded 16-byte loads.
+// barrier.
 struct StepSource {
     const float* A; int64_t lda; const float* B; int64_t ldb;
     const int32_t* a_rows;   // KC layout only: tile row x of A is memory row a_rows[x] (NULL: row x)
     int k_begin, k_lim;      // reduction range of this phase
-    int n_steps, n_fast;     // steps in this phase; the first n_fast need no guards
+    int n_steps, n_fast;     // steps in this phase; the first n_fast lie wholly inside the reduction range
     int ones_col;            // virtual column of ones in A (XC layout only), or -1
 };
 
+// Guarded or unguarded fetch of step t of the flat list (any step; used outside the pipelined loop).
 template <bool A_KC, bool B_KC, int BM, int BN>
 __device__ __forceinline__ void fetch_step(float4 (&ra)[BM / 32], float4 (&rb)[BN / 32], const StepSource& p0,
                                            const StepSource& p1, int t, int am0, int a_lim, int bn0, int b_lim,
@@ -202,85 +211,157 @@ __device__ __forceinline__ void fetch_step(float4 (&ra)[BM / 32], float4 (&rb)[B
     }
 }
 
-template <bool A_KC, bool B_KC, int BM, int BN>
-__device__ __forceinline__ void run_steps(const StepSource& p0, const StepSource& p1, int total_steps, int am0, int a_lim,
-                                          int bn0, int b_lim, float* As, float* Bs,
-                                          floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
+// The steps that lie wholly inside the operands ("fast" steps: all but the last step of a phase whose length is
+// no multiple of 32) run first, through a pipeline with S register stages and S LDS copies: while step f is
+// multiplied out of copy f % S, the loads of steps f+1 .. f+S are in flight (a load has S - 1 whole steps to
+// arrive before an LDS store waits for it). The loop body holds no branch around a load: every step issues the
+// same loads (past the last pipelined step they re-read that step and the values are dropped), so the wait
+// before an LDS store counts exactly the loads issued after the ones it needs instead of draining them all.
+// The pipeline takes a multiple of S steps (the loop is unrolled S times, since registers and LDS copies are
+// indexed statically). The steps left over (up to S - 1 fast ones and the at most two guarded ones) are
+// requested before the loop, rest in registers meanwhile, and are multiplied after it. Tile rows beyond the
+// operand are clamped to its last row in the KC layout (their products belong to output rows that are never
+// stored); in the XC layout an edge tile has no fast steps and takes the plain loop.
+template <bool A_KC, bool B_KC, int BM, int BN, int S>
+__device__ __forceinline__ void run_steps(StepSource p0, StepSource p1, int am0, int a_lim, int bn0, int b_lim, float* As,
+                                          float* Bs, floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
     constexpr int A_FLOATS = TileShape<A_KC, BM>::FLOATS, B_FLOATS = TileShape<B_KC, BN>::FLOATS;
+    constexpr int PA = BM / 32, PB = BN / 32;
+    const int total_steps = p0.n_steps + p1.n_steps;
     if (total_steps <= 0) return;
-    // One register stage (see run_steps2 for two).
-    float4 ra[BM / 32], rb[BN / 32];
+    const int tid = (int)threadIdx.x;
+    const bool x_fast = (A_KC || am0 + BM <= a_lim) && (B_KC || bn0 + BN <= b_lim);
+    if (!x_fast) p0.n_fast = p1.n_fast = 0;
+    const int F0 = p0.n_fast, F = p0.n_fast + p1.n_fast;
     // memory rows of this thread's tile rows (loop invariant; used by the KC layout only)
-    int32_t arow[2][BM / 32], brow[BN / 32];
+    int32_t arow[2][PA], brow[PB];
 #pragma unroll
-    for (int i = 0; i < BM / 32; ++i) {
-        const int gx = am0 + (int)(threadIdx.x >> 3) + 32 * i;
-        arow[0][i] = (A_KC && p0.a_rows) ? (gx < a_lim ? p0.a_rows[gx] : 0) : gx;
-        arow[1][i] = (A_KC && p1.a_rows) ? (gx < a_lim ? p1.a_rows[gx] : 0) : gx;
+    for (int i = 0; i < PA; ++i) {
+        const int gx = min(am0 + (tid >> 3) + 32 * i, a_lim - 1);
+        arow[0][i] = (A_KC && p0.a_rows) ? p0.a_rows[gx] : gx;
+        arow[1][i] = (A_KC && p1.a_rows) ? p1.a_rows[gx] : gx;
     }
 #pragma unroll
-    for (int i = 0; i < BN / 32; ++i) brow[i] = bn0 + (int)(threadIdx.x >> 3) + 32 * i;
-    fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, 0, am0, a_lim, bn0, b_lim, arow, brow);
-    tile_store<A_KC, BM>(ra, As);
-    tile_store<B_KC, BN>(rb, Bs);
-    __syncthreads();
-    for (int t = 0; t < total_steps; ++t) {
-        const int cur = t & 1;
-        const bool more = t + 1 < total_steps;
-        if (more) fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, t + 1, am0, a_lim, bn0, b_lim, arow, brow);
-        tile_mma<A_KC, B_KC, BM, BN>(As + cur * A_FLOATS, Bs + cur * B_FLOATS, acc, wm, wn);
-        if (more) {
-            tile_store<A_KC, BM>(ra, As + (cur ^ 1) * A_FLOATS);
-            tile_store<B_KC, BN>(rb, Bs + (cur ^ 1) * B_FLOATS);
-        }
-        __syncthreads();
-    }
-}
+    for (int i = 0; i < PB; ++i) brow[i] = min(bn0 + (tid >> 3) + 32 * i, b_lim - 1);
 
-// Two register stages: the loads of steps t+1 and t+2 are in flight while step t is multiplied, so a load has two
-// steps to arrive instead of one. Worth its 4 x (BM + BN) / 32 extra registers where few blocks share a compute unit
-// (tall-skinny products whose tiles do not even fill the chip twice): there the step time is the load latency.
-template <bool A_KC, bool B_KC, int BM, int BN>
-__device__ __forceinline__ void run_steps2(const StepSource& p0, const StepSource& p1, int total_steps, int am0, int a_lim,
-                                           int bn0, int b_lim, float* As, float* Bs,
-                                           floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
-    constexpr int A_FLOATS = TileShape<A_KC, BM>::FLOATS, B_FLOATS = TileShape<B_KC, BN>::FLOATS;
-    if (total_steps <= 0) return;
-    float4 ra0[BM / 32], rb0[BN / 32], ra1[BM / 32], rb1[BN / 32];
-    int32_t arow[2][BM / 32], brow[BN / 32];
-#pragma unroll
-    for (int i = 0; i < BM / 32; ++i) {
-        const int gx = am0 + (int)(threadIdx.x >> 3) + 32 * i;
-        arow[0][i] = (A_KC && p0.a_rows) ? (gx < a_lim ? p0.a_rows[gx] : 0) : gx;
-        arow[1][i] = (A_KC && p1.a_rows) ? (gx < a_lim ? p1.a_rows[gx] : 0) : gx;
-    }
-#pragma unroll
-    for (int i = 0; i < BN / 32; ++i) brow[i] = bn0 + (int)(threadIdx.x >> 3) + 32 * i;
-    fetch_step<A_KC, B_KC, BM, BN>(ra0, rb0, p0, p1, 0, am0, a_lim, bn0, b_lim, arow, brow);
-    tile_store<A_KC, BM>(ra0, As);
-    tile_store<B_KC, BN>(rb0, Bs);
-    if (total_steps > 1) fetch_step<A_KC, B_KC, BM, BN>(ra0, rb0, p0, p1, 1, am0, a_lim, bn0, b_lim, arow, brow);
-    if (total_steps > 2) fetch_step<A_KC, B_KC, BM, BN>(ra1, rb1, p0, p1, 2, am0, a_lim, bn0, b_lim, arow, brow);
-    __syncthreads();
-    for (int t = 0; t < total_steps; t += 2) {
-        // even step: LDS copy 0 is current, stage 0 holds step t+1
-        tile_mma<A_KC, B_KC, BM, BN>(As, Bs, acc, wm, wn);
-        if (t + 1 < total_steps) {
-            tile_store<A_KC, BM>(ra0, As + A_FLOATS);
-            tile_store<B_KC, BN>(rb0, Bs + B_FLOATS);
-            if (t + 3 < total_steps) fetch_step<A_KC, B_KC, BM, BN>(ra0, rb0, p0, p1, t + 3, am0, a_lim, bn0, b_lim, arow, brow);
-        }
+    if (F == 0) {
+        // plain loop, one register stage, every step through the guarded fetch
+        float4 ra[PA], rb[PB];
+        fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, 0, am0, a_lim, bn0, b_lim, arow, brow);
+        tile_store<A_KC, BM>(ra, As);
+        tile_store<B_KC, BN>(rb, Bs);
         __syncthreads();
-        if (t + 1 >= total_steps) break;
-        // odd step: LDS copy 1 is current, stage 1 holds step t+2
-        tile_mma<A_KC, B_KC, BM, BN>(As + A_FLOATS, Bs + B_FLOATS, acc, wm, wn);
-        if (t + 2 < total_steps) {
-            tile_store<A_KC, BM>(ra1, As);
-            tile_store<B_KC, BN>(rb1, Bs);
-            if (t + 4 < total_steps) fetch_step<A_KC, B_KC, BM, BN>(ra1, rb1, p0, p1, t + 4, am0, a_lim, bn0, b_lim, arow, brow);
+        for (int t = 0; t < total_steps; ++t) {
+            const int cur = t & 1;
+            const bool more = t + 1 < total_steps;
+            if (more) fetch_step<A_KC, B_KC, BM, BN>(ra, rb, p0, p1, t + 1, am0, a_lim, bn0, b_lim, arow, brow);
+            tile_mma<A_KC, B_KC, BM, BN>(As + cur * A_FLOATS, Bs + cur * B_FLOATS, acc, wm, wn);
+            if (more) {
+                tile_store<A_KC, BM>(ra, As + (cur ^ 1) * A_FLOATS);
+                tile_store<B_KC, BN>(rb, Bs + (cur ^ 1) * B_FLOATS);
+            }
+            __syncthreads();
         }
-        __syncthreads();
+        return;
     }
+
+    const int Fp = F - F % S;
+    // flat step index of leftover i: first the fast steps the pipeline does not take, then the guarded ones
+    constexpr int NT = S + 1;
+    const int n_left = F - Fp;
+    const int g0 = p0.n_fast < p0.n_steps ? p0.n_fast : -1;
+    const int g1 = p1.n_fast < p1.n_steps ? p0.n_steps + p1.n_fast : -1;
+    const int n_tail = n_left + (g0 >= 0) + (g1 >= 0);
+    auto tail_step = [&](int i) {
+        if (i < n_left) { const int f = Fp + i; return f < F0 ? f : p0.n_steps + (f - F0); }
+        if (i == n_left && g0 >= 0) return g0;
+        return g1;
+    };
+    // per-thread load addresses of the next fast step, advanced step by step
+    constexpr int XQ_A = BM / 4, ROWS_A = 256 / XQ_A, XQ_B = BN / 4, ROWS_B = 256 / XQ_B;
+    const float* pa[PA];
+    const float* pb[PB];
+    int64_t inc_a, inc_b;
+    auto point_a = [&](const StepSource& p, bool second) {
+#pragma unroll
+        for (int i = 0; i < PA; ++i)
+            pa[i] = A_KC ? p.A + (int64_t)(second ? arow[1][i] : arow[0][i]) * p.lda + p.k_begin + (tid & 7) * 4
+                         : p.A + (int64_t)(p.k_begin + tid / XQ_A + ROWS_A * i) * p.lda + am0 + (tid % XQ_A) * 4;
+        inc_a = A_KC ? BK : BK * p.lda;
+    };
+    auto point_b = [&](const StepSource& p) {
+#pragma unroll
+        for (int i = 0; i < PB; ++i)
+            pb[i] = B_KC ? p.B + (int64_t)brow[i] * p.ldb + p.k_begin + (tid & 7) * 4
+                         : p.B + (int64_t)(p.k_begin + tid / XQ_B + ROWS_B * i) * p.ldb + bn0 + (tid % XQ_B) * 4;
+        inc_b = B_KC ? BK : BK * p.ldb;
+    };
+    if (F0 > 0) { point_a(p0, false); point_b(p0); } else { point_a(p1, true); point_b(p1); }
+    int fa = 0, fb = 0;      // fast steps whose A / B loads have been issued, less one
+    auto fetch_a = [&](float4 (&r)[PA]) {
+#pragma unroll
+        for (int i = 0; i < PA; ++i) r[i] = load4_fast(pa[i]);
+        if (fa + 1 < Fp) {
+            ++fa;
+            if (fa == F0) point_a(p1, true);
+            else {
+#pragma unroll
+                for (int i = 0; i < PA; ++i) pa[i] += inc_a;
+            }
+        }
+    };
+    auto fetch_b = [&](float4 (&r)[PB]) {
+#pragma unroll
+        for (int i = 0; i < PB; ++i) r[i] = load4_fast(pb[i]);
+        if (fb + 1 < Fp) {
+            ++fb;
+            if (fb == F0) point_b(p1);
+            else {
+#pragma unroll
+                for (int i = 0; i < PB; ++i) pb[i] += inc_b;
+            }
+        }
+    };
+
+    // Step f (position s = f % S of the unrolled loop): LDS copy s is current; stage (s + 1) % S holds step f + 1,
+    // goes to copy (s + 1) % S (last read in step f + 1 - S, which a barrier has closed) and is refilled with
+    // step f + 1 + S. The stores and loads are issued between the MFMA groups of the current step.
+    float4 ra[S][PA], rb[S][PB];
+    if (Fp > 0) {
+        fetch_a(ra[0]); fetch_b(rb[0]);
+        tile_store<A_KC, BM>(ra[0], As);
+        tile_store<B_KC, BN>(rb[0], Bs);
+#pragma unroll
+        for (int i = 1; i <= S; ++i) { fetch_a(ra[i % S]); fetch_b(rb[i % S]); }
+        __syncthreads();
+        for (int f = 0; f < Fp; f += S) {
+#pragma unroll
+            for (int st = 0; st < S; ++st) {
+                const int nx = (st + 1) % S;
+                tile_mma<A_KC, B_KC, BM, BN>(As + st * A_FLOATS, Bs + st * B_FLOATS, acc, wm, wn, [&](int chunk) {
+                    if (chunk == 0) tile_store<A_KC, BM>(ra[nx], As + nx * A_FLOATS);
+                    if (chunk == 1) tile_store<B_KC, BN>(rb[nx], Bs + nx * B_FLOATS);
+                    if (chunk == 2) fetch_a(ra[nx]);
+                    if (chunk == 3) fetch_b(rb[nx]);
+                });
+                __syncthreads();
+            }
+        }
+    }
+    // Every LDS copy is free here: the last barrier followed the last reads. Leftover i goes through copy i % S;
+    // by the time copy i % S is written again (leftover i + S) S >= 2 barriers have passed since it was read.
+    float4 rta[NT][PA], rtb[NT][PB];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+        if (i < n_tail) fetch_step<A_KC, B_KC, BM, BN>(rta[i], rtb[i], p0, p1, tail_step(i), am0, a_lim, bn0, b_lim, arow, brow);
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+        if (i < n_tail) {
+            tile_store<A_KC, BM>(rta[i], As + (i % S) * A_FLOATS);
+            tile_store<B_KC, BN>(rtb[i], Bs + (i % S) * B_FLOATS);
+            __syncthreads();
+            tile_mma<A_KC, B_KC, BM, BN>(As + (i % S) * A_FLOATS, Bs + (i % S) * B_FLOATS, acc, wm, wn);
+        }
 }
 
 // Workgroups are handed to the 8 accelerator dies (XCDs, each with its own L2) round-robin by linear
@@ -296,11 +377,11 @@ static inline unsigned xcd_padded(int64_t total) { return (unsigned)(ceil_div(to
 
 // ------------------------------------------------------------------------------------------ NN
 
-template <bool B_KC, int BM, int BN, int STAGES = 1>
-__global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
+template <bool B_KC, int BM, int BN, int S = 2, int OCC = 2>
+__global__ void __launch_bounds__(256, OCC) gemm_nn_kernel(GemmNNArgs g) {
     constexpr int MI = BM / 64, NI = BN / 64;
-    __shared__ __attribute__((aligned(16))) float As[2 * TileShape<true, BM>::FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[2 * TileShape<B_KC, BN>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float As[S * TileShape<true, BM>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float Bs[S * TileShape<B_KC, BN>::FLOATS];
     int M = *g.d_M;
     if (M > g.M_cap) M = g.M_cap;
     // the grid covers the row capacity; only the tiles of the actual M rows are dealt out to the XCDs
@@ -319,14 +400,12 @@ __global__ void __launch_bounds__(256) gemm_nn_kernel(GemmNNArgs g) {
     floatx16 acc[SETS][MI][NI];
     acc_zero<SETS, MI, NI>(acc);
     {
-        const bool full_x = (m0 + BM <= M) && (n0 + BN <= g.N);
         const int q0 = g.accumulate ? 0 : prob, q1 = g.accumulate && n_phases > 1 ? 1 : q0;
         StepSource p0{g.A[q0], g.lda[q0], g.B[q0], g.ldb[q0], g.a_rows[q0], 0, g.K[q0], (g.K[q0] + BK - 1) / BK,
-                      full_x ? g.K[q0] / BK : 0, -1};
+                      g.K[q0] / BK, -1};
         StepSource p1{g.A[q1], g.lda[q1], g.B[q1], g.ldb[q1], g.a_rows[q1], 0, g.K[q1],
-                      n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0, full_x ? g.K[q1] / BK : 0, -1};
-        if (STAGES == 2) run_steps2<true, B_KC, BM, BN>(p0, p1, p0.n_steps + p1.n_steps, m0, M, n0, g.N, As, Bs, acc, wm, wn);
-        else run_steps<true, B_KC, BM, BN>(p0, p1, p0.n_steps + p1.n_steps, m0, M, n0, g.N, As, Bs, acc, wm, wn);
+                      n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0, n_phases > 1 ? g.K[q1] / BK : 0, -1};
+        run_steps<true, B_KC, BM, BN, S>(p0, p1, m0, M, n0, g.N, As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
     float* C = g.C[prob];
@@ -491,12 +570,16 @@ static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st, hipEv
     if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), st, ev0, ev1, a);
     else {
-        // 64x64 tiles are picked when larger ones would leave compute units idle, i.e. when only two or three
-        // blocks share a unit: two register stages (NO_GEMM_STAGES=1 goes back to one: tuning aid)
+        // NO_GEMM_STAGES=<2|3|4> picks the pipeline depth of the 64x64 kernel (tuning aid)
         static const char* env_st = getenv("NO_GEMM_STAGES");
-        const int stages = env_st ? atoi(env_st) : 2;
-        if (stages == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64>), grid, dim3(256), st, ev0, ev1, a);
+        const int stages = env_st ? atoi(env_st) : 3;
+        static const char* env_occ = getenv("NO_GEMM_OCC");
+        const int occ = env_occ ? atoi(env_occ) : 3;
+        if (stages == 2 && occ == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else if (stages == 2 && occ == 3) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
+        else if (stages == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 4>), grid, dim3(256), st, ev0, ev1, a);
+        else if (occ == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 3, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 3, 3>), grid, dim3(256), st, ev0, ev1, a);
     }
 }
 
@@ -520,11 +603,11 @@ int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent
 
 // ------------------------------------------------------------------------------------------ TN
 
-template <int BM, int BN, int STAGES = 1>
-__global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
+template <int BM, int BN, int S = 2, int OCC = 2>
+__global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(GemmTNArgs g) {
     constexpr int MI = BM / 64, NI = BN / 64;
-    __shared__ __attribute__((aligned(16))) float As[2 * TileShape<false, BM>::FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[2 * TileShape<false, BN>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float As[S * TileShape<false, BM>::FLOATS];
+    __shared__ __attribute__((aligned(16))) float Bs[S * TileShape<false, BN>::FLOATS];
     int R = *g.d_R;
     if (R > g.R_cap) R = g.R_cap;
     // plain 3-D grid: dealing the slices out per XCD measured slower here (the partial tiles are written
@@ -544,12 +627,10 @@ __global__ void __launch_bounds__(256) gemm_tn_kernel(GemmTNArgs g) {
     const int64_t lda = g.lda[prob];
     const int ones_col = prob == 0 ? g.Kp : -1;       // product 0 carries the column sums of G in row Kp
     if (r0 < r1) {
-        const bool full_x = (m0 + BM <= g.Kp) && (n0 + BN <= g.N);
-        StepSource p0{A, lda, g.G, g.ldg, nullptr, r0, r1, (r1 - r0 + BK - 1) / BK, full_x ? (r1 - r0) / BK : 0, ones_col};
+        StepSource p0{A, lda, g.G, g.ldg, nullptr, r0, r1, (r1 - r0 + BK - 1) / BK, (r1 - r0) / BK, ones_col};
         StepSource p1 = p0;
-        p1.n_steps = 0;
-        if (STAGES == 2) run_steps2<false, false, BM, BN>(p0, p1, p0.n_steps, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
-        else run_steps<false, false, BM, BN>(p0, p1, p0.n_steps, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
+        p1.n_steps = p1.n_fast = 0;
+        run_steps<false, false, BM, BN, S>(p0, p1, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
     }
     const int lane = (int)(threadIdx.x & 63);
     const int rows_out = g.Kp + 1;
@@ -584,10 +665,15 @@ int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0, hi
     else if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 64>), grid, dim3(256), st, ev0, ev1, a);
     else {
-        static const char* env_st = getenv("NO_TN_STAGES");        // tuning aid (two stages measured no faster here)
-        const int stages = env_st ? atoi(env_st) : 1;
-        if (stages == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64>), grid, dim3(256), st, ev0, ev1, a);
+        static const char* env_st = getenv("NO_TN_STAGES");        // tuning aid: pipeline depth 2, 3 or 4
+        const int stages = env_st ? atoi(env_st) : 3;
+        static const char* env_occ = getenv("NO_TN_OCC");
+        const int occ = env_occ ? atoi(env_occ) : 3;
+        if (stages == 2 && occ == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else if (stages == 2 && occ == 3) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
+        else if (stages == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 4>), grid, dim3(256), st, ev0, ev1, a);
+        else if (occ == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 3, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 3, 3>), grid, dim3(256), st, ev0, ev1, a);
     }
     return launch_status("gemm_tn");
 }
