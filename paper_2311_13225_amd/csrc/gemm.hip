@@ -212,17 +212,21 @@ __device__ __forceinline__ void fetch_step(float4 (&ra)[BM / 32], float4 (&rb)[B
 }
 
 // The steps that lie wholly inside the operands ("fast" steps: all but the last step of a phase whose length is
-// no multiple of 32) run first, through a pipeline with S register stages and S LDS copies: while step f is
-// multiplied out of copy f % S, the loads of steps f+1 .. f+S are in flight (a load has S - 1 whole steps to
-// arrive before an LDS store waits for it). The loop body holds no branch around a load: every step issues the
-// same loads (past the last pipelined step they re-read that step and the values are dropped), so the wait
-// before an LDS store counts exactly the loads issued after the ones it needs instead of draining them all.
-// The pipeline takes a multiple of S steps (the loop is unrolled S times, since registers and LDS copies are
-// indexed statically). The steps left over (up to S - 1 fast ones and the at most two guarded ones) are
-// requested before the loop, rest in registers meanwhile, and are multiplied after it. Tile rows beyond the
+// no multiple of 32) run first, through a pipeline with R register stages and C = 2 G LDS copies, G being the number
+// of steps between two barriers. Step f is multiplied out of copy f % C; meanwhile stage f % R, which holds step
+// f + G, is stored into copy (f + G) % C and refilled with step f + G + R, so a load has R steps to arrive. A
+// barrier closes every G-th step: the copies written during a group of G steps are those read in the next group,
+// and those read in the previous one. With G = 2 a block meets half as many barriers, at twice the LDS.
+// The loop body holds no branch around a load: every step issues the same loads (past the last pipelined step
+// they re-read that step and the values are dropped), so the wait before an LDS store counts exactly the loads
+// issued after the ones it needs instead of draining them all. The pipeline takes a multiple of U = lcm(C, R)
+// steps (the loop is unrolled U times, since registers and LDS copies are indexed statically). The steps left over
+// (up to U - 1 fast ones and the at most two guarded ones) are multiplied after the loop. Tile rows beyond the
 // operand are clamped to its last row in the KC layout (their products belong to output rows that are never
 // stored); in the XC layout an edge tile has no fast steps and takes the plain loop.
-template <bool A_KC, bool B_KC, int BM, int BN, int S>
+constexpr int lcm_small(int a, int b) { int m = a; while (m % b) m += a; return m; }
+
+template <bool A_KC, bool B_KC, int BM, int BN, int GRP, int STG>
 __device__ __forceinline__ void run_steps(StepSource p0, StepSource p1, int am0, int a_lim, int bn0, int b_lim, float* As,
                                           float* Bs, floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
     constexpr int A_FLOATS = TileShape<A_KC, BM>::FLOATS, B_FLOATS = TileShape<B_KC, BN>::FLOATS;
@@ -265,9 +269,10 @@ __device__ __forceinline__ void run_steps(StepSource p0, StepSource p1, int am0,
         return;
     }
 
-    const int Fp = F - F % S;
+    constexpr int G = GRP, R = STG, C = 2 * G, U = lcm_small(C, R);
+    const int Fp = F - F % U;
     // flat step index of leftover i: first the fast steps the pipeline does not take, then the guarded ones
-    constexpr int NT = S + 1;
+    constexpr int NT = U + 1;
     const int n_left = F - Fp;
     const int g0 = p0.n_fast < p0.n_steps ? p0.n_fast : -1;
     const int g1 = p1.n_fast < p1.n_steps ? p0.n_steps + p1.n_fast : -1;
@@ -323,33 +328,36 @@ __device__ __forceinline__ void run_steps(StepSource p0, StepSource p1, int am0,
         }
     };
 
-    // Step f (position s = f % S of the unrolled loop): LDS copy s is current; stage (s + 1) % S holds step f + 1,
-    // goes to copy (s + 1) % S (last read in step f + 1 - S, which a barrier has closed) and is refilled with
-    // step f + 1 + S. The stores and loads are issued between the MFMA groups of the current step.
-    float4 ra[S][PA], rb[S][PB];
+    float4 ra[R][PA], rb[R][PB];
     if (Fp > 0) {
-        fetch_a(ra[0]); fetch_b(rb[0]);
-        tile_store<A_KC, BM>(ra[0], As);
-        tile_store<B_KC, BN>(rb[0], Bs);
+        // steps 0 .. G-1 go to copies 0 .. G-1, steps G .. G+R-1 wait in stages 0 .. R-1
 #pragma unroll
-        for (int i = 1; i <= S; ++i) { fetch_a(ra[i % S]); fetch_b(rb[i % S]); }
+        for (int i = 0; i < G; ++i) {
+            fetch_a(ra[0]); fetch_b(rb[0]);
+            tile_store<A_KC, BM>(ra[0], As + i * A_FLOATS);
+            tile_store<B_KC, BN>(rb[0], Bs + i * B_FLOATS);
+        }
+#pragma unroll
+        for (int i = 0; i < R; ++i) { fetch_a(ra[i]); fetch_b(rb[i]); }
         __syncthreads();
-        for (int f = 0; f < Fp; f += S) {
+        for (int f = 0; f < Fp; f += U) {
 #pragma unroll
-            for (int st = 0; st < S; ++st) {
-                const int nx = (st + 1) % S;
-                tile_mma<A_KC, B_KC, BM, BN>(As + st * A_FLOATS, Bs + st * B_FLOATS, acc, wm, wn, [&](int chunk) {
-                    if (chunk == 0) tile_store<A_KC, BM>(ra[nx], As + nx * A_FLOATS);
-                    if (chunk == 1) tile_store<B_KC, BN>(rb[nx], Bs + nx * B_FLOATS);
-                    if (chunk == 2) fetch_a(ra[nx]);
-                    if (chunk == 3) fetch_b(rb[nx]);
+            for (int u = 0; u < U; ++u) {
+                const int cur = u % C, nx = (u + G) % C, rs = u % R;
+                // the stores and loads are issued between the MFMA groups of the current step
+                tile_mma<A_KC, B_KC, BM, BN>(As + cur * A_FLOATS, Bs + cur * B_FLOATS, acc, wm, wn, [&](int chunk) {
+                    if (chunk == 0) tile_store<A_KC, BM>(ra[rs], As + nx * A_FLOATS);
+                    if (chunk == 1) tile_store<B_KC, BN>(rb[rs], Bs + nx * B_FLOATS);
+                    if (chunk == 2) fetch_a(ra[rs]);
+                    if (chunk == 3) fetch_b(rb[rs]);
                 });
-                __syncthreads();
+                if ((u + 1) % G == 0) __syncthreads();
             }
         }
     }
-    // Every LDS copy is free here: the last barrier followed the last reads. Leftover i goes through copy i % S;
-    // by the time copy i % S is written again (leftover i + S) S >= 2 barriers have passed since it was read.
+    // Every LDS copy is free here: the last barrier followed the last reads. Leftover i goes through copy i % C;
+    // by the time copy i % C is written again (leftover i + C) C >= 2 barriers have passed since it was read.
+    // (Requesting the leftovers before the loop costs registers for its whole length: measured slower.)
     float4 rta[NT][PA], rtb[NT][PB];
 #pragma unroll
     for (int i = 0; i < NT; ++i)
@@ -357,11 +365,34 @@ __device__ __forceinline__ void run_steps(StepSource p0, StepSource p1, int am0,
 #pragma unroll
     for (int i = 0; i < NT; ++i)
         if (i < n_tail) {
-            tile_store<A_KC, BM>(rta[i], As + (i % S) * A_FLOATS);
-            tile_store<B_KC, BN>(rtb[i], Bs + (i % S) * B_FLOATS);
+            tile_store<A_KC, BM>(rta[i], As + (i % C) * A_FLOATS);
+            tile_store<B_KC, BN>(rtb[i], Bs + (i % C) * B_FLOATS);
             __syncthreads();
-            tile_mma<A_KC, B_KC, BM, BN>(As + (i % S) * A_FLOATS, Bs + (i % S) * B_FLOATS, acc, wm, wn);
+            tile_mma<A_KC, B_KC, BM, BN>(As + (i % C) * A_FLOATS, Bs + (i % C) * B_FLOATS, acc, wm, wn);
         }
+}
+
+// Epilogue staging: the block's BM x BN accumulator tile goes to LDS (row pitch BN + 4 floats, over the operand
+// copies, which are no longer read), so that the tile leaves as 16-byte stores along rows, four row segments per
+// wavefront instruction, instead of 4-byte stores of the MFMA register layout.
+template <int BM, int BN> struct OutTile {
+    static constexpr int PITCH = BN + 4, QC = BN / 4, ROWS_PER_PASS = 256 / QC, PASSES = BM / ROWS_PER_PASS;
+    static constexpr int FLOATS = BM * PITCH;
+};
+template <int BM, int BN>
+__device__ __forceinline__ void acc_to_lds(float* Cs, const floatx16 (&acc)[AccSets<BM, BN>::N][BM / 64][BN / 64], int wm, int wn) {
+    constexpr int MI = BM / 64, NI = BN / 64, SETS = AccSets<BM, BN>::N;
+    const int lane = (int)(threadIdx.x & 63);
+    __syncthreads();      // every wavefront has finished reading the operand copies
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                Cs[(wm * (BM / 2) + mi * 32 + acc_row(r, lane)) * OutTile<BM, BN>::PITCH + wn * (BN / 2) + ni * 32 + (lane & 31)] =
+                    acc_get<SETS, MI, NI>(acc, mi, ni, r);
+    __syncthreads();
 }
 
 // Workgroups are handed to the 8 accelerator dies (XCDs, each with its own L2) round-robin by linear
@@ -377,11 +408,15 @@ static inline unsigned xcd_padded(int64_t total) { return (unsigned)(ceil_div(to
 
 // ------------------------------------------------------------------------------------------ NN
 
-template <bool B_KC, int BM, int BN, int S = 2, int OCC = 2>
+template <bool B_KC, int BM, int BN, int GRP = 1, int STG = 2, int OCC = 2>
 __global__ void __launch_bounds__(256, OCC) gemm_nn_kernel(GemmNNArgs g) {
     constexpr int MI = BM / 64, NI = BN / 64;
-    __shared__ __attribute__((aligned(16))) float As[S * TileShape<true, BM>::FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[S * TileShape<B_KC, BN>::FLOATS];
+    constexpr int A_TOTAL = 2 * GRP * TileShape<true, BM>::FLOATS, B_TOTAL = 2 * GRP * TileShape<B_KC, BN>::FLOATS;
+    // the output tile is staged over the operand copies
+    constexpr int SMEM = A_TOTAL + B_TOTAL > OutTile<BM, BN>::FLOATS ? A_TOTAL + B_TOTAL : OutTile<BM, BN>::FLOATS;
+    __shared__ __attribute__((aligned(16))) float smem[SMEM];
+    float* As = smem;
+    float* Bs = smem + A_TOTAL;
     int M = *g.d_M;
     if (M > g.M_cap) M = g.M_cap;
     // the grid covers the row capacity; only the tiles of the actual M rows are dealt out to the XCDs
@@ -405,36 +440,63 @@ __global__ void __launch_bounds__(256, OCC) gemm_nn_kernel(GemmNNArgs g) {
                       g.K[q0] / BK, -1};
         StepSource p1{g.A[q1], g.lda[q1], g.B[q1], g.ldb[q1], g.a_rows[q1], 0, g.K[q1],
                       n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0, n_phases > 1 ? g.K[q1] / BK : 0, -1};
-        run_steps<true, B_KC, BM, BN, S>(p0, p1, m0, M, n0, g.N, As, Bs, acc, wm, wn);
+        run_steps<true, B_KC, BM, BN, GRP, STG>(p0, p1, m0, M, n0, g.N, As, Bs, acc, wm, wn);
     }
-    const int lane = (int)(threadIdx.x & 63);
+    using OT = OutTile<BM, BN>;
+    acc_to_lds<BM, BN>(smem, acc, wm, wn);
     float* C = g.C[prob];
     const int64_t ldc = g.ldc[prob];
     const int32_t* sp = g.row_scale_indptr[prob];
+    const int32_t* c_rows = prob == 0 ? g.c_rows : nullptr;
+    const int32_t* c_keep_rows = prob == 0 ? g.c_keep_rows : nullptr;
+    const int tid = (int)threadIdx.x, cq = tid % OT::QC, tr = tid / OT::QC;
+    const int col = n0 + cq * 4;
+    // 16-byte stores need aligned rows; otherwise (e.g. 41 classes) the four elements go one by one
+    const bool vec = (ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(C) & 15) == 0) &&
+                     (!c_keep_rows || (reinterpret_cast<uintptr_t>(g.c_keep) & 15) == 0) && col + 4 <= g.N;
+    // the per-row indices and scales of this thread's rows are requested before the first store waits for one of them
+    int32_t crow[OT::PASSES], krow[OT::PASSES];
+    float scale[OT::PASSES];
+    float bias_v[4];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+    for (int i = 0; i < 4; ++i) bias_v[i] = g.bias ? g.bias[min(col + i, g.N - 1)] : 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * (BM / 2) + mi * 32 + acc_row(r, lane);
-            if (row >= M) continue;
-            float scale = 1.f;
-            if (sp) { int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale = len > 0 ? 1.f / (float)len : 0.f; }
-            const int64_t crow = (g.c_rows && prob == 0) ? (int64_t)g.c_rows[row] : (int64_t)row;
-            const int64_t krow = (g.c_keep_rows && prob == 0) ? (int64_t)g.c_keep_rows[row] : -1;
+    for (int j = 0; j < OT::PASSES; ++j) {
+        const int row = min(m0 + tr + OT::ROWS_PER_PASS * j, M - 1);
+        crow[j] = c_rows ? c_rows[row] : row;
+        krow[j] = c_keep_rows ? c_keep_rows[row] : -1;
+        scale[j] = 1.f;
+        if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale[j] = len > 0 ? 1.f / (float)len : 0.f; }
+    }
+    // One explicit wait for every load above (vmcnt 0; the other counters left alone): the stores below sit in
+    // divergent branches, and a wait placed after them would have to drain the stores as well, row after row.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const int col = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
-                if (col >= g.N) continue;
-                float v = acc_get<SETS, MI, NI>(acc, mi, ni, r);
-                if (g.bias) v += g.bias[col];
-                if (g.relu) v = v > 0.f ? v : 0.f;
-                C[crow * ldc + col] = v * scale;
-                if (krow >= 0) {
-                    g.c_keep[krow * ldc + col] = v * scale;
-                    if (col == 0) g.c_keep_stamp[krow] = g.stamp;
-                }
-            }
+    for (int j = 0; j < OT::PASSES; ++j) {
+        const int lr = tr + OT::ROWS_PER_PASS * j, row = m0 + lr;
+        if (row >= M || col >= g.N) continue;
+        const float4 t = *reinterpret_cast<const float4*>(&smem[lr * OT::PITCH + cq * 4]);
+        float v[4] = {t.x + bias_v[0], t.y + bias_v[1], t.z + bias_v[2], t.w + bias_v[3]};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (g.relu) v[i] = v[i] > 0.f ? v[i] : 0.f;
+            v[i] *= scale[j];
         }
+        float* dst = C + (int64_t)crow[j] * ldc + col;
+        float* keep = krow[j] >= 0 ? g.c_keep + (int64_t)krow[j] * ldc + col : nullptr;
+        if (vec) {
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            if (keep) *reinterpret_cast<float4*>(keep) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (col + i < g.N) {
+                    dst[i] = v[i];
+                    if (keep) keep[i] = v[i];
+                }
+        }
+        if (keep && col == 0) g.c_keep_stamp[krow[j]] = g.stamp;
+    }
 }
 
 // Small products (few output tiles, e.g. the classifier layer over the seeds and its input gradient): a block owns a 32x32 output
@@ -523,23 +585,34 @@ __global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
     float* C = g.C[prob];
     const int64_t ldc = g.ldc[prob];
     const int32_t* sp = g.row_scale_indptr[prob];
+    const int32_t* c_rows = prob == 0 ? g.c_rows : nullptr;
+    const int32_t* c_keep_rows = prob == 0 ? g.c_keep_rows : nullptr;
+    int32_t crow[4], krow[4];
+    float scale[4], bias_v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {       // indices and scales of this thread's four elements, requested together
+        const int e = (int)threadIdx.x + 256 * i;
+        const int r = e >> 6, ln = e & 63;
+        const int row = min(m0 + acc_row(r, ln), M - 1), col = min(n0 + (ln & 31), g.N - 1);
+        crow[i] = c_rows ? c_rows[row] : row;
+        krow[i] = c_keep_rows ? c_keep_rows[row] : -1;
+        bias_v[i] = g.bias ? g.bias[col] : 0.f;
+        scale[i] = 1.f;
+        if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale[i] = len > 0 ? 1.f / (float)len : 0.f; }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt 0: see gemm_nn_kernel
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int e = (int)threadIdx.x + 256 * i;
         const int r = e >> 6, ln = e & 63;
         const int row = m0 + acc_row(r, ln), col = n0 + (ln & 31);
         if (row >= M || col >= g.N) continue;
-        float v = ((red[0][r][ln] + red[1][r][ln]) + red[2][r][ln]) + red[3][r][ln];
-        if (g.bias) v += g.bias[col];
+        float v = ((red[0][r][ln] + red[1][r][ln]) + red[2][r][ln]) + red[3][r][ln] + bias_v[i];
         if (g.relu) v = v > 0.f ? v : 0.f;
-        float scale = 1.f;
-        if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale = len > 0 ? 1.f / (float)len : 0.f; }
-        const int64_t crow = (g.c_rows && prob == 0) ? (int64_t)g.c_rows[row] : (int64_t)row;
-        C[crow * ldc + col] = v * scale;
-        const int64_t krow = (g.c_keep_rows && prob == 0) ? (int64_t)g.c_keep_rows[row] : -1;
-        if (krow >= 0) {
-            g.c_keep[krow * ldc + col] = v * scale;
-            if (col == 0) g.c_keep_stamp[krow] = g.stamp;
+        C[(int64_t)crow[i] * ldc + col] = v * scale[i];
+        if (krow[i] >= 0) {
+            g.c_keep[(int64_t)krow[i] * ldc + col] = v * scale[i];
+            if (col == 0) g.c_keep_stamp[krow[i]] = g.stamp;
         }
     }
 }
@@ -570,16 +643,16 @@ static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st, hipEv
     if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), st, ev0, ev1, a);
     else {
-        // NO_GEMM_STAGES=<2|3|4> picks the pipeline depth of the 64x64 kernel (tuning aid)
+        // NO_GEMM_GROUP=<1|2>: steps per barrier; NO_GEMM_STAGES=<2|4>: register stages (4 with groups of 2 only);
+        // NO_GEMM_OCC=<2|3>: blocks per compute unit the register budget allows (tuning aids)
+        static const char* env_g = getenv("NO_GEMM_GROUP");
         static const char* env_st = getenv("NO_GEMM_STAGES");
-        const int stages = env_st ? atoi(env_st) : 3;
         static const char* env_occ = getenv("NO_GEMM_OCC");
-        const int occ = env_occ ? atoi(env_occ) : 3;
-        if (stages == 2 && occ == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else if (stages == 2 && occ == 3) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
-        else if (stages == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 4>), grid, dim3(256), st, ev0, ev1, a);
-        else if (occ == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 3, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 3, 3>), grid, dim3(256), st, ev0, ev1, a);
+        const int group = env_g ? atoi(env_g) : 1, stages = env_st ? atoi(env_st) : 2, occ = env_occ ? atoi(env_occ) : 3;
+        if (group == 2 && stages == 4) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 4, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else if (group == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else if (occ == 3) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
+        else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 1, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
     }
 }
 
@@ -603,11 +676,15 @@ int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent
 
 // ------------------------------------------------------------------------------------------ TN
 
-template <int BM, int BN, int S = 2, int OCC = 2>
+template <int BM, int BN, int GRP = 1, int STG = 2, int OCC = 2>
 __global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(GemmTNArgs g) {
     constexpr int MI = BM / 64, NI = BN / 64;
-    __shared__ __attribute__((aligned(16))) float As[S * TileShape<false, BM>::FLOATS];
-    __shared__ __attribute__((aligned(16))) float Bs[S * TileShape<false, BN>::FLOATS];
+    constexpr int A_TOTAL = 2 * GRP * TileShape<false, BM>::FLOATS, B_TOTAL = 2 * GRP * TileShape<false, BN>::FLOATS;
+    // the output tile is staged over the operand copies
+    constexpr int SMEM = A_TOTAL + B_TOTAL > OutTile<BM, BN>::FLOATS ? A_TOTAL + B_TOTAL : OutTile<BM, BN>::FLOATS;
+    __shared__ __attribute__((aligned(16))) float smem[SMEM];
+    float* As = smem;
+    float* Bs = smem + A_TOTAL;
     int R = *g.d_R;
     if (R > g.R_cap) R = g.R_cap;
     // plain 3-D grid: dealing the slices out per XCD measured slower here (the partial tiles are written
@@ -630,23 +707,29 @@ __global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(GemmTNArgs g) {
         StepSource p0{A, lda, g.G, g.ldg, nullptr, r0, r1, (r1 - r0 + BK - 1) / BK, (r1 - r0) / BK, ones_col};
         StepSource p1 = p0;
         p1.n_steps = p1.n_fast = 0;
-        run_steps<false, false, BM, BN, S>(p0, p1, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
+        run_steps<false, false, BM, BN, GRP, STG>(p0, p1, m0, g.Kp, n0, g.N, As, Bs, acc, wm, wn);
     }
-    const int lane = (int)(threadIdx.x & 63);
+    using OT = OutTile<BM, BN>;
+    acc_to_lds<BM, BN>(smem, acc, wm, wn);
     const int rows_out = g.Kp + 1;
     float* P = g.P + ((int64_t)prob * g.splits + split) * (int64_t)rows_out * g.N;
+    const int tid = (int)threadIdx.x, cq = tid % OT::QC, tr = tid / OT::QC;
+    const int col = n0 + cq * 4;
+    const bool vec = (g.N % 4 == 0) && ((reinterpret_cast<uintptr_t>(P) & 15) == 0) && col + 4 <= g.N;
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+    for (int j = 0; j < OT::PASSES; ++j) {
+        const int lr = tr + OT::ROWS_PER_PASS * j, row = m0 + lr;
+        if (row >= rows_out || col >= g.N) continue;
+        const float4 t = *reinterpret_cast<const float4*>(&smem[lr * OT::PITCH + cq * 4]);
+        float* dst = P + (int64_t)row * g.N + col;
+        if (vec) *reinterpret_cast<float4*>(dst) = t;
+        else {
+            const float v[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * (BM / 2) + mi * 32 + acc_row(r, lane);
-            if (row >= rows_out) continue;
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const int col = n0 + wn * (BN / 2) + ni * 32 + (lane & 31);
-                if (col < g.N) P[(int64_t)row * g.N + col] = acc_get<SETS, MI, NI>(acc, mi, ni, r);
-            }
+            for (int i = 0; i < 4; ++i)
+                if (col + i < g.N) dst[i] = v[i];
         }
+    }
 }
 
 int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
@@ -665,15 +748,14 @@ int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0, hi
     else if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 64>), grid, dim3(256), st, ev0, ev1, a);
     else {
-        static const char* env_st = getenv("NO_TN_STAGES");        // tuning aid: pipeline depth 2, 3 or 4
-        const int stages = env_st ? atoi(env_st) : 3;
+        static const char* env_g = getenv("NO_TN_GROUP");          // tuning aids, as for the forward product
+        static const char* env_st = getenv("NO_TN_STAGES");
         static const char* env_occ = getenv("NO_TN_OCC");
-        const int occ = env_occ ? atoi(env_occ) : 3;
-        if (stages == 2 && occ == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else if (stages == 2 && occ == 3) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
-        else if (stages == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 4>), grid, dim3(256), st, ev0, ev1, a);
-        else if (occ == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 3, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 3, 3>), grid, dim3(256), st, ev0, ev1, a);
+        const int group = env_g ? atoi(env_g) : 1, stages = env_st ? atoi(env_st) : 2, occ = env_occ ? atoi(env_occ) : 3;
+        if (group == 2 && stages == 4) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 4, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else if (group == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
+        else if (occ == 3) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
+        else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
     }
     return launch_status("gemm_tn");
 }
