@@ -495,7 +495,7 @@ __global__ void __launch_bounds__(256, OCC) gemm_nn_kernel(GemmNNArgs g) {
                     if (keep) keep[i] = v[i];
                 }
         }
-        if (keep && col == 0) g.c_keep_stamp[krow[j]] = g.stamp;
+        if (keep && col == 0 && g.c_keep_stamp) g.c_keep_stamp[krow[j]] = g.stamp;
     }
 }
 
@@ -612,7 +612,7 @@ __global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
         C[(int64_t)crow[i] * ldc + col] = v * scale[i];
         if (krow[i] >= 0) {
             g.c_keep[(int64_t)krow[i] * ldc + col] = v * scale[i];
-            if (col == 0) g.c_keep_stamp[krow[i]] = g.stamp;
+            if (col == 0 && g.c_keep_stamp) g.c_keep_stamp[krow[i]] = g.stamp;
         }
     }
 }

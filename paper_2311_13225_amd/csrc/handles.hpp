@@ -46,6 +46,8 @@ struct no_blocks_s {
     // bottom hop with a cache
     no::DevBuf<int32_t> compute_list, compute_pos, hit_pos, hit_slot, probe_slot;
     no::DevBuf<int32_t> refresh_slot;        // [n_compute]: cache slot a computed row refreshes (its vertex is hot), else -1
+    no::DevBuf<int32_t> refresh_old;         // [n_compute]: the version that slot held before the split stamped it
+    no_cache_s* stamped_cache = nullptr;     // the cache whose versions the last split stamped (NULL: none)
     no::DevBuf<int32_t> compute_inv;         // [|V^1|]: index in the compute list of position i of V^1, -1 if served from the cache
     bool last_used_cache = false;
     // The transposes and the final wipe of the id map do not feed the forward pass: they run on a side
@@ -67,7 +69,7 @@ struct no_blocks_s {
         ws_side.release();
         for (auto& h : hop) h.release();
         counts.release(); seeds.release(); map.release(); tmp_a.release(); ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();
-        probe_slot.release(); compute_inv.release(); refresh_slot.release();
+        probe_slot.release(); compute_inv.release(); refresh_slot.release(); refresh_old.release();
     }
 };
 
@@ -123,8 +125,11 @@ struct SideGather { const void* table = nullptr; int32_t row_bytes = 0; void* ou
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key,
                            uint32_t domain, int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b,
                            hipStream_t st, bool join = true, const SideGather* gather = nullptr,
-                           bool inline_side = false);
+                           bool inline_side = false, bool stamp_refresh = false);
 int32_t blocks_join(no_blocks_s* b, hipStream_t st);
+// stamp_refresh: the split writes `step` into the version of every cache slot the batch will recompute (training
+// calls; the row follows with the layer-1 product). blocks_unstamp takes the stamps back for a batch that is dropped.
+int32_t blocks_unstamp(no_blocks_s* b, hipStream_t st);
 // The pending bulk refresh becomes the cache contents once `st` has waited for it (no_refresh_hot_commit).
 int32_t refresh_commit_impl(no_cache_s* c, hipStream_t st);
 int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fanouts, int32_t n_layers,

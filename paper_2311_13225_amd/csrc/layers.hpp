@@ -83,7 +83,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int agg_stage = -1,
                      int gemm_stage = -1, const void* agg_table = nullptr, hipEvent_t wait_before_gemm = nullptr,
-                     int32_t arch = NO_ARCH_SAGE_MEAN, const Layer1Reuse* reuse = nullptr);
+                     int32_t arch = NO_ARCH_SAGE_MEAN, const Layer1Reuse* reuse = nullptr, bool aggregate_done = false);
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,

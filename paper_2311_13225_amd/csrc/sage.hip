@@ -316,14 +316,17 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
-                     const void* agg_table, hipEvent_t wait_before_gemm, int32_t arch, const Layer1Reuse* reuse) {
+                     const void* agg_table, hipEvent_t wait_before_gemm, int32_t arch, const Layer1Reuse* reuse,
+                     bool aggregate_done) {
+    // aggregate_done: `mean` (and the reused rows of H^1) were already written by an earlier launch of the same
+    // aggregation (a batch prepared ahead); only the product runs
     // reuse: the output rows are scattered into H^1, recomputed hot rows also refresh the cache, and the reused
     // rows are copied in from the cache by extra blocks of the aggregation launch (they do not depend on this layer)
     const RowCopyJob* hits = (reuse && reuse->hits.dst) ? &reuse->hits : nullptr;
     auto scatter = [&](GemmNNArgs& a) {
         if (!reuse) return;
         a.c_rows = reuse->compute_pos;
-        a.c_keep = reuse->emb; a.c_keep_rows = reuse->refresh_slot; a.c_keep_stamp = reuse->version; a.stamp = reuse->step;
+        a.c_keep = reuse->emb; a.c_keep_rows = reuse->refresh_slot; a.c_keep_stamp = reuse->version; a.stamp = reuse->step;      // version == NULL: stamped by the split already
     };
     if (arch == NO_ARCH_GCN) {
         // Eq. 1 over N_in(v) U {v} (the destination's own row joins the average), Eq. 2 with one matrix
@@ -351,9 +354,10 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     static const char* no_direct = getenv("NO_SELF_FROM_COPY");      // tuning aid: self product reads the dense copy
     const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global && !no_direct;
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (prof && agg_stage >= 0) prof->kernel_pair(agg_stage, &e0, &e1);
-    NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst, blk.n_dst_cap,
-                            mean, st, false, nullptr, hits, e0, e1));
+    if (prof && agg_stage >= 0 && !aggregate_done) prof->kernel_pair(agg_stage, &e0, &e1);
+    if (!aggregate_done)
+        NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
+                                blk.n_dst_cap, mean, st, false, nullptr, hits, e0, e1));
     if (wait_before_gemm && !direct_self)
         NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
     const float* x_dst = direct_self ? (const float*)agg_table : (const float*)x_src;

@@ -329,7 +329,11 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
                                                                 const int64_t* __restrict__ tile_sums, int32_t* map,
                                                                 int32_t* compute_list, int32_t* compute_pos, int32_t* compute_inv,
                                                                 int32_t* refresh_slot, int32_t* hit_pos,
-                                                                int32_t* hit_slot, int32_t* extra /* n_compute, n_hit, -, -, n_refresh */) {
+                                                                int32_t* hit_slot, int32_t* extra /* n_compute, n_hit, -, -, n_refresh */,
+                                                                int32_t* version, int32_t stamp, int32_t* refresh_old) {
+    // version != NULL: the slot of a hot vertex that will be recomputed is stamped with the step right here (the row
+    // itself arrives with the step's layer-1 product), so that the split of the next batch depends on this split only
+    // and not on that product; the version it replaces is kept, in case the batch is never trained on.
     __shared__ int64_t smem[ETHREADS / 64 + 1];
     const int64_t n = *d_n_v1;
     const int64_t n_tiles = (n + ETILE - 1) / ETILE;
@@ -373,7 +377,12 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
             if (c[t]) {
                 compute_pos[run] = (int32_t)i;
                 compute_inv[i] = (int32_t)run;
-                refresh_slot[run] = slot[t] <= -2 ? -2 - slot[t] : -1;
+                const int32_t rslot = slot[t] <= -2 ? -2 - slot[t] : -1;
+                refresh_slot[run] = rslot;
+                if (version && rslot >= 0) {
+                    refresh_old[run] = version[rslot];
+                    version[rslot] = stamp;
+                }
                 compute_list[run] = v;
                 map[v] = (int32_t)run;
             } else {
@@ -389,6 +398,16 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
 }
 
 __global__ void set_counts_kernel(int32_t* p, int32_t a, int32_t b, int32_t c) { p[0] = a; p[1] = b; p[4] = c; }
+
+// Takes back the stamps of a split whose batch is not trained on.
+__global__ void unstamp_kernel(const int32_t* __restrict__ refresh_slot, const int32_t* __restrict__ refresh_old,
+                               const int32_t* d_n_compute, int32_t n_cap, int32_t* version) {
+    const int32_t n = min(*d_n_compute, n_cap);
+    for (int32_t i = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x); i < n; i += (int32_t)(gridDim.x * blockDim.x)) {
+        const int32_t slot = refresh_slot[i];
+        if (slot >= 0) version[slot] = refresh_old[i];
+    }
+}
 
 // ---------------------------------------------------------------------------- host side
 
@@ -500,8 +519,9 @@ int32_t blocks_join(no_blocks_s* b, hipStream_t st) {
 
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key, uint32_t domain,
                            int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st, bool join,
-                           const SideGather* gather, bool inline_side) {
+                           const SideGather* gather, bool inline_side, bool stamp_refresh) {
     NO_CHECK(blocks_join(b, st));      // a previous call that was never joined
+    b->stamped_cache = nullptr;
     const int32_t L = b->n_layers;
     int32_t* extra = b->counts.p + 4 * L;     // n_compute, n_hit, -, -, n_refresh
     const uint32_t key0 = (uint32_t)stream_key, key1 = (uint32_t)(stream_key >> 32);
@@ -526,7 +546,9 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
             indices_done[h - 1] = true;
             hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, d_dst,
                                (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
-                               b->hit_slot.p, extra);
+                               b->hit_slot.p, extra, stamp_refresh ? cache->version.p : nullptr, (int32_t)step,
+                               b->refresh_old.p);
+            b->stamped_cache = stamp_refresh ? cache : nullptr;
             d_dst = b->compute_list.p;
             d_n = extra + 0;
         }
@@ -548,6 +570,17 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
     NO_CHECK(launch_status("sample_blocks"));
     if (join) NO_CHECK(blocks_join(b, st));
     return NO_OK;
+}
+
+int32_t blocks_unstamp(no_blocks_s* b, hipStream_t st) {
+    if (!b->stamped_cache) return NO_OK;
+    const int32_t L = b->n_layers;
+    const int32_t cap = b->hop[L - 1].n_dst_cap;
+    hipLaunchKernelGGL(unstamp_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(cap, 256), 1024)), dim3(256), 0, st,
+                       (const int32_t*)b->refresh_slot.p, (const int32_t*)b->refresh_old.p, (const int32_t*)(b->counts.p + 4 * L), cap,
+                       b->stamped_cache->version.p);
+    b->stamped_cache = nullptr;
+    return launch_status("blocks_unstamp");
 }
 
 int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fanouts, int32_t n_layers,
@@ -610,6 +643,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
         NO_CHECK(b->compute_pos.alloc(v1_cap));
         NO_CHECK(b->compute_inv.alloc(v1_cap));
         NO_CHECK(b->refresh_slot.alloc(v1_cap));
+        NO_CHECK(b->refresh_old.alloc(v1_cap));
         NO_CHECK(b->hit_pos.alloc(v1_cap));
         NO_CHECK(b->hit_slot.alloc(v1_cap));
         NO_CHECK(b->probe_slot.alloc(v1_cap));

@@ -33,9 +33,12 @@ struct no_model_s {
     // own while the current batch trains; created by the first call that asks for it
     no_blocks_s* blocks_alt = nullptr;
     no::DevBuf<char> x0_alt;
+    no::DevBuf<float> mean_alt;          // layer-1 aggregate of the batch prepared ahead
+    no::DevBuf<float> h0_alt;            // H^1 of that batch (its reused rows arrive with the aggregate)
     hipStream_t sample_stream = nullptr;
-    hipEvent_t ev_can_sample = nullptr, ev_sampled = nullptr;
+    hipEvent_t ev_can_sample = nullptr, ev_sampled = nullptr, ev_l1_done = nullptr;
     bool ahead_valid = false;
+    bool ahead_aggregated = false;       // mean_alt (and the reused rows of H^1) were written for the batch prepared ahead
     int64_t ahead_step = -1;
     uint64_t ahead_seed = 0;
     const int32_t* ahead_seeds = nullptr;
@@ -47,6 +50,9 @@ struct no_model_s {
         if (sample_stream) { (void)hipStreamSynchronize(sample_stream); (void)hipStreamDestroy(sample_stream); sample_stream = nullptr; }
         if (ev_can_sample) { (void)hipEventDestroy(ev_can_sample); ev_can_sample = nullptr; }
         if (ev_sampled) { (void)hipEventDestroy(ev_sampled); ev_sampled = nullptr; }
+        if (ev_l1_done) { (void)hipEventDestroy(ev_l1_done); ev_l1_done = nullptr; }
+        mean_alt.release();
+        h0_alt.release();
         if (blocks_alt) { blocks_alt->release(); delete blocks_alt; blocks_alt = nullptr; }
         x0_alt.release();
         if (blocks) { blocks->release(); delete blocks; blocks = nullptr; }
@@ -207,9 +213,12 @@ static int32_t ensure_lookahead(no_model_s* m, no_graph_s* g) {
     if (m->blocks_alt) return NO_OK;
     NO_CHECK(blocks_create_impl(g, m->n_seeds_cap, m->fanouts, m->n_layers, true, &m->blocks_alt));
     NO_CHECK(m->x0_alt.alloc(m->x0.n));
+    NO_CHECK(m->mean_alt.alloc(m->mean[0].n));
+    NO_CHECK(m->h0_alt.alloc(m->h[0].n));
     NO_HIP_CHECK(hipStreamCreateWithFlags(&m->sample_stream, hipStreamNonBlocking));
     NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_can_sample, hipEventDisableTiming));
     NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_sampled, hipEventDisableTiming));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_l1_done, hipEventDisableTiming));
     return NO_OK;
 }
 
@@ -240,15 +249,24 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     // a batch sampled ahead by the previous call is used if it is exactly this one; anything else is dropped
     const bool presampled = m->ahead_valid && m->ahead_step == step && m->ahead_seed == seed && m->ahead_seeds == d_seeds &&
                             m->ahead_n == n_seeds && m->ahead_cache == cache;
+    bool aggregated = false;
     if (m->ahead_valid) {
+        // (ev_sampled is recorded after everything the sampling stream did for that batch, the aggregation included)
         NO_HIP_CHECK(hipStreamWaitEvent(st, m->ev_sampled, 0));
         if (presampled) {
             std::swap(m->blocks, m->blocks_alt);
             std::swap(m->x0.p, m->x0_alt.p);
+            if (m->ahead_aggregated) {
+                std::swap(m->mean[0].p, m->mean_alt.p);
+                std::swap(m->h[0].p, m->h0_alt.p);
+                aggregated = true;
+            }
         } else {
             NO_CHECK(blocks_join(m->blocks_alt, st));
+            NO_CHECK(blocks_unstamp(m->blocks_alt, st));      // the batch prepared ahead is not the one asked for
         }
         m->ahead_valid = false;
+        m->ahead_aggregated = false;
     }
     no_blocks_s* B = m->blocks;
     no_step_stats* stats = d_stats ? d_stats : m->stats.p;
@@ -271,13 +289,63 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     sg.needed_by_forward = m->feat_dtype != NO_F32 || no_direct;   // fp32: the forward product reads the table rows itself
     prof.begin(NO_STAGE_SAMPLE);
     if (!presampled)
-        NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg));
+        NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg, false, true));
     prof.end();
     const bool used_cache = B->last_used_cache;
     m->last_used_cache = used_cache;
     const int32_t* extra = B->counts.p + 4 * L;
     const HopBuffers& bottom = B->hop[L - 1];
     (void)bottom;
+
+    // The next batch is prepared on the sampling stream in two parts. Part one: sampling and the dense copy of its
+    // destination rows. Its split into reused and computed rows reads the cache's versions only, and those are
+    // stamped by the splits themselves (this step's split stamped the slots this step recomputes), so part one
+    // depends on no kernel of this step and starts with it. Only a bulk refresh due at the boundary between the two
+    // steps holds it back: that is committed after this step's layer 1, and the next batch is split against the new
+    // rows. Part two, after this step's layer 1: the batch's layer-1 aggregation (mean aggregator, two or more
+    // layers), which depends on no weight, into a second aggregate buffer; with it the batch's reused rows are copied
+    // from the cache (they may be rows this step's layer 1 has just refreshed) into a second H^1, so this step's
+    // buffers stay as the step leaves them. Both run beside this step's matrix-bound kernels.
+    auto launch_sampling_ahead = [&]() -> int32_t {
+        if (commit_refresh_before_next && cache) NO_CHECK(refresh_commit_impl(cache, st));
+        NO_HIP_CHECK(hipEventRecord(m->ev_can_sample, st));
+        NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_can_sample, 0));
+        SideGather sg2 = sg;
+        sg2.out = m->x0_alt.p;
+        NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
+                                    m->blocks_alt, m->sample_stream, false, &sg2, true, true));
+        NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
+        m->ahead_valid = true;
+        m->ahead_step = step + 1;
+        m->ahead_seed = seed;
+        m->ahead_seeds = d_next_seeds;
+        m->ahead_n = n_next_seeds;
+        m->ahead_cache = cache;
+        return NO_OK;
+    };
+    auto launch_aggregate_ahead = [&]() -> int32_t {
+        if (L < 2 || m->arch != NO_ARCH_SAGE_MEAN) return NO_OK;
+        no_blocks_s* NB = m->blocks_alt;
+        no_block_view nv;
+        fill_block_view(NB, L - 1, &nv);
+        RowCopyJob next_hits{};
+        const bool next_cache = NB->last_used_cache;
+        if (next_cache) {
+            NO_HIP_CHECK(hipEventRecord(m->ev_l1_done, st));
+            NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_l1_done, 0));
+            next_hits.src = cache->emb.p; next_hits.src_rows = NB->hit_slot.p; next_hits.dst_rows = NB->hit_pos.p;
+            next_hits.d_n = NB->counts.p + 4 * L + 1; next_hits.n_cap = nv.n_dst_cap; next_hits.dst = m->h0_alt.p;
+            next_hits.dim = m->dims[1];
+        }
+        NO_CHECK(mean_aggregate(d_features, m->feat_dtype, m->dims[0], nv.d_indptr, nv.d_nbr_global, nv.d_n_dst, nv.n_dst_cap,
+                                m->mean_alt.p, m->sample_stream, false, nullptr, next_cache ? &next_hits : nullptr));
+        NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
+        m->ahead_aggregated = true;
+        return NO_OK;
+    };
+    static const char* late = getenv("NO_LOOKAHEAD_LATE");      // tuning aid: part one always after layer 1
+    const bool lookahead_early = d_next_seeds && !late && !(commit_refresh_before_next && cache);
+    if (lookahead_early) NO_CHECK(launch_sampling_ahead());
 
     // forward
     no_block_view view[NO_MAX_LAYERS];
@@ -295,7 +363,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             // weights, version = step); the reused rows are copied from the cache beside the aggregation
             reuse.compute_pos = B->compute_pos.p;
             reuse.refresh_slot = B->refresh_slot.p;
-            reuse.emb = cache->emb.p; reuse.version = cache->version.p; reuse.step = (int32_t)step;
+            reuse.emb = cache->emb.p; reuse.version = nullptr /* stamped by the split */; reuse.step = (int32_t)step;
             reuse.hits.src = cache->emb.p; reuse.hits.src_rows = B->hit_slot.p; reuse.hits.dst_rows = B->hit_pos.p;
             reuse.hits.d_n = extra + 1; reuse.hits.n_cap = blk.n_dst_cap; reuse.hits.dst = m->h[0].p; reuse.hits.dim = d_out;
         }
@@ -313,30 +381,15 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
                                   NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features,
                                   (m->arch == NO_ARCH_GCN || presampled) ? nullptr : B->ev_gather_done, m->arch,
-                                  (l == 1 && used_cache) ? &reuse : nullptr));
+                                  (l == 1 && used_cache) ? &reuse : nullptr, aggregated));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
                               l == 1 ? &prof : nullptr, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, nullptr, nullptr, m->arch));
         if (l == L && L >= 2) prof.end();
         if (l == 1 && d_next_seeds) {
-            // This step has made its last change to the cache (the rows refreshed on a miss): the next batch can be
-            // sampled now, on the sampling stream, next to the rest of this step. A bulk refresh due at the boundary
-            // between the two steps is committed first, so the next batch is split against the new rows.
-            if (commit_refresh_before_next && cache) NO_CHECK(refresh_commit_impl(cache, st));
-            NO_HIP_CHECK(hipEventRecord(m->ev_can_sample, st));
-            NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_can_sample, 0));
-            SideGather sg2 = sg;
-            sg2.out = m->x0_alt.p;
-            NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
-                                        m->blocks_alt, m->sample_stream, false, &sg2, true));
-            NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
-            m->ahead_valid = true;
-            m->ahead_step = step + 1;
-            m->ahead_seed = seed;
-            m->ahead_seeds = d_next_seeds;
-            m->ahead_n = n_next_seeds;
-            m->ahead_cache = cache;
+            if (!lookahead_early) NO_CHECK(launch_sampling_ahead());
+            NO_CHECK(launch_aggregate_ahead());
         }
     }
 
