@@ -306,6 +306,11 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     // layers), which depends on no weight, into a second aggregate buffer; with it the batch's reused rows are copied
     // from the cache (they may be rows this step's layer 1 has just refreshed) into a second H^1, so this step's
     // buffers stay as the step leaves them. Both run beside this step's matrix-bound kernels.
+    // (The transposes, the local indices of the upper hops and the dense copy go to that batch's own side stream: they
+    // are needed by its backward pass and upper layers only, and would otherwise sit between its sampling and its
+    // aggregation on the sampling stream, which is the longer of the two chains. NO_LOOKAHEAD_INLINE=1 keeps them on
+    // the sampling stream: tuning aid.)
+    static const char* ahead_inline = getenv("NO_LOOKAHEAD_INLINE");
     auto launch_sampling_ahead = [&]() -> int32_t {
         if (commit_refresh_before_next && cache) NO_CHECK(refresh_commit_impl(cache, st));
         NO_HIP_CHECK(hipEventRecord(m->ev_can_sample, st));
@@ -313,7 +318,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         SideGather sg2 = sg;
         sg2.out = m->x0_alt.p;
         NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
-                                    m->blocks_alt, m->sample_stream, false, &sg2, true, true));
+                                    m->blocks_alt, m->sample_stream, false, &sg2, ahead_inline != nullptr, true));
         NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
         m->ahead_valid = true;
         m->ahead_step = step + 1;
@@ -380,7 +385,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
                                   NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features,
-                                  (m->arch == NO_ARCH_GCN || presampled) ? nullptr : B->ev_gather_done, m->arch,
+                                  m->arch == NO_ARCH_GCN ? nullptr : B->ev_gather_done, m->arch,
                                   (l == 1 && used_cache) ? &reuse : nullptr, aggregated));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
