@@ -274,19 +274,25 @@ int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const 
                       const int32_t* d_seeds, int32_t n_seeds, no_cache_t cache, int64_t step,
                       uint64_t seed, float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream);
 
-/* no_train_step for batch `step`, plus sampling ahead (Section 4.2, Stage 1: sampling runs ahead of training so
- * that the two do not wait for each other). Results of the step are those of no_train_step. In addition, if
- * d_next_seeds != NULL, batch step + 1 (d_next_seeds[n_next_seeds], same seed) is sampled into a second set of
- * blocks on the model's own sampling stream (default priority) as soon as this step has made its last change to
- * the cache (the layer-1 rows it refreshes on a miss), i.e. next to this step's upper layers and backward pass.
- * The next call uses that sample if it asks for exactly it (step + 1, the same d_next_seeds pointer and count,
- * seed and cache); otherwise the sample is dropped and the batch is sampled again. d_next_seeds must stay valid
- * and unchanged until then. commit_refresh_before_next != 0: a pending bulk refresh (no_refresh_hot_begin) is
- * committed after this step's last use of the cache and before the next batch is sampled; use it on the last
- * step of a super-batch instead of calling no_refresh_hot_commit between the two steps. The first call with
- * d_next_seeds != NULL allocates the second set of blocks (as much memory as no_blocks_create for the same
- * capacities, plus one copy of the destination rows). Errors as no_train_step, and NO_ERR_CAPACITY for
- * n_next_seeds outside [1, capacity]. */
+/* no_train_step for batch `step`, plus preparing the next batch ahead (Section 4.2, Stage 1: sampling runs ahead of
+ * training so that the two do not wait for each other). Results of the step are those of no_train_step. In
+ * addition, if d_next_seeds != NULL, batch step + 1 (d_next_seeds[n_next_seeds], same seed) is prepared on the
+ * model's own sampling stream (default priority) beside this step: it is sampled into a second set of blocks from
+ * the step's start, and after this step's layer 1 its layer-1 aggregation runs into a second buffer (mean
+ * aggregator with two or more layers), together with the copy of its reused rows out of the cache. The next call
+ * uses that batch if it asks for exactly it (step + 1, the same d_next_seeds pointer and count, seed and cache);
+ * otherwise it is dropped and the batch is sampled again. d_next_seeds and d_features must stay valid and unchanged
+ * until then.
+ * Cache versions: the split of a batch into reused and computed vertices writes the batch's step into the version
+ * of every slot the batch will recompute (the row follows when its layer 1 runs), so while a batch is prepared
+ * ahead those entries of no_cache_view already read step + 1; a dropped batch's entries are restored by the call
+ * that drops it. Do not commit a bulk refresh or reset the cache between the two calls.
+ * commit_refresh_before_next != 0: a pending bulk refresh (no_refresh_hot_begin) is committed after this step's
+ * last use of the cache and before the next batch is sampled (which then starts after this step's layer 1); use it
+ * on the last step of a super-batch instead of calling no_refresh_hot_commit between the two steps. The first
+ * call with d_next_seeds != NULL allocates the second set of blocks (as much memory as no_blocks_create for the
+ * same capacities) plus second copies of the destination rows, the layer-1 aggregate and H^1. Errors as
+ * no_train_step, and NO_ERR_CAPACITY for n_next_seeds outside [1, capacity]. */
 int32_t no_train_step_ahead(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
                             const int32_t* d_seeds, int32_t n_seeds, const int32_t* d_next_seeds, int32_t n_next_seeds,
                             int32_t commit_refresh_before_next, no_cache_t cache, int64_t step, uint64_t seed,
