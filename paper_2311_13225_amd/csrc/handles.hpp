@@ -130,6 +130,10 @@ int32_t blocks_join(no_blocks_s* b, hipStream_t st);
 // stamp_refresh: the split writes `step` into the version of every cache slot the batch will recompute (training
 // calls; the row follows with the layer-1 product). blocks_unstamp takes the stamps back for a batch that is dropped.
 int32_t blocks_unstamp(no_blocks_s* b, hipStream_t st);
+// Caches handed out and not yet destroyed: a dropped batch's stamps are only taken back from a cache that still exists.
+void cache_register(no_cache_s* c);
+void cache_unregister(no_cache_s* c);
+bool cache_is_live(no_cache_s* c);
 // The pending bulk refresh becomes the cache contents once `st` has waited for it (no_refresh_hot_commit).
 int32_t refresh_commit_impl(no_cache_s* c, hipStream_t st);
 int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fanouts, int32_t n_layers,

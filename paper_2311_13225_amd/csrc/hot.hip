@@ -1,6 +1,8 @@
 // no_select_hot and the embedding cache (Section 4.1.2): hotness = how often a vertex lands in
 // V^1 (the set whose layer-1 embedding could be reused) while pre-sampling the training batches;
 // the hot set is the top floor(fraction * V) by (count descending, id ascending).
+#include <mutex>
+#include <unordered_set>
 #include "primitives.hpp"
 #include "handles.hpp"
 
@@ -28,6 +30,14 @@ __global__ void hot_slots_kernel(const uint32_t* order, int64_t n_hot, int32_t* 
 }  // namespace no
 
 using namespace no;
+
+namespace no {
+static std::mutex g_cache_mutex;
+static std::unordered_set<no_cache_s*> g_live_caches;
+void cache_register(no_cache_s* c) { std::lock_guard<std::mutex> l(g_cache_mutex); g_live_caches.insert(c); }
+void cache_unregister(no_cache_s* c) { std::lock_guard<std::mutex> l(g_cache_mutex); g_live_caches.erase(c); }
+bool cache_is_live(no_cache_s* c) { std::lock_guard<std::mutex> l(g_cache_mutex); return g_live_caches.count(c) != 0; }
+}  // namespace no
 
 extern "C" int32_t no_select_hot(no_graph_t g, const int32_t* d_train_ids, int64_t n_train, int32_t batch,
                                  const int32_t* h_fanouts, int32_t n_layers, int32_t presample_epochs,
@@ -114,6 +124,7 @@ extern "C" int32_t no_select_hot(no_graph_t g, const int32_t* d_train_ids, int64
     }
     NO_HIP_CHECK(hipStreamSynchronize(st));
     guard.c = nullptr;
+    no::cache_register(c);
     *out = c;
     return NO_OK;
 }
@@ -151,6 +162,7 @@ extern "C" int32_t no_cache_invalidate(no_cache_t c, void* stream) {
 extern "C" int32_t no_cache_destroy(no_cache_t c) {
     clear_error();
     if (!c) return NO_OK;
+    no::cache_unregister(c);
     c->release();
     delete c;
     return NO_OK;

@@ -574,6 +574,10 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
 
 int32_t blocks_unstamp(no_blocks_s* b, hipStream_t st) {
     if (!b->stamped_cache) return NO_OK;
+    if (!cache_is_live(b->stamped_cache)) {      // destroyed since: nothing to restore
+        b->stamped_cache = nullptr;
+        return NO_OK;
+    }
     const int32_t L = b->n_layers;
     const int32_t cap = b->hop[L - 1].n_dst_cap;
     hipLaunchKernelGGL(unstamp_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(cap, 256), 1024)), dim3(256), 0, st,

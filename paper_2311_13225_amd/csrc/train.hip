@@ -47,6 +47,9 @@ struct no_model_s {
     no::StageProfiler prof;
     void release() {
         if (prof.created) { for (auto& e : prof.ev) (void)hipEventDestroy(e); prof.created = false; }
+        // a batch prepared ahead and never trained on: its split's stamps leave the cache with the model
+        if (ahead_valid && blocks_alt && sample_stream) (void)no::blocks_unstamp(blocks_alt, sample_stream);
+        ahead_valid = false;
         if (sample_stream) { (void)hipStreamSynchronize(sample_stream); (void)hipStreamDestroy(sample_stream); sample_stream = nullptr; }
         if (ev_can_sample) { (void)hipEventDestroy(ev_can_sample); ev_can_sample = nullptr; }
         if (ev_sampled) { (void)hipEventDestroy(ev_sampled); ev_sampled = nullptr; }

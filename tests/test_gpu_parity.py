@@ -633,6 +633,9 @@ def test_every_vertex_hot_leaves_an_empty_bottom_hop(ahead):
 
 
 def test_sampling_ahead_dropped_when_not_consumed():
+    """A batch prepared ahead that the next call does not ask for is dropped: the steps, and the cache they leave,
+    equal those of plain stepping. The prepared batch's split had stamped the versions of the slots it would have
+    recomputed; the call that drops it (or the model's destruction) must take those stamps back."""
     b = nb()
     import dataclasses
     w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=2, hot_fraction=0.2)
@@ -641,8 +644,8 @@ def test_sampling_ahead_dropped_when_not_consumed():
     lab = si.labels(w.n_vertices, w.n_classes, w.seed)
     train = si.train_split(w.n_vertices, 0.65, w.seed)
     weights = si.init_weights(w.dims, w.seed)
-    losses = []
-    for mode in ("plain", "mismatch"):
+    losses, caches = [], []
+    for mode in ("plain", "mismatch", "destroyed"):
         model = b.no_model_create(gg, w.dims, w.batch, w.fanouts)
         for l in range(w.n_layers):
             for t, a in zip(b.no_model_params(model, l + 1), weights[l]):
@@ -651,15 +654,40 @@ def test_sampling_ahead_dropped_when_not_consumed():
         tfeat, tlab = dev(feat), dev(lab)
         seeds = [dev(si.batch_seeds(train, w.batch, t)) for t in range(4)]
         out = []
+        stamped_seen = 0
         for t in range(4):
             if mode == "plain":
                 st = b.no_train_step(model, gg, tfeat, tlab, seeds[t], gc, t, w.seed, 0.02)
             else:
                 # announce a batch that never comes (wrong tensor), then ask for the right one
                 st = b.no_train_step_ahead(model, gg, tfeat, tlab, seeds[t], seeds[0], False, gc, t, w.seed, 0.02)
+                torch.cuda.synchronize()
+                stamped_seen += int((b.no_cache_view(gc, w.n_vertices)["version"] == t + 1).sum().item())
             out.append((st.loss, st.n_hit, tuple(st.n_src[:2])))
+        if mode == "mismatch":
+            assert stamped_seen > 0          # the case is exercised: prepared batches did stamp slots
+            # one more plain call drops the last prepared batch
+            st = b.no_train_step(model, gg, tfeat, tlab, seeds[0], gc, 4, w.seed, 0.0)
+        elif mode == "plain":
+            st = b.no_train_step(model, gg, tfeat, tlab, seeds[0], gc, 4, w.seed, 0.0)
+        else:
+            # the model goes away with a prepared batch pending; the cache must read as after four plain steps
+            model.close()
+            model = None
+        torch.cuda.synchronize()
+        view = b.no_cache_view(gc, w.n_vertices)
+        caches.append((view["version"].cpu().numpy().copy(), view["emb"].cpu().numpy().copy()))
         losses.append(out)
-    assert losses[0] == losses[1]
+        if model is not None:
+            model.close()
+        gc.close()
+    assert losses[0] == losses[1] == losses[2]
+    assert np.array_equal(caches[0][0], caches[1][0]) and np.array_equal(caches[0][1], caches[1][1])
+    # "destroyed" stopped one (lr = 0) step earlier: its versions are those of plain stepping before that step, i.e.
+    # no entry carries step 4
+    assert (caches[2][0] <= 3).all()
+    untouched = caches[0][0] <= 3
+    assert np.array_equal(caches[2][0][untouched], caches[0][0][untouched])
 
 
 def test_cache_invalidate_and_set_staleness():
