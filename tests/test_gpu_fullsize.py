@@ -22,6 +22,15 @@ def test_dense_workload_full_size_steps():
     assert hits > 0
 
 
+def test_dense_workload_full_size_steps_prepared_ahead():
+    """The stepping bench.py times: no_train_step_ahead, each batch prepared (sampled, split against the cache,
+    layer-1 aggregate) beside the step before it."""
+    print("dense full size, batches prepared ahead", flush=True)
+    w = si.WORKLOADS["dense"]
+    hits = run_steps(w, 4, use_cache=True, lr=0.01, bits=w.rowptr_bits, presample=1, ahead=True)
+    assert hits > 0
+
+
 def test_dense_workload_csr_and_hot_set_full_size():
     print("dense csr + hot set", flush=True)
     w = si.WORKLOADS["dense"]
