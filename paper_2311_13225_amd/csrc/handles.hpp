@@ -48,6 +48,7 @@ struct no_blocks_s {
     no::DevBuf<int32_t> refresh_slot;        // [n_compute]: cache slot a computed row refreshes (its vertex is hot), else -1
     no::DevBuf<int32_t> refresh_old;         // [n_compute]: the version that slot held before the split stamped it
     no_cache_s* stamped_cache = nullptr;     // the cache whose versions the last split stamped (NULL: none)
+    bool scan_two_pass = false;              // the edge compaction of the next sampling call: two launches instead of one
     no::DevBuf<int32_t> compute_inv;         // [|V^1|]: index in the compute list of position i of V^1, -1 if served from the cache
     bool last_used_cache = false;
     // The transposes and the final wipe of the id map do not feed the forward pass: they run on a side

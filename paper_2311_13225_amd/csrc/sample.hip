@@ -51,7 +51,10 @@ __global__ void __launch_bounds__(256) sample_rows_kernel(const RowT* __restrict
                                                           uint32_t key1, uint32_t c3, int32_t* __restrict__ nbr_pad,
                                                           int32_t* __restrict__ src_global, int32_t* map,
                                                           int32_t insert_dst, int32_t* seeds_copy, int32_t* count_out,
-                                                          int32_t n_vertices, int32_t* bad_id_flag) {
+                                                          int32_t n_vertices, int32_t* bad_id_flag,
+                                                          unsigned long long* scan_status, int32_t n_status) {
+    // the tile status words of the scan that follows this launch start out empty
+    for (int32_t t = (int32_t)(blockIdx.x * 256 + threadIdx.x); t < n_status; t += (int32_t)(gridDim.x * 256)) scan_status[t] = 0ull;
     int32_t n_dst = d_n_dst ? *d_n_dst : n_fixed;
     if (n_dst > n_cap) n_dst = n_cap;
     if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = n_dst;
@@ -194,6 +197,121 @@ __global__ void __launch_bounds__(ETHREADS) edge_assign_kernel(const int32_t* __
     }
     int64_t total;
     int64_t run = block_exclusive_scan<int64_t, ETHREADS>(s, &total, smem) + tile_off;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        const int64_t q = q0 + t;
+        if (q < n_pad) {
+            const int32_t e = (int32_t)(run & 0xffffffffll);
+            const int32_t row = k == 1 ? (int32_t)q : (int32_t)__umul64hi((uint64_t)q, k_magic);   // q / k, exact
+            if (q - (int64_t)row * k == 0) indptr[row] = e;
+            if (f[t] & 1) {
+                nbr[e] = u[t];
+                edge_row[e] = row;
+                if (f[t] >> 32) {
+                    const int32_t local = n_dst + (int32_t)(run >> 32);
+                    src_global[local] = u[t];
+                    map[u[t]] = local;     // only the first occurrence writes; later readers never match n_dst + q
+                }
+            }
+            run += f[t];
+        }
+    }
+}
+
+// One-launch form of the two kernels above (tile sums, then assignment): a single-pass scan. A block publishes its
+// tile's sum in a status word, adds up the words of the tiles before it until it meets one that already holds an
+// inclusive prefix (workgroups are dispatched in index order, so every earlier tile is running or done), publishes its
+// own inclusive prefix and assigns. A word packs both 31-bit counts and a 2-bit state, so it is written and read by one
+// 64-bit access at device scope and needs no fence; the words are emptied by the sampling launch before. The wait on
+// an earlier tile is bounded: on expiry the block reports through `fail_flag` and goes on (wrong output, no hang).
+constexpr unsigned long long SCAN_SUM = 1ull, SCAN_PREFIX = 2ull;
+__device__ __forceinline__ unsigned long long scan_pack(int64_t v, unsigned long long state) {
+    return ((unsigned long long)(v & 0x7fffffffll)) | ((unsigned long long)((v >> 32) & 0x7fffffffll) << 31) | (state << 62);
+}
+__device__ __forceinline__ int64_t scan_unpack(unsigned long long w) {
+    return (int64_t)(w & 0x7fffffffull) | ((int64_t)((w >> 31) & 0x7fffffffull) << 32);
+}
+
+__global__ void __launch_bounds__(ETHREADS) edge_scan_kernel(const int32_t* __restrict__ nbr_pad, int32_t* map,
+                                                             const int32_t* d_n_dst, int32_t k, uint64_t k_magic,
+                                                             unsigned long long* status, int32_t* __restrict__ indptr,
+                                                             int32_t* __restrict__ nbr, int32_t* __restrict__ edge_row,
+                                                             int32_t* __restrict__ src_global,
+                                                             int32_t* counts /* [0]=n_dst (in), [1]=n_src, [2]=nnz */,
+                                                             int32_t* zero_a, int32_t* zero_b, int32_t n_zero, int32_t* fail_flag) {
+    __shared__ int64_t smem[ETHREADS / 64 + 1];
+    __shared__ int64_t prefix_sh;
+    for (int64_t t = (int64_t)blockIdx.x * ETHREADS + threadIdx.x; t < n_zero; t += (int64_t)gridDim.x * ETHREADS) {
+        zero_a[t] = 0;
+        zero_b[t] = 0;
+    }
+    const int32_t n_dst = *d_n_dst;
+    const int64_t n_pad = (int64_t)n_dst * k;
+    if (n_pad == 0) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) { indptr[0] = 0; counts[1] = n_dst; counts[2] = 0; }
+        return;
+    }
+    const int64_t base = (int64_t)blockIdx.x * ETILE;
+    if (base >= n_pad) return;
+    const int64_t q0 = base + (int64_t)threadIdx.x * EITEMS;
+    int64_t f[EITEMS];
+    int32_t u[EITEMS];
+    int64_t s = 0;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        f[t] = 0;
+        u[t] = -1;
+        if (q0 + t < n_pad) f[t] = slot_flags(nbr_pad, map, q0 + t, n_dst, &u[t]);
+        s += f[t];
+    }
+    int64_t total;
+    int64_t run = block_exclusive_scan<int64_t, ETHREADS>(s, &total, smem);
+    if (threadIdx.x < 64) {
+        // wavefront 0 looks back 64 tiles at a time: lane l reads the word of tile (first - l)
+        const int lane = (int)threadIdx.x;
+        int64_t prefix = 0;
+        if (blockIdx.x > 0) {
+            if (lane == 0)
+                __hip_atomic_store(&status[blockIdx.x], scan_pack(total, SCAN_SUM), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int64_t first = (int64_t)blockIdx.x - 1;      // nearest tile not yet added
+            int spins = 0;
+            while (first >= 0) {
+                const int64_t j = first - lane;
+                unsigned long long w = SCAN_PREFIX << 62;                      // lanes past tile 0: an empty prefix
+                if (j >= 0) w = __hip_atomic_load(&status[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned long long state = w >> 62;
+                const unsigned long long is_prefix = __ballot(state == SCAN_PREFIX), is_empty = __ballot(state == 0ull);
+                // usable lanes: those before the first empty word; the walk ends at the first prefix among them
+                const int n_ok = is_empty ? __builtin_ctzll(is_empty) : 64;
+                const int p_at = is_prefix ? __builtin_ctzll(is_prefix) : 64;
+                const int take = p_at < n_ok ? p_at + 1 : n_ok;               // lanes [0, take) are added
+                int64_t v = lane < take ? scan_unpack(w) : 0;
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+                prefix += v;
+                first -= take;
+                if (p_at < n_ok) break;                                       // reached an inclusive prefix
+                if (take == 0) {
+                    if (++spins > (1 << 20)) { if (lane == 0) *fail_flag = 2; break; }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+            }
+        }
+        if (lane == 0) {
+            __hip_atomic_store(&status[blockIdx.x], scan_pack(prefix + total, SCAN_PREFIX), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            prefix_sh = prefix;
+            if (base + ETILE >= n_pad) {      // the last tile holds the totals
+                const int64_t all = prefix + total;
+                const int32_t nnz = (int32_t)(all & 0xffffffffll), n_new = (int32_t)(all >> 32);
+                indptr[n_dst] = nnz;
+                counts[1] = n_dst + n_new;
+                counts[2] = nnz;
+            }
+        }
+    }
+    __syncthreads();
+    run += prefix_sh;
 #pragma unroll
     for (int t = 0; t < EITEMS; ++t) {
         const int64_t q = q0 + t;
@@ -430,20 +548,32 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     hipLaunchKernelGGL((sample_rows_kernel<G, RowT>), dim3((unsigned)ceil_div(H.n_dst_cap, 256 / G)), dim3(256), 0, st,    \
                        rowptr, col, d_dst, d_n_dst_in, n_fixed, H.n_dst_cap, k, key0, key1, c3, H.nbr_pad.p,               \
                        H.src_global.p, b->map.p, insert_dst ? 1 : 0, seeds_copy, cnt, (int32_t)b->n_vertices,               \
-                       b->counts.p + 4 * b->n_layers + 5)
+                       b->counts.p + 4 * b->n_layers + 5, (unsigned long long*)b->ws.p, (int32_t)edge_tiles(H.nnz_cap))
     if (k <= 8) NO_LAUNCH_SAMPLE(8);
     else if (k <= 16) NO_LAUNCH_SAMPLE(16);
     else if (k <= 32) NO_LAUNCH_SAMPLE(32);
     else NO_LAUNCH_SAMPLE(64);
 #undef NO_LAUNCH_SAMPLE
     const unsigned tiles = (unsigned)edge_tiles(H.nnz_cap);
-    hipLaunchKernelGGL(edge_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p,
-                       (const int32_t*)b->map.p, (const int32_t*)cnt, k, tile_sums, H.csc_cnt.p, H.csc_cur.p,
-                       H.has_csc ? H.n_src_cap + 1 : 0);
     const uint64_t k_magic = k > 1 ? (~0ull / (uint64_t)k) + 1ull : 0ull;     // ceil(2^64 / k)
-    hipLaunchKernelGGL(edge_assign_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
-                       (const int32_t*)cnt, k, k_magic, (const int64_t*)tile_sums, H.indptr.p, H.nbr_global.p, H.edge_row.p,
-                       H.src_global.p, cnt);
+    // One launch where the sampling has the chip to itself or nearly so; two where it runs beside another batch's
+    // products (sampling ahead): there the single-pass blocks, which wait on their predecessors while holding a slot,
+    // measured slower than two short launches. NO_SCAN_TWO_PASS=<0|1> forces either form (tuning aid).
+    static const char* env_two_pass = getenv("NO_SCAN_TWO_PASS");
+    const bool two_pass = env_two_pass ? atoi(env_two_pass) != 0 : b->scan_two_pass;
+    if (two_pass) {
+        hipLaunchKernelGGL(edge_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p,
+                           (const int32_t*)b->map.p, (const int32_t*)cnt, k, tile_sums, H.csc_cnt.p, H.csc_cur.p,
+                           H.has_csc ? H.n_src_cap + 1 : 0);
+        hipLaunchKernelGGL(edge_assign_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
+                           (const int32_t*)cnt, k, k_magic, (const int64_t*)tile_sums, H.indptr.p, H.nbr_global.p, H.edge_row.p,
+                           H.src_global.p, cnt);
+    } else {
+        hipLaunchKernelGGL(edge_scan_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
+                           (const int32_t*)cnt, k, k_magic, (unsigned long long*)b->ws.p, H.indptr.p, H.nbr_global.p,
+                           H.edge_row.p, H.src_global.p, cnt, H.csc_cnt.p, H.csc_cur.p, H.has_csc ? H.n_src_cap + 1 : 0,
+                           b->counts.p + 4 * b->n_layers + 5);
+    }
     if (indices_now)
         hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st,
                            (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,

@@ -291,6 +291,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     static const char* no_direct = getenv("NO_SELF_FROM_COPY");
     sg.needed_by_forward = m->feat_dtype != NO_F32 || no_direct;   // fp32: the forward product reads the table rows itself
     prof.begin(NO_STAGE_SAMPLE);
+    if (!presampled) B->scan_two_pass = false;
     if (!presampled)
         NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg, false, true));
     prof.end();
@@ -320,6 +321,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_can_sample, 0));
         SideGather sg2 = sg;
         sg2.out = m->x0_alt.p;
+        m->blocks_alt->scan_two_pass = true;      // this sampling shares the chip with the step's products
         NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
                                     m->blocks_alt, m->sample_stream, false, &sg2, ahead_inline != nullptr, true));
         NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
