@@ -49,6 +49,10 @@ inline int32_t launch_status(const char* what) {
 // Launch with an optional pair of events that take the kernel's own start and end times (HIP's extended launch):
 // a stage that is a single kernel is then timed like a kernel trace times it, without the dispatch latency and the
 // event packets that a record-before / record-after pair on the stream adds.
+// Events that only order work between streams of this device: no timing, and a device-scope release when recorded
+// (the default is a system-scope fence: cache write-back and invalidation, paid by the record and by the kernels after it).
+#define NO_SYNC_EVENT_FLAGS (hipEventDisableTiming | hipEventReleaseToDevice)
+
 #define NO_LAUNCH_TIMED(kernel, grid, block, st, ev0, ev1, ...)                                      \
     do {                                                                                             \
         if (ev0) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev0, ev1, 0, __VA_ARGS__);        \

@@ -643,15 +643,10 @@ static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st, hipEv
     if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), st, ev0, ev1, a);
     else {
-        // NO_GEMM_GROUP=<1|2>: steps per barrier; NO_GEMM_STAGES=<2|4>: register stages (4 with groups of 2 only);
-        // NO_GEMM_OCC=<2|3>: blocks per compute unit the register budget allows (tuning aids)
-        static const char* env_g = getenv("NO_GEMM_GROUP");
-        static const char* env_st = getenv("NO_GEMM_STAGES");
+        // NO_GEMM_OCC=<2|3>: blocks per compute unit the register budget allows (tuning aid)
         static const char* env_occ = getenv("NO_GEMM_OCC");
-        const int group = env_g ? atoi(env_g) : 1, stages = env_st ? atoi(env_st) : 2, occ = env_occ ? atoi(env_occ) : 3;
-        if (group == 2 && stages == 4) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 4, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else if (group == 2) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 2, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else if (occ == 3) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
+        const int occ = env_occ ? atoi(env_occ) : 3;
+        if (occ == 3) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
         else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 1, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
     }
 }
@@ -748,13 +743,9 @@ int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0, hi
     else if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 128>), grid, dim3(256), st, ev0, ev1, a);
     else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 64>), grid, dim3(256), st, ev0, ev1, a);
     else {
-        static const char* env_g = getenv("NO_TN_GROUP");          // tuning aids, as for the forward product
-        static const char* env_st = getenv("NO_TN_STAGES");
-        static const char* env_occ = getenv("NO_TN_OCC");
-        const int group = env_g ? atoi(env_g) : 1, stages = env_st ? atoi(env_st) : 2, occ = env_occ ? atoi(env_occ) : 3;
-        if (group == 2 && stages == 4) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 4, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else if (group == 2) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 2, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
-        else if (occ == 3) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
+        static const char* env_occ = getenv("NO_TN_OCC");          // tuning aid, as for the forward product
+        const int occ = env_occ ? atoi(env_occ) : 3;
+        if (occ == 3) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
         else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
     }
     return launch_status("gemm_tn");

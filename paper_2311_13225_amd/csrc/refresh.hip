@@ -32,8 +32,8 @@ static int32_t refresh_create(no_cache_s* c, no_graph_s* g, no_dtype dt, int32_t
         NO_CHECK(r->x_f32.alloc((size_t)c->n_hot * feat_dim));
     }
     NO_HIP_CHECK(hipStreamCreateWithFlags(&r->stream, hipStreamNonBlocking));
-    NO_HIP_CHECK(hipEventCreateWithFlags(&r->ev_snap, hipEventDisableTiming));
-    NO_HIP_CHECK(hipEventCreateWithFlags(&r->ev_done, hipEventDisableTiming));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&r->ev_snap, NO_SYNC_EVENT_FLAGS));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&r->ev_done, NO_SYNC_EVENT_FLAGS));
     c->refresh = r;
     guard.r = nullptr;
     return NO_OK;

@@ -767,10 +767,10 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
     NO_CHECK(b->ws.alloc((size_t)(edge_tiles(max_items + 1) + 2) * sizeof(int64_t)));
     NO_CHECK(b->ws_side.alloc((size_t)(edge_tiles(max_items + 1) + 2) * sizeof(int64_t)));
     NO_HIP_CHECK(hipStreamCreateWithFlags(&b->side, hipStreamNonBlocking));
-    for (int32_t h = 0; h < n_layers; ++h) NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_fork[h], hipEventDisableTiming));
-    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_side_done, hipEventDisableTiming));
-    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_gather_done, hipEventDisableTiming));
-    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_indices_done, hipEventDisableTiming));
+    for (int32_t h = 0; h < n_layers; ++h) NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_fork[h], NO_SYNC_EVENT_FLAGS));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_side_done, NO_SYNC_EVENT_FLAGS));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_gather_done, NO_SYNC_EVENT_FLAGS));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_indices_done, NO_SYNC_EVENT_FLAGS));
     if (n_layers >= 2) {
         size_t v1_cap = (size_t)b->hop[n_layers - 2].n_src_cap;
         NO_CHECK(b->compute_list.alloc(v1_cap));

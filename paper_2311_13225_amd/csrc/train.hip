@@ -219,9 +219,9 @@ static int32_t ensure_lookahead(no_model_s* m, no_graph_s* g) {
     NO_CHECK(m->mean_alt.alloc(m->mean[0].n));
     NO_CHECK(m->h0_alt.alloc(m->h[0].n));
     NO_HIP_CHECK(hipStreamCreateWithFlags(&m->sample_stream, hipStreamNonBlocking));
-    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_can_sample, hipEventDisableTiming));
-    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_sampled, hipEventDisableTiming));
-    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_l1_done, hipEventDisableTiming));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_can_sample, NO_SYNC_EVENT_FLAGS));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_sampled, NO_SYNC_EVENT_FLAGS));
+    NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_l1_done, NO_SYNC_EVENT_FLAGS));
     return NO_OK;
 }
 
