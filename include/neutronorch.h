@@ -280,9 +280,9 @@ int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const 
  * model's own sampling stream (default priority) beside this step: it is sampled into a second set of blocks from
  * the step's start, and after this step's layer 1 its layer-1 aggregation runs into a second buffer (mean
  * aggregator with two or more layers), together with the copy of its reused rows out of the cache. The next call
- * uses that batch if it asks for exactly it (step + 1, the same d_next_seeds pointer and count, seed and cache);
- * otherwise it is dropped and the batch is sampled again. d_next_seeds and d_features must stay valid and unchanged
- * until then.
+ * uses that batch if it asks for exactly it (step + 1, the same d_next_seeds pointer and count, seed, cache and
+ * d_features); otherwise it is dropped and the batch is sampled again. d_next_seeds and d_features must stay valid
+ * and unchanged until then.
  * Cache versions: the split of a batch into reused and computed vertices writes the batch's step into the version
  * of every slot the batch will recompute (the row follows when its layer 1 runs), so while a batch is prepared
  * ahead those entries of no_cache_view already read step + 1; a dropped batch's entries are restored by the call

@@ -44,6 +44,7 @@ struct no_model_s {
     const int32_t* ahead_seeds = nullptr;
     int32_t ahead_n = 0;
     no_cache_s* ahead_cache = nullptr;
+    const void* ahead_features = nullptr;
     no::StageProfiler prof;
     void release() {
         if (prof.created) { for (auto& e : prof.ev) (void)hipEventDestroy(e); prof.created = false; }
@@ -251,7 +252,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     }
     // a batch sampled ahead by the previous call is used if it is exactly this one; anything else is dropped
     const bool presampled = m->ahead_valid && m->ahead_step == step && m->ahead_seed == seed && m->ahead_seeds == d_seeds &&
-                            m->ahead_n == n_seeds && m->ahead_cache == cache;
+                            m->ahead_n == n_seeds && m->ahead_cache == cache && m->ahead_features == d_features;
     bool aggregated = false;
     if (m->ahead_valid) {
         // (ev_sampled is recorded after everything the sampling stream did for that batch, the aggregation included)
@@ -331,6 +332,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         m->ahead_seeds = d_next_seeds;
         m->ahead_n = n_next_seeds;
         m->ahead_cache = cache;
+        m->ahead_features = d_features;
         return NO_OK;
     };
     auto launch_aggregate_ahead = [&]() -> int32_t {
