@@ -53,6 +53,11 @@ def main():
                          "(batch t+1 sampled on a second stream while batch t trains)")
     ap.add_argument("--arch", choices=["sage", "gcn"], default="sage",
                     help="layer form: GraphSAGE-mean (the headline configuration) or the GCN-style layer")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="seeds per batch instead of the workload's (the paper's batch-size sweep, 256 .. 10000)")
+    ap.add_argument("--fanouts", default="",
+                    help="comma-separated fanouts from the seeds down instead of the workload's (deeper models: the "
+                         "paper repeats the last value, e.g. 25,10,5,5)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain copy of known size (1,000,000 rows x 1024 B through no_gather_features with "
                          "ids 0..n-1): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -84,6 +89,10 @@ def main():
                           "bytes_written_per_launch": rows * dim * 4}), flush=True)
         return
     w = si.WORKLOADS[args.workload]
+    if args.batch > 0 or args.fanouts:
+        import dataclasses
+        w = dataclasses.replace(w, batch=args.batch if args.batch > 0 else w.batch,
+                                fanouts=tuple(int(x) for x in args.fanouts.split(",")) if args.fanouts else w.fanouts)
     K, W = args.steps, args.warmup
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
 

@@ -472,6 +472,16 @@ def test_train_step_single_layer_and_bf16_features():
     run_steps(wb, 3, use_cache=True)
 
 
+@pytest.mark.parametrize("fanouts,arch,ahead", [((5, 4, 3, 3), "sage", False), ((4, 3, 3, 2, 2), "sage", True),
+                                                ((4, 3, 3, 2, 2), "gcn", False), ((5, 4, 3, 3), "gcn", True)])
+def test_deeper_models_four_and_five_layers(fanouts, arch, ahead):
+    """The depths of the paper's model-depth experiments (the fanout list repeats its last value): every hop, the
+    cache split at the bottom one, reuse and the look-ahead on a 4- and a 5-layer model, both layer forms."""
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=fanouts, staleness=2, hot_fraction=0.2, batch=64, hidden=48)
+    assert run_steps(w, 4, use_cache=True, lr=0.02, ahead=ahead, arch=arch) > 0
+
+
 @pytest.mark.parametrize("hot_fraction,staleness", [(0.0, 2), (0.1, 0), (0.1, 2), (0.1, 4), (0.3, 2), (0.3, 4)])
 def test_hot_reuse_sweep_points(hot_fraction, staleness):
     """The hot-reuse sweep (hot fraction x staleness bound, the shape of the paper's Fig. 14 experiment) on a
