@@ -21,7 +21,6 @@ struct GemmNNArgs {
     int32_t n_problems;                   // 1 or 2
     int32_t accumulate;                   // 1: both products are summed into C[0]; 0: independent problems (grid.z)
     const int32_t* d_M; int32_t M_cap; int32_t N;
-    int32_t M_est;                        // expected row count for tile selection (0: half the capacity)
     const float* bias; int32_t relu;
     // Scattered output of C[0] (layer 1 with reuse, Section 4.1.2): row m goes to row c_rows[m] (NULL: m); a row with
     // c_keep_rows[m] >= 0 is also stored as row c_keep_rows[m] of c_keep (same leading dimension) and
