@@ -220,8 +220,9 @@ __global__ void __launch_bounds__(ETHREADS) edge_assign_kernel(const int32_t* __
 
 // One-launch form of the two kernels above (tile sums, then assignment): a single-pass scan. A block publishes its
 // tile's sum in a status word, adds up the words of the tiles before it until it meets one that already holds an
-// inclusive prefix (workgroups are dispatched in index order, so every earlier tile is running or done), publishes its
-// own inclusive prefix and assigns. A word packs both 31-bit counts and a 2-bit state, so it is written and read by one
+// inclusive prefix, publishes its own inclusive prefix and assigns. (Workgroups are handed out in index order, per
+// die in turn: an earlier tile is done, running, or the next to start on its die, and a waiting block never holds
+// the slot an earlier tile needs.) A word packs both 31-bit counts and a 2-bit state, so it is written and read by one
 // 64-bit access at device scope and needs no fence; the words are emptied by the sampling launch before. The wait on
 // an earlier tile is bounded: on expiry the block reports through `fail_flag` and goes on (wrong output, no hang).
 constexpr unsigned long long SCAN_SUM = 1ull, SCAN_PREFIX = 2ull;
