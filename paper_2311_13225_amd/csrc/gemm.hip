@@ -434,16 +434,9 @@ __global__ void __launch_bounds__(256, OCC) gemm_nn_kernel(GemmNNArgs g) {
     constexpr int SETS = AccSets<BM, BN>::N;
     floatx16 acc[SETS][MI][NI];
     acc_zero<SETS, MI, NI>(acc);
-    {
-        const int q0 = g.accumulate ? 0 : prob, q1 = g.accumulate && n_phases > 1 ? 1 : q0;
-        StepSource p0{g.A[q0], g.lda[q0], g.B[q0], g.ldb[q0], g.a_rows[q0], 0, g.K[q0], (g.K[q0] + BK - 1) / BK,
-                      g.K[q0] / BK, -1};
-        StepSource p1{g.A[q1], g.lda[q1], g.B[q1], g.ldb[q1], g.a_rows[q1], 0, g.K[q1],
-                      n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0, n_phases > 1 ? g.K[q1] / BK : 0, -1};
-        run_steps<true, B_KC, BM, BN, GRP, STG>(p0, p1, m0, M, n0, g.N, As, Bs, acc, wm, wn);
-    }
+    // What the epilogue needs per output row is requested here, ahead of the operands, so that it arrives behind
+    // them instead of costing a memory round trip after the last product.
     using OT = OutTile<BM, BN>;
-    acc_to_lds<BM, BN>(smem, acc, wm, wn);
     float* C = g.C[prob];
     const int64_t ldc = g.ldc[prob];
     const int32_t* sp = g.row_scale_indptr[prob];
@@ -468,6 +461,15 @@ __global__ void __launch_bounds__(256, OCC) gemm_nn_kernel(GemmNNArgs g) {
         scale[j] = 1.f;
         if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale[j] = len > 0 ? 1.f / (float)len : 0.f; }
     }
+    {
+        const int q0 = g.accumulate ? 0 : prob, q1 = g.accumulate && n_phases > 1 ? 1 : q0;
+        StepSource p0{g.A[q0], g.lda[q0], g.B[q0], g.ldb[q0], g.a_rows[q0], 0, g.K[q0], (g.K[q0] + BK - 1) / BK,
+                      g.K[q0] / BK, -1};
+        StepSource p1{g.A[q1], g.lda[q1], g.B[q1], g.ldb[q1], g.a_rows[q1], 0, g.K[q1],
+                      n_phases > 1 ? (g.K[q1] + BK - 1) / BK : 0, n_phases > 1 ? g.K[q1] / BK : 0, -1};
+        run_steps<true, B_KC, BM, BN, GRP, STG>(p0, p1, m0, M, n0, g.N, As, Bs, acc, wm, wn);
+    }
+    acc_to_lds<BM, BN>(smem, acc, wm, wn);
     // One explicit wait for every load above (vmcnt 0; the other counters left alone): the stores below sit in
     // divergent branches, and a wait placed after them would have to drain the stores as well, row after row.
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -516,6 +518,25 @@ __global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
     const int lane = (int)(threadIdx.x & 63), wave = (int)(threadIdx.x >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     const int row_c = min(m0 + l32, M - 1), col_c = min(n0 + l32, g.N - 1);
+    float* C = g.C[prob];
+    const int64_t ldc = g.ldc[prob];
+    const int32_t* sp = g.row_scale_indptr[prob];
+    const int32_t* c_rows = prob == 0 ? g.c_rows : nullptr;
+    const int32_t* c_keep_rows = prob == 0 ? g.c_keep_rows : nullptr;
+    int32_t crow[4], krow[4];
+    float scale[4], bias_v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {       // indices and scales of this thread's four output elements, requested before the
+                                        // operands so that they arrive behind them instead of after the products
+        const int e = (int)threadIdx.x + 256 * i;
+        const int r = e >> 6, ln = e & 63;
+        const int row = min(m0 + acc_row(r, ln), M - 1), col = min(n0 + (ln & 31), g.N - 1);
+        crow[i] = c_rows ? c_rows[row] : row;
+        krow[i] = c_keep_rows ? c_keep_rows[row] : -1;
+        bias_v[i] = g.bias ? g.bias[col] : 0.f;
+        scale[i] = 1.f;
+        if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale[i] = len > 0 ? 1.f / (float)len : 0.f; }
+    }
     floatx16 acc, acc2;                       // two sets, so consecutive MFMAs of a round do not depend on each other
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = acc2[r] = 0.f;
@@ -582,24 +603,6 @@ __global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r] + acc2[r];
     __syncthreads();
-    float* C = g.C[prob];
-    const int64_t ldc = g.ldc[prob];
-    const int32_t* sp = g.row_scale_indptr[prob];
-    const int32_t* c_rows = prob == 0 ? g.c_rows : nullptr;
-    const int32_t* c_keep_rows = prob == 0 ? g.c_keep_rows : nullptr;
-    int32_t crow[4], krow[4];
-    float scale[4], bias_v[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {       // indices and scales of this thread's four elements, requested together
-        const int e = (int)threadIdx.x + 256 * i;
-        const int r = e >> 6, ln = e & 63;
-        const int row = min(m0 + acc_row(r, ln), M - 1), col = min(n0 + (ln & 31), g.N - 1);
-        crow[i] = c_rows ? c_rows[row] : row;
-        krow[i] = c_keep_rows ? c_keep_rows[row] : -1;
-        bias_v[i] = g.bias ? g.bias[col] : 0.f;
-        scale[i] = 1.f;
-        if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale[i] = len > 0 ? 1.f / (float)len : 0.f; }
-    }
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt 0: see gemm_nn_kernel
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
