@@ -286,7 +286,8 @@ int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const 
  * Cache versions: the split of a batch into reused and computed vertices writes the batch's step into the version
  * of every slot the batch will recompute (the row follows when its layer 1 runs), so while a batch is prepared
  * ahead those entries of no_cache_view already read step + 1; a dropped batch's entries are restored by the call
- * that drops it. Do not commit a bulk refresh or reset the cache between the two calls.
+ * that drops it. Do not commit a bulk refresh, invalidate the cache or change its bound between the two calls (the
+ * prepared batch was split against the cache as it stood).
  * commit_refresh_before_next != 0: a pending bulk refresh (no_refresh_hot_begin) is committed after this step's
  * last use of the cache and before the next batch is sampled (which then starts after this step's layer 1); use it
  * on the last step of a super-batch instead of calling no_refresh_hot_commit between the two steps. The first
