@@ -236,7 +236,8 @@ def layer_case(V, E, F, d_out, fanouts, B, seed, bf16=False):
 
 @pytest.mark.parametrize("F,d_out,relu,bf16", [(64, 64, True, False), (602, 256, True, False), (100, 47, False, False),
                                                (33, 5, True, False), (256, 130, True, False), (128, 256, True, True),
-                                               (6, 3, False, True), (40, 200, True, False), (70, 41, False, False)])
+                                               (6, 3, False, True), (40, 200, True, False), (70, 41, False, False),
+                                               (256, 41, False, False), (200, 50, True, False)])
 def test_sage_layer_forward_backward(F, d_out, relu, bf16):
     b = nb()
     blk, x, xb, w_self, w_neigh, bias, rng = layer_case(4000, 60_000, F, d_out, (7, 6), 300, 11, bf16)
