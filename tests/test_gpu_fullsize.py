@@ -55,3 +55,13 @@ def test_sparse_workload_full_size_steps():
     w = si.WORKLOADS["sparse"]
     hits = run_steps(w, 3, use_cache=True, lr=0.01, bits=w.rowptr_bits, presample=1, n_train_presample=20 * w.batch)
     assert hits > 0
+
+
+def test_sweep_workload_full_size_steps_prepared_ahead():
+    """The shape of the hot-ratio sweep (Fig. 14) used here: batch 4096, 256 features, hot 10 %, S = 2, at full size, batches
+    prepared ahead."""
+    print("sweep full size, batches prepared ahead", flush=True)
+    w = si.WORKLOADS["sweep"]
+    hits = run_steps(w, 3, use_cache=True, lr=0.01, bits=w.rowptr_bits, presample=1, n_train_presample=5 * w.batch,
+                     ahead=True)
+    assert hits > 0
