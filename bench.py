@@ -164,6 +164,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(W, K, ahead=use_ahead)
+    enqueue_ms_per_step = (time.perf_counter() - t0) * 1e3 / K      # host time to enqueue a step (no wait for the GPU)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / K
@@ -315,6 +316,7 @@ def main():
         "cache_hit_rate": round(n_hit / max(n_v1, 1.0), 4),
         "stage_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
         "profiled_ms_per_step": round(sum(v for k, v in per_step.items() if k != "gather"), 4),
+        "host_enqueue_ms_per_step": round(enqueue_ms_per_step, 4),
         "setup_s": {"build_csr": round(t_csr, 2), "select_hot": round(t_hot, 2)},
         "loss_after_last_step": round(float(loss_last), 5),
         "superbatch_schedule": superbatch,
