@@ -668,8 +668,15 @@ int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent
 
 // ------------------------------------------------------------------------------------------ TN
 
+// The jobs of one launch (by value in the kernel arguments): job j owns the linear block ids [end_block[j-1], end_block[j]).
+struct TNLaunch { GemmTNArgs job[NO_MAX_LAYERS]; uint32_t end_block[NO_MAX_LAYERS]; int32_t n; };
+
 template <int BM, int BN, int GRP = 1, int STG = 2, int OCC = 2>
-__global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(GemmTNArgs g) {
+__global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(TNLaunch launch) {
+    int job = 0;
+    uint32_t first = 0;
+    while (job + 1 < launch.n && blockIdx.x >= launch.end_block[job]) first = launch.end_block[job++];
+    const GemmTNArgs& g = launch.job[job];
     constexpr int MI = BM / 64, NI = BN / 64;
     constexpr int A_TOTAL = 2 * GRP * TileShape<false, BM>::FLOATS, B_TOTAL = 2 * GRP * TileShape<false, BN>::FLOATS;
     // the output tile is staged over the operand copies
@@ -679,9 +686,12 @@ __global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(GemmTNArgs g) {
     float* Bs = smem + A_TOTAL;
     int R = *g.d_R;
     if (R > g.R_cap) R = g.R_cap;
-    // plain 3-D grid: dealing the slices out per XCD measured slower here (the partial tiles are written
-    // once and the operand slices are small), so the tiles of a slice stay spread over the dies
-    const int bx = (int)blockIdx.x, by = (int)blockIdx.y, bz = (int)blockIdx.z;
+    // a job's blocks in the order of a plain 3-D grid (column tile fastest, then row tile, then problem x slice): dealing
+    // the slices out per XCD measured slower here (the partial tiles are written once and the operand slices are small),
+    // so the tiles of a slice stay spread over the dies
+    const uint32_t id = blockIdx.x - first;
+    const uint32_t gx = (uint32_t)((g.N + BN - 1) / BN), gy = (uint32_t)((g.Kp + 1 + BM - 1) / BM);
+    const int bx = (int)(id % gx), by = (int)((id / gx) % gy), bz = (int)(id / (gx * gy));
     const int prob = bz / g.splits, split = bz % g.splits;
     int chunk = (R + g.splits - 1) / g.splits;
     chunk = (chunk + BK - 1) / BK * BK;
@@ -724,8 +734,7 @@ __global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(GemmTNArgs g) {
     }
 }
 
-int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
-    if (a.Kp <= 0 || a.N <= 0) return NO_OK;
+int32_t gemm_tn_partials(const GemmTNArgs* jobs, int32_t n_jobs, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     // 64x64 tiles: the output of one split is small, so the chip is filled by many small blocks over a
     // moderate number of splits rather than by few large blocks over many splits (fewer partials to reduce).
     // NO_TN_TILE=<bm>x<bn> pins another shape (tuning aid; both values in {64, 128}).
@@ -735,15 +744,27 @@ int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0, hi
         int fm = 0, fn = 0;
         if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128)) { bm = fm; bn = fn; }
     }
-    dim3 grid((unsigned)ceil_div(a.N, bn), (unsigned)ceil_div(a.Kp + 1, bm), (unsigned)(a.n_problems * a.splits));
-    if (bm == 128 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 128>), grid, dim3(256), st, ev0, ev1, a);
-    else if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 128>), grid, dim3(256), st, ev0, ev1, a);
-    else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 64>), grid, dim3(256), st, ev0, ev1, a);
+    TNLaunch launch{};
+    uint64_t blocks = 0;
+    for (int32_t j = 0; j < n_jobs && launch.n < NO_MAX_LAYERS; ++j) {
+        const GemmTNArgs& a = jobs[j];
+        if (a.Kp <= 0 || a.N <= 0) continue;
+        blocks += (uint64_t)ceil_div(a.N, bn) * (uint64_t)ceil_div(a.Kp + 1, bm) * (uint64_t)(a.n_problems * a.splits);
+        NO_REQUIRE(blocks < (1ull << 31), NO_ERR_CAPACITY, "gemm_tn: too many blocks");
+        launch.job[launch.n] = a;
+        launch.end_block[launch.n] = (uint32_t)blocks;
+        ++launch.n;
+    }
+    if (launch.n == 0) return NO_OK;
+    dim3 grid((unsigned)blocks);
+    if (bm == 128 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 128>), grid, dim3(256), st, ev0, ev1, launch);
+    else if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 128>), grid, dim3(256), st, ev0, ev1, launch);
+    else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 64>), grid, dim3(256), st, ev0, ev1, launch);
     else {
         static const char* env_occ = getenv("NO_TN_OCC");          // tuning aid, as for the forward product
         const int occ = env_occ ? atoi(env_occ) : 3;
-        if (occ == 3) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
-        else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
+        if (occ == 3) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, launch);
+        else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 2>), grid, dim3(256), st, ev0, ev1, launch);
     }
     return launch_status("gemm_tn");
 }
@@ -778,20 +799,25 @@ __device__ void write_step_stats(const StatsJob& j) {
     }
 }
 
-__global__ void __launch_bounds__(256) reduce_grads_kernel(const float* __restrict__ P, int32_t splits, int32_t Kp, int32_t N,
-                                                           float* g_self, float* g_neigh, float* g_bias, float lr, float* w_self,
-                                                           float* w_neigh, float* w_bias, StatsJob job) {
-    if (job.stats && blockIdx.x == gridDim.x - 1) {      // the extra block of the launch
-        if (blockIdx.y == 0) write_step_stats(job);
+struct ReduceLaunch { ReduceArgs job[NO_MAX_LAYERS]; uint32_t end_block[NO_MAX_LAYERS]; int32_t n; };
+
+__global__ void __launch_bounds__(256) reduce_grads_kernel(ReduceLaunch launch, StatsJob stats) {
+    if (stats.stats && blockIdx.x == gridDim.x - 1) {      // the extra block of the launch
+        if (blockIdx.y == 0) write_step_stats(stats);
         return;
     }
+    int job = 0;
+    uint32_t first = 0;
+    while (job + 1 < launch.n && blockIdx.x >= launch.end_block[job]) first = launch.end_block[job++];
+    const ReduceArgs& a = launch.job[job];
+    const int32_t Kp = a.Kp, N = a.N, splits = a.splits;
     const int64_t per = (int64_t)(Kp + 1) * N;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = (int64_t)(blockIdx.x - first) * blockDim.x + threadIdx.x;
     const int q = (int)blockIdx.y;
-    if (i >= per) return;
+    if (i >= per || q >= a.n_problems) return;
     const bool bias_row = i >= (int64_t)Kp * N;
     if (q == 1 && bias_row) return;
-    const float* p = P + (int64_t)q * splits * per + i;
+    const float* p = a.P + (int64_t)q * splits * per + i;
     // eight partials are requested before the first add; the adds stay in split order
     float s = 0.f;
     int32_t k = 0;
@@ -803,21 +829,29 @@ __global__ void __launch_bounds__(256) reduce_grads_kernel(const float* __restri
         for (int j = 0; j < 8; ++j) s += v[j];
     }
     for (; k < splits; ++k) s += p[(int64_t)k * per];
-    float* gout = bias_row ? g_bias + (i - (int64_t)Kp * N) : (q == 0 ? g_self + i : g_neigh + i);
+    float* gout = bias_row ? a.g_bias + (i - (int64_t)Kp * N) : (q == 0 ? a.g_self + i : a.g_neigh + i);
     *gout = s;
-    if (lr != 0.f) {
-        float* w = bias_row ? w_bias + (i - (int64_t)Kp * N) : (q == 0 ? w_self + i : w_neigh + i);
-        *w -= lr * s;
+    if (a.lr != 0.f) {
+        float* w = bias_row ? a.w_bias + (i - (int64_t)Kp * N) : (q == 0 ? a.w_self + i : a.w_neigh + i);
+        *w -= a.lr * s;
     }
 }
 
-int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
-                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems,
-                     const StatsJob* stats_job) {
-    const int64_t per = (int64_t)(Kp + 1) * N;
+int32_t reduce_grads(const ReduceArgs* jobs, int32_t n_jobs, hipStream_t st, const StatsJob* stats_job) {
+    ReduceLaunch launch{};
+    uint64_t blocks = 0;
+    for (int32_t j = 0; j < n_jobs && launch.n < NO_MAX_LAYERS; ++j) {
+        const ReduceArgs& a = jobs[j];
+        if (a.Kp <= 0 || a.N <= 0) continue;
+        blocks += (uint64_t)ceil_div((int64_t)(a.Kp + 1) * a.N, 256);
+        NO_REQUIRE(blocks < (1ull << 31), NO_ERR_CAPACITY, "reduce_grads: too many blocks");
+        launch.job[launch.n] = a;
+        launch.end_block[launch.n] = (uint32_t)blocks;
+        ++launch.n;
+    }
     const StatsJob job = stats_job ? *stats_job : StatsJob{};
-    hipLaunchKernelGGL(reduce_grads_kernel, dim3((unsigned)ceil_div(per, 256) + (job.stats ? 1u : 0u), (unsigned)n_problems), dim3(256), 0, st, P, splits, Kp, N, g_self,
-                       g_neigh, g_bias, lr, w_self, w_neigh, w_bias, job);
+    if (launch.n == 0 && !job.stats) return NO_OK;
+    hipLaunchKernelGGL(reduce_grads_kernel, dim3((unsigned)blocks + (job.stats ? 1u : 0u), 2u), dim3(256), 0, st, launch, job);
     return launch_status("reduce_grads");
 }
 

@@ -47,13 +47,28 @@ struct StatsJob {
     no_step_stats* stats = nullptr;       // NULL: no job
 };
 
+// The reduction that follows a split product: sums the partials in split order into the three gradients; with
+// lr != 0 also applies W <- W - lr * g.
+struct ReduceArgs {
+    const float* P; int32_t splits, Kp, N;
+    float* g_self; float* g_neigh; float* g_bias;
+    float lr; float* w_self; float* w_neigh; float* w_bias;
+    int32_t n_problems;                                  // 2, or 1: only g_self and g_bias
+};
+
+// Weight-gradient work of several layers carried by one product launch and one reduction launch: the gradients of an
+// upper layer are nobody's input within the step, so they need not sit on the step's chain of dependent launches
+// between that layer's input gradient and the layer below. Job 0's blocks are dealt out first.
+struct GradJobs {
+    GemmTNArgs tn[NO_MAX_LAYERS]; ReduceArgs red[NO_MAX_LAYERS];
+    int32_t n = 0;
+};
+
 // ev0 / ev1 (optional): events that take the product kernel's own start and end times
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
-int32_t gemm_tn_partials(const GemmTNArgs& a, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
-// Sums the partials in split order into the three gradients; with lr != 0 also applies W <- W - lr * g.
-int32_t reduce_grads(const float* P, int32_t splits, int32_t Kp, int32_t N, float* g_self, float* g_neigh, float* g_bias,
-                     float lr, float* w_self, float* w_neigh, float* w_bias, hipStream_t st, int32_t n_problems = 2,
-                     const StatsJob* stats_job = nullptr);
+int32_t gemm_tn_partials(const GemmTNArgs* jobs, int32_t n_jobs, hipStream_t st, hipEvent_t ev0 = nullptr,
+                         hipEvent_t ev1 = nullptr);
+int32_t reduce_grads(const ReduceArgs* jobs, int32_t n_jobs, hipStream_t st, const StatsJob* stats_job = nullptr);
 
 inline int ptr_align(const void* p, int64_t ld) {
     if ((((uintptr_t)p) & 15) == 0 && (ld & 3) == 0) return 4;

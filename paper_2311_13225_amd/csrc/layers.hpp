@@ -92,7 +92,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       const int32_t* grad_rows = nullptr, float lr = 0.f, float* w_self_rw = nullptr,
                       float* w_neigh_rw = nullptr, float* bias_rw = nullptr, int32_t arch = NO_ARCH_SAGE_MEAN,
                       const StatsJob* stats_job = nullptr, const float* gz_in = nullptr,
-                      const BelowLayer* below = nullptr);
+                      const BelowLayer* below = nullptr, GradJobs* pending = nullptr, bool defer = false);
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
                     const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
 

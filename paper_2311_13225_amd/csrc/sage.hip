@@ -389,7 +389,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int prep_stage, int dw_stage,
                       int reduce_stage, int dx_stage, const int32_t* grad_rows, float lr, float* w_self_rw,
                       float* w_neigh_rw, float* bias_rw, int32_t arch, const StatsJob* stats_job, const float* gz_in,
-                      const BelowLayer* below) {
+                      const BelowLayer* below, GradJobs* pending, bool defer) {
     const bool gcn = arch == NO_ARCH_GCN;
     const int32_t n_cap = blk.n_dst_cap;
     if (prof && prep_stage >= 0) prof->begin(prep_stage);
@@ -443,12 +443,26 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     t.G = gz; t.ldg = d_out; t.g_align = ptr_align(gz, d_out);
     t.P = w.partials; t.Kp = d_in; t.N = d_out;
     t.d_R = blk.d_n_dst; t.R_cap = n_cap; t.splits = w.splits;
+    const ReduceArgs r{w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, gcn ? 1 : 2};
+    if (pending && defer) {
+        // an upper layer inside a step: its product and reduction ride on the bottom layer's launches
+        if (pending->n >= NO_MAX_LAYERS) { set_error("sage_backward: too many deferred layers"); return NO_ERR_CAPACITY; }
+        pending->tn[pending->n] = t;
+        pending->red[pending->n] = r;
+        ++pending->n;
+        return launch_status("sage_backward");
+    }
+    GemmTNArgs tj[NO_MAX_LAYERS];
+    ReduceArgs rj[NO_MAX_LAYERS];
+    int32_t n_jobs = 0;
+    tj[n_jobs] = t; rj[n_jobs] = r; ++n_jobs;
+    for (int32_t i = 0; pending && i < pending->n && n_jobs < NO_MAX_LAYERS; ++i, ++n_jobs) { tj[n_jobs] = pending->tn[i]; rj[n_jobs] = pending->red[i]; }
+    if (pending) pending->n = 0;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (prof && dw_stage >= 0) prof->kernel_pair(dw_stage, &e0, &e1);
-    NO_CHECK(gemm_tn_partials(t, st, e0, e1));
+    NO_CHECK(gemm_tn_partials(tj, n_jobs, st, e0, e1));
     if (prof && reduce_stage >= 0) prof->begin(reduce_stage);
-    NO_CHECK(reduce_grads(w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, st,
-                          gcn ? 1 : 2, stats_job));
+    NO_CHECK(reduce_grads(rj, n_jobs, st, stats_job));
     if (prof && reduce_stage >= 0) prof->end();
     return launch_status("sage_backward");
 }

@@ -419,6 +419,11 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
 
     // backward (first joins the side stream: the transposes are needed from here on)
     NO_CHECK(blocks_join(B, st));
+    // The weight gradients of the layers above the bottom one (and their SGD step) are nobody's input within the step:
+    // their products and reductions are carried by the bottom layer's two launches, which end the step, instead of
+    // adding two launches per layer to the chain of dependent kernels. (NO_DW_INLINE=1: tuning aid, one pair per layer.)
+    static const char* dw_inline = getenv("NO_DW_INLINE");
+    GradJobs pending;
     for (int32_t l = L; l >= 1; --l) {
         const no_block_view& blk = view[L - l];
         const int32_t d_in = m->dims[l - 1], d_out = m->dims[l];
@@ -453,7 +458,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
                                l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
                                -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                                m->params.p + m->off_bias[l - 1], m->arch, l == 1 ? &stats_job : nullptr, gz_in,
-                               l >= 2 ? &below : nullptr));
+                               l >= 2 ? &below : nullptr, dw_inline ? nullptr : &pending, l >= 2));
     }
 
     // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;
