@@ -113,6 +113,32 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const
             for (int c = 0; c < VEC; ++c) acc[c] = o[c];
         }
         int32_t p = b;
+        if (!MEAN && g_log2 == 6 && (units & 63) == 0) {      // (every lane of the wavefront is at work on this row)
+            // Backward through the transpose, one wavefront per source row: a popular source has hundreds of entries, and
+            // eight rows per round trip (each behind a round trip for its indices) would make that one row the kernel's
+            // critical path. The wavefront reads 64 indices with one load and keeps 16 rows in flight; segments shorter
+            // than 16 (nearly all of them) fall through to the rounds of 8, 4 and 1-3 below.
+            for (; p + 16 <= e;) {
+                const int32_t n = min(64, e - p);
+                const int32_t mine = lane < n ? idx[p + lane] : 0;
+                int32_t t = 0;
+                for (; t + 16 <= n; t += 16) {
+                    float a[16][VEC];
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int32_t ix = __shfl(mine, t + j, 64);
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) a[j][c] = 0.f;
+                        RowVec<T, VEC>::add(a[j], col + (int64_t)ix * ld_src);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 16; ++j)
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc[c] += a[j][c];
+                }
+                p += t;
+            }
+        }
         for (; p + 8 <= e; p += 8) {
             int32_t ix[8];
 #pragma unroll
