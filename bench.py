@@ -280,7 +280,9 @@ def main():
     # launch copy from the cache into H^1 (read + write)
     agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4 + (n_hit * w.dims[1] * 4 * 2 if L >= 2 else 0)
     gemm_fwd_flops = 2.0 * n_dst_bottom * ((1 if gcn else 2) * F) * w.dims[1]
-    gemm_dw_flops = gemm_fwd_flops
+    # the weight-gradient launch of layer 1 also carries the (smaller) weight-gradient products of the layers above
+    gemm_dw_flops = gemm_fwd_flops + sum(
+        2.0 * mean([st_.n_dst[L - l] for st_ in stats]) * ((1 if gcn else 2) * w.dims[l - 1]) * w.dims[l] for l in range(2, L + 1))
     kern = {
         "gather_rows_kernel": ("hbm", gather_bytes / 1e9 / (per_step["gather"] / 1e3), HBM_PEAK_GBPS, "GB/s", per_step["gather"]),
         "segment_rows_kernel(mean,l1)": ("hbm", agg_bytes / 1e9 / (per_step["agg_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", per_step["agg_l1"]),
