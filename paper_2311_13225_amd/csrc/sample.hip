@@ -516,6 +516,141 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
     }
 }
 
+// One-launch form of the two kernels above (a single-pass scan like edge_scan_kernel, with the same status words,
+// emptied by the sampling launch of the hop above, and the same bounded waits): a block probes the cache for its tile,
+// publishes the tile's counts, adds up the tiles before it and writes its part of the split from the probe results it
+// still holds in registers. The first idx_blocks blocks write the local indices of the hop above out of the id map;
+// the split re-keys that map, so every tile block waits, before its map writes, until a counter says that all index
+// blocks with work have read (they come first in index order and take two round trips, the probe takes four: the
+// wait is there for correctness, not because it is ever long).
+__global__ void __launch_bounds__(ETHREADS) v1_split_kernel(CacheProbe probe, const int32_t* d_n_v1, unsigned long long* status,
+                                                            uint32_t idx_blocks, const int32_t* d_nnz,
+                                                            const int32_t* __restrict__ nbr, int32_t* map,
+                                                            int32_t* __restrict__ indices, int32_t* csc_cnt,
+                                                            unsigned int* idx_done, int32_t* compute_list,
+                                                            int32_t* compute_pos, int32_t* compute_inv, int32_t* refresh_slot,
+                                                            int32_t* hit_pos, int32_t* hit_slot,
+                                                            int32_t* extra /* n_compute, n_hit, -, -, n_refresh */,
+                                                            int32_t* version, int32_t stamp, int32_t* refresh_old,
+                                                            int32_t* fail_flag) {
+    if (blockIdx.x < idx_blocks) {
+        const int64_t e = (int64_t)blockIdx.x * ETHREADS + threadIdx.x;
+        const int32_t nnz = *d_nnz;
+        if ((int64_t)blockIdx.x * ETHREADS >= nnz) return;      // (whole block: no work, no signal)
+        if (e < nnz) {
+            const int32_t local = map[nbr[e]];
+            indices[e] = local;
+            if (csc_cnt) atomicAdd(&csc_cnt[local], 1);     // integer count: order independent
+        }
+        __syncthreads();      // every map read of the block has returned (its value went into a store)
+        if (threadIdx.x == 0) __hip_atomic_fetch_add(idx_done, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    const uint32_t tile = blockIdx.x - idx_blocks;
+    __shared__ int64_t smem[ETHREADS / 64 + 1];
+    __shared__ int64_t prefix_sh;
+    const int64_t n = *d_n_v1;
+    const int64_t base = (int64_t)tile * ETILE;
+    if (base >= n) return;
+    const int64_t i0 = base + (int64_t)threadIdx.x * EITEMS;
+    // three dependent loads per vertex; each level is issued for all items before the next is needed
+    int32_t v[EITEMS], slot[EITEMS], ver[EITEMS];
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) v[t] = i0 + t < n ? probe.v1[i0 + t] : -1;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) slot[t] = v[t] >= 0 ? probe.slot_of_vertex[v[t]] : -1;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) ver[t] = slot[t] >= 0 ? probe.version[slot[t]] : -1;
+    int64_t f[EITEMS];
+    int64_t s = 0;
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        f[t] = i0 + t < n ? probe.flags(slot[t], ver[t]) : 0;
+        s += f[t];
+    }
+    int64_t total;
+    int64_t run = block_exclusive_scan<int64_t, ETHREADS>(s, &total, smem);
+    if (threadIdx.x < 64) {
+        const int lane = (int)threadIdx.x;
+        int64_t prefix = 0;
+        if (tile > 0) {
+            if (lane == 0)
+                __hip_atomic_store(&status[tile], scan_pack(total, SCAN_SUM), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int64_t first = (int64_t)tile - 1;
+            int spins = 0;
+            while (first >= 0) {
+                const int64_t j = first - lane;
+                unsigned long long w = SCAN_PREFIX << 62;
+                if (j >= 0) w = __hip_atomic_load(&status[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned long long state = w >> 62;
+                const unsigned long long is_prefix = __ballot(state == SCAN_PREFIX), is_empty = __ballot(state == 0ull);
+                const int n_ok = is_empty ? __builtin_ctzll(is_empty) : 64;
+                const int p_at = is_prefix ? __builtin_ctzll(is_prefix) : 64;
+                const int take = p_at < n_ok ? p_at + 1 : n_ok;
+                int64_t val = lane < take ? scan_unpack(w) : 0;
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) val += __shfl_xor(val, o, 64);
+                prefix += val;
+                first -= take;
+                if (p_at < n_ok) break;
+                if (take == 0) {
+                    if (++spins > (1 << 20)) { if (lane == 0) *fail_flag = 2; break; }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+            }
+        }
+        if (lane == 0) {
+            __hip_atomic_store(&status[tile], scan_pack(prefix + total, SCAN_PREFIX), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            prefix_sh = prefix;
+            if (base + ETILE >= n) {      // the last tile holds the totals
+                const int64_t all = prefix + total;
+                const int32_t n_compute = (int32_t)(all & 0xffffffffll);
+                extra[0] = n_compute;
+                extra[1] = (int32_t)n - n_compute;
+                extra[4] = (int32_t)(all >> 32);
+            }
+        }
+    }
+    if (threadIdx.x == 0) {
+        const int32_t nnz = *d_nnz;
+        const unsigned int expected = (unsigned int)((nnz + ETHREADS - 1) / ETHREADS);
+        int spins = 0;
+        while (__hip_atomic_load(idx_done, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < expected) {
+            if (++spins > (1 << 20)) { *fail_flag = 2; break; }
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+    __syncthreads();
+    run = (run & 0xffffffffll) + (prefix_sh & 0xffffffffll);
+#pragma unroll
+    for (int t = 0; t < EITEMS; ++t) {
+        const int64_t i = i0 + t;
+        if (i < n) {
+            const int32_t c = (int32_t)(f[t] & 1);
+            if (c) {
+                compute_pos[run] = (int32_t)i;
+                compute_inv[i] = (int32_t)run;
+                const int32_t rslot = slot[t] >= 0 ? slot[t] : -1;       // hot but to be computed
+                refresh_slot[run] = rslot;
+                if (version && rslot >= 0) {
+                    refresh_old[run] = ver[t];
+                    version[rslot] = stamp;
+                }
+                compute_list[run] = v[t];
+                map[v[t]] = (int32_t)run;
+            } else {
+                const int64_t p = i - run;
+                hit_pos[p] = (int32_t)i;
+                compute_inv[i] = -1;
+                hit_slot[p] = slot[t];
+                map[v[t]] = EMPTY;
+            }
+            run += c;
+        }
+    }
+}
+
 __global__ void set_counts_kernel(int32_t* p, int32_t a, int32_t b, int32_t c) { p[0] = a; p[1] = b; p[4] = c; }
 
 // Takes back the stamps of a split whose batch is not trained on.
@@ -535,7 +670,7 @@ static inline int64_t edge_tiles(int64_t n_pad_cap) { int64_t t = ceil_div(n_pad
 template <typename RowT>
 static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b, int32_t h, const int32_t* d_dst,
                           const int32_t* d_n_dst_in, int32_t n_fixed, bool insert_dst, uint32_t key0, uint32_t key1,
-                          uint32_t domain, hipStream_t st, bool indices_now) {
+                          uint32_t domain, hipStream_t st, bool indices_now, int32_t extra_status = 0) {
     HopBuffers& H = b->hop[h];
     int32_t* cnt = b->counts.p + 4 * h;              // n_dst, n_src, nnz
     const int32_t k = H.fanout;
@@ -549,7 +684,7 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     hipLaunchKernelGGL((sample_rows_kernel<G, RowT>), dim3((unsigned)ceil_div(H.n_dst_cap, 256 / G)), dim3(256), 0, st,    \
                        rowptr, col, d_dst, d_n_dst_in, n_fixed, H.n_dst_cap, k, key0, key1, c3, H.nbr_pad.p,               \
                        H.src_global.p, b->map.p, insert_dst ? 1 : 0, seeds_copy, cnt, (int32_t)b->n_vertices,               \
-                       b->counts.p + 4 * b->n_layers + 5, (unsigned long long*)b->ws.p, (int32_t)edge_tiles(H.nnz_cap))
+                       b->counts.p + 4 * b->n_layers + 5, (unsigned long long*)b->ws.p, (int32_t)edge_tiles(H.nnz_cap) + extra_status)
     if (k <= 8) NO_LAUNCH_SAMPLE(8);
     else if (k <= 16) NO_LAUNCH_SAMPLE(16);
     else if (k <= 32) NO_LAUNCH_SAMPLE(32);
@@ -648,6 +783,17 @@ int32_t blocks_join(no_blocks_s* b, hipStream_t st) {
     return NO_OK;
 }
 
+// One launch for the V^1 split where the sampling has the chip to itself, two launches where it runs beside another
+// batch's products, as for the edge compaction and for the same reason (measured on a V^1 of five tiles: sampling alone
+// 72 -> 68 us in one launch, but 2 % fewer steps per second when sampling ahead). NO_V1_TWO_PASS=<0|1> forces either
+// form (tuning aid).
+static bool v1_one_launch(const no_blocks_s* b, unsigned tiles) {
+    (void)tiles;
+    static const char* env = getenv("NO_V1_TWO_PASS");
+    if (env) return atoi(env) == 0;
+    return !b->scan_two_pass;
+}
+
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key, uint32_t domain,
                            int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st, bool join,
                            const SideGather* gather, bool inline_side, bool stamp_refresh) {
@@ -670,6 +816,16 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
             const unsigned tiles = (unsigned)edge_tiles(P.n_src_cap);
             const unsigned idx_blocks = (unsigned)ceil_div(P.nnz_cap, ETHREADS);
             int64_t* tile_sums = (int64_t*)b->ws.p;
+            if (v1_one_launch(b, tiles)) {
+                // (status words and the counter behind them: emptied by the sampling launch of hop L-2, past its own)
+                unsigned long long* v1_status = (unsigned long long*)b->ws.p + edge_tiles(P.nnz_cap);
+                hipLaunchKernelGGL(v1_split_kernel, dim3(idx_blocks + tiles), dim3(ETHREADS), 0, st, probe, d_n, v1_status,
+                                   idx_blocks, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2), (const int32_t*)P.nbr_global.p,
+                                   b->map.p, P.indices.p, P.has_csc ? P.csc_cnt.p : nullptr, (unsigned int*)(v1_status + tiles),
+                                   b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
+                                   b->hit_slot.p, extra, stamp_refresh ? cache->version.p : nullptr, (int32_t)step,
+                                   b->refresh_old.p, b->counts.p + 4 * b->n_layers + 5);
+            } else {
             hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles + idx_blocks), dim3(ETHREADS), 0, st, probe, d_n, tile_sums,
                                b->probe_slot.p, tiles, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2),
                                (const int32_t*)P.nbr_global.p, (const int32_t*)b->map.p, P.indices.p,
@@ -679,6 +835,8 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
                                (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
                                b->hit_slot.p, extra, stamp_refresh ? cache->version.p : nullptr, (int32_t)step,
                                b->refresh_old.p);
+            }
+            indices_done[h - 1] = true;
             b->stamped_cache = stamp_refresh ? cache : nullptr;
             d_dst = b->compute_list.p;
             d_n = extra + 0;
@@ -686,12 +844,15 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
         // with the cache split ahead, the hops above L-2 read the map before the split re-keys it; every other
         // hop's indices wait for the side stream
         const bool indices_now = use_cache && h < L - 2;
+        // the hop above the bottom one also empties the status words of the V^1 split that follows it
+        const int32_t extra_status = (use_cache && h == L - 2 && v1_one_launch(b, (unsigned)edge_tiles(b->hop[h].n_src_cap)))
+                                         ? (int32_t)edge_tiles(b->hop[h].n_src_cap) + 1 : 0;
         if (g->rowptr_bits == 64)
             NO_CHECK(sample_hop<int64_t>(g->rowptr64.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st,
-                                         indices_now));
+                                         indices_now, extra_status));
         else
             NO_CHECK(sample_hop<int32_t>(g->rowptr32.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st,
-                                         indices_now));
+                                         indices_now, extra_status));
         if (indices_now) indices_done[h] = true;
         d_dst = b->hop[h].src_global.p;
         d_n = b->counts.p + 4 * h + 1;
@@ -765,7 +926,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
     NO_CHECK(fill_i32(b->map.p, EMPTY, g->n_vertices, nullptr));
     NO_CHECK(b->tmp_a.alloc((size_t)max_sort));
     const int64_t max_items = max_pad > max_src ? max_pad : max_src;
-    NO_CHECK(b->ws.alloc((size_t)(edge_tiles(max_items + 1) + 2) * sizeof(int64_t)));
+    NO_CHECK(b->ws.alloc((size_t)(2 * edge_tiles(max_items + 1) + 4) * sizeof(int64_t)));      // two sets of status words
     NO_CHECK(b->ws_side.alloc((size_t)(edge_tiles(max_items + 1) + 2) * sizeof(int64_t)));
     NO_HIP_CHECK(hipStreamCreateWithFlags(&b->side, hipStreamNonBlocking));
     for (int32_t h = 0; h < n_layers; ++h) NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_fork[h], NO_SYNC_EVENT_FLAGS));
