@@ -3,13 +3,13 @@
 //
 // A row is cut into vector units of W bytes (the widest of 16/8/4/2 that the row size, strides and
 // base addresses allow). A group of G = min(64, pow2 >= units) lanes copies one row, so a wavefront
-// reads 64/G rows at once with fully coalesced 64*W-byte requests; ROWS rows per group are kept in
-// flight to cover HBM latency.
+// reads 64/G rows at once with fully coalesced 64*W-byte requests; ROWS rows per group and up to four
+// lane-group widths of each row are kept in flight to cover HBM latency.
 #include "common.hpp"
 
 namespace no {
 
-template <typename VecT, int ROWS>
+template <typename VecT, int ROWS, int UNR>
 __global__ void __launch_bounds__(256) gather_rows_kernel(const char* __restrict__ table, int64_t table_stride,
                                                           const int32_t* __restrict__ ids, const int32_t* d_n,
                                                           int32_t n_cap, char* __restrict__ out, int64_t out_stride,
@@ -31,14 +31,24 @@ __global__ void __launch_bounds__(256) gather_rows_kernel(const char* __restrict
             r[q] = base + (int64_t)q * rows_per_pass + sub;
             src[q] = (r[q] < n) ? table + (int64_t)ids[r[q]] * table_stride : nullptr;
         }
-        for (int32_t u = u0; u < units; u += g) {
-            VecT v[ROWS];
+        // UNR lane-group widths of every row are requested before the first store (a 2408-byte row in 8-byte units is
+        // five widths: one round trip per pass over ROWS rows instead of five)
+        for (int32_t ub = u0; ub < units; ub += g * UNR) {
+            VecT v[UNR][ROWS];
 #pragma unroll
-            for (int q = 0; q < ROWS; ++q)
-                if (src[q]) v[q] = *reinterpret_cast<const VecT*>(src[q] + (int64_t)u * sizeof(VecT));
+            for (int j = 0; j < UNR; ++j)
 #pragma unroll
-            for (int q = 0; q < ROWS; ++q)
-                if (src[q]) *reinterpret_cast<VecT*>(out + r[q] * out_stride + (int64_t)u * sizeof(VecT)) = v[q];
+                for (int q = 0; q < ROWS; ++q) {
+                    const int32_t u = ub + j * g;
+                    if (src[q] && u < units) v[j][q] = *reinterpret_cast<const VecT*>(src[q] + (int64_t)u * sizeof(VecT));
+                }
+#pragma unroll
+            for (int j = 0; j < UNR; ++j)
+#pragma unroll
+                for (int q = 0; q < ROWS; ++q) {
+                    const int32_t u = ub + j * g;
+                    if (src[q] && u < units) *reinterpret_cast<VecT*>(out + r[q] * out_stride + (int64_t)u * sizeof(VecT)) = v[j][q];
+                }
         }
     }
 }
@@ -56,8 +66,16 @@ static void launch_gather(const char* table, int64_t ts, const int32_t* ids, con
     const int64_t max_blocks = 256 * 16;
     if (blocks > max_blocks) blocks = max_blocks;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL((gather_rows_kernel<VecT, ROWS>), dim3((unsigned)blocks), dim3(256), 0, st, table, ts, ids, d_n, n_cap,
-                       out, os, units, g_log2);
+    const int32_t widths = (int32_t)ceil_div(units, 1 << g_log2);      // lane-group widths per row
+    if (widths > 2)
+        hipLaunchKernelGGL((gather_rows_kernel<VecT, ROWS, 4>), dim3((unsigned)blocks), dim3(256), 0, st, table, ts, ids, d_n,
+                           n_cap, out, os, units, g_log2);
+    else if (widths == 2)
+        hipLaunchKernelGGL((gather_rows_kernel<VecT, ROWS, 2>), dim3((unsigned)blocks), dim3(256), 0, st, table, ts, ids, d_n,
+                           n_cap, out, os, units, g_log2);
+    else
+        hipLaunchKernelGGL((gather_rows_kernel<VecT, ROWS, 1>), dim3((unsigned)blocks), dim3(256), 0, st, table, ts, ids, d_n,
+                           n_cap, out, os, units, g_log2);
 }
 
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
