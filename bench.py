@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--fanouts", default="",
                     help="comma-separated fanouts from the seeds down instead of the workload's (deeper models: the "
                          "paper repeats the last value, e.g. 25,10,5,5)")
+    ap.add_argument("--hot-fraction", type=float, default=-1.0,
+                    help="share of the vertices kept hot instead of the workload's (the hot-ratio sweep of Fig. 14: 0, 0.1, 0.3)")
+    ap.add_argument("--staleness", type=int, default=-1, help="staleness bound S instead of the workload's")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain copy of known size (1,000,000 rows x 1024 B through no_gather_features with "
                          "ids 0..n-1): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -119,9 +122,13 @@ def main():
         tfeat = dev(feat.view(np.int16) if bf16 else feat)
     tlab = dev(lab)
     ttrain = dev(train)
+    if args.hot_fraction >= 0.0 or args.staleness >= 0:
+        import dataclasses
+        w = dataclasses.replace(w, hot_fraction=args.hot_fraction if args.hot_fraction >= 0.0 else w.hot_fraction,
+                                staleness=args.staleness if args.staleness >= 0 else w.staleness)
     cache = None
     t_hot = 0.0
-    if not args.no_cache:
+    if not args.no_cache and w.hot_fraction > 0.0:
         t0 = time.time()
         pre = ttrain if args.presample_batches <= 0 else ttrain[: args.presample_batches * w.batch].contiguous()
         cache = b.no_select_hot(g, pre, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
@@ -295,7 +302,9 @@ def main():
     # recorded in profiles/dense_hbm_traffic.json for this workload; null for other workloads or kernels
     traffic_all = {}
     tpath = os.path.join(ROOT, "profiles", "dense_hbm_traffic.json")
-    if args.workload == "dense" and cache is not None and os.path.exists(tpath):
+    default_shape = (args.batch <= 0 and not args.fanouts and args.hot_fraction < 0.0 and args.staleness < 0 and
+                     args.arch == "sage")
+    if args.workload == "dense" and default_shape and cache is not None and os.path.exists(tpath):
         try:
             traffic_all = json.load(open(tpath)).get("bytes_per_launch", {})
         except Exception:
@@ -312,10 +321,16 @@ def main():
         "gather_frac_hbm_peak": round(kern["gather_rows_kernel"][1] / HBM_PEAK_GBPS, 4),
         "aggregate_GBps": round(kern["segment_rows_kernel(mean,l1)"][1], 2),
         "aggregate_frac_hbm_peak": round(kern["segment_rows_kernel(mean,l1)"][1] / HBM_PEAK_GBPS, 4),
+        # the same launch priced by the bytes it moved (rocprofv3 counters; a source row shared by several destinations
+        # is fetched again when it has left the L2), not by the compulsory bytes above
+        "aggregate_moved_GBps": (round(traffic_all["segment_rows_kernel(mean,l1)"] / 1e9 / (per_step["agg_l1"] / 1e3), 2)
+                                 if "segment_rows_kernel(mean,l1)" in traffic_all else None),
         "rows_gathered_per_step": round(n_src_bottom, 1),
         "gather_measurement": "no_gather_features alone on the %d source rows of the last step's bottom hop "
                               "(in the step the neighbour rows are read inside the aggregation)" % n_src_last,
         "cache_hit_rate": round(n_hit / max(n_v1, 1.0), 4),
+        "bytes_gathered_per_step": {"features": round(n_src_bottom * F * es, 1),
+                                    "embeddings": round(n_hit * w.dims[1] * 4 if L >= 2 else 0.0, 1)},
         "stage_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
         "profiled_ms_per_step": round(sum(v for k, v in per_step.items() if k != "gather"), 4),
         "host_enqueue_ms_per_step": round(enqueue_ms_per_step, 4),
