@@ -483,6 +483,16 @@ def test_deeper_models_four_and_five_layers(fanouts, arch, ahead):
     assert run_steps(w, 4, use_cache=True, lr=0.02, ahead=ahead, arch=arch) > 0
 
 
+@pytest.mark.parametrize("ahead", [False, True])
+def test_deepest_model_eight_layers(ahead):
+    """The largest number of layers the library takes (NO_MAX_LAYERS): seven upper layers hand their weight-gradient
+    work to the bottom layer's launches, which then carry all eight."""
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(3, 2, 2, 2, 2, 2, 2, 2), staleness=2, hot_fraction=0.2, batch=16,
+                            hidden=24)
+    assert run_steps(w, 3, use_cache=True, lr=0.02, ahead=ahead) > 0
+
+
 @pytest.mark.parametrize("hot_fraction,staleness", [(0.0, 2), (0.1, 0), (0.1, 2), (0.1, 4), (0.3, 2), (0.3, 4)])
 def test_hot_reuse_sweep_points(hot_fraction, staleness):
     """The hot-reuse sweep (hot fraction x staleness bound, the shape of the paper's Fig. 14 experiment) on a
