@@ -217,10 +217,11 @@ def test_gather_is_bit_copy(dim, dtype):
 
 # --------------------------------------------------------------------------------------- layers
 
-def layer_case(V, E, F, d_out, fanouts, B, seed, bf16=False):
-    src, dst = si.rmat_edges(V, E, seed)
+def layer_case(V, E, F, d_out, fanouts, B, seed, bf16=False, edges=None, seeds=None):
+    src, dst = edges if edges is not None else si.rmat_edges(V, E, seed)
     og = ora.build_csr(src, dst, V)
-    seeds = si.train_split(V, 0.65, seed)[:B]
+    if seeds is None:
+        seeds = si.train_split(V, 0.65, seed)[:B]
     sb = ora.sample_blocks(og, seeds, fanouts, seed, 0)
     blk = sb.blocks[-1]
     rng = np.random.default_rng(seed)
@@ -239,8 +240,28 @@ def layer_case(V, E, F, d_out, fanouts, B, seed, bf16=False):
                                                (6, 3, False, True), (40, 200, True, False), (70, 41, False, False),
                                                (256, 41, False, False), (200, 50, True, False)])
 def test_sage_layer_forward_backward(F, d_out, relu, bf16):
+    check_layer_forward_backward(layer_case(4000, 60_000, F, d_out, (7, 6), 300, 11, bf16), F, d_out, relu, bf16)
+
+
+def test_sage_layer_backward_with_a_popular_source():
+    """One source that every destination samples: its transposed segment has several hundred entries (more than the 64
+    indices a wavefront reads at a time, and a tail that is no multiple of 16), next to ordinary short segments."""
+    V = 700
+    hub = np.zeros(V - 1, np.int32)
+    v = np.arange(1, V, dtype=np.int32)
+    src = np.concatenate([hub, v - 1, (v % (V - 1)) + 1, ((v * 7) % (V - 1)) + 1]).astype(np.int32)
+    dst = np.concatenate([v, v, v, v]).astype(np.int32)
+    seeds = np.arange(1, 1 + 333, dtype=np.int32)
+    case = layer_case(V, 0, 256, 64, (6,), 333, 5, False, edges=(src, dst), seeds=seeds)
+    blk = case[0]
+    seg = np.diff(blk.csc_indptr)
+    assert seg.max() >= 300 and seg.max() % 16 != 0 and np.median(seg) <= 3
+    check_layer_forward_backward(case, 256, 64, True, False)
+
+
+def check_layer_forward_backward(case, F, d_out, relu, bf16):
     b = nb()
-    blk, x, xb, w_self, w_neigh, bias, rng = layer_case(4000, 60_000, F, d_out, (7, 6), 300, 11, bf16)
+    blk, x, xb, w_self, w_neigh, bias, rng = case
     n_dst, n_src, nnz = blk.n_dst, blk.n_src, blk.nnz
     cap_dst, cap_src = n_dst + 77, n_src + 130          # capacities larger than the actual sizes
     d_n_dst, d_n_src = dev(np.array([n_dst], np.int32)), dev(np.array([n_src], np.int32))
