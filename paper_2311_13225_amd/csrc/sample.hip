@@ -132,7 +132,16 @@ __device__ __forceinline__ int64_t slot_flags(const int32_t* __restrict__ nbr_pa
     return 1ll + ((map[u] == n_dst + (int32_t)q) ? (1ll << 32) : 0ll);    // low word: sampled; high word: first seen
 }
 
-__global__ void __launch_bounds__(ETHREADS) edge_tile_sums_kernel(const int32_t* __restrict__ nbr_pad, const int32_t* map,
+// (the two-launch form: the tile sums pass marks the first occurrences in the padded array itself, -2 - id in place of id,
+// so that the assignment pass reads its flags with the slots and does not wait for a second probe of the id map)
+__device__ __forceinline__ int64_t slot_flags_marked(const int32_t* __restrict__ nbr_pad, int64_t q, int32_t* u_out) {
+    const int32_t e = nbr_pad[q];
+    *u_out = e <= -2 ? -2 - e : e;
+    if (e == -1) return 0;
+    return 1ll + (e <= -2 ? (1ll << 32) : 0ll);
+}
+
+__global__ void __launch_bounds__(ETHREADS) edge_tile_sums_kernel(int32_t* __restrict__ nbr_pad, const int32_t* map,
                                                                   const int32_t* d_n_dst, int32_t k, int64_t* tile_sums,
                                                                   int32_t* zero_a, int32_t* zero_b, int32_t n_zero) {
     for (int64_t t = (int64_t)blockIdx.x * ETHREADS + threadIdx.x; t < n_zero; t += (int64_t)gridDim.x * ETHREADS) {
@@ -149,7 +158,11 @@ __global__ void __launch_bounds__(ETHREADS) edge_tile_sums_kernel(const int32_t*
 #pragma unroll
     for (int t = 0; t < EITEMS; ++t) {
         int32_t u;
-        if (q0 + t < n_pad) s += slot_flags(nbr_pad, map, q0 + t, n_dst, &u);
+        if (q0 + t < n_pad) {
+            const int64_t f = slot_flags(nbr_pad, map, q0 + t, n_dst, &u);
+            if (f >> 32) nbr_pad[q0 + t] = -2 - u;
+            s += f;
+        }
     }
     s = block_sum<int64_t, ETHREADS>(s, smem);
     if (threadIdx.x == 0) tile_sums[blockIdx.x] = s;
@@ -192,7 +205,7 @@ __global__ void __launch_bounds__(ETHREADS) edge_assign_kernel(const int32_t* __
     for (int t = 0; t < EITEMS; ++t) {
         f[t] = 0;
         u[t] = -1;
-        if (q0 + t < n_pad) f[t] = slot_flags(nbr_pad, map, q0 + t, n_dst, &u[t]);
+        if (q0 + t < n_pad) f[t] = slot_flags_marked(nbr_pad, q0 + t, &u[t]);
         s += f[t];
     }
     int64_t total;
@@ -698,7 +711,7 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     static const char* env_two_pass = getenv("NO_SCAN_TWO_PASS");
     const bool two_pass = env_two_pass ? atoi(env_two_pass) != 0 : b->scan_two_pass;
     if (two_pass) {
-        hipLaunchKernelGGL(edge_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p,
+        hipLaunchKernelGGL(edge_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, H.nbr_pad.p,
                            (const int32_t*)b->map.p, (const int32_t*)cnt, k, tile_sums, H.csc_cnt.p, H.csc_cur.p,
                            H.has_csc ? H.n_src_cap + 1 : 0);
         hipLaunchKernelGGL(edge_assign_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
