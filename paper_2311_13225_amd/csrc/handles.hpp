@@ -44,7 +44,7 @@ struct no_blocks_s {
     no::DevBuf<int32_t> tmp_a;          // unordered transpose fill [max nnz_cap with a transpose]
     no::DevBuf<char> ws;                // tile sums of the scans
     // bottom hop with a cache
-    no::DevBuf<int32_t> compute_list, compute_pos, hit_pos, hit_slot, probe_slot;
+    no::DevBuf<int32_t> compute_list, compute_pos, hit_pos, hit_slot, probe_slot, probe_ver;
     no::DevBuf<int32_t> refresh_slot;        // [n_compute]: cache slot a computed row refreshes (its vertex is hot), else -1
     no::DevBuf<int32_t> refresh_old;         // [n_compute]: the version that slot held before the split stamped it
     no_cache_s* stamped_cache = nullptr;     // the cache whose versions the last split stamped (NULL: none)
@@ -70,7 +70,7 @@ struct no_blocks_s {
         ws_side.release();
         for (auto& h : hop) h.release();
         counts.release(); seeds.release(); map.release(); tmp_a.release(); ws.release(); compute_list.release(); compute_pos.release(); hit_pos.release(); hit_slot.release();
-        probe_slot.release(); compute_inv.release(); refresh_slot.release(); refresh_old.release();
+        probe_slot.release(); probe_ver.release(); compute_inv.release(); refresh_slot.release(); refresh_old.release();
     }
 };
 

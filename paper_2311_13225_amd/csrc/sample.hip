@@ -417,6 +417,7 @@ struct CacheProbe {
 // sharing the launch keeps that pass off the dependency chain of the sampling.
 __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe, const int32_t* d_n_v1, int64_t* tile_sums,
                                                                 int32_t* __restrict__ probe_slot /* [n]: slot if served from the cache; -1 cold; -2 - slot if hot but to be computed */,
+                                                                int32_t* __restrict__ probe_ver /* [n]: the version the probe read (hot vertices) */,
                                                                 uint32_t v1_blocks, const int32_t* d_nnz,
                                                                 const int32_t* __restrict__ nbr, const int32_t* map,
                                                                 int32_t* __restrict__ indices, int32_t* csc_cnt) {
@@ -447,6 +448,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe
         if (i0 + t < n) {
             const int64_t f = probe.flags(slot[t], ver[t]);
             probe_slot[i0 + t] = (f & 1) ? (slot[t] >= 0 ? -2 - slot[t] : -1) : slot[t];
+            probe_ver[i0 + t] = ver[t];
             s += f;
         }
     }
@@ -457,6 +459,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_tile_sums_kernel(CacheProbe probe
 // Stable split of V^1 into rows to compute and rows served from the cache; re-keys the id map for
 // the bottom hop (computed vertex -> its index in the compute list, reusable vertex -> no entry).
 __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* __restrict__ v1, const int32_t* __restrict__ probe_slot,
+                                                                const int32_t* __restrict__ probe_ver,
                                                                 const int32_t* d_n_v1,
                                                                 const int64_t* __restrict__ tile_sums, int32_t* map,
                                                                 int32_t* compute_list, int32_t* compute_pos, int32_t* compute_inv,
@@ -489,14 +492,15 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
         tile_off = block_sum<int64_t, ETHREADS>(s, smem);
     }
     const int64_t i0 = base + (int64_t)threadIdx.x * EITEMS;
-    int32_t c[EITEMS], slot[EITEMS], vv[EITEMS];
+    int32_t c[EITEMS], slot[EITEMS], vv[EITEMS], pv[EITEMS];
     int64_t s = 0;
 #pragma unroll
     for (int t = 0; t < EITEMS; ++t) {
         c[t] = 0;
         slot[t] = -1;
         vv[t] = 0;
-        if (i0 + t < n) { slot[t] = probe_slot[i0 + t]; vv[t] = v1[i0 + t]; c[t] = slot[t] < 0 ? 1 : 0; }
+        pv[t] = -1;
+        if (i0 + t < n) { slot[t] = probe_slot[i0 + t]; vv[t] = v1[i0 + t]; pv[t] = probe_ver[i0 + t]; c[t] = slot[t] < 0 ? 1 : 0; }
         s += c[t];
     }
     int64_t total;
@@ -512,7 +516,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_partition_kernel(const int32_t* _
                 const int32_t rslot = slot[t] <= -2 ? -2 - slot[t] : -1;
                 refresh_slot[run] = rslot;
                 if (version && rslot >= 0) {
-                    refresh_old[run] = version[rslot];
+                    refresh_old[run] = pv[t];      // (what the probe read: nothing writes the versions in between)
                     version[rslot] = stamp;
                 }
                 compute_list[run] = v;
@@ -840,12 +844,12 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
                                    b->refresh_old.p, b->counts.p + 4 * b->n_layers + 5);
             } else {
             hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles + idx_blocks), dim3(ETHREADS), 0, st, probe, d_n, tile_sums,
-                               b->probe_slot.p, tiles, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2),
+                               b->probe_slot.p, b->probe_ver.p, tiles, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2),
                                (const int32_t*)P.nbr_global.p, (const int32_t*)b->map.p, P.indices.p,
                                P.has_csc ? P.csc_cnt.p : nullptr);
             indices_done[h - 1] = true;
             hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, d_dst,
-                               (const int32_t*)b->probe_slot.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
+                               (const int32_t*)b->probe_slot.p, (const int32_t*)b->probe_ver.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
                                b->hit_slot.p, extra, stamp_refresh ? cache->version.p : nullptr, (int32_t)step,
                                b->refresh_old.p);
             }
@@ -956,6 +960,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
         NO_CHECK(b->hit_pos.alloc(v1_cap));
         NO_CHECK(b->hit_slot.alloc(v1_cap));
         NO_CHECK(b->probe_slot.alloc(v1_cap));
+        NO_CHECK(b->probe_ver.alloc(v1_cap));
     }
     NO_HIP_CHECK(hipDeviceSynchronize());
     guard.b = nullptr;
