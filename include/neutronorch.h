@@ -34,7 +34,8 @@ enum {
     NO_ERR_CAPACITY = -3,      /* a handle or workspace is too small for the request */
     NO_ERR_OVERFLOW = -4,      /* 32-bit row pointers requested but E >= 2^31, or V >= 2^31 */
     NO_ERR_HIP = -5,           /* a HIP runtime call failed; see no_last_error() */
-    NO_ERR_UNSUPPORTED = -6
+    NO_ERR_UNSUPPORTED = -6,
+    NO_ERR_TIMEOUT = -7        /* a kernel's bounded wait on another workgroup expired; the outputs of that call are invalid */
 };
 
 typedef enum { NO_F32 = 0, NO_BF16 = 1 } no_dtype;
@@ -110,8 +111,8 @@ int32_t no_blocks_create(no_graph_t g, int32_t n_seeds_cap, const int32_t* h_fan
  * min(deg(v), fanouts[h]) distinct entries of its CSR row, uniformly without replacement, as a
  * pure function of (seed + step, domain 0, h, v, slot) through Philox4x32-10; the whole row in
  * stored order when deg <= fanout. The destinations of hop h+1 are the sources of hop h. Seed ids outside
- * [0, V) are read as vertex 0 and flagged (no_step_stats.bad_seed); the blocks are then meaningless but
- * every access stays inside the library's and the graph's arrays.
+ * [0, V) are read as vertex 0 and flagged (no_step_stats.bad_seed, status of no_blocks_sizes); the blocks are then
+ * meaningless but every access stays inside the library's and the graph's arrays.
  * With cache != NULL (and n_layers >= 2) the destinations of the bottom hop are only those
  * vertices of V^1 that cannot be served from the cache at `step` (not hot, empty slot, or
  * step - version > S). Asynchronous. */
@@ -120,7 +121,9 @@ int32_t no_sample_blocks(no_graph_t g, const int32_t* d_seeds, int32_t n_seeds, 
 
 int32_t no_blocks_view(no_blocks_t blocks, int32_t hop, no_block_view* out);
 /* Copies (n_dst, n_src, nnz, n_hit) of every hop to h_sizes[4*n_layers] (n_hit is 0 except at
- * the bottom hop with a cache). Synchronises the stream. */
+ * the bottom hop with a cache). Synchronises the stream. The sizes are written in every case; the status is
+ * NO_ERR_TIMEOUT if a scan of the last sampling call into these blocks gave up its bounded wait (the blocks are then
+ * invalid), else NO_ERR_OUT_OF_RANGE if that call met a seed id outside [0, V). */
 int32_t no_blocks_sizes(no_blocks_t blocks, void* stream, int32_t* h_sizes);
 int32_t no_blocks_destroy(no_blocks_t blocks);
 
@@ -132,7 +135,8 @@ int32_t no_blocks_destroy(no_blocks_t blocks);
  * for presample_epochs epochs every batch is sampled for hops 0..n_layers-2 (Philox domain 1,
  * stream seed + epoch*n_batches + b) and each vertex of the resulting V^1 counts once. The hot
  * set is the floor(hot_fraction * V) most frequent vertices, ties by ascending id; slot = rank.
- * Creates an empty cache [n_hot, emb_dim] fp32 (versions -1). Synchronises the stream. */
+ * Creates an empty cache [n_hot, emb_dim] fp32 (versions -1). Synchronises the stream. A train id outside [0, V)
+ * gives NO_ERR_OUT_OF_RANGE (it is never followed), an expired scan wait NO_ERR_TIMEOUT; no cache is returned then. */
 int32_t no_select_hot(no_graph_t g, const int32_t* d_train_ids, int64_t n_train, int32_t batch,
                       const int32_t* h_fanouts, int32_t n_layers, int32_t presample_epochs,
                       double hot_fraction, int32_t staleness, int32_t emb_dim, uint64_t seed,
@@ -238,7 +242,13 @@ typedef struct no_step_stats {
     int32_t n_hit;        /* rows of V^1 served from the cache */
     int32_t n_refresh;    /* computed rows written back to the cache */
     int32_t n_v1;         /* |V^1| */
-    int32_t bad_seed;     /* 1 if any seed id of this or an earlier step lay outside [0, V) (it was read as vertex 0) */
+    int32_t bad_seed;     /* 1 if a seed id of this step lay outside [0, V) (it was read as vertex 0) */
+    int32_t n_miss_hot;   /* hot vertices of V^1 that could not be served (empty or too old a row) and were computed */
+    int32_t n_cold;       /* vertices of V^1 outside the hot set: n_v1 = n_hit + n_miss_hot + n_cold */
+    int32_t scan_timeout; /* 1 if a scan of this step's sampling gave up its bounded wait: the step's results are invalid */
+    int32_t bad_label;    /* 1 if a seed's label lay outside [0, C) (that seed then adds nothing to loss and gradient) */
+    int64_t bytes_gathered_features;    /* feature rows the step collected: n_src of the bottom hop x row bytes */
+    int64_t bytes_gathered_embeddings;  /* cached layer-1 rows it pulled instead: n_hit x hidden x 4 */
 } no_step_stats;
 
 /* dims = [F, hidden.., C] (n_layers+1 entries). Weights live inside the handle; the caller
@@ -269,7 +279,8 @@ int32_t no_model_gathered(no_model_t m, const void** d_x0);
  * seeds, backward (reused rows take no gradient), W <- W - lr * grad for every tensor; every computed
  * hot vertex's layer-1 row (made by the pre-update weights) is stored in the cache with version = step.
  * d_stats (device, may be NULL) receives the statistics; if h_stats != NULL the stream is
- * synchronised and the statistics are copied to the host. */
+ * synchronised and the statistics are copied to the host, and the call returns NO_ERR_TIMEOUT if they say that a
+ * scan's wait expired (h_stats is filled all the same). */
 int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
                       const int32_t* d_seeds, int32_t n_seeds, no_cache_t cache, int64_t step,
                       uint64_t seed, float lr, no_step_stats* d_stats, no_step_stats* h_stats, void* stream);
@@ -286,8 +297,9 @@ int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const 
  * Cache versions: the split of a batch into reused and computed vertices writes the batch's step into the version
  * of every slot the batch will recompute (the row follows when its layer 1 runs), so while a batch is prepared
  * ahead those entries of no_cache_view already read step + 1; a dropped batch's entries are restored by the call
- * that drops it. Do not commit a bulk refresh, invalidate the cache or change its bound between the two calls (the
- * prepared batch was split against the cache as it stood).
+ * that drops it. A bulk-refresh commit, an invalidate or a change of the bound between the two calls also drops the
+ * prepared batch (it was split against the cache as it stood; nothing is restored where all versions were replaced),
+ * and the batch is sampled again.
  * commit_refresh_before_next != 0: a pending bulk refresh (no_refresh_hot_begin) is committed after this step's
  * last use of the cache and before the next batch is sampled (which then starts after this step's layer 1); use it
  * on the last step of a super-batch instead of calling no_refresh_hot_commit between the two steps. The first
@@ -330,6 +342,12 @@ enum {
     NO_STAGE_COUNT = 11
 };
 int32_t no_model_profile(no_model_t m, int32_t enable);   /* enabling resets the accumulators */
+/* Test aid for the error path of the single-pass scans (edge compaction and V^1 split in one launch): their blocks
+ * wait, for at most spin_limit polls, on the status word of an earlier tile. spin_limit > 0 replaces the limit
+ * (default 2^20; 0 restores it); withhold_first_tile != 0 makes tile 0 keep its word back, so that with two or more
+ * tiles the wait of tile 1 is certain to expire. Every kernel still runs to its end; the call's results are wrong and
+ * flagged (no_step_stats.scan_timeout, NO_ERR_TIMEOUT). Process-wide; for callers that test that path only. */
+int32_t no_debug_scan_wait(int32_t spin_limit, int32_t withhold_first_tile);
 /* h_total_ms[NO_STAGE_COUNT]: summed milliseconds per stage; *h_steps: steps accumulated. */
 int32_t no_model_stage_ms(no_model_t m, double* h_total_ms, int32_t* h_steps);
 const char* no_stage_name(int32_t stage);

@@ -22,7 +22,7 @@ NO_ARCH_SAGE_MEAN, NO_ARCH_GCN = 0, 1
 NO_CSR_INPUT_ON_DEVICE = 1
 NO_MAX_LAYERS = 8
 ERROR_NAMES = {0: "NO_OK", -1: "NO_ERR_INVALID_ARG", -2: "NO_ERR_OUT_OF_RANGE", -3: "NO_ERR_CAPACITY",
-               -4: "NO_ERR_OVERFLOW", -5: "NO_ERR_HIP", -6: "NO_ERR_UNSUPPORTED"}
+               -4: "NO_ERR_OVERFLOW", -5: "NO_ERR_HIP", -6: "NO_ERR_UNSUPPORTED", -7: "NO_ERR_TIMEOUT"}
 
 
 class NoError(RuntimeError):
@@ -44,7 +44,9 @@ class no_block_view(C.Structure):
 class no_step_stats(C.Structure):
     _fields_ = [("loss", C.c_float), ("n_dst", C.c_int32 * NO_MAX_LAYERS), ("n_src", C.c_int32 * NO_MAX_LAYERS),
                 ("nnz", C.c_int32 * NO_MAX_LAYERS), ("n_hit", C.c_int32), ("n_refresh", C.c_int32),
-                ("n_v1", C.c_int32), ("bad_seed", C.c_int32)]
+                ("n_v1", C.c_int32), ("bad_seed", C.c_int32), ("n_miss_hot", C.c_int32), ("n_cold", C.c_int32),
+                ("scan_timeout", C.c_int32), ("bad_label", C.c_int32), ("bytes_gathered_features", C.c_int64),
+                ("bytes_gathered_embeddings", C.c_int64)]
 
 
 _lib = None
@@ -88,6 +90,7 @@ _SIGNATURES = {
     "no_model_profile": (_I32, [_P, _I32]),
     "no_model_stage_ms": (_I32, [_P, _P, _P]),
     "no_stage_name": (C.c_char_p, [_I32]),
+    "no_debug_scan_wait": (_I32, [_I32, _I32]),
 }
 NO_STAGE_COUNT = 11
 EXPORTS = sorted(_SIGNATURES)
@@ -108,9 +111,11 @@ def lib():
     return _lib
 
 
-def _check(code: int):
+def _check(code: int, stats=None):
     if code != 0:
-        raise NoError(code, lib().no_last_error().decode())
+        e = NoError(code, lib().no_last_error().decode())
+        e.stats = stats          # a step that fails after its statistics were copied back still hands them over
+        raise e
 
 
 def _stream(stream=None) -> int:
@@ -472,7 +477,7 @@ def no_train_step(m: Model, g: Graph, features: torch.Tensor, labels: torch.Tens
     hs = no_step_stats() if want_stats else None
     _check(lib().no_train_step(m.h, g.h, features.data_ptr(), labels.data_ptr(), seeds.data_ptr(), seeds.numel(),
                                cache.h if cache is not None else None, step, seed & 0xFFFFFFFFFFFFFFFF, lr, None,
-                               C.byref(hs) if want_stats else None, _stream(stream)))
+                               C.byref(hs) if want_stats else None, _stream(stream)), hs)
     return hs
 
 
@@ -492,7 +497,7 @@ def no_train_step_ahead(m: Model, g: Graph, features: torch.Tensor, labels: torc
                                      0 if next_seeds is None else next_seeds.numel(),
                                      1 if commit_refresh_before_next else 0,
                                      cache.h if cache is not None else None, step, seed & 0xFFFFFFFFFFFFFFFF, lr, None,
-                                     C.byref(hs) if want_stats else None, _stream(stream)))
+                                     C.byref(hs) if want_stats else None, _stream(stream)), hs)
     return hs
 
 
@@ -515,3 +520,8 @@ def no_model_stage_ms(m: Model) -> Tuple[dict, int]:
     steps = C.c_int32()
     _check(lib().no_model_stage_ms(m.h, ms, C.byref(steps)))
     return {lib().no_stage_name(i).decode(): float(ms[i]) for i in range(NO_STAGE_COUNT)}, steps.value
+
+
+def no_debug_scan_wait(spin_limit: int = 0, withhold_first_tile: bool = False):
+    """Test aid: spin limit of the single-pass scans' bounded waits (0 = default) and whether tile 0 withholds its word."""
+    _check(lib().no_debug_scan_wait(spin_limit, 1 if withhold_first_tile else 0))

@@ -795,7 +795,13 @@ __device__ void write_step_stats(const StatsJob& j) {
         stats->n_hit = j.used_cache ? counts[4 * n_layers + 1] : 0;
         stats->n_refresh = j.used_cache ? counts[4 * n_layers + 4] : 0;
         stats->n_v1 = n_layers >= 2 ? counts[4 * (n_layers - 2) + 1] : counts[0];
-        stats->bad_seed = counts[4 * n_layers + 5];
+        stats->bad_seed = counts[4 * n_layers + 5] == j.call_id ? 1 : 0;
+        stats->scan_timeout = counts[4 * n_layers + 6] == j.call_id ? 1 : 0;
+        stats->bad_label = counts[4 * n_layers + 7] == j.call_id ? 1 : 0;
+        stats->n_miss_hot = stats->n_refresh;      // every computed hot vertex refreshes its slot
+        stats->n_cold = stats->n_v1 - stats->n_hit - stats->n_miss_hot;
+        stats->bytes_gathered_features = (int64_t)counts[4 * (n_layers - 1) + 1] * j.feat_row_bytes;
+        stats->bytes_gathered_embeddings = (int64_t)stats->n_hit * j.emb_row_bytes;
     }
 }
 

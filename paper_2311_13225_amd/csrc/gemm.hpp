@@ -44,6 +44,8 @@ struct GemmTNArgs {
 struct StatsJob {
     const float* row_loss = nullptr; int32_t n = 0;
     const int32_t* counts = nullptr; int32_t n_layers = 0; int32_t used_cache = 0;
+    int32_t call_id = 0;                  // a flag word of `counts` is raised iff it holds this value
+    int32_t feat_row_bytes = 0, emb_row_bytes = 0;
     no_step_stats* stats = nullptr;       // NULL: no job
 };
 

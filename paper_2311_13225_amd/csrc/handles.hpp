@@ -37,8 +37,12 @@ struct no_blocks_s {
     int64_t n_vertices = 0;
     bool build_csc = true;             // transpose hops 0..L-2 (select_hot's private blocks skip it)
     no::HopBuffers hop[NO_MAX_LAYERS];
-    // counts[4*h + {0,1,2}] = n_dst, n_src, nnz of hop h; counts[4*L + {0,1,4,5}] = n_compute, n_hit, n_refresh, bad-seed flag
+    // counts[4*h + {0,1,2}] = n_dst, n_src, nnz of hop h; counts[4*L + {0,1,4}] = n_compute, n_hit, n_refresh;
+    // counts[4*L + {5,6,7}] = flag words (bad seed id, a scan's bounded wait expired, bad label): a kernel that meets
+    // the condition stores the id of the sampling call it works for, so a word counts only while it equals call_id
+    // and never has to be cleared
     no::DevBuf<int32_t> counts;
+    int32_t call_id = 0;               // id of the last sampling call into these blocks (1, 2, ...; never 0)
     no::DevBuf<int32_t> seeds;          // copy of the seed ids (hop 0 destinations)
     no::DevBuf<int32_t> map;            // vertex -> local id, EMPTY between calls, [V]
     no::DevBuf<int32_t> tmp_a;          // unordered transpose fill [max nnz_cap with a transpose]
@@ -48,6 +52,8 @@ struct no_blocks_s {
     no::DevBuf<int32_t> refresh_slot;        // [n_compute]: cache slot a computed row refreshes (its vertex is hot), else -1
     no::DevBuf<int32_t> refresh_old;         // [n_compute]: the version that slot held before the split stamped it
     no_cache_s* stamped_cache = nullptr;     // the cache whose versions the last split stamped (NULL: none)
+    uint64_t stamped_uid = 0;                // ... its identity and the state of its contents when they were stamped
+    uint64_t stamped_contents = 0;
     bool scan_two_pass = false;              // the edge compaction of the next sampling call: two launches instead of one
     no::DevBuf<int32_t> compute_inv;         // [|V^1|]: index in the compute list of position i of V^1, -1 if served from the cache
     bool last_used_cache = false;
@@ -109,6 +115,10 @@ struct no_cache_s {
     int32_t emb_dim = 0;
     no::DevBuf<int32_t> hot_ids, slot_of_vertex, version, freq;
     no::DevBuf<float> emb;
+    // identity and change counters: a batch split ahead of time is only valid against the cache as it stood
+    uint64_t uid = 0;                  // unique per cache ever created (an address may be reused after a destroy)
+    uint64_t generation = 0;           // bumped by a refresh commit, an invalidate and a change of the bound
+    uint64_t contents = 0;             // bumped by a refresh commit and an invalidate (all versions replaced)
     RefreshState* refresh = nullptr;
     void release() {
         if (refresh) { refresh->release(); delete refresh; refresh = nullptr; }
@@ -131,6 +141,9 @@ int32_t blocks_join(no_blocks_s* b, hipStream_t st);
 // stamp_refresh: the split writes `step` into the version of every cache slot the batch will recompute (training
 // calls; the row follows with the layer-1 product). blocks_unstamp takes the stamps back for a batch that is dropped.
 int32_t blocks_unstamp(no_blocks_s* b, hipStream_t st);
+// Test aid (no_debug_scan_wait): spin limit of the single-pass scans' bounded waits, and whether tile 0 withholds its word.
+struct ScanWaitDebug { int32_t spin_limit; int32_t withhold_first_tile; };
+ScanWaitDebug scan_wait_debug();
 // Caches handed out and not yet destroyed: a dropped batch's stamps are only taken back from a cache that still exists.
 void cache_register(no_cache_s* c);
 void cache_unregister(no_cache_s* c);

@@ -10,10 +10,15 @@
 
 namespace no {
 
-__global__ void count_members_kernel(const int32_t* ids, const int32_t* d_n, int32_t n_fixed, int32_t* freq) {
+// n_vertices > 0: the ids come straight from the caller; one outside [0, V) is not counted and raises *bad_flag
+__global__ void count_members_kernel(const int32_t* ids, const int32_t* d_n, int32_t n_fixed, int32_t* freq,
+                                     int32_t n_vertices, int32_t* bad_flag) {
     int32_t n = d_n ? *d_n : n_fixed;
     int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) atomicAdd(&freq[ids[i]], 1);       // integer count: order independent
+    if (i >= n) return;
+    const int32_t v = ids[i];
+    if (n_vertices > 0 && (uint32_t)v >= (uint32_t)n_vertices) { *bad_flag = 1; return; }
+    atomicAdd(&freq[v], 1);       // integer count: order independent
 }
 
 __global__ void hot_keys_kernel(const int32_t* freq, int64_t n, uint32_t max_count, uint32_t* keys, uint32_t* ids) {
@@ -34,7 +39,8 @@ using namespace no;
 namespace no {
 static std::mutex g_cache_mutex;
 static std::unordered_set<no_cache_s*> g_live_caches;
-void cache_register(no_cache_s* c) { std::lock_guard<std::mutex> l(g_cache_mutex); g_live_caches.insert(c); }
+static uint64_t g_next_cache_uid = 1;
+void cache_register(no_cache_s* c) { std::lock_guard<std::mutex> l(g_cache_mutex); c->uid = g_next_cache_uid++; g_live_caches.insert(c); }
 void cache_unregister(no_cache_s* c) { std::lock_guard<std::mutex> l(g_cache_mutex); g_live_caches.erase(c); }
 bool cache_is_live(no_cache_s* c) { std::lock_guard<std::mutex> l(g_cache_mutex); return g_live_caches.count(c) != 0; }
 }  // namespace no
@@ -82,6 +88,10 @@ extern "C" int32_t no_select_hot(no_graph_t g, const int32_t* d_train_ids, int64
     no_blocks_s* b = nullptr;
     if (n_layers >= 2) NO_CHECK(blocks_create_impl(g, batch, h_fanouts, n_layers - 1, false, &b));
     struct BGuard { no_blocks_s* b; ~BGuard() { if (b) { b->release(); delete b; } } } bguard{b};
+    DevBuf<int32_t> bad_flag;          // single-layer models: an id outside [0, V) among the train ids
+    struct FGuard { DevBuf<int32_t>* f; ~FGuard() { f->release(); } } fguard{&bad_flag};
+    NO_CHECK(bad_flag.alloc(1));
+    NO_CHECK(fill_i32(bad_flag.p, 0, 1, st));
     for (int32_t p = 0; p < presample_epochs; ++p)
         for (int64_t bi = 0; bi < nb; ++bi) {
             const int64_t lo = bi * batch;
@@ -92,10 +102,10 @@ extern "C" int32_t no_select_hot(no_graph_t g, const int32_t* d_train_ids, int64
                 const HopBuffers& H = b->hop[n_layers - 2];
                 hipLaunchKernelGGL(count_members_kernel, dim3((unsigned)ceil_div(H.n_src_cap, 256)), dim3(256), 0, st,
                                    (const int32_t*)H.src_global.p, (const int32_t*)(b->counts.p + 4 * (n_layers - 2) + 1), 0,
-                                   c->freq.p);
+                                   c->freq.p, 0, (int32_t*)nullptr);
             } else {
                 hipLaunchKernelGGL(count_members_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st,
-                                   d_train_ids + lo, (const int32_t*)nullptr, n, c->freq.p);
+                                   d_train_ids + lo, (const int32_t*)nullptr, n, c->freq.p, (int32_t)V, bad_flag.p);
             }
         }
     NO_CHECK(launch_status("presample"));
@@ -123,6 +133,14 @@ extern "C" int32_t no_select_hot(no_graph_t g, const int32_t* d_train_ids, int64
         NO_HIP_CHECK(hipStreamSynchronize(st));
     }
     NO_HIP_CHECK(hipStreamSynchronize(st));
+    {
+        // the private blocks start with zeroed flag words, so anything in them was raised by one of the batches above
+        int32_t flags[4] = {0, 0, 0, 0};
+        if (b) NO_HIP_CHECK(hipMemcpy(flags, b->counts.p + 4 * (n_layers - 1) + 5, 2 * sizeof(int32_t), hipMemcpyDeviceToHost));
+        NO_HIP_CHECK(hipMemcpy(flags + 2, bad_flag.p, sizeof(int32_t), hipMemcpyDeviceToHost));
+        NO_REQUIRE(flags[1] == 0, NO_ERR_TIMEOUT, "no_select_hot: a scan gave up waiting for an earlier tile");
+        NO_REQUIRE(flags[0] == 0 && flags[2] == 0, NO_ERR_OUT_OF_RANGE, "no_select_hot: a train id lies outside [0, V)");
+    }
     guard.c = nullptr;
     no::cache_register(c);
     *out = c;
@@ -150,12 +168,15 @@ extern "C" int32_t no_cache_set_staleness(no_cache_t c, int32_t staleness) {
     NO_REQUIRE(c != nullptr, NO_ERR_INVALID_ARG, "no_cache_set_staleness: cache is NULL");
     NO_REQUIRE(staleness >= 0, NO_ERR_INVALID_ARG, "no_cache_set_staleness: staleness must be >= 0");
     c->staleness = staleness;
+    ++c->generation;
     return NO_OK;
 }
 
 extern "C" int32_t no_cache_invalidate(no_cache_t c, void* stream) {
     clear_error();
     NO_REQUIRE(c != nullptr, NO_ERR_INVALID_ARG, "no_cache_invalidate: cache is NULL");
+    ++c->generation;
+    ++c->contents;
     return fill_i32(c->version.p, -1, c->n_hot, (hipStream_t)stream);
 }
 

@@ -108,6 +108,8 @@ int32_t refresh_commit_impl(no_cache_s* c, hipStream_t st) {
     std::swap(r->snap.p, r->snap_cur.p);
     r->have_cur = true;
     r->pending = false;
+    ++c->generation;      // a batch split against the previous rows is no longer the batch a step would sample now
+    ++c->contents;
     return NO_OK;
 }
 }  // namespace no

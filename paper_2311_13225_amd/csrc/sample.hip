@@ -51,7 +51,7 @@ __global__ void __launch_bounds__(256) sample_rows_kernel(const RowT* __restrict
                                                           uint32_t key1, uint32_t c3, int32_t* __restrict__ nbr_pad,
                                                           int32_t* __restrict__ src_global, int32_t* map,
                                                           int32_t insert_dst, int32_t* seeds_copy, int32_t* count_out,
-                                                          int32_t n_vertices, int32_t* bad_id_flag,
+                                                          int32_t n_vertices, int32_t* bad_id_flag, int32_t flag_value,
                                                           unsigned long long* scan_status, int32_t n_status) {
     // the tile status words of the scan that follows this launch start out empty
     for (int32_t t = (int32_t)(blockIdx.x * 256 + threadIdx.x); t < n_status; t += (int32_t)(gridDim.x * 256)) scan_status[t] = 0ull;
@@ -68,7 +68,7 @@ __global__ void __launch_bounds__(256) sample_rows_kernel(const RowT* __restrict
         if (insert_dst && (uint32_t)v >= (uint32_t)n_vertices) {
             // a caller-supplied seed outside [0, V): stay inside the graph's arrays and report it
             v = 0;
-            *bad_id_flag = 1;
+            *bad_id_flag = flag_value;
         }
         begin = (int64_t)rowptr[v];
         d = (int64_t)rowptr[v + 1] - begin;
@@ -237,7 +237,8 @@ __global__ void __launch_bounds__(ETHREADS) edge_assign_kernel(const int32_t* __
 // die in turn: an earlier tile is done, running, or the next to start on its die, and a waiting block never holds
 // the slot an earlier tile needs.) A word packs both 31-bit counts and a 2-bit state, so it is written and read by one
 // 64-bit access at device scope and needs no fence; the words are emptied by the sampling launch before. The wait on
-// an earlier tile is bounded: on expiry the block reports through `fail_flag` and goes on (wrong output, no hang).
+// an earlier tile is bounded: on expiry the block stores the call's id in `fail_flag` and goes on (wrong output, no hang;
+// the host reports NO_ERR_TIMEOUT wherever it next reads the blocks' counts).
 constexpr unsigned long long SCAN_SUM = 1ull, SCAN_PREFIX = 2ull;
 __device__ __forceinline__ unsigned long long scan_pack(int64_t v, unsigned long long state) {
     return ((unsigned long long)(v & 0x7fffffffll)) | ((unsigned long long)((v >> 32) & 0x7fffffffll) << 31) | (state << 62);
@@ -252,9 +253,12 @@ __global__ void __launch_bounds__(ETHREADS) edge_scan_kernel(const int32_t* __re
                                                              int32_t* __restrict__ nbr, int32_t* __restrict__ edge_row,
                                                              int32_t* __restrict__ src_global,
                                                              int32_t* counts /* [0]=n_dst (in), [1]=n_src, [2]=nnz */,
-                                                             int32_t* zero_a, int32_t* zero_b, int32_t n_zero, int32_t* fail_flag) {
+                                                             int32_t* zero_a, int32_t* zero_b, int32_t n_zero, int32_t* fail_flag,
+                                                             int32_t flag_value, int32_t spin_limit, int32_t withhold_first,
+                                                             unsigned int* done) {
     __shared__ int64_t smem[ETHREADS / 64 + 1];
     __shared__ int64_t prefix_sh;
+    __shared__ int cleanup_sh;
     for (int64_t t = (int64_t)blockIdx.x * ETHREADS + threadIdx.x; t < n_zero; t += (int64_t)gridDim.x * ETHREADS) {
         zero_a[t] = 0;
         zero_b[t] = 0;
@@ -306,12 +310,17 @@ __global__ void __launch_bounds__(ETHREADS) edge_scan_kernel(const int32_t* __re
                 first -= take;
                 if (p_at < n_ok) break;                                       // reached an inclusive prefix
                 if (take == 0) {
-                    if (++spins > (1 << 20)) { if (lane == 0) *fail_flag = 2; break; }
+                    if (++spins > spin_limit) {
+                        if (lane == 0) __hip_atomic_store(fail_flag, flag_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
                     __builtin_amdgcn_s_sleep(1);
                 }
             }
         }
         if (lane == 0) {
+            // (withhold_first: test aid; tile 0 keeps its word back, so the tile after it must give up its wait)
+            if (!(withhold_first && blockIdx.x == 0))
             __hip_atomic_store(&status[blockIdx.x], scan_pack(prefix + total, SCAN_PREFIX), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
             prefix_sh = prefix;
@@ -344,6 +353,24 @@ __global__ void __launch_bounds__(ETHREADS) edge_scan_kernel(const int32_t* __re
             }
             run += f[t];
         }
+    }
+    // A wait that expired leaves wrong prefixes behind, and kernels after this one would follow them out of their
+    // arrays. The tile that finishes last therefore checks the flag and, if it is raised, turns the hop into a
+    // consistent empty block: no edges, no new sources, and no entry of this hop left in the id map.
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int n_tiles = (unsigned int)((n_pad + ETILE - 1) / ETILE);
+        const bool last = __hip_atomic_fetch_add(done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == n_tiles - 1;
+        cleanup_sh = last && __hip_atomic_load(fail_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == flag_value;
+    }
+    __syncthreads();
+    if (cleanup_sh) {
+        for (int64_t q = threadIdx.x; q < n_pad; q += ETHREADS) {
+            const int32_t v = nbr_pad[q];
+            if (v >= 0 && map[v] >= n_dst) map[v] = EMPTY;      // (entries below n_dst belong to the destinations)
+        }
+        for (int32_t r = (int32_t)threadIdx.x; r <= n_dst; r += ETHREADS) indptr[r] = 0;
+        if (threadIdx.x == 0) { counts[1] = n_dst; counts[2] = 0; }
     }
 }
 
@@ -549,7 +576,10 @@ __global__ void __launch_bounds__(ETHREADS) v1_split_kernel(CacheProbe probe, co
                                                             int32_t* hit_pos, int32_t* hit_slot,
                                                             int32_t* extra /* n_compute, n_hit, -, -, n_refresh */,
                                                             int32_t* version, int32_t stamp, int32_t* refresh_old,
-                                                            int32_t* fail_flag) {
+                                                            int32_t* fail_flag, int32_t flag_value, int32_t spin_limit,
+                                                            int32_t withhold_first, unsigned int* done, int32_t csc_len,
+                                                            int32_t* above_nnz, int32_t* above_indptr,
+                                                            const int32_t* above_n_dst) {
     if (blockIdx.x < idx_blocks) {
         const int64_t e = (int64_t)blockIdx.x * ETHREADS + threadIdx.x;
         const int32_t nnz = *d_nnz;
@@ -557,7 +587,8 @@ __global__ void __launch_bounds__(ETHREADS) v1_split_kernel(CacheProbe probe, co
         if (e < nnz) {
             const int32_t local = map[nbr[e]];
             indices[e] = local;
-            if (csc_cnt) atomicAdd(&csc_cnt[local], 1);     // integer count: order independent
+            // (the range check only matters after an expired wait, when the split may have re-keyed the map already)
+            if (csc_cnt && (uint32_t)local < (uint32_t)csc_len) atomicAdd(&csc_cnt[local], 1);     // integer count: order independent
         }
         __syncthreads();      // every map read of the block has returned (its value went into a store)
         if (threadIdx.x == 0) __hip_atomic_fetch_add(idx_done, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
@@ -566,6 +597,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_split_kernel(CacheProbe probe, co
     const uint32_t tile = blockIdx.x - idx_blocks;
     __shared__ int64_t smem[ETHREADS / 64 + 1];
     __shared__ int64_t prefix_sh;
+    __shared__ int cleanup_sh;
     const int64_t n = *d_n_v1;
     const int64_t base = (int64_t)tile * ETILE;
     if (base >= n) return;
@@ -611,12 +643,16 @@ __global__ void __launch_bounds__(ETHREADS) v1_split_kernel(CacheProbe probe, co
                 first -= take;
                 if (p_at < n_ok) break;
                 if (take == 0) {
-                    if (++spins > (1 << 20)) { if (lane == 0) *fail_flag = 2; break; }
+                    if (++spins > spin_limit) {
+                        if (lane == 0) __hip_atomic_store(fail_flag, flag_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
                     __builtin_amdgcn_s_sleep(1);
                 }
             }
         }
         if (lane == 0) {
+            if (!(withhold_first && tile == 0))
             __hip_atomic_store(&status[tile], scan_pack(prefix + total, SCAN_PREFIX), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
             prefix_sh = prefix;
@@ -634,7 +670,7 @@ __global__ void __launch_bounds__(ETHREADS) v1_split_kernel(CacheProbe probe, co
         const unsigned int expected = (unsigned int)((nnz + ETHREADS - 1) / ETHREADS);
         int spins = 0;
         while (__hip_atomic_load(idx_done, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < expected) {
-            if (++spins > (1 << 20)) { *fail_flag = 2; break; }
+            if (++spins > spin_limit) { __hip_atomic_store(fail_flag, flag_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
             __builtin_amdgcn_s_sleep(1);
         }
     }
@@ -665,6 +701,23 @@ __global__ void __launch_bounds__(ETHREADS) v1_split_kernel(CacheProbe probe, co
             }
             run += c;
         }
+    }
+    // After an expired wait the split (and possibly the local indices of the hop above, if the map was re-keyed under
+    // their readers) cannot be trusted. The tile that finishes last then leaves a consistent state that no later
+    // kernel can follow out of its arrays: nothing to compute, nothing reused, no edges in the hop above, and no
+    // entry of V^1 left in the id map. (Versions already stamped stay stamped: the caller is told to invalidate.)
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int n_tiles = (unsigned int)((n + ETILE - 1) / ETILE);
+        const bool last = __hip_atomic_fetch_add(done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == n_tiles - 1;
+        cleanup_sh = last && __hip_atomic_load(fail_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == flag_value;
+    }
+    __syncthreads();
+    if (cleanup_sh) {
+        for (int64_t i = threadIdx.x; i < n; i += ETHREADS) map[probe.v1[i]] = EMPTY;
+        const int32_t nd = *above_n_dst;
+        for (int32_t r = (int32_t)threadIdx.x; r <= nd; r += ETHREADS) above_indptr[r] = 0;
+        if (threadIdx.x == 0) { extra[0] = 0; extra[1] = 0; extra[4] = 0; *above_nnz = 0; }
     }
 }
 
@@ -701,7 +754,8 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     hipLaunchKernelGGL((sample_rows_kernel<G, RowT>), dim3((unsigned)ceil_div(H.n_dst_cap, 256 / G)), dim3(256), 0, st,    \
                        rowptr, col, d_dst, d_n_dst_in, n_fixed, H.n_dst_cap, k, key0, key1, c3, H.nbr_pad.p,               \
                        H.src_global.p, b->map.p, insert_dst ? 1 : 0, seeds_copy, cnt, (int32_t)b->n_vertices,               \
-                       b->counts.p + 4 * b->n_layers + 5, (unsigned long long*)b->ws.p, (int32_t)edge_tiles(H.nnz_cap) + extra_status)
+                       b->counts.p + 4 * b->n_layers + 5, b->call_id, (unsigned long long*)b->ws.p,                          \
+                       (int32_t)edge_tiles(H.nnz_cap) + 1 + extra_status)
     if (k <= 8) NO_LAUNCH_SAMPLE(8);
     else if (k <= 16) NO_LAUNCH_SAMPLE(16);
     else if (k <= 32) NO_LAUNCH_SAMPLE(32);
@@ -714,6 +768,7 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     // measured slower than two short launches. NO_SCAN_TWO_PASS=<0|1> forces either form (tuning aid).
     static const char* env_two_pass = getenv("NO_SCAN_TWO_PASS");
     const bool two_pass = env_two_pass ? atoi(env_two_pass) != 0 : b->scan_two_pass;
+    const ScanWaitDebug dbg = scan_wait_debug();
     if (two_pass) {
         hipLaunchKernelGGL(edge_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, H.nbr_pad.p,
                            (const int32_t*)b->map.p, (const int32_t*)cnt, k, tile_sums, H.csc_cnt.p, H.csc_cur.p,
@@ -725,7 +780,8 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
         hipLaunchKernelGGL(edge_scan_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
                            (const int32_t*)cnt, k, k_magic, (unsigned long long*)b->ws.p, H.indptr.p, H.nbr_global.p,
                            H.edge_row.p, H.src_global.p, cnt, H.csc_cnt.p, H.csc_cur.p, H.has_csc ? H.n_src_cap + 1 : 0,
-                           b->counts.p + 4 * b->n_layers + 5);
+                           b->counts.p + 4 * b->n_layers + 6, b->call_id, dbg.spin_limit, dbg.withhold_first_tile,
+                           (unsigned int*)((unsigned long long*)b->ws.p + tiles));
     }
     if (indices_now)
         hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st,
@@ -816,6 +872,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
                            const SideGather* gather, bool inline_side, bool stamp_refresh) {
     NO_CHECK(blocks_join(b, st));      // a previous call that was never joined
     b->stamped_cache = nullptr;
+    b->call_id = b->call_id % 0x3fffffff + 1;      // flag words written by this call's kernels carry this value
     const int32_t L = b->n_layers;
     int32_t* extra = b->counts.p + 4 * L;     // n_compute, n_hit, -, -, n_refresh
     const uint32_t key0 = (uint32_t)stream_key, key1 = (uint32_t)(stream_key >> 32);
@@ -834,14 +891,18 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
             const unsigned idx_blocks = (unsigned)ceil_div(P.nnz_cap, ETHREADS);
             int64_t* tile_sums = (int64_t*)b->ws.p;
             if (v1_one_launch(b, tiles)) {
+                const ScanWaitDebug dbg = scan_wait_debug();
                 // (status words and the counter behind them: emptied by the sampling launch of hop L-2, past its own)
-                unsigned long long* v1_status = (unsigned long long*)b->ws.p + edge_tiles(P.nnz_cap);
+                // (word edge_tiles(P.nnz_cap) is the completion counter of hop L-2's edge scan)
+                unsigned long long* v1_status = (unsigned long long*)b->ws.p + edge_tiles(P.nnz_cap) + 1;
                 hipLaunchKernelGGL(v1_split_kernel, dim3(idx_blocks + tiles), dim3(ETHREADS), 0, st, probe, d_n, v1_status,
                                    idx_blocks, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2), (const int32_t*)P.nbr_global.p,
                                    b->map.p, P.indices.p, P.has_csc ? P.csc_cnt.p : nullptr, (unsigned int*)(v1_status + tiles),
                                    b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
                                    b->hit_slot.p, extra, stamp_refresh ? cache->version.p : nullptr, (int32_t)step,
-                                   b->refresh_old.p, b->counts.p + 4 * b->n_layers + 5);
+                                   b->refresh_old.p, b->counts.p + 4 * b->n_layers + 6, b->call_id, dbg.spin_limit,
+                                   dbg.withhold_first_tile, (unsigned int*)(v1_status + tiles + 1), P.n_src_cap + 1,
+                                   b->counts.p + 4 * (h - 1) + 2, P.indptr.p, (const int32_t*)(b->counts.p + 4 * (h - 1)));
             } else {
             hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles + idx_blocks), dim3(ETHREADS), 0, st, probe, d_n, tile_sums,
                                b->probe_slot.p, b->probe_ver.p, tiles, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2),
@@ -855,6 +916,8 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
             }
             indices_done[h - 1] = true;
             b->stamped_cache = stamp_refresh ? cache : nullptr;
+            b->stamped_uid = cache->uid;
+            b->stamped_contents = cache->contents;
             d_dst = b->compute_list.p;
             d_n = extra + 0;
         }
@@ -863,7 +926,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
         const bool indices_now = use_cache && h < L - 2;
         // the hop above the bottom one also empties the status words of the V^1 split that follows it
         const int32_t extra_status = (use_cache && h == L - 2 && v1_one_launch(b, (unsigned)edge_tiles(b->hop[h].n_src_cap)))
-                                         ? (int32_t)edge_tiles(b->hop[h].n_src_cap) + 1 : 0;
+                                         ? (int32_t)edge_tiles(b->hop[h].n_src_cap) + 2 : 0;
         if (g->rowptr_bits == 64)
             NO_CHECK(sample_hop<int64_t>(g->rowptr64.p, g->col.p, b, h, d_dst, d_n, n_seeds, h == 0, key0, key1, domain, st,
                                          indices_now, extra_status));
@@ -883,7 +946,10 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
 
 int32_t blocks_unstamp(no_blocks_s* b, hipStream_t st) {
     if (!b->stamped_cache) return NO_OK;
-    if (!cache_is_live(b->stamped_cache)) {      // destroyed since: nothing to restore
+    // nothing to restore when the cache was destroyed since (its address may already name another cache), or when all
+    // its versions were replaced (refresh commit: the stamps sit in the copy that is now the pending one; invalidate)
+    if (!cache_is_live(b->stamped_cache) || b->stamped_cache->uid != b->stamped_uid ||
+        b->stamped_cache->contents != b->stamped_contents) {
         b->stamped_cache = nullptr;
         return NO_OK;
     }
@@ -943,7 +1009,7 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
     NO_CHECK(fill_i32(b->map.p, EMPTY, g->n_vertices, nullptr));
     NO_CHECK(b->tmp_a.alloc((size_t)max_sort));
     const int64_t max_items = max_pad > max_src ? max_pad : max_src;
-    NO_CHECK(b->ws.alloc((size_t)(2 * edge_tiles(max_items + 1) + 4) * sizeof(int64_t)));      // two sets of status words
+    NO_CHECK(b->ws.alloc((size_t)(2 * edge_tiles(max_items + 1) + 8) * sizeof(int64_t)));      // two sets of status words and their counters
     NO_CHECK(b->ws_side.alloc((size_t)(edge_tiles(max_items + 1) + 2) * sizeof(int64_t)));
     NO_HIP_CHECK(hipStreamCreateWithFlags(&b->side, hipStreamNonBlocking));
     for (int32_t h = 0; h < n_layers; ++h) NO_HIP_CHECK(hipEventCreateWithFlags(&b->ev_fork[h], NO_SYNC_EVENT_FLAGS));
@@ -1056,6 +1122,24 @@ extern "C" int32_t no_blocks_sizes(no_blocks_t blocks, void* stream, int32_t* h_
         h_sizes[4 * h + 2] = tmp[4 * h + 2];
         h_sizes[4 * h + 3] = (h == L - 1 && blocks->last_used_cache) ? tmp[4 * L + 1] : 0;
     }
+    const int32_t id = blocks->call_id;
+    NO_REQUIRE(id == 0 || tmp[4 * L + 6] != id, NO_ERR_TIMEOUT,
+               "no_blocks_sizes: a scan of the last sampling call gave up waiting for an earlier tile; the blocks are invalid");
+    NO_REQUIRE(id == 0 || tmp[4 * L + 5] != id, NO_ERR_OUT_OF_RANGE,
+               "no_blocks_sizes: the last sampling call met a seed id outside [0, V) (read as vertex 0)");
+    return NO_OK;
+}
+
+namespace no {
+static ScanWaitDebug g_scan_wait_debug{1 << 20, 0};
+ScanWaitDebug scan_wait_debug() { return g_scan_wait_debug; }
+}  // namespace no
+
+extern "C" int32_t no_debug_scan_wait(int32_t spin_limit, int32_t withhold_first_tile) {
+    clear_error();
+    NO_REQUIRE(spin_limit >= 0, NO_ERR_INVALID_ARG, "no_debug_scan_wait: spin_limit must be >= 0");
+    g_scan_wait_debug.spin_limit = spin_limit > 0 ? spin_limit : (1 << 20);
+    g_scan_wait_debug.withhold_first_tile = withhold_first_tile ? 1 : 0;
     return NO_OK;
 }
 

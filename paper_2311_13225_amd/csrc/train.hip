@@ -44,6 +44,7 @@ struct no_model_s {
     const int32_t* ahead_seeds = nullptr;
     int32_t ahead_n = 0;
     no_cache_s* ahead_cache = nullptr;
+    uint64_t ahead_cache_uid = 0, ahead_cache_generation = 0;
     const void* ahead_features = nullptr;
     no::StageProfiler prof;
     void release() {
@@ -73,7 +74,8 @@ namespace no {
 // One wavefront per seed: numerically stable softmax cross-entropy and its gradient, scaled by 1/n.
 __global__ void __launch_bounds__(256) softmax_xent_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
                                                            const int32_t* __restrict__ seeds, int32_t n, int32_t n_classes,
-                                                           float* __restrict__ grad, float* __restrict__ row_loss) {
+                                                           float* __restrict__ grad, float* __restrict__ row_loss,
+                                                           int32_t* bad_label_flag, int32_t flag_value) {
     const int lane = (int)(threadIdx.x & 63);
     const int row = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     if (row >= n) return;
@@ -87,6 +89,12 @@ __global__ void __launch_bounds__(256) softmax_xent_kernel(const float* __restri
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
     const int y = labels[seeds[row]];
+    if ((uint32_t)y >= (uint32_t)n_classes) {
+        // a label outside [0, C): the seed adds nothing to the loss or the gradient, and the step is flagged
+        for (int c = lane; c < n_classes; c += 64) grad[(int64_t)row * n_classes + c] = 0.f;
+        if (lane == 0) { row_loss[row] = 0.f; *bad_label_flag = flag_value; }
+        return;
+    }
     const float inv = 1.f / s, inv_n = 1.f / (float)n;
     for (int c = lane; c < n_classes; c += 64) {
         float p = expf(z[c] - mx) * inv;
@@ -251,8 +259,11 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         NO_CHECK(ensure_lookahead(m, g));
     }
     // a batch sampled ahead by the previous call is used if it is exactly this one; anything else is dropped
+    // (a cache is the same cache only with the same identity and an unchanged generation: a refresh commit, an
+    //  invalidate or a new bound since the split make the prepared batch another batch than a step would sample now)
     const bool presampled = m->ahead_valid && m->ahead_step == step && m->ahead_seed == seed && m->ahead_seeds == d_seeds &&
-                            m->ahead_n == n_seeds && m->ahead_cache == cache && m->ahead_features == d_features;
+                            m->ahead_n == n_seeds && m->ahead_cache == cache && m->ahead_features == d_features &&
+                            (!cache || (cache->uid == m->ahead_cache_uid && cache->generation == m->ahead_cache_generation));
     bool aggregated = false;
     if (m->ahead_valid) {
         // (ev_sampled is recorded after everything the sampling stream did for that batch, the aggregation included)
@@ -332,6 +343,8 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         m->ahead_seeds = d_next_seeds;
         m->ahead_n = n_next_seeds;
         m->ahead_cache = cache;
+        m->ahead_cache_uid = cache ? cache->uid : 0;
+        m->ahead_cache_generation = cache ? cache->generation : 0;
         m->ahead_features = d_features;
         return NO_OK;
     };
@@ -409,12 +422,16 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     const int32_t C = m->dims[L];
     prof.begin(NO_STAGE_LOSS);
     hipLaunchKernelGGL(softmax_xent_kernel, dim3(wave_rows_blocks(n_seeds)), dim3(256), 0, st, (const float*)m->h[L - 1].p,
-                       d_labels, (const int32_t*)B->seeds.p, n_seeds, C, m->gh[L - 1].p, m->row_loss.p);
+                       d_labels, (const int32_t*)B->seeds.p, n_seeds, C, m->gh[L - 1].p, m->row_loss.p,
+                       B->counts.p + 4 * L + 7, B->call_id);
     prof.end();
     // (mean loss and block sizes are written by an extra block of the step's last kernel, the layer-1 reduction)
     StatsJob stats_job;
     stats_job.row_loss = m->row_loss.p; stats_job.n = n_seeds;
     stats_job.counts = B->counts.p; stats_job.n_layers = L; stats_job.used_cache = used_cache ? 1 : 0;
+    stats_job.call_id = B->call_id;
+    stats_job.feat_row_bytes = row_bytes;
+    stats_job.emb_row_bytes = (L >= 2 && used_cache) ? m->dims[1] * 4 : 0;
     stats_job.stats = stats;
 
     // backward (first joins the side stream: the transposes are needed from here on)
@@ -476,6 +493,8 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     if (h_stats) {
         NO_HIP_CHECK(hipMemcpyAsync(h_stats, stats, sizeof(no_step_stats), hipMemcpyDeviceToHost, st));
         NO_HIP_CHECK(hipStreamSynchronize(st));
+        NO_REQUIRE(!h_stats->scan_timeout, NO_ERR_TIMEOUT,
+                   "no_train_step: a scan of the sampling gave up waiting for an earlier tile; the step's results are invalid");
     }
     return NO_OK;
 }

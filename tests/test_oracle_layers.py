@@ -255,3 +255,103 @@ def test_bf16_features_are_upcast_exactly():
     r2 = ora.train_step(g, si.bf16_bits_to_f32(fb), lab, train[:B], fanouts, weights, 0.1, 0, 0)
     assert r1.loss == r2.loss
     assert r1.x0.dtype == np.uint16
+
+
+# ------------------------------------------------------------------ the ReLU-decision hook of the backward pass
+# (Eq. 2's activation inside the backward loop of Algorithm 1: the derivative of ReLU is a float deciding a bit.
+# The GPU parity tests may hand the oracle the decisions taken in fp32 for pre-activations that are zero to within
+# rounding; these pins fix what the hook does so that it cannot hide anything else.)
+
+def test_relu_decision_hook_defaults_to_the_sign_of_the_pre_activation():
+    *_, g, feat, lab, train, weights, fanouts, B = _small_problem()
+    blk = ora.sample_blocks(g, train[:B], [3, 3], 0, 0).blocks[1]
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((blk.n_src, 7))
+    (ws, wn, bias), = si.init_weights([7, 5], 2)
+    mean, z, h = ora.sage_layer_fwd_z(blk, x, ws, wn, bias, relu=True)
+    assert np.array_equal(h > 0, z > 0) and (z > 0).any() and (z < 0).any()
+    gh = rng.standard_normal(h.shape)
+    ref = ora.sage_layer_bwd(blk, x, mean, h, gh, ws, wn, True, True)
+    same = ora.sage_layer_bwd(blk, x, mean, h, gh, ws, wn, True, True, active=(z > 0))
+    for a, b in zip(ref, same):
+        assert np.array_equal(a, b)
+    # without an activation the hook is ignored
+    lin = ora.sage_layer_bwd(blk, x, mean, z, gh, ws, wn, False, True)
+    lin2 = ora.sage_layer_bwd(blk, x, mean, z, gh, ws, wn, False, True, active=np.zeros(z.shape, bool))
+    for a, b in zip(lin, lin2):
+        assert np.array_equal(a, b)
+    # GCN-style layer: same contract
+    a, zg, hg = ora.gcn_layer_fwd_z(blk, x, ws, bias, relu=True)
+    refg = ora.gcn_layer_bwd(blk, a, hg, gh, ws, True, True)
+    sameg = ora.gcn_layer_bwd(blk, a, hg, gh, ws, True, True, active=(zg > 0))
+    for p, q in zip(refg, sameg):
+        assert np.array_equal(p, q)
+
+
+def test_flipping_one_relu_decision_moves_every_gradient_by_its_rank_one_term():
+    """Decision (r, c) flipped from 'off' to 'on' adds grad_h[r, c] to gz[r, c] and nothing else, so
+    gw_self += outer(x_dst[r], e_c) g, gw_neigh += outer(mean[r], e_c) g, gbias[c] += g, and the input gradient
+    gains g * w_self[:, c] on row r plus g * w_neigh[:, c] / len(row r) on each sampled source of r."""
+    *_, g, feat, lab, train, weights, fanouts, B = _small_problem()
+    blk = ora.sample_blocks(g, train[:B], [3, 3], 0, 0).blocks[1]
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((blk.n_src, 7))
+    (ws, wn, bias), = si.init_weights([7, 5], 3)
+    ws, wn = ws.astype(np.float64), wn.astype(np.float64)
+    mean, z, h = ora.sage_layer_fwd_z(blk, x, ws, wn, bias, relu=True)
+    gh = rng.standard_normal(h.shape)
+    off = np.argwhere(z < 0)
+    rows_with_edges = np.flatnonzero(np.diff(blk.indptr) > 0)
+    r, c = next((int(a), int(b)) for a, b in off if a in rows_with_edges)
+    act = z > 0
+    base = ora.sage_layer_bwd(blk, x, mean, h, gh, ws, wn, True, True, active=act)
+    act2 = act.copy()
+    act2[r, c] = True
+    flip = ora.sage_layer_bwd(blk, x, mean, h, gh, ws, wn, True, True, active=act2)
+    gval = gh[r, c]
+    e_c = np.zeros(5)
+    e_c[c] = 1.0
+    assert np.allclose(flip[0] - base[0], gval * np.outer(x[r], e_c), rtol=1e-12, atol=1e-14)
+    assert np.allclose(flip[1] - base[1], gval * np.outer(mean[r], e_c), rtol=1e-12, atol=1e-14)
+    assert np.allclose(flip[2] - base[2], gval * e_c, rtol=1e-12, atol=1e-14)
+    dgx = np.zeros_like(x)
+    dgx[r] += gval * ws[:, c]
+    seg = blk.indices[blk.indptr[r]:blk.indptr[r + 1]]
+    for u in seg:
+        dgx[u] += gval * wn[:, c] / len(seg)
+    assert np.allclose(flip[3] - base[3], dgx, rtol=1e-12, atol=1e-14)
+    assert np.abs(flip[0] - base[0]).max() > 0
+
+
+@pytest.mark.parametrize("arch", ["sage", "gcn"])
+def test_step_hook_is_consulted_for_hidden_layers_only_and_none_means_default(arch):
+    *_, g, feat, lab, train, weights, fanouts, B = _small_problem(V=150, E=2500)
+    ws = [((w[0], w[2]) if arch == "gcn" else w) for w in weights]
+    cache = ora.select_hot(g, train, B, fanouts, 2, 0.3, 5, 6, 0)
+    cache.emb[:] = np.random.default_rng(4).standard_normal(cache.emb.shape)
+    cache.version[::2] = 1
+    seeds = train[:B]
+    ref = ora.train_step(g, feat, lab, seeds, fanouts, ws, 0.01, 1, 3, cache.copy(), arch=arch)
+    seen = []
+
+    def hook_none(layer, z):
+        seen.append((layer, z.shape))
+        return None
+
+    r1 = ora.train_step(g, feat, lab, seeds, fanouts, ws, 0.01, 1, 3, cache.copy(), relu_decisions=hook_none, arch=arch)
+    r2 = ora.train_step(g, feat, lab, seeds, fanouts, ws, 0.01, 1, 3, cache.copy(),
+                        relu_decisions=lambda layer, z: z > 0, arch=arch)
+    L = len(fanouts)
+    assert [s[0] for s in seen] == list(range(L - 1, 0, -1))           # layers with a ReLU, top down; never layer L
+    # layer 1's pre-activations cover the computed rows only (reused rows take no gradient)
+    assert seen[-1][1][0] == len(ref.batch.compute_pos) and ref.n_hit > 0
+    for r in (r1, r2):
+        assert r.loss == ref.loss
+        for ga, gb in zip(r.grads, ref.grads):
+            for a, b in zip(ga, gb):
+                assert np.array_equal(a, b)
+    # a hook that switches everything off zeroes every gradient below the classifier layer
+    r0 = ora.train_step(g, feat, lab, seeds, fanouts, ws, 0.01, 1, 3, cache.copy(),
+                        relu_decisions=lambda layer, z: np.zeros(z.shape, bool), arch=arch)
+    assert all(not np.any(a) for ga in r0.grads[:-1] for a in ga)
+    assert any(np.any(a) for a in r0.grads[-1])
