@@ -857,7 +857,7 @@ def test_step_statistics_account_for_every_vertex_of_v1():
     assert seen_hit > 0 and seen_miss > 0
 
 
-@pytest.mark.parametrize("fanouts,batch,which", [((10, 10), 512, "edge scan"), ((2, 10), 1024, "V^1 split")])
+@pytest.mark.parametrize("fanouts,batch,which", [((10, 10), 512, "edge scan"), ((1, 10), 2000, "V^1 split")])
 def test_scan_wait_expiry_is_reported_and_every_kernel_still_ends(fanouts, batch, which):
     """Error path of the one-launch scans: the host makes tile 0 withhold its status word and shortens the bounded
     wait, so the tile after it must give up. The scan then leaves a consistent empty hop behind (so that no later
