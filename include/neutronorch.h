@@ -219,6 +219,20 @@ int32_t no_sage_layer_bwd(const no_block_view* blk, const void* d_x_src, no_dtyp
                           float* d_gw_self, float* d_gw_neigh, float* d_gbias, float* d_grad_x_src,
                           void* d_ws, size_t ws_bytes, void* stream);
 
+/* no_sage_layer_bwd for callers that can neither allocate device memory nor hand over a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and results, with the
+ * workspace in a static device array of NO_LAYER_STATIC_WS_BYTES that the library's code object carries (each GPU the
+ * library runs on holds its copy until the process ends). The call allocates nothing and frees nothing. It returns
+ * NO_ERR_CAPACITY, before any launch, when no_sage_layer_ws_bytes(n_dst_cap, n_src_cap, d_in, d_out) exceeds
+ * NO_LAYER_STATIC_WS_BYTES. All calls on one GPU share that GPU's array and nothing in it survives a call: two calls
+ * that overlap in time on one GPU (different streams, or different threads) race; calls in stream order do not. */
+#define NO_LAYER_STATIC_WS_BYTES ((size_t)64 << 20)
+int32_t no_sage_layer_bwd_static(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+                                 const float* d_mean, const float* d_h, const float* d_grad_h,
+                                 const float* d_w_self, const float* d_w_neigh, int32_t d_out, int32_t relu,
+                                 float* d_gw_self, float* d_gw_neigh, float* d_gbias, float* d_grad_x_src,
+                                 void* stream);
+
 /* GCN-style layer (Eq. 1 as printed, AGGREGATE = average over N_in(v) U {v}; Eq. 2 with one matrix).
  * Forward: d_agg[v,:] = (d_x_src[v,:] + sum of d_x_src[indices[e],:] over row v) / (len(row v) + 1) (destination
  * v is source row v); d_h = act(d_agg * W + bias). Shapes, dtypes, workspace and errors as no_sage_layer_fwd.

@@ -74,6 +74,7 @@ _SIGNATURES = {
     "no_sage_layer_fwd": (_I32, [_P, _P, _I32, _I32, _P, _P, _P, _I32, _I32, _P, _P, _P, C.c_size_t, _P]),
     "no_sage_layer_bwd": (_I32, [_P, _P, _I32, _I32, _P, _P, _P, _P, _P, _I32, _I32, _P, _P, _P, _P, _P,
                                  C.c_size_t, _P]),
+    "no_sage_layer_bwd_static": (_I32, [_P, _P, _I32, _I32, _P, _P, _P, _P, _P, _I32, _I32, _P, _P, _P, _P, _P]),
     "no_model_create": (_I32, [_P, _I32, _P, _I32, _P, _I32, _P]),
     "no_model_params": (_I32, [_P, _I32, _P, _P, _P]),
     "no_model_grads": (_I32, [_P, _I32, _P, _P, _P]),
@@ -391,6 +392,21 @@ def no_sage_layer_bwd(blk: no_block_view, x_src: torch.Tensor, mean: torch.Tenso
                                    h.data_ptr(), grad_h.data_ptr(), w_self.data_ptr(), w_neigh.data_ptr(), d_out,
                                    1 if relu else 0, gw_self.data_ptr(), gw_neigh.data_ptr(), gbias.data_ptr(),
                                    _ptr(grad_x_src), ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+NO_LAYER_STATIC_WS_BYTES = 64 << 20
+
+
+def no_sage_layer_bwd_static(blk: no_block_view, x_src: torch.Tensor, mean: torch.Tensor, h: torch.Tensor,
+                             grad_h: torch.Tensor, w_self: torch.Tensor, w_neigh: torch.Tensor, relu: bool,
+                             gw_self: torch.Tensor, gw_neigh: torch.Tensor, gbias: torch.Tensor,
+                             grad_x_src: Optional[torch.Tensor], stream=None):
+    """no_sage_layer_bwd with the workspace in the library's static device array (allocates nothing)."""
+    d_in, d_out = w_self.shape
+    _check(lib().no_sage_layer_bwd_static(C.byref(blk), x_src.data_ptr(), _dtype_code(x_src), d_in, mean.data_ptr(),
+                                          h.data_ptr(), grad_h.data_ptr(), w_self.data_ptr(), w_neigh.data_ptr(), d_out,
+                                          1 if relu else 0, gw_self.data_ptr(), gw_neigh.data_ptr(), gbias.data_ptr(),
+                                          _ptr(grad_x_src), _stream(stream)))
 
 
 def no_gcn_layer_fwd(blk: no_block_view, x_src: torch.Tensor, w: torch.Tensor, bias: torch.Tensor, relu: bool,

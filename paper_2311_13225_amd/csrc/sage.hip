@@ -6,6 +6,7 @@
 #include "layers.hpp"
 
 #include <stdlib.h>
+#include <mutex>
 
 namespace no {
 
@@ -540,6 +541,59 @@ extern "C" int32_t no_sage_layer_bwd(const no_block_view* blk, const void* d_x_s
     LayerWorkspace w = carve_workspace(d_ws, blk->n_dst_cap, d_in, d_out);
     NO_REQUIRE(d_ws != nullptr && ws_bytes >= w.bytes, NO_ERR_CAPACITY, "no_sage_layer_bwd: workspace too small (%zu < %zu)",
                ws_bytes, w.bytes);
+    return sage_backward(*blk, d_x_src, dt_x, d_in, d_mean, d_h, d_grad_h, d_w_self, d_w_neigh, d_out, relu, d_gw_self,
+                         d_gw_neigh, d_gbias, d_grad_x_src, w, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------ backward without any allocation
+//
+// The workspace of no_sage_layer_bwd (masked gradient, mean gradient, fp32 copy of bf16 rows, split partial products)
+// held in a file-scope device array instead of a caller's buffer, for callers that cannot allocate or pass one.
+constexpr size_t kStaticWsBytes = NO_LAYER_STATIC_WS_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// The address of this device's copy of `scratch` (every GPU holds its own copy at its own address; the array's name
+// is only a host-side handle for the lookup and is never passed to a kernel or a memory call).
+static int32_t static_workspace(void** out) {
+    int dev = -1;
+    NO_HIP_CHECK(hipGetDevice(&dev));
+    NO_REQUIRE(dev >= 0 && dev < kMaxDevices, NO_ERR_UNSUPPORTED, "static workspace: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        NO_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        NO_REQUIRE(p != nullptr, NO_ERR_HIP, "static workspace: no device address for the scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return NO_OK;
+}
+}  // namespace
+
+extern "C" int32_t no_sage_layer_bwd_static(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+                                            const float* d_mean, const float* d_h, const float* d_grad_h,
+                                            const float* d_w_self, const float* d_w_neigh, int32_t d_out, int32_t relu,
+                                            float* d_gw_self, float* d_gw_neigh, float* d_gbias, float* d_grad_x_src,
+                                            void* stream) {
+    clear_error();
+    NO_CHECK(check_layer_args(blk, d_x_src, dt_x, d_in, d_out, "no_sage_layer_bwd_static"));
+    NO_REQUIRE(d_mean && d_h && d_grad_h && d_w_self && d_w_neigh && d_gw_self && d_gw_neigh && d_gbias, NO_ERR_INVALID_ARG,
+               "no_sage_layer_bwd_static: NULL argument");
+    NO_REQUIRE(!d_grad_x_src || (blk->d_csc_indptr && blk->d_csc_dst && blk->d_n_src), NO_ERR_INVALID_ARG,
+               "no_sage_layer_bwd_static: input gradient requested but the block has no transpose");
+    const size_t need = carve_workspace(nullptr, blk->n_dst_cap, d_in, d_out).bytes;
+    NO_REQUIRE(need <= kStaticWsBytes, NO_ERR_CAPACITY,
+               "no_sage_layer_bwd_static: the layer needs %zu bytes of workspace, the static one holds %zu", need,
+               kStaticWsBytes);
+    void* ws = nullptr;
+    NO_CHECK(static_workspace(&ws));
+    // (every part of the workspace is written by this call's kernels before it is read: nothing has to start at zero)
+    LayerWorkspace w = carve_workspace(ws, blk->n_dst_cap, d_in, d_out);
     return sage_backward(*blk, d_x_src, dt_x, d_in, d_mean, d_h, d_grad_h, d_w_self, d_w_neigh, d_out, relu, d_gw_self,
                          d_gw_neigh, d_gbias, d_grad_x_src, w, (hipStream_t)stream);
 }
