@@ -5,12 +5,14 @@ A "step" is one pass of the whole path (sample L hops, gather, forward, loss, ba
 cache refresh) over one batch of seeds of the named synthetic workload, with graph, features,
 labels, weights and the seed batches already resident in HBM. Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dense|tiny|sparse|sweep]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|dense|sparse|sweep|tiny]
 
-`value` = train steps/s of the unprofiled timed region. A second pass over the same steps with
-per-stage HIP events on the step's stream gives the stage times, the sampled-edges/s and gather
-GB/s figures (`extra`) and the `roofline` object of the dominant kernel. `cpu_baseline` times the
-CPU oracle on a bounded number of the same steps.
+The default workload is `large`, the largest configuration (111 M vertices, 1.6 G edges, 28 GB of bf16
+features): the one the gather / aggregation target is stated on. `value` = train steps/s of the unprofiled
+timed region. A second pass over the same steps with per-stage HIP events on the step's stream gives the
+stage times, the sampled-edges/s and gather GB/s figures (`extra`) and the `roofline` object of the dominant
+kernel. `cpu_baseline` times the CPU oracle on a bounded sample (on the mid-size graph with this workload's
+feature and model shape when the workload's own graph and table do not fit the oracle's time budget).
 """
 import argparse
 import json
@@ -35,7 +37,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="dense")
+    ap.add_argument("--workload", default="large")
     ap.add_argument("--no-cache", action="store_true", help="exact training (no hot-embedding reuse)")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: auto, 0: skip)")
     ap.add_argument("--presample-epochs", type=int, default=3)
@@ -146,14 +148,15 @@ def main():
             for t, a in zip(b.no_model_params(model, l + 1), weights[l]):
                 t.copy_(dev(a))
 
-    seed_batches = [dev(si.batch_seeds(train, w.batch, t)) for t in range(W + K)]
+    # one batch more than is trained on: the last timed step also prepares a next batch, like every other step
+    seed_batches = [dev(si.batch_seeds(train, w.batch, t)) for t in range(W + K + 1)]
     stream = torch.cuda.current_stream()
 
     def run(first, count, want_stats=False, ahead=False):
         out = []
         for t in range(first, first + count):
             if ahead:
-                nxt = seed_batches[t + 1] if t + 1 < W + K else None
+                nxt = seed_batches[t + 1]
                 st = b.no_train_step_ahead(model, g, tfeat, tlab, seed_batches[t], nxt, False, cache, t, w.seed, args.lr,
                                            want_stats=want_stats)
             else:
@@ -200,7 +203,7 @@ def main():
                     b.no_refresh_hot_begin(cache, g, tfeat, w1[0], None if gcn else w1[1], w1[2], w.fanouts[-1], t, w.seed)
                     sb_pending[0] = True
                 if use_ahead:
-                    nxt = seed_batches[t + 1] if t + 1 < W + K else None
+                    nxt = seed_batches[t + 1]
                     # the boundary commit moves inside the call that samples the first batch of the next super-batch
                     commit = nxt is not None and (t + 1) % n_sb == 0 and sb_pending[0]
                     out.append(b.no_train_step_ahead(model, g, tfeat, tlab, seed_batches[t], nxt, commit, cache, t, w.seed,
@@ -247,136 +250,164 @@ def main():
     run(0, W)
     torch.cuda.synchronize()
     b.no_model_profile(model, True)
-    stats = run(W, K, want_stats=True)
+    L = w.n_layers
+    blocks = b.no_model_blocks(model)
+    N_GATHER_LISTS = 16
+    id_lists = []            # bottom-hop source ids of the last N_GATHER_LISTS profiled steps (device copies)
+    stats = []
+    for t in range(W, W + K):
+        st = b.no_train_step(model, g, tfeat, tlab, seed_batches[t], cache, t, w.seed, args.lr, want_stats=True)
+        stats.append(st)
+        if t >= W + K - N_GATHER_LISTS:
+            view = b.no_blocks_view(blocks, L - 1)
+            id_lists.append(b._view(view.d_src_global, (int(st.n_src[L - 1]),), "<i4", blocks).clone())
     stage_ms, n_prof = b.no_model_stage_ms(model)
     b.no_model_profile(model, False)
     per_step = {k: v / max(n_prof, 1) for k, v in stage_ms.items()}
-    L = w.n_layers
     es = 2 if bf16 else 4
     F = w.feat_dim
+    rp = w.rowptr_bits // 8
     mean = lambda xs: float(sum(xs)) / max(len(xs), 1)
-    nnz_total = mean([sum(s.nnz[h] for h in range(L)) for s in stats])
-    n_src_bottom = mean([s.n_src[L - 1] for s in stats])
-    n_dst_bottom = mean([s.n_dst[L - 1] for s in stats])
-    nnz_bottom = mean([s.nnz[L - 1] for s in stats])
-    n_hit = mean([s.n_hit for s in stats])
-    n_v1 = mean([s.n_v1 for s in stats])
+    hop = lambda name, h: mean([getattr(s_, name)[h] for s_ in stats])
+    nnz_total = sum(hop("nnz", h) for h in range(L))
+    n_src_bottom, n_dst_bottom, nnz_bottom = hop("n_src", L - 1), hop("n_dst", L - 1), hop("nnz", L - 1)
+    n_hit = mean([s_.n_hit for s_ in stats])
+    n_v1 = mean([s_.n_v1 for s_ in stats])
     loss_last = stats[-1].loss
-    # Gather: inside the step only the bottom destinations' rows are copied (on the side stream, next to the
-    # aggregation, which reads the neighbour rows in place), so the step has no gather stage to time. The
-    # gather figure is no_gather_features on the FULL source list of the last step's bottom hop (what an
-    # unfused step would collect), timed alone with events on the stream it runs on.
-    blocks = b.no_model_blocks(model)
-    view = b.no_blocks_view(blocks, L - 1)
-    n_src_last = int(stats[-1].n_src[L - 1])
-    ids_last = b._view(view.d_src_global, (n_src_last,), "<i4", blocks).clone()
-    gout = torch.empty((n_src_last, F), dtype=tfeat.dtype, device="cuda")
-    for _ in range(3):
-        b.no_gather_features(tfeat, ids_last, gout)
+    # Gather: inside the step only the bottom destinations' rows are copied (on the side stream; the aggregation
+    # reads the neighbour rows in place), so the step has no gather stage to time. The gather figure is
+    # no_gather_features on the FULL source lists of the bottom hop (what an unfused step would collect), rotating
+    # over the lists of the last 16 steps and over 16 output buffers so that the rows read and written between two
+    # uses of a buffer exceed the 256 MB last-level cache: a cold, HBM-bound figure, timed with events on the
+    # stream it runs on.
+    gouts = [torch.empty((int(ids.numel()), F), dtype=tfeat.dtype, device="cuda") for ids in id_lists]
+    for ids, gout in zip(id_lists, gouts):
+        b.no_gather_features(tfeat, ids, gout)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n_rep = 20
+    n_rep = 4
     e0.record()
     for _ in range(n_rep):
-        b.no_gather_features(tfeat, ids_last, gout)
+        for ids, gout in zip(id_lists, gouts):
+            b.no_gather_features(tfeat, ids, gout)
     e1.record()
     torch.cuda.synchronize()
-    per_step["gather"] = e0.elapsed_time(e1) / n_rep          # ms per launch, standalone
-    gather_bytes = n_src_last * (4 + 2 * F * es)
-    del gout
+    n_launch = n_rep * len(id_lists)
+    per_step["gather"] = e0.elapsed_time(e1) / n_launch          # ms per launch, standalone
+    gather_rows = mean([int(ids.numel()) for ids in id_lists])
+    gather_bytes = gather_rows * (4 + 2 * F * es)
+    gather_working_set = sum(int(ids.numel()) for ids in id_lists) * 2 * F * es
+    del gouts
     # compulsory traffic (each distinct source row once) plus the reused layer-1 rows that extra blocks of the same
     # launch copy from the cache into H^1 (read + write)
     agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4 + (n_hit * w.dims[1] * 4 * 2 if L >= 2 else 0)
     gemm_fwd_flops = 2.0 * n_dst_bottom * ((1 if gcn else 2) * F) * w.dims[1]
     # the weight-gradient launch of layer 1 also carries the (smaller) weight-gradient products of the layers above
     gemm_dw_flops = gemm_fwd_flops + sum(
-        2.0 * mean([st_.n_dst[L - l] for st_ in stats]) * ((1 if gcn else 2) * w.dims[l - 1]) * w.dims[l] for l in range(2, L + 1))
+        2.0 * hop("n_dst", L - l) * ((1 if gcn else 2) * w.dims[l - 1]) * w.dims[l] for l in range(2, L + 1))
+    # Sampling, algorithmic bytes. Per destination of a hop: two row pointers and its id; per sampled edge: the
+    # column entry read and the neighbour id written. Relabelling: each sampled slot read and written once, one 4-byte
+    # probe of the id map, the new sources' ids. Transpose (hops above the bottom one): indices and rows read, two
+    # arrays written.
+    sample_rows_bytes = lambda h: hop("n_dst", h) * (2 * rp + 4) + hop("nnz", h) * 8
+    relabel_bytes = lambda h: hop("nnz", h) * 12 + hop("n_src", h) * 4 + hop("n_dst", h) * 4
+    csc_bytes = lambda h: hop("nnz", h) * 16 if h < L - 1 else 0.0
+    sampling_bytes = sum(sample_rows_bytes(h) + relabel_bytes(h) + csc_bytes(h) for h in range(L))
+    ms = per_step
     kern = {
-        "gather_rows_kernel": ("hbm", gather_bytes / 1e9 / (per_step["gather"] / 1e3), HBM_PEAK_GBPS, "GB/s", per_step["gather"]),
-        "segment_rows_kernel(mean,l1)": ("hbm", agg_bytes / 1e9 / (per_step["agg_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", per_step["agg_l1"]),
-        "gemm_nn_kernel(l1 fwd)": ("mfma", gemm_fwd_flops / 1e12 / (per_step["gemm_fwd_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", per_step["gemm_fwd_l1"]),
-        "gemm_tn_kernel(l1 dW)": ("mfma", gemm_dw_flops / 1e12 / (per_step["gemm_dw_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", per_step["gemm_dw_l1"]),
+        "gather_rows_kernel": ("hbm", gather_bytes / 1e9 / (ms["gather"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["gather"]),
+        "segment_rows_kernel(mean,l1)": ("hbm", agg_bytes / 1e9 / (ms["agg_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["agg_l1"]),
+        "gemm_nn_kernel(l1 fwd)": ("mfma", gemm_fwd_flops / 1e12 / (ms["gemm_fwd_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms["gemm_fwd_l1"]),
+        "gemm_tn_kernel(l1 dW)": ("mfma", gemm_dw_flops / 1e12 / (ms["gemm_dw_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms["gemm_dw_l1"]),
+        "sample_rows_kernel(bottom hop)": ("hbm", sample_rows_bytes(L - 1) / 1e9 / (max(ms["sample_rows_bottom"], 1e-6) / 1e3),
+                                           HBM_PEAK_GBPS, "GB/s", ms["sample_rows_bottom"]),
     }
     dominant = max(kern, key=lambda k: kern[k][4])
     bound, achieved, peak, unit, dur = kern[dominant]
-    # HBM bytes per launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by the copy reference),
-    # recorded in profiles/dense_hbm_traffic.json for this workload; null for other workloads or kernels
-    traffic_all = {}
-    tpath = os.path.join(ROOT, "profiles", "dense_hbm_traffic.json")
+    # HBM bytes per launch from rocprofv3 --pmc runs of this workload (FETCH_SIZE + WRITE_SIZE, scaled by a copy of
+    # known size), stored in profiles/<workload>_hbm_traffic.json: a constant of that profile run, not of this run;
+    # null for shapes other than the workload's default
+    traffic_all, traffic_source = {}, None
+    tpath = os.path.join(ROOT, "profiles", "%s_hbm_traffic.json" % args.workload)
     default_shape = (args.batch <= 0 and not args.fanouts and args.hot_fraction < 0.0 and args.staleness < 0 and
                      args.arch == "sage")
-    if args.workload == "dense" and default_shape and cache is not None and os.path.exists(tpath):
+    if default_shape and cache is not None and os.path.exists(tpath):
         try:
-            traffic_all = json.load(open(tpath)).get("bytes_per_launch", {})
+            tj = json.load(open(tpath))
+            traffic_all = tj.get("bytes_per_launch", {})
+            traffic_source = "stored: profiles/%s_hbm_traffic.json (%s)" % (args.workload, tj.get("measured", "rocprofv3 --pmc"))
         except Exception:
             traffic_all = {}
+    entry = lambda k, v: {"bound": v[0], "achieved": round(v[1], 3), "peak": v[2], "unit": v[3],
+                          "frac": round(v[1] / v[2], 4), "avg_launch_ms": round(v[4], 4), "traffic": traffic_all.get(k)}
     roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
                 "frac": round(achieved / peak, 4), "traffic": traffic_all.get(dominant), "avg_launch_ms": round(dur, 4),
-                "all": {k: {"bound": v[0], "achieved": round(v[1], 3), "peak": v[2], "unit": v[3],
-                            "frac": round(v[1] / v[2], 4), "avg_launch_ms": round(v[4], 4),
-                            "traffic": traffic_all.get(k)} for k, v in kern.items()}}
+                "traffic_source": traffic_source,
+                "all": {k: entry(k, v) for k, v in kern.items()}}
+    # the whole sampling stage (about four launches per hop plus the transposes), priced by its algorithmic bytes
+    roofline["all"]["sampling stage (a1-a3, all hops, all its kernels)"] = {
+        "bound": "hbm", "achieved": round(sampling_bytes / 1e9 / (ms["sample"] / 1e3), 3), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(sampling_bytes / 1e9 / (ms["sample"] / 1e3) / HBM_PEAK_GBPS, 5), "avg_launch_ms": round(ms["sample"], 4),
+        "traffic": traffic_all.get("sampling stage"), "note": "a chain of dependent launches bound by latency, not by bytes"}
+    target = 0.60
+    gather_frac = kern["gather_rows_kernel"][1] / HBM_PEAK_GBPS
+    agg_frac = kern["segment_rows_kernel(mean,l1)"][1] / HBM_PEAK_GBPS
     extra = {
-        "sampled_edges_per_s": round(nnz_total / (per_step["sample"] / 1e3), 1),
+        # every hop's sampled edges over the whole sampling stage: sampling, relabelling, hot lookup, local indices,
+        # transposes and the wipe of the id map (the measurement pass joins the side stream inside the stage)
+        "sampled_edges_per_s": round(nnz_total / (ms["sample"] / 1e3), 1),
         "sampled_edges_per_step": round(nnz_total, 1),
+        "sampling_algorithmic_bytes_per_step": round(sampling_bytes, 1),
         "gather_GBps": round(kern["gather_rows_kernel"][1], 2),
-        "gather_frac_hbm_peak": round(kern["gather_rows_kernel"][1] / HBM_PEAK_GBPS, 4),
+        "gather_frac_hbm_peak": round(gather_frac, 4),
         "aggregate_GBps": round(kern["segment_rows_kernel(mean,l1)"][1], 2),
-        "aggregate_frac_hbm_peak": round(kern["segment_rows_kernel(mean,l1)"][1] / HBM_PEAK_GBPS, 4),
-        # the same launch priced by the bytes it moved (rocprofv3 counters; a source row shared by several destinations
-        # is fetched again when it has left the L2), not by the compulsory bytes above
-        "aggregate_moved_GBps": (round(traffic_all["segment_rows_kernel(mean,l1)"] / 1e9 / (per_step["agg_l1"] / 1e3), 2)
-                                 if "segment_rows_kernel(mean,l1)" in traffic_all else None),
+        "aggregate_frac_hbm_peak": round(agg_frac, 4),
+        "target_60pct_hbm_peak": {"gather": bool(gather_frac >= target), "aggregate": bool(agg_frac >= target)},
         "rows_gathered_per_step": round(n_src_bottom, 1),
-        "gather_measurement": "no_gather_features alone on the %d source rows of the last step's bottom hop "
-                              "(in the step the neighbour rows are read inside the aggregation)" % n_src_last,
+        "gather_measurement": "no_gather_features alone, rotating over the bottom-hop source lists of the last %d steps "
+                              "(%.0f rows each on average) and %d output buffers: %.0f MB read + written per round, past "
+                              "the 256 MB last-level cache (in the step the neighbour rows are read inside the aggregation)"
+                              % (len(id_lists), gather_rows, len(id_lists), gather_working_set / 1e6),
         "cache_hit_rate": round(n_hit / max(n_v1, 1.0), 4),
-        "bytes_gathered_per_step": {"features": round(n_src_bottom * F * es, 1),
-                                    "embeddings": round(n_hit * w.dims[1] * 4 if L >= 2 else 0.0, 1)},
+        "v1_per_step": {"hit": round(n_hit, 1), "miss_hot": round(mean([s_.n_miss_hot for s_ in stats]), 1),
+                        "cold": round(mean([s_.n_cold for s_ in stats]), 1)},
+        # written by the step's statistics block on the device
+        "bytes_gathered_per_step": {"features": round(mean([s_.bytes_gathered_features for s_ in stats]), 1),
+                                    "embeddings": round(mean([s_.bytes_gathered_embeddings for s_ in stats]), 1)},
         "stage_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
-        "profiled_ms_per_step": round(sum(v for k, v in per_step.items() if k != "gather"), 4),
+        "profiled_ms_per_step": round(sum(v for k, v in per_step.items() if k not in ("gather", "sample_rows_bottom")), 4),
         "host_enqueue_ms_per_step": round(enqueue_ms_per_step, 4),
         "setup_s": {"build_csr": round(t_csr, 2), "select_hot": round(t_hot, 2)},
         "loss_after_last_step": round(float(loss_last), 5),
         "superbatch_schedule": superbatch,
     }
     log("[bench] stage ms/step: " + ", ".join("%s=%.3f" % kv for kv in per_step.items()))
+    n_edges_made = len(src)
 
-    # ---- CPU baseline: the oracle, as it stands, on a bounded number of the same steps
+    # ---- CPU baseline: the oracle, as it stands, on a bounded sample
     cpu = None
-    cpu_steps = 0 if device_features else args.cpu_steps
-    if cpu_steps != 0:
-        from oracle import oracle as ora
-        try:
-            from threadpoolctl import threadpool_info
-            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            blas_threads = 1
-        t0 = time.time()
-        og = ora.build_csr(src, dst, w.n_vertices)
-        oc = None
-        if cache is not None:
-            pre_h = train if args.presample_batches <= 0 else train[: args.presample_batches * w.batch]
-            oc = ora.select_hot(og, pre_h, w.batch, w.fanouts, args.presample_epochs, w.hot_fraction, w.staleness,
-                                w.hidden, w.seed)
-        log("[bench] oracle setup (CSR + hot set): %.1fs" % (time.time() - t0))
-        ow = [tuple(np.asarray(t, np.float64) for t in ((x[0], x[2]) if gcn else x)) for x in weights]
-        # one untimed step to estimate the cost, then time as many as fit in ~20 s (at least 2)
-        t0 = time.perf_counter()
-        r = ora.train_step(og, feat, lab, si.batch_seeds(train, w.batch, 0), w.fanouts, ow, args.lr, w.seed, 0, oc,
-                           feat_is_bf16=bf16, arch=args.arch)
-        one = time.perf_counter() - t0
-        ow = r.new_weights
-        if cpu_steps < 0:
-            cpu_steps = int(max(2, min(K, 20.0 / max(one, 1e-3))))
-        t0 = time.perf_counter()
-        for t in range(1, 1 + cpu_steps):
-            r = ora.train_step(og, feat, lab, si.batch_seeds(train, w.batch, t), w.fanouts, ow, args.lr, w.seed, t, oc,
-                               feat_is_bf16=bf16, arch=args.arch)
-            ow = r.new_weights
-        cpu_elapsed = time.perf_counter() - t0
-        cpu = {"value": round(cpu_steps / cpu_elapsed, 4), "unit": "steps/s", "cores": int(blas_threads), "kind": "oracle",
-               "sample": "%d steps (steps 1..%d of the same workload, after 1 untimed step); C parts single-threaded, "
-                         "numpy fp64 BLAS on %d threads" % (cpu_steps, cpu_steps, blas_threads)}
-        log("[bench] oracle: %d steps in %.1fs" % (cpu_steps, cpu_elapsed))
+    if args.cpu_steps != 0:
+        import dataclasses
+        # free what the GPU legs needed on the host (12.8 GB of edges for the large workload)
+        cw, c_src, c_dst, c_feat, c_lab, c_train = w, src, dst, feat, lab, train
+        where = "the same workload"
+        if device_features:
+            del src, dst, c_src, c_dst
+            # The workload's own graph and table are beyond the oracle's time budget (its CSR build alone takes minutes
+            # for 1.6 G edges): the oracle runs on the mid-size sparse graph with this workload's feature width and
+            # dtype, classes, model, fanouts, batch, hot share and bound.
+            sp = si.WORKLOADS["sparse"]
+            cw = dataclasses.replace(sp, name="sparse graph with the %s workload's shapes" % w.name, feat_dim=w.feat_dim,
+                                     feat_dtype=w.feat_dtype, n_classes=w.n_classes, hidden=w.hidden, fanouts=w.fanouts,
+                                     batch=w.batch, hot_fraction=w.hot_fraction, staleness=w.staleness)
+            t0 = time.time()
+            c_src, c_dst = si.rmat_edges(cw.n_vertices, cw.n_edges, cw.seed, symmetrise=cw.symmetrise)
+            c_feat = si.features(cw.n_vertices, cw.feat_dim, cw.seed, cw.feat_dtype)
+            c_lab = si.labels(cw.n_vertices, cw.n_classes, cw.seed)
+            c_train = si.train_split(cw.n_vertices, 0.65, cw.seed)
+            where = ("R-MAT %d vertices / %d edges (the mid-size graph) with the %s workload's %d x %s features, %d classes, "
+                     "model, fanouts and batch" % (cw.n_vertices, len(c_src), w.name, cw.feat_dim, cw.feat_dtype, cw.n_classes))
+            log("[bench] oracle inputs (%s): %.1fs" % (where, time.time() - t0))
+        cpu = cpu_baseline(cw, c_src, c_dst, c_feat, c_lab, c_train, weights, cache is not None, args, gcn, K, where)
 
     line = {
         "metric": "train_steps_per_s", "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1,
@@ -384,13 +415,68 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: R-MAT %d vertices / %d directed edges, %d x %s features, %d classes, %d-layer "
                                "%s hidden %d, fanout %s, batch %d, hot %.0f%%, S=%d"
-                               % (w.name, w.n_vertices, len(src), w.feat_dim, w.feat_dtype, w.n_classes, w.n_layers,
+                               % (w.name, w.n_vertices, n_edges_made, w.feat_dim, w.feat_dtype, w.n_classes, w.n_layers,
                                   "GCN-style" if gcn else "GraphSAGE-mean", w.hidden, list(w.fanouts), w.batch, 0.0 if cache is None else 100 * w.hot_fraction,
                                   w.staleness),
                    "hot_reuse": cache is not None},
         "roofline": roofline, "cpu_baseline": cpu, "extra": extra,
     }
     print(json.dumps(line), flush=True)
+
+
+def cpu_baseline(cw, src, dst, feat, lab, train, weights, with_cache, args, gcn, K, where):
+    """Times the CPU oracle (never tuned for this) on a bounded number of steps: once with numpy's BLAS on all the
+    threads it takes by itself, once with every library limited to one thread. The C parts (sampling, relabelling,
+    gather, aggregation) are single-threaded in both."""
+    import numpy as np
+
+    import synth_inputs as si
+    from oracle import oracle as ora
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threadpool_limits = None
+        blas_threads = 1
+    bf16 = cw.feat_dtype == "bf16"
+    t0 = time.time()
+    og = ora.build_csr(src, dst, cw.n_vertices)
+    oc = None
+    pre_batches = 64
+    if with_cache and cw.hot_fraction > 0.0:
+        # hotness from one pre-sampling epoch over the first batches only: bounds the oracle's set-up time
+        oc = ora.select_hot(og, train[: pre_batches * cw.batch], cw.batch, cw.fanouts, 1, cw.hot_fraction, cw.staleness,
+                            cw.hidden, cw.seed)
+    log("[bench] oracle setup (CSR + hot set): %.1fs" % (time.time() - t0))
+    ow = [tuple(np.asarray(t, np.float64) for t in ((x[0], x[2]) if gcn else x)) for x in weights]
+    arch = "gcn" if gcn else "sage"
+    state = {"w": ow, "t": 0}
+
+    def steps(n):
+        t0 = time.perf_counter()
+        for _ in range(n):
+            t = state["t"]
+            r = ora.train_step(og, feat, lab, si.batch_seeds(train, cw.batch, t), cw.fanouts, state["w"], args.lr, cw.seed, t, oc,
+                               feat_is_bf16=bf16, arch=arch)
+            state["w"] = r.new_weights
+            state["t"] = t + 1
+        return time.perf_counter() - t0
+
+    one = steps(1)                     # untimed for the figures: estimates the cost of a step
+    n = args.cpu_steps if args.cpu_steps > 0 else int(max(2, min(K, 10.0 / max(one, 1e-3))))
+    el_all = steps(n)
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            el_one = steps(n)
+    else:
+        el_one = None
+    log("[bench] oracle: %d steps in %.1fs on %d BLAS threads, %s on one thread" %
+        (n, el_all, blas_threads, "-" if el_one is None else "%.1fs" % el_one))
+    return {"value": round(n / el_all, 4), "unit": "steps/s", "cores": int(blas_threads), "kind": "oracle",
+            "single_thread": None if el_one is None else {"value": round(n / el_one, 4), "unit": "steps/s", "cores": 1},
+            "sample": "%s; %d steps after 1 untimed step, then the next %d steps on one thread; hot set from one pre-sampling "
+                      "epoch over the first %d batches; C parts (sampling, relabel, gather, aggregation) single-threaded, numpy "
+                      "fp64 products on %d threads for `value`" % (where, n, n, pre_batches, blas_threads)}
 
 
 if __name__ == "__main__":

@@ -340,9 +340,11 @@ int32_t no_model_destroy(no_model_t m);
  * every step records an event pair around each stage and synchronises the stream at its end to
  * accumulate the elapsed times (so it is for measurement passes, not for throughput runs).
  * Stages that are a single kernel launch: NO_STAGE_GATHER, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1,
- * NO_STAGE_GEMM_DW_L1. */
+ * NO_STAGE_GEMM_DW_L1, NO_STAGE_SAMPLE_ROWS_BOTTOM. While enabled, the step's stream also waits for the blocks' side
+ * stream (local indices, transposes, id-map wipe) before the end of NO_STAGE_SAMPLE, so that stage is all of the
+ * sampling work of the step. */
 enum {
-    NO_STAGE_SAMPLE = 0,      /* all hops: sampling, relabel, transpose, hot lookup */
+    NO_STAGE_SAMPLE = 0,      /* all hops: sampling, relabel, hot lookup, and (joined) local indices + transposes */
     NO_STAGE_GATHER = 1,      /* feature rows of the bottom hop's sources */
     NO_STAGE_AGG_L1 = 2,      /* layer-1 mean aggregation kernel */
     NO_STAGE_GEMM_FWD_L1 = 3, /* layer-1 dense update kernel */
@@ -353,7 +355,8 @@ enum {
     NO_STAGE_GEMM_DW_L1 = 8,  /* layer-1 weight-gradient kernel (split partial products) */
     NO_STAGE_BWD_L1_REDUCE = 9,
     NO_STAGE_UPDATE = 10,     /* unused: the SGD step is fused into the gradient reductions */
-    NO_STAGE_COUNT = 11
+    NO_STAGE_SAMPLE_ROWS_BOTTOM = 11, /* the bottom hop's sampling kernel alone (a part of NO_STAGE_SAMPLE) */
+    NO_STAGE_COUNT = 12
 };
 int32_t no_model_profile(no_model_t m, int32_t enable);   /* enabling resets the accumulators */
 /* Test aid for the error path of the single-pass scans (edge compaction and V^1 split in one launch): their blocks

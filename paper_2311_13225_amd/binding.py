@@ -93,7 +93,7 @@ _SIGNATURES = {
     "no_stage_name": (C.c_char_p, [_I32]),
     "no_debug_scan_wait": (_I32, [_I32, _I32]),
 }
-NO_STAGE_COUNT = 11
+NO_STAGE_COUNT = 12
 EXPORTS = sorted(_SIGNATURES)
 
 

@@ -67,6 +67,9 @@ struct no_blocks_s {
     bool upper_indices_deferred = false;     // the last call left the upper hops' indices to the side stream
     bool side_pending = false;
     no::DevBuf<char> ws_side;
+    // measurement only: a pair of events for the next call's sampling kernel of hop time_hop (taken by that call)
+    hipEvent_t time_ev0 = nullptr, time_ev1 = nullptr;
+    int32_t time_hop = -1;
     void release() {
         if (side) { (void)hipStreamSynchronize(side); (void)hipStreamDestroy(side); side = nullptr; }
         for (auto& e : ev_fork) if (e) { (void)hipEventDestroy(e); e = nullptr; }

@@ -750,8 +750,10 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     int64_t* tile_sums = (int64_t*)b->ws.p;
     const uint32_t c3 = (domain << 8) | (uint32_t)h;
     int32_t* seeds_copy = (h == 0) ? b->seeds.p : nullptr;
+    hipEvent_t tev0 = nullptr, tev1 = nullptr;
+    if (b->time_hop == h && b->time_ev0) { tev0 = b->time_ev0; tev1 = b->time_ev1; b->time_ev0 = b->time_ev1 = nullptr; b->time_hop = -1; }
 #define NO_LAUNCH_SAMPLE(G)                                                                                            \
-    hipLaunchKernelGGL((sample_rows_kernel<G, RowT>), dim3((unsigned)ceil_div(H.n_dst_cap, 256 / G)), dim3(256), 0, st,    \
+    NO_LAUNCH_TIMED((sample_rows_kernel<G, RowT>), dim3((unsigned)ceil_div(H.n_dst_cap, 256 / G)), dim3(256), st, tev0, tev1, \
                        rowptr, col, d_dst, d_n_dst_in, n_fixed, H.n_dst_cap, k, key0, key1, c3, H.nbr_pad.p,               \
                        H.src_global.p, b->map.p, insert_dst ? 1 : 0, seeds_copy, cnt, (int32_t)b->n_vertices,               \
                        b->counts.p + 4 * b->n_layers + 5, b->call_id, (unsigned long long*)b->ws.p,                          \

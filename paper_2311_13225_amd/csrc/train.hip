@@ -302,10 +302,16 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     sg.out = m->x0.p;
     static const char* no_direct = getenv("NO_SELF_FROM_COPY");
     sg.needed_by_forward = m->feat_dtype != NO_F32 || no_direct;   // fp32: the forward product reads the table rows itself
+    hipEvent_t sev0 = nullptr, sev1 = nullptr;
+    if (!presampled) prof.kernel_pair(NO_STAGE_SAMPLE_ROWS_BOTTOM, &sev0, &sev1);
     prof.begin(NO_STAGE_SAMPLE);
     if (!presampled) B->scan_two_pass = false;
-    if (!presampled)
+    if (!presampled) {
+        B->time_ev0 = sev0; B->time_ev1 = sev1; B->time_hop = sev0 ? L - 1 : -1;
         NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg, false, true));
+        // measurement passes count the side stream's share of the sampling (local indices, transposes, map wipe) too
+        if (prof.enabled) NO_CHECK(blocks_join(B, st));
+    }
     prof.end();
     const bool used_cache = B->last_used_cache;
     m->last_used_cache = used_cache;
@@ -604,6 +610,7 @@ extern "C" int32_t no_model_stage_ms(no_model_t m, double* h_total_ms, int32_t* 
 
 extern "C" const char* no_stage_name(int32_t stage) {
     static const char* names[NO_STAGE_COUNT] = {"sample", "gather", "agg_l1", "gemm_fwd_l1", "fwd_upper", "loss",
-                                                "bwd_upper", "bwd_l1_prep", "gemm_dw_l1", "bwd_l1_reduce", "update"};
+                                                "bwd_upper", "bwd_l1_prep", "gemm_dw_l1", "bwd_l1_reduce", "update",
+                                                "sample_rows_bottom"};
     return (stage >= 0 && stage < NO_STAGE_COUNT) ? names[stage] : "?";
 }
