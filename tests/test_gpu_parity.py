@@ -330,6 +330,63 @@ def test_sage_layer_empty_block_and_small_workspace():
 
 # --------------------------------------------------------------------------------------- whole step
 
+def make_relu_hook(b, model, st, n_layers, ambiguous):
+    """The ReLU decision is a float deciding a bit. Where the oracle's pre-activation is zero to
+    within rounding (|z| <= 1e-5 max|z|) the decision the kernel took in fp32 is as valid as the
+    oracle's, so the oracle's backward uses the kernel's; everywhere else the two must agree exactly
+    (asserted here), so a wrong mask cannot hide behind this. How many decisions may be taken over is bounded."""
+    def relu_decisions(layer, z_ora):
+        blocks_ = b.no_model_blocks(model)
+        sizes_ = b.no_blocks_sizes(blocks_)
+        n_rows = st.n_v1 if (layer == 1 and n_layers >= 2) else z_ora.shape[0]
+        gh = b.no_model_activations(model, layer, n_rows, 1)[0].cpu().numpy()
+        if gh.shape[0] != z_ora.shape[0]:
+            gh = gh[b.block_arrays(blocks_, n_layers - 1, sizes_)["compute_pos"]]
+        if z_ora.size == 0:
+            return np.zeros(z_ora.shape, dtype=bool)
+        tau = 1e-5 * max(np.abs(z_ora).max(), 1e-30)
+        assert (gh[z_ora > tau] > 0).all(), "layer %d: kernel masks a clearly positive pre-activation" % layer
+        assert (gh[z_ora < -tau] == 0).all(), "layer %d: kernel keeps a clearly negative pre-activation" % layer
+        flips = int(((gh > 0) != (z_ora > 0)).sum())
+        in_band = int((np.abs(z_ora) <= tau).sum())
+        ambiguous.append((layer, flips, in_band, z_ora.size))
+        # the witness may only decide a vanishing share of the entries: at most RELU_FLIP_SHARE of a layer's
+        # pre-activations (plus RELU_FLIP_FLOOR for tiny layers) may differ from the oracle's own decision
+        assert flips <= RELU_FLIP_FLOOR + RELU_FLIP_SHARE * z_ora.size, (
+            "layer %d: %d of %d ReLU decisions taken from the kernel (in band: %d)" % (layer, flips, z_ora.size, in_band))
+        return gh > 0
+    return relu_decisions
+
+
+def check_step_outputs(b, model, st, r, n_layers, step, with_cache_blocks, gcn, feat_dtype):
+    """One step of the library (its statistics `st`, the model's blocks, activations, gradients and parameters)
+    against the oracle's StepResult `r`: integers bit for bit, floats within the tolerance."""
+    pick = (lambda three: (three[0], three[2])) if gcn else (lambda three: three)
+    blocks = b.no_model_blocks(model)
+    sizes = compare_blocks(b, blocks, r.batch, with_cache=with_cache_blocks)
+    for h in range(n_layers):
+        assert (st.n_dst[h], st.n_src[h], st.nnz[h]) == tuple(int(x) for x in sizes[h, :3])
+    assert st.n_hit == r.n_hit
+    # gathered rows (the step materialises the bottom destinations' rows; the rest is read in place): bit copy
+    n_dst_bottom = r.batch.blocks[-1].n_dst
+    if not gcn:
+        x0 = b.no_model_gathered(model, n_dst_bottom).cpu().numpy()
+        assert np.array_equal(x0.view(feat_dtype), r.x0[:n_dst_bottom])
+    # floats
+    assert abs(st.loss - r.loss) <= RTOL * abs(r.loss) + 1e-6, (st.loss, r.loss)
+    for l in range(1, n_layers + 1):
+        n_rows = r.h[l - 1].shape[0]
+        n_dst = r.batch.blocks[n_layers - l].n_dst
+        gh, gm = b.no_model_activations(model, l, n_rows, n_dst)
+        assert_close(gm.cpu().numpy(), r.mean[l - 1], "mean%d step %d" % (l, step))
+        assert_close(gh.cpu().numpy(), r.h[l - 1], "h%d step %d" % (l, step))
+        names = ["gw", "gbias"] if gcn else ["gw_self", "gw_neigh", "gbias"]
+        for t, ref, name in zip(pick(b.no_model_grads(model, l)), r.grads[l - 1], names):
+            assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step))
+        for t, ref, name in zip(pick(b.no_model_params(model, l)), r.new_weights[l - 1], names):
+            assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name[1:], l, step))
+
+
 def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None, bits=32, presample=1,
               n_train_presample=None, superbatch=0, arch="sage", ahead=False):
     b = nb()
@@ -388,60 +445,12 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
         else:
             st = b.no_train_step(model, gg, tfeat, tlab, seed_tensors[step], gc, step, w.seed, lr)
         ambiguous = []
-
-        def relu_decisions(layer, z_ora):
-            """The ReLU decision is a float deciding a bit. Where the oracle's pre-activation is zero to
-            within rounding (|z| <= 1e-5 max|z|) the decision the kernel took in fp32 is as valid as the
-            oracle's, so the oracle's backward uses the kernel's; everywhere else the two must agree exactly
-            (asserted here), so a wrong mask cannot hide behind this."""
-            blocks_ = b.no_model_blocks(model)
-            sizes_ = b.no_blocks_sizes(blocks_)
-            n_rows = st.n_v1 if (layer == 1 and w.n_layers >= 2) else z_ora.shape[0]
-            gh = b.no_model_activations(model, layer, n_rows, 1)[0].cpu().numpy()
-            if gh.shape[0] != z_ora.shape[0]:
-                gh = gh[b.block_arrays(blocks_, w.n_layers - 1, sizes_)["compute_pos"]]
-            if z_ora.size == 0:
-                return np.zeros(z_ora.shape, dtype=bool)
-            tau = 1e-5 * max(np.abs(z_ora).max(), 1e-30)
-            assert (gh[z_ora > tau] > 0).all(), "layer %d: kernel masks a clearly positive pre-activation" % layer
-            assert (gh[z_ora < -tau] == 0).all(), "layer %d: kernel keeps a clearly negative pre-activation" % layer
-            flips = int(((gh > 0) != (z_ora > 0)).sum())
-            in_band = int((np.abs(z_ora) <= tau).sum())
-            ambiguous.append((layer, flips, in_band, z_ora.size))
-            # the witness may only decide a vanishing share of the entries: at most RELU_FLIP_SHARE of a layer's
-            # pre-activations (plus RELU_FLIP_FLOOR for tiny layers) may differ from the oracle's own decision
-            assert flips <= RELU_FLIP_FLOOR + RELU_FLIP_SHARE * z_ora.size, (
-                "layer %d: %d of %d ReLU decisions taken from the kernel (in band: %d)" % (layer, flips, z_ora.size, in_band))
-            return gh > 0
-
+        relu_decisions = make_relu_hook(b, model, st, w.n_layers, ambiguous)
         r = ora.train_step(og, feat, lab, seeds, w.fanouts, ow, lr, w.seed, step, oc, feat_is_bf16=bf16,
                            relu_decisions=relu_decisions, arch=arch)
         print("  relu decisions taken from the kernel (layer, flips, in band, entries):", ambiguous, flush=True)
-        # integers: block sizes, blocks, hits
-        blocks = b.no_model_blocks(model)
-        sizes = compare_blocks(b, blocks, r.batch, with_cache=use_cache and w.n_layers >= 2 and oc.n_hot > 0)
-        for h in range(w.n_layers):
-            assert (st.n_dst[h], st.n_src[h], st.nnz[h]) == tuple(int(x) for x in sizes[h, :3])
-        assert st.n_hit == r.n_hit
+        check_step_outputs(b, model, st, r, w.n_layers, step, use_cache and w.n_layers >= 2 and oc.n_hot > 0, gcn, feat.dtype)
         hits += r.n_hit
-        # gathered rows (the step materialises the bottom destinations' rows; the rest is read in place): bit copy
-        n_dst_bottom = r.batch.blocks[-1].n_dst
-        if not gcn:
-            x0 = b.no_model_gathered(model, n_dst_bottom).cpu().numpy()
-            assert np.array_equal(x0.view(feat.dtype), r.x0[:n_dst_bottom])
-        # floats
-        assert abs(st.loss - r.loss) <= RTOL * abs(r.loss) + 1e-6, (st.loss, r.loss)
-        for l in range(1, w.n_layers + 1):
-            n_rows = r.h[l - 1].shape[0]
-            n_dst = r.batch.blocks[w.n_layers - l].n_dst
-            gh, gm = b.no_model_activations(model, l, n_rows, n_dst)
-            assert_close(gm.cpu().numpy(), r.mean[l - 1], "mean%d step %d" % (l, step))
-            assert_close(gh.cpu().numpy(), r.h[l - 1], "h%d step %d" % (l, step))
-            names = ["gw", "gbias"] if gcn else ["gw_self", "gw_neigh", "gbias"]
-            for t, ref, name in zip(pick(b.no_model_grads(model, l)), r.grads[l - 1], names):
-                assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step))
-            for t, ref, name in zip(pick(b.no_model_params(model, l)), r.new_weights[l - 1], names):
-                assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name[1:], l, step))
         if superbatch and not ahead:
             # weight-drift monitor (Section 4.3): largest change of a layer-1 parameter in this update, and the drift
             # from the parameters behind the rows now in the cache
