@@ -351,44 +351,80 @@ def sage_layer_bwd(blk: Block, x_src: np.ndarray, mean: np.ndarray, h: np.ndarra
     return gw_self, gw_neigh, gb, gx
 
 
-def gcn_aggregate(x_src: np.ndarray, indptr: np.ndarray, indices: np.ndarray, n_dst: int) -> np.ndarray:
-    """Eq. 1 as printed, AGGREGATE = average over N_in(v) U {v}: a_v = (x_v + sum of the sampled row) / (len + 1).
-    Destination v is source row v of the block."""
+GCN_NORMS = ("mean", "sum", "sym")
+
+
+def gcn_norm_of(arch: str) -> str:
+    """Layer-form name -> normalisation of the GCN-style aggregate: "gcn" (average), "gcn_sum", "gcn_sym"."""
+    return {"gcn": "mean", "gcn_sum": "sum", "gcn_sym": "sym"}[arch]
+
+
+def gcn_scales(indptr: np.ndarray, indices: np.ndarray, n_dst: int, n_src: int, norm: str):
+    """Row scale r_v and source scale s_u of the GCN-style aggregate a_v = r_v (s_v x_v + sum_{u in row v} s_u x_u)
+    over the sampled block with self loops, A~ = A_i + I (destination v is source row v):
+      "mean": r = 1 / (len + 1), s = 1            (AGGREGATE = average, Eq. 1)
+      "sum":  r = 1, s = 1                        (AGGREGATE = sum, Eq. 1)
+      "sym":  r = (len + 1)^-1/2, s_u = c_u^-1/2  (symmetric normalisation, Table 1: A^ = D_r^-1/2 A~ D_c^-1/2 with D_r the
+              row sums of A~, len + 1, and D_c its column sums, c_u = number of sampled edges that leave u, plus one
+              if u is a destination). A source no edge leaves and that is no destination has weight 0 (it is in no sum).
+    """
+    ln = np.diff(np.asarray(indptr[: n_dst + 1], dtype=np.int64)).astype(np.float64)
+    nnz = int(indptr[n_dst])
+    if norm == "mean":
+        return 1.0 / (ln + 1.0), np.ones(n_src)
+    if norm == "sum":
+        return np.ones(n_dst), np.ones(n_src)
+    if norm == "sym":
+        c = np.bincount(np.asarray(indices[:nnz], dtype=np.int64), minlength=n_src).astype(np.float64)
+        c[:n_dst] += 1.0
+        s = np.zeros(n_src)
+        s[c > 0] = c[c > 0] ** -0.5
+        return (ln + 1.0) ** -0.5, s
+    raise ValueError(norm)
+
+
+def gcn_aggregate(x_src: np.ndarray, indptr: np.ndarray, indices: np.ndarray, n_dst: int, norm: str = "mean") -> np.ndarray:
+    """Eq. 1 as printed, over N_in(v) U {v} of the sampled block: a_v = r_v (s_v x_v + sum over the sampled row of
+    s_u x_u), with the scales of `gcn_scales`. Destination v is source row v of the block."""
     x = np.asarray(x_src, dtype=np.float64)
+    r, s = gcn_scales(indptr, indices, n_dst, x.shape[0], norm)
     ln = np.diff(np.asarray(indptr[: n_dst + 1], dtype=np.int64))
-    out = x[:n_dst].copy()
+    xs = x * s[:, None]
+    out = xs[:n_dst].copy()
     rows = np.repeat(np.arange(n_dst), ln)
-    np.add.at(out, rows, x[np.asarray(indices[: ln.sum()], dtype=np.int64)])
-    return out / (ln + 1.0)[:, None]
+    np.add.at(out, rows, xs[np.asarray(indices[: ln.sum()], dtype=np.int64)])
+    return out * r[:, None]
 
 
 def gcn_aggregate_adjoint(grad_a: np.ndarray, indptr: np.ndarray, indices: np.ndarray, n_dst: int,
-                          n_src: int) -> np.ndarray:
+                          n_src: int, norm: str = "mean") -> np.ndarray:
     g = np.asarray(grad_a, dtype=np.float64)
+    r, s = gcn_scales(indptr, indices, n_dst, n_src, norm)
     ln = np.diff(np.asarray(indptr[: n_dst + 1], dtype=np.int64))
-    gs = g / (ln + 1.0)[:, None]
+    gs = g * r[:, None]
     out = np.zeros((n_src, g.shape[1]), dtype=np.float64)
     out[:n_dst] += gs
     rows = np.repeat(np.arange(n_dst), ln)
     np.add.at(out, np.asarray(indices[: ln.sum()], dtype=np.int64), gs[rows])
-    return out
+    return out * s[:, None]
 
 
-def gcn_layer_fwd_z(blk: Block, x_src: np.ndarray, w, bias, relu: bool):
-    """GCN-style layer: Eq. 1 over N_in(v) U {v} (average), Eq. 2 with one weight matrix. Returns (a, z, h)."""
-    a = gcn_aggregate(x_src, blk.indptr, blk.indices, blk.n_dst)
+def gcn_layer_fwd_z(blk: Block, x_src: np.ndarray, w, bias, relu: bool, norm: str = "mean"):
+    """GCN-style layer: Eq. 1 over N_in(v) U {v} (average, sum or symmetric normalisation), Eq. 2 with one weight
+    matrix. Returns (a, z, h)."""
+    a = gcn_aggregate(x_src, blk.indptr, blk.indices, blk.n_dst, norm)
     z = a @ np.asarray(w, np.float64) + np.asarray(bias, np.float64)
     h = np.maximum(z, 0.0) if relu else z
     return a, z, h
 
 
-def gcn_layer_fwd(blk: Block, x_src: np.ndarray, w, bias, relu: bool):
-    a, _, h = gcn_layer_fwd_z(blk, x_src, w, bias, relu)
+def gcn_layer_fwd(blk: Block, x_src: np.ndarray, w, bias, relu: bool, norm: str = "mean"):
+    a, _, h = gcn_layer_fwd_z(blk, x_src, w, bias, relu, norm)
     return a, h
 
 
 def gcn_layer_bwd(blk: Block, a: np.ndarray, h: np.ndarray, grad_h: np.ndarray, w, relu: bool, need_grad_x: bool,
-                  active: Optional[np.ndarray] = None):
+                  active: Optional[np.ndarray] = None, norm: str = "mean"):
     """Gradients of the GCN-style layer: (gw, gb, grad_x or None)."""
     if relu:
         gz = np.asarray(grad_h, np.float64) * ((np.asarray(h) > 0) if active is None else active)
@@ -398,7 +434,7 @@ def gcn_layer_bwd(blk: Block, a: np.ndarray, h: np.ndarray, grad_h: np.ndarray, 
     gb = gz.sum(axis=0)
     gx = None
     if need_grad_x:
-        gx = gcn_aggregate_adjoint(gz @ np.asarray(w, np.float64).T, blk.indptr, blk.indices, blk.n_dst, blk.n_src)
+        gx = gcn_aggregate_adjoint(gz @ np.asarray(w, np.float64).T, blk.indptr, blk.indices, blk.n_dst, blk.n_src, norm)
     return gw, gb, gx
 
 
@@ -439,8 +475,9 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
                weights, lr: float, seed: int, step: int, cache: Optional[Cache] = None,
                feat_is_bf16: bool = False, relu_decisions=None, arch: str = "sage") -> StepResult:
     """One pass of Algorithm 1's loop body with plain SGD; updates `cache` in place.
-    arch "sage": GraphSAGE-mean layers, weights[l] = (w_self, w_neigh, bias); arch "gcn": layers that average
-    over N_in(v) U {v} with one matrix, weights[l] = (w, bias); `mean` then holds that aggregate.
+    arch "sage": GraphSAGE-mean layers, weights[l] = (w_self, w_neigh, bias); arch "gcn" / "gcn_sum" / "gcn_sym":
+    layers that aggregate over N_in(v) U {v} (average / sum / symmetric normalisation) with one matrix,
+    weights[l] = (w, bias); `mean` then holds that aggregate.
     relu_decisions: optional callable(layer, z_layer) -> bool array or None, consulted in the backward
     pass for the ReLU decisions of layer `layer` given its pre-activations (rows of the computed vertices)."""
     L = len(fanouts)
@@ -453,8 +490,8 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
     for l in range(1, L + 1):
         blk = sb.blocks[L - l]
         xs.append(x)
-        if arch == "gcn":
-            mean, z, h = gcn_layer_fwd_z(blk, x, weights[l - 1][0], weights[l - 1][1], relu=(l < L))
+        if arch != "sage":
+            mean, z, h = gcn_layer_fwd_z(blk, x, weights[l - 1][0], weights[l - 1][1], relu=(l < L), norm=gcn_norm_of(arch))
         else:
             w_self, w_neigh, bias = weights[l - 1]
             mean, z, h = sage_layer_fwd_z(blk, x, w_self, w_neigh, bias, relu=(l < L))
@@ -479,9 +516,9 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
             h_l = h_l[sb.compute_pos]
             gh = gh[sb.compute_pos]        # reused rows take no gradient
         active = relu_decisions(l, zs[l - 1]) if (relu_decisions is not None and l < L) else None
-        if arch == "gcn":
+        if arch != "sage":
             gw, gb, gx = gcn_layer_bwd(blk, means[l - 1], h_l, gh, weights[l - 1][0], relu=(l < L),
-                                       need_grad_x=(l > 1), active=active)
+                                       need_grad_x=(l > 1), active=active, norm=gcn_norm_of(arch))
             grads[l - 1] = (gw, gb)
         else:
             w_self, w_neigh, _ = weights[l - 1]
@@ -503,7 +540,7 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
 # --------------------------------------------------------------------------- bulk refresh (Section 4.2)
 
 def refresh_hot(g: Graph, feat: np.ndarray, cache: Cache, layer1_weights, fanout: int, version: int, seed: int,
-                feat_is_bf16: bool = False):
+                feat_is_bf16: bool = False, norm: str = "mean"):
     """Stage 2 of Section 4.2 for one super-batch: the layer-1 embedding of EVERY hot vertex, from a one-hop
     sample at the bottom fanout and the given (snapshot of the) layer-1 parameters. Row i belongs to
     hot_ids[i]. Returns the pending cache contents (emb [n_hot, d1] fp64, version [n_hot] = `version`);
@@ -512,7 +549,7 @@ def refresh_hot(g: Graph, feat: np.ndarray, cache: Cache, layer1_weights, fanout
     blk = sample_hop(g, cache.hot_ids, fanout, _u64(seed + version), DOMAIN_REFRESH, 0)
     x = _to_f64(gather_features(feat, blk.src_global), feat_is_bf16)
     if len(layer1_weights) == 2:          # GCN-style layer: (w, bias)
-        _, h = gcn_layer_fwd(blk, x, layer1_weights[0], layer1_weights[1], relu=True)
+        _, h = gcn_layer_fwd(blk, x, layer1_weights[0], layer1_weights[1], relu=True, norm=norm)
     else:
         w_self, w_neigh, bias = layer1_weights
         _, h = sage_layer_fwd(blk, x, w_self, w_neigh, bias, relu=True)
@@ -539,7 +576,8 @@ def train_superbatches(g: Graph, feat: np.ndarray, labels: np.ndarray, batches: 
         if t % n == 0:
             if pending is not None:
                 commit_refresh(cache, *pending)
-            pending = refresh_hot(g, feat, cache, weights[0], fanouts[-1], t, seed, feat_is_bf16)
+            pending = refresh_hot(g, feat, cache, weights[0], fanouts[-1], t, seed, feat_is_bf16,
+                                  norm="mean" if arch == "sage" else gcn_norm_of(arch))
         r = train_step(g, feat, labels, seeds, fanouts, weights, lr, seed, t, cache, feat_is_bf16, arch=arch)
         if on_step is not None:
             on_step(t, r, cache)
