@@ -53,8 +53,9 @@ def main():
     ap.add_argument("--no-ahead", action="store_true",
                     help="throughput pass with no_train_step (sample, then train) instead of no_train_step_ahead "
                          "(batch t+1 sampled on a second stream while batch t trains)")
-    ap.add_argument("--arch", choices=["sage", "gcn"], default="sage",
-                    help="layer form: GraphSAGE-mean (the headline configuration) or the GCN-style layer")
+    ap.add_argument("--arch", choices=["sage", "gcn", "gcn_sum", "gcn_sym"], default="sage",
+                    help="layer form: GraphSAGE-mean (the headline configuration) or a GCN-style layer (average, sum, "
+                         "symmetric normalisation)")
     ap.add_argument("--batch", type=int, default=0,
                     help="seeds per batch instead of the workload's (the paper's batch-size sweep, 256 .. 10000)")
     ap.add_argument("--fanouts", default="",
@@ -139,9 +140,11 @@ def main():
         t_hot = time.time() - t0
         log("[bench] no_select_hot (%d pre-sampling epochs): %.2fs" % (args.presample_epochs, t_hot))
     model = b.no_model_create(g, w.dims, w.batch, w.fanouts, b.NO_BF16 if bf16 else b.NO_F32)
-    gcn = args.arch == "gcn"
+    gcn = args.arch != "sage"
     if gcn:
-        b.no_model_set_arch(model, b.NO_ARCH_GCN)
+        b.no_model_set_arch(model, b.ARCH_OF_NAME[args.arch])
+        if cache is not None:
+            b.no_cache_set_layer_form(cache, b.ARCH_OF_NAME[args.arch])
 
     def load_weights():
         for l in range(w.n_layers):
@@ -416,7 +419,7 @@ def main():
         "config": {"workload": "%s: R-MAT %d vertices / %d directed edges, %d x %s features, %d classes, %d-layer "
                                "%s hidden %d, fanout %s, batch %d, hot %.0f%%, S=%d"
                                % (w.name, w.n_vertices, n_edges_made, w.feat_dim, w.feat_dtype, w.n_classes, w.n_layers,
-                                  "GCN-style" if gcn else "GraphSAGE-mean", w.hidden, list(w.fanouts), w.batch, 0.0 if cache is None else 100 * w.hot_fraction,
+                                  ("GCN-style (%s)" % args.arch) if gcn else "GraphSAGE-mean", w.hidden, list(w.fanouts), w.batch, 0.0 if cache is None else 100 * w.hot_fraction,
                                   w.staleness),
                    "hot_reuse": cache is not None},
         "roofline": roofline, "cpu_baseline": cpu, "extra": extra,
@@ -449,7 +452,7 @@ def cpu_baseline(cw, src, dst, feat, lab, train, weights, with_cache, args, gcn,
                             cw.hidden, cw.seed)
     log("[bench] oracle setup (CSR + hot set): %.1fs" % (time.time() - t0))
     ow = [tuple(np.asarray(t, np.float64) for t in ((x[0], x[2]) if gcn else x)) for x in weights]
-    arch = "gcn" if gcn else "sage"
+    arch = args.arch
     state = {"w": ow, "t": 0}
 
     def steps(n):

@@ -39,9 +39,15 @@ enum {
 };
 
 typedef enum { NO_F32 = 0, NO_BF16 = 1 } no_dtype;
-/* Layer form: GraphSAGE-mean (separate self path, two matrices) or GCN-style (Eq. 1 as printed: the average runs
- * over N_in(v) U {v}; Eq. 2 with one matrix). */
-typedef enum { NO_ARCH_SAGE_MEAN = 0, NO_ARCH_GCN = 1 } no_arch;
+/* Layer form: GraphSAGE-mean (separate self path, two matrices) or GCN-style (Eq. 1 as printed: the aggregate runs
+ * over N_in(v) U {v}; Eq. 2 with one matrix). The GCN-style aggregate a_v = r_v (s_v x_v + sum over the sampled row of
+ * s_u x_u) comes in the forms Eq. 1 and Table 1 name:
+ *   NO_ARCH_GCN      average:  r_v = 1 / (len(row v) + 1), s = 1
+ *   NO_ARCH_GCN_SUM  sum:      r = s = 1
+ *   NO_ARCH_GCN_SYM  symmetric normalisation of the block's adjacency with self loops, D_r^-1/2 (A + I) D_c^-1/2:
+ *                    r_v = (len(row v) + 1)^-1/2, s_u = c_u^-1/2 with c_u = number of the block's edges that leave
+ *                    source u, plus one if u is a destination (row and column sums of A + I). */
+typedef enum { NO_ARCH_SAGE_MEAN = 0, NO_ARCH_GCN = 1, NO_ARCH_GCN_SUM = 2, NO_ARCH_GCN_SYM = 3 } no_arch;
 
 enum { NO_MAX_LAYERS = 8, NO_MAX_FANOUT = 64 };
 
@@ -149,6 +155,8 @@ int32_t no_cache_view(no_cache_t c, int64_t* n_hot, int32_t* staleness, int32_t*
                       const int32_t** d_hot_ids, const int32_t** d_slot_of_vertex,
                       int32_t** d_version, float** d_emb, const int32_t** d_freq);
 int32_t no_cache_set_staleness(no_cache_t c, int32_t staleness);
+/* Which GCN-style form no_refresh_hot_begin computes when it is given one matrix (default NO_ARCH_GCN, the average). */
+int32_t no_cache_set_layer_form(no_cache_t c, no_arch form);
 int32_t no_cache_invalidate(no_cache_t c, void* stream);   /* all versions = -1 */
 int32_t no_cache_destroy(no_cache_t c);
 
@@ -168,7 +176,7 @@ int32_t no_cache_destroy(no_cache_t c);
  * (dt, feat_dim, fanout) for later calls. Errors: NO_ERR_INVALID_ARG (NULL, bad sizes, another refresh still
  * pending, parameters differing from the first call), NO_ERR_OVERFLOW (n_hot * (fanout + 1) >= 2^31),
  * NO_ERR_HIP. A cache without hot vertices makes both calls no-ops. d_w_neigh == NULL selects the GCN-style
- * layer (one matrix d_w_self, average over N_in(v) U {v}).
+ * layer (one matrix d_w_self, aggregate over N_in(v) U {v} in the form set by no_cache_set_layer_form).
  *
  * no_refresh_hot_commit: `stream` waits for the pending refresh, then the pending rows and versions
  * become the cache's contents (the two copies are swapped: pointers returned by no_cache_view before the
@@ -233,16 +241,19 @@ int32_t no_sage_layer_bwd_static(const no_block_view* blk, const void* d_x_src, 
                                  float* d_gw_self, float* d_gw_neigh, float* d_gbias, float* d_grad_x_src,
                                  void* stream);
 
-/* GCN-style layer (Eq. 1 as printed, AGGREGATE = average over N_in(v) U {v}; Eq. 2 with one matrix).
- * Forward: d_agg[v,:] = (d_x_src[v,:] + sum of d_x_src[indices[e],:] over row v) / (len(row v) + 1) (destination
- * v is source row v); d_h = act(d_agg * W + bias). Shapes, dtypes, workspace and errors as no_sage_layer_fwd.
- * Backward: gz as above; d_gw = agg^T gz, d_gbias = column sums of gz; if d_grad_x_src != NULL:
- * with ga[v,:] = (gz[v,:] W^T) / (len(row v) + 1): d_grad_x_src[u,:] = [u < n_dst] ga[u,:] + sum of ga[v,:] over the
- * transposed entries (v,e) of u. The workspace size is no_sage_layer_ws_bytes. */
-int32_t no_gcn_layer_fwd(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+/* GCN-style layer (Eq. 1 as printed, AGGREGATE over N_in(v) U {v}; Eq. 2 with one matrix); `form` is one of
+ * NO_ARCH_GCN (average), NO_ARCH_GCN_SUM, NO_ARCH_GCN_SYM (Table 1's symmetric normalisation), see no_arch.
+ * Forward: d_agg[v,:] = r_v (s_v d_x_src[v,:] + sum of s_u d_x_src[u,:] over the entries u = indices[e] of row v)
+ * (destination v is source row v); d_h = act(d_agg * W + bias). Shapes, dtypes, workspace and errors as
+ * no_sage_layer_fwd. Backward: gz as above; d_gw = agg^T gz, d_gbias = column sums of gz; if d_grad_x_src != NULL:
+ * with ga[v,:] = r_v (gz[v,:] W^T): d_grad_x_src[u,:] = s_u ([u < n_dst] ga[u,:] + sum of ga[v,:] over the transposed
+ * entries (v,e) of u). NO_ARCH_GCN_SYM reads the column sums from the view's transpose (d_csc_indptr must be set:
+ * NO_ERR_INVALID_ARG otherwise), in the forward pass and for the input gradient. The workspace size is
+ * no_sage_layer_ws_bytes. */
+int32_t no_gcn_layer_fwd(const no_block_view* blk, no_arch form, const void* d_x_src, no_dtype dt_x, int32_t d_in,
                          const float* d_w, const float* d_bias, int32_t d_out, int32_t relu, float* d_agg,
                          float* d_h, void* d_ws, size_t ws_bytes, void* stream);
-int32_t no_gcn_layer_bwd(const no_block_view* blk, int32_t d_in, const float* d_agg, const float* d_h,
+int32_t no_gcn_layer_bwd(const no_block_view* blk, no_arch form, int32_t d_in, const float* d_agg, const float* d_h,
                          const float* d_grad_h, const float* d_w, int32_t d_out, int32_t relu, float* d_gw,
                          float* d_gbias, float* d_grad_x_src, void* d_ws, size_t ws_bytes, void* stream);
 
@@ -271,9 +282,9 @@ int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t* h_dims, i
                         const int32_t* h_fanouts, no_dtype feat_dtype, no_model_t* out);
 int32_t no_model_params(no_model_t m, int32_t layer /*1-based*/, float** d_w_self, float** d_w_neigh,
                         float** d_bias);
-/* Selects the layer form of every layer (default NO_ARCH_SAGE_MEAN); call before the first step. With
- * NO_ARCH_GCN layer l computes h = act(W^T a + b), a_v = (x_v + sum of the sampled row) / (len + 1) (Eq. 1 over
- * N_in(v) U {v}, AGGREGATE = average; Eq. 2): W is the layer's w_self array, w_neigh and its gradient are unused,
+/* Selects the layer form of every layer (default NO_ARCH_SAGE_MEAN); call before the first step. With a GCN-style
+ * form (NO_ARCH_GCN, NO_ARCH_GCN_SUM, NO_ARCH_GCN_SYM) layer l computes h = act(W^T a + b) with the aggregate a of
+ * that form over N_in(v) U {v} (Eq. 1; Eq. 2): W is the layer's w_self array, w_neigh and its gradient are unused,
  * the `mean` activation holds a, and no_model_gathered is not filled (the aggregation reads the table itself). */
 int32_t no_model_set_arch(no_model_t m, no_arch arch);
 /* Gradients of the last step, device pointers (same shapes as the parameters). */

@@ -18,7 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libneutronorch.so")
 
 NO_F32, NO_BF16 = 0, 1
-NO_ARCH_SAGE_MEAN, NO_ARCH_GCN = 0, 1
+NO_ARCH_SAGE_MEAN, NO_ARCH_GCN, NO_ARCH_GCN_SUM, NO_ARCH_GCN_SYM = 0, 1, 2, 3
+ARCH_OF_NAME = {"sage": NO_ARCH_SAGE_MEAN, "gcn": NO_ARCH_GCN, "gcn_sum": NO_ARCH_GCN_SUM, "gcn_sym": NO_ARCH_GCN_SYM}
 NO_CSR_INPUT_ON_DEVICE = 1
 NO_MAX_LAYERS = 8
 ERROR_NAMES = {0: "NO_OK", -1: "NO_ERR_INVALID_ARG", -2: "NO_ERR_OUT_OF_RANGE", -3: "NO_ERR_CAPACITY",
@@ -79,8 +80,9 @@ _SIGNATURES = {
     "no_model_params": (_I32, [_P, _I32, _P, _P, _P]),
     "no_model_grads": (_I32, [_P, _I32, _P, _P, _P]),
     "no_model_set_arch": (_I32, [_P, _I32]),
-    "no_gcn_layer_fwd": (_I32, [_P, _P, _I32, _I32, _P, _P, _I32, _I32, _P, _P, _P, C.c_size_t, _P]),
-    "no_gcn_layer_bwd": (_I32, [_P, _I32, _P, _P, _P, _P, _I32, _I32, _P, _P, _P, _P, C.c_size_t, _P]),
+    "no_gcn_layer_fwd": (_I32, [_P, _I32, _P, _I32, _I32, _P, _P, _I32, _I32, _P, _P, _P, C.c_size_t, _P]),
+    "no_gcn_layer_bwd": (_I32, [_P, _I32, _I32, _P, _P, _P, _P, _I32, _I32, _P, _P, _P, _P, C.c_size_t, _P]),
+    "no_cache_set_layer_form": (_I32, [_P, _I32]),
     "no_model_activations": (_I32, [_P, _I32, _P, _P]),
     "no_model_blocks": (_I32, [_P, _P]),
     "no_model_gathered": (_I32, [_P, _P]),
@@ -323,6 +325,10 @@ def no_cache_set_staleness(c: Cache, staleness: int):
     _check(lib().no_cache_set_staleness(c.h, staleness))
 
 
+def no_cache_set_layer_form(c: Cache, form: int):
+    _check(lib().no_cache_set_layer_form(c.h, form))
+
+
 def no_cache_invalidate(c: Cache, stream=None):
     _check(lib().no_cache_invalidate(c.h, _stream(stream)))
 
@@ -410,18 +416,18 @@ def no_sage_layer_bwd_static(blk: no_block_view, x_src: torch.Tensor, mean: torc
 
 
 def no_gcn_layer_fwd(blk: no_block_view, x_src: torch.Tensor, w: torch.Tensor, bias: torch.Tensor, relu: bool,
-                     agg: torch.Tensor, h: torch.Tensor, ws: torch.Tensor, stream=None):
+                     agg: torch.Tensor, h: torch.Tensor, ws: torch.Tensor, stream=None, form: int = NO_ARCH_GCN):
     d_in, d_out = w.shape
-    _check(lib().no_gcn_layer_fwd(C.byref(blk), x_src.data_ptr(), _dtype_code(x_src), d_in, w.data_ptr(), bias.data_ptr(),
+    _check(lib().no_gcn_layer_fwd(C.byref(blk), form, x_src.data_ptr(), _dtype_code(x_src), d_in, w.data_ptr(), bias.data_ptr(),
                                   d_out, 1 if relu else 0, agg.data_ptr(), h.data_ptr(), ws.data_ptr(),
                                   ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def no_gcn_layer_bwd(blk: no_block_view, agg: torch.Tensor, h: torch.Tensor, grad_h: torch.Tensor, w: torch.Tensor,
                      relu: bool, gw: torch.Tensor, gbias: torch.Tensor, grad_x_src: Optional[torch.Tensor],
-                     ws: torch.Tensor, stream=None):
+                     ws: torch.Tensor, stream=None, form: int = NO_ARCH_GCN):
     d_in, d_out = w.shape
-    _check(lib().no_gcn_layer_bwd(C.byref(blk), d_in, agg.data_ptr(), h.data_ptr(), grad_h.data_ptr(), w.data_ptr(), d_out,
+    _check(lib().no_gcn_layer_bwd(C.byref(blk), form, d_in, agg.data_ptr(), h.data_ptr(), grad_h.data_ptr(), w.data_ptr(), d_out,
                                   1 if relu else 0, gw.data_ptr(), gbias.data_ptr(), _ptr(grad_x_src), ws.data_ptr(),
                                   ws.numel() * ws.element_size(), _stream(stream)))
 

@@ -459,7 +459,10 @@ __global__ void __launch_bounds__(256, OCC) gemm_nn_kernel(GemmNNArgs g) {
         crow[j] = c_rows ? c_rows[row] : row;
         krow[j] = c_keep_rows ? c_keep_rows[row] : -1;
         scale[j] = 1.f;
-        if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale[j] = len > 0 ? 1.f / (float)len : 0.f; }
+        if (sp) {
+            const int len = sp[row + 1] - sp[row] + g.row_scale_plus;
+            scale[j] = len > 0 ? (g.row_scale_rsqrt ? 1.f / sqrtf((float)len) : 1.f / (float)len) : 0.f;
+        }
     }
     {
         const int q0 = g.accumulate ? 0 : prob, q1 = g.accumulate && n_phases > 1 ? 1 : q0;
@@ -535,7 +538,10 @@ __global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
         krow[i] = c_keep_rows ? c_keep_rows[row] : -1;
         bias_v[i] = g.bias ? g.bias[col] : 0.f;
         scale[i] = 1.f;
-        if (sp) { const int len = sp[row + 1] - sp[row] + g.row_scale_plus; scale[i] = len > 0 ? 1.f / (float)len : 0.f; }
+        if (sp) {
+            const int len = sp[row + 1] - sp[row] + g.row_scale_plus;
+            scale[i] = len > 0 ? (g.row_scale_rsqrt ? 1.f / sqrtf((float)len) : 1.f / (float)len) : 0.f;
+        }
     }
     floatx16 acc, acc2;                       // two sets, so consecutive MFMAs of a round do not depend on each other
 #pragma unroll

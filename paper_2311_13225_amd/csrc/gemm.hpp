@@ -18,6 +18,7 @@ struct GemmNNArgs {
     float* C[2]; int64_t ldc[2];
     const int32_t* row_scale_indptr[2];   // per problem: multiply row m by 1/(indptr[m+1]-indptr[m]+row_scale_plus) (0 if that is 0)
     int32_t row_scale_plus;               // 1 when the row itself counts in the average (Eq. 1 over N_in(v) U {v})
+    int32_t row_scale_rsqrt;              // 1: the factor is that count to the power -1/2 (symmetric normalisation)
     int32_t n_problems;                   // 1 or 2
     int32_t accumulate;                   // 1: both products are summed into C[0]; 0: independent problems (grid.z)
     const int32_t* d_M; int32_t M_cap; int32_t N;

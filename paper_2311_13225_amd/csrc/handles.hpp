@@ -36,6 +36,8 @@ struct no_blocks_s {
     int32_t n_seeds_cap = 0;
     int64_t n_vertices = 0;
     bool build_csc = true;             // transpose hops 0..L-2 (select_hot's private blocks skip it)
+    bool count_sources = false;        // count the edges that leave each source in every hop, the bottom one too
+                                       // (column sums of the symmetric normalisation)
     no::HopBuffers hop[NO_MAX_LAYERS];
     // counts[4*h + {0,1,2}] = n_dst, n_src, nnz of hop h; counts[4*L + {0,1,4}] = n_compute, n_hit, n_refresh;
     // counts[4*L + {5,6,7}] = flag words (bad seed id, a scan's bounded wait expired, bad label): a kernel that meets
@@ -122,6 +124,7 @@ struct no_cache_s {
     uint64_t uid = 0;                  // unique per cache ever created (an address may be reused after a destroy)
     uint64_t generation = 0;           // bumped by a refresh commit, an invalidate and a change of the bound
     uint64_t contents = 0;             // bumped by a refresh commit and an invalidate (all versions replaced)
+    int32_t gcn_form = NO_ARCH_GCN;    // the GCN-style form a one-matrix bulk refresh computes
     RefreshState* refresh = nullptr;
     void release() {
         if (refresh) { refresh->release(); delete refresh; refresh = nullptr; }

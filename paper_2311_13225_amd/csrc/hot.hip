@@ -172,6 +172,16 @@ extern "C" int32_t no_cache_set_staleness(no_cache_t c, int32_t staleness) {
     return NO_OK;
 }
 
+extern "C" int32_t no_cache_set_layer_form(no_cache_t c, no_arch form) {
+    clear_error();
+    NO_REQUIRE(c != nullptr, NO_ERR_INVALID_ARG, "no_cache_set_layer_form: cache is NULL");
+    NO_REQUIRE(form == NO_ARCH_GCN || form == NO_ARCH_GCN_SUM || form == NO_ARCH_GCN_SYM, NO_ERR_INVALID_ARG,
+               "no_cache_set_layer_form: not a GCN-style form");
+    NO_REQUIRE(!(c->refresh && c->refresh->pending), NO_ERR_INVALID_ARG, "no_cache_set_layer_form: a refresh is pending");
+    c->gcn_form = form;
+    return NO_OK;
+}
+
 extern "C" int32_t no_cache_invalidate(no_cache_t c, void* stream) {
     clear_error();
     NO_REQUIRE(c != nullptr, NO_ERR_INVALID_ARG, "no_cache_invalidate: cache is NULL");

@@ -53,6 +53,21 @@ struct RowCopyJob {
     uint32_t first_block = 0;             // set by the launcher
 };
 
+// How segment_rows_kernel combines a destination's row (forward aggregate, Eq. 1).
+enum { AGG_NEIGH_MEAN = 0,   // average of the sampled row (GraphSAGE-mean; the self path is a separate product)
+       AGG_SELF_MEAN = 1,    // over N_in(v) U {v}: average
+       AGG_SELF_SUM = 2,     //                     sum
+       AGG_SELF_SYM = 3 };   //                     symmetric normalisation (per-source weights)
+
+inline bool arch_is_gcn(int32_t arch) { return arch == NO_ARCH_GCN || arch == NO_ARCH_GCN_SUM || arch == NO_ARCH_GCN_SYM; }
+
+// Where the number of block edges that leave each source comes from (symmetric normalisation): counts per local
+// source, or the row pointers of the block's transpose (is_ptr); `local` maps entry p of the aggregated index array
+// to its local source when that array holds other ids (the fused layer-1 aggregate reads global ids).
+struct SourceWeights {
+    const int32_t* cnt = nullptr; int32_t is_ptr = 0; const int32_t* local = nullptr;
+};
+
 // Layer 1 with reuse (Section 4.1.2): where the computed rows go, which of them refresh the cache, and the reused
 // rows to copy in from the cache.
 struct Layer1Reuse {
@@ -70,20 +85,22 @@ struct BelowLayer { const float* h = nullptr; const int32_t* out_rows = nullptr;
 int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out);
 LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_t d_out);
 
-// with_self: the destination's own row (row r of x_src, or row self_idx[r]) joins the average (Eq. 1 over N_in(v) U {v})
+// agg_mode other than AGG_NEIGH_MEAN: the destination's own row (row r of x_src, or row self_idx[r]) joins the
+// aggregate (Eq. 1 over N_in(v) U {v})
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
-                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, bool with_self = false,
-                       const int32_t* self_idx = nullptr, const RowCopyJob* copy = nullptr, hipEvent_t ev0 = nullptr,
-                       hipEvent_t ev1 = nullptr);
+                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st,
+                       int32_t agg_mode = AGG_NEIGH_MEAN, const int32_t* self_idx = nullptr, const RowCopyJob* copy = nullptr,
+                       hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, const SourceWeights* weights = nullptr);
 int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
                             const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
                             hipStream_t st, const float* mask_h = nullptr, const int32_t* out_rows = nullptr,
-                            float* masked_out = nullptr);
+                            float* masked_out = nullptr, const SourceWeights* weights = nullptr);
 int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* w_self,
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int agg_stage = -1,
                      int gemm_stage = -1, const void* agg_table = nullptr, hipEvent_t wait_before_gemm = nullptr,
-                     int32_t arch = NO_ARCH_SAGE_MEAN, const Layer1Reuse* reuse = nullptr, bool aggregate_done = false);
+                     int32_t arch = NO_ARCH_SAGE_MEAN, const Layer1Reuse* reuse = nullptr, bool aggregate_done = false,
+                     const SourceWeights* weights = nullptr);
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
@@ -92,7 +109,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       const int32_t* grad_rows = nullptr, float lr = 0.f, float* w_self_rw = nullptr,
                       float* w_neigh_rw = nullptr, float* bias_rw = nullptr, int32_t arch = NO_ARCH_SAGE_MEAN,
                       const StatsJob* stats_job = nullptr, const float* gz_in = nullptr,
-                      const BelowLayer* below = nullptr, GradJobs* pending = nullptr, bool defer = false);
+                      const BelowLayer* below = nullptr, GradJobs* pending = nullptr, bool defer = false,
+                      const SourceWeights* weights = nullptr);
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
                     const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
 

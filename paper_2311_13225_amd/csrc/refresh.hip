@@ -44,7 +44,7 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
                                         int64_t version, uint64_t seed, void* stream) {
     clear_error();
     NO_REQUIRE(c && g && d_features && d_w_self && d_bias, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: NULL argument");
-    const int32_t arch = d_w_neigh ? NO_ARCH_SAGE_MEAN : NO_ARCH_GCN;       // one matrix: the GCN-style layer
+    const int32_t arch = d_w_neigh ? NO_ARCH_SAGE_MEAN : c->gcn_form;       // one matrix: the GCN-style layer
     NO_REQUIRE(dt == NO_F32 || dt == NO_BF16, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: unknown dtype");
     NO_REQUIRE(feat_dim >= 1, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: feat_dim must be positive");
     NO_REQUIRE(fanout >= 1 && fanout <= NO_MAX_FANOUT, NO_ERR_INVALID_ARG, "no_refresh_hot_begin: bad fanout");
@@ -80,6 +80,7 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
     sg.row_bytes = feat_dim * (dt == NO_BF16 ? 2 : 4);
     sg.out = r->x0.p;
     sg.needed_by_forward = true;
+    r->blocks->count_sources = arch == NO_ARCH_GCN_SYM;
     NO_CHECK(sample_blocks_impl(g, c->hot_ids.p, n_hot, seed + (uint64_t)version, 2u, 1, nullptr, 0, r->blocks, r->stream, true,
                                 bf16 ? &sg : nullptr));
     no_block_view view;
@@ -87,9 +88,11 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
     view.d_indices = view.d_nbr_global;        // aggregate straight from the table through the global ids
     LayerWorkspace w;
     w.x_dst_f32 = bf16 ? r->x_f32.p : nullptr;
+    SourceWeights sw;
+    if (arch == NO_ARCH_GCN_SYM) { sw.cnt = r->blocks->hop[0].csc_cnt.p; sw.local = r->blocks->hop[0].indices.p; }
     NO_CHECK(sage_forward(view, bf16 ? (const void*)r->x0.p : d_features, dt, feat_dim, w_self, w_neigh, bias, d_out, 1,
                           r->mean.p, r->emb_pending.p, w, r->stream, nullptr, -1, -1, d_features,
-                          bf16 ? r->blocks->ev_gather_done : nullptr, arch));
+                          bf16 ? r->blocks->ev_gather_done : nullptr, arch, nullptr, false, &sw));
     NO_CHECK(fill_i32(r->version_pending.p, (int32_t)version, n_hot, r->stream));
     NO_HIP_CHECK(hipEventRecord(r->ev_done, r->stream));
     r->pending = true;

@@ -52,24 +52,34 @@ template <> struct RowVec<uint16_t, 1> {
     static __device__ __forceinline__ void add(float (&acc)[1], const uint16_t* p) { acc[0] += bf16_to_f32(p[0]); }
 };
 
-// out[row, :] = init + scale * sum_{p in [seg[row], seg[row+1])} src[idx[p], :]
-//   MEAN: scale = 1/len (0 for an empty segment), init = 0            (forward aggregate); with_self: the
-//         row's own source row is added first and scale = 1/(len + 1)
-//   else: scale = 1, init = out[row,:] for row < *d_n_init, else 0    (backward through the transpose)
+// Per-source weights of the symmetric normalisation (Table 1: the adjacency matrix after symmetric normalisation, here
+// of the sampled block with self loops): s_u = (c_u + [u < n_self])^-1/2, c_u = number of the block's edges that leave u.
+__device__ __forceinline__ float source_weight(const SourceWeights& sw, int32_t u, int32_t n_self) {
+    const int32_t c = (sw.is_ptr ? sw.cnt[u + 1] - sw.cnt[u] : sw.cnt[u]) + (u < n_self ? 1 : 0);
+    return c > 0 ? 1.f / sqrtf((float)c) : 0.f;
+}
+
+// out[row, :] = init + scale * sum_{p in [seg[row], seg[row+1])} w_p * src[idx[p], :]
+//   MEAN: init = 0 and, by agg_mode: AGG_NEIGH_MEAN scale = 1/len (0 for an empty segment): forward aggregate of the
+//         GraphSAGE-mean layer. The other modes add the row's own source row first (Eq. 1 over N_in(v) U {v}):
+//         AGG_SELF_MEAN scale = 1/(len + 1); AGG_SELF_SUM scale = 1; AGG_SELF_SYM scale = (len + 1)^-1/2 and every term
+//         (the self row included) is weighed by its source's s_u (WEIGHTED).
+//   else: scale = 1, w = 1, init = out[row,:] for row < *d_n_init, else 0 (backward through the transpose); WEIGHTED: the
+//         result is multiplied by s_row (the adjoint of the forward weights, row = source).
 // A group of G = 2^g_log2 lanes owns one work item = (row, chunk of G vector units); a lane owns one
 // vector unit of it. Rows wider than 64 units are split into several items handled by different
 // wavefronts, so a wide row keeps many short independent load chains in flight instead of one long one;
 // the items of a row are consecutive, which keeps the reads of a source row next to each other in time.
 // Up to eight source rows are loaded before the first add; the adds stay in segment order.
-template <typename T, int VEC, bool MEAN>
+template <typename T, int VEC, bool MEAN, bool WEIGHTED>
 __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const T* __restrict__ src, int64_t ld_src,
                                                            const int32_t* __restrict__ seg, const int32_t* __restrict__ idx,
                                                            const int32_t* d_n_rows, int32_t n_rows_cap,
                                                            const int32_t* d_n_init, float* __restrict__ out, int64_t ld_out,
                                                            int32_t units, int32_t g_log2, int32_t n_chunks,
-                                                           const int32_t* __restrict__ self_idx, int32_t with_self,
+                                                           const int32_t* __restrict__ self_idx, int32_t agg_mode,
                                                            const float* __restrict__ mask_h, const int32_t* __restrict__ out_rows,
-                                                           float* __restrict__ masked_out) {
+                                                           float* __restrict__ masked_out, SourceWeights sw) {
     if (job.dst && blockIdx.x >= job.first_block) {
         // extra blocks of the launch: dst[dst_rows[i], :] = src[src_rows[i], :], one wavefront per row (rows that are
         // ready before this kernel's own output is, e.g. the cached layer-1 rows of the reused vertices)
@@ -93,6 +103,7 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const
     const int32_t items_per_pass = 64 >> g_log2;
     const int32_t sub = lane >> g_log2, u0 = lane & ((1 << g_log2) - 1);
     const int64_t n_items = (int64_t)n * n_chunks;
+    const bool with_self = MEAN && agg_mode != AGG_NEIGH_MEAN;
     for (int64_t item = wave * items_per_pass + sub; item < n_items; item += n_waves * items_per_pass) {
         const int64_t row = item / n_chunks;
         const int32_t u = (int32_t)(item - row * n_chunks) * (1 << g_log2) + u0;
@@ -103,10 +114,16 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const
         float acc[VEC];
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
-        if (MEAN && with_self) {
-            // Eq. 1 over N_in(v) U {v}: the destination's own row (row `row` of src, or self_idx[row]) joins the average
+        if (with_self) {
+            // Eq. 1 over N_in(v) U {v}: the destination's own row (row `row` of src, or self_idx[row]) joins the aggregate
             RowVec<T, VEC>::add(acc, col + (int64_t)(self_idx ? self_idx[row] : (int32_t)row) * ld_src);
-            scale = 1.f / (float)(e - b + 1);
+            if (WEIGHTED) {
+                const float ws = source_weight(sw, (int32_t)row, n);
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] *= ws;
+            }
+            scale = agg_mode == AGG_SELF_MEAN ? 1.f / (float)(e - b + 1)
+                  : agg_mode == AGG_SELF_SUM  ? 1.f : 1.f / sqrtf((float)(e - b + 1));
         }
         float* o = out + row * ld_out + (int64_t)u * VEC;
         if (!MEAN && row < n_init) {
@@ -144,6 +161,11 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const
             int32_t ix[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) ix[j] = idx[p + j];
+            float wt[8];
+            if (MEAN && WEIGHTED) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) wt[j] = source_weight(sw, sw.local ? sw.local[p + j] : ix[j], n);
+            }
             float a[8][VEC];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -154,12 +176,17 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const
 #pragma unroll
             for (int j = 0; j < 8; ++j)
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) acc[c] += a[j][c];
+                for (int c = 0; c < VEC; ++c) acc[c] += (MEAN && WEIGHTED) ? wt[j] * a[j][c] : a[j][c];
         }
         if (p + 4 <= e) {
             int32_t ix[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) ix[j] = idx[p + j];
+            float wt[4];
+            if (MEAN && WEIGHTED) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) wt[j] = source_weight(sw, sw.local ? sw.local[p + j] : ix[j], n);
+            }
             float a[4][VEC];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -170,11 +197,17 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) acc[c] += a[j][c];
+                for (int c = 0; c < VEC; ++c) acc[c] += (MEAN && WEIGHTED) ? wt[j] * a[j][c] : a[j][c];
             p += 4;
         }
         if (p < e) {        // one to three rows left
             const int32_t i0 = idx[p], i1 = p + 1 < e ? idx[p + 1] : i0, i2 = p + 2 < e ? idx[p + 2] : i0;
+            float w0 = 1.f, w1 = 1.f, w2 = 1.f;
+            if (MEAN && WEIGHTED) {
+                w0 = source_weight(sw, sw.local ? sw.local[p] : i0, n);
+                w1 = p + 1 < e ? source_weight(sw, sw.local ? sw.local[p + 1] : i1, n) : 0.f;
+                w2 = p + 2 < e ? source_weight(sw, sw.local ? sw.local[p + 2] : i2, n) : 0.f;
+            }
             float a[3][VEC];
 #pragma unroll
             for (int j = 0; j < 3; ++j)
@@ -184,7 +217,14 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const
             if (p + 1 < e) RowVec<T, VEC>::add(a[1], col + (int64_t)i1 * ld_src);
             if (p + 2 < e) RowVec<T, VEC>::add(a[2], col + (int64_t)i2 * ld_src);
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) acc[c] = ((acc[c] + a[0][c]) + a[1][c]) + a[2][c];
+            for (int c = 0; c < VEC; ++c)
+                acc[c] = (MEAN && WEIGHTED) ? ((acc[c] + w0 * a[0][c]) + w1 * a[1][c]) + w2 * a[2][c]
+                                            : ((acc[c] + a[0][c]) + a[1][c]) + a[2][c];
+        }
+        if (!MEAN && WEIGHTED) {
+            const float ws = source_weight(sw, (int32_t)row, n_init);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[c] *= ws;
         }
         if (!MEAN && masked_out) {
             // the consumer is the layer below: apply its ReLU decision (its output h, row `row`) and place the row
@@ -206,9 +246,9 @@ __global__ void __launch_bounds__(256) segment_rows_kernel(RowCopyJob job, const
 template <typename T, int VEC, bool MEAN>
 static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, const int32_t* idx, const int32_t* d_n,
                            int32_t n_cap, const int32_t* d_n_init, float* out, int64_t ld_out, int32_t dim, hipStream_t st,
-                           const int32_t* self_idx = nullptr, int32_t with_self = 0, const float* mask_h = nullptr,
+                           const int32_t* self_idx = nullptr, int32_t agg_mode = AGG_NEIGH_MEAN, const float* mask_h = nullptr,
                            const int32_t* out_rows = nullptr, float* masked_out = nullptr, const RowCopyJob* copy = nullptr,
-                           hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr) {
+                           hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, const SourceWeights* weights = nullptr) {
     const int32_t units = dim / VEC;
     int g_log2 = 0;
     while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
@@ -225,48 +265,55 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
         if (copy_blocks > 1024) copy_blocks = 1024;
         if (copy_blocks < 1) copy_blocks = 1;
     }
-    NO_LAUNCH_TIMED((segment_rows_kernel<T, VEC, MEAN>), dim3((unsigned)(blocks + copy_blocks)), dim3(256), st, ev0, ev1, job, src, ld_src, seg, idx, d_n,
-                       n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, with_self, mask_h, out_rows, masked_out);
+    const SourceWeights sw = weights ? *weights : SourceWeights{};
+    if (sw.cnt)
+        NO_LAUNCH_TIMED((segment_rows_kernel<T, VEC, MEAN, true>), dim3((unsigned)(blocks + copy_blocks)), dim3(256), st, ev0, ev1, job, src, ld_src, seg, idx, d_n,
+                        n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, agg_mode, mask_h, out_rows, masked_out, sw);
+    else
+        NO_LAUNCH_TIMED((segment_rows_kernel<T, VEC, MEAN, false>), dim3((unsigned)(blocks + copy_blocks)), dim3(256), st, ev0, ev1, job, src, ld_src, seg, idx, d_n,
+                        n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, agg_mode, mask_h, out_rows, masked_out, sw);
 }
 
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
-                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, bool with_self,
-                       const int32_t* self_idx, const RowCopyJob* copy, hipEvent_t ev0, hipEvent_t ev1) {
+                       const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, int32_t agg_mode,
+                       const int32_t* self_idx, const RowCopyJob* copy, hipEvent_t ev0, hipEvent_t ev1,
+                       const SourceWeights* weights) {
     if (n_dst_cap <= 0) return NO_OK;
-    const int32_t ws = with_self ? 1 : 0;
+#define NO_SEG_FWD(T, V, ptr) \
+    launch_segment<T, V, true>(ptr, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, agg_mode, \
+                               nullptr, nullptr, nullptr, copy, ev0, ev1, weights)
     if (dt == NO_F32) {
         const float* x = (const float*)x_src;
         const bool a16 = (((uintptr_t)x | (uintptr_t)mean) & 15) == 0, a8 = (((uintptr_t)x | (uintptr_t)mean) & 7) == 0;
-        if (dim % 4 == 0 && a16) launch_segment<float, 4, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
-        else if (dim % 2 == 0 && a8) launch_segment<float, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
-        else launch_segment<float, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
+        if (dim % 4 == 0 && a16) NO_SEG_FWD(float, 4, x);
+        else if (dim % 2 == 0 && a8) NO_SEG_FWD(float, 2, x);
+        else NO_SEG_FWD(float, 1, x);
     } else {
         const uint16_t* x = (const uint16_t*)x_src;
-        if (dim % 8 == 0 && ((uintptr_t)x & 15) == 0 && ((uintptr_t)mean & 15) == 0)
-            launch_segment<uint16_t, 8, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
-        else if (dim % 2 == 0 && ((uintptr_t)x & 3) == 0)
-            launch_segment<uint16_t, 2, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
-        else launch_segment<uint16_t, 1, true>(x, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, ws, nullptr, nullptr, nullptr, copy, ev0, ev1);
+        if (dim % 8 == 0 && ((uintptr_t)x & 15) == 0 && ((uintptr_t)mean & 15) == 0) NO_SEG_FWD(uint16_t, 8, x);
+        else if (dim % 2 == 0 && ((uintptr_t)x & 3) == 0) NO_SEG_FWD(uint16_t, 2, x);
+        else NO_SEG_FWD(uint16_t, 1, x);
     }
+#undef NO_SEG_FWD
     return launch_status("mean_aggregate");
 }
 
-// grad_x[u,:] = (u < n_dst ? grad_x[u,:] : 0) + sum over transposed entries of u of gmean_scaled[csc_dst[p],:]
+// grad_x[u,:] = s_u * ((u < n_dst ? grad_x[u,:] : 0) + sum over transposed entries of u of gmean_scaled[csc_dst[p],:]),
+// s_u = 1 unless source weights are given
 int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
                             const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
-                            hipStream_t st, const float* mask_h, const int32_t* out_rows, float* masked_out) {
+                            hipStream_t st, const float* mask_h, const int32_t* out_rows, float* masked_out,
+                            const SourceWeights* weights) {
     if (n_src_cap <= 0) return NO_OK;
     const uintptr_t al = (uintptr_t)gmean_scaled | (uintptr_t)grad_x | (uintptr_t)mask_h | (uintptr_t)masked_out;
     const bool a16 = (al & 15) == 0, a8 = (al & 7) == 0;
-    if (dim % 4 == 0 && a16)
-        launch_segment<float, 4, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st,
-                                        nullptr, 0, mask_h, out_rows, masked_out);
-    else if (dim % 2 == 0 && a8)
-        launch_segment<float, 2, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st,
-                                        nullptr, 0, mask_h, out_rows, masked_out);
-    else
-        launch_segment<float, 1, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st,
-                                        nullptr, 0, mask_h, out_rows, masked_out);
+#define NO_SEG_BWD(V) \
+    launch_segment<float, V, false>(gmean_scaled, dim, csc_indptr, csc_dst, d_n_src, n_src_cap, d_n_dst, grad_x, dim, dim, st, \
+                                    nullptr, AGG_NEIGH_MEAN, mask_h, out_rows, masked_out, nullptr, nullptr, nullptr, weights)
+    if (dim % 4 == 0 && a16) NO_SEG_BWD(4);
+    else if (dim % 2 == 0 && a8) NO_SEG_BWD(2);
+    else NO_SEG_BWD(1);
+#undef NO_SEG_BWD
     return launch_status("transpose_aggregate");
 }
 
@@ -344,7 +391,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
                      const void* agg_table, hipEvent_t wait_before_gemm, int32_t arch, const Layer1Reuse* reuse,
-                     bool aggregate_done) {
+                     bool aggregate_done, const SourceWeights* weights) {
     // aggregate_done: `mean` (and the reused rows of H^1) were already written by an earlier launch of the same
     // aggregation (a batch prepared ahead); only the product runs
     // reuse: the output rows are scattered into H^1, recomputed hot rows also refresh the cache, and the reused
@@ -355,12 +402,19 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
         a.c_rows = reuse->compute_pos;
         a.c_keep = reuse->emb; a.c_keep_rows = reuse->refresh_slot; a.c_keep_stamp = reuse->version; a.stamp = reuse->step;      // version == NULL: stamped by the split already
     };
-    if (arch == NO_ARCH_GCN) {
-        // Eq. 1 over N_in(v) U {v} (the destination's own row joins the average), Eq. 2 with one matrix
+    if (arch_is_gcn(arch)) {
+        // Eq. 1 over N_in(v) U {v} (the destination's own row joins the aggregate: average, sum, or symmetric
+        // normalisation with per-source weights), Eq. 2 with one matrix
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (prof && agg_stage >= 0) prof->kernel_pair(agg_stage, &e0, &e1);
+        const int32_t mode = arch == NO_ARCH_GCN_SUM ? AGG_SELF_SUM : arch == NO_ARCH_GCN_SYM ? AGG_SELF_SYM : AGG_SELF_MEAN;
+        if (arch == NO_ARCH_GCN_SYM && !(weights && weights->cnt)) {
+            set_error("GCN-style layer with symmetric normalisation: the block has no per-source edge counts");
+            return NO_ERR_INVALID_ARG;
+        }
         NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
-                                blk.n_dst_cap, mean, st, true, agg_table ? blk.d_src_global : nullptr, hits, e0, e1));
+                                blk.n_dst_cap, mean, st, mode, agg_table ? blk.d_src_global : nullptr, hits, e0, e1,
+                                arch == NO_ARCH_GCN_SYM ? weights : nullptr));
         GemmNNArgs a{};
         a.A[0] = mean; a.lda[0] = d_in; a.a_align[0] = ptr_align(mean, d_in);
         a.B[0] = w_self; a.ldb[0] = d_out; a.b_align[0] = ptr_align(w_self, d_out);
@@ -384,7 +438,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     if (prof && agg_stage >= 0 && !aggregate_done) prof->kernel_pair(agg_stage, &e0, &e1);
     if (!aggregate_done)
         NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
-                                blk.n_dst_cap, mean, st, false, nullptr, hits, e0, e1));
+                                blk.n_dst_cap, mean, st, AGG_NEIGH_MEAN, nullptr, hits, e0, e1));
     if (wait_before_gemm && !direct_self)
         NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
     const float* x_dst = direct_self ? (const float*)agg_table : (const float*)x_src;
@@ -416,8 +470,12 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int prep_stage, int dw_stage,
                       int reduce_stage, int dx_stage, const int32_t* grad_rows, float lr, float* w_self_rw,
                       float* w_neigh_rw, float* bias_rw, int32_t arch, const StatsJob* stats_job, const float* gz_in,
-                      const BelowLayer* below, GradJobs* pending, bool defer) {
-    const bool gcn = arch == NO_ARCH_GCN;
+                      const BelowLayer* below, GradJobs* pending, bool defer, const SourceWeights* weights) {
+    const bool gcn = arch_is_gcn(arch);
+    if (arch == NO_ARCH_GCN_SYM && grad_x_src && !(weights && weights->cnt)) {
+        set_error("GCN-style layer with symmetric normalisation: the block has no per-source edge counts");
+        return NO_ERR_INVALID_ARG;
+    }
     const int32_t n_cap = blk.n_dst_cap;
     if (prof && prep_stage >= 0) prof->begin(prep_stage);
     // gz_in: the layer above already applied this layer's ReLU decision and row selection while it wrote the gradient
@@ -449,16 +507,19 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
         if (gcn) {
             // one matrix: gz W^T / (len + 1) is both the destination's own share (rows [0, n_dst) of grad_x) and
             // what the transpose spreads over the sampled sources
+            // (sum: no factor; symmetric normalisation: (len + 1)^-1/2 here, the source's own factor after the transpose)
             a.B[1] = w_self; a.b_align[1] = a.b_align[0];
             a.row_scale_indptr[0] = blk.d_indptr;
             a.row_scale_plus = 1;
+            a.row_scale_rsqrt = arch == NO_ARCH_GCN_SYM ? 1 : 0;
+            if (arch == NO_ARCH_GCN_SUM) a.row_scale_indptr[0] = a.row_scale_indptr[1] = nullptr;
         }
         a.n_problems = 2; a.accumulate = 0;
         a.d_M = blk.d_n_dst; a.M_cap = n_cap; a.N = d_in;
         NO_CHECK(gemm_nn(a, true, st));
         NO_CHECK(transpose_aggregate(w.gmean, d_in, blk.d_csc_indptr, blk.d_csc_dst, blk.d_n_src, blk.n_src_cap,
                                      blk.d_n_dst, grad_x_src, st, below ? below->h : nullptr, below ? below->out_rows : nullptr,
-                                     below ? below->gz_out : nullptr));
+                                     below ? below->gz_out : nullptr, arch == NO_ARCH_GCN_SYM ? weights : nullptr));
         if (prof && dx_stage >= 0) prof->end();
     }
     // weight gradients x_dst^T gz, mean^T gz and the bias gradient (column sums of gz, carried by a virtual
@@ -598,24 +659,42 @@ extern "C" int32_t no_sage_layer_bwd_static(const no_block_view* blk, const void
                          d_gw_neigh, d_gbias, d_grad_x_src, w, (hipStream_t)stream);
 }
 
-extern "C" int32_t no_gcn_layer_fwd(const no_block_view* blk, const void* d_x_src, no_dtype dt_x, int32_t d_in,
+static int32_t check_gcn_form(const no_block_view* blk, no_arch form, SourceWeights* sw, const char* who) {
+    NO_REQUIRE(form == NO_ARCH_GCN || form == NO_ARCH_GCN_SUM || form == NO_ARCH_GCN_SYM, NO_ERR_INVALID_ARG,
+               "%s: form must be one of the GCN-style layer forms", who);
+    *sw = SourceWeights{};
+    if (form == NO_ARCH_GCN_SYM) {
+        // the column sums of the block's adjacency are the lengths of the transpose's columns
+        NO_REQUIRE(blk->d_csc_indptr != nullptr, NO_ERR_INVALID_ARG,
+                   "%s: symmetric normalisation needs the block's transpose (its column lengths)", who);
+        sw->cnt = blk->d_csc_indptr;
+        sw->is_ptr = 1;
+    }
+    return NO_OK;
+}
+
+extern "C" int32_t no_gcn_layer_fwd(const no_block_view* blk, no_arch form, const void* d_x_src, no_dtype dt_x, int32_t d_in,
                                     const float* d_w, const float* d_bias, int32_t d_out, int32_t relu, float* d_agg,
                                     float* d_h, void* d_ws, size_t ws_bytes, void* stream) {
     clear_error();
     NO_CHECK(check_layer_args(blk, d_x_src, dt_x, d_in, d_out, "no_gcn_layer_fwd"));
+    SourceWeights sw;
+    NO_CHECK(check_gcn_form(blk, form, &sw, "no_gcn_layer_fwd"));
     NO_REQUIRE(d_w && d_bias && d_agg && d_h, NO_ERR_INVALID_ARG, "no_gcn_layer_fwd: NULL argument");
     LayerWorkspace w = carve_workspace(d_ws, blk->n_dst_cap, d_in, d_out);
     NO_REQUIRE(d_ws != nullptr && ws_bytes >= w.bytes, NO_ERR_CAPACITY, "no_gcn_layer_fwd: workspace too small (%zu < %zu)",
                ws_bytes, w.bytes);
     return sage_forward(*blk, d_x_src, dt_x, d_in, d_w, nullptr, d_bias, d_out, relu, d_agg, d_h, w, (hipStream_t)stream,
-                        nullptr, -1, -1, nullptr, nullptr, NO_ARCH_GCN);
+                        nullptr, -1, -1, nullptr, nullptr, form, nullptr, false, &sw);
 }
 
-extern "C" int32_t no_gcn_layer_bwd(const no_block_view* blk, int32_t d_in, const float* d_agg, const float* d_h,
+extern "C" int32_t no_gcn_layer_bwd(const no_block_view* blk, no_arch form, int32_t d_in, const float* d_agg, const float* d_h,
                                     const float* d_grad_h, const float* d_w, int32_t d_out, int32_t relu, float* d_gw,
                                     float* d_gbias, float* d_grad_x_src, void* d_ws, size_t ws_bytes, void* stream) {
     clear_error();
     NO_CHECK(check_layer_args(blk, d_agg, NO_F32, d_in, d_out, "no_gcn_layer_bwd"));
+    SourceWeights sw;
+    NO_CHECK(check_gcn_form(blk, d_grad_x_src ? form : (form == NO_ARCH_GCN_SYM ? NO_ARCH_GCN : form), &sw, "no_gcn_layer_bwd"));
     NO_REQUIRE(d_h && d_grad_h && d_w && d_gw && d_gbias, NO_ERR_INVALID_ARG, "no_gcn_layer_bwd: NULL argument");
     NO_REQUIRE(!d_grad_x_src || (blk->d_csc_indptr && blk->d_csc_dst && blk->d_n_src), NO_ERR_INVALID_ARG,
                "no_gcn_layer_bwd: input gradient requested but the block has no transpose");
@@ -624,5 +703,5 @@ extern "C" int32_t no_gcn_layer_bwd(const no_block_view* blk, int32_t d_in, cons
                ws_bytes, w.bytes);
     return sage_backward(*blk, d_agg, NO_F32, d_in, d_agg, d_h, d_grad_h, d_w, nullptr, d_out, relu, d_gw, nullptr, d_gbias,
                          d_grad_x_src, w, (hipStream_t)stream, nullptr, -1, -1, -1, -1, nullptr, 0.f, nullptr, nullptr, nullptr,
-                         NO_ARCH_GCN);
+                         form, nullptr, nullptr, nullptr, nullptr, false, &sw);
 }

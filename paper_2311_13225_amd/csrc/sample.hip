@@ -736,6 +736,8 @@ __global__ void unstamp_kernel(const int32_t* __restrict__ refresh_slot, const i
 // ---------------------------------------------------------------------------- host side
 
 static inline int64_t edge_tiles(int64_t n_pad_cap) { int64_t t = ceil_div(n_pad_cap, ETILE); return t < 1 ? 1 : t; }
+// does this hop count the edges that leave each source (for its transpose, or for the symmetric normalisation)?
+static inline bool counts_sources(const no_blocks_s* b, const HopBuffers& H) { return H.has_csc || b->count_sources; }
 
 template <typename RowT>
 static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b, int32_t h, const int32_t* d_dst,
@@ -774,21 +776,21 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     if (two_pass) {
         hipLaunchKernelGGL(edge_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, H.nbr_pad.p,
                            (const int32_t*)b->map.p, (const int32_t*)cnt, k, tile_sums, H.csc_cnt.p, H.csc_cur.p,
-                           H.has_csc ? H.n_src_cap + 1 : 0);
+                           counts_sources(b, H) ? H.n_src_cap + 1 : 0);
         hipLaunchKernelGGL(edge_assign_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
                            (const int32_t*)cnt, k, k_magic, (const int64_t*)tile_sums, H.indptr.p, H.nbr_global.p, H.edge_row.p,
                            H.src_global.p, cnt);
     } else {
         hipLaunchKernelGGL(edge_scan_kernel, dim3(tiles), dim3(ETHREADS), 0, st, (const int32_t*)H.nbr_pad.p, b->map.p,
                            (const int32_t*)cnt, k, k_magic, (unsigned long long*)b->ws.p, H.indptr.p, H.nbr_global.p,
-                           H.edge_row.p, H.src_global.p, cnt, H.csc_cnt.p, H.csc_cur.p, H.has_csc ? H.n_src_cap + 1 : 0,
+                           H.edge_row.p, H.src_global.p, cnt, H.csc_cnt.p, H.csc_cur.p, counts_sources(b, H) ? H.n_src_cap + 1 : 0,
                            b->counts.p + 4 * b->n_layers + 6, b->call_id, dbg.spin_limit, dbg.withhold_first_tile,
                            (unsigned int*)((unsigned long long*)b->ws.p + tiles));
     }
     if (indices_now)
         hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, st,
                            (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p, H.indices.p,
-                           H.has_csc ? H.csc_cnt.p : nullptr);
+                           counts_sources(b, H) ? H.csc_cnt.p : nullptr);
     return launch_status("sample_hop");
 }
 
@@ -827,10 +829,10 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
         if (indices_done[h]) continue;
         hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd,
                            (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p,
-                           H.indices.p, H.has_csc ? H.csc_cnt.p : nullptr);
+                           H.indices.p, counts_sources(b, H) ? H.csc_cnt.p : nullptr);
         if (h < n_hops - 1 && !inline_side) b->upper_indices_deferred = true;
     }
-    if (!inline_side) NO_HIP_CHECK(hipEventRecord(b->ev_indices_done, sd));
+    NO_HIP_CHECK(hipEventRecord(b->ev_indices_done, sd));
     for (int32_t h = 0; h < n_hops; ++h) {
         HopBuffers& H = b->hop[h];
         int32_t* cnt = b->counts.p + 4 * h;
@@ -899,7 +901,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
                 unsigned long long* v1_status = (unsigned long long*)b->ws.p + edge_tiles(P.nnz_cap) + 1;
                 hipLaunchKernelGGL(v1_split_kernel, dim3(idx_blocks + tiles), dim3(ETHREADS), 0, st, probe, d_n, v1_status,
                                    idx_blocks, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2), (const int32_t*)P.nbr_global.p,
-                                   b->map.p, P.indices.p, P.has_csc ? P.csc_cnt.p : nullptr, (unsigned int*)(v1_status + tiles),
+                                   b->map.p, P.indices.p, counts_sources(b, P) ? P.csc_cnt.p : nullptr, (unsigned int*)(v1_status + tiles),
                                    b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
                                    b->hit_slot.p, extra, stamp_refresh ? cache->version.p : nullptr, (int32_t)step,
                                    b->refresh_old.p, b->counts.p + 4 * b->n_layers + 6, b->call_id, dbg.spin_limit,
@@ -909,7 +911,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
             hipLaunchKernelGGL(v1_tile_sums_kernel, dim3(tiles + idx_blocks), dim3(ETHREADS), 0, st, probe, d_n, tile_sums,
                                b->probe_slot.p, b->probe_ver.p, tiles, (const int32_t*)(b->counts.p + 4 * (h - 1) + 2),
                                (const int32_t*)P.nbr_global.p, (const int32_t*)b->map.p, P.indices.p,
-                               P.has_csc ? P.csc_cnt.p : nullptr);
+                               counts_sources(b, P) ? P.csc_cnt.p : nullptr);
             indices_done[h - 1] = true;
             hipLaunchKernelGGL(v1_partition_kernel, dim3(tiles), dim3(ETHREADS), 0, st, d_dst,
                                (const int32_t*)b->probe_slot.p, (const int32_t*)b->probe_ver.p, d_n, (const int64_t*)tile_sums, b->map.p, b->compute_list.p, b->compute_pos.p, b->compute_inv.p, b->refresh_slot.p, b->hit_pos.p,
@@ -992,10 +994,10 @@ int32_t blocks_create_impl(no_graph_s* g, int32_t n_seeds_cap, const int32_t* fa
         NO_CHECK(H.nbr_global.alloc((size_t)nnz_cap));
         NO_CHECK(H.indices.alloc((size_t)nnz_cap));
         NO_CHECK(H.edge_row.alloc((size_t)nnz_cap));
+        NO_CHECK(H.csc_cnt.alloc((size_t)src_cap + 1));       // (every hop: the bottom hop's counts serve the symmetric
+        NO_CHECK(H.csc_cur.alloc((size_t)src_cap + 1));       //  normalisation; the two arrays are emptied together)
         if (H.has_csc) {
             NO_CHECK(H.csc_indptr.alloc((size_t)src_cap + 1));
-            NO_CHECK(H.csc_cnt.alloc((size_t)src_cap + 1));
-            NO_CHECK(H.csc_cur.alloc((size_t)src_cap + 1));
             NO_CHECK(H.csc_dst.alloc((size_t)nnz_cap));
             NO_CHECK(H.csc_eid.alloc((size_t)nnz_cap));
             if (nnz_cap > max_sort) max_sort = nnz_cap;

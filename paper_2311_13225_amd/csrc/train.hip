@@ -185,8 +185,11 @@ extern "C" int32_t no_model_params(no_model_t m, int32_t layer, float** d_w_self
 extern "C" int32_t no_model_set_arch(no_model_t m, no_arch arch) {
     clear_error();
     NO_REQUIRE(m != nullptr, NO_ERR_INVALID_ARG, "no_model_set_arch: model is NULL");
-    NO_REQUIRE(arch == NO_ARCH_SAGE_MEAN || arch == NO_ARCH_GCN, NO_ERR_INVALID_ARG, "no_model_set_arch: unknown layer form");
+    NO_REQUIRE(arch == NO_ARCH_SAGE_MEAN || arch_is_gcn(arch), NO_ERR_INVALID_ARG, "no_model_set_arch: unknown layer form");
     m->arch = arch;
+    // the symmetric normalisation needs the number of edges that leave each source, in the bottom hop too
+    m->blocks->count_sources = arch == NO_ARCH_GCN_SYM;
+    if (m->blocks_alt) m->blocks_alt->count_sources = arch == NO_ARCH_GCN_SYM;
     return NO_OK;
 }
 
@@ -224,6 +227,7 @@ extern "C" int32_t no_model_gathered(no_model_t m, const void** d_x0) {
 static int32_t ensure_lookahead(no_model_s* m, no_graph_s* g) {
     if (m->blocks_alt) return NO_OK;
     NO_CHECK(blocks_create_impl(g, m->n_seeds_cap, m->fanouts, m->n_layers, true, &m->blocks_alt));
+    m->blocks_alt->count_sources = m->arch == NO_ARCH_GCN_SYM;
     NO_CHECK(m->x0_alt.alloc(m->x0.n));
     NO_CHECK(m->mean_alt.alloc(m->mean[0].n));
     NO_CHECK(m->h0_alt.alloc(m->h[0].n));
@@ -297,7 +301,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     const int32_t es = m->feat_dtype == NO_F32 ? 4 : 2;
     const int32_t row_bytes = m->dims[0] * es;
     SideGather sg;
-    sg.table = m->arch == NO_ARCH_GCN ? nullptr : d_features;    // GCN-style layers read every row inside the aggregation
+    sg.table = arch_is_gcn(m->arch) ? nullptr : d_features;    // GCN-style layers read every row inside the aggregation
     sg.row_bytes = row_bytes;
     sg.out = m->x0.p;
     static const char* no_direct = getenv("NO_SELF_FROM_COPY");
@@ -369,7 +373,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             next_hits.dim = m->dims[1];
         }
         NO_CHECK(mean_aggregate(d_features, m->feat_dtype, m->dims[0], nv.d_indptr, nv.d_nbr_global, nv.d_n_dst, nv.n_dst_cap,
-                                m->mean_alt.p, m->sample_stream, false, nullptr, next_cache ? &next_hits : nullptr));
+                                m->mean_alt.p, m->sample_stream, AGG_NEIGH_MEAN, nullptr, next_cache ? &next_hits : nullptr));
         NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
         m->ahead_aggregated = true;
         return NO_OK;
@@ -399,6 +403,14 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             reuse.hits.d_n = extra + 1; reuse.hits.n_cap = blk.n_dst_cap; reuse.hits.dst = m->h[0].p; reuse.hits.dim = d_out;
         }
         LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
+        // symmetric normalisation: the column sums of the block's adjacency are the per-source edge counts of the hop
+        // (written with the local indices on the blocks' side stream); the fused layer-1 aggregate reads global ids,
+        // so it also takes the local index of every entry
+        SourceWeights sw;
+        if (m->arch == NO_ARCH_GCN_SYM) {
+            sw.cnt = B->hop[L - l].csc_cnt.p;
+            if (l == 1) { sw.local = B->hop[L - 1].indices.p; NO_HIP_CHECK(hipStreamWaitEvent(st, B->ev_indices_done, 0)); }
+        }
         if (l == 2) prof.begin(NO_STAGE_FWD_UPPER);
         // layers above the bottom one aggregate through local indices; without the cache split those are written
         // on the blocks' side stream
@@ -411,12 +423,13 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
                                   NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features,
-                                  m->arch == NO_ARCH_GCN ? nullptr : B->ev_gather_done, m->arch,
-                                  (l == 1 && used_cache) ? &reuse : nullptr, aggregated));
+                                  arch_is_gcn(m->arch) ? nullptr : B->ev_gather_done, m->arch,
+                                  (l == 1 && used_cache) ? &reuse : nullptr, aggregated, &sw));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
-                              l == 1 ? &prof : nullptr, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, nullptr, nullptr, m->arch));
+                              l == 1 ? &prof : nullptr, NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, nullptr, nullptr, m->arch,
+                              nullptr, false, &sw));
         if (l == L && L >= 2) prof.end();
         if (l == 1 && d_next_seeds) {
             if (!lookahead_early) NO_CHECK(launch_sampling_ahead());
@@ -474,6 +487,8 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         }
         if (l < L) gz_in = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out).gz;
         LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
+        SourceWeights sw;
+        if (m->arch == NO_ARCH_GCN_SYM) sw.cnt = B->hop[L - l].csc_cnt.p;
         NO_CHECK(sage_backward(blk, x, dt, d_in, m->mean[l - 1].p, h_l, gh_l, m->params.p + m->off_w_self[l - 1],
                                m->params.p + m->off_w_neigh[l - 1], d_out, l < L ? 1 : 0,
                                m->grads.p + m->off_w_self[l - 1], m->grads.p + m->off_w_neigh[l - 1],
@@ -481,7 +496,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
                                l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
                                -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                                m->params.p + m->off_bias[l - 1], m->arch, l == 1 ? &stats_job : nullptr, gz_in,
-                               l >= 2 ? &below : nullptr, dw_inline ? nullptr : &pending, l >= 2));
+                               l >= 2 ? &below : nullptr, dw_inline ? nullptr : &pending, l >= 2, &sw));
     }
 
     // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;
@@ -543,7 +558,7 @@ extern "C" int32_t no_model_weight_drift(no_model_t m, no_cache_t cache, float l
     hipStream_t st = (hipStream_t)stream;
     const int32_t d_in = m->dims[0], d_out = m->dims[1];
     const size_t wsz = (size_t)d_in * d_out;
-    const bool gcn = m->arch == NO_ARCH_GCN;
+    const bool gcn = arch_is_gcn(m->arch);
     uint32_t* bits = (uint32_t*)(m->stats.p + 1);           // two words behind the statistics record
     NO_CHECK(fill_i32((int32_t*)bits, 0, 2, st));
     auto launch = [&](const float* a, const float* b, size_t n, float scale, uint32_t* out) {
@@ -558,7 +573,7 @@ extern "C" int32_t no_model_weight_drift(no_model_t m, no_cache_t cache, float l
     launch(m->grads.p + m->off_bias[0], nullptr, (size_t)d_out, lr, bits);
     // the drift of the layer-1 parameters away from the ones the rows now in the cache were refreshed with
     const RefreshState* r = cache ? cache->refresh : nullptr;
-    const bool have = r && r->have_cur && r->feat_dim == d_in && cache->emb_dim == d_out && (r->snap_arch == NO_ARCH_GCN) == gcn;
+    const bool have = r && r->have_cur && r->feat_dim == d_in && cache->emb_dim == d_out && arch_is_gcn(r->snap_arch) == gcn;
     if (have) {
         const float* s_self = r->snap_cur.p;
         const float* s_neigh = s_self + wsz;

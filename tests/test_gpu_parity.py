@@ -399,9 +399,9 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
     weights = si.init_weights(w.dims, w.seed)
     bf16 = w.feat_dtype == "bf16"
     model = b.no_model_create(gg, w.dims, w.batch, w.fanouts, b.NO_BF16 if bf16 else b.NO_F32)
-    gcn = arch == "gcn"
+    gcn = arch != "sage"
     if gcn:
-        b.no_model_set_arch(model, b.NO_ARCH_GCN)
+        b.no_model_set_arch(model, b.ARCH_OF_NAME[arch])
     for l in range(w.n_layers):
         for t, a in zip(b.no_model_params(model, l + 1), weights[l]):
             t.copy_(dev(a))
@@ -414,6 +414,8 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
         oc = ora.select_hot(og, pre, w.batch, w.fanouts, presample, frac, w.staleness, w.hidden, w.seed)
         gc = b.no_select_hot(gg, dev(pre), w.batch, w.fanouts, presample, frac, w.staleness, w.hidden, w.seed)
         assert np.array_equal(b.no_cache_view(gc, V)["hot_ids"].cpu().numpy(), oc.hot_ids)
+        if gcn:
+            b.no_cache_set_layer_form(gc, b.ARCH_OF_NAME[arch])
     tfeat = dev(feat.view(np.int16) if bf16 else feat)
     tlab = dev(lab)
     ow = [tuple(np.asarray(t, np.float64) for t in pick(x)) for x in weights]
@@ -435,7 +437,8 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
                 if not ahead:           # sampling ahead: committed inside the previous step's call
                     b.no_refresh_hot_commit(gc)
             pending_snap = ow[0]
-            pending = ora.refresh_hot(og, feat, oc, ow[0], w.fanouts[-1], step, w.seed, feat_is_bf16=bf16)
+            pending = ora.refresh_hot(og, feat, oc, ow[0], w.fanouts[-1], step, w.seed, feat_is_bf16=bf16,
+                                      norm=ora.gcn_norm_of(arch) if gcn else "mean")
             p1 = b.no_model_params(model, 1)
             b.no_refresh_hot_begin(gc, gg, tfeat, p1[0], None if gcn else p1[1], p1[2], w.fanouts[-1], step, w.seed)
         if ahead:
@@ -607,11 +610,15 @@ def test_superbatch_schedule_with_bulk_refresh():
     assert run_steps(w3, 6, use_cache=True, lr=0.02, bits=64, superbatch=2) > 0
 
 
+@pytest.mark.parametrize("form", ["gcn", "gcn_sum", "gcn_sym"])
 @pytest.mark.parametrize("F,d_out,relu,bf16", [(64, 64, True, False), (602, 256, True, False), (100, 47, False, False),
                                                (33, 5, True, False), (128, 256, True, True), (70, 41, False, False)])
-def test_gcn_layer_forward_backward(F, d_out, relu, bf16):
-    """GCN-style layer (Eq. 1 over N_in(v) U {v}, one matrix) through its own entry points."""
+def test_gcn_layer_forward_backward(F, d_out, relu, bf16, form):
+    """GCN-style layer (Eq. 1 over N_in(v) U {v}: average, sum, or the symmetric normalisation of Table 1; one matrix)
+    through its own entry points."""
     b = nb()
+    norm = ora.gcn_norm_of(form)
+    fcode = b.ARCH_OF_NAME[form]
     blk, x, xb, w_self, _, bias, rng = layer_case(4000, 60_000, F, d_out, (7, 6), 300, 11, bf16)
     n_dst, n_src = blk.n_dst, blk.n_src
     cap_dst, cap_src = n_dst + 77, n_src + 130
@@ -624,8 +631,8 @@ def test_gcn_layer_forward_backward(F, d_out, relu, bf16):
     agg = torch.full((cap_dst, F), 7.0, device="cuda")
     h = torch.full((cap_dst, d_out), 7.0, device="cuda")
     tw, tbias = dev(w_self), dev(bias)
-    b.no_gcn_layer_fwd(view, xs, tw, tbias, relu, agg, h, ws)
-    o_agg, o_h = ora.gcn_layer_fwd(blk, x, w_self, bias, relu)
+    b.no_gcn_layer_fwd(view, xs, tw, tbias, relu, agg, h, ws, form=fcode)
+    o_agg, o_h = ora.gcn_layer_fwd(blk, x, w_self, bias, relu, norm)
     assert_close(agg[:n_dst].cpu().numpy(), o_agg, "agg")
     assert_close(h[:n_dst].cpu().numpy(), o_h, "h")
     assert (h[n_dst:] == 7.0).all() and (agg[n_dst:] == 7.0).all()
@@ -641,30 +648,39 @@ def test_gcn_layer_forward_backward(F, d_out, relu, bf16):
     aa = torch.zeros((cap_dst, F), device="cuda")
     aa[:n_dst] = dev(o_agg.astype(np.float32))
     for need_gx in (True, False):
-        b.no_gcn_layer_bwd(view, aa, hh, gh, tw, relu, gw, gb, gx if need_gx else None, ws)
-        r = ora.gcn_layer_bwd(blk, o_agg.astype(np.float32), o_h32, grad_h, w_self, relu, need_gx)
+        b.no_gcn_layer_bwd(view, aa, hh, gh, tw, relu, gw, gb, gx if need_gx else None, ws, form=fcode)
+        r = ora.gcn_layer_bwd(blk, o_agg.astype(np.float32), o_h32, grad_h, w_self, relu, need_gx, norm=norm)
         assert_close(gw.cpu().numpy(), r[0], "gw")
         assert_close(gb.cpu().numpy(), r[1], "gbias")
         if need_gx:
             assert_close(gx[:n_src].cpu().numpy(), r[2], "grad_x")
             assert (gx[n_src:] == 3.0).all()
     g1 = gw.clone()
-    b.no_gcn_layer_bwd(view, aa, hh, gh, tw, relu, gw, gb, None, ws)
+    b.no_gcn_layer_bwd(view, aa, hh, gh, tw, relu, gw, gb, None, ws, form=fcode)
     assert torch.equal(g1, gw)
+    if form == "gcn_sym":
+        # the column sums come from the transpose: a view without one is refused
+        bare = b.block_view_from_tensors(d_n_dst, d_n_src, indptr, dev(blk.indices), cap_dst, cap_src)
+        with pytest.raises(b.NoError) as ei:
+            b.no_gcn_layer_fwd(bare, xs, tw, tbias, relu, agg, h, ws, form=fcode)
+        assert ei.value.code == -1
 
 
-def test_gcn_train_steps():
-    """Whole steps with GCN-style layers: plain, with reuse (2 and 3 layers, bf16 table), and under the
-    super-batch schedule with bulk refresh."""
+@pytest.mark.parametrize("arch", ["gcn", "gcn_sum", "gcn_sym"])
+def test_gcn_train_steps(arch):
+    """Whole steps with GCN-style layers (average, sum, symmetric normalisation): plain, with reuse (2 and 3 layers,
+    bf16 table), under the super-batch schedule with bulk refresh, and with batches prepared ahead."""
     import dataclasses
-    run_steps(si.WORKLOADS["tiny"], 3, use_cache=False, arch="gcn")
+    lr = 0.02 if arch != "gcn_sum" else 0.002        # (sums over up to 16 rows make larger activations)
+    run_steps(si.WORKLOADS["tiny"], 3, use_cache=False, arch=arch, lr=lr)
     w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=2, hot_fraction=0.2)
-    assert run_steps(w, 5, use_cache=True, lr=0.02, arch="gcn") > 0
+    assert run_steps(w, 5, use_cache=True, lr=lr, arch=arch) > 0
     w3 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(4, 3, 3), staleness=3, hot_fraction=0.3, n_classes=47,
                              feat_dim=100, hidden=40, batch=128, feat_dtype="bf16")
-    assert run_steps(w3, 6, use_cache=True, lr=0.02, bits=64, superbatch=2, arch="gcn") > 0
+    assert run_steps(w3, 6, use_cache=True, lr=lr, bits=64, superbatch=2, arch=arch) > 0
+    assert run_steps(w3, 4, use_cache=True, lr=lr, bits=64, superbatch=2, arch=arch, ahead=True) > 0
     w1 = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=(6,), batch=200)
-    run_steps(w1, 2, use_cache=False, arch="gcn")
+    run_steps(w1, 2, use_cache=False, arch=arch, lr=lr)
 
 
 def test_sampling_ahead_gives_the_same_steps():
