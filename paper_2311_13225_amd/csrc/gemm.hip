@@ -699,11 +699,35 @@ __global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(TNLaunch launch) {
     const uint32_t gx = (uint32_t)((g.N + BN - 1) / BN), gy = (uint32_t)((g.Kp + 1 + BM - 1) / BM);
     const int bx = (int)(id % gx), by = (int)((id / gx) % gy), bz = (int)(id / (gx * gy));
     const int prob = bz / g.splits, split = bz % g.splits;
-    int chunk = (R + g.splits - 1) / g.splits;
+    const int used = tn_used_splits(R, g.splits, g.rows_per_split);
+    if (split >= used) return;                 // (the reduction reads the first `used` partials only)
+    int chunk = (R + used - 1) / used;
     chunk = (chunk + BK - 1) / BK * BK;
     const int r0 = split * chunk;
     const int r1 = min(R, r0 + chunk);
     const int m0 = by * BM, n0 = bx * BN;
+    if (m0 >= g.Kp) {
+        // Kp is a multiple of the tile height: this row tile holds nothing but row Kp, the column sums of G that product
+        // 0 carries (the bias gradient). A tile of matrix products for one row would be a third of the launch's work at
+        // Kp = 128: the sums are taken directly, in a fixed order (row r0 + i by thread group i mod 4, groups combined in
+        // order). Product 1 has no such row (the reduction never reads it).
+        if (prob != 0) return;
+        float* red = smem;                                   // [4][BN]
+        const int c = (int)(threadIdx.x % BN), part = (int)(threadIdx.x / BN);
+        constexpr int PARTS = 256 / BN;
+        float s = 0.f;
+        if (n0 + c < g.N)
+            for (int r = r0 + part; r < r1; r += PARTS) s += g.G[(int64_t)r * g.ldg + n0 + c];
+        red[part * BN + c] = s;
+        __syncthreads();
+        if (part == 0 && n0 + c < g.N) {
+            float t = red[c];
+#pragma unroll
+            for (int q = 1; q < PARTS; ++q) t += red[q * BN + c];
+            g.P[((int64_t)prob * g.splits + split) * (int64_t)(g.Kp + 1) * g.N + (int64_t)g.Kp * g.N + n0 + c] = t;
+        }
+        return;
+    }
     const int wave = (int)(threadIdx.x >> 6), wm = wave >> 1, wn = wave & 1;
     constexpr int SETS = AccSets<BM, BN>::N;
     floatx16 acc[SETS][MI][NI];
@@ -822,14 +846,20 @@ __global__ void __launch_bounds__(256) reduce_grads_kernel(ReduceLaunch launch, 
     uint32_t first = 0;
     while (job + 1 < launch.n && blockIdx.x >= launch.end_block[job]) first = launch.end_block[job++];
     const ReduceArgs& a = launch.job[job];
-    const int32_t Kp = a.Kp, N = a.N, splits = a.splits;
+    const int32_t Kp = a.Kp, N = a.N;
+    int32_t splits = a.splits;
+    if (a.d_R) {
+        int32_t R = *a.d_R;
+        if (R > a.R_cap) R = a.R_cap;
+        splits = tn_used_splits(R, a.splits, a.rows_per_split);
+    }
     const int64_t per = (int64_t)(Kp + 1) * N;
     const int64_t i = (int64_t)(blockIdx.x - first) * blockDim.x + threadIdx.x;
     const int q = (int)blockIdx.y;
     if (i >= per || q >= a.n_problems) return;
     const bool bias_row = i >= (int64_t)Kp * N;
     if (q == 1 && bias_row) return;
-    const float* p = a.P + (int64_t)q * splits * per + i;
+    const float* p = a.P + (int64_t)q * a.splits * per + i;
     // eight partials are requested before the first add; the adds stay in split order
     float s = 0.f;
     int32_t k = 0;

@@ -35,9 +35,19 @@ struct GemmTNArgs {
     const float* G; int64_t ldg; int g_align;            // [R, N]
     float* P;                                            // partials [2][splits][Kp+1][N]; row Kp of product 0 = column sums of G
     int32_t Kp, N;
-    const int32_t* d_R; int32_t R_cap; int32_t splits;
+    const int32_t* d_R; int32_t R_cap; int32_t splits;   // splits: the most row slices (the partials' layout is sized for it)
     int32_t n_problems = 2;                              // 1: only A[0]
+    int32_t rows_per_split = 0;                          // > 0: only ceil(R / rows_per_split) slices are used when that is fewer
 };
+
+// The number of row slices a split product over R rows really uses: the capacity-sized bound `splits`, cut down so that a
+// slice keeps about rows_per_split rows (a function of R alone, so the summation order is the same in every run).
+__host__ __device__ inline int32_t tn_used_splits(int32_t R, int32_t splits, int32_t rows_per_split) {
+    if (rows_per_split <= 0) return splits;
+    int32_t s = (R + rows_per_split - 1) / rows_per_split;
+    if (s < 1) s = 1;
+    return s < splits ? s : splits;
+}
 
 // Statistics of a training step, written by one extra block of the last gradient reduction of the step (they are
 // nobody's input, so they do not get a launch of their own on the step's dependency chain): mean of the per-seed
@@ -57,6 +67,7 @@ struct ReduceArgs {
     float* g_self; float* g_neigh; float* g_bias;
     float lr; float* w_self; float* w_neigh; float* w_bias;
     int32_t n_problems;                                  // 2, or 1: only g_self and g_bias
+    const int32_t* d_R = nullptr; int32_t R_cap = 0; int32_t rows_per_split = 0;   // as in the product: the slices it used
 };
 
 // Weight-gradient work of several layers carried by one product launch and one reduction launch: the gradients of an

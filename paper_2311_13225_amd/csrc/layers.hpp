@@ -41,6 +41,7 @@ struct LayerWorkspace {
     float* gz = nullptr;             // [n_dst_cap, d_out] masked output gradient
     float* gmean = nullptr;          // [n_dst_cap, d_in]  gradient of the mean, pre-divided by the row length
     float* x_dst_f32 = nullptr;      // [n_dst_cap, d_in]  fp32 copy of bf16 destination rows
+    bool x_dst_f32_ready = false;    // that copy was already made (by the step's side stream, with the dense row copy)
     float* partials = nullptr;       // [2, splits, d_in + 1, d_out]
     int32_t splits = 1;
     size_t bytes = 0;
@@ -68,6 +69,11 @@ struct SourceWeights {
     const int32_t* cnt = nullptr; int32_t is_ptr = 0; const int32_t* local = nullptr;
 };
 
+// The sampler's fixed-stride slot array of a hop (row r: entries [r*k, r*k + k), global ids in slot order, -1 from the
+// first unused slot on, first occurrences possibly marked as -2 - id): lets the fused layer-1 aggregate skip the row
+// pointers and the compacted index array.
+struct PaddedSlots { const int32_t* pad = nullptr; int32_t k = 0; };
+
 // Layer 1 with reuse (Section 4.1.2): where the computed rows go, which of them refresh the cache, and the reused
 // rows to copy in from the cache.
 struct Layer1Reuse {
@@ -90,7 +96,8 @@ LayerWorkspace carve_workspace(void* ws, int32_t n_dst_cap, int32_t d_in, int32_
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
                        const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st,
                        int32_t agg_mode = AGG_NEIGH_MEAN, const int32_t* self_idx = nullptr, const RowCopyJob* copy = nullptr,
-                       hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, const SourceWeights* weights = nullptr);
+                       hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, const SourceWeights* weights = nullptr,
+                       const PaddedSlots* padded = nullptr);
 int32_t transpose_aggregate(const float* gmean_scaled, int32_t dim, const int32_t* csc_indptr, const int32_t* csc_dst,
                             const int32_t* d_n_src, int32_t n_src_cap, const int32_t* d_n_dst, float* grad_x,
                             hipStream_t st, const float* mask_h = nullptr, const int32_t* out_rows = nullptr,
@@ -100,7 +107,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int agg_stage = -1,
                      int gemm_stage = -1, const void* agg_table = nullptr, hipEvent_t wait_before_gemm = nullptr,
                      int32_t arch = NO_ARCH_SAGE_MEAN, const Layer1Reuse* reuse = nullptr, bool aggregate_done = false,
-                     const SourceWeights* weights = nullptr);
+                     const SourceWeights* weights = nullptr, const PaddedSlots* padded = nullptr);
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
@@ -111,6 +118,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       const StatsJob* stats_job = nullptr, const float* gz_in = nullptr,
                       const BelowLayer* below = nullptr, GradJobs* pending = nullptr, bool defer = false,
                       const SourceWeights* weights = nullptr);
+int32_t bf16_rows_to_f32(const uint16_t* x, const int32_t* d_n, int32_t n_cap, int32_t dim, float* out, hipStream_t st);
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
                     const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
 

@@ -88,11 +88,12 @@ extern "C" int32_t no_refresh_hot_begin(no_cache_t c, no_graph_t g, const void* 
     view.d_indices = view.d_nbr_global;        // aggregate straight from the table through the global ids
     LayerWorkspace w;
     w.x_dst_f32 = bf16 ? r->x_f32.p : nullptr;
+    const PaddedSlots slots{r->blocks->hop[0].nbr_pad.p, r->blocks->hop[0].fanout};
     SourceWeights sw;
     if (arch == NO_ARCH_GCN_SYM) { sw.cnt = r->blocks->hop[0].csc_cnt.p; sw.local = r->blocks->hop[0].indices.p; }
     NO_CHECK(sage_forward(view, bf16 ? (const void*)r->x0.p : d_features, dt, feat_dim, w_self, w_neigh, bias, d_out, 1,
                           r->mean.p, r->emb_pending.p, w, r->stream, nullptr, -1, -1, d_features,
-                          bf16 ? r->blocks->ev_gather_done : nullptr, arch, nullptr, false, &sw));
+                          bf16 ? r->blocks->ev_gather_done : nullptr, arch, nullptr, false, &sw, &slots));
     NO_CHECK(fill_i32(r->version_pending.p, (int32_t)version, n_hot, r->stream));
     NO_HIP_CHECK(hipEventRecord(r->ev_done, r->stream));
     r->pending = true;

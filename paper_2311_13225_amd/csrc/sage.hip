@@ -59,6 +59,32 @@ __device__ __forceinline__ float source_weight(const SourceWeights& sw, int32_t 
     return c > 0 ? 1.f / sqrtf((float)c) : 0.f;
 }
 
+// A vector unit as it comes from memory, and its accumulation in fp32 (the two halves of RowVec::add, for kernels that
+// keep many units in flight in their memory form: 4 registers per bf16 unit of 8 instead of 8)
+template <typename T, int VEC> struct RawUnit;
+template <> struct RawUnit<float, 4> { using type = float4; };
+template <> struct RawUnit<float, 2> { using type = float2; };
+template <> struct RawUnit<float, 1> { using type = float; };
+template <> struct RawUnit<uint16_t, 8> { using type = uint4; };
+template <> struct RawUnit<uint16_t, 2> { using type = uint32_t; };
+template <> struct RawUnit<uint16_t, 1> { using type = uint16_t; };
+__device__ __forceinline__ void accum_unit(float (&acc)[4], const float4& v) { acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w; }
+__device__ __forceinline__ void accum_unit(float (&acc)[2], const float2& v) { acc[0] += v.x; acc[1] += v.y; }
+__device__ __forceinline__ void accum_unit(float (&acc)[1], const float& v) { acc[0] += v; }
+__device__ __forceinline__ void accum_unit(float (&acc)[8], const uint4& v) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += __uint_as_float(w[i] << 16);
+        acc[2 * i + 1] += __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void accum_unit(float (&acc)[2], const uint32_t& w) {
+    acc[0] += __uint_as_float(w << 16);
+    acc[1] += __uint_as_float(w & 0xffff0000u);
+}
+__device__ __forceinline__ void accum_unit(float (&acc)[1], const uint16_t& b) { acc[0] += bf16_to_f32(b); }
+
 // out[row, :] = init + scale * sum_{p in [seg[row], seg[row+1])} w_p * src[idx[p], :]
 //   MEAN: init = 0 and, by agg_mode: AGG_NEIGH_MEAN scale = 1/len (0 for an empty segment): forward aggregate of the
 //         GraphSAGE-mean layer. The other modes add the row's own source row first (Eq. 1 over N_in(v) U {v}):
@@ -255,7 +281,8 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
     const int32_t n_chunks = (int32_t)ceil_div(units, 1 << g_log2);
     int64_t waves = ceil_div((int64_t)n_cap * n_chunks, 64 >> g_log2);
     int64_t blocks = ceil_div(waves, 4);
-    if (blocks > 256 * 64) blocks = 256 * 64;
+    static const char* env_blocks = getenv("NO_AGG_BLOCKS");
+    if (blocks > (env_blocks ? atoi(env_blocks) : 256 * 64)) blocks = env_blocks ? atoi(env_blocks) : 256 * 64;
     if (blocks < 1) blocks = 1;
     RowCopyJob job = copy ? *copy : RowCopyJob{};
     int64_t copy_blocks = 0;
@@ -274,11 +301,137 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
                         n_cap, d_n_init, out, ld_out, units, g_log2, n_chunks, self_idx, agg_mode, mask_h, out_rows, masked_out, sw);
 }
 
+// The layer-1 aggregate straight from the sampler's fixed-stride slot array: row r's sampled neighbours are the
+// entries pad[r*k .. r*k + k) in slot order (the order of the compacted row), -1 from the first unused slot on, and a
+// first occurrence may carry the relabelling's mark (-2 - id in place of id). Reading the slots needs neither the row
+// pointers nor the compacted index array, so a work item's chain of dependent memory round trips is "row count -> slots
+// -> rows -> store" instead of "row count -> row pointers -> indices -> rows -> store": the kernel is bound by that chain
+// (every wave handles one or two items), not by bytes in flight. NS (8 or 16) slots and their rows are in flight at a time. Same sums in the same order as segment_rows_kernel<MEAN>.
+// agg_mode as there (no per-source weights here).
+template <typename T, int VEC, int NS>
+__global__ void __launch_bounds__(256) padded_rows_kernel(RowCopyJob job, const T* __restrict__ src, int64_t ld_src,
+                                                          const int32_t* __restrict__ pad, int32_t k,
+                                                          const int32_t* d_n_rows, int32_t n_rows_cap,
+                                                          float* __restrict__ out, int64_t ld_out, int32_t units,
+                                                          int32_t g_log2, int32_t n_chunks,
+                                                          const int32_t* __restrict__ self_idx, int32_t agg_mode) {
+    if (job.dst && blockIdx.x >= job.first_block) {
+        const int32_t nj = *job.d_n;
+        const int64_t w0 = (((int64_t)(blockIdx.x - job.first_block)) * blockDim.x + threadIdx.x) >> 6;
+        const int64_t nw = ((int64_t)(gridDim.x - job.first_block) * blockDim.x) >> 6;
+        const int ln = (int)(threadIdx.x & 63);
+        for (int64_t i = w0; i < nj; i += nw) {
+            const float* s_ = job.src + (int64_t)job.src_rows[i] * job.dim;
+            float* d_ = job.dst + (int64_t)job.dst_rows[i] * job.dim;
+            for (int c = ln; c < job.dim; c += 64) d_[c] = s_[c];
+        }
+        return;
+    }
+    using Raw = typename RawUnit<T, VEC>::type;
+    int32_t n = *d_n_rows;
+    if (n > n_rows_cap) n = n_rows_cap;
+    const int32_t lane = (int32_t)(threadIdx.x & 63);
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)(job.dst ? job.first_block : gridDim.x) * blockDim.x) >> 6;
+    const int32_t items_per_pass = 64 >> g_log2;
+    const int32_t sub = lane >> g_log2, u0 = lane & ((1 << g_log2) - 1);
+    const int64_t n_items = (int64_t)n * n_chunks;
+    const bool with_self = agg_mode != AGG_NEIGH_MEAN;
+    for (int64_t item = wave * items_per_pass + sub; item < n_items; item += n_waves * items_per_pass) {
+        const int64_t row = item / n_chunks;
+        const int32_t u = (int32_t)(item - row * n_chunks) * (1 << g_log2) + u0;
+        if (u >= units) continue;
+        const int32_t* slots = pad + row * k;
+        int32_t e[NS];
+#pragma unroll
+        for (int j = 0; j < NS; ++j) e[j] = j < k ? slots[j] : -1;
+        int32_t self_row = (int32_t)row;
+        if (with_self && self_idx) self_row = self_idx[row];
+        const T* col = src + (int64_t)u * VEC;
+        float acc[VEC];
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+        if (with_self) RowVec<T, VEC>::add(acc, col + (int64_t)self_row * ld_src);
+        int32_t len = 0;
+        for (int32_t j0 = 0;;) {
+            Raw raw[NS];
+#pragma unroll
+            for (int j = 0; j < NS; ++j)
+                if (e[j] != -1) raw[j] = *reinterpret_cast<const Raw*>(col + (int64_t)(e[j] <= -2 ? -2 - e[j] : e[j]) * ld_src);
+#pragma unroll
+            for (int j = 0; j < NS; ++j)
+                if (e[j] != -1) {
+                    accum_unit(acc, raw[j]);
+                    ++len;
+                }
+            j0 += NS;
+            if (j0 >= k || e[NS - 1] == -1) break;          // unused slots are at the end of a row
+#pragma unroll
+            for (int j = 0; j < NS; ++j) e[j] = j0 + j < k ? slots[j0 + j] : -1;
+        }
+        const float scale = agg_mode == AGG_NEIGH_MEAN ? (len > 0 ? 1.f / (float)len : 0.f)
+                          : agg_mode == AGG_SELF_MEAN  ? 1.f / (float)(len + 1) : 1.f;
+        float* o = out + row * ld_out + (int64_t)u * VEC;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) o[c] = acc[c] * scale;
+    }
+}
+
+template <typename T, int VEC>
+static void launch_padded(const T* src, int64_t ld_src, const int32_t* pad, int32_t k, const int32_t* d_n, int32_t n_cap,
+                          float* out, int64_t ld_out, int32_t dim, hipStream_t st, const int32_t* self_idx, int32_t agg_mode,
+                          const RowCopyJob* copy, hipEvent_t ev0, hipEvent_t ev1) {
+    const int32_t units = dim / VEC;
+    int g_log2 = 0;
+    while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
+    const int32_t n_chunks = (int32_t)ceil_div(units, 1 << g_log2);
+    int64_t waves = ceil_div((int64_t)n_cap * n_chunks, 64 >> g_log2);
+    int64_t blocks = ceil_div(waves, 4);
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    if (blocks < 1) blocks = 1;
+    RowCopyJob job = copy ? *copy : RowCopyJob{};
+    int64_t copy_blocks = 0;
+    if (job.dst) {
+        job.first_block = (uint32_t)blocks;
+        copy_blocks = ceil_div(job.n_cap, 4);
+        if (copy_blocks > 1024) copy_blocks = 1024;
+        if (copy_blocks < 1) copy_blocks = 1;
+    }
+    if (k <= 8)
+        NO_LAUNCH_TIMED((padded_rows_kernel<T, VEC, 8>), dim3((unsigned)(blocks + copy_blocks)), dim3(256), st, ev0, ev1, job, src,
+                        ld_src, pad, k, d_n, n_cap, out, ld_out, units, g_log2, n_chunks, self_idx, agg_mode);
+    else
+        NO_LAUNCH_TIMED((padded_rows_kernel<T, VEC, 16>), dim3((unsigned)(blocks + copy_blocks)), dim3(256), st, ev0, ev1, job, src,
+                        ld_src, pad, k, d_n, n_cap, out, ld_out, units, g_log2, n_chunks, self_idx, agg_mode);
+}
+
 int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_t* indptr, const int32_t* indices,
                        const int32_t* d_n_dst, int32_t n_dst_cap, float* mean, hipStream_t st, int32_t agg_mode,
                        const int32_t* self_idx, const RowCopyJob* copy, hipEvent_t ev0, hipEvent_t ev1,
-                       const SourceWeights* weights) {
+                       const SourceWeights* weights, const PaddedSlots* padded) {
     if (n_dst_cap <= 0) return NO_OK;
+    static const char* no_padded = getenv("NO_AGG_NO_PADDED");
+    if (padded && padded->pad && !(weights && weights->cnt) && !no_padded) {
+        // the rows are addressed through the sampler's slot array (global ids): two memory round trips fewer per item
+        const int32_t* pad = padded->pad;
+        const int32_t k = padded->k;
+#define NO_PAD_FWD(T, V, ptr) \
+    launch_padded<T, V>(ptr, dim, pad, k, d_n_dst, n_dst_cap, mean, dim, dim, st, self_idx, agg_mode, copy, ev0, ev1)
+        if (dt == NO_F32) {
+            const float* x = (const float*)x_src;
+            const bool a16 = (((uintptr_t)x | (uintptr_t)mean) & 15) == 0, a8 = (((uintptr_t)x | (uintptr_t)mean) & 7) == 0;
+            if (dim % 4 == 0 && a16) NO_PAD_FWD(float, 4, x);
+            else if (dim % 2 == 0 && a8) NO_PAD_FWD(float, 2, x);
+            else NO_PAD_FWD(float, 1, x);
+        } else {
+            const uint16_t* x = (const uint16_t*)x_src;
+            if (dim % 8 == 0 && ((uintptr_t)x & 15) == 0 && ((uintptr_t)mean & 15) == 0) NO_PAD_FWD(uint16_t, 8, x);
+            else if (dim % 2 == 0 && ((uintptr_t)x & 3) == 0) NO_PAD_FWD(uint16_t, 2, x);
+            else NO_PAD_FWD(uint16_t, 1, x);
+        }
+#undef NO_PAD_FWD
+        return launch_status("mean_aggregate (slot array)");
+    }
 #define NO_SEG_FWD(T, V, ptr) \
     launch_segment<T, V, true>(ptr, dim, indptr, indices, d_n_dst, n_dst_cap, nullptr, mean, dim, dim, st, self_idx, agg_mode, \
                                nullptr, nullptr, nullptr, copy, ev0, ev1, weights)
@@ -353,6 +506,12 @@ static inline unsigned ew_blocks(int64_t total) {
     return (unsigned)b;
 }
 
+int32_t bf16_rows_to_f32(const uint16_t* x, const int32_t* d_n, int32_t n_cap, int32_t dim, float* out, hipStream_t st) {
+    if (n_cap <= 0 || dim <= 0) return NO_OK;
+    hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)n_cap * dim)), dim3(256), 0, st, x, d_n, n_cap, dim, out);
+    return launch_status("bf16_rows_to_f32");
+}
+
 // ------------------------------------------------------------------------ workspace layout
 
 // Number of row slices of the weight-gradient product: enough 64x64 output tiles x slices to give every
@@ -391,7 +550,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
                      const void* agg_table, hipEvent_t wait_before_gemm, int32_t arch, const Layer1Reuse* reuse,
-                     bool aggregate_done, const SourceWeights* weights) {
+                     bool aggregate_done, const SourceWeights* weights, const PaddedSlots* padded) {
     // aggregate_done: `mean` (and the reused rows of H^1) were already written by an earlier launch of the same
     // aggregation (a batch prepared ahead); only the product runs
     // reuse: the output rows are scattered into H^1, recomputed hot rows also refresh the cache, and the reused
@@ -414,7 +573,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
         }
         NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
                                 blk.n_dst_cap, mean, st, mode, agg_table ? blk.d_src_global : nullptr, hits, e0, e1,
-                                arch == NO_ARCH_GCN_SYM ? weights : nullptr));
+                                arch == NO_ARCH_GCN_SYM ? weights : nullptr, agg_table ? padded : nullptr));
         GemmNNArgs a{};
         a.A[0] = mean; a.lda[0] = d_in; a.a_align[0] = ptr_align(mean, d_in);
         a.B[0] = w_self; a.ldb[0] = d_out; a.b_align[0] = ptr_align(w_self, d_out);
@@ -438,13 +597,14 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     if (prof && agg_stage >= 0 && !aggregate_done) prof->kernel_pair(agg_stage, &e0, &e1);
     if (!aggregate_done)
         NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
-                                blk.n_dst_cap, mean, st, AGG_NEIGH_MEAN, nullptr, hits, e0, e1));
+                                blk.n_dst_cap, mean, st, AGG_NEIGH_MEAN, nullptr, hits, e0, e1, nullptr,
+                                agg_table ? padded : nullptr));
     if (wait_before_gemm && !direct_self)
         NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
     const float* x_dst = direct_self ? (const float*)agg_table : (const float*)x_src;
     if (dt == NO_BF16) {
-        hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)blk.n_dst_cap * d_in)), dim3(256), 0, st,
-                           (const uint16_t*)x_src, blk.d_n_dst, blk.n_dst_cap, d_in, w.x_dst_f32);
+        if (!w.x_dst_f32_ready)
+            NO_CHECK(bf16_rows_to_f32((const uint16_t*)x_src, blk.d_n_dst, blk.n_dst_cap, d_in, w.x_dst_f32, st));
         x_dst = w.x_dst_f32;
     }
     GemmNNArgs a{};
@@ -487,8 +647,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     }
     const float* x_dst = (const float*)x_src;
     if (dt == NO_BF16 && !gcn) {
-        hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)n_cap * d_in)), dim3(256), 0, st,
-                           (const uint16_t*)x_src, blk.d_n_dst, n_cap, d_in, w.x_dst_f32);
+        if (!w.x_dst_f32_ready)
+            NO_CHECK(bf16_rows_to_f32((const uint16_t*)x_src, blk.d_n_dst, n_cap, d_in, w.x_dst_f32, st));
         x_dst = w.x_dst_f32;
     }
     if (prof && prep_stage >= 0) prof->end();
@@ -531,7 +691,14 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     t.G = gz; t.ldg = d_out; t.g_align = ptr_align(gz, d_out);
     t.P = w.partials; t.Kp = d_in; t.N = d_out;
     t.d_R = blk.d_n_dst; t.R_cap = n_cap; t.splits = w.splits;
-    const ReduceArgs r{w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, gcn ? 1 : 2};
+    // Batches that fill a fraction of the capacity use fewer slices than the capacity-sized bound: a slice keeps at least
+    // this many rows. Measured on a batch of 24 K rows (bound: 64 slices): the product takes the same time from 64 down
+    // to 93 slices' worth of rows (256 per slice) and 10 % longer at 384 and above (too few blocks), while the reduction
+    // after it reads fewer partial tiles. NO_TN_ROWS_PER_SPLIT=<rows> (tuning aid; 0 = always all slices)
+    static const char* env_rps = getenv("NO_TN_ROWS_PER_SPLIT");
+    t.rows_per_split = env_rps ? atoi(env_rps) : 256;
+    ReduceArgs r{w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, gcn ? 1 : 2};
+    r.d_R = t.d_R; r.R_cap = t.R_cap; r.rows_per_split = t.rows_per_split;
     if (pending && defer) {
         // an upper layer inside a step: its product and reduction ride on the bottom layer's launches
         if (pending->n >= NO_MAX_LAYERS) { set_error("sage_backward: too many deferred layers"); return NO_ERR_CAPACITY; }

@@ -19,6 +19,7 @@ struct no_model_s {
     size_t off_w_self[NO_MAX_LAYERS], off_w_neigh[NO_MAX_LAYERS], off_bias[NO_MAX_LAYERS];
     size_t n_params = 0;
     no::DevBuf<char> x0;                             // gathered rows of the bottom hop's destinations [n_dst_cap, F]
+    no::DevBuf<float> x0_f32, x0_f32_alt;            // bf16 tables: the same rows in fp32 (operand of the layer-1 products)
     no::DevBuf<float> mean[NO_MAX_LAYERS];           // layer l (index l-1): [n_dst_cap, d_{l-1}]
     no::DevBuf<float> h[NO_MAX_LAYERS];              // layer l output [rows, d_l]; h[0] holds all of V^1
     no::DevBuf<float> gh[NO_MAX_LAYERS];             // gradient w.r.t. h[l-1]
@@ -59,7 +60,7 @@ struct no_model_s {
         mean_alt.release();
         h0_alt.release();
         if (blocks_alt) { blocks_alt->release(); delete blocks_alt; blocks_alt = nullptr; }
-        x0_alt.release();
+        x0_alt.release(); x0_f32.release(); x0_f32_alt.release();
         if (blocks) { blocks->release(); delete blocks; blocks = nullptr; }
         params.release(); grads.release(); x0.release();
         for (auto& b : mean) b.release();
@@ -147,6 +148,7 @@ extern "C" int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t
     const HopBuffers& bottom = m->blocks->hop[L - 1];
     const size_t es = feat_dtype == NO_F32 ? 4 : 2;
     NO_CHECK(m->x0.alloc((size_t)bottom.n_dst_cap * m->dims[0] * es));
+    if (feat_dtype == NO_BF16) NO_CHECK(m->x0_f32.alloc((size_t)bottom.n_dst_cap * m->dims[0]));
     size_t ws_bytes = 0;
     for (int32_t l = 1; l <= L; ++l) {
         const HopBuffers& H = m->blocks->hop[L - l];
@@ -229,6 +231,7 @@ static int32_t ensure_lookahead(no_model_s* m, no_graph_s* g) {
     NO_CHECK(blocks_create_impl(g, m->n_seeds_cap, m->fanouts, m->n_layers, true, &m->blocks_alt));
     m->blocks_alt->count_sources = m->arch == NO_ARCH_GCN_SYM;
     NO_CHECK(m->x0_alt.alloc(m->x0.n));
+    if (m->feat_dtype == NO_BF16) NO_CHECK(m->x0_f32_alt.alloc(m->x0_f32.n));
     NO_CHECK(m->mean_alt.alloc(m->mean[0].n));
     NO_CHECK(m->h0_alt.alloc(m->h[0].n));
     NO_HIP_CHECK(hipStreamCreateWithFlags(&m->sample_stream, hipStreamNonBlocking));
@@ -275,6 +278,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         if (presampled) {
             std::swap(m->blocks, m->blocks_alt);
             std::swap(m->x0.p, m->x0_alt.p);
+            std::swap(m->x0_f32.p, m->x0_f32_alt.p);
             if (m->ahead_aggregated) {
                 std::swap(m->mean[0].p, m->mean_alt.p);
                 std::swap(m->h[0].p, m->h0_alt.p);
@@ -304,6 +308,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     sg.table = arch_is_gcn(m->arch) ? nullptr : d_features;    // GCN-style layers read every row inside the aggregation
     sg.row_bytes = row_bytes;
     sg.out = m->x0.p;
+    sg.out_f32 = (m->feat_dtype == NO_BF16 && sg.table) ? m->x0_f32.p : nullptr;
     static const char* no_direct = getenv("NO_SELF_FROM_COPY");
     sg.needed_by_forward = m->feat_dtype != NO_F32 || no_direct;   // fp32: the forward product reads the table rows itself
     hipEvent_t sev0 = nullptr, sev1 = nullptr;
@@ -343,6 +348,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_can_sample, 0));
         SideGather sg2 = sg;
         sg2.out = m->x0_alt.p;
+        sg2.out_f32 = sg.out_f32 ? m->x0_f32_alt.p : nullptr;
         m->blocks_alt->scan_two_pass = true;      // this sampling shares the chip with the step's products
         NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
                                     m->blocks_alt, m->sample_stream, false, &sg2, ahead_inline != nullptr, true));
@@ -372,8 +378,10 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             next_hits.d_n = NB->counts.p + 4 * L + 1; next_hits.n_cap = nv.n_dst_cap; next_hits.dst = m->h0_alt.p;
             next_hits.dim = m->dims[1];
         }
+        const PaddedSlots next_slots{NB->hop[L - 1].nbr_pad.p, NB->hop[L - 1].fanout};
         NO_CHECK(mean_aggregate(d_features, m->feat_dtype, m->dims[0], nv.d_indptr, nv.d_nbr_global, nv.d_n_dst, nv.n_dst_cap,
-                                m->mean_alt.p, m->sample_stream, AGG_NEIGH_MEAN, nullptr, next_cache ? &next_hits : nullptr));
+                                m->mean_alt.p, m->sample_stream, AGG_NEIGH_MEAN, nullptr, next_cache ? &next_hits : nullptr,
+                                nullptr, nullptr, nullptr, &next_slots));
         NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
         m->ahead_aggregated = true;
         return NO_OK;
@@ -403,6 +411,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             reuse.hits.d_n = extra + 1; reuse.hits.n_cap = blk.n_dst_cap; reuse.hits.dst = m->h[0].p; reuse.hits.dim = d_out;
         }
         LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
+        if (l == 1 && sg.out_f32) { w.x_dst_f32 = m->x0_f32.p; w.x_dst_f32_ready = true; }     // made beside the row copy
         // symmetric normalisation: the column sums of the block's adjacency are the per-source edge counts of the hop
         // (written with the local indices on the blocks' side stream); the fused layer-1 aggregate reads global ids,
         // so it also takes the local index of every entry
@@ -420,11 +429,12 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             // dense product then waits for the destination rows copied on the side stream
             no_block_view fused = blk;
             fused.d_indices = blk.d_nbr_global;
+            const PaddedSlots slots{B->hop[L - 1].nbr_pad.p, B->hop[L - 1].fanout};
             NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
                                   NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features,
                                   arch_is_gcn(m->arch) ? nullptr : B->ev_gather_done, m->arch,
-                                  (l == 1 && used_cache) ? &reuse : nullptr, aggregated, &sw));
+                                  (l == 1 && used_cache) ? &reuse : nullptr, aggregated, &sw, &slots));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
@@ -487,6 +497,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         }
         if (l < L) gz_in = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out).gz;
         LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
+        if (l == 1 && sg.out_f32) { w.x_dst_f32 = m->x0_f32.p; w.x_dst_f32_ready = true; }
         SourceWeights sw;
         if (m->arch == NO_ARCH_GCN_SYM) sw.cnt = B->hop[L - l].csc_cnt.p;
         NO_CHECK(sage_backward(blk, x, dt, d_in, m->mean[l - 1].p, h_l, gh_l, m->params.p + m->off_w_self[l - 1],
