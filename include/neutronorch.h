@@ -63,14 +63,22 @@ const char* no_last_error(void);
  * Graph (input G(V,E) of Algorithm 1; N_in(v) of Eq. 1)
  * ---------------------------------------------------------------------------------------- */
 
-enum { NO_CSR_INPUT_ON_DEVICE = 1u };
+enum {
+    NO_CSR_INPUT_ON_DEVICE = 1u,   /* src / dst are device pointers */
+    NO_CSR_IDS_64 = 2u,            /* src / dst are int64 arrays (the ids themselves must still lie in [0, V), V < 2^31) */
+    NO_CSR_SYMMETRISE = 4u,        /* every edge (s -> d) is also taken as (d -> s): 2 * n_edges edges */
+    NO_CSR_DEDUP = 8u              /* of several equal edges (s -> d) one is kept (after symmetrising); needs < 2^31 edges */
+};
 
 /* Builds the in-neighbour CSR of a directed multigraph: row v lists every src with an edge
- * (src -> v), ascending by src, duplicates and self-loops kept.
- *   src, dst     int32[n_edges]; host pointers, or device pointers with NO_CSR_INPUT_ON_DEVICE.
- *   rowptr_bits  32 or 64: width of the row-pointer array (32 needs n_edges < 2^31).
+ * (src -> v), ascending by src; self-loops are kept, and so are duplicates unless NO_CSR_DEDUP is given.
+ *   src, dst     int32[n_edges] (int64[n_edges] with NO_CSR_IDS_64); host pointers, or device pointers with
+ *                NO_CSR_INPUT_ON_DEVICE.
+ *   rowptr_bits  32 or 64: width of the row-pointer array (32 needs fewer than 2^31 edges after symmetrising).
+ * Errors: NO_ERR_OUT_OF_RANGE for an endpoint outside [0, V), NO_ERR_OVERFLOW / NO_ERR_UNSUPPORTED for sizes beyond
+ * the limits above (at most 2^32 - 2 edges), NO_ERR_INVALID_ARG for unknown flags.
  * Synchronises the stream before returning (it validates ids and sizes scratch). */
-int32_t no_build_csr(const int32_t* src, const int32_t* dst, int64_t n_edges, int64_t n_vertices,
+int32_t no_build_csr(const void* src, const void* dst, int64_t n_edges, int64_t n_vertices,
                      int32_t rowptr_bits, uint32_t flags, void* stream, no_graph_t* out);
 
 /* Device pointers into the graph: d_rowptr is int32[V+1] or int64[V+1] by *rowptr_bits. */

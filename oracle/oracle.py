@@ -139,8 +139,16 @@ class Graph:
         return int(self.rowptr[-1])
 
 
-def build_csr(src: np.ndarray, dst: np.ndarray, n_vertices: int) -> Graph:
-    """In-neighbour CSR (Eq. 1 aggregates over N_in): row dst holds its sources, ascending."""
+def build_csr(src: np.ndarray, dst: np.ndarray, n_vertices: int, symmetrise: bool = False, dedup: bool = False) -> Graph:
+    """In-neighbour CSR (Eq. 1 aggregates over N_in): row dst holds its sources, ascending; duplicates kept.
+    symmetrise: every edge is also taken the other way round; dedup: of equal (src, dst) pairs one is kept."""
+    src = np.asarray(src)
+    dst = np.asarray(dst)
+    if symmetrise:
+        src, dst = np.concatenate([src, dst]), np.concatenate([dst, src])
+    if dedup and len(src):
+        pairs = np.unique(np.stack([np.asarray(dst, np.int64), np.asarray(src, np.int64)], axis=1), axis=0)
+        dst, src = pairs[:, 0], pairs[:, 1]
     src = np.ascontiguousarray(src, dtype=np.int32)
     dst = np.ascontiguousarray(dst, dtype=np.int32)
     rowptr = np.zeros(n_vertices + 1, dtype=np.int64)

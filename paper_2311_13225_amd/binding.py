@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libneutronorch.so")
 NO_F32, NO_BF16 = 0, 1
 NO_ARCH_SAGE_MEAN, NO_ARCH_GCN, NO_ARCH_GCN_SUM, NO_ARCH_GCN_SYM = 0, 1, 2, 3
 ARCH_OF_NAME = {"sage": NO_ARCH_SAGE_MEAN, "gcn": NO_ARCH_GCN, "gcn_sum": NO_ARCH_GCN_SUM, "gcn_sym": NO_ARCH_GCN_SYM}
-NO_CSR_INPUT_ON_DEVICE = 1
+NO_CSR_INPUT_ON_DEVICE, NO_CSR_IDS_64, NO_CSR_SYMMETRISE, NO_CSR_DEDUP = 1, 2, 4, 8
 NO_MAX_LAYERS = 8
 ERROR_NAMES = {0: "NO_OK", -1: "NO_ERR_INVALID_ARG", -2: "NO_ERR_OUT_OF_RANGE", -3: "NO_ERR_CAPACITY",
                -4: "NO_ERR_OVERFLOW", -5: "NO_ERR_HIP", -6: "NO_ERR_UNSUPPORTED", -7: "NO_ERR_TIMEOUT"}
@@ -206,21 +206,25 @@ class Model(_Handle):
 
 # ------------------------------------------------------------------------------------------ graph
 
-def no_build_csr(src, dst, n_vertices: int, rowptr_bits: int = 64, stream=None) -> Graph:
-    """src, dst: int32 numpy arrays (host) or CUDA tensors (device)."""
+def no_build_csr(src, dst, n_vertices: int, rowptr_bits: int = 64, stream=None, symmetrise: bool = False,
+                 dedup: bool = False) -> Graph:
+    """src, dst: int32 or int64 numpy arrays (host) or CUDA tensors (device)."""
     on_device = isinstance(src, torch.Tensor) and src.is_cuda
     if on_device:
-        assert src.dtype == torch.int32 and dst.dtype == torch.int32 and src.is_contiguous() and dst.is_contiguous()
+        assert src.dtype == dst.dtype and src.dtype in (torch.int32, torch.int64) and src.is_contiguous() and dst.is_contiguous()
+        ids64 = src.dtype == torch.int64
         ps, pd, n = src.data_ptr(), dst.data_ptr(), src.numel()
     else:
-        src = np.ascontiguousarray(src, dtype=np.int32)
-        dst = np.ascontiguousarray(dst, dtype=np.int32)
+        ids64 = np.asarray(src).dtype == np.int64
+        src = np.ascontiguousarray(src, dtype=np.int64 if ids64 else np.int32)
+        dst = np.ascontiguousarray(dst, dtype=np.int64 if ids64 else np.int32)
         ps, pd, n = src.ctypes.data, dst.ctypes.data, len(src)
     assert len(dst) == n
     torch.cuda.init()
     out = C.c_void_p()
-    _check(lib().no_build_csr(ps, pd, n, n_vertices, rowptr_bits, NO_CSR_INPUT_ON_DEVICE if on_device else 0,
-                              _stream(stream), C.byref(out)))
+    flags = (NO_CSR_INPUT_ON_DEVICE if on_device else 0) | (NO_CSR_IDS_64 if ids64 else 0) | \
+            (NO_CSR_SYMMETRISE if symmetrise else 0) | (NO_CSR_DEDUP if dedup else 0)
+    _check(lib().no_build_csr(ps, pd, n, n_vertices, rowptr_bits, flags, _stream(stream), C.byref(out)))
     return Graph(out)
 
 

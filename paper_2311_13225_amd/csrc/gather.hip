@@ -6,7 +6,6 @@
 // reads 64/G rows at once with fully coalesced 64*W-byte requests; up to four lane-group widths of a
 // row are kept in flight per group.
 #include "common.hpp"
-#include <stdlib.h>
 
 namespace no {
 
@@ -60,29 +59,26 @@ static void launch_gather(const char* table, int64_t ts, const int32_t* ids, con
     const int32_t units = row_bytes / (int32_t)sizeof(VecT);
     int g_log2 = 0;
     while ((1 << g_log2) < units && g_log2 < 6) ++g_log2;
-    // One row per lane group and pass: with 2, 4 or 8 rows per group in flight the kernel measured 5-45 % slower on every
-    // row size tried (400 B: 2.9 -> 5.1 TB/s; 1 KB: 4.9 -> 5.4; 2408 B: 5.2 -> 5.7). A group then alternates loads and
-    // stores at a finer grain, and the many short wavefronts keep reads and writes overlapped across the chip.
-    static const char* env_rows = getenv("NO_GATHER_ROWS");
-    static const char* env_blocks = getenv("NO_GATHER_BLOCKS");
-    const int rows = env_rows ? atoi(env_rows) : 1;
-    const int64_t rows_per_wave = (int64_t)(64 >> g_log2) * rows;
+    // One row per lane group and pass: with 2, 4 or 8 rows per group in flight the kernel measured slower on every row
+    // size tried, with the ids repeated (rows served by the caches: 5-45 % slower) and with fresh ids and buffers every
+    // launch (256-byte rows out of a 28 GB table: 15 -> 27 us; 2408-byte rows: 35 -> 37-50 us). A group then alternates
+    // loads and stores at a finer grain, and the many short wavefronts keep reads and writes overlapped across the chip.
+    // A plain contiguous copy of the same bytes takes 13 us and 29 us: the gather pays one more dependent round trip
+    // (ids, then rows).
+    constexpr int ROWS = 1;
+    const int64_t rows_per_wave = (int64_t)(64 >> g_log2) * ROWS;
     int64_t waves = ceil_div(n_cap, rows_per_wave);
     int64_t blocks = ceil_div(waves, 4);
-    const int64_t max_blocks = env_blocks ? atoi(env_blocks) : 256 * 16;
+    const int64_t max_blocks = 256 * 16;
     if (blocks > max_blocks) blocks = max_blocks;
     if (blocks < 1) blocks = 1;
     const int32_t widths = (int32_t)ceil_div(units, 1 << g_log2);      // lane-group widths per row
-#define NO_GATHER_LAUNCH(R, U)                                                                                                \
-    hipLaunchKernelGGL((gather_rows_kernel<VecT, R, U>), dim3((unsigned)blocks), dim3(256), 0, st, table, ts, ids, d_n, \
+#define NO_GATHER_LAUNCH(U)                                                                                                \
+    hipLaunchKernelGGL((gather_rows_kernel<VecT, ROWS, U>), dim3((unsigned)blocks), dim3(256), 0, st, table, ts, ids, d_n, \
                        n_cap, out, os, units, g_log2)
-#define NO_GATHER_ROWS(R) \
-    do { if (widths > 2) NO_GATHER_LAUNCH(R, 4); else if (widths == 2) NO_GATHER_LAUNCH(R, 2); else NO_GATHER_LAUNCH(R, 1); } while (0)
-    if (rows == 8) NO_GATHER_ROWS(8);
-    else if (rows == 4) NO_GATHER_ROWS(4);
-    else if (rows == 2) NO_GATHER_ROWS(2);
-    else NO_GATHER_ROWS(1);
-#undef NO_GATHER_ROWS
+    if (widths > 2) NO_GATHER_LAUNCH(4);
+    else if (widths == 2) NO_GATHER_LAUNCH(2);
+    else NO_GATHER_LAUNCH(1);
 #undef NO_GATHER_LAUNCH
 }
 

@@ -626,49 +626,27 @@ __global__ void __launch_bounds__(256) gemm_nn_small_kernel(GemmNNArgs g) {
     }
 }
 
-// 64 x 64 tiles at every size: with the step pipeline and the register budget for three blocks per compute unit they
-// measured as fast as or faster than 64 x 128 and 128 x 64 from 8 K to 70 K rows (e.g. 27 K rows: 151 vs 165 us), and
-// they quantise best. NO_GEMM_TILE=<bm>x<bn> pins another shape (tuning aid; both values in {64, 128}, not both 128).
-static void pick_tile(int* bm, int* bn) {
-    *bm = 64; *bn = 64;
-    static const char* forced = getenv("NO_GEMM_TILE");
-    if (forced) {
-        int fm = 0, fn = 0;
-        if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128) && fm + fn < 256) {
-            *bm = fm; *bn = fn;
-        }
-    }
-}
-
+// 64 x 64 tiles at every size: with the branch-free pipeline and the scattered epilogue they measured as fast as or
+// faster than 64 x 128 and 128 x 64 from 8 K to 70 K rows (e.g. 27 K rows: 151 vs 165 us), and they quantise best;
+// register budget for three blocks per compute unit.
 template <bool B_KC>
-static void launch_nn(const GemmNNArgs& a, int bm, int bn, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+static void launch_nn(const GemmNNArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     const int64_t z = a.accumulate ? 1 : a.n_problems;
-    dim3 grid(xcd_padded(ceil_div(a.N, bn) * ceil_div(a.M_cap, bm) * z));
-    if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 128>), grid, dim3(256), st, ev0, ev1, a);
-    else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 128, 64>), grid, dim3(256), st, ev0, ev1, a);
-    else {
-        // NO_GEMM_OCC=<2|3>: blocks per compute unit the register budget allows (tuning aid)
-        static const char* env_occ = getenv("NO_GEMM_OCC");
-        const int occ = env_occ ? atoi(env_occ) : 3;
-        if (occ == 3) NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
-        else NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 1, 2, 2>), grid, dim3(256), st, ev0, ev1, a);
-    }
+    dim3 grid(xcd_padded(ceil_div(a.N, 64) * ceil_div(a.M_cap, 64) * z));
+    NO_LAUNCH_TIMED((gemm_nn_kernel<B_KC, 64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, a);
 }
 
 int32_t gemm_nn(const GemmNNArgs& a, bool b_transposed, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     if (a.M_cap <= 0 || a.N <= 0) return NO_OK;
     const int64_t z = a.accumulate ? 1 : a.n_problems;
-    static const char* no_small = getenv("NO_GEMM_NO_SMALL");      // tuning aid: keep small products on the tiled kernel
-    if (!no_small && ceil_div(a.M_cap, 64) * ceil_div(a.N, 64) * z <= 128) {
+    if (ceil_div(a.M_cap, 64) * ceil_div(a.N, 64) * z <= 128) {
         dim3 grid((unsigned)ceil_div(a.N, 32), (unsigned)ceil_div(a.M_cap, 32), (unsigned)z);
         if (b_transposed) NO_LAUNCH_TIMED((gemm_nn_small_kernel<true>), grid, dim3(256), st, ev0, ev1, a);
         else NO_LAUNCH_TIMED((gemm_nn_small_kernel<false>), grid, dim3(256), st, ev0, ev1, a);
         return launch_status("gemm_nn_small");
     }
-    int bm, bn;
-    pick_tile(&bm, &bn);
-    if (b_transposed) launch_nn<true>(a, bm, bn, st, ev0, ev1);
-    else launch_nn<false>(a, bm, bn, st, ev0, ev1);
+    if (b_transposed) launch_nn<true>(a, st, ev0, ev1);
+    else launch_nn<false>(a, st, ev0, ev1);
     return launch_status("gemm_nn");
 }
 
@@ -767,13 +745,7 @@ __global__ void __launch_bounds__(256, OCC) gemm_tn_kernel(TNLaunch launch) {
 int32_t gemm_tn_partials(const GemmTNArgs* jobs, int32_t n_jobs, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     // 64x64 tiles: the output of one split is small, so the chip is filled by many small blocks over a
     // moderate number of splits rather than by few large blocks over many splits (fewer partials to reduce).
-    // NO_TN_TILE=<bm>x<bn> pins another shape (tuning aid; both values in {64, 128}).
-    int bm = 64, bn = 64;
-    static const char* forced = getenv("NO_TN_TILE");
-    if (forced) {
-        int fm = 0, fn = 0;
-        if (sscanf(forced, "%dx%d", &fm, &fn) == 2 && (fm == 64 || fm == 128) && (fn == 64 || fn == 128)) { bm = fm; bn = fn; }
-    }
+    constexpr int bm = 64, bn = 64;
     TNLaunch launch{};
     uint64_t blocks = 0;
     for (int32_t j = 0; j < n_jobs && launch.n < NO_MAX_LAYERS; ++j) {
@@ -787,15 +759,7 @@ int32_t gemm_tn_partials(const GemmTNArgs* jobs, int32_t n_jobs, hipStream_t st,
     }
     if (launch.n == 0) return NO_OK;
     dim3 grid((unsigned)blocks);
-    if (bm == 128 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 128>), grid, dim3(256), st, ev0, ev1, launch);
-    else if (bm == 64 && bn == 128) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 128>), grid, dim3(256), st, ev0, ev1, launch);
-    else if (bm == 128 && bn == 64) NO_LAUNCH_TIMED((gemm_tn_kernel<128, 64>), grid, dim3(256), st, ev0, ev1, launch);
-    else {
-        static const char* env_occ = getenv("NO_TN_OCC");          // tuning aid, as for the forward product
-        const int occ = env_occ ? atoi(env_occ) : 3;
-        if (occ == 3) NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, launch);
-        else NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 2>), grid, dim3(256), st, ev0, ev1, launch);
-    }
+    NO_LAUNCH_TIMED((gemm_tn_kernel<64, 64, 1, 2, 3>), grid, dim3(256), st, ev0, ev1, launch);
     return launch_status("gemm_tn");
 }
 

@@ -144,7 +144,7 @@ struct SideGather { const void* table = nullptr; int32_t row_bytes = 0; void* ou
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key,
                            uint32_t domain, int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b,
                            hipStream_t st, bool join = true, const SideGather* gather = nullptr,
-                           bool inline_side = false, bool stamp_refresh = false);
+                           bool stamp_refresh = false);
 int32_t blocks_join(no_blocks_s* b, hipStream_t st);
 // stamp_refresh: the split writes `step` into the version of every cache slot the batch will recompute (training
 // calls; the row follows with the layer-1 product). blocks_unstamp takes the stamps back for a batch that is dropped.

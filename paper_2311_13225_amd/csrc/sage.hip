@@ -281,8 +281,7 @@ static void launch_segment(const T* src, int64_t ld_src, const int32_t* seg, con
     const int32_t n_chunks = (int32_t)ceil_div(units, 1 << g_log2);
     int64_t waves = ceil_div((int64_t)n_cap * n_chunks, 64 >> g_log2);
     int64_t blocks = ceil_div(waves, 4);
-    static const char* env_blocks = getenv("NO_AGG_BLOCKS");
-    if (blocks > (env_blocks ? atoi(env_blocks) : 256 * 64)) blocks = env_blocks ? atoi(env_blocks) : 256 * 64;
+    if (blocks > 256 * 64) blocks = 256 * 64;
     if (blocks < 1) blocks = 1;
     RowCopyJob job = copy ? *copy : RowCopyJob{};
     int64_t copy_blocks = 0;
@@ -410,8 +409,7 @@ int32_t mean_aggregate(const void* x_src, no_dtype dt, int32_t dim, const int32_
                        const int32_t* self_idx, const RowCopyJob* copy, hipEvent_t ev0, hipEvent_t ev1,
                        const SourceWeights* weights, const PaddedSlots* padded) {
     if (n_dst_cap <= 0) return NO_OK;
-    static const char* no_padded = getenv("NO_AGG_NO_PADDED");
-    if (padded && padded->pad && !(weights && weights->cnt) && !no_padded) {
+    if (padded && padded->pad && !(weights && weights->cnt)) {
         // the rows are addressed through the sampler's slot array (global ids): two memory round trips fewer per item
         const int32_t* pad = padded->pad;
         const int32_t k = padded->k;
@@ -518,11 +516,9 @@ int32_t bf16_rows_to_f32(const uint16_t* x, const int32_t* d_n, int32_t n_cap, i
 // compute unit several blocks, bounded so that a slice keeps at least 64 rows of the capacity.
 int32_t layer_splits(int32_t n_dst_cap, int32_t d_in, int32_t d_out) {
     const int64_t tiles = 2 * ceil_div(d_in + 1, 64) * ceil_div(d_out, 64);
-    static const char* env = getenv("NO_TN_BLOCKS");      // tuning aid: target number of blocks of the split product
-    const int64_t target = env && atoi(env) > 0 ? atoi(env) : 1600;
+    const int64_t target = 1600;      // blocks of the split product (measured: flat from 960 to 1600, slower beyond)
     int64_t s = ceil_div(target, tiles);
-    static const char* env_rows = getenv("NO_TN_MIN_ROWS");       // tuning aid: fewest rows of the capacity per slice
-    const int64_t by_rows = ceil_div(n_dst_cap, env_rows && atoi(env_rows) > 0 ? atoi(env_rows) : 64);
+    const int64_t by_rows = ceil_div(n_dst_cap, 64);
     if (s > by_rows) s = by_rows;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
@@ -591,8 +587,7 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
     // while x_src holds only the destination rows (fused gather + aggregate of the bottom layer). An fp32
     // table also feeds the self product directly, row m = table row src_global[m], so the forward pass
     // does not wait for the dense copy of the destination rows at all.
-    static const char* no_direct = getenv("NO_SELF_FROM_COPY");      // tuning aid: self product reads the dense copy
-    const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global && !no_direct;
+    const bool direct_self = agg_table && dt == NO_F32 && blk.d_src_global;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (prof && agg_stage >= 0 && !aggregate_done) prof->kernel_pair(agg_stage, &e0, &e1);
     if (!aggregate_done)
@@ -694,9 +689,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     // Batches that fill a fraction of the capacity use fewer slices than the capacity-sized bound: a slice keeps at least
     // this many rows. Measured on a batch of 24 K rows (bound: 64 slices): the product takes the same time from 64 down
     // to 93 slices' worth of rows (256 per slice) and 10 % longer at 384 and above (too few blocks), while the reduction
-    // after it reads fewer partial tiles. NO_TN_ROWS_PER_SPLIT=<rows> (tuning aid; 0 = always all slices)
-    static const char* env_rps = getenv("NO_TN_ROWS_PER_SPLIT");
-    t.rows_per_split = env_rps ? atoi(env_rps) : 256;
+    // after it reads fewer partial tiles.
+    t.rows_per_split = 256;
     ReduceArgs r{w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, gcn ? 1 : 2};
     r.d_R = t.d_R; r.R_cap = t.R_cap; r.rows_per_split = t.rows_per_split;
     if (pending && defer) {

@@ -769,9 +769,8 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
     const uint64_t k_magic = k > 1 ? (~0ull / (uint64_t)k) + 1ull : 0ull;     // ceil(2^64 / k)
     // One launch where the sampling has the chip to itself or nearly so; two where it runs beside another batch's
     // products (sampling ahead): there the single-pass blocks, which wait on their predecessors while holding a slot,
-    // measured slower than two short launches. NO_SCAN_TWO_PASS=<0|1> forces either form (tuning aid).
-    static const char* env_two_pass = getenv("NO_SCAN_TWO_PASS");
-    const bool two_pass = env_two_pass ? atoi(env_two_pass) != 0 : b->scan_two_pass;
+    // measured slower than two short launches.
+    const bool two_pass = b->scan_two_pass;
     const ScanWaitDebug dbg = scan_wait_debug();
     if (two_pass) {
         hipLaunchKernelGGL(edge_tile_sums_kernel, dim3(tiles), dim3(ETHREADS), 0, st, H.nbr_pad.p,
@@ -800,15 +799,11 @@ static int32_t sample_hop(const RowT* rowptr, const int32_t* col, no_blocks_s* b
 // that first saw it, so the map still answers for the hops above unless the cache split re-keyed it),
 // the transposes of the upper hops, and the wipe of the id map.
 static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d_n_src_last, hipStream_t st,
-                                const SideGather* gather, const bool* indices_done, bool inline_side) {
+                                const SideGather* gather, const bool* indices_done) {
     const int T = 256;
-    // inline_side: the caller's stream is itself off every dependency chain (sampling ahead), so the work stays on
-    // it and costs no fork, join or readiness events
-    hipStream_t sd = inline_side ? st : b->side;
-    if (!inline_side) {
-        NO_HIP_CHECK(hipEventRecord(b->ev_fork[0], st));
-        NO_HIP_CHECK(hipStreamWaitEvent(sd, b->ev_fork[0], 0));
-    }
+    hipStream_t sd = b->side;
+    NO_HIP_CHECK(hipEventRecord(b->ev_fork[0], st));
+    NO_HIP_CHECK(hipStreamWaitEvent(sd, b->ev_fork[0], 0));
     // the dense copy of the bottom destinations' rows goes first when the forward pass waits for it, else last
     // (then it runs next to the matrix products instead of next to the bandwidth-bound aggregation)
     auto copy_rows = [&]() -> int32_t {
@@ -818,7 +813,7 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
         if (gather->out_f32)
             NO_CHECK(bf16_rows_to_f32((const uint16_t*)gather->out, b->counts.p + 4 * (n_hops - 1), lastg.n_dst_cap,
                                       gather->row_bytes / 2, gather->out_f32, sd));
-        if (!inline_side) NO_HIP_CHECK(hipEventRecord(b->ev_gather_done, sd));
+        NO_HIP_CHECK(hipEventRecord(b->ev_gather_done, sd));
         return NO_OK;
     };
     const bool have_copy = gather && gather->table;
@@ -833,7 +828,7 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
         hipLaunchKernelGGL(edge_indices_kernel, dim3((unsigned)ceil_div(H.nnz_cap, T)), dim3(T), 0, sd,
                            (const int32_t*)(cnt + 2), (const int32_t*)H.nbr_global.p, (const int32_t*)b->map.p,
                            H.indices.p, counts_sources(b, H) ? H.csc_cnt.p : nullptr);
-        if (h < n_hops - 1 && !inline_side) b->upper_indices_deferred = true;
+        if (h < n_hops - 1) b->upper_indices_deferred = true;
     }
     NO_HIP_CHECK(hipEventRecord(b->ev_indices_done, sd));
     for (int32_t h = 0; h < n_hops; ++h) {
@@ -851,7 +846,7 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
     hipLaunchKernelGGL(map_wipe_kernel, dim3((unsigned)ceil_div(last.n_src_cap, T)), dim3(T), 0, sd,
                        (const int32_t*)last.src_global.p, d_n_src_last, b->map.p);
     if (have_copy && !gather->needed_by_forward) NO_CHECK(copy_rows());
-    b->side_pending = !inline_side;
+    b->side_pending = true;
     return launch_status("side work");
 }
 
@@ -865,18 +860,15 @@ int32_t blocks_join(no_blocks_s* b, hipStream_t st) {
 
 // One launch for the V^1 split where the sampling has the chip to itself, two launches where it runs beside another
 // batch's products, as for the edge compaction and for the same reason (measured on a V^1 of five tiles: sampling alone
-// 72 -> 68 us in one launch, but 2 % fewer steps per second when sampling ahead). NO_V1_TWO_PASS=<0|1> forces either
-// form (tuning aid).
+// 72 -> 68 us in one launch, but 2 % fewer steps per second when sampling ahead).
 static bool v1_one_launch(const no_blocks_s* b, unsigned tiles) {
     (void)tiles;
-    static const char* env = getenv("NO_V1_TWO_PASS");
-    if (env) return atoi(env) == 0;
     return !b->scan_two_pass;
 }
 
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key, uint32_t domain,
                            int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b, hipStream_t st, bool join,
-                           const SideGather* gather, bool inline_side, bool stamp_refresh) {
+                           const SideGather* gather, bool stamp_refresh) {
     NO_CHECK(blocks_join(b, st));      // a previous call that was never joined
     b->stamped_cache = nullptr;
     b->call_id = b->call_id % 0x3fffffff + 1;      // flag words written by this call's kernels carry this value
@@ -945,7 +937,7 @@ int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seed
         d_n = b->counts.p + 4 * h + 1;
     }
     if (!use_cache) hipLaunchKernelGGL(set_counts_kernel, dim3(1), dim3(1), 0, st, extra, 0, 0, 0);
-    NO_CHECK(launch_side_work(b, n_hops, d_n, st, gather, indices_done, inline_side));
+    NO_CHECK(launch_side_work(b, n_hops, d_n, st, gather, indices_done));
     NO_CHECK(launch_status("sample_blocks"));
     if (join) NO_CHECK(blocks_join(b, st));
     return NO_OK;

@@ -309,15 +309,14 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     sg.row_bytes = row_bytes;
     sg.out = m->x0.p;
     sg.out_f32 = (m->feat_dtype == NO_BF16 && sg.table) ? m->x0_f32.p : nullptr;
-    static const char* no_direct = getenv("NO_SELF_FROM_COPY");
-    sg.needed_by_forward = m->feat_dtype != NO_F32 || no_direct;   // fp32: the forward product reads the table rows itself
+    sg.needed_by_forward = m->feat_dtype != NO_F32;   // fp32: the forward product reads the table rows itself
     hipEvent_t sev0 = nullptr, sev1 = nullptr;
     if (!presampled) prof.kernel_pair(NO_STAGE_SAMPLE_ROWS_BOTTOM, &sev0, &sev1);
     prof.begin(NO_STAGE_SAMPLE);
     if (!presampled) B->scan_two_pass = false;
     if (!presampled) {
         B->time_ev0 = sev0; B->time_ev1 = sev1; B->time_hop = sev0 ? L - 1 : -1;
-        NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg, false, true));
+        NO_CHECK(sample_blocks_impl(g, d_seeds, n_seeds, seed + (uint64_t)step, 0u, L, cache, step, B, st, false, &sg, true));
         // measurement passes count the side stream's share of the sampling (local indices, transposes, map wipe) too
         if (prof.enabled) NO_CHECK(blocks_join(B, st));
     }
@@ -339,9 +338,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     // buffers stay as the step leaves them. Both run beside this step's matrix-bound kernels.
     // (The transposes, the local indices of the upper hops and the dense copy go to that batch's own side stream: they
     // are needed by its backward pass and upper layers only, and would otherwise sit between its sampling and its
-    // aggregation on the sampling stream, which is the longer of the two chains. NO_LOOKAHEAD_INLINE=1 keeps them on
-    // the sampling stream: tuning aid.)
-    static const char* ahead_inline = getenv("NO_LOOKAHEAD_INLINE");
+    // aggregation on the sampling stream, which is the longer of the two chains.)
     auto launch_sampling_ahead = [&]() -> int32_t {
         if (commit_refresh_before_next && cache) NO_CHECK(refresh_commit_impl(cache, st));
         NO_HIP_CHECK(hipEventRecord(m->ev_can_sample, st));
@@ -351,7 +348,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         sg2.out_f32 = sg.out_f32 ? m->x0_f32_alt.p : nullptr;
         m->blocks_alt->scan_two_pass = true;      // this sampling shares the chip with the step's products
         NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
-                                    m->blocks_alt, m->sample_stream, false, &sg2, ahead_inline != nullptr, true));
+                                    m->blocks_alt, m->sample_stream, false, &sg2, true));
         NO_HIP_CHECK(hipEventRecord(m->ev_sampled, m->sample_stream));
         m->ahead_valid = true;
         m->ahead_step = step + 1;
@@ -386,8 +383,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         m->ahead_aggregated = true;
         return NO_OK;
     };
-    static const char* late = getenv("NO_LOOKAHEAD_LATE");      // tuning aid: part one always after layer 1
-    const bool lookahead_early = d_next_seeds && !late && !(commit_refresh_before_next && cache);
+    const bool lookahead_early = d_next_seeds && !(commit_refresh_before_next && cache);
     if (lookahead_early) NO_CHECK(launch_sampling_ahead());
 
     // forward
@@ -467,8 +463,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     NO_CHECK(blocks_join(B, st));
     // The weight gradients of the layers above the bottom one (and their SGD step) are nobody's input within the step:
     // their products and reductions are carried by the bottom layer's two launches, which end the step, instead of
-    // adding two launches per layer to the chain of dependent kernels. (NO_DW_INLINE=1: tuning aid, one pair per layer.)
-    static const char* dw_inline = getenv("NO_DW_INLINE");
+    // adding two launches per layer to the chain of dependent kernels.
     GradJobs pending;
     for (int32_t l = L; l >= 1; --l) {
         const no_block_view& blk = view[L - l];
@@ -507,7 +502,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
                                l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
                                -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                                m->params.p + m->off_bias[l - 1], m->arch, l == 1 ? &stats_job : nullptr, gz_in,
-                               l >= 2 ? &below : nullptr, dw_inline ? nullptr : &pending, l >= 2, &sw));
+                               l >= 2 ? &below : nullptr, &pending, l >= 2, &sw));
     }
 
     // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;

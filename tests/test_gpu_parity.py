@@ -78,6 +78,30 @@ def test_build_csr_from_device_and_rejects_bad_ids():
         nb().no_build_csr(src, dst, 500, 48)
 
 
+@pytest.mark.parametrize("symmetrise,dedup,ids64,on_device", [(True, False, False, False), (False, True, False, True),
+                                                              (True, True, True, False), (False, False, True, True)])
+def test_build_csr_flags(symmetrise, dedup, ids64, on_device):
+    """Optional preparations of the edge list: both directions, duplicates dropped, 64-bit ids on input."""
+    b = nb()
+    V, E = 5000, 120_000
+    src, dst = si.rmat_edges(V, E, 3)
+    og = ora.build_csr(src, dst, V, symmetrise=symmetrise, dedup=dedup)
+    s_in, d_in = (src.astype(np.int64), dst.astype(np.int64)) if ids64 else (src, dst)
+    if on_device:
+        s_in, d_in = dev(s_in), dev(d_in)
+    gg = b.no_build_csr(s_in, d_in, V, 64, symmetrise=symmetrise, dedup=dedup)
+    v, e, bits, rowptr, col = b.no_graph_view(gg)
+    assert e == og.n_edges and (not dedup or e < (2 * E if symmetrise else E))
+    assert np.array_equal(rowptr.cpu().numpy(), og.rowptr)
+    assert np.array_equal(col.cpu().numpy()[:e], og.col)
+    if ids64:
+        bad = src.astype(np.int64)
+        bad[11] = 1 << 40
+        with pytest.raises(b.NoError) as ei:
+            b.no_build_csr(bad, dst.astype(np.int64), V, 64)
+        assert ei.value.code == -2
+
+
 # --------------------------------------------------------------------------------------- sampling
 
 def compare_blocks(b, blocks, sb, with_cache=False):

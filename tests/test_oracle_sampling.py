@@ -298,3 +298,24 @@ def test_bottom_hop_skips_reusable_hot_vertices():
         a = plain.blocks[1].nbr_global[plain.blocks[1].indptr[j]:plain.blocks[1].indptr[j + 1]]
         b = sb.blocks[1].nbr_global[sb.blocks[1].indptr[i]:sb.blocks[1].indptr[i + 1]]
         assert np.array_equal(a, b)
+
+
+def test_csr_symmetrise_and_dedup_against_set_arithmetic():
+    """The two optional preparations of the edge list: both directions of every edge, and one copy of equal edges."""
+    V = 40
+    src, dst = si.random_graph_small(V, 400, seed=7)
+    assert len({(int(a), int(b)) for a, b in zip(src, dst)}) < 400          # the input has multi-edges
+    g = ora.build_csr(src, dst, V, symmetrise=True, dedup=True)
+    want = {(int(a), int(b)) for a, b in zip(src, dst)} | {(int(b), int(a)) for a, b in zip(src, dst)}
+    got = [(int(g.col[e]), v) for v in range(V) for e in range(g.rowptr[v], g.rowptr[v + 1])]
+    assert len(got) == len(want) == g.n_edges and set(got) == want
+    for v in range(V):
+        row = g.col[g.rowptr[v]:g.rowptr[v + 1]]
+        assert (np.diff(row) > 0).all()
+    g2 = ora.build_csr(src, dst, V, symmetrise=True)
+    assert g2.n_edges == 800
+    for v in range(V):
+        assert sorted(g2.col[g2.rowptr[v]:g2.rowptr[v + 1]].tolist()) == sorted(
+            [int(a) for a, b in zip(src, dst) if b == v] + [int(b) for a, b in zip(src, dst) if a == v])
+    g3 = ora.build_csr(src, dst, V, dedup=True)
+    assert g3.n_edges == len({(int(a), int(b)) for a, b in zip(src, dst)})
