@@ -321,12 +321,22 @@ def mean_aggregate_adjoint(grad_mean: np.ndarray, indptr: np.ndarray, indices: n
     return out
 
 
-def sage_layer_fwd_z(blk: Block, x_src: np.ndarray, w_self, w_neigh, bias, relu: bool):
-    """Eq. 1 (mean over the sampled row) then Eq. 2 (dense update). Returns (mean, z, h), z = pre-activation."""
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Values rounded to bfloat16 (8 significant bits, fp32's exponent range), round-to-nearest-even, via fp32; returned
+    as fp64. The precision the matrix units take the operands of a product in when the feature table is bf16."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000).astype(np.uint32)
+    return r.view(np.float32).astype(np.float64)
+
+
+def sage_layer_fwd_z(blk: Block, x_src: np.ndarray, w_self, w_neigh, bias, relu: bool, bf16_products: bool = False):
+    """Eq. 1 (mean over the sampled row) then Eq. 2 (dense update). Returns (mean, z, h), z = pre-activation.
+    bf16_products: the two products of Eq. 2 take their operands (features, mean, weights) rounded to bf16 and
+    accumulate exactly: the arithmetic of a layer fed by a bf16 feature table ("bf16 with fp32 accumulate")."""
     x = np.asarray(x_src, dtype=np.float64)
     mean = mean_aggregate(x, blk.indptr, blk.indices, blk.n_dst)
-    z = x[: blk.n_dst] @ np.asarray(w_self, np.float64) + mean @ np.asarray(w_neigh, np.float64) \
-        + np.asarray(bias, np.float64)
+    q = round_to_bf16 if bf16_products else (lambda a: np.asarray(a, np.float64))
+    z = q(x[: blk.n_dst]) @ q(w_self) + q(mean) @ q(w_neigh) + np.asarray(bias, np.float64)
     h = np.maximum(z, 0.0) if relu else z
     return mean, z, h
 
@@ -338,18 +348,22 @@ def sage_layer_fwd(blk: Block, x_src: np.ndarray, w_self, w_neigh, bias, relu: b
 
 
 def sage_layer_bwd(blk: Block, x_src: np.ndarray, mean: np.ndarray, h: np.ndarray, grad_h: np.ndarray,
-                   w_self, w_neigh, relu: bool, need_grad_x: bool, active: Optional[np.ndarray] = None):
+                   w_self, w_neigh, relu: bool, need_grad_x: bool, active: Optional[np.ndarray] = None,
+                   bf16_products: bool = False):
     """Gradients of one layer. grad_x is None for the bottom layer (nothing below it learns).
     `active` (bool, shape of h) overrides the ReLU decision h > 0: a caller may supply decisions taken
-    in another precision for pre-activations that are zero to within rounding, where either is valid."""
+    in another precision for pre-activations that are zero to within rounding, where either is valid.
+    bf16_products: the two weight-gradient products take their operands (features, mean, gz) rounded to bf16; the bias
+    gradient is the plain column sum."""
     x = np.asarray(x_src, dtype=np.float64)
     if relu:
         gz = np.asarray(grad_h, np.float64) * ((np.asarray(h) > 0) if active is None else active)
     else:
         gz = np.asarray(grad_h, np.float64)
     x_dst = x[: blk.n_dst]
-    gw_self = x_dst.T @ gz
-    gw_neigh = np.asarray(mean, np.float64).T @ gz
+    q = round_to_bf16 if bf16_products else (lambda a: np.asarray(a, np.float64))
+    gw_self = q(x_dst).T @ q(gz)
+    gw_neigh = q(mean).T @ q(gz)
     gb = gz.sum(axis=0)
     gx = None
     if need_grad_x:
@@ -481,14 +495,19 @@ def _to_f64(x: np.ndarray, feat_is_bf16: bool) -> np.ndarray:
 
 def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray, fanouts: Sequence[int],
                weights, lr: float, seed: int, step: int, cache: Optional[Cache] = None,
-               feat_is_bf16: bool = False, relu_decisions=None, arch: str = "sage") -> StepResult:
+               feat_is_bf16: bool = False, relu_decisions=None, arch: str = "sage",
+               bf16_products: Optional[bool] = None) -> StepResult:
     """One pass of Algorithm 1's loop body with plain SGD; updates `cache` in place.
     arch "sage": GraphSAGE-mean layers, weights[l] = (w_self, w_neigh, bias); arch "gcn" / "gcn_sum" / "gcn_sym":
     layers that aggregate over N_in(v) U {v} (average / sum / symmetric normalisation) with one matrix,
     weights[l] = (w, bias); `mean` then holds that aggregate.
     relu_decisions: optional callable(layer, z_layer) -> bool array or None, consulted in the backward
-    pass for the ReLU decisions of layer `layer` given its pre-activations (rows of the computed vertices)."""
+    pass for the ReLU decisions of layer `layer` given its pre-activations (rows of the computed vertices).
+    bf16_products (default: on for a bf16 table with GraphSAGE-mean layers): layer 1's products, forward and weight
+    gradients, take bf16 operands (`sage_layer_fwd_z`, `sage_layer_bwd`); the layers above work on fp32 activations."""
     L = len(fanouts)
+    if bf16_products is None:
+        bf16_products = feat_is_bf16 and arch == "sage"
     sb = sample_blocks(g, seeds, fanouts, seed, step, cache)
     bottom = sb.blocks[-1]
     x0 = gather_features(feat, bottom.src_global)
@@ -502,7 +521,7 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
             mean, z, h = gcn_layer_fwd_z(blk, x, weights[l - 1][0], weights[l - 1][1], relu=(l < L), norm=gcn_norm_of(arch))
         else:
             w_self, w_neigh, bias = weights[l - 1]
-            mean, z, h = sage_layer_fwd_z(blk, x, w_self, w_neigh, bias, relu=(l < L))
+            mean, z, h = sage_layer_fwd_z(blk, x, w_self, w_neigh, bias, relu=(l < L), bf16_products=bf16_products and l == 1)
         means.append(mean)
         zs.append(z)
         if l == 1 and use_cache:
@@ -531,7 +550,8 @@ def train_step(g: Graph, feat: np.ndarray, labels: np.ndarray, seeds: np.ndarray
         else:
             w_self, w_neigh, _ = weights[l - 1]
             gws, gwn, gb, gx = sage_layer_bwd(blk, xs[l - 1], means[l - 1], h_l, gh, w_self, w_neigh,
-                                              relu=(l < L), need_grad_x=(l > 1), active=active)
+                                              relu=(l < L), need_grad_x=(l > 1), active=active,
+                                              bf16_products=bf16_products and l == 1)
             grads[l - 1] = (gws, gwn, gb)
         gh = gx
     new_w = [tuple(np.asarray(p, np.float64) - lr * q for p, q in zip(w, gr)) for w, gr in zip(weights, grads)]

@@ -251,7 +251,7 @@ def test_stale_gap_shrinks_with_learning_rate():
 def test_bf16_features_are_upcast_exactly():
     *_, g, feat, lab, train, weights, fanouts, B = _small_problem()
     fb = si.f32_to_bf16_bits(feat)
-    r1 = ora.train_step(g, fb, lab, train[:B], fanouts, weights, 0.1, 0, 0, None, feat_is_bf16=True)
+    r1 = ora.train_step(g, fb, lab, train[:B], fanouts, weights, 0.1, 0, 0, None, feat_is_bf16=True, bf16_products=False)
     r2 = ora.train_step(g, si.bf16_bits_to_f32(fb), lab, train[:B], fanouts, weights, 0.1, 0, 0)
     assert r1.loss == r2.loss
     assert r1.x0.dtype == np.uint16
@@ -355,3 +355,82 @@ def test_step_hook_is_consulted_for_hidden_layers_only_and_none_means_default(ar
                         relu_decisions=lambda layer, z: np.zeros(z.shape, bool), arch=arch)
     assert all(not np.any(a) for ga in r0.grads[:-1] for a in ga)
     assert any(np.any(a) for a in r0.grads[-1])
+
+
+# ------------------------------------------------------------------ bf16 operands for a bf16 feature table
+
+def test_round_to_bf16_matches_the_library_conversion_and_ties_go_to_even():
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-20, 20, 5000), [0.0, -0.0, 1.0, -1.0]]).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(ora.round_to_bf16(x).astype(np.float32), ref)
+    # exactly half-way cases: 1 + 2^-8 lies between 1 and 1 + 2^-7 and goes to the even one (1.0); 1 + 3 * 2^-8 goes up
+    assert ora.round_to_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert ora.round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    # values that are bf16 already are unchanged
+    b = si.bf16_bits_to_f32(si.f32_to_bf16_bits(x))
+    assert np.array_equal(ora.round_to_bf16(b).astype(np.float32), b)
+
+
+def test_bf16_products_stay_within_the_rounding_bound_of_the_exact_layer():
+    """Rounding an operand to bf16 (8 significant bits, nearest) moves it by at most 2^-9 of its size. A product with
+    one rounded operand (bf16 features x rounded weights) is off by at most 2^-9 of its size, with two rounded operands
+    (mean x weights) by 2 * 2^-9 + 2^-18: elementwise bounds on the pre-activations and on the weight gradients."""
+    *_, g, feat, lab, train, weights, fanouts, B = _small_problem(F=16, dims=(16, 12, 5), fanouts=(4, 3))
+    fb = si.f32_to_bf16_bits(feat)
+    x_tab = si.bf16_bits_to_f32(fb).astype(np.float64)
+    blk = ora.sample_blocks(g, train[:40], [4, 3], 0, 0).blocks[1]
+    x = x_tab[blk.src_global]
+    (ws, wn, bias) = weights[0]
+    u = 2.0 ** -9
+    mean, z, h = ora.sage_layer_fwd_z(blk, x, ws, wn, bias, True)
+    mean_b, z_b, h_b = ora.sage_layer_fwd_z(blk, x, ws, wn, bias, True, bf16_products=True)
+    assert np.array_equal(mean, mean_b)
+    bound = u * (np.abs(x[: blk.n_dst]) @ np.abs(ws)) + (2 * u + u * u) * (np.abs(mean) @ np.abs(wn))
+    assert (np.abs(z_b - z) <= bound * (1 + 1e-6) + 1e-300).all() and np.abs(z_b - z).max() > 0
+    gh = np.random.default_rng(1).standard_normal(h.shape)
+    act = z > 0
+    e = ora.sage_layer_bwd(blk, x, mean, h, gh, ws, wn, True, False, active=act)
+    r = ora.sage_layer_bwd(blk, x, mean, h, gh, ws, wn, True, False, active=act, bf16_products=True)
+    gz = gh * act
+    assert (np.abs(r[0] - e[0]) <= u * (np.abs(x[: blk.n_dst]).T @ np.abs(gz)) * (1 + 1e-6)).all()
+    assert (np.abs(r[1] - e[1]) <= (2 * u + u * u) * (np.abs(mean).T @ np.abs(gz)) * (1 + 1e-6)).all()
+    assert np.array_equal(r[2], e[2])                          # the bias gradient is the plain column sum
+
+
+def test_bf16_products_are_exact_when_every_operand_is_a_bf16_value():
+    """Fanout 1 makes the mean a feature row (bf16); weights and output gradients picked from a bf16 grid: nothing is
+    rounded, so the layer must equal the exact one bit for bit."""
+    *_, g, feat, lab, train, weights, fanouts, B = _small_problem(F=16, dims=(16, 12, 5), fanouts=(4, 3))
+    x_tab = si.bf16_bits_to_f32(si.f32_to_bf16_bits(feat)).astype(np.float64)
+    blk = ora.sample_blocks(g, train[:40], [4, 1], 0, 0).blocks[1]
+    x = x_tab[blk.src_global]
+    rng = np.random.default_rng(3)
+    ws, wn = rng.integers(-64, 64, (16, 12)) / 64.0, rng.integers(-64, 64, (16, 12)) / 128.0
+    bias = rng.standard_normal(12)
+    a = ora.sage_layer_fwd_z(blk, x, ws, wn, bias, True)
+    b_ = ora.sage_layer_fwd_z(blk, x, ws, wn, bias, True, bf16_products=True)
+    assert all(np.array_equal(p, q) for p, q in zip(a, b_))
+    gh = rng.integers(-32, 32, a[2].shape) / 16.0
+    e = ora.sage_layer_bwd(blk, x, a[0], a[2], gh, ws, wn, True, False)
+    r = ora.sage_layer_bwd(blk, x, a[0], a[2], gh, ws, wn, True, False, bf16_products=True)
+    assert all(np.array_equal(p, q) for p, q in zip(e[:3], r[:3]))
+
+
+def test_step_with_a_bf16_table_uses_bf16_products_in_layer_1_only():
+    *_, g, feat, lab, train, weights, fanouts, B = _small_problem()
+    fb = si.f32_to_bf16_bits(feat)
+    on = ora.train_step(g, fb, lab, train[:B], fanouts, weights, 0.1, 0, 0, None, feat_is_bf16=True)
+    off = ora.train_step(g, fb, lab, train[:B], fanouts, weights, 0.1, 0, 0, None, feat_is_bf16=True, bf16_products=False)
+    assert on.loss != off.loss and abs(on.loss - off.loss) < 2e-2 * abs(off.loss)
+    # the same blocks and the same (unrounded) mean; layer 1's output differs, and with it everything above
+    assert np.array_equal(on.mean[0], off.mean[0]) and not np.array_equal(on.h[0], off.h[0])
+    # layers above the bottom one are computed in full precision from whatever layer 1 gave them
+    blk = on.batch.blocks[-2]
+    _, _, h2 = ora.sage_layer_fwd_z(blk, on.h[0], *weights[1], relu=True)
+    assert np.array_equal(h2, on.h[1])
+    # GCN-style layers keep exact products
+    wg = [(w[0], w[2]) for w in weights]
+    a = ora.train_step(g, fb, lab, train[:B], fanouts, wg, 0.1, 0, 0, None, feat_is_bf16=True, arch="gcn")
+    b_ = ora.train_step(g, si.bf16_bits_to_f32(fb), lab, train[:B], fanouts, wg, 0.1, 0, 0, None, arch="gcn")
+    assert a.loss == b_.loss
