@@ -837,9 +837,13 @@ __global__ void __launch_bounds__(256) reduce_grads_kernel(ReduceLaunch launch, 
     for (; k < splits; ++k) s += p[(int64_t)k * per];
     float* gout = bias_row ? a.g_bias + (i - (int64_t)Kp * N) : (q == 0 ? a.g_self + i : a.g_neigh + i);
     *gout = s;
-    if (a.lr != 0.f) {
-        float* w = bias_row ? a.w_bias + (i - (int64_t)Kp * N) : (q == 0 ? a.w_self + i : a.w_neigh + i);
-        *w -= a.lr * s;
+    float* w = a.w_self ? (bias_row ? a.w_bias + (i - (int64_t)Kp * N) : (q == 0 ? a.w_self + i : a.w_neigh + i)) : nullptr;
+    if (a.lr != 0.f && w) *w -= a.lr * s;
+    if (a.wt_self && w && !bias_row) {
+        // the parameter's bf16 copy for the next step's products (transposed: [N][Kpad]), round-to-nearest-even
+        const uint32_t u = __float_as_uint(*w);
+        const int32_t k = (int32_t)(i / N), n = (int32_t)(i - (int64_t)k * N);
+        (q == 0 ? a.wt_self : a.wt_neigh)[(int64_t)n * a.Kpad + k] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
     }
 }
 

@@ -49,6 +49,29 @@ __host__ __device__ inline int32_t tn_used_splits(int32_t R, int32_t splits, int
     return s < splits ? s : splits;
 }
 
+// Products with bf16 operands (a layer fed by a bf16 feature table): see gemm_bf16.hip.
+struct GemmBf16NNArgs {
+    const uint16_t* X; int64_t ldx; const int32_t* x_rows;   // first operand: bf16 rows; row m is row x_rows[m] of X (NULL: m)
+    const float* Mn; int64_t ldm;                            // second operand: fp32 rows, rounded to bf16 on load
+    const uint16_t* Wt[2]; int32_t Kpad;                     // the two weight matrices as bf16 [N][Kpad] (weights_to_bf16_t)
+    int32_t K, N;
+    float* C; int64_t ldc;
+    const int32_t* d_M; int32_t M_cap;
+    const float* bias; int32_t relu;
+    const int32_t* c_rows; float* c_keep; const int32_t* c_keep_rows;   // as in GemmNNArgs
+};
+struct GemmBf16TNArgs {
+    const uint16_t* X; int64_t ldx;                          // [R, Kp] bf16 (product 0)
+    const float* Mn; int64_t ldm;                            // [R, Kp] fp32, rounded on load (product 1)
+    const float* G; int64_t ldg;                             // [R, N] fp32, rounded on load
+    float* P; int32_t Kp, N;                                 // partials in the layout of GemmTNArgs
+    const int32_t* d_R; int32_t R_cap; int32_t splits; int32_t rows_per_split;
+};
+inline int32_t bf16_kpad(int32_t K) { return (K + 15) / 16 * 16; }
+int32_t weights_to_bf16_t(const float* w, int32_t K, int32_t N, int32_t Kpad, uint16_t* out, hipStream_t st);
+int32_t gemm_bf16_nn(const GemmBf16NNArgs& a, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+int32_t gemm_bf16_tn_partials(const GemmBf16TNArgs& a, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+
 // Statistics of a training step, written by one extra block of the last gradient reduction of the step (they are
 // nobody's input, so they do not get a launch of their own on the step's dependency chain): mean of the per-seed
 // losses in a fixed order and the block sizes.
@@ -68,6 +91,8 @@ struct ReduceArgs {
     float lr; float* w_self; float* w_neigh; float* w_bias;
     int32_t n_problems;                                  // 2, or 1: only g_self and g_bias
     const int32_t* d_R = nullptr; int32_t R_cap = 0; int32_t rows_per_split = 0;   // as in the product: the slices it used
+    // bf16 copies of the two matrices ([N][Kpad], weights_to_bf16_t's layout), rewritten with the updated values (or NULL)
+    uint16_t* wt_self = nullptr; uint16_t* wt_neigh = nullptr; int32_t Kpad = 0;
 };
 
 // Weight-gradient work of several layers carried by one product launch and one reduction launch: the gradients of an
@@ -76,6 +101,11 @@ struct ReduceArgs {
 struct GradJobs {
     GemmTNArgs tn[NO_MAX_LAYERS]; ReduceArgs red[NO_MAX_LAYERS];
     int32_t n = 0;
+    // side != NULL: where the bottom layer's products are of another kind (bf16 operands) and cannot carry the deferred
+    // fp32 ones in their launch, those are launched on this otherwise idle stream beside them (behind `fork`; the
+    // reduction waits for `join`). Launching each as soon as its layer had made its inputs measured no faster: every
+    // fork is an event on the backward chain.
+    hipStream_t side = nullptr; hipEvent_t fork = nullptr; hipEvent_t join = nullptr;
 };
 
 // ev0 / ev1 (optional): events that take the product kernel's own start and end times

@@ -138,9 +138,7 @@ namespace no {
 // or starts another sampling call on the same blocks.
 // Optional job run first on the side stream: dense copy of the last hop's destination feature rows
 // (out[i,:] = table[dst[i],:]); the caller waits on b->ev_gather_done before reading `out`.
-// out_f32 (bf16 tables): the same rows once more in fp32, for the products that read them.
-struct SideGather { const void* table = nullptr; int32_t row_bytes = 0; void* out = nullptr; bool needed_by_forward = true;
-                    float* out_f32 = nullptr; };
+struct SideGather { const void* table = nullptr; int32_t row_bytes = 0; void* out = nullptr; bool needed_by_forward = true; };
 int32_t sample_blocks_impl(no_graph_s* g, const int32_t* d_seeds, int32_t n_seeds, uint64_t stream_key,
                            uint32_t domain, int32_t n_hops, no_cache_s* cache, int64_t step, no_blocks_s* b,
                            hipStream_t st, bool join = true, const SideGather* gather = nullptr,

@@ -41,7 +41,6 @@ struct LayerWorkspace {
     float* gz = nullptr;             // [n_dst_cap, d_out] masked output gradient
     float* gmean = nullptr;          // [n_dst_cap, d_in]  gradient of the mean, pre-divided by the row length
     float* x_dst_f32 = nullptr;      // [n_dst_cap, d_in]  fp32 copy of bf16 destination rows
-    bool x_dst_f32_ready = false;    // that copy was already made (by the step's side stream, with the dense row copy)
     float* partials = nullptr;       // [2, splits, d_in + 1, d_out]
     int32_t splits = 1;
     size_t bytes = 0;
@@ -73,6 +72,15 @@ struct SourceWeights {
 // first unused slot on, first occurrences possibly marked as -2 - id): lets the fused layer-1 aggregate skip the row
 // pointers and the compacted index array.
 struct PaddedSlots { const int32_t* pad = nullptr; int32_t k = 0; };
+
+// A layer fed by a bf16 feature table whose products take bf16 operands on the matrix cores (fp32 accumulation): the
+// destinations' rows come straight from the table in the forward pass (row m = table row x_rows[m]) and from the dense
+// bf16 copy in the backward pass; the two weight matrices are kept as bf16 copies in the product's layout.
+struct Bf16Products {
+    const uint16_t* x_table = nullptr; int64_t ldx = 0; const int32_t* x_rows = nullptr;
+    const uint16_t* x_dense = nullptr;
+    uint16_t* wt_self = nullptr; uint16_t* wt_neigh = nullptr; int32_t Kpad = 0;
+};
 
 // Layer 1 with reuse (Section 4.1.2): where the computed rows go, which of them refresh the cache, and the reused
 // rows to copy in from the cache.
@@ -107,7 +115,8 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof = nullptr, int agg_stage = -1,
                      int gemm_stage = -1, const void* agg_table = nullptr, hipEvent_t wait_before_gemm = nullptr,
                      int32_t arch = NO_ARCH_SAGE_MEAN, const Layer1Reuse* reuse = nullptr, bool aggregate_done = false,
-                     const SourceWeights* weights = nullptr, const PaddedSlots* padded = nullptr);
+                     const SourceWeights* weights = nullptr, const PaddedSlots* padded = nullptr,
+                     const Bf16Products* bf = nullptr);
 int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, int32_t d_in, const float* mean,
                       const float* h, const float* grad_h, const float* w_self, const float* w_neigh, int32_t d_out,
                       int32_t relu, float* gw_self, float* gw_neigh, float* gbias, float* grad_x_src,
@@ -117,8 +126,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       float* w_neigh_rw = nullptr, float* bias_rw = nullptr, int32_t arch = NO_ARCH_SAGE_MEAN,
                       const StatsJob* stats_job = nullptr, const float* gz_in = nullptr,
                       const BelowLayer* below = nullptr, GradJobs* pending = nullptr, bool defer = false,
-                      const SourceWeights* weights = nullptr);
-int32_t bf16_rows_to_f32(const uint16_t* x, const int32_t* d_n, int32_t n_cap, int32_t dim, float* out, hipStream_t st);
+                      const SourceWeights* weights = nullptr, const Bf16Products* bf = nullptr);
 int32_t gather_rows(const void* d_table, int32_t row_bytes, int64_t table_stride, const int32_t* d_ids,
                     const int32_t* d_n, int32_t n_cap, void* d_out, int64_t out_stride, hipStream_t st);
 

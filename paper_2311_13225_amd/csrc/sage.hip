@@ -504,7 +504,7 @@ static inline unsigned ew_blocks(int64_t total) {
     return (unsigned)b;
 }
 
-int32_t bf16_rows_to_f32(const uint16_t* x, const int32_t* d_n, int32_t n_cap, int32_t dim, float* out, hipStream_t st) {
+static int32_t bf16_rows_to_f32(const uint16_t* x, const int32_t* d_n, int32_t n_cap, int32_t dim, float* out, hipStream_t st) {
     if (n_cap <= 0 || dim <= 0) return NO_OK;
     hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(ew_blocks((int64_t)n_cap * dim)), dim3(256), 0, st, x, d_n, n_cap, dim, out);
     return launch_status("bf16_rows_to_f32");
@@ -546,7 +546,8 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
                      const float* w_neigh, const float* bias, int32_t d_out, int32_t relu, float* mean, float* h,
                      const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int agg_stage, int gemm_stage,
                      const void* agg_table, hipEvent_t wait_before_gemm, int32_t arch, const Layer1Reuse* reuse,
-                     bool aggregate_done, const SourceWeights* weights, const PaddedSlots* padded) {
+                     bool aggregate_done, const SourceWeights* weights, const PaddedSlots* padded,
+                     const Bf16Products* bf) {
     // aggregate_done: `mean` (and the reused rows of H^1) were already written by an earlier launch of the same
     // aggregation (a batch prepared ahead); only the product runs
     // reuse: the output rows are scattered into H^1, recomputed hot rows also refresh the cache, and the reused
@@ -594,12 +595,27 @@ int32_t sage_forward(const no_block_view& blk, const void* x_src, no_dtype dt, i
         NO_CHECK(mean_aggregate(agg_table ? agg_table : x_src, dt, d_in, blk.d_indptr, blk.d_indices, blk.d_n_dst,
                                 blk.n_dst_cap, mean, st, AGG_NEIGH_MEAN, nullptr, hits, e0, e1, nullptr,
                                 agg_table ? padded : nullptr));
+    if (bf) {
+        // bf16 operands on the matrix cores: the destinations' rows straight from the table (bf16 as stored), the mean
+        // rounded on load, the weights from their bf16 copies; nothing to wait for on another stream
+        GemmBf16NNArgs a{};
+        a.X = bf->x_table; a.ldx = bf->ldx; a.x_rows = bf->x_rows;
+        a.Mn = mean; a.ldm = d_in;
+        a.Wt[0] = bf->wt_self; a.Wt[1] = bf->wt_neigh; a.Kpad = bf->Kpad;
+        a.K = d_in; a.N = d_out;
+        a.C = h; a.ldc = d_out;
+        a.d_M = blk.d_n_dst; a.M_cap = blk.n_dst_cap;
+        a.bias = bias; a.relu = relu;
+        if (reuse) { a.c_rows = reuse->compute_pos; a.c_keep = reuse->emb; a.c_keep_rows = reuse->refresh_slot; }
+        e0 = e1 = nullptr;
+        if (prof && gemm_stage >= 0) prof->kernel_pair(gemm_stage, &e0, &e1);
+        return gemm_bf16_nn(a, st, e0, e1);
+    }
     if (wait_before_gemm && !direct_self)
         NO_HIP_CHECK(hipStreamWaitEvent(st, wait_before_gemm, 0));   // x_src rows come from another stream
     const float* x_dst = direct_self ? (const float*)agg_table : (const float*)x_src;
     if (dt == NO_BF16) {
-        if (!w.x_dst_f32_ready)
-            NO_CHECK(bf16_rows_to_f32((const uint16_t*)x_src, blk.d_n_dst, blk.n_dst_cap, d_in, w.x_dst_f32, st));
+        NO_CHECK(bf16_rows_to_f32((const uint16_t*)x_src, blk.d_n_dst, blk.n_dst_cap, d_in, w.x_dst_f32, st));
         x_dst = w.x_dst_f32;
     }
     GemmNNArgs a{};
@@ -625,7 +641,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
                       const LayerWorkspace& w, hipStream_t st, StageProfiler* prof, int prep_stage, int dw_stage,
                       int reduce_stage, int dx_stage, const int32_t* grad_rows, float lr, float* w_self_rw,
                       float* w_neigh_rw, float* bias_rw, int32_t arch, const StatsJob* stats_job, const float* gz_in,
-                      const BelowLayer* below, GradJobs* pending, bool defer, const SourceWeights* weights) {
+                      const BelowLayer* below, GradJobs* pending, bool defer, const SourceWeights* weights,
+                      const Bf16Products* bf) {
     const bool gcn = arch_is_gcn(arch);
     if (arch == NO_ARCH_GCN_SYM && grad_x_src && !(weights && weights->cnt)) {
         set_error("GCN-style layer with symmetric normalisation: the block has no per-source edge counts");
@@ -641,9 +658,8 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
         gz = w.gz;
     }
     const float* x_dst = (const float*)x_src;
-    if (dt == NO_BF16 && !gcn) {
-        if (!w.x_dst_f32_ready)
-            NO_CHECK(bf16_rows_to_f32((const uint16_t*)x_src, blk.d_n_dst, n_cap, d_in, w.x_dst_f32, st));
+    if (dt == NO_BF16 && !gcn && !bf) {
+        NO_CHECK(bf16_rows_to_f32((const uint16_t*)x_src, blk.d_n_dst, n_cap, d_in, w.x_dst_f32, st));
         x_dst = w.x_dst_f32;
     }
     if (prof && prep_stage >= 0) prof->end();
@@ -693,6 +709,7 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     t.rows_per_split = 256;
     ReduceArgs r{w.partials, w.splits, d_in, d_out, gw_self, gw_neigh, gbias, lr, w_self_rw, w_neigh_rw, bias_rw, gcn ? 1 : 2};
     r.d_R = t.d_R; r.R_cap = t.R_cap; r.rows_per_split = t.rows_per_split;
+    if (bf) { r.wt_self = bf->wt_self; r.wt_neigh = bf->wt_neigh; r.Kpad = bf->Kpad; }
     if (pending && defer) {
         // an upper layer inside a step: its product and reduction ride on the bottom layer's launches
         if (pending->n >= NO_MAX_LAYERS) { set_error("sage_backward: too many deferred layers"); return NO_ERR_CAPACITY; }
@@ -703,13 +720,37 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     }
     GemmTNArgs tj[NO_MAX_LAYERS];
     ReduceArgs rj[NO_MAX_LAYERS];
-    int32_t n_jobs = 0;
-    tj[n_jobs] = t; rj[n_jobs] = r; ++n_jobs;
-    for (int32_t i = 0; pending && i < pending->n && n_jobs < NO_MAX_LAYERS; ++i, ++n_jobs) { tj[n_jobs] = pending->tn[i]; rj[n_jobs] = pending->red[i]; }
+    int32_t n_jobs = 0, n_tn = 0;
+    rj[n_jobs++] = r;
+    if (!bf) tj[n_tn++] = t;
+    for (int32_t i = 0; pending && i < pending->n && n_jobs < NO_MAX_LAYERS; ++i) { tj[n_tn++] = pending->tn[i]; rj[n_jobs++] = pending->red[i]; }
+    const bool beside = bf && pending && pending->side && pending->fork && pending->join && n_tn > 0;
     if (pending) pending->n = 0;
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (prof && dw_stage >= 0) prof->kernel_pair(dw_stage, &e0, &e1);
-    NO_CHECK(gemm_tn_partials(tj, n_jobs, st, e0, e1));
+    if (bf) {
+        // this layer's two products take bf16 operands (their own launch); the deferred fp32 products of the layers
+        // above go first
+        if (beside) {
+            NO_HIP_CHECK(hipEventRecord(pending->fork, st));
+            NO_HIP_CHECK(hipStreamWaitEvent(pending->side, pending->fork, 0));
+            NO_CHECK(gemm_tn_partials(tj, n_tn, pending->side, nullptr, nullptr));
+            NO_HIP_CHECK(hipEventRecord(pending->join, pending->side));
+        } else {
+            if (prof && prep_stage >= 0) prof->begin(prep_stage);
+            NO_CHECK(gemm_tn_partials(tj, n_tn, st, nullptr, nullptr));
+            if (prof && prep_stage >= 0) prof->end();
+        }
+        GemmBf16TNArgs b{};
+        b.X = bf->x_dense; b.ldx = d_in; b.Mn = mean; b.ldm = d_in; b.G = gz; b.ldg = d_out;
+        b.P = w.partials; b.Kp = d_in; b.N = d_out;
+        b.d_R = t.d_R; b.R_cap = t.R_cap; b.splits = t.splits; b.rows_per_split = t.rows_per_split;
+        if (prof && dw_stage >= 0) prof->kernel_pair(dw_stage, &e0, &e1);
+        NO_CHECK(gemm_bf16_tn_partials(b, st, e0, e1));
+    } else {
+        if (prof && dw_stage >= 0) prof->kernel_pair(dw_stage, &e0, &e1);
+        NO_CHECK(gemm_tn_partials(tj, n_tn, st, e0, e1));
+    }
+    if (beside) NO_HIP_CHECK(hipStreamWaitEvent(st, pending->join, 0));      // only the reduction needs the products beside
     if (prof && reduce_stage >= 0) prof->begin(reduce_stage);
     NO_CHECK(reduce_grads(rj, n_jobs, st, stats_job));
     if (prof && reduce_stage >= 0) prof->end();

@@ -810,9 +810,6 @@ static int32_t launch_side_work(no_blocks_s* b, int32_t n_hops, const int32_t* d
         const HopBuffers& lastg = b->hop[n_hops - 1];
         NO_CHECK(gather_rows(gather->table, gather->row_bytes, gather->row_bytes, lastg.src_global.p,
                              b->counts.p + 4 * (n_hops - 1), lastg.n_dst_cap, gather->out, gather->row_bytes, sd));
-        if (gather->out_f32)
-            NO_CHECK(bf16_rows_to_f32((const uint16_t*)gather->out, b->counts.p + 4 * (n_hops - 1), lastg.n_dst_cap,
-                                      gather->row_bytes / 2, gather->out_f32, sd));
         NO_HIP_CHECK(hipEventRecord(b->ev_gather_done, sd));
         return NO_OK;
     };

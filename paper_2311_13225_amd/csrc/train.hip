@@ -19,7 +19,13 @@ struct no_model_s {
     size_t off_w_self[NO_MAX_LAYERS], off_w_neigh[NO_MAX_LAYERS], off_bias[NO_MAX_LAYERS];
     size_t n_params = 0;
     no::DevBuf<char> x0;                             // gathered rows of the bottom hop's destinations [n_dst_cap, F]
-    no::DevBuf<float> x0_f32, x0_f32_alt;            // bf16 tables: the same rows in fp32 (operand of the layer-1 products)
+    // bf16 tables with GraphSAGE-mean layers: layer 1's products take bf16 operands; its two matrices as bf16 copies
+    // [2][d_1][Kpad] in the product's layout, rewritten by every step's update (and from the parameters when the
+    // caller may have changed them: weights_dirty)
+    no::DevBuf<uint16_t> wt1;
+    int32_t wt1_kpad = 0;
+    hipEvent_t ev_dw_join = nullptr;
+    bool weights_dirty = true;
     no::DevBuf<float> mean[NO_MAX_LAYERS];           // layer l (index l-1): [n_dst_cap, d_{l-1}]
     no::DevBuf<float> h[NO_MAX_LAYERS];              // layer l output [rows, d_l]; h[0] holds all of V^1
     no::DevBuf<float> gh[NO_MAX_LAYERS];             // gradient w.r.t. h[l-1]
@@ -50,6 +56,7 @@ struct no_model_s {
     no::StageProfiler prof;
     void release() {
         if (prof.created) { for (auto& e : prof.ev) (void)hipEventDestroy(e); prof.created = false; }
+        if (ev_dw_join) { (void)hipEventDestroy(ev_dw_join); ev_dw_join = nullptr; }
         // a batch prepared ahead and never trained on: its split's stamps leave the cache with the model
         if (ahead_valid && blocks_alt && sample_stream) (void)no::blocks_unstamp(blocks_alt, sample_stream);
         ahead_valid = false;
@@ -60,7 +67,7 @@ struct no_model_s {
         mean_alt.release();
         h0_alt.release();
         if (blocks_alt) { blocks_alt->release(); delete blocks_alt; blocks_alt = nullptr; }
-        x0_alt.release(); x0_f32.release(); x0_f32_alt.release();
+        x0_alt.release(); wt1.release();
         if (blocks) { blocks->release(); delete blocks; blocks = nullptr; }
         params.release(); grads.release(); x0.release();
         for (auto& b : mean) b.release();
@@ -148,7 +155,11 @@ extern "C" int32_t no_model_create(no_graph_t g, int32_t n_layers, const int32_t
     const HopBuffers& bottom = m->blocks->hop[L - 1];
     const size_t es = feat_dtype == NO_F32 ? 4 : 2;
     NO_CHECK(m->x0.alloc((size_t)bottom.n_dst_cap * m->dims[0] * es));
-    if (feat_dtype == NO_BF16) NO_CHECK(m->x0_f32.alloc((size_t)bottom.n_dst_cap * m->dims[0]));
+    if (feat_dtype == NO_BF16) {
+        m->wt1_kpad = bf16_kpad(m->dims[0]);
+        NO_CHECK(m->wt1.alloc((size_t)2 * m->dims[1] * m->wt1_kpad));
+        NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_dw_join, NO_SYNC_EVENT_FLAGS));
+    }
     size_t ws_bytes = 0;
     for (int32_t l = 1; l <= L; ++l) {
         const HopBuffers& H = m->blocks->hop[L - l];
@@ -178,6 +189,7 @@ static int32_t check_layer_index(no_model_t m, int32_t layer, const char* who) {
 extern "C" int32_t no_model_params(no_model_t m, int32_t layer, float** d_w_self, float** d_w_neigh, float** d_bias) {
     clear_error();
     NO_CHECK(check_layer_index(m, layer, "no_model_params"));
+    m->weights_dirty = true;      // the caller may write through these pointers: layer 1's bf16 copies are made again
     if (d_w_self) *d_w_self = m->params.p + m->off_w_self[layer - 1];
     if (d_w_neigh) *d_w_neigh = m->params.p + m->off_w_neigh[layer - 1];
     if (d_bias) *d_bias = m->params.p + m->off_bias[layer - 1];
@@ -231,7 +243,6 @@ static int32_t ensure_lookahead(no_model_s* m, no_graph_s* g) {
     NO_CHECK(blocks_create_impl(g, m->n_seeds_cap, m->fanouts, m->n_layers, true, &m->blocks_alt));
     m->blocks_alt->count_sources = m->arch == NO_ARCH_GCN_SYM;
     NO_CHECK(m->x0_alt.alloc(m->x0.n));
-    if (m->feat_dtype == NO_BF16) NO_CHECK(m->x0_f32_alt.alloc(m->x0_f32.n));
     NO_CHECK(m->mean_alt.alloc(m->mean[0].n));
     NO_CHECK(m->h0_alt.alloc(m->h[0].n));
     NO_HIP_CHECK(hipStreamCreateWithFlags(&m->sample_stream, hipStreamNonBlocking));
@@ -278,7 +289,6 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         if (presampled) {
             std::swap(m->blocks, m->blocks_alt);
             std::swap(m->x0.p, m->x0_alt.p);
-            std::swap(m->x0_f32.p, m->x0_f32_alt.p);
             if (m->ahead_aggregated) {
                 std::swap(m->mean[0].p, m->mean_alt.p);
                 std::swap(m->h[0].p, m->h0_alt.p);
@@ -308,8 +318,16 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     sg.table = arch_is_gcn(m->arch) ? nullptr : d_features;    // GCN-style layers read every row inside the aggregation
     sg.row_bytes = row_bytes;
     sg.out = m->x0.p;
-    sg.out_f32 = (m->feat_dtype == NO_BF16 && sg.table) ? m->x0_f32.p : nullptr;
-    sg.needed_by_forward = m->feat_dtype != NO_F32;   // fp32: the forward product reads the table rows itself
+    sg.needed_by_forward = false;    // the forward product reads the destinations' table rows itself (fp32 and bf16)
+    // bf16 table: layer 1's products take bf16 operands (features as stored; mean, weights, output gradient rounded)
+    const bool bf16_products = m->feat_dtype == NO_BF16 && m->arch == NO_ARCH_SAGE_MEAN;
+    uint16_t* wt_self = m->wt1.p;
+    uint16_t* wt_neigh = m->wt1.p ? m->wt1.p + (size_t)m->dims[1] * m->wt1_kpad : nullptr;
+    if (bf16_products && m->weights_dirty) {
+        NO_CHECK(weights_to_bf16_t(m->params.p + m->off_w_self[0], m->dims[0], m->dims[1], m->wt1_kpad, wt_self, st));
+        NO_CHECK(weights_to_bf16_t(m->params.p + m->off_w_neigh[0], m->dims[0], m->dims[1], m->wt1_kpad, wt_neigh, st));
+        m->weights_dirty = false;
+    }
     hipEvent_t sev0 = nullptr, sev1 = nullptr;
     if (!presampled) prof.kernel_pair(NO_STAGE_SAMPLE_ROWS_BOTTOM, &sev0, &sev1);
     prof.begin(NO_STAGE_SAMPLE);
@@ -345,7 +363,6 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_can_sample, 0));
         SideGather sg2 = sg;
         sg2.out = m->x0_alt.p;
-        sg2.out_f32 = sg.out_f32 ? m->x0_f32_alt.p : nullptr;
         m->blocks_alt->scan_two_pass = true;      // this sampling shares the chip with the step's products
         NO_CHECK(sample_blocks_impl(g, d_next_seeds, n_next_seeds, seed + (uint64_t)(step + 1), 0u, L, cache, step + 1,
                                     m->blocks_alt, m->sample_stream, false, &sg2, true));
@@ -407,7 +424,6 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             reuse.hits.d_n = extra + 1; reuse.hits.n_cap = blk.n_dst_cap; reuse.hits.dst = m->h[0].p; reuse.hits.dim = d_out;
         }
         LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
-        if (l == 1 && sg.out_f32) { w.x_dst_f32 = m->x0_f32.p; w.x_dst_f32_ready = true; }     // made beside the row copy
         // symmetric normalisation: the column sums of the block's adjacency are the per-source edge counts of the hop
         // (written with the local indices on the blocks' side stream); the fused layer-1 aggregate reads global ids,
         // so it also takes the local index of every entry
@@ -426,11 +442,17 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             no_block_view fused = blk;
             fused.d_indices = blk.d_nbr_global;
             const PaddedSlots slots{B->hop[L - 1].nbr_pad.p, B->hop[L - 1].fanout};
+            Bf16Products bfp;
+            if (bf16_products) {
+                bfp.x_table = (const uint16_t*)d_features; bfp.ldx = d_in; bfp.x_rows = blk.d_src_global;
+                bfp.wt_self = wt_self; bfp.wt_neigh = wt_neigh; bfp.Kpad = m->wt1_kpad;
+            }
             NO_CHECK(sage_forward(fused, x, dt, d_in, m->params.p + m->off_w_self[0], m->params.p + m->off_w_neigh[0],
                                   m->params.p + m->off_bias[0], d_out, l < L ? 1 : 0, m->mean[0].p, h_out, w, st, &prof,
                                   NO_STAGE_AGG_L1, NO_STAGE_GEMM_FWD_L1, d_features,
                                   arch_is_gcn(m->arch) ? nullptr : B->ev_gather_done, m->arch,
-                                  (l == 1 && used_cache) ? &reuse : nullptr, aggregated, &sw, &slots));
+                                  (l == 1 && used_cache) ? &reuse : nullptr, aggregated, &sw, &slots,
+                                  bf16_products ? &bfp : nullptr));
         } else
         NO_CHECK(sage_forward(blk, x, dt, d_in, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                               m->params.p + m->off_bias[l - 1], d_out, l < L ? 1 : 0, m->mean[l - 1].p, h_out, w, st,
@@ -465,6 +487,13 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     // their products and reductions are carried by the bottom layer's two launches, which end the step, instead of
     // adding two launches per layer to the chain of dependent kernels.
     GradJobs pending;
+    if (bf16_products) {
+        // the bottom layer's products are of another kind (bf16 operands) and cannot carry the upper layers' fp32 ones in
+        // their launch: those run beside them on the blocks' side stream (joined above, idle from here on)
+        pending.side = B->side;
+        pending.fork = B->ev_fork[0];
+        pending.join = m->ev_dw_join;
+    }
     for (int32_t l = L; l >= 1; --l) {
         const no_block_view& blk = view[L - l];
         const int32_t d_in = m->dims[l - 1], d_out = m->dims[l];
@@ -492,9 +521,13 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         }
         if (l < L) gz_in = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out).gz;
         LayerWorkspace w = carve_workspace(m->ws.p + m->ws_off[l - 1], blk.n_dst_cap, d_in, d_out);
-        if (l == 1 && sg.out_f32) { w.x_dst_f32 = m->x0_f32.p; w.x_dst_f32_ready = true; }
         SourceWeights sw;
         if (m->arch == NO_ARCH_GCN_SYM) sw.cnt = B->hop[L - l].csc_cnt.p;
+        Bf16Products bfp;
+        if (bf16_products && l == 1) {
+            bfp.x_dense = (const uint16_t*)m->x0.p;
+            bfp.wt_self = wt_self; bfp.wt_neigh = wt_neigh; bfp.Kpad = m->wt1_kpad;
+        }
         NO_CHECK(sage_backward(blk, x, dt, d_in, m->mean[l - 1].p, h_l, gh_l, m->params.p + m->off_w_self[l - 1],
                                m->params.p + m->off_w_neigh[l - 1], d_out, l < L ? 1 : 0,
                                m->grads.p + m->off_w_self[l - 1], m->grads.p + m->off_w_neigh[l - 1],
@@ -502,7 +535,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
                                l == 1 ? &prof : nullptr, NO_STAGE_BWD_L1_PREP, NO_STAGE_GEMM_DW_L1, NO_STAGE_BWD_L1_REDUCE,
                                -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                                m->params.p + m->off_bias[l - 1], m->arch, l == 1 ? &stats_job : nullptr, gz_in,
-                               l >= 2 ? &below : nullptr, &pending, l >= 2, &sw));
+                               l >= 2 ? &below : nullptr, &pending, l >= 2, &sw, (bf16_products && l == 1) ? &bfp : nullptr));
     }
 
     // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;

@@ -12,6 +12,12 @@ from oracle import oracle as ora
 pytestmark = pytest.mark.gpu
 
 RTOL = 1e-4
+# Steps on a bf16 feature table (GraphSAGE-mean): layer 1's products take bf16 operands on both sides, but the values
+# that get rounded (the fp32 mean, the weights after an update, the output gradient) differ between the kernel (fp32)
+# and the oracle (fp64) in their last bits, and now and then one of them sits on a bf16 rounding boundary: one operand
+# of one of a product's 2K terms is then off by a bf16 ulp (2^-8 of its size), i.e. an output by up to ~2^-8 / sqrt(2K)
+# of its typical size (3e-4 at K = 64). Tolerance for such runs (well inside the 2e-2 allowed for bf16 features):
+RTOL_BF16 = 1e-3
 # Whole-step tests let the oracle's backward pass take the kernel's ReLU decision where the oracle's own
 # pre-activation is zero to within rounding (|z| <= 1e-5 max|z|); how many decisions that may be is bounded:
 RELU_FLIP_SHARE = 1e-5      # of a layer's pre-activations (observed at full size: about 1e-6)
@@ -30,13 +36,13 @@ def dev(a, dtype=None):
     return t.cuda()
 
 
-def assert_close(gpu, ref, what=""):
+def assert_close(gpu, ref, what="", rtol=RTOL):
     gpu = np.asarray(gpu, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
     if ref.size == 0:
         return
-    tol = RTOL * np.abs(ref) + RTOL * np.abs(ref).max()
+    tol = rtol * np.abs(ref) + rtol * np.abs(ref).max()
     err = np.abs(gpu - ref)
     bad = err > tol
     assert not bad.any(), "%s: %d of %d outside tolerance, worst err %.3e (tol %.3e)" % (
@@ -354,11 +360,12 @@ def test_sage_layer_empty_block_and_small_workspace():
 
 # --------------------------------------------------------------------------------------- whole step
 
-def make_relu_hook(b, model, st, n_layers, ambiguous):
+def make_relu_hook(b, model, st, n_layers, ambiguous, band=1e-5):
     """The ReLU decision is a float deciding a bit. Where the oracle's pre-activation is zero to
     within rounding (|z| <= 1e-5 max|z|) the decision the kernel took in fp32 is as valid as the
     oracle's, so the oracle's backward uses the kernel's; everywhere else the two must agree exactly
-    (asserted here), so a wrong mask cannot hide behind this. How many decisions may be taken over is bounded."""
+    (asserted here), so a wrong mask cannot hide behind this. How many decisions may be taken over is bounded.
+    (`band`: the relative width of "zero to within rounding"; wider for runs whose products take bf16 operands.)"""
     def relu_decisions(layer, z_ora):
         blocks_ = b.no_model_blocks(model)
         sizes_ = b.no_blocks_sizes(blocks_)
@@ -368,7 +375,7 @@ def make_relu_hook(b, model, st, n_layers, ambiguous):
             gh = gh[b.block_arrays(blocks_, n_layers - 1, sizes_)["compute_pos"]]
         if z_ora.size == 0:
             return np.zeros(z_ora.shape, dtype=bool)
-        tau = 1e-5 * max(np.abs(z_ora).max(), 1e-30)
+        tau = band * max(np.abs(z_ora).max(), 1e-30)
         assert (gh[z_ora > tau] > 0).all(), "layer %d: kernel masks a clearly positive pre-activation" % layer
         assert (gh[z_ora < -tau] == 0).all(), "layer %d: kernel keeps a clearly negative pre-activation" % layer
         flips = int(((gh > 0) != (z_ora > 0)).sum())
@@ -382,7 +389,7 @@ def make_relu_hook(b, model, st, n_layers, ambiguous):
     return relu_decisions
 
 
-def check_step_outputs(b, model, st, r, n_layers, step, with_cache_blocks, gcn, feat_dtype):
+def check_step_outputs(b, model, st, r, n_layers, step, with_cache_blocks, gcn, feat_dtype, rtol=RTOL):
     """One step of the library (its statistics `st`, the model's blocks, activations, gradients and parameters)
     against the oracle's StepResult `r`: integers bit for bit, floats within the tolerance."""
     pick = (lambda three: (three[0], three[2])) if gcn else (lambda three: three)
@@ -397,18 +404,18 @@ def check_step_outputs(b, model, st, r, n_layers, step, with_cache_blocks, gcn, 
         x0 = b.no_model_gathered(model, n_dst_bottom).cpu().numpy()
         assert np.array_equal(x0.view(feat_dtype), r.x0[:n_dst_bottom])
     # floats
-    assert abs(st.loss - r.loss) <= RTOL * abs(r.loss) + 1e-6, (st.loss, r.loss)
+    assert abs(st.loss - r.loss) <= rtol * abs(r.loss) + 1e-6, (st.loss, r.loss)
     for l in range(1, n_layers + 1):
         n_rows = r.h[l - 1].shape[0]
         n_dst = r.batch.blocks[n_layers - l].n_dst
         gh, gm = b.no_model_activations(model, l, n_rows, n_dst)
-        assert_close(gm.cpu().numpy(), r.mean[l - 1], "mean%d step %d" % (l, step))
-        assert_close(gh.cpu().numpy(), r.h[l - 1], "h%d step %d" % (l, step))
+        assert_close(gm.cpu().numpy(), r.mean[l - 1], "mean%d step %d" % (l, step), RTOL if l == 1 else rtol)
+        assert_close(gh.cpu().numpy(), r.h[l - 1], "h%d step %d" % (l, step), rtol)
         names = ["gw", "gbias"] if gcn else ["gw_self", "gw_neigh", "gbias"]
         for t, ref, name in zip(pick(b.no_model_grads(model, l)), r.grads[l - 1], names):
-            assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step))
+            assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name, l, step), rtol)
         for t, ref, name in zip(pick(b.no_model_params(model, l)), r.new_weights[l - 1], names):
-            assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name[1:], l, step))
+            assert_close(t.cpu().numpy(), ref, "%s%d step %d" % (name[1:], l, step), rtol)
 
 
 def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None, bits=32, presample=1,
@@ -424,6 +431,8 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
     bf16 = w.feat_dtype == "bf16"
     model = b.no_model_create(gg, w.dims, w.batch, w.fanouts, b.NO_BF16 if bf16 else b.NO_F32)
     gcn = arch != "sage"
+    bf16_products = bf16 and not gcn          # layer 1's products take bf16 operands (kernel and oracle)
+    rtol = RTOL_BF16 if bf16_products else RTOL
     if gcn:
         b.no_model_set_arch(model, b.ARCH_OF_NAME[arch])
     for l in range(w.n_layers):
@@ -472,23 +481,24 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
         else:
             st = b.no_train_step(model, gg, tfeat, tlab, seed_tensors[step], gc, step, w.seed, lr)
         ambiguous = []
-        relu_decisions = make_relu_hook(b, model, st, w.n_layers, ambiguous)
+        relu_decisions = make_relu_hook(b, model, st, w.n_layers, ambiguous, band=1e-3 if bf16_products else 1e-5)
         r = ora.train_step(og, feat, lab, seeds, w.fanouts, ow, lr, w.seed, step, oc, feat_is_bf16=bf16,
                            relu_decisions=relu_decisions, arch=arch)
         print("  relu decisions taken from the kernel (layer, flips, in band, entries):", ambiguous, flush=True)
-        check_step_outputs(b, model, st, r, w.n_layers, step, use_cache and w.n_layers >= 2 and oc.n_hot > 0, gcn, feat.dtype)
+        check_step_outputs(b, model, st, r, w.n_layers, step, use_cache and w.n_layers >= 2 and oc.n_hot > 0, gcn, feat.dtype,
+                           rtol)
         hits += r.n_hit
         if superbatch and not ahead:
             # weight-drift monitor (Section 4.3): largest change of a layer-1 parameter in this update, and the drift
             # from the parameters behind the rows now in the cache
             upd, drift = b.no_model_weight_drift(model, gc, lr)
             o_upd = ora.max_weight_update(ow[0], r.new_weights[0])
-            assert abs(upd - o_upd) <= RTOL * o_upd + 1e-12, (upd, o_upd)
+            assert abs(upd - o_upd) <= rtol * o_upd + 1e-12, (upd, o_upd)
             if current_snap is None:
                 assert drift == -1.0
             else:
                 o_drift = ora.weight_drift(r.new_weights[0], current_snap)
-                assert abs(drift - o_drift) <= RTOL * o_drift + 1e-7, (drift, o_drift)
+                assert abs(drift - o_drift) <= rtol * o_drift + 1e-7, (drift, o_drift)
         ow = r.new_weights
         if use_cache and oc.n_hot > 0:
             view = b.no_cache_view(gc, V)
@@ -501,10 +511,10 @@ def run_steps(w, n_steps, use_cache, lr=0.05, V=None, E=None, hot_fraction=None,
                 # the boundary commit ran inside this call (after the step's last use of the cache): the cache
                 # already holds what the oracle installs at the start of the next step
                 assert np.array_equal(gv[~stamped], pending[1][~stamped])
-                assert_close(view["emb"].cpu().numpy(), pending[0], "committed emb step %d" % step)
+                assert_close(view["emb"].cpu().numpy(), pending[0], "committed emb step %d" % step, rtol)
             else:
                 assert np.array_equal(gv[~stamped], oc.version[~stamped])
-                assert_close(view["emb"].cpu().numpy(), oc.emb, "emb step %d" % step)
+                assert_close(view["emb"].cpu().numpy(), oc.emb, "emb step %d" % step, rtol)
             if stamped_ahead is not None:
                 # the slots stamped ahead by the previous call are exactly those this step refreshed in the oracle
                 assert np.array_equal(np.flatnonzero(stamped_ahead), np.flatnonzero(oc.version == step)), step
