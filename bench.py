@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix
 
 
 def log(*a):
@@ -300,6 +301,21 @@ def main():
     gather_bytes = gather_rows * (4 + 2 * F * es)
     gather_working_set = sum(int(ids.numel()) for ids in id_lists) * 2 * F * es
     del gouts
+    # for scale: a plain contiguous device-to-device copy of as many bytes per launch, rotating over as many buffers
+    # (what a perfectly coalesced kernel with no dependent id load reaches at this launch size)
+    n_copy = int(gather_rows) * F * es
+    c_src = [torch.empty(n_copy, dtype=torch.uint8, device="cuda") for _ in id_lists]
+    c_dst = [torch.empty(n_copy, dtype=torch.uint8, device="cuda") for _ in id_lists]
+    for a_, b_ in zip(c_src, c_dst):
+        b_.copy_(a_)
+    e0.record()
+    for _ in range(n_rep):
+        for a_, b_ in zip(c_src, c_dst):
+            b_.copy_(a_)
+    e1.record()
+    torch.cuda.synchronize()
+    plain_copy_gbps = 2 * n_copy / 1e9 / (e0.elapsed_time(e1) / n_launch / 1e3)
+    del c_src, c_dst
     # compulsory traffic (each distinct source row once) plus the reused layer-1 rows that extra blocks of the same
     # launch copy from the cache into H^1 (read + write)
     agg_bytes = n_src_bottom * F * es + n_dst_bottom * F * 4 + nnz_bottom * 4 + (n_hit * w.dims[1] * 4 * 2 if L >= 2 else 0)
@@ -316,14 +332,34 @@ def main():
     csc_bytes = lambda h: hop("nnz", h) * 16 if h < L - 1 else 0.0
     sampling_bytes = sum(sample_rows_bytes(h) + relabel_bytes(h) + csc_bytes(h) for h in range(L))
     ms = per_step
+    AGG, FWD, DW = "padded_rows_kernel(mean,l1)", "gemm_nn_kernel(l1 fwd)", "gemm_tn_kernel(l1 dW)"
     kern = {
         "gather_rows_kernel": ("hbm", gather_bytes / 1e9 / (ms["gather"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["gather"]),
-        "segment_rows_kernel(mean,l1)": ("hbm", agg_bytes / 1e9 / (ms["agg_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["agg_l1"]),
-        "gemm_nn_kernel(l1 fwd)": ("mfma", gemm_fwd_flops / 1e12 / (ms["gemm_fwd_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms["gemm_fwd_l1"]),
-        "gemm_tn_kernel(l1 dW)": ("mfma", gemm_dw_flops / 1e12 / (ms["gemm_dw_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms["gemm_dw_l1"]),
+        AGG: ("hbm", agg_bytes / 1e9 / (ms["agg_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["agg_l1"]),
         "sample_rows_kernel(bottom hop)": ("hbm", sample_rows_bytes(L - 1) / 1e9 / (max(ms["sample_rows_bottom"], 1e-6) / 1e3),
                                            HBM_PEAK_GBPS, "GB/s", ms["sample_rows_bottom"]),
     }
+    bf16_products = bf16 and not gcn
+    mfma_note = None
+    if bf16_products:
+        # Layer 1 on a bf16 table: bf16 operands on the matrix cores. At 16x the fp32 matrix rate these two launches are
+        # bound by their operands' bytes: bf16 rows + fp32 mean in, fp32 rows out (and the refreshed cache rows); for the
+        # weight gradients bf16 rows + fp32 mean + fp32 output gradient in, the partial tiles out. Their matrix-core
+        # share is reported beside (flops over the bf16 peak).
+        FWD, DW = "gemm_bf16_nn_kernel(l1 fwd)", "gemm_bf16_tn_kernel(l1 dW)"
+        n_refresh = mean([s_.n_refresh for s_ in stats]) if L >= 2 else 0.0
+        H1 = w.dims[1]
+        fwd_bytes = n_dst_bottom * (F * 2 + F * 4) + n_dst_bottom * H1 * 4 + n_refresh * H1 * 4
+        used_splits = min(64.0, max(1.0, n_dst_bottom / 256.0))
+        dw_bytes = n_dst_bottom * (F * 2 + F * 4 + H1 * 4) + used_splits * 2 * (F + 1) * H1 * 4
+        l1_flops = 2.0 * n_dst_bottom * 2 * F * H1
+        kern[FWD] = ("hbm", fwd_bytes / 1e9 / (ms["gemm_fwd_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["gemm_fwd_l1"])
+        kern[DW] = ("hbm", dw_bytes / 1e9 / (ms["gemm_dw_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["gemm_dw_l1"])
+        mfma_note = {FWD: round(l1_flops / 1e12 / (ms["gemm_fwd_l1"] / 1e3) / MFMA_BF16_PEAK_TFLOPS, 4),
+                     DW: round(l1_flops / 1e12 / (ms["gemm_dw_l1"] / 1e3) / MFMA_BF16_PEAK_TFLOPS, 4)}
+    else:
+        kern[FWD] = ("mfma", gemm_fwd_flops / 1e12 / (ms["gemm_fwd_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms["gemm_fwd_l1"])
+        kern[DW] = ("mfma", gemm_dw_flops / 1e12 / (ms["gemm_dw_l1"] / 1e3), MFMA_F32_PEAK_TFLOPS, "TFLOP/s", ms["gemm_dw_l1"])
     dominant = max(kern, key=lambda k: kern[k][4])
     bound, achieved, peak, unit, dur = kern[dominant]
     # HBM bytes per launch from rocprofv3 --pmc runs of this workload (FETCH_SIZE + WRITE_SIZE, scaled by a copy of
@@ -346,6 +382,11 @@ def main():
                 "frac": round(achieved / peak, 4), "traffic": traffic_all.get(dominant), "avg_launch_ms": round(dur, 4),
                 "traffic_source": traffic_source,
                 "all": {k: entry(k, v) for k, v in kern.items()}}
+    if mfma_note:
+        for k, v in mfma_note.items():
+            roofline["all"][k]["frac_of_bf16_mfma_peak"] = v
+        if dominant in mfma_note:
+            roofline["frac_of_bf16_mfma_peak"] = mfma_note[dominant]
     # the whole sampling stage (about four launches per hop plus the transposes), priced by its algorithmic bytes
     roofline["all"]["sampling stage (a1-a3, all hops, all its kernels)"] = {
         "bound": "hbm", "achieved": round(sampling_bytes / 1e9 / (ms["sample"] / 1e3), 3), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -353,7 +394,7 @@ def main():
         "traffic": traffic_all.get("sampling stage"), "note": "a chain of dependent launches bound by latency, not by bytes"}
     target = 0.60
     gather_frac = kern["gather_rows_kernel"][1] / HBM_PEAK_GBPS
-    agg_frac = kern["segment_rows_kernel(mean,l1)"][1] / HBM_PEAK_GBPS
+    agg_frac = kern[AGG][1] / HBM_PEAK_GBPS
     extra = {
         # every hop's sampled edges over the whole sampling stage: sampling, relabelling, hot lookup, local indices,
         # transposes and the wipe of the id map (the measurement pass joins the side stream inside the stage)
@@ -362,7 +403,8 @@ def main():
         "sampling_algorithmic_bytes_per_step": round(sampling_bytes, 1),
         "gather_GBps": round(kern["gather_rows_kernel"][1], 2),
         "gather_frac_hbm_peak": round(gather_frac, 4),
-        "aggregate_GBps": round(kern["segment_rows_kernel(mean,l1)"][1], 2),
+        "plain_copy_same_bytes_GBps": round(plain_copy_gbps, 2),
+        "aggregate_GBps": round(kern[AGG][1], 2),
         "aggregate_frac_hbm_peak": round(agg_frac, 4),
         "target_60pct_hbm_peak": {"gather": bool(gather_frac >= target), "aggregate": bool(agg_frac >= target)},
         "rows_gathered_per_step": round(n_src_bottom, 1),
@@ -415,7 +457,7 @@ def main():
     line = {
         "metric": "train_steps_per_s", "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1,
         "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16+f32" if bf16_products else "f32", "data": "synthetic",
         "config": {"workload": "%s: R-MAT %d vertices / %d directed edges, %d x %s features, %d classes, %d-layer "
                                "%s hidden %d, fanout %s, batch %d, hot %.0f%%, S=%d"
                                % (w.name, w.n_vertices, n_edges_made, w.feat_dim, w.feat_dtype, w.n_classes, w.n_layers,

@@ -55,6 +55,7 @@ constexpr int NN_BM = 64;            // rows per block (32-row blocks, twice as 
                                      // each block re-reads both weight matrices)
 constexpr int NN_KC = 128;           // reduction indices staged at a time
 constexpr int NN_PITCH = NN_KC + 8;  // bf16 elements per LDS row (16 bytes of padding: rows start 4 banks apart)
+constexpr int NN_CPITCH = 64 + 4;    // floats per LDS row of a staged output tile
 
 // Stages rows [m0, m0 + 64) x reduction indices [k0, k0 + 128) of one operand into LDS as bf16 (zeros past K or M).
 // A thread's four units are requested together (row indices, then rows) before the first is stored.
@@ -123,6 +124,7 @@ __device__ __forceinline__ void stage_rows_bf16(uint16_t* As, const uint16_t* X,
 __global__ void __launch_bounds__(256) gemm_bf16_nn_kernel(GemmBf16NNArgs g) {
     __shared__ __attribute__((aligned(16))) uint16_t As[NN_BM * NN_PITCH];
     __shared__ int32_t crow_sh[NN_BM], krow_sh[NN_BM];
+    __shared__ __attribute__((aligned(16))) float Cs[4 * 32 * NN_CPITCH];       // per wavefront: one 32 x 64 output tile
     int M = *g.d_M;
     if (M > g.M_cap) M = g.M_cap;
     const int m0 = (int)blockIdx.x * NN_BM;
@@ -175,24 +177,49 @@ __global__ void __launch_bounds__(256) gemm_bf16_nn_kernel(GemmBf16NNArgs g) {
             }
         }
     }
-    if (!wave_on) return;
+    // Epilogue: a wavefront's 32 x 64 tiles go through LDS so that a lane stores 16 contiguous bytes of an output row
+    // (a quarter of the store instructions of the accumulators' own layout, whole 256-byte row segments per 16 lanes).
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-        const int col = c0 + ct * 32 + l32;
-        if (col >= g.N) continue;
-        const float bias = g.bias ? g.bias[col] : 0.f;
+    for (int rt = 0; rt < RT; ++rt) {
+        float* Ct = Cs + wave * 32 * NN_CPITCH;
+        if (wave_on) {
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
+            for (int ct = 0; ct < 2; ++ct) {
+                const int col = c0 + ct * 32 + l32;
+                const float bias = (g.bias && col < g.N) ? g.bias[col] : 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lr = rt * 32 + acc_tile_row(r, lane);
-                if (m0 + lr >= M) continue;
-                float v = acc[rt][ct][r] + bias;
-                if (g.relu) v = fmaxf(v, 0.f);
-                g.C[(int64_t)crow_sh[lr] * g.ldc + col] = v;
-                const int kr = krow_sh[lr];
-                if (kr >= 0) g.c_keep[(int64_t)kr * g.ldc + col] = v;
+                for (int r = 0; r < 16; ++r) {
+                    float v = acc[rt][ct][r] + bias;
+                    if (g.relu) v = fmaxf(v, 0.f);
+                    Ct[acc_tile_row(r, lane) * NN_CPITCH + ct * 32 + l32] = v;
+                }
             }
+        }
+        __syncthreads();
+        if (wave_on) {
+            const int c4 = (lane & 15) * 4, col = c0 + c4;
+            const bool vec = (g.ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.C) & 15) == 0) &&
+                             (!g.c_keep || (reinterpret_cast<uintptr_t>(g.c_keep) & 15) == 0) && col + 4 <= g.N;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int lr = i * 4 + (lane >> 4), row = rt * 32 + lr;
+                if (m0 + row >= M || col >= g.N) continue;
+                const float4 t = *reinterpret_cast<const float4*>(Ct + lr * NN_CPITCH + c4);
+                float* dst = g.C + (int64_t)crow_sh[row] * g.ldc + col;
+                const int kr = krow_sh[row];
+                float* keep = kr >= 0 ? g.c_keep + (int64_t)kr * g.ldc + col : nullptr;
+                if (vec) {
+                    *reinterpret_cast<float4*>(dst) = t;
+                    if (keep) *reinterpret_cast<float4*>(keep) = t;
+                } else {
+                    const float v[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (col + q < g.N) { dst[q] = v[q]; if (keep) keep[q] = v[q]; }
+                }
+            }
+        }
+        if (rt + 1 < RT) __syncthreads();
     }
 }
 
@@ -283,9 +310,15 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(GemmBf16TNArgs g, int
     int R = *g.d_R;
     if (R > g.R_cap) R = g.R_cap;
     const int per_split = 2 * tiles_m * tiles_n + bias_blocks;
-    const int split = (int)blockIdx.x / per_split, rem = (int)blockIdx.x % per_split;
     const int used = tn_used_splits(R, g.splits, g.rows_per_split);
-    if (split >= used) return;
+    // The blocks of a slice (two products x tiles, and the bias row) read the same rows of G and of the operands: they
+    // get consecutive logical ids, and logical ids are dealt to the eight dies in chunks (a workgroup's die is its id
+    // modulo 8), so that a slice is fetched into one L2 once instead of into several.
+    const int64_t total = (int64_t)used * per_split, padded = (total + 7) / 8 * 8;
+    if ((int64_t)blockIdx.x >= padded) return;
+    const int64_t lid = ((int64_t)blockIdx.x % 8) * (padded / 8) + (int64_t)blockIdx.x / 8;
+    if (lid >= total) return;
+    const int split = (int)(lid / per_split), rem = (int)(lid % per_split);
     int chunk = (R + used - 1) / used;
     chunk = (chunk + TN_RS - 1) / TN_RS * TN_RS;
     const int r0 = split * chunk, r1 = min(R, r0 + chunk);
@@ -361,7 +394,7 @@ int32_t gemm_bf16_tn_partials(const GemmBf16TNArgs& a, hipStream_t st, hipEvent_
     if (a.Kp <= 0 || a.N <= 0 || a.splits <= 0) return NO_OK;
     const int32_t tiles_m = (int32_t)ceil_div(a.Kp, TN_T), tiles_n = (int32_t)ceil_div(a.N, TN_T);
     const int32_t bias_blocks = (int32_t)ceil_div(a.N, 256);
-    const int64_t blocks = (int64_t)a.splits * (2 * tiles_m * tiles_n + bias_blocks);
+    const int64_t blocks = ((int64_t)a.splits * (2 * tiles_m * tiles_n + bias_blocks) + 7) / 8 * 8;
     NO_REQUIRE(blocks < (1ll << 31), NO_ERR_CAPACITY, "gemm_bf16_tn: too many blocks");
     NO_LAUNCH_TIMED(gemm_bf16_tn_kernel, dim3((unsigned)blocks), dim3(256), st, ev0, ev1, a, tiles_m, tiles_n, bias_blocks);
     return launch_status("gemm_bf16_tn");
