@@ -102,10 +102,12 @@ struct GradJobs {
     GemmTNArgs tn[NO_MAX_LAYERS]; ReduceArgs red[NO_MAX_LAYERS];
     int32_t n = 0;
     // side != NULL: where the bottom layer's products are of another kind (bf16 operands) and cannot carry the deferred
-    // fp32 ones in their launch, those are launched on this otherwise idle stream beside them (behind `fork`; the
-    // reduction waits for `join`). Launching each as soon as its layer had made its inputs measured no faster: every
-    // fork is an event on the backward chain.
+    // fp32 ones in their launch, those are launched together on this otherwise idle stream as soon as the last of them
+    // has its inputs (behind `fork`, recorded before layer 2's own backward kernels; the reduction waits for `join`), so
+    // they run beside layer 2's input gradient and the bottom layer's products. One fork: launching each job as soon as
+    // its own layer had made its inputs measured no faster (every fork is an event on the backward chain).
     hipStream_t side = nullptr; hipEvent_t fork = nullptr; hipEvent_t join = nullptr;
+    bool launched_beside = false;
 };
 
 // ev0 / ev1 (optional): events that take the product kernel's own start and end times

@@ -724,18 +724,14 @@ int32_t sage_backward(const no_block_view& blk, const void* x_src, no_dtype dt, 
     rj[n_jobs++] = r;
     if (!bf) tj[n_tn++] = t;
     for (int32_t i = 0; pending && i < pending->n && n_jobs < NO_MAX_LAYERS; ++i) { tj[n_tn++] = pending->tn[i]; rj[n_jobs++] = pending->red[i]; }
-    const bool beside = bf && pending && pending->side && pending->fork && pending->join && n_tn > 0;
-    if (pending) pending->n = 0;
+    const bool beside = pending && pending->launched_beside;      // the deferred products already run on the side stream
+    if (beside) n_tn = bf ? 0 : 1;
+    if (pending) { pending->n = 0; pending->launched_beside = false; }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (bf) {
         // this layer's two products take bf16 operands (their own launch); the deferred fp32 products of the layers
         // above go first
-        if (beside) {
-            NO_HIP_CHECK(hipEventRecord(pending->fork, st));
-            NO_HIP_CHECK(hipStreamWaitEvent(pending->side, pending->fork, 0));
-            NO_CHECK(gemm_tn_partials(tj, n_tn, pending->side, nullptr, nullptr));
-            NO_HIP_CHECK(hipEventRecord(pending->join, pending->side));
-        } else {
+        if (n_tn > 0) {
             if (prof && prep_stage >= 0) prof->begin(prep_stage);
             NO_CHECK(gemm_tn_partials(tj, n_tn, st, nullptr, nullptr));
             if (prof && prep_stage >= 0) prof->end();

@@ -5,7 +5,81 @@
 #include "handles.hpp"
 #include "layers.hpp"
 
+#include <condition_variable>
+#include <functional>
+#include <mutex>
+#include <string>
+#include <thread>
 #include <utility>
+
+namespace no {
+// A helper thread that enqueues the preparation of the next batch (about as many launches as the step itself) while
+// the calling thread enqueues the step: enqueueing, not the GPU, bounds a step once the kernels are short. One job at a
+// time; the job may wait once for a signal from the caller (the point in the caller's stream its second half depends
+// on has been recorded). The caller always joins before it returns, so no call overlaps another.
+struct AheadWorker {
+    std::thread th;
+    std::mutex mu;
+    std::condition_variable cv;
+    std::function<int32_t()> job;
+    bool has_job = false, busy = false, stop = false;
+    int signal = 0;               // 0: not yet; 1: go on; 2: the caller gave up (skip the second half)
+    int32_t status = NO_OK;
+    std::string msg;
+    int device = 0;
+    void start(int dev) {
+        device = dev;
+        th = std::thread([this] {
+            (void)hipSetDevice(device);
+            std::unique_lock<std::mutex> l(mu);
+            for (;;) {
+                cv.wait(l, [this] { return has_job || stop; });
+                if (stop) return;
+                has_job = false;
+                std::function<int32_t()> f = std::move(job);
+                l.unlock();
+                const int32_t s = f();
+                std::string m = s == NO_OK ? std::string() : std::string(no_last_error());
+                l.lock();
+                status = s;
+                msg = std::move(m);
+                busy = false;
+                cv.notify_all();
+            }
+        });
+    }
+    void submit(std::function<int32_t()> f) {
+        std::lock_guard<std::mutex> l(mu);
+        job = std::move(f);
+        has_job = busy = true;
+        signal = 0;
+        cv.notify_all();
+    }
+    void send(int value) {
+        std::lock_guard<std::mutex> l(mu);
+        if (signal == 0) signal = value;
+        cv.notify_all();
+    }
+    int wait_signal() {
+        std::unique_lock<std::mutex> l(mu);
+        cv.wait(l, [this] { return signal != 0; });
+        return signal;
+    }
+    int32_t join() {          // the job's status; its message becomes the calling thread's
+        std::unique_lock<std::mutex> l(mu);
+        cv.wait(l, [this] { return !busy; });
+        const int32_t s = status;
+        status = NO_OK;
+        if (s != NO_OK) set_error("%s", msg.c_str());
+        return s;
+    }
+    void shutdown() {
+        if (!th.joinable()) return;
+        { std::lock_guard<std::mutex> l(mu); stop = true; if (signal == 0) signal = 2; cv.notify_all(); }
+        th.join();
+    }
+};
+}  // namespace no
 
 struct no_model_s {
     int32_t n_layers = 0;
@@ -43,6 +117,7 @@ struct no_model_s {
     no::DevBuf<float> mean_alt;          // layer-1 aggregate of the batch prepared ahead
     no::DevBuf<float> h0_alt;            // H^1 of that batch (its reused rows arrive with the aggregate)
     hipStream_t sample_stream = nullptr;
+    no::AheadWorker* worker = nullptr;   // enqueues the next batch's preparation beside the calling thread
     hipEvent_t ev_can_sample = nullptr, ev_sampled = nullptr, ev_l1_done = nullptr;
     bool ahead_valid = false;
     bool ahead_aggregated = false;       // mean_alt (and the reused rows of H^1) were written for the batch prepared ahead
@@ -57,6 +132,7 @@ struct no_model_s {
     void release() {
         if (prof.created) { for (auto& e : prof.ev) (void)hipEventDestroy(e); prof.created = false; }
         if (ev_dw_join) { (void)hipEventDestroy(ev_dw_join); ev_dw_join = nullptr; }
+        if (worker) { worker->shutdown(); delete worker; worker = nullptr; }
         // a batch prepared ahead and never trained on: its split's stamps leave the cache with the model
         if (ahead_valid && blocks_alt && sample_stream) (void)no::blocks_unstamp(blocks_alt, sample_stream);
         ahead_valid = false;
@@ -249,6 +325,10 @@ static int32_t ensure_lookahead(no_model_s* m, no_graph_s* g) {
     NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_can_sample, NO_SYNC_EVENT_FLAGS));
     NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_sampled, NO_SYNC_EVENT_FLAGS));
     NO_HIP_CHECK(hipEventCreateWithFlags(&m->ev_l1_done, NO_SYNC_EVENT_FLAGS));
+    int dev = 0;
+    NO_HIP_CHECK(hipGetDevice(&dev));
+    m->worker = new AheadWorker();
+    m->worker->start(dev);
     return NO_OK;
 }
 
@@ -357,9 +437,7 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     // (The transposes, the local indices of the upper hops and the dense copy go to that batch's own side stream: they
     // are needed by its backward pass and upper layers only, and would otherwise sit between its sampling and its
     // aggregation on the sampling stream, which is the longer of the two chains.)
-    auto launch_sampling_ahead = [&]() -> int32_t {
-        if (commit_refresh_before_next && cache) NO_CHECK(refresh_commit_impl(cache, st));
-        NO_HIP_CHECK(hipEventRecord(m->ev_can_sample, st));
+    auto launch_sampling_ahead = [=]() -> int32_t {
         NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_can_sample, 0));
         SideGather sg2 = sg;
         sg2.out = m->x0_alt.p;
@@ -378,7 +456,8 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         m->ahead_features = d_features;
         return NO_OK;
     };
-    auto launch_aggregate_ahead = [&]() -> int32_t {
+    // (ev_l1_done is recorded on the step's stream, by the calling thread, after layer 1's launch)
+    auto launch_aggregate_ahead = [=]() -> int32_t {
         if (L < 2 || m->arch != NO_ARCH_SAGE_MEAN) return NO_OK;
         no_blocks_s* NB = m->blocks_alt;
         no_block_view nv;
@@ -386,7 +465,6 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         RowCopyJob next_hits{};
         const bool next_cache = NB->last_used_cache;
         if (next_cache) {
-            NO_HIP_CHECK(hipEventRecord(m->ev_l1_done, st));
             NO_HIP_CHECK(hipStreamWaitEvent(m->sample_stream, m->ev_l1_done, 0));
             next_hits.src = cache->emb.p; next_hits.src_rows = NB->hit_slot.p; next_hits.dst_rows = NB->hit_pos.p;
             next_hits.d_n = NB->counts.p + 4 * L + 1; next_hits.n_cap = nv.n_dst_cap; next_hits.dst = m->h0_alt.p;
@@ -400,8 +478,25 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
         m->ahead_aggregated = true;
         return NO_OK;
     };
+    // Part one starts with the step unless a refresh commit is due at the boundary. Then a helper thread enqueues both
+    // parts (it waits for the caller's signal between them) while this thread enqueues the step itself; otherwise
+    // both parts are enqueued here, after layer 1.
     const bool lookahead_early = d_next_seeds && !(commit_refresh_before_next && cache);
-    if (lookahead_early) NO_CHECK(launch_sampling_ahead());
+    const bool next_uses_cache = cache != nullptr && L >= 2 && cache->n_hot > 0;
+    struct WorkerScope {      // whatever way this call ends, the helper is told and waited for
+        AheadWorker* w = nullptr;
+        ~WorkerScope() { if (w) { w->send(2); (void)w->join(); } }
+    } scope;
+    if (lookahead_early) {
+        NO_HIP_CHECK(hipEventRecord(m->ev_can_sample, st));
+        m->ahead_valid = false;
+        scope.w = m->worker;
+        m->worker->submit([=]() -> int32_t {
+            NO_CHECK(launch_sampling_ahead());
+            if (m->worker->wait_signal() != 1) return NO_OK;      // (the batch is sampled; it just has no aggregate yet)
+            return launch_aggregate_ahead();
+        });
+    }
 
     // forward
     no_block_view view[NO_MAX_LAYERS];
@@ -460,8 +555,15 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
                               nullptr, false, &sw));
         if (l == L && L >= 2) prof.end();
         if (l == 1 && d_next_seeds) {
-            if (!lookahead_early) NO_CHECK(launch_sampling_ahead());
-            NO_CHECK(launch_aggregate_ahead());
+            if (next_uses_cache && L >= 2 && m->arch == NO_ARCH_SAGE_MEAN) NO_HIP_CHECK(hipEventRecord(m->ev_l1_done, st));
+            if (lookahead_early) {
+                m->worker->send(1);
+            } else {
+                if (commit_refresh_before_next && cache) NO_CHECK(refresh_commit_impl(cache, st));
+                NO_HIP_CHECK(hipEventRecord(m->ev_can_sample, st));
+                NO_CHECK(launch_sampling_ahead());
+                NO_CHECK(launch_aggregate_ahead());
+            }
         }
     }
 
@@ -489,7 +591,8 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
     GradJobs pending;
     if (bf16_products) {
         // the bottom layer's products are of another kind (bf16 operands) and cannot carry the upper layers' fp32 ones in
-        // their launch: those run beside them on the blocks' side stream (joined above, idle from here on)
+        // their launch: those run on the blocks' side stream (joined above, idle from here on), launched once layer 2
+        // has handed over its job, beside layer 2's input gradient and the bottom layer's products
         pending.side = B->side;
         pending.fork = B->ev_fork[0];
         pending.join = m->ev_dw_join;
@@ -528,6 +631,8 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
             bfp.x_dense = (const uint16_t*)m->x0.p;
             bfp.wt_self = wt_self; bfp.wt_neigh = wt_neigh; bfp.Kpad = m->wt1_kpad;
         }
+        const bool launch_beside = pending.side && l == 2;
+        if (launch_beside) NO_HIP_CHECK(hipEventRecord(pending.fork, st));      // (every deferred job's inputs are ready here)
         NO_CHECK(sage_backward(blk, x, dt, d_in, m->mean[l - 1].p, h_l, gh_l, m->params.p + m->off_w_self[l - 1],
                                m->params.p + m->off_w_neigh[l - 1], d_out, l < L ? 1 : 0,
                                m->grads.p + m->off_w_self[l - 1], m->grads.p + m->off_w_neigh[l - 1],
@@ -536,10 +641,21 @@ static int32_t train_step_impl(no_model_t m, no_graph_t g, const void* d_feature
                                -1, grad_rows, lr, m->params.p + m->off_w_self[l - 1], m->params.p + m->off_w_neigh[l - 1],
                                m->params.p + m->off_bias[l - 1], m->arch, l == 1 ? &stats_job : nullptr, gz_in,
                                l >= 2 ? &below : nullptr, &pending, l >= 2, &sw, (bf16_products && l == 1) ? &bfp : nullptr));
+        if (launch_beside && pending.n > 0) {
+            NO_HIP_CHECK(hipStreamWaitEvent(pending.side, pending.fork, 0));
+            NO_CHECK(gemm_tn_partials(pending.tn, pending.n, pending.side, nullptr, nullptr));
+            NO_HIP_CHECK(hipEventRecord(pending.join, pending.side));
+            pending.launched_beside = true;
+        }
     }
 
     // (the SGD step ran inside each layer's gradient reduction, after every kernel that read the weights;
     //  the cache was refreshed during the forward pass with rows made by the pre-update weights)
+    if (scope.w) {      // the helper's enqueues are part of this call
+        AheadWorker* wk = scope.w;
+        scope.w = nullptr;
+        NO_CHECK(wk->join());
+    }
     NO_CHECK(launch_status("train_step"));
     if (prof.enabled) {
         NO_HIP_CHECK(hipStreamSynchronize(st));
