@@ -232,12 +232,13 @@ int32_t gemm_bf16_nn(const GemmBf16NNArgs& a, hipStream_t st, hipEvent_t ev0, hi
 
 // ------------------------------------------------------------------------------------------ TN
 
-constexpr int TN_T = 128;            // output tile: 128 rows (feature columns) x 128 columns
+constexpr int TN_T = 128;            // output tile: 128 rows (operand columns) ...
+constexpr int TN_W = 64;             // ... x 64 columns of G (128 x 128 tiles, half as many blocks, measured slower)
 constexpr int TN_RS = 32;            // slice rows staged at a time
 constexpr int TN_PITCH = TN_T + 8;   // bf16 elements per LDS row (a staged slice row)
 
 // One staged round of a 32-row x 128-column tile held in registers between its request and its store to LDS.
-struct TnTileRegs { uint4 raw[2]; float4 f[4]; };
+struct TnTileRegs { uint4 raw[2]; float4 f[4]; };      // (a 128-column tile; a 64-column one uses half of f)
 
 __device__ __forceinline__ void tn_request_bf16(TnTileRegs& t, const uint16_t* X, int64_t ldx, int rs, int r1, int c0, int C, bool vec) {
     const int tid = (int)threadIdx.x;
@@ -267,11 +268,12 @@ __device__ __forceinline__ void tn_store_bf16(const TnTileRegs& t, uint16_t* T) 
         *reinterpret_cast<uint4*>(T + r * TN_PITCH + u * 8) = t.raw[i];
     }
 }
+template <int W>
 __device__ __forceinline__ void tn_request_f32(TnTileRegs& t, const float* A, int64_t lda, int rs, int r1, int c0, int C, bool vec) {
     const int tid = (int)threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int id = tid + 256 * i, r = id / (TN_T / 4), u = id % (TN_T / 4);
+    for (int i = 0; i < TN_RS * (W / 4) / 256; ++i) {
+        const int id = tid + 256 * i, r = id / (W / 4), u = id % (W / 4);
         const int row = rs + r, c = c0 + u * 4;
         t.f[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (row < r1 && c < C) {
@@ -286,11 +288,12 @@ __device__ __forceinline__ void tn_request_f32(TnTileRegs& t, const float* A, in
         }
     }
 }
+template <int W>
 __device__ __forceinline__ void tn_store_f32(const TnTileRegs& t, uint16_t* T) {
     const int tid = (int)threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int id = tid + 256 * i, r = id / (TN_T / 4), u = id % (TN_T / 4);
+    for (int i = 0; i < TN_RS * (W / 4) / 256; ++i) {
+        const int id = tid + 256 * i, r = id / (W / 4), u = id % (W / 4);
         *reinterpret_cast<uint2*>(T + r * TN_PITCH + u * 4) = make_uint2(pack_bf16(t.f[i].x, t.f[i].y), pack_bf16(t.f[i].z, t.f[i].w));
     }
 }
@@ -303,7 +306,7 @@ __device__ __forceinline__ uint4 tn_column_fragment(const uint16_t* T, int row0,
     return make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
 }
 
-// Block = (slice, product, 128 x 128 tile of the product), or (slice, 256 columns of the bias row).
+// Block = (slice, product, 128 x 64 tile of the product), or (slice, 256 columns of the bias row).
 __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(GemmBf16TNArgs g, int32_t tiles_m, int32_t tiles_n, int32_t bias_blocks) {
     __shared__ __attribute__((aligned(16))) uint16_t At[TN_RS * TN_PITCH];     // At[r][m]: slice row r, operand column m
     __shared__ __attribute__((aligned(16))) uint16_t Gt[TN_RS * TN_PITCH];     // Gt[r][n]
@@ -343,11 +346,12 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(GemmBf16TNArgs g, int
         return;
     }
     const int prob = rem / (tiles_m * tiles_n), tile = rem % (tiles_m * tiles_n);
-    const int mb = (tile / tiles_n) * TN_T, nb = (tile % tiles_n) * TN_T;
+    const int mb = (tile / tiles_n) * TN_T, nb = (tile % tiles_n) * TN_W;
     const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
-    f32x16_t acc[4];
+    constexpr int NJ = TN_W / 32;
+    f32x16_t acc[NJ];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
     const bool xvec = ((reinterpret_cast<uintptr_t>(g.X) & 15) == 0) && (g.ldx % 8 == 0) && (g.Kp % 8 == 0);
@@ -356,22 +360,22 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(GemmBf16TNArgs g, int
     TnTileRegs ta, tg;
     auto request = [&](int rs) {
         if (prob == 0) tn_request_bf16(ta, g.X, g.ldx, rs, r1, mb, g.Kp, xvec);
-        else tn_request_f32(ta, g.Mn, g.ldm, rs, r1, mb, g.Kp, mvec);
-        tn_request_f32(tg, g.G, g.ldg, rs, r1, nb, g.N, gvec);
+        else tn_request_f32<TN_T>(ta, g.Mn, g.ldm, rs, r1, mb, g.Kp, mvec);
+        tn_request_f32<TN_W>(tg, g.G, g.ldg, rs, r1, nb, g.N, gvec);
     };
     if (r0 < r1) request(r0);
     for (int rs = r0; rs < r1; rs += TN_RS) {
         __syncthreads();                     // the previous round's tiles have been read
-        if (prob == 0) tn_store_bf16(ta, At); else tn_store_f32(ta, At);
-        tn_store_f32(tg, Gt);
+        if (prob == 0) tn_store_bf16(ta, At); else tn_store_f32<TN_T>(ta, At);
+        tn_store_f32<TN_W>(tg, Gt);
         if (rs + TN_RS < r1) request(rs + TN_RS);      // the next round is in flight during this round's products
         __syncthreads();
-        // wavefront w: operand columns [mb + 32 w, +32) against all four 32-column groups of the tile
+        // wavefront w: operand columns [mb + 32 w, +32) against the 32-column groups of the tile
 #pragma unroll
         for (int ks = 0; ks < TN_RS / 16; ++ks) {
             const uint4 a = tn_column_fragment(At, ks * 16 + half * 8, wave * 32 + l32);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < NJ; ++j) {
                 const uint4 b = tn_column_fragment(Gt, ks * 16 + half * 8, j * 32 + l32);
                 acc[j] = mfma_bf16(a, b, acc[j]);
             }
@@ -379,7 +383,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(GemmBf16TNArgs g, int
     }
     float* P = g.P + ((int64_t)prob * g.splits + split) * per;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NJ; ++j) {
         const int n = nb + j * 32 + l32;
         if (n >= g.N) continue;
 #pragma unroll
@@ -392,7 +396,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(GemmBf16TNArgs g, int
 
 int32_t gemm_bf16_tn_partials(const GemmBf16TNArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     if (a.Kp <= 0 || a.N <= 0 || a.splits <= 0) return NO_OK;
-    const int32_t tiles_m = (int32_t)ceil_div(a.Kp, TN_T), tiles_n = (int32_t)ceil_div(a.N, TN_T);
+    const int32_t tiles_m = (int32_t)ceil_div(a.Kp, TN_T), tiles_n = (int32_t)ceil_div(a.N, TN_W);
     const int32_t bias_blocks = (int32_t)ceil_div(a.N, 256);
     const int64_t blocks = ((int64_t)a.splits * (2 * tiles_m * tiles_n + bias_blocks) + 7) / 8 * 8;
     NO_REQUIRE(blocks < (1ll << 31), NO_ERR_CAPACITY, "gemm_bf16_tn: too many blocks");
