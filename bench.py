@@ -333,6 +333,8 @@ def main():
     sampling_bytes = sum(sample_rows_bytes(h) + relabel_bytes(h) + csc_bytes(h) for h in range(L))
     ms = per_step
     AGG, FWD, DW = "padded_rows_kernel(mean,l1)", "gemm_nn_kernel(l1 fwd)", "gemm_tn_kernel(l1 dW)"
+    if args.arch == "gcn_sym":
+        AGG = "segment_rows_kernel(sym,l1)"        # per-source weights: through the compacted indices
     kern = {
         "gather_rows_kernel": ("hbm", gather_bytes / 1e9 / (ms["gather"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["gather"]),
         AGG: ("hbm", agg_bytes / 1e9 / (ms["agg_l1"] / 1e3), HBM_PEAK_GBPS, "GB/s", ms["agg_l1"]),
