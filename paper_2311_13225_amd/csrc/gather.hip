@@ -23,33 +23,32 @@ __global__ void __launch_bounds__(256) gather_rows_kernel(const char* __restrict
     const int32_t sub = lane >> g_log2;
     const int32_t u0 = lane & ((1 << g_log2) - 1);
     const int32_t g = 1 << g_log2;
-    for (int64_t base = wave * rows_per_pass * ROWS; base < n; base += n_waves * rows_per_pass * ROWS) {
-        int64_t r[ROWS];
-        const char* src[ROWS];
-#pragma unroll
-        for (int q = 0; q < ROWS; ++q) {
-            r[q] = base + (int64_t)q * rows_per_pass + sub;
-            src[q] = (r[q] < n) ? table + (int64_t)ids[r[q]] * table_stride : nullptr;
-        }
-        // UNR lane-group widths of every row are requested before the first store (a 2408-byte row in 8-byte units is
-        // five widths: one round trip per pass over ROWS rows instead of five)
+    // The ids of a wavefront's next pass are requested before the rows of the current one, so that a pass costs one
+    // memory round trip (rows) instead of two dependent ones (ids, then rows).
+    static_assert(ROWS == 1, "one row per lane group and pass");
+    const int64_t stride_rows = n_waves * rows_per_pass;
+    int64_t r = wave * rows_per_pass + sub;
+    int32_t id_cur = r < n ? ids[r] : -1;
+    for (; r - sub < n; r += stride_rows) {
+        const int64_t r_next = r + stride_rows;
+        const int32_t id_next = r_next < n ? ids[r_next] : -1;
+        const char* src = id_cur >= 0 ? table + (int64_t)id_cur * table_stride : nullptr;
+        // UNR lane-group widths of the row are requested before the first store (a 2408-byte row in 8-byte units is
+        // five widths: one round trip per pass instead of five)
         for (int32_t ub = u0; ub < units; ub += g * UNR) {
-            VecT v[UNR][ROWS];
+            VecT v[UNR];
 #pragma unroll
-            for (int j = 0; j < UNR; ++j)
+            for (int j = 0; j < UNR; ++j) {
+                const int32_t u = ub + j * g;
+                if (src && u < units) v[j] = *reinterpret_cast<const VecT*>(src + (int64_t)u * sizeof(VecT));
+            }
 #pragma unroll
-                for (int q = 0; q < ROWS; ++q) {
-                    const int32_t u = ub + j * g;
-                    if (src[q] && u < units) v[j][q] = *reinterpret_cast<const VecT*>(src[q] + (int64_t)u * sizeof(VecT));
-                }
-#pragma unroll
-            for (int j = 0; j < UNR; ++j)
-#pragma unroll
-                for (int q = 0; q < ROWS; ++q) {
-                    const int32_t u = ub + j * g;
-                    if (src[q] && u < units) *reinterpret_cast<VecT*>(out + r[q] * out_stride + (int64_t)u * sizeof(VecT)) = v[j][q];
-                }
+            for (int j = 0; j < UNR; ++j) {
+                const int32_t u = ub + j * g;
+                if (src && u < units) *reinterpret_cast<VecT*>(out + r * out_stride + (int64_t)u * sizeof(VecT)) = v[j];
+            }
         }
+        id_cur = id_next;
     }
 }
 
@@ -69,7 +68,9 @@ static void launch_gather(const char* table, int64_t ts, const int32_t* ids, con
     const int64_t rows_per_wave = (int64_t)(64 >> g_log2) * ROWS;
     int64_t waves = ceil_div(n_cap, rows_per_wave);
     int64_t blocks = ceil_div(waves, 4);
-    const int64_t max_blocks = 256 * 16;
+    // 8192 wavefronts fill the chip's wave slots once; each then walks its passes with the next ids already requested
+    // (measured, 118 K rows of 256 bytes from fresh ids and buffers: 2048 blocks 14.7 us, 4096 15.5, 1024 17.7)
+    const int64_t max_blocks = 256 * 8;
     if (blocks > max_blocks) blocks = max_blocks;
     if (blocks < 1) blocks = 1;
     const int32_t widths = (int32_t)ceil_div(units, 1 << g_log2);      // lane-group widths per row
