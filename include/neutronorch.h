@@ -311,6 +311,11 @@ int32_t no_model_gathered(no_model_t m, const void** d_x0);
  * (layer-1 rows of reusable hot vertices come from the cache), mean softmax cross-entropy on the
  * seeds, backward (reused rows take no gradient), W <- W - lr * grad for every tensor; every computed
  * hot vertex's layer-1 row (made by the pre-update weights) is stored in the cache with version = step.
+ * Precision: fp32 throughout, except that GraphSAGE-mean layer 1 on a bf16 feature table takes the operands of its
+ * products in bf16 with fp32 accumulation (the features as stored; the fp32 mean, the weights and the output gradient
+ * rounded to nearest-even on their way into the forward and weight-gradient products; the bias gradient, the mean itself,
+ * the layers above, the loss and the update stay fp32). The standalone layer entry points and the bulk refresh upcast
+ * bf16 rows and multiply in fp32.
  * d_stats (device, may be NULL) receives the statistics; if h_stats != NULL the stream is
  * synchronised and the statistics are copied to the host, and the call returns NO_ERR_TIMEOUT if they say that a
  * scan's wait expired (h_stats is filled all the same). */

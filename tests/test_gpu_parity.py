@@ -549,6 +549,12 @@ def test_train_step_single_layer_and_bf16_features():
     run_steps(w1, 2, use_cache=False)
     wb = dataclasses.replace(si.WORKLOADS["tiny"], feat_dtype="bf16", feat_dim=128, staleness=2, hot_fraction=0.1)
     run_steps(wb, 3, use_cache=True)
+    # a single layer on a bf16 table: the bf16-operand products feed the logits directly (16 columns: one partly
+    # filled column group), and a feature width that is no multiple of 8 or 16 (element-wise staging, padded weights)
+    wb1 = dataclasses.replace(si.WORKLOADS["tiny"], feat_dtype="bf16", feat_dim=128, fanouts=(6,), batch=200)
+    run_steps(wb1, 2, use_cache=False)
+    wb2 = dataclasses.replace(si.WORKLOADS["tiny"], feat_dtype="bf16", feat_dim=70, hidden=300, staleness=2, hot_fraction=0.1)
+    run_steps(wb2, 3, use_cache=True, ahead=True)
 
 
 @pytest.mark.parametrize("fanouts,arch,ahead", [((5, 4, 3, 3), "sage", False), ((4, 3, 3, 2, 2), "sage", True),
