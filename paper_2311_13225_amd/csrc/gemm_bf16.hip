@@ -150,9 +150,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_nn_kernel(GemmBf16NNArgs g) {
     for (int phase = 0; phase < 2; ++phase) {
         const uint16_t* Wt = g.Wt[phase];
         for (int k0 = 0; k0 < g.K; k0 += NN_KC) {
-            __syncthreads();          // the tile of the previous round has been read
+            __syncthreads();          // the previous tile has been read
             stage_rows_bf16(As, phase == 0 ? g.X : nullptr, g.ldx, g.x_rows, g.Mn, g.ldm, m0, M, k0, g.K);
-            // this wavefront's weight fragments of the round, straight from memory (zeros past N; Kpad covers the round)
+            // this wavefront's weight fragments for the tile, straight from memory (zeros past N; Kpad covers the tile)
             uint4 bw[NN_KC / 16][2];
 #pragma unroll
             for (int ks = 0; ks < NN_KC / 16; ++ks)
@@ -237,7 +237,7 @@ constexpr int TN_W = 64;             // ... x 64 columns of G (128 x 128 tiles, 
 constexpr int TN_RS = 32;            // slice rows staged at a time
 constexpr int TN_PITCH = TN_T + 8;   // bf16 elements per LDS row (a staged slice row)
 
-// One staged round of a 32-row x 128-column tile held in registers between its request and its store to LDS.
+// A 32-row x 128-column tile held in registers between its request and its store to LDS.
 struct TnTileRegs { uint4 raw[2]; float4 f[4]; };      // (a 128-column tile; a 64-column one uses half of f)
 
 __device__ __forceinline__ void tn_request_bf16(TnTileRegs& t, const uint16_t* X, int64_t ldx, int rs, int r1, int c0, int C, bool vec) {
@@ -365,10 +365,10 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(GemmBf16TNArgs g, int
     };
     if (r0 < r1) request(r0);
     for (int rs = r0; rs < r1; rs += TN_RS) {
-        __syncthreads();                     // the previous round's tiles have been read
+        __syncthreads();                     // the previous tile pair has been read
         if (prob == 0) tn_store_bf16(ta, At); else tn_store_f32<TN_T>(ta, At);
         tn_store_f32<TN_W>(tg, Gt);
-        if (rs + TN_RS < r1) request(rs + TN_RS);      // the next round is in flight during this round's products
+        if (rs + TN_RS < r1) request(rs + TN_RS);      // the next tile pair is in flight during the products of the current one
         __syncthreads();
         // wavefront w: operand columns [mb + 32 w, +32) against the 32-column groups of the tile
 #pragma unroll
