@@ -1029,3 +1029,40 @@ def test_refresh_commit_between_two_ahead_calls_drops_the_prepared_batch():
     assert results[0][0] == results[1][0]
     assert np.array_equal(results[0][1], results[1][1]) and np.array_equal(results[0][2], results[1][2])
     assert any(o[1] > 0 for o in results[0][0])
+
+
+def test_models_with_batches_prepared_ahead_come_and_go():
+    """Every model that prepares batches ahead owns a helper thread, streams and events: several models created, stepped
+    (alternately with and without a next batch, and with a next batch larger than the capacity, which is refused before
+    anything is enqueued) and destroyed in turn leave nothing behind that disturbs the next one, and all give the same
+    losses."""
+    b = nb()
+    import dataclasses
+    w = dataclasses.replace(si.WORKLOADS["tiny"], staleness=2, hot_fraction=0.2)
+    src, dst, og, gg = make_graph(w.n_vertices, w.n_edges, w.seed, 32)
+    feat, lab = dev(si.features(w.n_vertices, w.feat_dim, w.seed)), dev(si.labels(w.n_vertices, w.n_classes, w.seed))
+    train = si.train_split(w.n_vertices, 0.65, w.seed)
+    weights = si.init_weights(w.dims, w.seed)
+    seeds = [dev(si.batch_seeds(train, w.batch, t)) for t in range(5)]
+    too_many = dev(train[: w.batch + 1].copy())
+    runs = []
+    for trial in range(4):
+        model = b.no_model_create(gg, w.dims, w.batch, w.fanouts)
+        for l in range(w.n_layers):
+            for t, a in zip(b.no_model_params(model, l + 1), weights[l]):
+                t.copy_(dev(a))
+        gc = b.no_select_hot(gg, dev(train), w.batch, w.fanouts, 1, w.hot_fraction, w.staleness, w.hidden, w.seed)
+        out = []
+        for t in range(4):
+            nxt = seeds[t + 1] if (t + trial) % 2 == 0 else None
+            if t == 2:
+                with pytest.raises(b.NoError) as ei:
+                    b.no_train_step_ahead(model, gg, feat, lab, seeds[t], too_many, False, gc, t, w.seed, 0.02)
+                assert ei.value.code == -3
+            st = b.no_train_step_ahead(model, gg, feat, lab, seeds[t], nxt, False, gc, t, w.seed, 0.02)
+            out.append((st.loss, st.n_hit, st.n_miss_hot))
+        runs.append(out)
+        model.close()
+        gc.close()
+    assert all(r == runs[0] for r in runs[1:])
+    assert any(o[1] > 0 for o in runs[0])
