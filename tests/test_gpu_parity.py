@@ -922,12 +922,15 @@ def test_step_statistics_account_for_every_vertex_of_v1():
     assert seen_hit > 0 and seen_miss > 0
 
 
-@pytest.mark.parametrize("fanouts,batch,which", [((10, 10), 512, "edge scan"), ((1, 10), 2000, "V^1 split")])
+SCAN_TILE = 1024      # slots per tile of the library's scans
+
+
+@pytest.mark.parametrize("fanouts,batch,which", [((10, 10), 512, "edge scan"), ((1, 10), 1000, "V^1 split")])
 def test_scan_wait_expiry_is_reported_and_every_kernel_still_ends(fanouts, batch, which):
     """Error path of the one-launch scans: the host makes tile 0 withhold its status word and shortens the bounded
     wait, so the tile after it must give up. The scan then leaves a consistent empty hop behind (so that no later
     kernel follows a wrong prefix out of its arrays), every kernel runs to its end, the step and the block sizes report
-    NO_ERR_TIMEOUT, and the next call (limits restored) is clean again. Case 1: hop 0 spans two tiles of 2048 slots;
+    NO_ERR_TIMEOUT, and the next call (limits restored) is clean again. Case 1: hop 0 spans several tiles of slots;
     case 2: hop 0 is a single tile and V^1 spans two."""
     b = nb()
     import dataclasses
@@ -944,9 +947,9 @@ def test_scan_wait_expiry_is_reported_and_every_kernel_still_ends(fanouts, batch
     st0 = b.no_train_step(model, gg, feat, lab, seeds[0], gc, 0, 0, 0.01)
     assert st0.scan_timeout == 0
     if which == "edge scan":
-        assert st0.n_dst[0] * fanouts[0] > 2048
+        assert st0.n_dst[0] * fanouts[0] > SCAN_TILE
     else:
-        assert st0.n_dst[0] * fanouts[0] <= 2048 < st0.n_v1
+        assert st0.n_dst[0] * fanouts[0] <= SCAN_TILE < st0.n_v1
     blocks = b.no_blocks_create(gg, w.batch, w.fanouts)
     try:
         b.no_debug_scan_wait(4, True)
