@@ -558,13 +558,19 @@ def test_train_step_single_layer_and_bf16_features():
 
 
 @pytest.mark.parametrize("fanouts,arch,ahead", [((5, 4, 3, 3), "sage", False), ((4, 3, 3, 2, 2), "sage", True),
-                                                ((4, 3, 3, 2, 2), "gcn", False), ((5, 4, 3, 3), "gcn", True)])
+                                                ((4, 3, 3, 2, 2), "gcn", False), ((5, 4, 3, 3), "gcn", True),
+                                                ((5, 4, 3, 3), "gcn_sym", True), ((4, 3, 3, 2, 2), "gcn_sum", False)])
 def test_deeper_models_four_and_five_layers(fanouts, arch, ahead):
     """The depths of the paper's model-depth experiments (the fanout list repeats its last value): every hop, the
     cache split at the bottom one, reuse and the look-ahead on a 4- and a 5-layer model, both layer forms."""
     import dataclasses
     w = dataclasses.replace(si.WORKLOADS["tiny"], fanouts=fanouts, staleness=2, hot_fraction=0.2, batch=64, hidden=48)
-    assert run_steps(w, 4, use_cache=True, lr=0.02, ahead=ahead, arch=arch) > 0
+    assert run_steps(w, 4, use_cache=True, lr=0.002 if arch == "gcn_sum" else 0.02, ahead=ahead, arch=arch) > 0
+    if arch == "sage":
+        # the same depth on a bf16 table: bf16-operand products at the bottom, fp32 weight-gradient products of the
+        # layers above launched beside them
+        wb = dataclasses.replace(w, feat_dtype="bf16", feat_dim=96)
+        assert run_steps(wb, 3, use_cache=True, lr=0.02, ahead=ahead, arch=arch) > 0
 
 
 @pytest.mark.parametrize("ahead", [False, True])
