@@ -342,8 +342,11 @@ int32_t no_train_step(no_model_t m, no_graph_t g, const void* d_features, const 
  * last use of the cache and before the next batch is sampled (which then starts after this step's layer 1); use it
  * on the last step of a super-batch instead of calling no_refresh_hot_commit between the two steps. The first
  * call with d_next_seeds != NULL allocates the second set of blocks (as much memory as no_blocks_create for the
- * same capacities) plus second copies of the destination rows, the layer-1 aggregate and H^1. Errors as
- * no_train_step, and NO_ERR_CAPACITY for n_next_seeds outside [1, capacity]. */
+ * same capacities) plus second copies of the destination rows, the layer-1 aggregate and H^1, and starts a helper
+ * thread owned by the model: it enqueues the next batch's preparation on the model's own streams while the calling
+ * thread enqueues the step (half of a step's launches each), and the call joins it before it returns, so nothing of a
+ * call is still being enqueued afterwards; no_model_destroy ends the thread. Errors as no_train_step (an error of the
+ * helper's launches is reported by this call), and NO_ERR_CAPACITY for n_next_seeds outside [1, capacity]. */
 int32_t no_train_step_ahead(no_model_t m, no_graph_t g, const void* d_features, const int32_t* d_labels,
                             const int32_t* d_seeds, int32_t n_seeds, const int32_t* d_next_seeds, int32_t n_next_seeds,
                             int32_t commit_refresh_before_next, no_cache_t cache, int64_t step, uint64_t seed,
